@@ -1,0 +1,157 @@
+/*
+ * longer.h -- C ABI of the MI355X (gfx950) LONGER forward / KV-cache serving library.
+ *
+ * The library computes the data-parallel forward pass of the LONGER long-sequence
+ * stack (arXiv 2505.04421): token merge with an InnerTrans block (Section 3.4), the
+ * hybrid attention of Section 3.5 (one cross-causal layer whose queries are the global
+ * tokens plus the k most recent merged tokens, Eq. 5-8, followed by N self-causal layers,
+ * Eq. 9-10) and the two-stage KV-cache serving path of Section 3.6.3.
+ *
+ * Conventions (all entry points)
+ *   - every tensor pointer is a DEVICE pointer owned by the caller; the config and weight
+ *     structs themselves live in HOST memory and hold device pointers;
+ *   - tensors are dense row-major; weights are stored [in, out] so that y = x W + b, the
+ *     way Eq. 6 writes Q = O W_Q; element type is `dtype` of the config (fp32 or bf16)
+ *     for every activation, weight, bias and LayerNorm vector; logits are always fp32;
+ *   - `lens` is int32 [B] raw (un-merged) valid lengths, or NULL for "all L"; sequences are
+ *     stored oldest-first and right-padded; padded values are never read into the result
+ *     (they may hold NaN);
+ *   - `ws` is caller-supplied device scratch of at least longer_workspace_bytes()
+ *     (256-byte aligned); the library allocates nothing, enqueues all work on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and does not synchronise;
+ *     calls that share a workspace must be ordered on one stream;
+ *   - return value: 0 on success; LONGER_ERR_ARG for a null pointer / unsupported shape /
+ *     bad enum; LONGER_ERR_WS when the workspace is too small; LONGER_ERR_HIP when a HIP
+ *     call failed.  Nothing throws.  longer_last_error() gives a thread-local message.
+ *   - rows of invalid tokens (padded raw tokens, merged tokens past T_u = ceil(len/K),
+ *     recent-query slots with a negative merged index) are written as exact zeros.
+ *
+ * Supported shapes: bf16 with d in {64, 128, 256} and head width d/heads in {16, 32};
+ * fp32 with d in {32, 64} and head width 16; K and m must divide 32 (K for the merge,
+ * m for candidate scoring); ffn hidden width ffn_mult*d a multiple of 32.
+ *
+ * Mask (Eq. 8, applied by token type on chronologically stored data): a sequence query
+ * sees sequence keys that are not newer than itself and never a global key; a global
+ * query sees every valid sequence key and, for LONGER_GMASK_FULL, every global key of
+ * its own set, for LONGER_GMASK_CAUSAL (Eq. 8 read literally) only globals with an
+ * index >= its own.
+ */
+#ifndef LONGER_H_
+#define LONGER_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LONGER_OK        0
+#define LONGER_ERR_ARG  -1
+#define LONGER_ERR_WS   -2
+#define LONGER_ERR_HIP  -3
+
+typedef enum { LONGER_F32 = 0, LONGER_BF16 = 1 } longer_dtype;
+typedef enum { LONGER_GMASK_FULL = 0, LONGER_GMASK_CAUSAL = 1 } longer_gmask;
+typedef enum { LONGER_ACT_GELU_ERF = 0, LONGER_ACT_RELU = 1 } longer_act;
+
+/* Model shape.  Names follow the paper: d width, m global tokens (Section 3.3), K merge
+ * group size (Section 3.4), k_recent sampled recent queries (Eq. 5), n_self = N stacked
+ * self-attention layers (Eq. 10). */
+typedef struct {
+  int32_t d, heads, ffn_mult;
+  int32_t m, K, k_recent, n_self;
+  int32_t inner_layers, inner_heads;
+  int32_t act;      /* longer_act   */
+  int32_t gmask;    /* longer_gmask */
+  float   ln_eps;
+  int32_t dtype;    /* longer_dtype */
+} longer_config;
+
+/* One pre-LayerNorm transformer block: 12 d^2 + 13 d scalars for ffn_mult = 4 (Eq. 3).
+ * ln*_g/ln*_b [d]; wq,wk,wv,wo [d,d]; bq,bk,bv,bo [d]; w1 [d, f]; b1 [f]; w2 [f, d];
+ * b2 [d] with f = ffn_mult*d. */
+typedef struct {
+  const void *ln1_g, *ln1_b, *wq, *bq, *wk, *bk, *wv, *bv, *wo, *bo,
+             *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+} longer_block;
+
+typedef struct {
+  const longer_block* inner;   /* host array [inner_layers] */
+  const longer_block* cross;   /* host pointer to 1 block    */
+  const longer_block* self;    /* host array [n_self]        */
+  const void* head_w;          /* device [m*d], may be NULL when no logits are asked for */
+  const void* head_b;          /* device [1]  */
+} longer_weights;
+
+/* Scratch needed by any forward-path entry point for a batch of B users of padded raw
+ * length L, and by the serving entry points for U = B users with C candidates each
+ * (pass C = 0 when not scoring). */
+size_t longer_workspace_bytes(const longer_config* cfg, int B, int L, int C);
+
+/* Size of the opaque per-batch KV cache written by longer_kv_cache_build. */
+size_t longer_kv_cache_bytes(const longer_config* cfg, int U, int L);
+
+/* InnerTrans (Section 3.4, InnerTrans equation): cfg->inner_layers blocks applied inside
+ * each group of K adjacent raw tokens, attention bidirectional inside the group, keys
+ * masked by validity.  H [B, L, d] -> Z_out [B, T, K, d] with T = ceil(L / K). */
+int longer_inner_transformer(const longer_config* cfg, const longer_block* inner, const void* H,
+                             const int32_t* lens, int B, int L, void* Z_out,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* Token merge (Section 3.4): InnerTrans fused with the group gather and a mean over each
+ * group's valid tokens.  H [B, L, d] -> M_out [B, T, d]. */
+int longer_token_merge(const longer_config* cfg, const longer_block* inner, const void* H,
+                       const int32_t* lens, int B, int L, void* M_out,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* First layer, cross-causal attention (Section 3.5.1-3.5.2, Eq. 5-8): queries
+ * O = [G; M[T_u-k .. T_u-1]] over keys/values R = [G; M], then the FFN.
+ * G [B, m, d], M [B, T, d], lens = raw lengths -> X_out [B, m+k, d] (globals first, then
+ * the k recent slots, right-aligned). L is the padded raw length M was merged from. */
+int longer_hybrid_cross_attn(const longer_config* cfg, const longer_block* cross, const void* G,
+                             const void* M, const int32_t* lens, int B, int L, void* X_out,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* One self-causal layer over the reduced set (Section 3.5.3, Eq. 9).
+ * X_in [B, m+k, d] -> X_out [B, m+k, d] (may not alias). */
+int longer_self_attn_layer(const longer_config* cfg, const longer_block* blk, const void* X_in,
+                           const int32_t* lens, int B, int L, void* X_out,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/* The whole stack CrossAttn(O, R) -> SelfAttn x N (Eq. 10) after the token merge.
+ * H [B, L, d], G [B, m, d] -> Y_out [B, m+k, d]; logits_out [B] fp32 (or NULL):
+ * logit = <head_w, flatten(Y[0:m])> + head_b. */
+int longer_forward(const longer_config* cfg, const longer_weights* w, const void* H, const void* G,
+                   const int32_t* lens, int B, int L, void* Y_out, float* logits_out,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* Serving stage 1 (Section 3.6.3): everything that depends on the user sequence only --
+ * token merge, the sequence rows of every layer and their per-layer K/V -- written to
+ * `cache` (longer_kv_cache_bytes, opaque layout, 256-byte aligned).  H [U, L, d]. */
+int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, const void* H,
+                          const int32_t* lens, int U, int L, void* cache,
+                          void* ws, size_t ws_bytes, void* stream);
+
+/* Serving stage 2 (Section 3.6.3): every candidate's m global tokens run through the
+ * 1 + N layers attending to their own globals and the cached sequence K/V.
+ * G_cand [U, C, m, d] -> Yg_out [U, C, m, d] (or NULL) and logits_out [U, C] fp32.
+ * `lens`, U and L must be those the cache was built with. */
+int longer_score_candidates(const longer_config* cfg, const longer_weights* w, const void* cache,
+                            const int32_t* lens, int U, int L, const void* G_cand, int C,
+                            void* Yg_out, float* logits_out,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char* longer_last_error(void);
+
+/* In-bounds probe of the matrix-core register layout the kernels rely on: runs one
+ * 32x32 MFMA per element type on index-coded operands and writes, for every lane and
+ * accumulator register, the (row, column) it holds as row*32+column into out[2][64][16]
+ * (int32, device; [0] = bf16 32x32x16, [1] = fp32 32x32x2). */
+int longer_probe_mfma_layout(int32_t* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LONGER_H_ */

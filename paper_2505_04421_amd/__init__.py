@@ -1,0 +1,15 @@
+"""MI355X-native LONGER forward / KV-cache serving path.
+
+Thin ctypes binding over ``liblonger.so`` (C ABI in ``include/longer.h``): the
+functions here carry the same names as the C entry points and only marshal
+arguments -- every step of the path runs in the library's HIP kernels.  PyTorch
+is used for device memory and streams only.  There is no CPU fallback: if the
+library is missing, or no GPU is present when a compute call is made, the call
+raises.
+"""
+from .binding import (  # noqa: F401
+    LongerError, DeviceModel, load_library, library_path, make_config, exported_symbols,
+    longer_workspace_bytes, longer_kv_cache_bytes, longer_inner_transformer, longer_token_merge,
+    longer_hybrid_cross_attn, longer_self_attn_layer, longer_forward, longer_kv_cache_build,
+    longer_score_candidates, longer_probe_mfma_layout, longer_last_error,
+)

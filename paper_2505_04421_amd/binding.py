@@ -1,0 +1,233 @@
+"""ctypes binding of liblonger.so.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+BLOCK_FIELDS = ("ln1_g", "ln1_b", "wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo",
+                "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+ENTRY_POINTS = ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_inner_transformer",
+                "longer_token_merge", "longer_hybrid_cross_attn", "longer_self_attn_layer",
+                "longer_forward", "longer_kv_cache_build", "longer_score_candidates",
+                "longer_last_error", "longer_probe_mfma_layout")
+
+
+class LongerError(RuntimeError):
+    pass
+
+
+class CConfig(ctypes.Structure):
+    _fields_ = [("d", ctypes.c_int32), ("heads", ctypes.c_int32), ("ffn_mult", ctypes.c_int32),
+                ("m", ctypes.c_int32), ("K", ctypes.c_int32), ("k_recent", ctypes.c_int32),
+                ("n_self", ctypes.c_int32), ("inner_layers", ctypes.c_int32), ("inner_heads", ctypes.c_int32),
+                ("act", ctypes.c_int32), ("gmask", ctypes.c_int32), ("ln_eps", ctypes.c_float),
+                ("dtype", ctypes.c_int32)]
+
+
+class CBlock(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_void_p) for f in BLOCK_FIELDS]
+
+
+class CWeights(ctypes.Structure):
+    _fields_ = [("inner", ctypes.POINTER(CBlock)), ("cross", ctypes.POINTER(CBlock)),
+                ("self", ctypes.POINTER(CBlock)), ("head_w", ctypes.c_void_p), ("head_b", ctypes.c_void_p)]
+
+
+def library_path() -> str:
+    return os.path.join(HERE, "liblonger.so")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree library; raises LongerError when it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise LongerError("liblonger.so is not built: run `python -m paper_2505_04421_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no fallback path")
+    lib = ctypes.CDLL(path)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    cfgp, blkp, wp = ctypes.POINTER(CConfig), ctypes.POINTER(CBlock), ctypes.POINTER(CWeights)
+    lib.longer_workspace_bytes.restype = sz
+    lib.longer_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
+    lib.longer_kv_cache_bytes.restype = sz
+    lib.longer_kv_cache_bytes.argtypes = [cfgp, i32, i32]
+    lib.longer_inner_transformer.argtypes = [cfgp, blkp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.longer_token_merge.argtypes = [cfgp, blkp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.longer_hybrid_cross_attn.argtypes = [cfgp, blkp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.longer_self_attn_layer.argtypes = [cfgp, blkp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.longer_forward.argtypes = [cfgp, wp, vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.longer_kv_cache_build.argtypes = [cfgp, wp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.longer_score_candidates.argtypes = [cfgp, wp, vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+    lib.longer_last_error.restype = ctypes.c_char_p
+    lib.longer_probe_mfma_layout.argtypes = [vp, vp]
+    for name in ENTRY_POINTS:
+        if name not in ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_last_error"):
+            getattr(lib, name).restype = ctypes.c_int
+    _LIB = lib
+    return lib
+
+
+def exported_symbols() -> List[str]:
+    lib = load_library()
+    return [n for n in ENTRY_POINTS if hasattr(lib, n)]
+
+
+def longer_last_error() -> str:
+    return load_library().longer_last_error().decode()
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise LongerError("%s failed (%d): %s" % (what, rc, longer_last_error()))
+
+
+_ACT = {"gelu_erf": 0, "relu": 1}
+_GMASK = {"full": 0, "causal": 1}
+_DTYPE = {"f32": 0, "bf16": 1}
+
+
+def make_config(cfg) -> CConfig:
+    """From any object with the config's attribute names (e.g. longer_synth.Config)."""
+    return CConfig(d=cfg.d, heads=cfg.heads, ffn_mult=cfg.ffn_mult, m=cfg.m, K=cfg.K, k_recent=cfg.k_recent,
+                   n_self=cfg.n_self, inner_layers=cfg.inner_layers, inner_heads=cfg.inner_heads,
+                   act=_ACT[cfg.act], gmask=_GMASK[cfg.gmask], ln_eps=cfg.ln_eps, dtype=_DTYPE[cfg.dtype])
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda or not t.is_contiguous():
+        raise LongerError("tensor arguments must be contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _require_gpu():
+    import torch
+    if not torch.cuda.is_available():
+        raise LongerError("no GPU visible: the LONGER hot path has no CPU fallback")
+
+
+class DeviceModel:
+    """Uploads a weight tree (numpy fp32, see longer_synth.draw_weights) to the GPU in the
+    config's element type and keeps the C structs that point at it."""
+
+    def __init__(self, cfg, weights: Dict[str, object], device: str = "cuda:0"):
+        import torch
+        _require_gpu()
+        self.cfg = cfg
+        self.ccfg = make_config(cfg)
+        self.device = torch.device(device)
+        self.tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        self._keep = []
+        self.inner = (CBlock * max(1, len(weights["inner"])))(*[self._block(b) for b in weights["inner"]])
+        self.cross = (CBlock * 1)(self._block(weights["cross"]))
+        self.self_ = (CBlock * max(1, len(weights["self"])))(*[self._block(b) for b in weights["self"]])
+        hw, hb = self.upload(weights["head_w"]), self.upload(weights["head_b"])
+        self._keep += [hw, hb]
+        self.weights = CWeights(inner=self.inner, cross=self.cross, self=self.self_,
+                                head_w=hw.data_ptr(), head_b=hb.data_ptr())
+
+    def upload(self, a):
+        import torch
+        import numpy as np
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device).to(self.tdtype).contiguous()
+
+    def _block(self, blk) -> CBlock:
+        ts = {f: self.upload(blk[f]) for f in BLOCK_FIELDS}
+        self._keep.append(ts)
+        return CBlock(**{f: ts[f].data_ptr() for f in BLOCK_FIELDS})
+
+    def empty(self, *shape, dtype=None):
+        import torch
+        return torch.empty(*shape, dtype=dtype or self.tdtype, device=self.device)
+
+    def workspace(self, B: int, L: int, C: int = 0):
+        import torch
+        n = longer_workspace_bytes(self.ccfg, B, L, C)
+        if n == 0:
+            raise LongerError("workspace size query failed: " + longer_last_error())
+        return torch.empty(n, dtype=torch.uint8, device=self.device)
+
+    def kv_cache(self, U: int, L: int):
+        import torch
+        n = longer_kv_cache_bytes(self.ccfg, U, L)
+        if n == 0:
+            raise LongerError("cache size query failed: " + longer_last_error())
+        return torch.empty(n, dtype=torch.uint8, device=self.device)
+
+
+# ----------------------------------------------------------------------------- entry points
+def longer_workspace_bytes(ccfg: CConfig, B: int, L: int, C: int = 0) -> int:
+    return int(load_library().longer_workspace_bytes(ctypes.byref(ccfg), B, L, C))
+
+
+def longer_kv_cache_bytes(ccfg: CConfig, U: int, L: int) -> int:
+    return int(load_library().longer_kv_cache_bytes(ctypes.byref(ccfg), U, L))
+
+
+def longer_inner_transformer(ccfg, inner, H, lens, B, L, Z_out, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_inner_transformer(ctypes.byref(ccfg), inner, _ptr(H), _ptr(lens), B, L, _ptr(Z_out),
+                                                   _ptr(ws), ws.numel(), _stream(stream)), "longer_inner_transformer")
+
+
+def longer_token_merge(ccfg, inner, H, lens, B, L, M_out, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_token_merge(ctypes.byref(ccfg), inner, _ptr(H), _ptr(lens), B, L, _ptr(M_out),
+                                             _ptr(ws), ws.numel(), _stream(stream)), "longer_token_merge")
+
+
+def longer_hybrid_cross_attn(ccfg, cross, G, M, lens, B, L, X_out, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_hybrid_cross_attn(ctypes.byref(ccfg), cross, _ptr(G), _ptr(M), _ptr(lens), B, L,
+                                                   _ptr(X_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "longer_hybrid_cross_attn")
+
+
+def longer_self_attn_layer(ccfg, blk, X_in, lens, B, L, X_out, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_self_attn_layer(ctypes.byref(ccfg), blk, _ptr(X_in), _ptr(lens), B, L, _ptr(X_out),
+                                                 _ptr(ws), ws.numel(), _stream(stream)), "longer_self_attn_layer")
+
+
+def longer_forward(ccfg, weights, H, G, lens, B, L, Y_out, logits_out, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_forward(ctypes.byref(ccfg), ctypes.byref(weights), _ptr(H), _ptr(G), _ptr(lens), B, L,
+                                         _ptr(Y_out), _ptr(logits_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "longer_forward")
+
+
+def longer_kv_cache_build(ccfg, weights, H, lens, U, L, cache, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_kv_cache_build(ctypes.byref(ccfg), ctypes.byref(weights), _ptr(H), _ptr(lens), U, L,
+                                                _ptr(cache), _ptr(ws), ws.numel(), _stream(stream)),
+           "longer_kv_cache_build")
+
+
+def longer_score_candidates(ccfg, weights, cache, lens, U, L, G_cand, C, Yg_out, logits_out, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_score_candidates(ctypes.byref(ccfg), ctypes.byref(weights), _ptr(cache), _ptr(lens), U, L,
+                                                  _ptr(G_cand), C, _ptr(Yg_out), _ptr(logits_out), _ptr(ws), ws.numel(),
+                                                  _stream(stream)), "longer_score_candidates")
+
+
+def longer_probe_mfma_layout(out, stream=None):
+    _require_gpu()
+    _check(load_library().longer_probe_mfma_layout(_ptr(out), _stream(stream)), "longer_probe_mfma_layout")

@@ -1,0 +1,617 @@
+// The transformer-block kernel of the LONGER hot path, in four modes:
+//
+//   MODE_MERGE   token merge (Section 3.4): gather K-groups of raw tokens, run the
+//                InnerTrans blocks on them with attention inside each group, mean-pool
+//                each group to one token (or write the un-pooled rows);
+//   MODE_KVPROJ  key/value side of an attention layer (Eq. 6): K, V = LN1(rows) W + b,
+//                stored as ready-made MFMA operand fragments;
+//   MODE_ATTN    query side of the cross-causal layer (Eq. 5-8) or of a self-causal
+//                layer (Eq. 9): Q projection, masked online-softmax attention over the
+//                stored K/V fragments, output projection, FFN;
+//   MODE_SCORE   candidate scoring of the KV-cache serving path (Section 3.6.3): the m
+//                global tokens of each candidate through all 1 + N layers, attending to
+//                their own globals (inside the tile) and the cached sequence K/V.
+//
+// Every mode runs the same register-resident chain (see device.h); they differ in where
+// rows come from, which attention sources exist and what is written.
+#pragma once
+#include "device.h"
+
+namespace longer {
+
+struct RowSrc {
+  const void* p;        // base of rows (element type T, or fp32 when f32 != 0)
+  long long ustride;    // elements between consecutive users
+  int f32;
+};
+
+struct BlockParams {
+  // packed parameters: first layer of this launch, consecutive layers bstride bytes apart
+  const char* wbase;
+  size_t bstride;
+  int n_layers, FF;
+  float eps, scale_l2e;
+  int act, gmask_causal;
+  const int32_t* lens;
+  int B, L, K, T, m, k;
+  // MODE_MERGE
+  const void* H;
+  void* M_out; int M_f32;
+  void* Z_out;
+  // MODE_KVPROJ / MODE_ATTN rows: rows [0, m0) of a user come from src0, the rest from src1
+  RowSrc src0, src1;
+  int m0;
+  int rows_per_user, tiles_per_user;
+  int gather_recent;    // src1 row of slot i is T_u - k + i (cross layer) instead of i
+  int q0;               // MODE_ATTN: first query row (0: globals + slots, m: slots only)
+  // stored K/V fragments: per user kt_per_user key tiles of NT*GPT fragments each
+  char* kst; char* vst;
+  size_t kv_ustride;
+  int kt_per_user;
+  int KG;               // number of global keys in front of the sequence keys
+  int key_self;         // 1: sequence keys are the k recent slots, 0: all T merged tokens
+  // MODE_ATTN / MODE_SCORE outputs
+  void* X_out; int X_f32; long long X_ustride;
+  float* logits; const float* head;   // head: fp32 [m*D] weights then the bias
+  // MODE_SCORE
+  const void* Gc; int C;
+  const char* cache;    // layer 0 K then V, then layers 1..N
+  size_t c0_ustride, c0_voff, c1_off, c1_lstride, c1_ustride, c1_voff;
+  int kt0, kt1;
+};
+
+// ---------------------------------------------------------------------------- helpers
+template <typename T, int NT>
+__device__ __forceinline__ void load_rows(f32x16 (&x)[NT], const void* base, int is_f32, long long off,
+                                          bool valid, int hi) {
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (valid) {
+        long long o = off + 32 * t + 8 * q + 4 * hi;
+        if (is_f32 || sizeof(T) == 4) {
+          v = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(base) + o);
+        } else {
+          bf16x4 b = *reinterpret_cast<const bf16x4*>(reinterpret_cast<const __bf16*>(base) + o);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = (float)b[e];
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[t][4 * q + e] = v[e];
+    }
+  }
+}
+
+template <typename T, int NT>
+__device__ __forceinline__ void store_rows(const f32x16 (&x)[NT], void* base, int is_f32, long long off,
+                                           bool nonzero, int hi) {
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      f32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = nonzero ? x[t][4 * q + e] : 0.f;
+      long long o = off + 32 * t + 8 * q + 4 * hi;
+      if (is_f32 || sizeof(T) == 4) {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(base) + o) = v;
+      } else {
+        bf16x4 b;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) b[e] = (__bf16)v[e];
+        *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(base) + o) = b;
+      }
+    }
+  }
+}
+
+// accumulator tile initialised with a per-feature bias (transposed layout)
+__device__ __forceinline__ f32x16 bias_tile(const float* b, int tile, int hi) {
+  f32x16 a;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(b + 32 * tile + 8 * q + 4 * hi);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) a[4 * q + e] = v[e];
+  }
+  return a;
+}
+
+__device__ __forceinline__ f32x16 splat16(float v) {
+  f32x16 a;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) a[r] = v;
+  return a;
+}
+
+// bits b in [0,32) set iff base + b lies in [lo, hi)
+__device__ __forceinline__ uint32_t range_bits(int lo, int hi, int base) {
+  int a = max(lo - base, 0), b = min(hi - base, 32);
+  if (b <= a) return 0u;
+  uint32_t upper = b >= 32 ? 0xffffffffu : ((1u << b) - 1u);
+  return upper & ~((1u << a) - 1u);
+}
+
+template <bool EXACT>
+__device__ __forceinline__ float act_fn(float x, int act) {
+  if (act == 1) return fmaxf(x, 0.f);
+  // GELU, exact erf form
+  return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+}
+
+// LayerNorm over the feature dimension of TT token tiles, result as B-operand groups
+template <typename T, int D, int TT>
+__device__ __forceinline__ void layer_norm(const f32x16 (&x)[TT][D / 32], const float* gam, const float* bet,
+                                           float eps, int hi, typename ET<T>::grp (&out)[TT][D / ET<T>::GF]) {
+  using E = ET<T>;
+  constexpr int NT = D / 32;
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) {
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += x[tt][t][r];
+    s += xor32(s);
+    const float mean = s * (1.0f / D);
+    float v = 0.f;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { float dlt = x[tt][t][r] - mean; v += dlt * dlt; }
+    v += xor32(v);
+    const float rstd = 1.0f / sqrtf(v * (1.0f / D) + eps);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      f32x16 g = bias_tile(gam, t, hi), b = bias_tile(bet, t, hi), y;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) y[r] = (x[tt][t][r] - mean) * rstd * g[r] + b[r];
+#pragma unroll
+      for (int gg = 0; gg < E::GPT; ++gg) out[tt][t * E::GPT + gg] = E::pack(y, gg);
+    }
+  }
+}
+
+// One online-softmax step over a 32-key tile.  S holds, for this lane's query, the raw
+// scores of keys tile_row(r, hi); `ab` has bit (8 (r/4) + r%4) set iff that key is visible.
+// Updates the running max / sum, returns the rescale factor for the accumulators and the
+// probabilities as B-operand groups.
+template <typename T>
+__device__ __forceinline__ float softmax_step(const f32x16& S, uint32_t ab, float scale_l2e, float& m, float& l,
+                                              typename ET<T>::grp (&pop)[ET<T>::GPT]) {
+  float sc[16];
+  float mt = kNegBig;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const bool ok = (ab >> (8 * (r / 4) + (r % 4))) & 1u;
+    sc[r] = ok ? S[r] * scale_l2e : kNegBig;
+    mt = fmaxf(mt, sc[r]);
+  }
+  mt = fmaxf(mt, xor32(mt));
+  const float mnew = fmaxf(m, mt);
+  const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+  f32x16 pv;
+  float lt = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const bool ok = (ab >> (8 * (r / 4) + (r % 4))) & 1u;
+    const float pr = ok ? __builtin_amdgcn_exp2f(sc[r] - mnew) : 0.f;
+    pv[r] = pr;
+    lt += pr;
+  }
+  lt += xor32(lt);
+  l = l * alpha + lt;
+  m = mnew;
+#pragma unroll
+  for (int g = 0; g < ET<T>::GPT; ++g) pop[g] = ET<T>::pack(pv, g);
+  return alpha;
+}
+
+// ---------------------------------------------------------------------------- the kernel
+template <typename T, int D, int DH, int TT, int MODE>
+__global__ void __launch_bounds__(kThreads) block_kernel(const BlockParams p) {
+  using E = ET<T>;
+  using grp = typename E::grp;
+  constexpr int NT = D / 32, NG = D / E::GF, GPT = E::GPT;
+  constexpr int SEGV = NG * 64;
+  constexpr int HPT = 32 / DH;        // heads per 32-feature tile
+  constexpr int GPH = DH / E::GF;     // operand groups per head
+  constexpr bool FUSED = (MODE == MODE_MERGE || MODE == MODE_SCORE);
+  constexpr bool EXT = (MODE == MODE_ATTN || MODE == MODE_SCORE);
+  static_assert(DH == 16 || DH == 32, "head width");
+  __shared__ uint4 lds[2 * SEGV];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j = lane & 31, hi = lane >> 5;
+  const int NC = p.FF / 32;
+  const size_t vec_off = (size_t)(4 * NT + 2 * NC) * SEGV * 16;
+
+  // ------------------------------------------------------------------ rows of this wave
+  bool valid[TT];          // the lane's token exists and takes part
+  bool inrange[TT];        // the lane's row exists in the output tensor
+  int usr[TT], Tu[TT];
+  long long out_off[TT];   // element offset of the lane's output row
+  uint32_t tilebits[TT];   // MODE_MERGE / MODE_SCORE: in-tile keys visible to this lane
+  int lo1[TT], hi1[TT], lo2[TT], hi2[TT], kthi[TT];   // EXT: visible key ranges, key tile count
+  f32x16 resid[TT][NT];
+
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) {
+    const int tile = (blockIdx.x * kWaves + wave) * TT + tt;
+    valid[tt] = false; inrange[tt] = false; usr[tt] = 0; Tu[tt] = 0; out_off[tt] = 0; tilebits[tt] = 0;
+    lo1[tt] = hi1[tt] = lo2[tt] = hi2[tt] = kthi[tt] = 0;
+    if (MODE == MODE_MERGE) {
+      const long long slot = (long long)tile * 32 + j;
+      const long long gidx = slot / p.K;
+      const int jj = (int)(slot - gidx * p.K);
+      const int u = (int)(gidx / p.T), t = (int)(gidx - (long long)u * p.T);
+      inrange[tt] = u < p.B;
+      int len = 0;
+      if (inrange[tt]) { len = p.lens ? p.lens[u] : p.L; len = min(max(len, 0), p.L); }
+      const int pos = t * p.K + jj;
+      valid[tt] = inrange[tt] && pos < len;
+      usr[tt] = u; Tu[tt] = len;             // Tu holds the raw length here
+      out_off[tt] = slot;                    // group-slot index; scaled when writing
+      load_rows<T, NT>(resid[tt], p.H, 0, ((long long)u * p.L + pos) * D, valid[tt], hi);
+      const uint32_t vb = (uint32_t)__ballot(valid[tt]);
+      const uint32_t gb = (p.K >= 32 ? 0xffffffffu : ((1u << p.K) - 1u)) << (p.K * (j / p.K));
+      tilebits[tt] = (gb & vb) >> (4 * hi);
+    } else if (MODE == MODE_KVPROJ) {
+      const int u = tile / p.tiles_per_user, kt = tile - u * p.tiles_per_user;
+      const int c = 32 * kt + j;
+      inrange[tt] = u < p.B;
+      valid[tt] = inrange[tt] && c < p.rows_per_user;
+      usr[tt] = u; Tu[tt] = kt;              // Tu holds the key tile index here
+      const bool first = c < p.m0;
+      const void* sp = first ? p.src0.p : p.src1.p;
+      const int sf = first ? p.src0.f32 : p.src1.f32;
+      const long long su = first ? p.src0.ustride : p.src1.ustride;
+      load_rows<T, NT>(resid[tt], sp, sf, su * u + (long long)(first ? c : c - p.m0) * D, valid[tt], hi);
+    } else if (MODE == MODE_ATTN) {
+      const int u = tile / p.tiles_per_user, qt = tile - u * p.tiles_per_user;
+      const int a = p.q0 + 32 * qt + j;
+      inrange[tt] = u < p.B && (32 * qt + j) < p.rows_per_user;
+      int len = 0;
+      if (u < p.B) { len = p.lens ? p.lens[u] : p.L; len = min(max(len, 0), p.L); }
+      const int tu = (len + p.K - 1) / p.K;
+      const bool glob = a < p.m;
+      const int i = a - p.m, i0 = max(p.k - tu, 0);
+      valid[tt] = inrange[tt] && (glob || i >= i0);
+      usr[tt] = u; Tu[tt] = tu;
+      out_off[tt] = p.X_ustride * u + (long long)a * D;
+      const void* sp = glob ? p.src0.p : p.src1.p;
+      const int sf = glob ? p.src0.f32 : p.src1.f32;
+      const long long su = glob ? p.src0.ustride : p.src1.ustride;
+      const int row = glob ? a : (p.gather_recent ? tu - p.k + i : i);
+      load_rows<T, NT>(resid[tt], sp, sf, su * u + (long long)row * D, valid[tt], hi);
+      // visible key ranges (Eq. 8 by token type)
+      const int s0 = p.key_self ? i0 : 0;
+      if (glob) {
+        lo1[tt] = p.gmask_causal ? a : 0; hi1[tt] = p.KG;
+        lo2[tt] = p.KG + s0; hi2[tt] = p.KG + (p.key_self ? p.k : tu);
+      } else {
+        lo1[tt] = 0; hi1[tt] = 0;
+        lo2[tt] = p.KG + s0; hi2[tt] = p.KG + (p.key_self ? i : tu - p.k + i) + 1;
+      }
+      if (!valid[tt]) { hi1[tt] = lo1[tt]; hi2[tt] = lo2[tt]; }
+      kthi[tt] = (p.KG + (p.key_self ? p.k : tu) + 31) / 32;
+      if (u >= p.B) kthi[tt] = 0;
+    } else {  // MODE_SCORE
+      const int u = blockIdx.y;
+      const int a = 32 * tile + j;
+      const int cand = a / p.m, gi = a - cand * p.m;
+      inrange[tt] = cand < p.C;
+      valid[tt] = inrange[tt];
+      int len = p.lens ? p.lens[u] : p.L; len = min(max(len, 0), p.L);
+      usr[tt] = u; Tu[tt] = (len + p.K - 1) / p.K;
+      out_off[tt] = ((long long)u * p.C * p.m + a) * D;
+      load_rows<T, NT>(resid[tt], p.Gc, 0, out_off[tt], valid[tt], hi);
+      const uint32_t vb = (uint32_t)__ballot(valid[tt]);
+      const int gbase = p.m * (j / p.m);
+      tilebits[tt] = (range_bits(gbase + (p.gmask_causal ? gi : 0), gbase + p.m, 0) & vb) >> (4 * hi);
+    }
+  }
+
+  if (MODE == MODE_MERGE) {
+    // a workgroup whose tokens are all padding writes zeros and leaves
+    bool any = false;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) any |= valid[tt];
+    if (!__syncthreads_or(any ? 1 : 0)) {
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) {
+        if (!inrange[tt]) continue;
+        if (p.Z_out) store_rows<T, NT>(resid[tt], p.Z_out, 0, out_off[tt] * D, false, hi);
+        if (p.M_out && (out_off[tt] % p.K) == 0)
+          store_rows<T, NT>(resid[tt], p.M_out, p.M_f32, (out_off[tt] / p.K) * D, false, hi);
+      }
+      return;
+    }
+  }
+
+  WStream<SEGV, MODE, NT> ws;
+  const int steps = MODE == MODE_KVPROJ ? 2 * NT : (MODE == MODE_ATTN ? 2 * NT + 2 * NC : 4 * NT + 2 * NC);
+  ws.init(lds, p.wbase, p.bstride, steps, p.n_layers);
+
+  for (int layer = 0; layer < p.n_layers; ++layer) {
+    const float* vec = reinterpret_cast<const float*>(p.wbase + (size_t)layer * p.bstride + vec_off);
+    const VecLayout vl{D, p.FF};
+    grp xn[TT][NG];
+    layer_norm<T, D, TT>(resid, vec + vl.ln1_g(), vec + vl.ln1_b(), p.eps, hi, xn);
+    grp oop[TT][NG];
+
+#pragma unroll
+    for (int ft = 0; ft < NT; ++ft) {
+      f32x16 aq[TT], ak[TT], av[TT];
+      if (MODE != MODE_KVPROJ) {
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) aq[tt] = bias_tile(vec + vl.bq(), ft, hi);
+#pragma unroll
+        for (int s = 0; s < NG; ++s) {
+          const grp w = ws.template frag<grp>(s);
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt) aq[tt] = E::mma(w, xn[tt][s], aq[tt]);
+        }
+        ws.advance();
+      }
+      if (FUSED || MODE == MODE_KVPROJ) {
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) ak[tt] = bias_tile(vec + vl.bk(), ft, hi);
+#pragma unroll
+        for (int s = 0; s < NG; ++s) {
+          const grp w = ws.template frag<grp>(s);
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt) ak[tt] = E::mma(w, xn[tt][s], ak[tt]);
+        }
+        ws.advance();
+        const float bvl = vec[vl.bv() + 32 * ft + j];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) av[tt] = splat16(bvl);
+#pragma unroll
+        for (int s = 0; s < NG; ++s) {
+          const grp w = ws.template frag<grp>(s);
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt) av[tt] = E::mma(xn[tt][s], w, av[tt]);   // operands swapped: lane = feature
+        }
+        ws.advance();
+      }
+      if (MODE == MODE_KVPROJ) {
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+          if (!inrange[tt]) continue;
+          const size_t fo = (size_t)usr[tt] * p.kv_ustride + ((size_t)(Tu[tt] * NT + ft) * GPT) * 1024 + lane * 16;
+#pragma unroll
+          for (int g = 0; g < GPT; ++g) {
+            *reinterpret_cast<grp*>(p.kst + fo + g * 1024) = E::pack(ak[tt], g);
+            *reinterpret_cast<grp*>(p.vst + fo + g * 1024) = E::pack(av[tt], g);
+          }
+        }
+        continue;
+      }
+
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) {
+        grp qop[GPT];
+#pragma unroll
+        for (int g = 0; g < GPT; ++g) qop[g] = E::pack(aq[tt], g);
+        float mrun[HPT], lrun[HPT];
+        f32x16 acc[HPT];
+#pragma unroll
+        for (int hh = 0; hh < HPT; ++hh) { mrun[hh] = kNegBig; lrun[hh] = 0.f; acc[hh] = splat16(0.f); }
+
+        if (FUSED) {   // keys of the lane's own tile (group attention / the candidate's own globals)
+          grp kop[GPT], vop[GPT];
+#pragma unroll
+          for (int g = 0; g < GPT; ++g) { kop[g] = E::pack(ak[tt], g); vop[g] = E::pack(av[tt], g); }
+#pragma unroll
+          for (int hh = 0; hh < HPT; ++hh) {
+            f32x16 S = splat16(0.f);
+#pragma unroll
+            for (int g2 = 0; g2 < GPH; ++g2) S = E::mma(kop[hh * GPH + g2], qop[hh * GPH + g2], S);
+            grp pop[GPT];
+            softmax_step<T>(S, tilebits[tt], p.scale_l2e, mrun[hh], lrun[hh], pop);
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) acc[hh] = E::mma(vop[g], pop[g], acc[hh]);
+          }
+        }
+        if (EXT) {     // stored K/V fragments (all waves of a tile's user read the same ones)
+          const char* kb; const char* vb; int nkt, rlo, rhi;
+          if (MODE == MODE_ATTN) {
+            kb = p.kst + (size_t)usr[tt] * p.kv_ustride; vb = p.vst + (size_t)usr[tt] * p.kv_ustride;
+            nkt = kthi[tt]; rlo = 0; rhi = 0;
+          } else {
+            const int i0 = max(p.k - Tu[tt], 0);
+            if (layer == 0) {
+              kb = p.cache + (size_t)usr[tt] * p.c0_ustride; vb = kb + p.c0_voff;
+              nkt = min(p.kt0, (Tu[tt] + 31) / 32); rlo = 0; rhi = Tu[tt];
+            } else {
+              kb = p.cache + p.c1_off + (size_t)(layer - 1) * p.c1_lstride + (size_t)usr[tt] * p.c1_ustride;
+              vb = kb + p.c1_voff;
+              nkt = Tu[tt] > 0 ? p.kt1 : 0; rlo = i0; rhi = p.k;
+            }
+            if (!valid[tt]) rhi = rlo;
+          }
+          for (int kt = 0; kt < nkt; ++kt) {
+            uint32_t bits;
+            if (MODE == MODE_ATTN) bits = range_bits(lo1[tt], hi1[tt], 32 * kt) | range_bits(lo2[tt], hi2[tt], 32 * kt);
+            else bits = range_bits(rlo, rhi, 32 * kt);
+            const uint32_t ab = bits >> (4 * hi);
+            const size_t fo = ((size_t)(kt * NT + ft) * GPT) * 1024 + lane * 16;
+            grp kfr[GPT], vfr[GPT];
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) {
+              kfr[g] = *reinterpret_cast<const grp*>(kb + fo + g * 1024);
+              vfr[g] = *reinterpret_cast<const grp*>(vb + fo + g * 1024);
+            }
+#pragma unroll
+            for (int hh = 0; hh < HPT; ++hh) {
+              f32x16 S = splat16(0.f);
+#pragma unroll
+              for (int g2 = 0; g2 < GPH; ++g2) S = E::mma(kfr[hh * GPH + g2], qop[hh * GPH + g2], S);
+              grp pop[GPT];
+              const float alpha = softmax_step<T>(S, ab, p.scale_l2e, mrun[hh], lrun[hh], pop);
+#pragma unroll
+              for (int r = 0; r < 16; ++r) acc[hh][r] *= alpha;
+#pragma unroll
+              for (int g = 0; g < GPT; ++g) acc[hh] = E::mma(vfr[g], pop[g], acc[hh]);
+            }
+          }
+        }
+        // normalise; with two heads per tile each head owns half of the accumulator rows
+        f32x16 o;
+        float inv[HPT];
+#pragma unroll
+        for (int hh = 0; hh < HPT; ++hh) inv[hh] = lrun[hh] > 0.f ? 1.0f / lrun[hh] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int hh = HPT == 1 ? 0 : r / 8;
+          o[r] = acc[hh][r] * inv[hh];
+        }
+#pragma unroll
+        for (int g = 0; g < GPT; ++g) oop[tt][ft * GPT + g] = E::pack(o, g);
+      }
+    }
+    if (MODE == MODE_KVPROJ) return;
+
+    // output projection + residual
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const f32x16 bo = bias_tile(vec + vl.bo(), nt, hi);
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) resid[tt][nt] += bo;
+#pragma unroll
+      for (int s = 0; s < NG; ++s) {
+        const grp w = ws.template frag<grp>(s);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) resid[tt][nt] = E::mma(w, oop[tt][s], resid[tt][nt]);
+      }
+      ws.advance();
+    }
+
+    // FFN, 32 hidden features at a time: hidden chunk never leaves registers
+    layer_norm<T, D, TT>(resid, vec + vl.ln2_g(), vec + vl.ln2_b(), p.eps, hi, xn);
+#pragma unroll 1
+    for (int c = 0; c < NC; ++c) {
+      f32x16 ah[TT];
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) ah[tt] = bias_tile(vec + vl.b1(), c, hi);
+#pragma unroll
+      for (int s = 0; s < NG; ++s) {
+        const grp w = ws.template frag<grp>(s);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) ah[tt] = E::mma(w, xn[tt][s], ah[tt]);
+      }
+      ws.advance();
+      grp hop[TT][GPT];
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ah[tt][r] = act_fn<sizeof(T) == 4>(ah[tt][r], p.act);
+#pragma unroll
+        for (int g = 0; g < GPT; ++g) hop[tt][g] = E::pack(ah[tt], g);
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+        for (int g = 0; g < GPT; ++g) {
+          const grp w = ws.template frag<grp>(nt * GPT + g);
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt) resid[tt][nt] = E::mma(w, hop[tt][g], resid[tt][nt]);
+        }
+      }
+      ws.advance();
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const f32x16 b2 = bias_tile(vec + vl.b2(), nt, hi);
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) resid[tt][nt] += b2;
+    }
+  }
+
+  // ------------------------------------------------------------------ epilogues
+  if (MODE == MODE_MERGE) {
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      if (p.Z_out && inrange[tt]) store_rows<T, NT>(resid[tt], p.Z_out, 0, out_off[tt] * D, valid[tt], hi);
+      if (p.M_out) {
+        // mean over the valid tokens of each group: tokens of a group sit on K adjacent lanes
+        const int jj = (int)(out_off[tt] % p.K);
+        const int t = (int)((out_off[tt] / p.K) % p.T);
+        const int nv = min(max(Tu[tt] - t * p.K, 0), p.K);
+        const float wgt = valid[tt] ? 1.0f / (float)nv : 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float v = resid[tt][nt][r] * wgt;
+            for (int sft = 1; sft < p.K; sft <<= 1) v += __shfl_xor(v, sft, 64);
+            resid[tt][nt][r] = v;
+          }
+        if (inrange[tt] && jj == 0)
+          store_rows<T, NT>(resid[tt], p.M_out, p.M_f32, (out_off[tt] / p.K) * D, true, hi);
+      }
+    }
+  } else if (MODE == MODE_ATTN || MODE == MODE_SCORE) {
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      if (p.X_out && inrange[tt]) store_rows<T, NT>(resid[tt], p.X_out, p.X_f32, out_off[tt], valid[tt], hi);
+      if (p.logits) {
+        // logit = <head_w, flatten(global rows)> + head_b
+        const int tile = (blockIdx.x * kWaves + wave) * TT + tt;
+        int a, width;       // row inside the head's m rows; lanes per logit
+        bool take;
+        if (MODE == MODE_ATTN) {
+          const int qt = tile % p.tiles_per_user;
+          a = p.q0 + 32 * qt + j; take = valid[tt] && a < p.m; width = 32;
+        } else {
+          a = (32 * tile + j) % p.m; take = valid[tt]; width = p.m;
+        }
+        float part = 0.f;
+        if (take) {
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            const f32x16 hw = bias_tile(p.head + (size_t)a * D, nt, hi);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) part += resid[tt][nt][r] * hw[r];
+          }
+        }
+        part += xor32(part);
+        for (int sft = 1; sft < width; sft <<= 1) part += __shfl_xor(part, sft, 64);
+        part += p.head[(size_t)p.m * D];
+        if (MODE == MODE_ATTN) {
+          if (lane == 0 && usr[tt] < p.B && (tile % p.tiles_per_user) == 0 && p.q0 == 0) p.logits[usr[tt]] = part;
+        } else {
+          const int cand = (32 * tile + j) / p.m;
+          if (hi == 0 && (j % p.m) == 0 && cand < p.C) p.logits[(size_t)usr[tt] * p.C + cand] = part;
+        }
+      }
+    }
+  }
+}
+
+// Host-side launcher, one definition per (T, D, DH) instantiation file.
+template <typename T, int D, int DH>
+int launch_block(int mode, int tt, const BlockParams& p, dim3 grid, hipStream_t stream);
+
+#define LONGER_INSTANTIATE(T, D, DH)                                                                  \
+  template <>                                                                                         \
+  int launch_block<T, D, DH>(int mode, int tt, const BlockParams& p, dim3 grid, hipStream_t stream) { \
+    if (tt == 2) {                                                                                    \
+      if (mode == MODE_MERGE) hipLaunchKernelGGL((block_kernel<T, D, DH, 2, MODE_MERGE>), grid, dim3(kThreads), 0, stream, p); \
+      else return -1;                                                                                 \
+    } else {                                                                                          \
+      switch (mode) {                                                                                 \
+        case MODE_MERGE: hipLaunchKernelGGL((block_kernel<T, D, DH, 1, MODE_MERGE>), grid, dim3(kThreads), 0, stream, p); break;   \
+        case MODE_KVPROJ: hipLaunchKernelGGL((block_kernel<T, D, DH, 1, MODE_KVPROJ>), grid, dim3(kThreads), 0, stream, p); break; \
+        case MODE_ATTN: hipLaunchKernelGGL((block_kernel<T, D, DH, 1, MODE_ATTN>), grid, dim3(kThreads), 0, stream, p); break;     \
+        case MODE_SCORE: hipLaunchKernelGGL((block_kernel<T, D, DH, 1, MODE_SCORE>), grid, dim3(kThreads), 0, stream, p); break;   \
+        default: return -1;                                                                           \
+      }                                                                                               \
+    }                                                                                                 \
+    return hipGetLastError() == hipSuccess ? 0 : -3;                                                  \
+  }
+
+}  // namespace longer

@@ -1,0 +1,540 @@
+// C ABI of the library (declared in include/longer.h): argument checks, workspace
+// layout, parameter packing and the launch sequence of each entry point.
+#include "../../include/longer.h"
+#include "block_kernel.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace longer {
+
+// explicit specialisations defined in the inst_*.hip files
+template <> int launch_block<__bf16, 64, 16>(int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<__bf16, 128, 16>(int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<__bf16, 256, 32>(int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<float, 32, 16>(int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<float, 64, 16>(int, int, const BlockParams&, dim3, hipStream_t);
+
+typedef int (*launch_fn)(int, int, const BlockParams&, dim3, hipStream_t);
+
+static launch_fn find_launch(int dtype, int D, int DH) {
+  if (dtype == LONGER_BF16) {
+    if (D == 64 && DH == 16) return &launch_block<__bf16, 64, 16>;
+    if (D == 128 && DH == 16) return &launch_block<__bf16, 128, 16>;
+    if (D == 256 && DH == 32) return &launch_block<__bf16, 256, 32>;
+  } else if (dtype == LONGER_F32) {
+    if (D == 32 && DH == 16) return &launch_block<float, 32, 16>;
+    if (D == 64 && DH == 16) return &launch_block<float, 64, 16>;
+  }
+  return nullptr;
+}
+
+static thread_local char g_err[256] = "";
+
+static int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+// ------------------------------------------------------------------------------------
+// Pack kernel: raw [in, out] matrices of one block -> MFMA A/B fragments in the order
+// the block kernel streams them, plus the small vectors as fp32.
+struct RawBlock { longer_block b; };
+
+template <typename T>
+__global__ void pack_block_kernel(const RawBlock raw, char* dst, int D, int FF) {
+  using E = ET<T>;
+  const int NT = D / 32, NC = FF / 32, NG = D / E::GF, SEGV = NG * 64;
+  const long long nvec16 = (long long)(4 * NT + 2 * NC) * SEGV;
+  const long long nvecf = 9LL * D + FF;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < nvec16) {
+    const int seg = (int)(idx / SEGV);
+    const int within = (int)(idx - (long long)seg * SEGV);
+    const int f = within / 64, lane = within % 64, n_in = lane & 31, hi = lane >> 5;
+    const T* W;
+    int ncols, nt, s;
+    if (seg < 4 * NT) {
+      const int which = seg / NT;
+      W = reinterpret_cast<const T*>(which == 0 ? raw.b.wq : which == 1 ? raw.b.wk : which == 2 ? raw.b.wv : raw.b.wo);
+      ncols = D; nt = seg % NT; s = f;
+    } else {
+      const int c = (seg - 4 * NT) / 2;
+      if (((seg - 4 * NT) & 1) == 0) { W = reinterpret_cast<const T*>(raw.b.w1); ncols = FF; nt = c; s = f; }
+      else { W = reinterpret_cast<const T*>(raw.b.w2); ncols = D; nt = f / E::GPT; s = c * E::GPT + (f % E::GPT); }
+    }
+    const int t = s / E::GPT, g = s % E::GPT;
+    typename E::grp out;
+    for (int e = 0; e < E::EPL; ++e) {
+      const int k = 32 * t + tile_row(E::EPL * g + e, hi);
+      out[e] = W[(size_t)k * ncols + 32 * nt + n_in];
+    }
+    reinterpret_cast<typename E::grp*>(dst)[idx] = out;
+  } else if (idx < nvec16 + nvecf) {
+    const int i = (int)(idx - nvec16);
+    const VecLayout vl{D, FF};
+    float* v = reinterpret_cast<float*>(dst + (size_t)nvec16 * 16);
+    const T* src;
+    int off;
+    if (i < vl.ln1_b()) { src = (const T*)raw.b.ln1_g; off = i; }
+    else if (i < vl.bq()) { src = (const T*)raw.b.ln1_b; off = i - vl.ln1_b(); }
+    else if (i < vl.bk()) { src = (const T*)raw.b.bq; off = i - vl.bq(); }
+    else if (i < vl.bv()) { src = (const T*)raw.b.bk; off = i - vl.bk(); }
+    else if (i < vl.bo()) { src = (const T*)raw.b.bv; off = i - vl.bv(); }
+    else if (i < vl.ln2_g()) { src = (const T*)raw.b.bo; off = i - vl.bo(); }
+    else if (i < vl.ln2_b()) { src = (const T*)raw.b.ln2_g; off = i - vl.ln2_g(); }
+    else if (i < vl.b2()) { src = (const T*)raw.b.ln2_b; off = i - vl.ln2_b(); }
+    else if (i < vl.b1()) { src = (const T*)raw.b.b2; off = i - vl.b2(); }
+    else { src = (const T*)raw.b.b1; off = i - vl.b1(); }
+    v[i] = (float)src[off];
+  }
+}
+
+template <typename T>
+__global__ void pack_head_kernel(const T* hw, const T* hb, float* dst, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = (float)hw[i];
+  else if (i == n) dst[i] = (float)hb[0];
+}
+
+__global__ void probe_kernel(int32_t* out) {
+  const int lane = threadIdx.x & 63, j = lane & 31, hi = lane >> 5;
+  // one contraction slot (hi = 0, element 0) carries a value, all others are zero
+  bf16x8 a_row = {0, 0, 0, 0, 0, 0, 0, 0}, a_one = a_row, b_col = a_row, b_one = a_row;
+  if (hi == 0) { a_row[0] = (__bf16)(float)j; a_one[0] = (__bf16)1.0f; b_col[0] = (__bf16)(float)j; b_one[0] = (__bf16)1.0f; }
+  f32x16 z = splat16(0.f);
+  f32x16 rows = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_row, b_one, z, 0, 0, 0);
+  f32x16 cols = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_one, b_col, z, 0, 0, 0);
+  for (int r = 0; r < 16; ++r) out[lane * 16 + r] = (int)rows[r] * 32 + (int)cols[r];
+  const float fa_row = hi == 0 ? (float)j : 0.f, f_one = hi == 0 ? 1.f : 0.f;
+  rows = __builtin_amdgcn_mfma_f32_32x32x2f32(fa_row, f_one, z, 0, 0, 0);
+  cols = __builtin_amdgcn_mfma_f32_32x32x2f32(f_one, fa_row, z, 0, 0, 0);
+  for (int r = 0; r < 16; ++r) out[1024 + lane * 16 + r] = (int)rows[r] * 32 + (int)cols[r];
+}
+
+// ------------------------------------------------------------------------------------
+struct Shape {
+  int D, DH, DHi, FF, es, n, NT, GPT;
+  size_t pb;          // packed block bytes
+  launch_fn main_fn, inner_fn;
+};
+
+static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool need_main) {
+  if (!c) return fail(LONGER_ERR_ARG, "config is NULL");
+  if (c->dtype != LONGER_F32 && c->dtype != LONGER_BF16) return fail(LONGER_ERR_ARG, "dtype %d unknown", c->dtype);
+  if (c->act != LONGER_ACT_GELU_ERF && c->act != LONGER_ACT_RELU) return fail(LONGER_ERR_ARG, "act %d unknown", c->act);
+  if (c->gmask != LONGER_GMASK_FULL && c->gmask != LONGER_GMASK_CAUSAL) return fail(LONGER_ERR_ARG, "gmask %d unknown", c->gmask);
+  if (c->d <= 0 || c->d % 32) return fail(LONGER_ERR_ARG, "d=%d must be a positive multiple of 32", c->d);
+  if (c->ffn_mult <= 0) return fail(LONGER_ERR_ARG, "ffn_mult=%d", c->ffn_mult);
+  if (!(c->ln_eps > 0.f)) return fail(LONGER_ERR_ARG, "ln_eps must be positive");
+  if (c->K <= 0 || 32 % c->K) return fail(LONGER_ERR_ARG, "K=%d must divide 32", c->K);
+  if (c->m <= 0 || 32 % c->m) return fail(LONGER_ERR_ARG, "m=%d must divide 32", c->m);
+  if (c->k_recent <= 0) return fail(LONGER_ERR_ARG, "k_recent=%d", c->k_recent);
+  if (c->n_self < 0 || c->inner_layers < 0 || c->n_self + c->inner_layers + 1 > 32)
+    return fail(LONGER_ERR_ARG, "layer counts out of range");
+  s->D = c->d; s->FF = c->ffn_mult * c->d; s->es = c->dtype == LONGER_BF16 ? 2 : 4;
+  s->n = c->m + c->k_recent; s->NT = c->d / 32; s->GPT = c->dtype == LONGER_BF16 ? 2 : 4;
+  s->pb = packed_block_bytes(s->D, s->FF, s->es);
+  s->main_fn = s->inner_fn = nullptr; s->DH = s->DHi = 0;
+  if (need_main) {
+    if (c->heads <= 0 || c->d % c->heads) return fail(LONGER_ERR_ARG, "heads=%d does not divide d=%d", c->heads, c->d);
+    s->DH = c->d / c->heads;
+    s->main_fn = find_launch(c->dtype, c->d, s->DH);
+    if (!s->main_fn) return fail(LONGER_ERR_ARG, "unsupported shape: dtype=%d d=%d head width=%d", c->dtype, c->d, s->DH);
+  }
+  if (need_inner) {
+    if (c->inner_layers < 1) return fail(LONGER_ERR_ARG, "inner_layers=%d", c->inner_layers);
+    if (c->inner_heads <= 0 || c->d % c->inner_heads) return fail(LONGER_ERR_ARG, "inner_heads=%d does not divide d", c->inner_heads);
+    s->DHi = c->d / c->inner_heads;
+    s->inner_fn = find_launch(c->dtype, c->d, s->DHi);
+    if (!s->inner_fn) return fail(LONGER_ERR_ARG, "unsupported shape: dtype=%d d=%d inner head width=%d", c->dtype, c->d, s->DHi);
+  }
+  return 0;
+}
+
+static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+// workspace layout shared by all entry points
+struct Layout {
+  size_t packed, head, M, kst, vst, xa, xb, total;
+  size_t kv_ustride;
+  int ktmax;
+};
+
+static Layout make_layout(const longer_config* c, const Shape& s, int B, int L) {
+  Layout l;
+  const int T = cdiv(L, c->K);
+  const int nblk = c->inner_layers + 1 + c->n_self;
+  size_t o = 0;
+  l.packed = o; o += (size_t)nblk * s.pb;
+  l.head = o; o += align256(((size_t)c->m * s.D + 1) * 4);
+  l.M = o; o += align256((size_t)B * T * s.D * 4);
+  l.ktmax = cdiv((long long)c->m + T, 32) > cdiv(s.n, 32) ? cdiv((long long)c->m + T, 32) : cdiv(s.n, 32);
+  l.kv_ustride = (size_t)l.ktmax * s.NT * s.GPT * 1024;
+  l.kst = o; o += (size_t)B * l.kv_ustride;
+  l.vst = o; o += (size_t)B * l.kv_ustride;
+  l.xa = o; o += align256((size_t)B * s.n * s.D * 4);
+  l.xb = o; o += align256((size_t)B * s.n * s.D * 4);
+  l.total = o;
+  return l;
+}
+
+struct CacheLayout {
+  int kt0, kt1;
+  size_t c0_ustride, c0_voff, c1_off, c1_lstride, c1_ustride, c1_voff, total;
+};
+
+static CacheLayout make_cache_layout(const longer_config* c, const Shape& s, int U, int L) {
+  CacheLayout cl;
+  const int T = cdiv(L, c->K);
+  cl.kt0 = cdiv(T, 32); cl.kt1 = cdiv(c->k_recent, 32);
+  const size_t tile = (size_t)s.NT * s.GPT * 1024;
+  cl.c0_voff = (size_t)cl.kt0 * tile; cl.c0_ustride = 2 * cl.c0_voff;
+  cl.c1_off = (size_t)U * cl.c0_ustride;
+  cl.c1_voff = (size_t)cl.kt1 * tile; cl.c1_ustride = 2 * cl.c1_voff;
+  cl.c1_lstride = (size_t)U * cl.c1_ustride;
+  cl.total = cl.c1_off + (size_t)c->n_self * cl.c1_lstride;
+  return cl;
+}
+
+static int pack_blocks(const longer_config* c, const Shape& s, const longer_block* blocks, int nb, char* dst, hipStream_t st) {
+  for (int i = 0; i < nb; ++i) {
+    const longer_block& b = blocks[i];
+    const void* ptrs[16] = {b.ln1_g, b.ln1_b, b.wq, b.bq, b.wk, b.bk, b.wv, b.bv, b.wo, b.bo, b.ln2_g, b.ln2_b, b.w1, b.b1, b.w2, b.b2};
+    for (int j = 0; j < 16; ++j)
+      if (!ptrs[j]) return fail(LONGER_ERR_ARG, "block %d: parameter pointer %d is NULL", i, j);
+    RawBlock rb; rb.b = b;
+    const long long n = (long long)packed_num_segs(s.D, s.FF) * (s.D / (32 / s.es)) * 64 + 9LL * s.D + s.FF;
+    const int grid = cdiv(n, 256);
+    if (c->dtype == LONGER_BF16) hipLaunchKernelGGL(pack_block_kernel<__bf16>, dim3(grid), dim3(256), 0, st, rb, dst + (size_t)i * s.pb, s.D, s.FF);
+    else hipLaunchKernelGGL(pack_block_kernel<float>, dim3(grid), dim3(256), 0, st, rb, dst + (size_t)i * s.pb, s.D, s.FF);
+  }
+  return hipGetLastError() == hipSuccess ? 0 : fail(LONGER_ERR_HIP, "pack kernel launch failed");
+}
+
+static int pack_head(const longer_config* c, const Shape& s, const longer_weights* w, float* dst, hipStream_t st) {
+  if (!w->head_w || !w->head_b) return fail(LONGER_ERR_ARG, "head_w / head_b is NULL but logits were asked for");
+  const int n = c->m * s.D;
+  if (c->dtype == LONGER_BF16) hipLaunchKernelGGL(pack_head_kernel<__bf16>, dim3(cdiv(n + 1, 256)), dim3(256), 0, st, (const __bf16*)w->head_w, (const __bf16*)w->head_b, dst, n);
+  else hipLaunchKernelGGL(pack_head_kernel<float>, dim3(cdiv(n + 1, 256)), dim3(256), 0, st, (const float*)w->head_w, (const float*)w->head_b, dst, n);
+  return hipGetLastError() == hipSuccess ? 0 : fail(LONGER_ERR_HIP, "head pack launch failed");
+}
+
+static BlockParams base_params(const longer_config* c, const Shape& s, const int32_t* lens, int B, int L, int DH) {
+  BlockParams p;
+  memset(&p, 0, sizeof(p));
+  p.bstride = s.pb; p.n_layers = 1; p.FF = s.FF; p.eps = c->ln_eps;
+  p.scale_l2e = (float)(1.4426950408889634 / std::sqrt((double)DH));
+  p.act = c->act; p.gmask_causal = c->gmask == LONGER_GMASK_CAUSAL;
+  p.lens = lens; p.B = B; p.L = L; p.K = c->K; p.T = cdiv(L, c->K); p.m = c->m; p.k = c->k_recent;
+  return p;
+}
+
+static int check_common(const void* ws, size_t ws_bytes, size_t need, int B, int L) {
+  if (B <= 0 || L <= 0) return fail(LONGER_ERR_ARG, "B=%d, L=%d must be positive", B, L);
+  if (!ws) return fail(LONGER_ERR_ARG, "workspace is NULL");
+  if (((uintptr_t)ws & 255) != 0) return fail(LONGER_ERR_ARG, "workspace must be 256-byte aligned");
+  if (ws_bytes < need) return fail(LONGER_ERR_WS, "workspace too small: %zu < %zu bytes", ws_bytes, need);
+  return 0;
+}
+
+// -- stage launchers (packed parameters already in place) -----------------------------
+static int run_merge(const longer_config* c, const Shape& s, const char* packed, const void* H, const int32_t* lens,
+                     int B, int L, void* M_out, int M_f32, void* Z_out, hipStream_t st) {
+  BlockParams p = base_params(c, s, lens, B, L, s.DHi);
+  p.wbase = packed; p.n_layers = c->inner_layers;
+  p.H = H; p.M_out = M_out; p.M_f32 = M_f32; p.Z_out = Z_out;
+  const int tt = 1;
+  const long long slots = (long long)B * p.T * c->K;
+  const int grid = cdiv(slots, 32LL * tt * kWaves);
+  int rc = s.inner_fn(MODE_MERGE, tt, p, dim3(grid), st);
+  return rc ? fail(LONGER_ERR_HIP, "merge kernel launch failed") : 0;
+}
+
+struct AttnIO {
+  RowSrc src0, src1;     // rows of a user: [0, m0) from src0, rest from src1
+  int m0;
+  int key_rows;          // rows projected to K/V per user
+  int KG, key_self, gather_recent, q0, q_rows;
+  char* kst; char* vst; size_t kv_ustride;
+  RowSrc q0src, q1src;   // query rows: globals from q0src, slots from q1src
+  void* X_out; int X_f32; long long X_ustride;
+  float* logits; const float* head;
+};
+
+static int run_layer(const longer_config* c, const Shape& s, const char* packed_blk, const int32_t* lens, int B, int L,
+                     const AttnIO& io, bool do_attn, hipStream_t st) {
+  {
+    BlockParams p = base_params(c, s, lens, B, L, s.DH);
+    p.wbase = packed_blk;
+    p.src0 = io.src0; p.src1 = io.src1; p.m0 = io.m0;
+    p.rows_per_user = io.key_rows; p.tiles_per_user = cdiv(io.key_rows, 32);
+    p.kst = io.kst; p.vst = io.vst; p.kv_ustride = io.kv_ustride; p.kt_per_user = p.tiles_per_user;
+    const int grid = cdiv((long long)B * p.tiles_per_user, kWaves);
+    if (s.main_fn(MODE_KVPROJ, 1, p, dim3(grid), st)) return fail(LONGER_ERR_HIP, "kv projection launch failed");
+  }
+  if (!do_attn) return 0;
+  BlockParams p = base_params(c, s, lens, B, L, s.DH);
+  p.wbase = packed_blk;
+  p.src0 = io.q0src; p.src1 = io.q1src;
+  p.rows_per_user = io.q_rows; p.tiles_per_user = cdiv(io.q_rows, 32);
+  p.gather_recent = io.gather_recent; p.q0 = io.q0;
+  p.kst = io.kst; p.vst = io.vst; p.kv_ustride = io.kv_ustride;
+  p.KG = io.KG; p.key_self = io.key_self;
+  p.X_out = io.X_out; p.X_f32 = io.X_f32; p.X_ustride = io.X_ustride;
+  p.logits = io.logits; p.head = io.head;
+  const int grid = cdiv((long long)B * p.tiles_per_user, kWaves);
+  if (s.main_fn(MODE_ATTN, 1, p, dim3(grid), st)) return fail(LONGER_ERR_HIP, "attention launch failed");
+  return 0;
+}
+
+}  // namespace longer
+
+using namespace longer;
+
+extern "C" {
+
+const char* longer_last_error(void) { return g_err; }
+
+size_t longer_workspace_bytes(const longer_config* cfg, int B, int L, int C) {
+  Shape s;
+  (void)C;
+  if (check_cfg(cfg, &s, false, false) || B <= 0 || L <= 0) return 0;
+  return make_layout(cfg, s, B, L).total;
+}
+
+size_t longer_kv_cache_bytes(const longer_config* cfg, int U, int L) {
+  Shape s;
+  if (check_cfg(cfg, &s, false, false) || U <= 0 || L <= 0) return 0;
+  return make_cache_layout(cfg, s, U, L).total;
+}
+
+static int merge_entry(const longer_config* cfg, const longer_block* inner, const void* H, const int32_t* lens,
+                       int B, int L, void* M_out, void* Z_out, void* ws, size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = check_cfg(cfg, &s, true, false);
+  if (rc) return rc;
+  if (!inner || !H || (!M_out && !Z_out)) return fail(LONGER_ERR_ARG, "NULL argument");
+  const Layout l = make_layout(cfg, s, B, L);
+  if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  char* w8 = (char*)ws;
+  if ((rc = pack_blocks(cfg, s, inner, cfg->inner_layers, w8 + l.packed, st))) return rc;
+  return run_merge(cfg, s, w8 + l.packed, H, lens, B, L, M_out, 0, Z_out, st);
+}
+
+int longer_inner_transformer(const longer_config* cfg, const longer_block* inner, const void* H, const int32_t* lens,
+                             int B, int L, void* Z_out, void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  return merge_entry(cfg, inner, H, lens, B, L, nullptr, Z_out, ws, ws_bytes, stream);
+}
+
+int longer_token_merge(const longer_config* cfg, const longer_block* inner, const void* H, const int32_t* lens,
+                       int B, int L, void* M_out, void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  return merge_entry(cfg, inner, H, lens, B, L, M_out, nullptr, ws, ws_bytes, stream);
+}
+
+// K/V and query wiring of the cross layer over R = [G; M]
+static AttnIO cross_io(const longer_config* cfg, const Shape& s, const Layout& l, char* w8, const void* G, const void* M,
+                       int M_f32, int B, int L, void* X_out, int X_f32) {
+  const int T = cdiv(L, cfg->K);
+  AttnIO io;
+  memset(&io, 0, sizeof(io));
+  io.src0 = RowSrc{G, (long long)cfg->m * s.D, 0};
+  io.src1 = RowSrc{M, (long long)T * s.D, M_f32};
+  io.m0 = cfg->m; io.key_rows = cfg->m + T; io.KG = cfg->m; io.key_self = 0; io.gather_recent = 1;
+  io.q0 = 0; io.q_rows = s.n;
+  io.kst = w8 + l.kst; io.vst = w8 + l.vst; io.kv_ustride = l.kv_ustride;
+  io.q0src = io.src0; io.q1src = io.src1;
+  io.X_out = X_out; io.X_f32 = X_f32; io.X_ustride = (long long)s.n * s.D;
+  return io;
+}
+
+// a self layer over X [B, n, d]
+static AttnIO self_io(const longer_config* cfg, const Shape& s, const Layout& l, char* w8, const void* X, int X_in_f32,
+                      void* X_out, int X_f32) {
+  AttnIO io;
+  memset(&io, 0, sizeof(io));
+  const size_t es_in = X_in_f32 ? 4 : s.es;
+  io.src0 = RowSrc{X, (long long)s.n * s.D, X_in_f32};
+  io.src1 = RowSrc{(const char*)X + (size_t)cfg->m * s.D * es_in, (long long)s.n * s.D, X_in_f32};
+  io.m0 = cfg->m; io.key_rows = s.n; io.KG = cfg->m; io.key_self = 1; io.gather_recent = 0;
+  io.q0 = 0; io.q_rows = s.n;
+  io.kst = w8 + l.kst; io.vst = w8 + l.vst; io.kv_ustride = l.kv_ustride;
+  io.q0src = io.src0; io.q1src = io.src1;
+  io.X_out = X_out; io.X_f32 = X_f32; io.X_ustride = (long long)s.n * s.D;
+  return io;
+}
+
+int longer_hybrid_cross_attn(const longer_config* cfg, const longer_block* cross, const void* G, const void* M,
+                             const int32_t* lens, int B, int L, void* X_out, void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  Shape s;
+  int rc = check_cfg(cfg, &s, false, true);
+  if (rc) return rc;
+  if (!cross || !G || !M || !X_out) return fail(LONGER_ERR_ARG, "NULL argument");
+  const Layout l = make_layout(cfg, s, B, L);
+  if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  char* w8 = (char*)ws;
+  if ((rc = pack_blocks(cfg, s, cross, 1, w8 + l.packed, st))) return rc;
+  AttnIO io = cross_io(cfg, s, l, w8, G, M, 0, B, L, X_out, 0);
+  return run_layer(cfg, s, w8 + l.packed, lens, B, L, io, true, st);
+}
+
+int longer_self_attn_layer(const longer_config* cfg, const longer_block* blk, const void* X_in, const int32_t* lens,
+                           int B, int L, void* X_out, void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  Shape s;
+  int rc = check_cfg(cfg, &s, false, true);
+  if (rc) return rc;
+  if (!blk || !X_in || !X_out || X_in == X_out) return fail(LONGER_ERR_ARG, "NULL or aliased argument");
+  const Layout l = make_layout(cfg, s, B, L);
+  if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  char* w8 = (char*)ws;
+  if ((rc = pack_blocks(cfg, s, blk, 1, w8 + l.packed, st))) return rc;
+  AttnIO io = self_io(cfg, s, l, w8, X_in, 0, X_out, 0);
+  return run_layer(cfg, s, w8 + l.packed, lens, B, L, io, true, st);
+}
+
+static int check_weights(const longer_config* cfg, const longer_weights* w) {
+  if (!w || !w->inner || !w->cross || (cfg->n_self > 0 && !w->self)) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
+  return 0;
+}
+
+int longer_forward(const longer_config* cfg, const longer_weights* w, const void* H, const void* G, const int32_t* lens,
+                   int B, int L, void* Y_out, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  Shape s;
+  int rc = check_cfg(cfg, &s, true, true);
+  if (rc) return rc;
+  if ((rc = check_weights(cfg, w))) return rc;
+  if (!H || !G || !Y_out) return fail(LONGER_ERR_ARG, "NULL argument");
+  const Layout l = make_layout(cfg, s, B, L);
+  if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  char* w8 = (char*)ws;
+  char* pk = w8 + l.packed;
+  if ((rc = pack_blocks(cfg, s, w->inner, cfg->inner_layers, pk, st))) return rc;
+  char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
+  if ((rc = pack_blocks(cfg, s, w->cross, 1, pk_cross, st))) return rc;
+  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, pk_cross + s.pb, st))) return rc;
+  float* head = (float*)(w8 + l.head);
+  if (logits_out && (rc = pack_head(cfg, s, w, head, st))) return rc;
+
+  if ((rc = run_merge(cfg, s, pk, H, lens, B, L, w8 + l.M, 1, nullptr, st))) return rc;
+  void* xbuf[2] = {w8 + l.xa, w8 + l.xb};
+  const bool last0 = cfg->n_self == 0;
+  AttnIO io = cross_io(cfg, s, l, w8, G, w8 + l.M, 1, B, L, last0 ? Y_out : xbuf[0], last0 ? 0 : 1);
+  if (last0 && logits_out) { io.logits = logits_out; io.head = head; }
+  if ((rc = run_layer(cfg, s, pk_cross, lens, B, L, io, true, st))) return rc;
+  for (int i = 0; i < cfg->n_self; ++i) {
+    const bool last = i + 1 == cfg->n_self;
+    AttnIO si = self_io(cfg, s, l, w8, xbuf[i & 1], 1, last ? Y_out : xbuf[(i + 1) & 1], last ? 0 : 1);
+    if (last && logits_out) { si.logits = logits_out; si.head = head; }
+    if ((rc = run_layer(cfg, s, pk_cross + (size_t)(i + 1) * s.pb, lens, B, L, si, true, st))) return rc;
+  }
+  return 0;
+}
+
+int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, const void* H, const int32_t* lens,
+                          int U, int L, void* cache, void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  Shape s;
+  int rc = check_cfg(cfg, &s, true, true);
+  if (rc) return rc;
+  if ((rc = check_weights(cfg, w))) return rc;
+  if (!H || !cache) return fail(LONGER_ERR_ARG, "NULL argument");
+  if (((uintptr_t)cache & 255) != 0) return fail(LONGER_ERR_ARG, "cache must be 256-byte aligned");
+  const Layout l = make_layout(cfg, s, U, L);
+  if ((rc = check_common(ws, ws_bytes, l.total, U, L))) return rc;
+  const CacheLayout cl = make_cache_layout(cfg, s, U, L);
+  hipStream_t st = (hipStream_t)stream;
+  char* w8 = (char*)ws;
+  char* pk = w8 + l.packed;
+  if ((rc = pack_blocks(cfg, s, w->inner, cfg->inner_layers, pk, st))) return rc;
+  char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
+  if ((rc = pack_blocks(cfg, s, w->cross, 1, pk_cross, st))) return rc;
+  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, pk_cross + s.pb, st))) return rc;
+  if ((rc = run_merge(cfg, s, pk, H, lens, U, L, w8 + l.M, 1, nullptr, st))) return rc;
+
+  const int T = cdiv(L, cfg->K);
+  char* c8 = (char*)cache;
+  void* xbuf[2] = {w8 + l.xa, w8 + l.xb};
+  // layer 0: keys = merged tokens only; queries = the k recent slots
+  AttnIO io;
+  memset(&io, 0, sizeof(io));
+  io.src0 = RowSrc{nullptr, 0, 0};
+  io.src1 = RowSrc{w8 + l.M, (long long)T * s.D, 1};
+  io.m0 = 0; io.key_rows = T; io.KG = 0; io.key_self = 0; io.gather_recent = 1;
+  io.q0 = cfg->m; io.q_rows = cfg->k_recent;
+  io.kst = c8; io.vst = c8 + cl.c0_voff; io.kv_ustride = cl.c0_ustride;
+  io.q0src = io.src0; io.q1src = io.src1;
+  io.X_out = xbuf[0]; io.X_f32 = 1; io.X_ustride = (long long)s.n * s.D;
+  if ((rc = run_layer(cfg, s, pk_cross, lens, U, L, io, cfg->n_self > 0, st))) return rc;
+  for (int i = 0; i < cfg->n_self; ++i) {
+    const char* xin = (const char*)xbuf[i & 1];
+    AttnIO si;
+    memset(&si, 0, sizeof(si));
+    si.src0 = RowSrc{nullptr, 0, 0};
+    si.src1 = RowSrc{xin + (size_t)cfg->m * s.D * 4, (long long)s.n * s.D, 1};
+    si.m0 = 0; si.key_rows = cfg->k_recent; si.KG = 0; si.key_self = 1; si.gather_recent = 0;
+    si.q0 = cfg->m; si.q_rows = cfg->k_recent;
+    si.kst = c8 + cl.c1_off + (size_t)i * cl.c1_lstride; si.vst = si.kst + cl.c1_voff; si.kv_ustride = cl.c1_ustride;
+    si.q0src = si.src0; si.q1src = si.src1;
+    si.X_out = xbuf[(i + 1) & 1]; si.X_f32 = 1; si.X_ustride = (long long)s.n * s.D;
+    // the last layer's sequence rows feed nothing: only its K/V are needed
+    if ((rc = run_layer(cfg, s, pk_cross + (size_t)(i + 1) * s.pb, lens, U, L, si, i + 1 < cfg->n_self, st))) return rc;
+  }
+  return 0;
+}
+
+int longer_score_candidates(const longer_config* cfg, const longer_weights* w, const void* cache, const int32_t* lens,
+                            int U, int L, const void* G_cand, int C, void* Yg_out, float* logits_out,
+                            void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  Shape s;
+  int rc = check_cfg(cfg, &s, false, true);
+  if (rc) return rc;
+  if (!w || !w->cross || (cfg->n_self > 0 && !w->self)) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
+  if (!cache || !G_cand || (!Yg_out && !logits_out)) return fail(LONGER_ERR_ARG, "NULL argument");
+  if (C <= 0) return fail(LONGER_ERR_ARG, "C=%d must be positive", C);
+  const Layout l = make_layout(cfg, s, U, L);
+  if ((rc = check_common(ws, ws_bytes, l.total, U, L))) return rc;
+  const CacheLayout cl = make_cache_layout(cfg, s, U, L);
+  hipStream_t st = (hipStream_t)stream;
+  char* w8 = (char*)ws;
+  char* pk_cross = w8 + l.packed + (size_t)cfg->inner_layers * s.pb;
+  if ((rc = pack_blocks(cfg, s, w->cross, 1, pk_cross, st))) return rc;
+  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, pk_cross + s.pb, st))) return rc;
+  float* head = (float*)(w8 + l.head);
+  if (logits_out && (rc = pack_head(cfg, s, w, head, st))) return rc;
+
+  BlockParams p = base_params(cfg, s, lens, U, L, s.DH);
+  p.wbase = pk_cross; p.n_layers = 1 + cfg->n_self;
+  p.Gc = G_cand; p.C = C; p.cache = (const char*)cache;
+  p.c0_ustride = cl.c0_ustride; p.c0_voff = cl.c0_voff; p.c1_off = cl.c1_off; p.c1_lstride = cl.c1_lstride;
+  p.c1_ustride = cl.c1_ustride; p.c1_voff = cl.c1_voff; p.kt0 = cl.kt0; p.kt1 = cl.kt1;
+  p.X_out = Yg_out; p.X_f32 = 0;
+  p.logits = logits_out; p.head = head;
+  const int tiles = cdiv((long long)C * cfg->m, 32);
+  dim3 grid(cdiv(tiles, kWaves), U);
+  if (s.main_fn(MODE_SCORE, 1, p, grid, st)) return fail(LONGER_ERR_HIP, "score kernel launch failed");
+  return 0;
+}
+
+int longer_probe_mfma_layout(int32_t* out, void* stream) {
+  g_err[0] = 0;
+  if (!out) return fail(LONGER_ERR_ARG, "out is NULL");
+  hipLaunchKernelGGL(probe_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, out);
+  return hipGetLastError() == hipSuccess ? 0 : fail(LONGER_ERR_HIP, "probe launch failed");
+}
+
+}  // extern "C"

@@ -1,0 +1,88 @@
+"""Helpers for the GPU parity tests: run the C-ABI entry points (through the Python
+binding) on a seeded case and bring the results back as numpy arrays."""
+import numpy as np
+import torch
+
+import paper_2505_04421_amd as lg
+
+
+class Runner:
+    def __init__(self, case):
+        self.case = case
+        self.cfg = case["cfg"]
+        self.model = lg.DeviceModel(self.cfg, case["weights"])
+        self.B, self.L = self.cfg.B, self.cfg.L
+        self.ws = self.model.workspace(self.B, self.L, self.cfg.C)
+        self.lens = None
+        if case["lens"] is not None:
+            self.lens = torch.from_numpy(case["lens"].astype(np.int32)).to(self.model.device)
+
+    def up(self, a):
+        return self.model.upload(a)
+
+    def host(self, t):
+        torch.cuda.synchronize()
+        return t.float().cpu().numpy().astype(np.float64)
+
+    def token_merge(self, H=None):
+        c, m = self.cfg, self.model
+        H = self.up(self.case["H"] if H is None else H)
+        out = m.empty(self.B, c.T, c.d)
+        lg.longer_token_merge(m.ccfg, m.inner, H, self.lens, self.B, self.L, out, self.ws)
+        return self.host(out)
+
+    def inner_transformer(self):
+        c, m = self.cfg, self.model
+        H = self.up(self.case["H"])
+        out = m.empty(self.B, c.T, c.K, c.d)
+        lg.longer_inner_transformer(m.ccfg, m.inner, H, self.lens, self.B, self.L, out, self.ws)
+        return self.host(out)
+
+    def cross(self, G, M):
+        c, m = self.cfg, self.model
+        out = m.empty(self.B, c.n, c.d)
+        lg.longer_hybrid_cross_attn(m.ccfg, m.cross, self.up(G), self.up(M), self.lens, self.B, self.L, out, self.ws)
+        return self.host(out)
+
+    def self_layer(self, X, i=0):
+        c, m = self.cfg, self.model
+        out = m.empty(self.B, c.n, c.d)
+        blk = (type(m.self_[0]) * 1)(m.self_[i])
+        lg.longer_self_attn_layer(m.ccfg, blk, self.up(X), self.lens, self.B, self.L, out, self.ws)
+        return self.host(out)
+
+    def forward(self, H=None, G=None):
+        c, m = self.cfg, self.model
+        H = self.up(self.case["H"] if H is None else H)
+        G = self.up(self.case["G"] if G is None else G)
+        Y = m.empty(self.B, c.n, c.d)
+        logits = m.empty(self.B, dtype=torch.float32)
+        lg.longer_forward(m.ccfg, m.weights, H, G, self.lens, self.B, self.L, Y, logits, self.ws)
+        return self.host(Y), self.host(logits)
+
+    def serve(self, want_hidden=True):
+        c, m = self.cfg, self.model
+        H = self.up(self.case["H"])
+        Gc = self.up(self.case["G_cand"])
+        cache = m.kv_cache(self.B, self.L)
+        lg.longer_kv_cache_build(m.ccfg, m.weights, H, self.lens, self.B, self.L, cache, self.ws)
+        Yg = m.empty(self.B, c.C, c.m, c.d) if want_hidden else None
+        logits = m.empty(self.B, c.C, dtype=torch.float32)
+        lg.longer_score_candidates(m.ccfg, m.weights, cache, self.lens, self.B, self.L, Gc, c.C, Yg, logits, self.ws)
+        return (self.host(Yg) if want_hidden else None), self.host(logits)
+
+
+def rel_l2_per_user(got, ref):
+    """max over the leading (user) axis of ||got - ref|| / ||ref||."""
+    got = got.reshape(got.shape[0], -1)
+    ref = ref.reshape(ref.shape[0], -1)
+    num = np.linalg.norm(got - ref, axis=1)
+    den = np.linalg.norm(ref, axis=1)
+    den = np.where(den > 0, den, 1.0)
+    return float((num / den).max())
+
+
+def assert_zero_where_ref_zero_rows(got, ref):
+    """Rows that the oracle reports as invalid (all-zero) must be exact zeros."""
+    zr = (ref == 0).all(axis=-1)
+    assert (got[zr] == 0).all()

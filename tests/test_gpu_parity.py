@@ -1,0 +1,144 @@
+"""Parity of the HIP path (through the C ABI) against the fp64 oracle, element by
+element on seeded inputs.  Tolerances: max relative L2 per user 1e-5 (fp32 mode) and
+1e-2 (bf16 mode), the bar the benchmark definition states."""
+import numpy as np
+import pytest
+import torch
+
+import longer_synth as synth
+from oracle import longer_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 1e-2}
+
+
+def _runner(case):
+    from gpu_util import Runner
+    return Runner(case)
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def test_mfma_register_layout_probe():
+    import paper_2505_04421_amd as lg
+    out = torch.zeros(2, 64, 16, dtype=torch.int32, device="cuda")
+    lg.longer_probe_mfma_layout(out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    exp = np.zeros((64, 16), dtype=np.int64)
+    for lane in range(64):
+        for r in range(16):
+            exp[lane, r] = (8 * (r // 4) + 4 * (lane // 32) + r % 4) * 32 + lane % 32
+    assert np.array_equal(got[0], exp), got[0][:2]
+    assert np.array_equal(got[1], exp), got[1][:2]
+
+
+def _check(name, got, ref, tol):
+    from gpu_util import rel_l2_per_user, assert_zero_where_ref_zero_rows
+    assert np.isfinite(got).all(), name + ": non-finite output"
+    err = rel_l2_per_user(got, ref)
+    _say("  %-28s rel-L2 max %.3e (tol %.0e)" % (name, err, tol))
+    assert err <= tol, (name, err)
+    assert_zero_where_ref_zero_rows(got, ref)
+    return err
+
+
+def _entry_points(case, tol, with_inner=True):
+    cfg, w = case["cfg"], case["weights"]
+    r = _runner(case)
+    H, G, lens = case["H"], case["G"], case["lens"]
+    M_ref = orc.token_merge(cfg, w["inner"], H, lens)
+    _check("longer_token_merge", r.token_merge(), M_ref, tol)
+    if with_inner:
+        _check("longer_inner_transformer", r.inner_transformer(), orc.inner_transformer(cfg, w["inner"], H, lens), tol)
+    # the later stages are checked on the oracle's own (rounded) intermediates so that each
+    # entry point is compared in isolation, then end to end
+    rnd = synth.round_bf16 if cfg.dtype == "bf16" else (lambda a: a.astype(np.float32))
+    M_in = rnd(M_ref.astype(np.float32))
+    X1_ref = orc.hybrid_cross_attn(cfg, w["cross"], G, M_in, lens, L=cfg.L)
+    _check("longer_hybrid_cross_attn", r.cross(G, M_in), X1_ref, tol)
+    if cfg.n_self:
+        X_in = rnd(X1_ref.astype(np.float32))
+        X2_ref = orc.self_attn_layer(cfg, w["self"][0], X_in, lens, L=cfg.L)
+        _check("longer_self_attn_layer", r.self_layer(X_in, 0), X2_ref, tol)
+    Y_ref, lg_ref = orc.forward(cfg, w, H, G, lens)
+    Y, logits = r.forward()
+    _check("longer_forward Y", Y, Y_ref, tol)
+    _check("longer_forward logits", logits[None, :], lg_ref[None, :], tol)
+
+
+def test_c1_fp32_all_entry_points():
+    _say("C1 fp32")
+    _entry_points(synth.make_case(synth.CONFIGS["C1"]), TOL["f32"])
+
+
+@pytest.mark.parametrize("gmask", ["full", "causal"])
+def test_fp32_ragged_short_users_and_ragged_last_group(gmask):
+    """L not a multiple of K, users shorter than k*K (invalid query slots), a user of
+    length 0 and NaN in the padding."""
+    cfg = synth.CONFIGS["C1"].replace(B=5, L=70, ragged=True, len_lo=1, len_hi=70, gmask=gmask, n_self=2, index=11)
+    case = synth.make_case(cfg)
+    case["lens"] = np.array([70, 0, 3, 29, 41], dtype=np.int32)
+    H = np.random.default_rng(5).standard_normal(case["H"].shape).astype(np.float32)
+    pos = np.arange(cfg.L)[None, :, None]
+    case["H"] = np.where(pos < case["lens"][:, None, None], H, np.float32("nan")).astype(np.float32)
+    _say("fp32 ragged, gmask=" + gmask)
+    _entry_points(case, TOL["f32"])
+
+
+def test_fp32_d64():
+    cfg = synth.CONFIGS["C1"].replace(d=64, heads=4, inner_heads=4, m=4, K=8, L=96, k_recent=5, index=12, inner_layers=2)
+    _say("fp32 d=64")
+    _entry_points(synth.make_case(cfg), TOL["f32"])
+
+
+def test_c2_bf16_all_entry_points():
+    _say("C2 bf16 (16 users)")
+    _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
+
+
+def test_c3_bf16_all_entry_points():
+    _say("C3 bf16 (6 users)")
+    _entry_points(synth.make_case(synth.CONFIGS["C3"], users=6), TOL["bf16"], with_inner=False)
+
+
+def test_c4_bf16_ragged_nan_padding():
+    _say("C4 bf16 ragged (6 users, NaN padding)")
+    case = synth.make_case(synth.CONFIGS["C4"], users=6, pad_value=float("nan"))
+    case["lens"][0] = 100        # fewer merged tokens (7) than query slots (64)
+    case["lens"][1] = 5000
+    case["H"][0, 100:] = np.nan
+    _entry_points(case, TOL["bf16"], with_inner=False)
+
+
+def _serving(case, tol):
+    from gpu_util import rel_l2_per_user
+    cfg, w = case["cfg"], case["weights"]
+    r = _runner(case)
+    Yg, logits = r.serve()
+    cache = orc.kv_cache_build(cfg, w, case["H"], case["lens"])
+    Yg_ref, lg_ref = orc.score_candidates(cfg, w, cache, case["G_cand"])
+    U, C = cfg.B, cfg.C
+    _check("longer_score_candidates Yg", Yg.reshape(U * C, -1), Yg_ref.reshape(U * C, -1), tol)
+    _check("longer_score_candidates logit", logits, lg_ref, tol)
+    # KV-cached scoring equals the full forward pass with that candidate's globals (GPU vs GPU)
+    Yf, lf = r.forward(G=case["G_cand"][:, 0])
+    err = rel_l2_per_user(Yg[:, 0], Yf[:, :cfg.m])
+    _say("  cached vs full forward (GPU)  rel-L2 max %.3e" % err)
+    assert err <= tol
+
+
+def test_fp32_serving_small():
+    cfg = synth.CONFIGS["C1"].replace(B=3, L=70, C=9, n_self=2, ragged=True, len_lo=5, len_hi=70, index=13)
+    case = synth.make_case(cfg)
+    case["lens"][0] = 9
+    _say("fp32 serving")
+    _serving(case, TOL["f32"])
+
+
+def test_c5_bf16_serving():
+    _say("C5 bf16 serving (2 users x 24 candidates)")
+    _serving(synth.make_case(synth.CONFIGS["C5"], users=2, candidates=24), TOL["bf16"])
