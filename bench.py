@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the LONGER hot path on one MI355X.
+
+A step is one ``longer_forward`` call (token merge -> cross-causal layer -> N self-causal
+layers -> head) over one batch of the headline configuration C3 (256 users, L = 2000,
+d = 128, bf16), inputs resident in HBM, rotating over three input buffers.  The line also
+carries the KV-cache serving rate on configuration C5, the roofline figures of the
+dominant kernel (the fused token-merge kernel, MFMA bound) measured with HIP events on
+the launch stream, and the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-serving] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def _oracle_flops(cfg, lens=None, B=None):
+    # FLOP bookkeeping only (closed-form counts of Eq. 3 applied to the configuration)
+    from oracle import longer_oracle as orc
+    return orc.algorithmic_flops(cfg, lens, B=B), orc
+
+
+def cpu_baseline(cfg, seconds_target=15.0):
+    """Time the fp64 oracle on a bounded sample of users of the same workload."""
+    import numpy as np
+    import longer_synth as synth
+    from oracle import longer_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    case = synth.make_case(cfg, users=1)
+    t0 = time.perf_counter()
+    orc.forward(case["cfg"], case["weights"], case["H"], case["G"], case["lens"])
+    t1 = time.perf_counter() - t0
+    users = int(max(1, min(2 * cfg.B, seconds_target / max(t1, 1e-3))))
+    case = synth.make_case(cfg, users=users)
+    t0 = time.perf_counter()
+    orc.forward(case["cfg"], case["weights"], case["H"], case["G"], case["lens"])
+    dt = time.perf_counter() - t0
+    return {"value": users / dt, "unit": "user sequences/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d users of %s (L=%d, d=%d), one fp64 numpy pass, %.1f s" % (users, cfg.name, cfg.L, cfg.d, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C3")
+    ap.add_argument("--no-serving", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the forward path needs no collectives; users shard "
+              "across GPUs with no exchange). --gpus %d is not supported." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import longer_synth as synth
+    import paper_2505_04421_amd as lg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    dev = "cuda:0"
+    cfg = synth.CONFIGS[args.config]
+    case = synth.make_case(cfg)
+    model = lg.DeviceModel(cfg, case["weights"], dev)
+    B, L = cfg.B, cfg.L
+    ws = model.workspace(B, L)
+    lens_np = case["lens"]
+    lens = None if lens_np is None else torch.from_numpy(lens_np.astype(np.int32)).to(dev)
+    nbuf = 3
+    Hs = [model.upload(case["H"])]
+    for i in range(1, nbuf):        # distinct buffers so the input is not served from the last-level cache
+        Hs.append(torch.roll(Hs[0], shifts=i, dims=0).contiguous() if lens is None else Hs[0].clone())
+    G = model.upload(case["G"])
+    Y = model.empty(B, cfg.n, cfg.d)
+    logits = model.empty(B, dtype=torch.float32)
+
+    def step(i):
+        lg.longer_forward(model.ccfg, model.weights, Hs[i % nbuf], G, lens, B, L, Y, logits, ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    lg.longer_stage_timing(True)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stages = lg.longer_stage_timing_read()
+    lg.longer_stage_timing(False)
+    ms_per_step = dt * 1e3 / args.steps
+    seq_per_s = B / (dt / args.steps)
+
+    fl, _ = _oracle_flops(cfg, lens_np)
+    merge_ms, merge_n = stages["merge"]
+    merge_avg_ms = merge_ms / max(merge_n, 1)
+    achieved = fl["inner"] / (merge_avg_ms * 1e-3) / 1e12
+    total_tflops = fl["total"] / (ms_per_step * 1e-3) / 1e12
+    # algorithmic HBM bytes of the merge kernel: each valid raw token read once, each merged token written once
+    es = 2 if cfg.dtype == "bf16" else 4
+    valid_tokens = float(B * L if lens_np is None else lens_np.sum())
+    merged_tokens = float(B * cfg.T if lens_np is None else np.ceil(lens_np / cfg.K).sum())
+    merge_bytes = valid_tokens * cfg.d * es + merged_tokens * cfg.d * 4
+    out = {
+        "metric": "user sequences/s fwd at L=2000 bf16; candidates/s KV-cached; % MFMA peak",
+        "value": seq_per_s, "unit": "user sequences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "%s: longer_forward, B=%d users, L=%d, d=%d, m=%d, K=%d (T=%d), N_in=%d, k=%d, N=%d, heads=%d"
+                   % (cfg.name, B, L, cfg.d, cfg.m, cfg.K, cfg.T, cfg.inner_layers, cfg.k_recent, cfg.n_self, cfg.heads),
+                   "lens": "none" if lens_np is None else "uniform[%d,%d]" % (cfg.len_lo, cfg.len_hi)},
+        "algorithmic_gflop_per_step": fl["total"] / 1e9,
+        "mfma_peak_frac_whole_step": total_tflops / PEAK_BF16_TFLOPS,
+        "stage_ms_per_step": {k: v[0] / args.steps for k, v in stages.items() if v[1]},
+        "roofline": {"kernel": "block_kernel<MODE_MERGE> (fused gather + InnerTrans + pooling)", "bound": "mfma",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "avg_launch_ms": merge_avg_ms, "algorithmic_gflop_per_launch": fl["inner"] / 1e9,
+                     "algorithmic_hbm_GBs": merge_bytes / (merge_avg_ms * 1e-3) / 1e9},
+    }
+
+    if not args.no_serving:
+        c5 = synth.CONFIGS["C5"]
+        case5 = synth.make_case(c5)
+        m5 = lg.DeviceModel(c5, case5["weights"], dev)
+        ws5 = m5.workspace(c5.B, c5.L, c5.C)
+        H5, Gc5 = m5.upload(case5["H"]), m5.upload(case5["G_cand"])
+        cache = m5.kv_cache(c5.B, c5.L)
+        lg5 = m5.empty(c5.B, c5.C, dtype=torch.float32)
+        for _ in range(2):
+            lg.longer_kv_cache_build(m5.ccfg, m5.weights, H5, None, c5.B, c5.L, cache, ws5)
+            lg.longer_score_candidates(m5.ccfg, m5.weights, cache, None, c5.B, c5.L, Gc5, c5.C, None, lg5, ws5)
+        torch.cuda.synchronize()
+        reps = max(3, args.steps // 3)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            lg.longer_kv_cache_build(m5.ccfg, m5.weights, H5, None, c5.B, c5.L, cache, ws5)
+        torch.cuda.synchronize()
+        build_ms = (time.perf_counter() - t0) * 1e3 / reps
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            lg.longer_score_candidates(m5.ccfg, m5.weights, cache, None, c5.B, c5.L, Gc5, c5.C, None, lg5, ws5)
+        torch.cuda.synchronize()
+        score_ms = (time.perf_counter() - t0) * 1e3 / reps
+        from oracle import longer_oracle as orc
+        fl5 = orc.algorithmic_flops_score(c5, c5.T) * c5.B * c5.C
+        out["serving"] = {"workload": "C5: %d users x %d candidates, L=%d, d=%d, K=%d (T=%d), k=%d, N=%d"
+                          % (c5.B, c5.C, c5.L, c5.d, c5.K, c5.T, c5.k_recent, c5.n_self),
+                          "candidates_per_s": c5.B * c5.C / (score_ms * 1e-3), "score_ms": score_ms,
+                          "cache_build_ms": build_ms,
+                          "candidates_per_s_incl_build": c5.B * c5.C / ((score_ms + build_ms) * 1e-3),
+                          "score_mfma_peak_frac": fl5 / (score_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        del m5, ws5, H5, Gc5, cache
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

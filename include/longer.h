@@ -145,6 +145,17 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* longer_last_error(void);
 
+/* Measurement aid: when enabled, every kernel launch group of the entry points is bracketed
+ * by a pair of HIP events recorded on the caller's stream (at most 8192 pairs between two
+ * reads; later launches go unrecorded).  longer_stage_timing_read waits for the recorded
+ * events, adds up the elapsed milliseconds and the number of launch groups per stage into
+ * HOST arrays of LONGER_NUM_STAGES entries (0 parameter packing, 1 token merge, 2 K/V
+ * projection, 3 attention + FFN, 4 candidate scoring) and clears the record.  Not
+ * thread-safe; do not enable under graph capture. */
+#define LONGER_NUM_STAGES 5
+int longer_stage_timing(int enable);
+int longer_stage_timing_read(double* ms_out, int32_t* launches_out);
+
 /* In-bounds probe of the matrix-core register layout the kernels rely on: runs one
  * 32x32 MFMA per element type on index-coded operands and writes, for every lane and
  * accumulator register, the (row, column) it holds as row*32+column into out[2][64][16]

@@ -13,7 +13,8 @@ BLOCK_FIELDS = ("ln1_g", "ln1_b", "wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo"
 ENTRY_POINTS = ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_inner_transformer",
                 "longer_token_merge", "longer_hybrid_cross_attn", "longer_self_attn_layer",
                 "longer_forward", "longer_kv_cache_build", "longer_score_candidates",
-                "longer_last_error", "longer_probe_mfma_layout")
+                "longer_last_error", "longer_probe_mfma_layout", "longer_stage_timing",
+                "longer_stage_timing_read")
 
 
 class LongerError(RuntimeError):
@@ -66,6 +67,8 @@ def load_library() -> ctypes.CDLL:
     lib.longer_score_candidates.argtypes = [cfgp, wp, vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
     lib.longer_last_error.restype = ctypes.c_char_p
     lib.longer_probe_mfma_layout.argtypes = [vp, vp]
+    lib.longer_stage_timing.argtypes = [i32]
+    lib.longer_stage_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     for name in ENTRY_POINTS:
         if name not in ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_last_error"):
             getattr(lib, name).restype = ctypes.c_int
@@ -231,3 +234,19 @@ def longer_score_candidates(ccfg, weights, cache, lens, U, L, G_cand, C, Yg_out,
 def longer_probe_mfma_layout(out, stream=None):
     _require_gpu()
     _check(load_library().longer_probe_mfma_layout(_ptr(out), _stream(stream)), "longer_probe_mfma_layout")
+
+
+STAGES = ("pack", "merge", "kvproj", "attn", "score")
+
+
+def longer_stage_timing(enable: bool):
+    _require_gpu()
+    _check(load_library().longer_stage_timing(1 if enable else 0), "longer_stage_timing")
+
+
+def longer_stage_timing_read():
+    """{stage: (total_ms, launch_groups)} since the last read."""
+    ms = (ctypes.c_double * len(STAGES))()
+    n = (ctypes.c_int32 * len(STAGES))()
+    _check(load_library().longer_stage_timing_read(ms, n), "longer_stage_timing_read")
+    return {s: (ms[i], n[i]) for i, s in enumerate(STAGES)}

@@ -42,6 +42,31 @@ static int fail(int code, const char* fmt, ...) {
 }
 
 // ------------------------------------------------------------------------------------
+// Optional per-stage timing with HIP events on the caller's stream (measurement aid).
+enum Stage { ST_PACK = 0, ST_MERGE = 1, ST_KVPROJ = 2, ST_ATTN = 3, ST_SCORE = 4 };
+static_assert(LONGER_NUM_STAGES == 5, "stage table");
+struct StageTimer {
+  static constexpr int kMaxPairs = 8192;
+  bool on = false;
+  int n = 0;
+  hipEvent_t* ev = nullptr;      // 2 * kMaxPairs events, created on first enable
+  unsigned char stage[kMaxPairs];
+};
+static StageTimer g_timer;
+
+struct StageScope {
+  hipStream_t st; int idx;
+  StageScope(int stage, hipStream_t s) : st(s), idx(-1) {
+    if (g_timer.on && g_timer.n < StageTimer::kMaxPairs) {
+      idx = g_timer.n++;
+      g_timer.stage[idx] = (unsigned char)stage;
+      (void)hipEventRecord(g_timer.ev[2 * idx], st);
+    }
+  }
+  ~StageScope() { if (idx >= 0) (void)hipEventRecord(g_timer.ev[2 * idx + 1], st); }
+};
+
+// ------------------------------------------------------------------------------------
 // Pack kernel: raw [in, out] matrices of one block -> MFMA A/B fragments in the order
 // the block kernel streams them, plus the small vectors as fp32.
 struct RawBlock { longer_block b; };
@@ -203,6 +228,7 @@ static CacheLayout make_cache_layout(const longer_config* c, const Shape& s, int
 }
 
 static int pack_blocks(const longer_config* c, const Shape& s, const longer_block* blocks, int nb, char* dst, hipStream_t st) {
+  StageScope scope(ST_PACK, st);
   for (int i = 0; i < nb; ++i) {
     const longer_block& b = blocks[i];
     const void* ptrs[16] = {b.ln1_g, b.ln1_b, b.wq, b.bq, b.wk, b.bk, b.wv, b.bv, b.wo, b.bo, b.ln2_g, b.ln2_b, b.w1, b.b1, b.w2, b.b2};
@@ -252,6 +278,7 @@ static int run_merge(const longer_config* c, const Shape& s, const char* packed,
   const int tt = 1;
   const long long slots = (long long)B * p.T * c->K;
   const int grid = cdiv(slots, 32LL * tt * kWaves);
+  StageScope scope(ST_MERGE, st);
   int rc = s.inner_fn(MODE_MERGE, tt, p, dim3(grid), st);
   return rc ? fail(LONGER_ERR_HIP, "merge kernel launch failed") : 0;
 }
@@ -276,6 +303,7 @@ static int run_layer(const longer_config* c, const Shape& s, const char* packed_
     p.rows_per_user = io.key_rows; p.tiles_per_user = cdiv(io.key_rows, 32);
     p.kst = io.kst; p.vst = io.vst; p.kv_ustride = io.kv_ustride; p.kt_per_user = p.tiles_per_user;
     const int grid = cdiv((long long)B * p.tiles_per_user, kWaves);
+    StageScope scope(ST_KVPROJ, st);
     if (s.main_fn(MODE_KVPROJ, 1, p, dim3(grid), st)) return fail(LONGER_ERR_HIP, "kv projection launch failed");
   }
   if (!do_attn) return 0;
@@ -289,6 +317,7 @@ static int run_layer(const longer_config* c, const Shape& s, const char* packed_
   p.X_out = io.X_out; p.X_f32 = io.X_f32; p.X_ustride = io.X_ustride;
   p.logits = io.logits; p.head = io.head;
   const int grid = cdiv((long long)B * p.tiles_per_user, kWaves);
+  StageScope scope(ST_ATTN, st);
   if (s.main_fn(MODE_ATTN, 1, p, dim3(grid), st)) return fail(LONGER_ERR_HIP, "attention launch failed");
   return 0;
 }
@@ -526,7 +555,36 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
   p.logits = logits_out; p.head = head;
   const int tiles = cdiv((long long)C * cfg->m, 32);
   dim3 grid(cdiv(tiles, kWaves), U);
+  StageScope scope(ST_SCORE, st);
   if (s.main_fn(MODE_SCORE, 1, p, grid, st)) return fail(LONGER_ERR_HIP, "score kernel launch failed");
+  return 0;
+}
+
+int longer_stage_timing(int enable) {
+  g_err[0] = 0;
+  if (enable && !g_timer.ev) {
+    g_timer.ev = new hipEvent_t[2 * StageTimer::kMaxPairs];
+    for (int i = 0; i < 2 * StageTimer::kMaxPairs; ++i)
+      if (hipEventCreate(&g_timer.ev[i]) != hipSuccess) return fail(LONGER_ERR_HIP, "hipEventCreate failed");
+  }
+  g_timer.on = enable != 0;
+  g_timer.n = 0;
+  return 0;
+}
+
+int longer_stage_timing_read(double* ms_out, int32_t* launches_out) {
+  g_err[0] = 0;
+  if (!ms_out || !launches_out) return fail(LONGER_ERR_ARG, "NULL argument");
+  for (int i = 0; i < LONGER_NUM_STAGES; ++i) { ms_out[i] = 0.0; launches_out[i] = 0; }
+  for (int i = 0; i < g_timer.n; ++i) {
+    if (hipEventSynchronize(g_timer.ev[2 * i + 1]) != hipSuccess) return fail(LONGER_ERR_HIP, "hipEventSynchronize failed");
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_timer.ev[2 * i], g_timer.ev[2 * i + 1]) != hipSuccess)
+      return fail(LONGER_ERR_HIP, "hipEventElapsedTime failed");
+    ms_out[g_timer.stage[i]] += ms;
+    launches_out[g_timer.stage[i]] += 1;
+  }
+  g_timer.n = 0;
   return 0;
 }
 

@@ -109,8 +109,9 @@ def test_c4_bf16_ragged_nan_padding():
     _say("C4 bf16 ragged (6 users, NaN padding)")
     case = synth.make_case(synth.CONFIGS["C4"], users=6, pad_value=float("nan"))
     case["lens"][0] = 100        # fewer merged tokens (7) than query slots (64)
-    case["lens"][1] = 5000
+    case["lens"][1] = 5000       # a full-length user: the last group (5000 = 312*16 + 8) is ragged by L itself
     case["H"][0, 100:] = np.nan
+    case["H"][1] = synth.round_bf16(np.random.default_rng(3).standard_normal(case["H"][1].shape).astype(np.float32))
     _entry_points(case, TOL["bf16"], with_inner=False)
 
 
