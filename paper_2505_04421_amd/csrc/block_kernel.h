@@ -221,12 +221,13 @@ __global__ void __launch_bounds__(kThreads) block_kernel(const BlockParams p) {
   constexpr int GPH = DH / E::GF;     // operand groups per head
   constexpr bool FUSED = (MODE == MODE_MERGE || MODE == MODE_SCORE);
   constexpr bool EXT = (MODE == MODE_ATTN || MODE == MODE_SCORE);
+  constexpr int NB = SEGV * 16 >= 16384 ? 6 : 8;   // ring depth of the weight stream
   static_assert(DH == 16 || DH == 32, "head width");
-  __shared__ uint4 lds[2 * SEGV];
+  __shared__ uint4 lds[NB * SEGV];
+  __shared__ uint4 vecl[SEGV];          // the current block's fp32 vectors
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j = lane & 31, hi = lane >> 5;
   const int NC = p.FF / 32;
-  const size_t vec_off = (size_t)(4 * NT + 2 * NC) * SEGV * 16;
 
   // ------------------------------------------------------------------ rows of this wave
   bool valid[TT];          // the lane's token exists and takes part
@@ -331,12 +332,16 @@ __global__ void __launch_bounds__(kThreads) block_kernel(const BlockParams p) {
     }
   }
 
-  WStream<SEGV, MODE, NT> ws;
-  const int steps = MODE == MODE_KVPROJ ? 2 * NT : (MODE == MODE_ATTN ? 2 * NT + 2 * NC : 4 * NT + 2 * NC);
-  ws.init(lds, p.wbase, p.bstride, steps, p.n_layers);
+  WStream<SEGV, MODE, NT, NB> ws;
+  const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : (MODE == MODE_ATTN ? 2 * NT + 2 * NC : 4 * NT + 2 * NC));
+  ws.init(lds, p.wbase, p.bstride, steps, p.n_layers, 4 * NT + 2 * NC);
 
   for (int layer = 0; layer < p.n_layers; ++layer) {
-    const float* vec = reinterpret_cast<const float*>(p.wbase + (size_t)layer * p.bstride + vec_off);
+    // the block's first segment holds its fp32 vectors: keep a copy for the whole layer
+#pragma unroll
+    for (int i = 0; i < SEGV / kThreads; ++i) vecl[tid + kThreads * i] = ws.cur()[tid + kThreads * i];
+    ws.advance();
+    const float* vec = reinterpret_cast<const float*>(vecl);
     const VecLayout vl{D, p.FF};
     grp xn[TT][NG];
     layer_norm<T, D, TT>(resid, vec + vl.ln1_g(), vec + vl.ln1_b(), p.eps, hi, xn);
@@ -473,7 +478,7 @@ __global__ void __launch_bounds__(kThreads) block_kernel(const BlockParams p) {
         for (int g = 0; g < GPT; ++g) oop[tt][ft * GPT + g] = E::pack(o, g);
       }
     }
-    if (MODE == MODE_KVPROJ) return;
+    if (MODE == MODE_KVPROJ) { wait_vmcnt<0>(); return; }
 
     // output projection + residual
 #pragma unroll
@@ -492,6 +497,12 @@ __global__ void __launch_bounds__(kThreads) block_kernel(const BlockParams p) {
 
     // FFN, 32 hidden features at a time: hidden chunk never leaves registers
     layer_norm<T, D, TT>(resid, vec + vl.ln2_g(), vec + vl.ln2_b(), p.eps, hi, xn);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {      // FFN output bias goes in first: the vectors may be
+      const f32x16 b2 = bias_tile(vec + vl.b2(), nt, hi);   // replaced right after the last segment
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) resid[tt][nt] += b2;
+    }
 #pragma unroll 1
     for (int c = 0; c < NC; ++c) {
       f32x16 ah[TT];
@@ -523,14 +534,9 @@ __global__ void __launch_bounds__(kThreads) block_kernel(const BlockParams p) {
       }
       ws.advance();
     }
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const f32x16 b2 = bias_tile(vec + vl.b2(), nt, hi);
-#pragma unroll
-      for (int tt = 0; tt < TT; ++tt) resid[tt][nt] += b2;
-    }
   }
 
+  wait_vmcnt<0>();   // nothing of the weight stream may still be in flight when the wave ends
   // ------------------------------------------------------------------ epilogues
   if (MODE == MODE_MERGE) {
 #pragma unroll

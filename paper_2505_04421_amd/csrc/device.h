@@ -103,72 +103,101 @@ struct VecLayout {
 
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// bytes of one packed block for element size es
+// bytes of one packed block for element size es: all weight segments, then the fp32
+// vectors padded to one more segment (they travel through the weight stream as well)
 __host__ __device__ inline size_t packed_seg_bytes(int D, int es) { return (size_t)D * 32 * es; }   // D/GF KiB, GF = 32/es
 __host__ __device__ inline int packed_num_segs(int D, int FF) { return 4 * (D / 32) + 2 * (FF / 32); }
 __host__ __device__ inline size_t packed_vec_offset(int D, int FF, int es) {
   return (size_t)packed_num_segs(D, FF) * packed_seg_bytes(D, es);
 }
 __host__ __device__ inline size_t packed_block_bytes(int D, int FF, int es) {
-  return align256(packed_vec_offset(D, FF, es) + (size_t)(9 * D + FF) * 4);
+  return (size_t)(packed_num_segs(D, FF) + 1) * packed_seg_bytes(D, es);
 }
 
 enum Mode { MODE_MERGE = 0, MODE_KVPROJ = 1, MODE_ATTN = 2, MODE_SCORE = 3 };
 
+// 16 bytes per lane from global memory straight into LDS (no VGPR round trip):
+// lane i of the wave writes LDS bytes [lds_wave_base + 16 i, +16).  lds_wave_base must be
+// wave-uniform.  Completion is tracked by the wave's vector-memory counter.
+__device__ __forceinline__ void gload_lds16(const void* g, unsigned lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %1\n\t"
+               "s_nop 0\n\t"
+               "global_load_lds_dwordx4 %0, off\n\t"
+               :: "v"(g), "s"(lds_wave_base) : "memory");
+}
+
+// wait until at most N vector-memory operations of this wave are outstanding
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
 // ------------------------------------------------------------------------------------
-// Weight stream: all four waves of a workgroup consume the same sequence of segments.
-// Segment s+1 is fetched from global memory into registers while segment s is being
-// consumed from LDS, then written to the other LDS buffer; one barrier per segment.
-template <int SEGV, int MODE, int NT>
+// Weight stream: all waves of a workgroup consume the same sequence of 16-byte-per-lane
+// segments.  Segments travel global -> LDS directly into a ring of NB buffers, NB-1
+// segments ahead of the consumer, so that L2/HBM latency is covered by the MFMA work of
+// several segments; one barrier per segment.  The first segment of every block carries
+// the block's fp32 vectors (LayerNorm gain/bias, biases).
+template <int SEGV, int MODE, int NT, int NB>
 struct WStream {
   static constexpr int NSTAGE = SEGV / kThreads;
+  static constexpr int NPRE = NB - 1;
+  // K/V projection stores fragments inside its loop; loads and stores may retire out of
+  // order with respect to each other, so that mode always drains the counter.
+  static constexpr bool DRAIN = (MODE == MODE_KVPROJ);
   static_assert(SEGV % kThreads == 0 && NSTAGE >= 1, "segment must cover all threads");
   uint4* lds;
   const char* wbase;
   size_t bstride;
-  int steps_per_block, total_steps, step, cur, tid;
-  uint4 stage[NSTAGE];
+  unsigned lds_wave;     // LDS byte address of this wave's first 16-byte slot in ring buffer 0
+  int steps_per_block, total_steps, step, tid;
 
   __device__ __forceinline__ const uint4* seg_ptr(int s) const {
     int blk = s / steps_per_block;
-    int r = s - blk * steps_per_block;
+    int r = s - blk * steps_per_block - 1;
     int idx;
-    if (MODE == MODE_MERGE || MODE == MODE_SCORE) idx = r < 3 * NT ? (r % 3) * NT + r / 3 : r;
+    if (r < 0) idx = steps_segs();                    // the vector segment sits after the weights
+    else if (MODE == MODE_MERGE || MODE == MODE_SCORE) idx = r < 3 * NT ? (r % 3) * NT + r / 3 : r;
     else if (MODE == MODE_ATTN) idx = r < NT ? r : r + 2 * NT;
     else idx = (1 + (r & 1)) * NT + (r >> 1);
     return reinterpret_cast<const uint4*>(wbase + (size_t)blk * bstride) + (size_t)idx * SEGV;
   }
+  __device__ __forceinline__ int steps_segs() const { return nsegs; }
+  int nsegs;
   __device__ __forceinline__ void issue(int s) {
     if (s < total_steps) {
       const uint4* g = seg_ptr(s);
+      const unsigned dst = lds_wave + (unsigned)(s % NB) * (SEGV * 16);
 #pragma unroll
-      for (int i = 0; i < NSTAGE; ++i) stage[i] = g[tid + kThreads * i];
+      for (int i = 0; i < NSTAGE; ++i) gload_lds16(g + tid + kThreads * i, dst + kThreads * 16 * i);
     }
   }
-  __device__ __forceinline__ void store(int buf) {
+  __device__ __forceinline__ void init(uint4* lds_, const char* wbase_, size_t bstride_, int spb, int nblocks, int nsegs_) {
+    lds = lds_; wbase = wbase_; bstride = bstride_; steps_per_block = spb; total_steps = spb * nblocks; nsegs = nsegs_;
+    tid = threadIdx.x; step = 0;
+    lds_wave = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)lds_ + (unsigned)(tid >> 6) * 1024u);
 #pragma unroll
-    for (int i = 0; i < NSTAGE; ++i) lds[buf * SEGV + tid + kThreads * i] = stage[i];
-  }
-  __device__ __forceinline__ void init(uint4* lds_, const char* wbase_, size_t bstride_, int spb, int nblocks) {
-    lds = lds_; wbase = wbase_; bstride = bstride_; steps_per_block = spb; total_steps = spb * nblocks;
-    tid = threadIdx.x; step = 0; cur = 0;
-    issue(0);
-    store(0);
+    for (int s = 0; s < NB; ++s) issue(s);
+    // segments 0 .. NB-1 are in flight; the oldest must have landed
+    if (!DRAIN && NB <= total_steps) wait_vmcnt<(NB - 1) * NSTAGE>();
+    else wait_vmcnt<0>();
     __syncthreads();
-    issue(1);
   }
-  // the current segment has been consumed by this wave: publish the next one
+  // the current segment has been consumed by this wave: move to the next one
   __device__ __forceinline__ void advance() {
-    store(cur ^ 1);
-    __syncthreads();
-    cur ^= 1;
     ++step;
-    issue(step + 1);
+    // segments step .. step+NPRE-1 are in flight (when that many remain): the oldest must have landed
+    if (!DRAIN && step + NPRE <= total_steps) wait_vmcnt<(NPRE - 1) * NSTAGE>();
+    else wait_vmcnt<0>();
+    __syncthreads();               // everyone sees segment `step`; everyone is done with `step - 1`
+    issue(step + NPRE);            // into the buffer that held segment step - 1
   }
   template <typename G>
   __device__ __forceinline__ G frag(int f) const {
-    return *reinterpret_cast<const G*>(&lds[cur * SEGV + f * 64 + (tid & 63)]);
+    return *reinterpret_cast<const G*>(&lds[(step % NB) * SEGV + f * 64 + (tid & 63)]);
   }
+  __device__ __forceinline__ const uint4* cur() const { return &lds[(step % NB) * SEGV]; }
 };
 
 }  // namespace longer
