@@ -26,9 +26,8 @@ struct RowSrc {
 };
 
 struct BlockParams {
-  // packed parameters: first layer of this launch, consecutive layers bstride bytes apart
+  // packed parameters: the linear segment stream this launch consumes (all its layers)
   const char* wbase;
-  size_t bstride;
   int n_layers, FF;
   float eps, scale_l2e;
   int act, gmask_causal;
@@ -141,8 +140,7 @@ __device__ __forceinline__ uint32_t range_bits(int lo, int hi, int base) {
 // the interval end) and clamped to [0, 1]; max abs error 1.3e-3, below the bf16 rounding
 // step of the values it produces.
 template <bool EXACT>
-__device__ __forceinline__ float act_fn(float x, int act) {
-  if (act == 1) return fmaxf(x, 0.f);
+__device__ __forceinline__ float gelu_fn(float x) {
   if (EXACT) return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
   const float xc = __builtin_amdgcn_fmed3f(x, -3.5f, 3.5f);
   const float u = xc * xc;
@@ -155,33 +153,47 @@ __device__ __forceinline__ float act_fn(float x, int act) {
   return x * phi;
 }
 
-// LayerNorm over the feature dimension of TT token tiles, result as B-operand groups
+// LayerNorm over the feature dimension of TT token tiles, result as B-operand groups.
+// fp32 mode takes the variance in a second pass over the centred values; bf16 mode uses
+// E[x^2] - mean^2 in one pass (the result is rounded to bf16 anyway).
 template <typename T, int D, int TT>
 __device__ __forceinline__ void layer_norm(const f32x16 (&x)[TT][D / 32], const float* gam, const float* bet,
                                            float eps, int hi, typename ET<T>::grp (&out)[TT][D / ET<T>::GF]) {
   using E = ET<T>;
   constexpr int NT = D / 32;
+  constexpr bool EXACT = sizeof(T) == 4;
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
-    float s = 0.f;
+    float s = 0.f, q = 0.f;
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s += x[tt][t][r];
+      for (int r = 0; r < 16; ++r) { s += x[tt][t][r]; if (!EXACT) q = fmaf(x[tt][t][r], x[tt][t][r], q); }
     s += xor32(s);
     const float mean = s * (1.0f / D);
-    float v = 0.f;
+    float var;
+    if (EXACT) {
+      float v = 0.f;
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+      for (int t = 0; t < NT; ++t)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { float dlt = x[tt][t][r] - mean; v += dlt * dlt; }
-    v += xor32(v);
-    const float rstd = 1.0f / sqrtf(v * (1.0f / D) + eps);
+        for (int r = 0; r < 16; ++r) { float dlt = x[tt][t][r] - mean; v += dlt * dlt; }
+      v += xor32(v);
+      var = v * (1.0f / D);
+    } else {
+      q += xor32(q);
+      var = fmaxf(q * (1.0f / D) - mean * mean, 0.f);
+    }
+    const float rstd = 1.0f / sqrtf(var + eps);
+    const float shift = -mean * rstd;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       f32x16 g = bias_tile(gam, t, hi), b = bias_tile(bet, t, hi), y;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) y[r] = (x[tt][t][r] - mean) * rstd * g[r] + b[r];
+      for (int r = 0; r < 16; ++r) {
+        const float nrm = EXACT ? (x[tt][t][r] - mean) * rstd : fmaf(x[tt][t][r], rstd, shift);
+        y[r] = fmaf(nrm, g[r], b[r]);
+      }
 #pragma unroll
       for (int gg = 0; gg < E::GPT; ++gg) out[tt][t * E::GPT + gg] = E::pack(y, gg);
     }
@@ -223,8 +235,70 @@ __device__ __forceinline__ float softmax_step(const f32x16& S, uint32_t ab, floa
   return alpha;
 }
 
+// Softmax over the keys of the lane's own tile when only a window of W accumulator
+// registers can be visible (groups of at most 2 W adjacent tokens: register window
+// [W widx, W widx + W) with widx = (lane % 32) / (2 W)).  `wb` holds the visibility bits of
+// the window (bit 8 (c/4) + c%4 for window register c).  Same contract as softmax_step;
+// with W = 16 it is softmax_step.
+template <typename T, int W>
+__device__ __forceinline__ float softmax_window(const f32x16& S, int widx, uint32_t wb, float scale_l2e, float& m,
+                                                float& l, typename ET<T>::grp (&pop)[ET<T>::GPT]) {
+  if (W == 16) return softmax_step<T>(S, wb, scale_l2e, m, l, pop);
+  float x[W];
+  const bool b0 = widx & 1, b1 = widx & 2;
+#pragma unroll
+  for (int c = 0; c < W; ++c) {
+    if (W == 8) x[c] = b0 ? S[8 + c] : S[c];
+    else { const float lo = b0 ? S[4 + c] : S[c], up = b0 ? S[12 + c] : S[8 + c]; x[c] = b1 ? up : lo; }
+  }
+  float mt = kNegBig;
+#pragma unroll
+  for (int c = 0; c < W; ++c) {
+    const bool ok = (wb >> (8 * (c / 4) + (c % 4))) & 1u;
+    x[c] = ok ? x[c] * scale_l2e : kNegBig;
+    mt = fmaxf(mt, x[c]);
+  }
+  mt = fmaxf(mt, xor32(mt));
+  const float mnew = fmaxf(m, mt);
+  const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+  float lt = 0.f;
+#pragma unroll
+  for (int c = 0; c < W; ++c) {
+    const bool ok = (wb >> (8 * (c / 4) + (c % 4))) & 1u;
+    x[c] = ok ? __builtin_amdgcn_exp2f(x[c] - mnew) : 0.f;
+    lt += x[c];
+  }
+  lt += xor32(lt);
+  l = l * alpha + lt;
+  m = mnew;
+  if (sizeof(T) == 2) {
+    // pairs of probabilities -> packed bf16, dropped into the window's slots of the 8 pair slots
+    uint32_t pk[W / 2];
+#pragma unroll
+    for (int c = 0; c < W / 2; ++c) {
+      const bf16x2 t2 = {(__bf16)x[2 * c], (__bf16)x[2 * c + 1]};
+      pk[c] = __builtin_bit_cast(uint32_t, t2);
+    }
+    uint32_t slot[8];
+#pragma unroll
+    for (int ps = 0; ps < 8; ++ps) slot[ps] = (ps / (W / 2) == widx) ? pk[ps % (W / 2)] : 0u;
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const u32x4 v = {slot[4 * g], slot[4 * g + 1], slot[4 * g + 2], slot[4 * g + 3]};
+      pop[g] = __builtin_bit_cast(typename ET<T>::grp, v);
+    }
+  } else {
+    f32x16 pv;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) pv[r] = (r / W == widx) ? x[r % W] : 0.f;
+#pragma unroll
+    for (int g = 0; g < ET<T>::GPT; ++g) pop[g] = ET<T>::pack(pv, g);
+  }
+  return alpha;
+}
+
 // ---------------------------------------------------------------------------- the kernel
-template <typename T, int D, int DH, int TT, int MODE>
+template <typename T, int D, int DH, int TT, int MODE, int W>
 __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block_kernel(const BlockParams p) {
   using E = ET<T>;
   using grp = typename E::grp;
@@ -247,7 +321,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
   bool inrange[TT];        // the lane's row exists in the output tensor
   int usr[TT], Tu[TT];
   long long out_off[TT];   // element offset of the lane's output row
-  uint32_t tilebits[TT];   // MODE_MERGE / MODE_SCORE: in-tile keys visible to this lane
+  uint32_t tilebits[TT];   // MODE_MERGE / MODE_SCORE: in-tile keys visible to this lane (window bits)
+  const int widx = W == 16 ? 0 : j / (2 * W);
   int lo1[TT], hi1[TT], lo2[TT], hi2[TT], kthi[TT];   // EXT: visible key ranges, key tile count
   f32x16 resid[TT][NT];
 
@@ -271,7 +346,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
       load_rows<T, NT>(resid[tt], p.H, 0, ((long long)u * p.L + pos) * D, valid[tt], hi);
       const uint32_t vb = (uint32_t)__ballot(valid[tt]);
       const uint32_t gb = (p.K >= 32 ? 0xffffffffu : ((1u << p.K) - 1u)) << (p.K * (j / p.K));
-      tilebits[tt] = (gb & vb) >> (4 * hi);
+      tilebits[tt] = ((gb & vb) >> (4 * hi)) >> (2 * W * widx);
     } else if (MODE == MODE_KVPROJ) {
       const int u = tile / p.tiles_per_user, kt = tile - u * p.tiles_per_user;
       const int c = 32 * kt + j;
@@ -324,7 +399,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
       load_rows<T, NT>(resid[tt], p.Gc, 0, out_off[tt], valid[tt], hi);
       const uint32_t vb = (uint32_t)__ballot(valid[tt]);
       const int gbase = p.m * (j / p.m);
-      tilebits[tt] = (range_bits(gbase + (p.gmask_causal ? gi : 0), gbase + p.m, 0) & vb) >> (4 * hi);
+      tilebits[tt] = ((range_bits(gbase + (p.gmask_causal ? gi : 0), gbase + p.m, 0) & vb) >> (4 * hi)) >> (2 * W * widx);
     }
   }
 
@@ -345,9 +420,9 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
     }
   }
 
-  WStream<SEGV, MODE, NT, NB> ws;
+  WStream<SEGV, NB, MODE == MODE_KVPROJ> ws;
   const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : (MODE == MODE_ATTN ? 2 * NT + 2 * NC : 4 * NT + 2 * NC));
-  ws.init(lds, p.wbase, p.bstride, steps, p.n_layers, 4 * NT + 2 * NC);
+  ws.init(lds, p.wbase, steps * p.n_layers);
 
   for (int layer = 0; layer < p.n_layers; ++layer) {
     // the block's first segment holds its fp32 vectors: keep a copy for the whole layer
@@ -429,7 +504,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
 #pragma unroll
             for (int g2 = 0; g2 < GPH; ++g2) S = E::mma(kop[hh * GPH + g2], qop[hh * GPH + g2], S);
             grp pop[GPT];
-            softmax_step<T>(S, tilebits[tt], p.scale_l2e, mrun[hh], lrun[hh], pop);
+            softmax_window<T, W>(S, widx, tilebits[tt], p.scale_l2e, mrun[hh], lrun[hh], pop);
 #pragma unroll
             for (int g = 0; g < GPT; ++g) acc[hh] = E::mma(vop[g], pop[g], acc[hh]);
           }
@@ -531,8 +606,13 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
       grp hop[TT][GPT];
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) {
+        if (p.act == 1) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) ah[tt][r] = act_fn<sizeof(T) == 4>(ah[tt][r], p.act);
+          for (int r = 0; r < 16; ++r) ah[tt][r] = fmaxf(ah[tt][r], 0.f);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) ah[tt][r] = gelu_fn<sizeof(T) == 4>(ah[tt][r]);
+        }
 #pragma unroll
         for (int g = 0; g < GPT; ++g) hop[tt][g] = E::pack(ah[tt], g);
       }
@@ -611,24 +691,32 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
   }
 }
 
-// Host-side launcher, one definition per (T, D, DH) instantiation file.
+// Host-side launcher, one definition per (T, D, DH) instantiation file.  `win` is the
+// register window of the in-tile softmax (4, 8 or 16; merge and scoring modes only).
 template <typename T, int D, int DH>
-int launch_block(int mode, int tt, const BlockParams& p, dim3 grid, hipStream_t stream);
+int launch_block(int mode, int tt, int win, const BlockParams& p, dim3 grid, hipStream_t stream);
+
+#define LONGER_LAUNCH(T, D, DH, TTV, MODEV, WV) \
+  hipLaunchKernelGGL((block_kernel<T, D, DH, TTV, MODEV, WV>), grid, dim3(kThreads), 0, stream, p)
 
 #define LONGER_INSTANTIATE(T, D, DH)                                                                  \
   template <>                                                                                         \
-  int launch_block<T, D, DH>(int mode, int tt, const BlockParams& p, dim3 grid, hipStream_t stream) { \
-    if (tt == 2) {                                                                                    \
-      if (mode == MODE_MERGE) hipLaunchKernelGGL((block_kernel<T, D, DH, 2, MODE_MERGE>), grid, dim3(kThreads), 0, stream, p); \
-      else return -1;                                                                                 \
-    } else {                                                                                          \
-      switch (mode) {                                                                                 \
-        case MODE_MERGE: hipLaunchKernelGGL((block_kernel<T, D, DH, 1, MODE_MERGE>), grid, dim3(kThreads), 0, stream, p); break;   \
-        case MODE_KVPROJ: hipLaunchKernelGGL((block_kernel<T, D, DH, 1, MODE_KVPROJ>), grid, dim3(kThreads), 0, stream, p); break; \
-        case MODE_ATTN: hipLaunchKernelGGL((block_kernel<T, D, DH, 1, MODE_ATTN>), grid, dim3(kThreads), 0, stream, p); break;     \
-        case MODE_SCORE: hipLaunchKernelGGL((block_kernel<T, D, DH, 1, MODE_SCORE>), grid, dim3(kThreads), 0, stream, p); break;   \
-        default: return -1;                                                                           \
-      }                                                                                               \
+  int launch_block<T, D, DH>(int mode, int tt, int win, const BlockParams& p, dim3 grid, hipStream_t stream) { \
+    if (tt != 1) return -1;                                                                           \
+    switch (mode) {                                                                                   \
+      case MODE_MERGE:                                                                                \
+        if (win == 4) LONGER_LAUNCH(T, D, DH, 1, MODE_MERGE, 4);                                      \
+        else if (win == 8) LONGER_LAUNCH(T, D, DH, 1, MODE_MERGE, 8);                                 \
+        else LONGER_LAUNCH(T, D, DH, 1, MODE_MERGE, 16);                                              \
+        break;                                                                                        \
+      case MODE_KVPROJ: LONGER_LAUNCH(T, D, DH, 1, MODE_KVPROJ, 16); break;                           \
+      case MODE_ATTN: LONGER_LAUNCH(T, D, DH, 1, MODE_ATTN, 16); break;                               \
+      case MODE_SCORE:                                                                                \
+        if (win == 4) LONGER_LAUNCH(T, D, DH, 1, MODE_SCORE, 4);                                      \
+        else if (win == 8) LONGER_LAUNCH(T, D, DH, 1, MODE_SCORE, 8);                                 \
+        else LONGER_LAUNCH(T, D, DH, 1, MODE_SCORE, 16);                                              \
+        break;                                                                                        \
+      default: return -1;                                                                             \
     }                                                                                                 \
     return hipGetLastError() == hipSuccess ? 0 : -3;                                                  \
   }

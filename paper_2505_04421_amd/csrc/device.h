@@ -29,6 +29,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;   // 4 waves, one per SIMD
 constexpr int kWaves = 4;
@@ -103,15 +105,20 @@ struct VecLayout {
 
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// bytes of one packed block for element size es: all weight segments, then the fp32
-// vectors padded to one more segment (they travel through the weight stream as well)
+// Packed parameters of one block travel as "segments" of D/GF fragments (1 KiB each: 64
+// lanes x 16 B).  Two layouts, both in exactly the order a kernel consumes them so that a
+// launch reads one linear stream:
+//   FUSED  [vec][q0 k0 v0 q1 k1 v1 ...][o0 ..][w1(0) w2(0) w1(1) w2(1) ...]      (merge, scoring)
+//   SPLIT  [vec][k0 v0 k1 v1 ...] then [vec][q0 q1 ..][o0 ..][w1(0) w2(0) ...]   (K/V projection, attention)
+// "vec" is one segment holding the block's fp32 vectors (VecLayout), zero padded.
+enum PackLayout { LAYOUT_FUSED = 0, LAYOUT_SPLIT = 1 };
 __host__ __device__ inline size_t packed_seg_bytes(int D, int es) { return (size_t)D * 32 * es; }   // D/GF KiB, GF = 32/es
-__host__ __device__ inline int packed_num_segs(int D, int FF) { return 4 * (D / 32) + 2 * (FF / 32); }
-__host__ __device__ inline size_t packed_vec_offset(int D, int FF, int es) {
-  return (size_t)packed_num_segs(D, FF) * packed_seg_bytes(D, es);
-}
+__host__ __device__ inline int fused_segs(int D, int FF) { return 1 + 4 * (D / 32) + 2 * (FF / 32); }
+__host__ __device__ inline int kv_segs(int D) { return 1 + 2 * (D / 32); }
+__host__ __device__ inline int attn_segs(int D, int FF) { return 1 + 2 * (D / 32) + 2 * (FF / 32); }
+// room for either layout
 __host__ __device__ inline size_t packed_block_bytes(int D, int FF, int es) {
-  return (size_t)(packed_num_segs(D, FF) + 1) * packed_seg_bytes(D, es);
+  return (size_t)(fused_segs(D, FF) + 1) * packed_seg_bytes(D, es);
 }
 
 enum Mode { MODE_MERGE = 0, MODE_KVPROJ = 1, MODE_ATTN = 2, MODE_SCORE = 3 };
@@ -134,70 +141,60 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // ------------------------------------------------------------------------------------
-// Weight stream: all waves of a workgroup consume the same sequence of 16-byte-per-lane
-// segments.  Segments travel global -> LDS directly into a ring of NB buffers, NB-1
-// segments ahead of the consumer, so that L2/HBM latency is covered by the MFMA work of
-// several segments; one barrier per segment.  The first segment of every block carries
-// the block's fp32 vectors (LayerNorm gain/bias, biases).
-template <int SEGV, int MODE, int NT, int NB>
+// Weight stream: all waves of a workgroup consume the same linear sequence of segments.
+// Segments travel global -> LDS directly into a ring of NB buffers, NB-1 segments ahead
+// of the consumer, so that L2/HBM latency is covered by the MFMA work of several
+// segments; one barrier per segment.
+template <int SEGV, int NB, bool DRAIN>
 struct WStream {
   static constexpr int NSTAGE = SEGV / kThreads;
   static constexpr int NPRE = NB - 1;
-  // K/V projection stores fragments inside its loop; loads and stores may retire out of
-  // order with respect to each other, so that mode always drains the counter.
-  static constexpr bool DRAIN = (MODE == MODE_KVPROJ);
   static_assert(SEGV % kThreads == 0 && NSTAGE >= 1, "segment must cover all threads");
   uint4* lds;
-  const char* wbase;
-  size_t bstride;
+  const uint4* gnext;    // this thread's 16 bytes of the next segment to fetch
   unsigned lds_wave;     // LDS byte address of this wave's first 16-byte slot in ring buffer 0
-  int steps_per_block, total_steps, step, tid;
+  int total, step, issued, slot_issue, slot_cur, lane;
 
-  __device__ __forceinline__ const uint4* seg_ptr(int s) const {
-    int blk = s / steps_per_block;
-    int r = s - blk * steps_per_block - 1;
-    int idx;
-    if (r < 0) idx = steps_segs();                    // the vector segment sits after the weights
-    else if (MODE == MODE_MERGE || MODE == MODE_SCORE) idx = r < 3 * NT ? (r % 3) * NT + r / 3 : r;
-    else if (MODE == MODE_ATTN) idx = r < NT ? r : r + 2 * NT;
-    else idx = (1 + (r & 1)) * NT + (r >> 1);
-    return reinterpret_cast<const uint4*>(wbase + (size_t)blk * bstride) + (size_t)idx * SEGV;
-  }
-  __device__ __forceinline__ int steps_segs() const { return nsegs; }
-  int nsegs;
-  __device__ __forceinline__ void issue(int s) {
-    if (s < total_steps) {
-      const uint4* g = seg_ptr(s);
-      const unsigned dst = lds_wave + (unsigned)(s % NB) * (SEGV * 16);
+  __device__ __forceinline__ void issue() {
+    if (issued < total) {
+      const unsigned dst = lds_wave + (unsigned)slot_issue * (SEGV * 16);
 #pragma unroll
-      for (int i = 0; i < NSTAGE; ++i) gload_lds16(g + tid + kThreads * i, dst + kThreads * 16 * i);
+      for (int i = 0; i < NSTAGE; ++i) gload_lds16(gnext + kThreads * i, dst + kThreads * 16 * i);
+      gnext += SEGV;
+      ++issued;
+      slot_issue = slot_issue + 1 == NB ? 0 : slot_issue + 1;
     }
   }
-  __device__ __forceinline__ void init(uint4* lds_, const char* wbase_, size_t bstride_, int spb, int nblocks, int nsegs_) {
-    lds = lds_; wbase = wbase_; bstride = bstride_; steps_per_block = spb; total_steps = spb * nblocks; nsegs = nsegs_;
-    tid = threadIdx.x; step = 0;
+  // DRAIN: a mode that stores to global memory inside its loop (loads and stores may
+  // retire out of order with respect to each other) always waits for everything.
+  __device__ __forceinline__ void init(uint4* lds_, const void* gbase, int total_) {
+    lds = lds_; total = total_; step = 0; issued = 0; slot_issue = 0; slot_cur = 0;
+    const int tid = threadIdx.x;
+    lane = tid & 63;
+    gnext = reinterpret_cast<const uint4*>(gbase) + tid;
     lds_wave = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)lds_ + (unsigned)(tid >> 6) * 1024u);
 #pragma unroll
-    for (int s = 0; s < NB; ++s) issue(s);
+    for (int s = 0; s < NB; ++s) issue();
     // segments 0 .. NB-1 are in flight; the oldest must have landed
-    if (!DRAIN && NB <= total_steps) wait_vmcnt<(NB - 1) * NSTAGE>();
+    if (!DRAIN && NB <= total) wait_vmcnt<(NB - 1) * NSTAGE>();
     else wait_vmcnt<0>();
     __syncthreads();
   }
   // the current segment has been consumed by this wave: move to the next one
   __device__ __forceinline__ void advance() {
     ++step;
+    slot_cur = slot_cur + 1 == NB ? 0 : slot_cur + 1;
     // segments step .. step+NPRE-1 are in flight (when that many remain): the oldest must have landed
-    if (!DRAIN && step + NPRE <= total_steps) wait_vmcnt<(NPRE - 1) * NSTAGE>();
+    if (!DRAIN && step + NPRE <= total) wait_vmcnt<(NPRE - 1) * NSTAGE>();
     else wait_vmcnt<0>();
     __syncthreads();               // everyone sees segment `step`; everyone is done with `step - 1`
-    issue(step + NPRE);            // into the buffer that held segment step - 1
+    issue();                       // into the buffer that held segment step - 1
   }
   template <typename G>
   __device__ __forceinline__ G frag(int f) const {
-    return *reinterpret_cast<const G*>(&lds[(step % NB) * SEGV + f * 64 + (tid & 63)]);
+    return *reinterpret_cast<const G*>(&lds[slot_cur * SEGV + f * 64 + lane]);
   }
-  __device__ __forceinline__ const uint4* cur() const { return &lds[(step % NB) * SEGV]; }
+  __device__ __forceinline__ const uint4* cur() const { return &lds[slot_cur * SEGV]; }
 };
 
 }  // namespace longer

@@ -11,13 +11,13 @@
 namespace longer {
 
 // explicit specialisations defined in the inst_*.hip files
-template <> int launch_block<__bf16, 64, 16>(int, int, const BlockParams&, dim3, hipStream_t);
-template <> int launch_block<__bf16, 128, 16>(int, int, const BlockParams&, dim3, hipStream_t);
-template <> int launch_block<__bf16, 256, 32>(int, int, const BlockParams&, dim3, hipStream_t);
-template <> int launch_block<float, 32, 16>(int, int, const BlockParams&, dim3, hipStream_t);
-template <> int launch_block<float, 64, 16>(int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<__bf16, 64, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<__bf16, 128, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<__bf16, 256, 32>(int, int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<float, 32, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<float, 64, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 
-typedef int (*launch_fn)(int, int, const BlockParams&, dim3, hipStream_t);
+typedef int (*launch_fn)(int, int, int, const BlockParams&, dim3, hipStream_t);
 
 static launch_fn find_launch(int dtype, int D, int DH) {
   if (dtype == LONGER_BF16) {
@@ -68,56 +68,81 @@ struct StageScope {
 
 // ------------------------------------------------------------------------------------
 // Pack kernel: raw [in, out] matrices of one block -> MFMA A/B fragments in the order
-// the block kernel streams them, plus the small vectors as fp32.
+// the block kernels stream them (see PackLayout in device.h), the small vectors as fp32.
 struct RawBlock { longer_block b; };
 
 template <typename T>
-__global__ void pack_block_kernel(const RawBlock raw, char* dst, int D, int FF) {
+__global__ void pack_block_kernel(const RawBlock raw, char* dst, int D, int FF, int layout) {
   using E = ET<T>;
   const int NT = D / 32, NC = FF / 32, NG = D / E::GF, SEGV = NG * 64;
-  const long long nvec16 = (long long)(4 * NT + 2 * NC) * SEGV;
-  const long long nvecf = 9LL * D + FF;
+  const int nseg = layout == LAYOUT_FUSED ? fused_segs(D, FF) : kv_segs(D) + attn_segs(D, FF);
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < nvec16) {
-    const int seg = (int)(idx / SEGV);
-    const int within = (int)(idx - (long long)seg * SEGV);
-    const int f = within / 64, lane = within % 64, n_in = lane & 31, hi = lane >> 5;
-    const T* W;
-    int ncols, nt, s;
-    if (seg < 4 * NT) {
-      const int which = seg / NT;
-      W = reinterpret_cast<const T*>(which == 0 ? raw.b.wq : which == 1 ? raw.b.wk : which == 2 ? raw.b.wv : raw.b.wo);
-      ncols = D; nt = seg % NT; s = f;
+  if (idx >= (long long)nseg * SEGV) return;
+  int seg = (int)(idx / SEGV);
+  const int within = (int)(idx - (long long)seg * SEGV);
+  // decode the destination segment: kind 0 vec, 1 q, 2 k, 3 v, 4 o, 5 w1, 6 w2; tile/chunk index
+  int kind, ti;
+  if (layout == LAYOUT_FUSED) {
+    if (seg == 0) { kind = 0; ti = 0; }
+    else if (seg <= 3 * NT) { kind = 1 + (seg - 1) % 3; ti = (seg - 1) / 3; }
+    else if (seg <= 4 * NT) { kind = 4; ti = seg - 1 - 3 * NT; }
+    else { kind = 5 + ((seg - 1 - 4 * NT) & 1); ti = (seg - 1 - 4 * NT) >> 1; }
+  } else {
+    if (seg < kv_segs(D)) {
+      if (seg == 0) { kind = 0; ti = 0; }
+      else { kind = 2 + ((seg - 1) & 1); ti = (seg - 1) >> 1; }
     } else {
-      const int c = (seg - 4 * NT) / 2;
-      if (((seg - 4 * NT) & 1) == 0) { W = reinterpret_cast<const T*>(raw.b.w1); ncols = FF; nt = c; s = f; }
-      else { W = reinterpret_cast<const T*>(raw.b.w2); ncols = D; nt = f / E::GPT; s = c * E::GPT + (f % E::GPT); }
+      seg -= kv_segs(D);
+      if (seg == 0) { kind = 0; ti = 0; }
+      else if (seg <= NT) { kind = 1; ti = seg - 1; }
+      else if (seg <= 2 * NT) { kind = 4; ti = seg - 1 - NT; }
+      else { kind = 5 + ((seg - 1 - 2 * NT) & 1); ti = (seg - 1 - 2 * NT) >> 1; }
     }
-    const int t = s / E::GPT, g = s % E::GPT;
-    typename E::grp out;
-    for (int e = 0; e < E::EPL; ++e) {
-      const int k = 32 * t + tile_row(E::EPL * g + e, hi);
-      out[e] = W[(size_t)k * ncols + 32 * nt + n_in];
-    }
-    reinterpret_cast<typename E::grp*>(dst)[idx] = out;
-  } else if (idx < nvec16 + nvecf) {
-    const int i = (int)(idx - nvec16);
-    const VecLayout vl{D, FF};
-    float* v = reinterpret_cast<float*>(dst + (size_t)nvec16 * 16);
-    const T* src;
-    int off;
-    if (i < vl.ln1_b()) { src = (const T*)raw.b.ln1_g; off = i; }
-    else if (i < vl.bq()) { src = (const T*)raw.b.ln1_b; off = i - vl.ln1_b(); }
-    else if (i < vl.bk()) { src = (const T*)raw.b.bq; off = i - vl.bq(); }
-    else if (i < vl.bv()) { src = (const T*)raw.b.bk; off = i - vl.bk(); }
-    else if (i < vl.bo()) { src = (const T*)raw.b.bv; off = i - vl.bv(); }
-    else if (i < vl.ln2_g()) { src = (const T*)raw.b.bo; off = i - vl.bo(); }
-    else if (i < vl.ln2_b()) { src = (const T*)raw.b.ln2_g; off = i - vl.ln2_g(); }
-    else if (i < vl.b2()) { src = (const T*)raw.b.ln2_b; off = i - vl.ln2_b(); }
-    else if (i < vl.b1()) { src = (const T*)raw.b.b2; off = i - vl.b2(); }
-    else { src = (const T*)raw.b.b1; off = i - vl.b1(); }
-    v[i] = (float)src[off];
   }
+  if (kind == 0) {
+    const VecLayout vl{D, FF};
+    f32x4 out;
+    for (int e = 0; e < 4; ++e) {
+      const int i = within * 4 + e;
+      float v = 0.f;
+      if (i < vl.total()) {
+        const T* src;
+        int off;
+        if (i < vl.ln1_b()) { src = (const T*)raw.b.ln1_g; off = i; }
+        else if (i < vl.bq()) { src = (const T*)raw.b.ln1_b; off = i - vl.ln1_b(); }
+        else if (i < vl.bk()) { src = (const T*)raw.b.bq; off = i - vl.bq(); }
+        else if (i < vl.bv()) { src = (const T*)raw.b.bk; off = i - vl.bk(); }
+        else if (i < vl.bo()) { src = (const T*)raw.b.bv; off = i - vl.bv(); }
+        else if (i < vl.ln2_g()) { src = (const T*)raw.b.bo; off = i - vl.bo(); }
+        else if (i < vl.ln2_b()) { src = (const T*)raw.b.ln2_g; off = i - vl.ln2_g(); }
+        else if (i < vl.b2()) { src = (const T*)raw.b.ln2_b; off = i - vl.ln2_b(); }
+        else if (i < vl.b1()) { src = (const T*)raw.b.b2; off = i - vl.b2(); }
+        else { src = (const T*)raw.b.b1; off = i - vl.b1(); }
+        v = (float)src[off];
+      }
+      out[e] = v;
+    }
+    reinterpret_cast<f32x4*>(dst)[idx] = out;
+    return;
+  }
+  const int f = within / 64, lane = within % 64, n_in = lane & 31, hi = lane >> 5;
+  const T* W;
+  int ncols, nt, sg;
+  if (kind <= 4) {
+    W = reinterpret_cast<const T*>(kind == 1 ? raw.b.wq : kind == 2 ? raw.b.wk : kind == 3 ? raw.b.wv : raw.b.wo);
+    ncols = D; nt = ti; sg = f;
+  } else if (kind == 5) {
+    W = reinterpret_cast<const T*>(raw.b.w1); ncols = FF; nt = ti; sg = f;
+  } else {
+    W = reinterpret_cast<const T*>(raw.b.w2); ncols = D; nt = f / E::GPT; sg = ti * E::GPT + (f % E::GPT);
+  }
+  const int t = sg / E::GPT, g = sg % E::GPT;
+  typename E::grp out;
+  for (int e = 0; e < E::EPL; ++e) {
+    const int k = 32 * t + tile_row(E::EPL * g + e, hi);
+    out[e] = W[(size_t)k * ncols + 32 * nt + n_in];
+  }
+  reinterpret_cast<typename E::grp*>(dst)[idx] = out;
 }
 
 template <typename T>
@@ -145,7 +170,8 @@ __global__ void probe_kernel(int32_t* out) {
 // ------------------------------------------------------------------------------------
 struct Shape {
   int D, DH, DHi, FF, es, n, NT, GPT;
-  size_t pb;          // packed block bytes
+  size_t pb;          // bytes reserved per packed block (either layout)
+  size_t seg;         // bytes of one stream segment
   launch_fn main_fn, inner_fn;
 };
 
@@ -165,6 +191,8 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
   s->D = c->d; s->FF = c->ffn_mult * c->d; s->es = c->dtype == LONGER_BF16 ? 2 : 4;
   s->n = c->m + c->k_recent; s->NT = c->d / 32; s->GPT = c->dtype == LONGER_BF16 ? 2 : 4;
   s->pb = packed_block_bytes(s->D, s->FF, s->es);
+  s->seg = packed_seg_bytes(s->D, s->es);
+  if ((size_t)(9 * s->D + s->FF) * 4 > s->seg) return fail(LONGER_ERR_ARG, "ffn_mult=%d too large for d=%d", c->ffn_mult, c->d);
   s->main_fn = s->inner_fn = nullptr; s->DH = s->DHi = 0;
   if (need_main) {
     if (c->heads <= 0 || c->d % c->heads) return fail(LONGER_ERR_ARG, "heads=%d does not divide d=%d", c->heads, c->d);
@@ -227,7 +255,8 @@ static CacheLayout make_cache_layout(const longer_config* c, const Shape& s, int
   return cl;
 }
 
-static int pack_blocks(const longer_config* c, const Shape& s, const longer_block* blocks, int nb, char* dst, hipStream_t st) {
+static int pack_blocks(const longer_config* c, const Shape& s, const longer_block* blocks, int nb, int layout, char* dst,
+                       size_t stride, hipStream_t st) {
   StageScope scope(ST_PACK, st);
   for (int i = 0; i < nb; ++i) {
     const longer_block& b = blocks[i];
@@ -235,10 +264,11 @@ static int pack_blocks(const longer_config* c, const Shape& s, const longer_bloc
     for (int j = 0; j < 16; ++j)
       if (!ptrs[j]) return fail(LONGER_ERR_ARG, "block %d: parameter pointer %d is NULL", i, j);
     RawBlock rb; rb.b = b;
-    const long long n = (long long)packed_num_segs(s.D, s.FF) * (s.D / (32 / s.es)) * 64 + 9LL * s.D + s.FF;
+    const int nseg = layout == LAYOUT_FUSED ? fused_segs(s.D, s.FF) : kv_segs(s.D) + attn_segs(s.D, s.FF);
+    const long long n = (long long)nseg * (long long)(s.seg / 16);
     const int grid = cdiv(n, 256);
-    if (c->dtype == LONGER_BF16) hipLaunchKernelGGL(pack_block_kernel<__bf16>, dim3(grid), dim3(256), 0, st, rb, dst + (size_t)i * s.pb, s.D, s.FF);
-    else hipLaunchKernelGGL(pack_block_kernel<float>, dim3(grid), dim3(256), 0, st, rb, dst + (size_t)i * s.pb, s.D, s.FF);
+    if (c->dtype == LONGER_BF16) hipLaunchKernelGGL(pack_block_kernel<__bf16>, dim3(grid), dim3(256), 0, st, rb, dst + (size_t)i * stride, s.D, s.FF, layout);
+    else hipLaunchKernelGGL(pack_block_kernel<float>, dim3(grid), dim3(256), 0, st, rb, dst + (size_t)i * stride, s.D, s.FF, layout);
   }
   return hipGetLastError() == hipSuccess ? 0 : fail(LONGER_ERR_HIP, "pack kernel launch failed");
 }
@@ -254,7 +284,7 @@ static int pack_head(const longer_config* c, const Shape& s, const longer_weight
 static BlockParams base_params(const longer_config* c, const Shape& s, const int32_t* lens, int B, int L, int DH) {
   BlockParams p;
   memset(&p, 0, sizeof(p));
-  p.bstride = s.pb; p.n_layers = 1; p.FF = s.FF; p.eps = c->ln_eps;
+  p.n_layers = 1; p.FF = s.FF; p.eps = c->ln_eps;
   p.scale_l2e = (float)(1.4426950408889634 / std::sqrt((double)DH));
   p.act = c->act; p.gmask_causal = c->gmask == LONGER_GMASK_CAUSAL;
   p.lens = lens; p.B = B; p.L = L; p.K = c->K; p.T = cdiv(L, c->K); p.m = c->m; p.k = c->k_recent;
@@ -276,10 +306,11 @@ static int run_merge(const longer_config* c, const Shape& s, const char* packed,
   p.wbase = packed; p.n_layers = c->inner_layers;
   p.H = H; p.M_out = M_out; p.M_f32 = M_f32; p.Z_out = Z_out;
   const int tt = 1;
+  const int win = c->K <= 8 ? 4 : (c->K <= 16 ? 8 : 16);
   const long long slots = (long long)B * p.T * c->K;
   const int grid = cdiv(slots, 32LL * tt * kWaves);
   StageScope scope(ST_MERGE, st);
-  int rc = s.inner_fn(MODE_MERGE, tt, p, dim3(grid), st);
+  int rc = s.inner_fn(MODE_MERGE, tt, win, p, dim3(grid), st);
   return rc ? fail(LONGER_ERR_HIP, "merge kernel launch failed") : 0;
 }
 
@@ -304,11 +335,11 @@ static int run_layer(const longer_config* c, const Shape& s, const char* packed_
     p.kst = io.kst; p.vst = io.vst; p.kv_ustride = io.kv_ustride; p.kt_per_user = p.tiles_per_user;
     const int grid = cdiv((long long)B * p.tiles_per_user, kWaves);
     StageScope scope(ST_KVPROJ, st);
-    if (s.main_fn(MODE_KVPROJ, 1, p, dim3(grid), st)) return fail(LONGER_ERR_HIP, "kv projection launch failed");
+    if (s.main_fn(MODE_KVPROJ, 1, 16, p, dim3(grid), st)) return fail(LONGER_ERR_HIP, "kv projection launch failed");
   }
   if (!do_attn) return 0;
   BlockParams p = base_params(c, s, lens, B, L, s.DH);
-  p.wbase = packed_blk;
+  p.wbase = packed_blk + (size_t)kv_segs(s.D) * s.seg;     // the attention sub-stream follows the K/V one
   p.src0 = io.q0src; p.src1 = io.q1src;
   p.rows_per_user = io.q_rows; p.tiles_per_user = cdiv(io.q_rows, 32);
   p.gather_recent = io.gather_recent; p.q0 = io.q0;
@@ -318,7 +349,7 @@ static int run_layer(const longer_config* c, const Shape& s, const char* packed_
   p.logits = io.logits; p.head = io.head;
   const int grid = cdiv((long long)B * p.tiles_per_user, kWaves);
   StageScope scope(ST_ATTN, st);
-  if (s.main_fn(MODE_ATTN, 1, p, dim3(grid), st)) return fail(LONGER_ERR_HIP, "attention launch failed");
+  if (s.main_fn(MODE_ATTN, 1, 16, p, dim3(grid), st)) return fail(LONGER_ERR_HIP, "attention launch failed");
   return 0;
 }
 
@@ -353,7 +384,7 @@ static int merge_entry(const longer_config* cfg, const longer_block* inner, cons
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
-  if ((rc = pack_blocks(cfg, s, inner, cfg->inner_layers, w8 + l.packed, st))) return rc;
+  if ((rc = pack_blocks(cfg, s, inner, cfg->inner_layers, LAYOUT_FUSED, w8 + l.packed, (size_t)fused_segs(s.D, s.FF) * s.seg, st))) return rc;
   return run_merge(cfg, s, w8 + l.packed, H, lens, B, L, M_out, 0, Z_out, st);
 }
 
@@ -412,7 +443,7 @@ int longer_hybrid_cross_attn(const longer_config* cfg, const longer_block* cross
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
-  if ((rc = pack_blocks(cfg, s, cross, 1, w8 + l.packed, st))) return rc;
+  if ((rc = pack_blocks(cfg, s, cross, 1, LAYOUT_SPLIT, w8 + l.packed, s.pb, st))) return rc;
   AttnIO io = cross_io(cfg, s, l, w8, G, M, 0, B, L, X_out, 0);
   return run_layer(cfg, s, w8 + l.packed, lens, B, L, io, true, st);
 }
@@ -428,7 +459,7 @@ int longer_self_attn_layer(const longer_config* cfg, const longer_block* blk, co
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
-  if ((rc = pack_blocks(cfg, s, blk, 1, w8 + l.packed, st))) return rc;
+  if ((rc = pack_blocks(cfg, s, blk, 1, LAYOUT_SPLIT, w8 + l.packed, s.pb, st))) return rc;
   AttnIO io = self_io(cfg, s, l, w8, X_in, 0, X_out, 0);
   return run_layer(cfg, s, w8 + l.packed, lens, B, L, io, true, st);
 }
@@ -451,10 +482,10 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
   char* pk = w8 + l.packed;
-  if ((rc = pack_blocks(cfg, s, w->inner, cfg->inner_layers, pk, st))) return rc;
+  if ((rc = pack_blocks(cfg, s, w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(s.D, s.FF) * s.seg, st))) return rc;
   char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
-  if ((rc = pack_blocks(cfg, s, w->cross, 1, pk_cross, st))) return rc;
-  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, pk_cross + s.pb, st))) return rc;
+  if ((rc = pack_blocks(cfg, s, w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb, st))) return rc;
+  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, LAYOUT_SPLIT, pk_cross + s.pb, s.pb, st))) return rc;
   float* head = (float*)(w8 + l.head);
   if (logits_out && (rc = pack_head(cfg, s, w, head, st))) return rc;
 
@@ -488,10 +519,10 @@ int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, con
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
   char* pk = w8 + l.packed;
-  if ((rc = pack_blocks(cfg, s, w->inner, cfg->inner_layers, pk, st))) return rc;
+  if ((rc = pack_blocks(cfg, s, w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(s.D, s.FF) * s.seg, st))) return rc;
   char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
-  if ((rc = pack_blocks(cfg, s, w->cross, 1, pk_cross, st))) return rc;
-  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, pk_cross + s.pb, st))) return rc;
+  if ((rc = pack_blocks(cfg, s, w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb, st))) return rc;
+  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, LAYOUT_SPLIT, pk_cross + s.pb, s.pb, st))) return rc;
   if ((rc = run_merge(cfg, s, pk, H, lens, U, L, w8 + l.M, 1, nullptr, st))) return rc;
 
   const int T = cdiv(L, cfg->K);
@@ -541,8 +572,9 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
   char* pk_cross = w8 + l.packed + (size_t)cfg->inner_layers * s.pb;
-  if ((rc = pack_blocks(cfg, s, w->cross, 1, pk_cross, st))) return rc;
-  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, pk_cross + s.pb, st))) return rc;
+  const size_t fstride = (size_t)fused_segs(s.D, s.FF) * s.seg;   // scoring streams all layers back to back
+  if ((rc = pack_blocks(cfg, s, w->cross, 1, LAYOUT_FUSED, pk_cross, fstride, st))) return rc;
+  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, LAYOUT_FUSED, pk_cross + fstride, fstride, st))) return rc;
   float* head = (float*)(w8 + l.head);
   if (logits_out && (rc = pack_head(cfg, s, w, head, st))) return rc;
 
@@ -556,7 +588,8 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
   const int tiles = cdiv((long long)C * cfg->m, 32);
   dim3 grid(cdiv(tiles, kWaves), U);
   StageScope scope(ST_SCORE, st);
-  if (s.main_fn(MODE_SCORE, 1, p, grid, st)) return fail(LONGER_ERR_HIP, "score kernel launch failed");
+  const int win = cfg->m <= 8 ? 4 : (cfg->m <= 16 ? 8 : 16);
+  if (s.main_fn(MODE_SCORE, 1, win, p, grid, st)) return fail(LONGER_ERR_HIP, "score kernel launch failed");
   return 0;
 }
 
