@@ -241,15 +241,27 @@ __device__ __forceinline__ float softmax_step(const f32x16& S, uint32_t ab, floa
 // the window (bit 8 (c/4) + c%4 for window register c).  Same contract as softmax_step;
 // with W = 16 it is softmax_step.
 template <typename T, int W>
-__device__ __forceinline__ float softmax_window(const f32x16& S, int widx, uint32_t wb, float scale_l2e, float& m,
-                                                float& l, typename ET<T>::grp (&pop)[ET<T>::GPT]) {
+__device__ __forceinline__ float softmax_window(const f32x16& S, int widx, const uint32_t (&wmask)[16 / W], uint32_t wb,
+                                                float scale_l2e, float& m, float& l,
+                                                typename ET<T>::grp (&pop)[ET<T>::GPT]) {
   if (W == 16) return softmax_step<T>(S, wb, scale_l2e, m, l, pop);
   float x[W];
   const bool b0 = widx & 1, b1 = widx & 2;
+  // each score goes through an opaque register copy so that the choice below stays a
+  // two-way select per value (not a variable-index extract from the 16-wide vector)
+  float sv[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { float t = S[r]; asm("" : "+v"(t)); sv[r] = t; }
 #pragma unroll
   for (int c = 0; c < W; ++c) {
-    if (W == 8) x[c] = b0 ? S[8 + c] : S[c];
-    else { const float lo = b0 ? S[4 + c] : S[c], up = b0 ? S[12 + c] : S[8 + c]; x[c] = b1 ? up : lo; }
+    if (W == 8) {
+      const float a0 = sv[c], a1 = sv[8 + c];
+      x[c] = b0 ? a1 : a0;
+    } else {
+      const float a0 = sv[c], a1 = sv[4 + c], a2 = sv[8 + c], a3 = sv[12 + c];
+      const float lo = b0 ? a1 : a0, up = b0 ? a3 : a2;
+      x[c] = b1 ? up : lo;
+    }
   }
   float mt = kNegBig;
 #pragma unroll
@@ -279,9 +291,9 @@ __device__ __forceinline__ float softmax_window(const f32x16& S, int widx, uint3
       const bf16x2 t2 = {(__bf16)x[2 * c], (__bf16)x[2 * c + 1]};
       pk[c] = __builtin_bit_cast(uint32_t, t2);
     }
-    uint32_t slot[8];
+    uint32_t slot[8];     // wmask[w] is all ones in the lanes whose window is w, else zero
 #pragma unroll
-    for (int ps = 0; ps < 8; ++ps) slot[ps] = (ps / (W / 2) == widx) ? pk[ps % (W / 2)] : 0u;
+    for (int ps = 0; ps < 8; ++ps) slot[ps] = pk[ps % (W / 2)] & wmask[ps / (W / 2)];
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const u32x4 v = {slot[4 * g], slot[4 * g + 1], slot[4 * g + 2], slot[4 * g + 3]};
@@ -290,7 +302,7 @@ __device__ __forceinline__ float softmax_window(const f32x16& S, int widx, uint3
   } else {
     f32x16 pv;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) pv[r] = (r / W == widx) ? x[r % W] : 0.f;
+    for (int r = 0; r < 16; ++r) pv[r] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, x[r % W]) & wmask[r / W]);
 #pragma unroll
     for (int g = 0; g < ET<T>::GPT; ++g) pop[g] = ET<T>::pack(pv, g);
   }
@@ -323,6 +335,9 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
   long long out_off[TT];   // element offset of the lane's output row
   uint32_t tilebits[TT];   // MODE_MERGE / MODE_SCORE: in-tile keys visible to this lane (window bits)
   const int widx = W == 16 ? 0 : j / (2 * W);
+  uint32_t wmask[16 / W];
+#pragma unroll
+  for (int w = 0; w < 16 / W; ++w) { wmask[w] = widx == w ? 0xffffffffu : 0u; asm("" : "+v"(wmask[w])); }
   int lo1[TT], hi1[TT], lo2[TT], hi2[TT], kthi[TT];   // EXT: visible key ranges, key tile count
   f32x16 resid[TT][NT];
 
@@ -504,7 +519,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
 #pragma unroll
             for (int g2 = 0; g2 < GPH; ++g2) S = E::mma(kop[hh * GPH + g2], qop[hh * GPH + g2], S);
             grp pop[GPT];
-            softmax_window<T, W>(S, widx, tilebits[tt], p.scale_l2e, mrun[hh], lrun[hh], pop);
+            softmax_window<T, W>(S, widx, wmask, tilebits[tt], p.scale_l2e, mrun[hh], lrun[hh], pop);
 #pragma unroll
             for (int g = 0; g < GPT; ++g) acc[hh] = E::mma(vop[g], pop[g], acc[hh]);
           }
