@@ -29,6 +29,20 @@ def _oracle_flops(cfg, lens=None, B=None):
     return orc.algorithmic_flops(cfg, lens, B=B), orc
 
 
+def measured_traffic(cfg):
+    """HBM bytes per launch of the merge kernel from the committed rocprofv3 counter summary
+    (two --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); None
+    when no summary exists for this workload."""
+    path = os.path.join(ROOT, "profiles", "merge_%s_hbm_traffic.md" % cfg.name.lower())
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg, seconds_target=15.0):
     """Time the fp64 oracle on a bounded sample of users of the same workload."""
     import numpy as np
@@ -60,6 +74,9 @@ def main():
     ap.add_argument("--config", default="C3")
     ap.add_argument("--no-serving", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a kernel of known HBM traffic that "
+                         "calibrates the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the forward path needs no collectives; users shard "
@@ -92,6 +109,13 @@ def main():
 
     def step(i):
         lg.longer_forward(model.ccfg, model.weights, Hs[i % nbuf], G, lens, B, L, Y, logits, ws)
+
+    if args.copy_probe_mib > 0:
+        src = torch.empty(args.copy_probe_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)
@@ -130,7 +154,7 @@ def main():
         "stage_ms_per_step": {k: v[0] / args.steps for k, v in stages.items() if v[1]},
         "roofline": {"kernel": "block_kernel<MODE_MERGE> (fused gather + InnerTrans + pooling)", "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(cfg),
                      "avg_launch_ms": merge_avg_ms, "algorithmic_gflop_per_launch": fl["inner"] / 1e9,
                      "algorithmic_hbm_GBs": merge_bytes / (merge_avg_ms * 1e-3) / 1e9},
     }

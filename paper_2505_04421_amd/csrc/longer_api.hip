@@ -362,15 +362,17 @@ extern "C" {
 const char* longer_last_error(void) { return g_err; }
 
 size_t longer_workspace_bytes(const longer_config* cfg, int B, int L, int C) {
+  g_err[0] = 0;
   Shape s;
   (void)C;
-  if (check_cfg(cfg, &s, false, false) || B <= 0 || L <= 0) return 0;
+  if (check_cfg(cfg, &s, cfg && cfg->inner_layers > 0, true) || B <= 0 || L <= 0) return 0;
   return make_layout(cfg, s, B, L).total;
 }
 
 size_t longer_kv_cache_bytes(const longer_config* cfg, int U, int L) {
+  g_err[0] = 0;
   Shape s;
-  if (check_cfg(cfg, &s, false, false) || U <= 0 || L <= 0) return 0;
+  if (check_cfg(cfg, &s, false, true) || U <= 0 || L <= 0) return 0;
   return make_cache_layout(cfg, s, U, L).total;
 }
 

@@ -1,0 +1,74 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the
+header declares, answers size queries and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import longer_synth as synth
+import paper_2505_04421_amd as lg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "longer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(longer_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = lg.load_library()
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(lg.binding.ENTRY_POINTS)
+
+
+def test_size_queries():
+    c3 = lg.make_config(synth.CONFIGS["C3"])
+    ws = lg.longer_workspace_bytes(c3, 256, 2000)
+    assert ws > 0 and ws % 256 == 0
+    assert lg.longer_workspace_bytes(c3, 512, 2000) > ws
+    c5 = lg.make_config(synth.CONFIGS["C5"])
+    # per user: layer 0 holds ceil(625/32) = 20 key tiles, layers 1..3 hold ceil(64/32) = 2; a tile is
+    # 8 feature tiles x 2 fragments x 1 KiB for K and the same for V
+    per_user = (20 + 3 * 2) * 8 * 2 * 1024 * 2
+    assert lg.longer_kv_cache_bytes(c5, 16, 10000) == 16 * per_user
+
+
+@pytest.mark.parametrize("field,value", [("d", 48), ("heads", 3), ("K", 5), ("m", 3), ("dtype", 7), ("act", 9),
+                                         ("gmask", 2), ("ln_eps", 0.0), ("ffn_mult", 0)])
+def test_bad_config_is_rejected(field, value):
+    cfg = lg.make_config(synth.CONFIGS["C3"])
+    setattr(cfg, field, value)
+    assert lg.longer_workspace_bytes(cfg, 4, 64) == 0
+    assert lg.longer_last_error() != ""
+
+
+def test_entry_points_reject_null_and_small_workspace():
+    lib = lg.load_library()
+    cfg = lg.make_config(synth.CONFIGS["C1"])
+    blk = (lg.binding.CBlock * 1)()
+    fake = ctypes.c_void_p(256)       # never dereferenced: argument checks come first
+    rc = lib.longer_token_merge(ctypes.byref(cfg), blk, fake, None, 4, 64, fake, None, 0, None)
+    assert rc == -1 and "workspace" in lg.longer_last_error()
+    rc = lib.longer_token_merge(ctypes.byref(cfg), blk, fake, None, 4, 64, fake, ctypes.c_void_p(4096), 16, None)
+    assert rc == -2
+    rc = lib.longer_token_merge(ctypes.byref(cfg), blk, None, None, 4, 64, fake, ctypes.c_void_p(4096), 1 << 30, None)
+    assert rc == -1
+    rc = lib.longer_token_merge(ctypes.byref(cfg), blk, fake, None, 0, 64, fake, ctypes.c_void_p(4096), 1 << 30, None)
+    assert rc == -1
+    unsupported = lg.make_config(synth.CONFIGS["C1"].replace(d=96, heads=6, inner_heads=6))
+    rc = lib.longer_token_merge(ctypes.byref(unsupported), blk, fake, None, 4, 64, fake, ctypes.c_void_p(4096), 1 << 30, None)
+    assert rc == -1 and "unsupported" in lg.longer_last_error()
+
+
+def test_compute_calls_fail_loudly_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(lg.LongerError):
+        lg.DeviceModel(synth.CONFIGS["C1"], synth.draw_weights(synth.CONFIGS["C1"]))
