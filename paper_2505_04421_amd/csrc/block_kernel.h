@@ -134,22 +134,22 @@ __device__ __forceinline__ uint32_t range_bits(int lo, int hi, int base) {
   return upper & ~((1u << a) - 1u);
 }
 
-// FFN activation.  EXACT (fp32 mode): GELU in its erf form.  Otherwise (bf16 mode, where
-// the result is rounded to bf16 right away): GELU(x) = x * Phi(x) with Phi - 1/2 replaced
-// by an odd polynomial of degree 9 on [-3.5, 3.5] (minimax fit, constrained to reach 1 at
-// the interval end) and clamped to [0, 1]; max abs error 1.3e-3, below the bf16 rounding
-// step of the values it produces.
+// GELU.  EXACT (fp32 mode): the erf form.  Otherwise (bf16 mode, where the result is rounded
+// to bf16 right away): GELU(x) = x * Phi(x) with Phi - 1/2 replaced by an odd polynomial of
+// degree 9 (minimax fit on [-3.5, 3.5], constrained to reach 1 at the interval end; it keeps
+// growing beyond it) and Phi clamped to [0, 1] by the output modifier of the last fma;
+// max abs error 1.3e-3, below the bf16 rounding step of the values it produces.
 template <bool EXACT>
 __device__ __forceinline__ float gelu_fn(float x) {
   if (EXACT) return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
-  const float xc = __builtin_amdgcn_fmed3f(x, -3.5f, 3.5f);
-  const float u = xc * xc;
+  const float u = x * x;
   float pl = 9.366767568843253e-06f;
   pl = fmaf(pl, u, -0.0003847714538096606f);
   pl = fmaf(pl, u, 0.0064495445928312006f);
   pl = fmaf(pl, u, -0.05893596715178192f);
   pl = fmaf(pl, u, 0.3934098519357524f);
-  const float phi = __builtin_amdgcn_fmed3f(fmaf(xc, pl, 0.5f), 0.f, 1.f);
+  float phi;
+  asm("v_fma_f32 %0, %1, %2, 0.5 clamp" : "=v"(phi) : "v"(x), "v"(pl));
   return x * phi;
 }
 
@@ -320,9 +320,11 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
   constexpr int GPH = DH / E::GF;     // operand groups per head
   constexpr bool FUSED = (MODE == MODE_MERGE || MODE == MODE_SCORE);
   constexpr bool EXT = (MODE == MODE_ATTN || MODE == MODE_SCORE);
-  constexpr int NB = SEGV * 16 >= 16384 ? 6 : 8;   // ring depth of the weight stream
+  constexpr bool BIGSEG = SEGV * 16 >= 16384;
+  constexpr int PSEG = BIGSEG ? 1 : 2;              // segments per panel of the weight stream (one barrier per panel)
+  constexpr int NB = BIGSEG ? 6 : 4;                // ring depth in panels
   static_assert(DH == 16 || DH == 32, "head width");
-  __shared__ uint4 lds[NB * SEGV];
+  __shared__ uint4 lds[NB * PSEG * SEGV];
   __shared__ uint4 vecl[SEGV];          // the current block's fp32 vectors
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j = lane & 31, hi = lane >> 5;
@@ -435,14 +437,17 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
     }
   }
 
-  WStream<SEGV, NB, MODE == MODE_KVPROJ> ws;
+  WStream<SEGV, PSEG, NB, MODE == MODE_KVPROJ> ws;
   const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : (MODE == MODE_ATTN ? 2 * NT + 2 * NC : 4 * NT + 2 * NC));
   ws.init(lds, p.wbase, steps * p.n_layers);
 
   for (int layer = 0; layer < p.n_layers; ++layer) {
     // the block's first segment holds its fp32 vectors: keep a copy for the whole layer
+    // (barriers: nobody still reads the previous block's copy; everybody sees the new one)
+    if (layer > 0) __syncthreads();
 #pragma unroll
     for (int i = 0; i < SEGV / kThreads; ++i) vecl[tid + kThreads * i] = ws.cur()[tid + kThreads * i];
+    __syncthreads();
     ws.advance();
     const float* vec = reinterpret_cast<const float*>(vecl);
     const VecLayout vl{D, p.FF};

@@ -142,59 +142,63 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 // ------------------------------------------------------------------------------------
 // Weight stream: all waves of a workgroup consume the same linear sequence of segments.
-// Segments travel global -> LDS directly into a ring of NB buffers, NB-1 segments ahead
-// of the consumer, so that L2/HBM latency is covered by the MFMA work of several
-// segments; one barrier per segment.
-template <int SEGV, int NB, bool DRAIN>
+// Segments travel global -> LDS directly, in panels of PSEG segments, into a ring of NB
+// panel buffers, NB-1 panels ahead of the consumer, so that L2/HBM latency is covered by
+// the MFMA work of several panels; one barrier per panel.  The stream's length is rounded
+// up to whole panels: the packed buffer must hold PSEG-1 readable segments past its end.
+template <int SEGV, int PSEG, int NB, bool DRAIN>
 struct WStream {
-  static constexpr int NSTAGE = SEGV / kThreads;
+  static constexpr int PANV = SEGV * PSEG;              // 16-byte vectors per panel
+  static constexpr int NSTAGE = PANV / kThreads;
   static constexpr int NPRE = NB - 1;
-  static_assert(SEGV % kThreads == 0 && NSTAGE >= 1, "segment must cover all threads");
+  static_assert(PANV % kThreads == 0 && NSTAGE >= 1, "panel must cover all threads");
   uint4* lds;
-  const uint4* gnext;    // this thread's 16 bytes of the next segment to fetch
+  const uint4* gnext;    // this thread's 16 bytes of the next panel to fetch
   unsigned lds_wave;     // LDS byte address of this wave's first 16-byte slot in ring buffer 0
-  int total, step, issued, slot_issue, slot_cur, lane;
+  int total, step, sub, issued, slot_issue, slot_cur, lane;   // total / step / issued count panels
 
   __device__ __forceinline__ void issue() {
     if (issued < total) {
-      const unsigned dst = lds_wave + (unsigned)slot_issue * (SEGV * 16);
+      const unsigned dst = lds_wave + (unsigned)slot_issue * (PANV * 16);
 #pragma unroll
       for (int i = 0; i < NSTAGE; ++i) gload_lds16(gnext + kThreads * i, dst + kThreads * 16 * i);
-      gnext += SEGV;
+      gnext += PANV;
       ++issued;
       slot_issue = slot_issue + 1 == NB ? 0 : slot_issue + 1;
     }
   }
   // DRAIN: a mode that stores to global memory inside its loop (loads and stores may
   // retire out of order with respect to each other) always waits for everything.
-  __device__ __forceinline__ void init(uint4* lds_, const void* gbase, int total_) {
-    lds = lds_; total = total_; step = 0; issued = 0; slot_issue = 0; slot_cur = 0;
+  __device__ __forceinline__ void init(uint4* lds_, const void* gbase, int total_segments) {
+    lds = lds_; total = (total_segments + PSEG - 1) / PSEG; step = 0; sub = 0; issued = 0; slot_issue = 0; slot_cur = 0;
     const int tid = threadIdx.x;
     lane = tid & 63;
     gnext = reinterpret_cast<const uint4*>(gbase) + tid;
     lds_wave = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)lds_ + (unsigned)(tid >> 6) * 1024u);
 #pragma unroll
     for (int s = 0; s < NB; ++s) issue();
-    // segments 0 .. NB-1 are in flight; the oldest must have landed
+    // panels 0 .. NB-1 are in flight; the oldest must have landed
     if (!DRAIN && NB <= total) wait_vmcnt<(NB - 1) * NSTAGE>();
     else wait_vmcnt<0>();
     __syncthreads();
   }
   // the current segment has been consumed by this wave: move to the next one
   __device__ __forceinline__ void advance() {
+    if (PSEG > 1 && ++sub < PSEG) return;      // still inside the panel: nothing to wait for
+    sub = 0;
     ++step;
     slot_cur = slot_cur + 1 == NB ? 0 : slot_cur + 1;
-    // segments step .. step+NPRE-1 are in flight (when that many remain): the oldest must have landed
+    // panels step .. step+NPRE-1 are in flight (when that many remain): the oldest must have landed
     if (!DRAIN && step + NPRE <= total) wait_vmcnt<(NPRE - 1) * NSTAGE>();
     else wait_vmcnt<0>();
-    __syncthreads();               // everyone sees segment `step`; everyone is done with `step - 1`
-    issue();                       // into the buffer that held segment step - 1
+    __syncthreads();               // everyone sees panel `step`; everyone is done with `step - 1`
+    issue();                       // into the buffer that held panel step - 1
   }
   template <typename G>
   __device__ __forceinline__ G frag(int f) const {
-    return *reinterpret_cast<const G*>(&lds[slot_cur * SEGV + f * 64 + lane]);
+    return *reinterpret_cast<const G*>(&lds[slot_cur * PANV + sub * SEGV + f * 64 + lane]);
   }
-  __device__ __forceinline__ const uint4* cur() const { return &lds[slot_cur * SEGV]; }
+  __device__ __forceinline__ const uint4* cur() const { return &lds[slot_cur * PANV + sub * SEGV]; }
 };
 
 }  // namespace longer
