@@ -143,3 +143,59 @@ def test_fp32_serving_small():
 def test_c5_bf16_serving():
     _say("C5 bf16 serving (2 users x 24 candidates)")
     _serving(synth.make_case(synth.CONFIGS["C5"], users=2, candidates=24), TOL["bf16"])
+
+
+# --------------------------------------------------------------------------- full benchmark sizes
+# The whole batch runs through the library in the launch configuration bench.py times; the
+# oracle recomputes a sample of users (users are independent) and every sampled row is
+# compared element by element.  All other users are checked for finiteness and for exact
+# zeros in their invalid rows.
+def _full_size_forward(name, sample, pad_value=0.0):
+    from gpu_util import rel_l2_per_user
+    case = synth.make_case(synth.CONFIGS[name], pad_value=pad_value)
+    cfg, w = case["cfg"], case["weights"]
+    r = _runner(case)
+    Y, logits = r.forward()
+    assert np.isfinite(Y).all() and np.isfinite(logits).all()
+    idx = np.array(sample)
+    lens = None if case["lens"] is None else case["lens"][idx]
+    Y_ref, lg_ref = orc.forward(cfg, w, case["H"][idx], case["G"][idx], lens)
+    tol = TOL[cfg.dtype]
+    _check(name + " full batch, sampled users Y", Y[idx], Y_ref, tol)
+    _check(name + " full batch, sampled logits", logits[idx][None, :], lg_ref[None, :], tol)
+    if case["lens"] is not None:
+        Tu = (case["lens"] + cfg.K - 1) // cfg.K
+        for u in np.nonzero(Tu < cfg.k_recent)[0]:
+            assert (Y[u, cfg.m:cfg.m + cfg.k_recent - Tu[u]] == 0).all()
+
+
+def test_c2_full_size_sampled_users():
+    _say("C2 full size (128 users)")
+    _full_size_forward("C2", [0, 37, 127])
+
+
+def test_c3_full_size_sampled_users():
+    _say("C3 full size (256 users x 2000)")
+    _full_size_forward("C3", [0, 101, 255])
+
+
+def test_c4_full_size_sampled_users():
+    _say("C4 full size (512 users, ragged, NaN padding)")
+    case = synth.make_case(synth.CONFIGS["C4"])
+    shortest, longest = int(np.argmin(case["lens"])), int(np.argmax(case["lens"]))
+    _full_size_forward("C4", sorted({0, shortest, longest, 511}), pad_value=float("nan"))
+
+
+def test_c5_full_size_sampled_candidates():
+    _say("C5 full size (16 users x 1000 candidates)")
+    case = synth.make_case(synth.CONFIGS["C5"])
+    cfg, w = case["cfg"], case["weights"]
+    r = _runner(case)
+    Yg, logits = r.serve()
+    assert np.isfinite(Yg).all() and np.isfinite(logits).all()
+    users, cands = [0, 9, 15], [0, 1, 499, 999]
+    cache = orc.kv_cache_build(cfg, w, case["H"][users], None)
+    Yg_ref, lg_ref = orc.score_candidates(cfg, w, cache, case["G_cand"][users][:, cands])
+    got = Yg[users][:, cands]
+    _check("C5 sampled Yg", got.reshape(len(users) * len(cands), -1), Yg_ref.reshape(len(users) * len(cands), -1), TOL["bf16"])
+    _check("C5 sampled logits", logits[users][:, cands], lg_ref, TOL["bf16"])
