@@ -126,6 +126,19 @@ __device__ __forceinline__ f32x16 splat16(float v) {
   return a;
 }
 
+// x += x of the lane that the DPP control CTRL pairs this lane with (within rows of 16 lanes)
+template <int CTRL, int NT>
+__device__ __forceinline__ void lane_sum(f32x16 (&x)[NT]) {
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float v = x[t][r];   // (a bit cast straight from the vector element reads element 0)
+      const int o = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true);
+      x[t][r] = v + __builtin_bit_cast(float, o);
+    }
+}
+
 // bits b in [0,32) set iff base + b lies in [lo, hi)
 __device__ __forceinline__ uint32_t range_bits(int lo, int hi, int base) {
   int a = max(lo - base, 0), b = min(hi - base, 32);
@@ -349,10 +362,11 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
     valid[tt] = false; inrange[tt] = false; usr[tt] = 0; Tu[tt] = 0; out_off[tt] = 0; tilebits[tt] = 0;
     lo1[tt] = hi1[tt] = lo2[tt] = hi2[tt] = kthi[tt] = 0;
     if (MODE == MODE_MERGE) {
-      const long long slot = (long long)tile * 32 + j;
-      const long long gidx = slot / p.K;
-      const int jj = (int)(slot - gidx * p.K);
-      const int u = (int)(gidx / p.T), t = (int)(gidx - (long long)u * p.T);
+      // K divides 32, so it is a power of two; the launcher keeps the slot count below 2^31
+      const uint32_t slot = (uint32_t)tile * 32u + (uint32_t)j;
+      const uint32_t gidx = slot >> __builtin_ctz(p.K);
+      const int jj = (int)(slot & (uint32_t)(p.K - 1));
+      const int u = (int)(gidx / (uint32_t)p.T), t = (int)(gidx - (uint32_t)u * (uint32_t)p.T);
       inrange[tt] = u < p.B;
       int len = 0;
       if (inrange[tt]) { len = p.lens ? p.lens[u] : p.L; len = min(max(len, 0), p.L); }
@@ -430,8 +444,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
       for (int tt = 0; tt < TT; ++tt) {
         if (!inrange[tt]) continue;
         if (p.Z_out) store_rows<T, NT>(resid[tt], p.Z_out, 0, out_off[tt] * D, false, hi);
-        if (p.M_out && (out_off[tt] % p.K) == 0)
-          store_rows<T, NT>(resid[tt], p.M_out, p.M_f32, (out_off[tt] / p.K) * D, false, hi);
+        if (p.M_out && (out_off[tt] & (p.K - 1)) == 0)
+          store_rows<T, NT>(resid[tt], p.M_out, p.M_f32, (out_off[tt] >> __builtin_ctz(p.K)) * D, false, hi);
       }
       return;
     }
@@ -657,20 +671,28 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
       if (p.Z_out && inrange[tt]) store_rows<T, NT>(resid[tt], p.Z_out, 0, out_off[tt] * D, valid[tt], hi);
       if (p.M_out) {
         // mean over the valid tokens of each group: tokens of a group sit on K adjacent lanes
-        const int jj = (int)(out_off[tt] % p.K);
-        const int t = (int)((out_off[tt] / p.K) % p.T);
+        const uint32_t gidx = (uint32_t)out_off[tt] >> __builtin_ctz(p.K);
+        const int jj = (int)((uint32_t)out_off[tt] & (uint32_t)(p.K - 1));
+        const int t = (int)(gidx % (uint32_t)p.T);
         const int nv = min(max(Tu[tt] - t * p.K, 0), p.K);
         const float wgt = valid[tt] ? 1.0f / (float)nv : 0.f;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+        for (int nt = 0; nt < NT; ++nt) resid[tt][nt] *= wgt;
+        // butterfly over the K lanes of a group, one level for all values at a time; the
+        // mirrors serve as the xor-4 / xor-8 exchanges because the partial sums are already
+        // uniform inside each block of 4 / 8 lanes
+        if (p.K >= 2) lane_sum<0xB1, NT>(resid[tt]);     // quad_perm [1,0,3,2]
+        if (p.K >= 4) lane_sum<0x4E, NT>(resid[tt]);     // quad_perm [2,3,0,1]
+        if (p.K >= 8) lane_sum<0x141, NT>(resid[tt]);    // row_half_mirror
+        if (p.K >= 16) lane_sum<0x140, NT>(resid[tt]);   // row_mirror
+        if (p.K >= 32) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float v = resid[tt][nt][r] * wgt;
-            for (int sft = 1; sft < p.K; sft <<= 1) v += __shfl_xor(v, sft, 64);
-            resid[tt][nt][r] = v;
-          }
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) resid[tt][nt][r] += __shfl_xor(resid[tt][nt][r], 16, 64);
+        }
         if (inrange[tt] && jj == 0)
-          store_rows<T, NT>(resid[tt], p.M_out, p.M_f32, (out_off[tt] / p.K) * D, true, hi);
+          store_rows<T, NT>(resid[tt], p.M_out, p.M_f32, (long long)gidx * D, true, hi);
       }
     }
   } else if (MODE == MODE_ATTN || MODE == MODE_SCORE) {

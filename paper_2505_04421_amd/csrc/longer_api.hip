@@ -224,7 +224,7 @@ static Layout make_layout(const longer_config* c, const Shape& s, int B, int L) 
   const int T = cdiv(L, c->K);
   const int nblk = c->inner_layers + 1 + c->n_self;
   size_t o = 0;
-  l.packed = o; o += (size_t)nblk * s.pb;
+  l.packed = o; o += (size_t)nblk * s.pb + 4 * s.seg;   // a stream may read whole panels past its end
   l.head = o; o += align256(((size_t)c->m * s.D + 1) * 4);
   l.M = o; o += align256((size_t)B * T * s.D * 4);
   l.ktmax = cdiv((long long)c->m + T, 32) > cdiv(s.n, 32) ? cdiv((long long)c->m + T, 32) : cdiv(s.n, 32);
@@ -308,6 +308,7 @@ static int run_merge(const longer_config* c, const Shape& s, const char* packed,
   const int tt = 1;
   const int win = c->K <= 8 ? 4 : (c->K <= 16 ? 8 : 16);
   const long long slots = (long long)B * p.T * c->K;
+  if (slots + 32LL * tt * kWaves >= (1LL << 31)) return fail(LONGER_ERR_ARG, "B*ceil(L/K)*K = %lld token slots: at most 2^31 per call", slots);
   const int grid = cdiv(slots, 32LL * tt * kWaves);
   StageScope scope(ST_MERGE, st);
   int rc = s.inner_fn(MODE_MERGE, tt, win, p, dim3(grid), st);
