@@ -182,7 +182,7 @@ __device__ __forceinline__ void layer_norm(const f32x16 (&x)[TT][D / 32], const 
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s += x[tt][t][r]; if (!EXACT) q = fmaf(x[tt][t][r], x[tt][t][r], q); }
-    s += xor32(s);
+    s = sum_halves(s);
     const float mean = s * (1.0f / D);
     float var;
     if (EXACT) {
@@ -191,10 +191,10 @@ __device__ __forceinline__ void layer_norm(const f32x16 (&x)[TT][D / 32], const 
       for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) { float dlt = x[tt][t][r] - mean; v += dlt * dlt; }
-      v += xor32(v);
+      v = sum_halves(v);
       var = v * (1.0f / D);
     } else {
-      q += xor32(q);
+      q = sum_halves(q);
       var = fmaxf(q * (1.0f / D) - mean * mean, 0.f);
     }
     const float rstd = 1.0f / sqrtf(var + eps);
@@ -228,7 +228,7 @@ __device__ __forceinline__ float softmax_step(const f32x16& S, uint32_t ab, floa
     sc[r] = ok ? S[r] * scale_l2e : kNegBig;
     mt = fmaxf(mt, sc[r]);
   }
-  mt = fmaxf(mt, xor32(mt));
+  mt = max_halves(mt);
   const float mnew = fmaxf(m, mt);
   const float alpha = __builtin_amdgcn_exp2f(m - mnew);
   f32x16 pv;
@@ -240,7 +240,7 @@ __device__ __forceinline__ float softmax_step(const f32x16& S, uint32_t ab, floa
     pv[r] = pr;
     lt += pr;
   }
-  lt += xor32(lt);
+  lt = sum_halves(lt);
   l = l * alpha + lt;
   m = mnew;
 #pragma unroll
@@ -283,7 +283,7 @@ __device__ __forceinline__ float softmax_window(const f32x16& S, int widx, const
     x[c] = ok ? x[c] * scale_l2e : kNegBig;
     mt = fmaxf(mt, x[c]);
   }
-  mt = fmaxf(mt, xor32(mt));
+  mt = max_halves(mt);
   const float mnew = fmaxf(m, mt);
   const float alpha = __builtin_amdgcn_exp2f(m - mnew);
   float lt = 0.f;
@@ -293,7 +293,7 @@ __device__ __forceinline__ float softmax_window(const f32x16& S, int widx, const
     x[c] = ok ? __builtin_amdgcn_exp2f(x[c] - mnew) : 0.f;
     lt += x[c];
   }
-  lt += xor32(lt);
+  lt = sum_halves(lt);
   l = l * alpha + lt;
   m = mnew;
   if (sizeof(T) == 2) {
@@ -719,7 +719,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
             for (int r = 0; r < 16; ++r) part += resid[tt][nt][r] * hw[r];
           }
         }
-        part += xor32(part);
+        part = sum_halves(part);
         for (int sft = 1; sft < width; sft <<= 1) part += __shfl_xor(part, sft, 64);
         part += p.head[(size_t)p.m * D];
         if (MODE == MODE_ATTN) {

@@ -82,7 +82,19 @@ __host__ __device__ __forceinline__ constexpr int tile_row(int r, int hi) {
   return 8 * (r / 4) + 4 * hi + (r % 4);
 }
 
-__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+// Lane l and lane l ^ 32 hold the two feature halves of one token.  Their values are
+// combined with the cross-half register swap (v_permlane32_swap: the upper 32 lanes of one
+// operand trade places with the lower 32 lanes of the other), no LDS round trip: with both
+// operands = v, one result is v's lower half in every lane, the other v's upper half.
+__device__ __forceinline__ void both_halves(float v, float& lo, float& up) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  const unsigned b = __builtin_bit_cast(unsigned, v);
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+  const unsigned r0 = r[0], r1 = r[1];
+  lo = __builtin_bit_cast(float, r0); up = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ float sum_halves(float v) { float a, b; both_halves(v, a, b); return a + b; }
+__device__ __forceinline__ float max_halves(float v) { float a, b; both_halves(v, a, b); return fmaxf(a, b); }
 
 // ------------------------------------------------------------------------------------
 // Packed parameters of one block (written by the pack kernel, read by the block kernels)
