@@ -560,17 +560,42 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
             }
             if (!valid[tt]) rhi = rlo;
           }
+          // scoring (long key sequences, one candidate tile per wave): the fragments of key
+          // tile kt + 1 are requested before tile kt is worked on
+          constexpr bool AHEAD = MODE == MODE_SCORE;
+          grp knx[GPT], vnx[GPT];
+          if (AHEAD && nkt > 0) {
+            const size_t fo = ((size_t)ft * GPT) * 1024 + lane * 16;
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) {
+              knx[g] = *reinterpret_cast<const grp*>(kb + fo + g * 1024);
+              vnx[g] = *reinterpret_cast<const grp*>(vb + fo + g * 1024);
+            }
+          }
           for (int kt = 0; kt < nkt; ++kt) {
             uint32_t bits;
             if (MODE == MODE_ATTN) bits = range_bits(lo1[tt], hi1[tt], 32 * kt) | range_bits(lo2[tt], hi2[tt], 32 * kt);
             else bits = range_bits(rlo, rhi, 32 * kt);
             const uint32_t ab = bits >> (4 * hi);
-            const size_t fo = ((size_t)(kt * NT + ft) * GPT) * 1024 + lane * 16;
             grp kfr[GPT], vfr[GPT];
+            if (AHEAD) {
 #pragma unroll
-            for (int g = 0; g < GPT; ++g) {
-              kfr[g] = *reinterpret_cast<const grp*>(kb + fo + g * 1024);
-              vfr[g] = *reinterpret_cast<const grp*>(vb + fo + g * 1024);
+              for (int g = 0; g < GPT; ++g) { kfr[g] = knx[g]; vfr[g] = vnx[g]; }
+            } else {
+              const size_t fo = ((size_t)(kt * NT + ft) * GPT) * 1024 + lane * 16;
+#pragma unroll
+              for (int g = 0; g < GPT; ++g) {
+                kfr[g] = *reinterpret_cast<const grp*>(kb + fo + g * 1024);
+                vfr[g] = *reinterpret_cast<const grp*>(vb + fo + g * 1024);
+              }
+            }
+            if (AHEAD && kt + 1 < nkt) {
+              const size_t fo = ((size_t)((kt + 1) * NT + ft) * GPT) * 1024 + lane * 16;
+#pragma unroll
+              for (int g = 0; g < GPT; ++g) {
+                knx[g] = *reinterpret_cast<const grp*>(kb + fo + g * 1024);
+                vnx[g] = *reinterpret_cast<const grp*>(vb + fo + g * 1024);
+              }
             }
 #pragma unroll
             for (int hh = 0; hh < HPT; ++hh) {
