@@ -8,6 +8,11 @@
 //   MODE_ATTN    query side of the cross-causal layer (Eq. 5-8) or of a self-causal
 //                layer (Eq. 9): Q projection, masked online-softmax attention over the
 //                stored K/V fragments, output projection, FFN;
+//   MODE_STACK   the whole reduced stack of one user in one workgroup (Eq. 10): the query side
+//                of the cross-causal layer as in MODE_ATTN, then every self-causal layer
+//                with its K/V projected in place and handed between the workgroup's waves
+//                through LDS - no launch and no global round trip between the layers
+//                (needs m + k <= 128 rows);
 //   MODE_SCORE   candidate scoring of the KV-cache serving path (Section 3.6.3): the m
 //                global tokens of each candidate through all 1 + N layers, attending to
 //                their own globals (inside the tile) and the cached sequence K/V.
@@ -324,7 +329,7 @@ __device__ __forceinline__ float softmax_window(const f32x16& S, int widx, const
 
 // ---------------------------------------------------------------------------- the kernel
 template <typename T, int D, int DH, int TT, int MODE, int W>
-__global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block_kernel(const BlockParams p) {
+__global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE_STACK) ? 2 : 1) block_kernel(const BlockParams p) {
   using E = ET<T>;
   using grp = typename E::grp;
   constexpr int NT = D / 32, NG = D / E::GF, GPT = E::GPT;
@@ -333,12 +338,16 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
   constexpr int GPH = DH / E::GF;     // operand groups per head
   constexpr bool FUSED = (MODE == MODE_MERGE || MODE == MODE_SCORE);
   constexpr bool EXT = (MODE == MODE_ATTN || MODE == MODE_SCORE);
+  constexpr bool STACK = MODE == MODE_STACK;
+  constexpr bool ATTNLIKE = MODE == MODE_ATTN || STACK;   // rows are [globals; recent slots] of a user
   constexpr bool BIGSEG = SEGV * 16 >= 16384;
   constexpr int PSEG = BIGSEG ? 1 : 2;              // segments per panel of the weight stream (one barrier per panel)
   constexpr int NB = BIGSEG ? 6 : 4;                // ring depth in panels
   static_assert(DH == 16 || DH == 32, "head width");
   __shared__ uint4 lds[NB * PSEG * SEGV];
   __shared__ uint4 vecl[SEGV];          // the current block's fp32 vectors
+  // MODE_STACK: K and V fragments of the current feature tile, [parity of ft][wave = key tile][K, V][group][lane]
+  __shared__ uint4 kvl[STACK ? 2 * kWaves * 2 * GPT * 64 : 1];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j = lane & 31, hi = lane >> 5;
   const int NC = p.FF / 32;
@@ -354,6 +363,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
 #pragma unroll
   for (int w = 0; w < 16 / W; ++w) { wmask[w] = widx == w ? 0xffffffffu : 0u; asm("" : "+v"(wmask[w])); }
   int lo1[TT], hi1[TT], lo2[TT], hi2[TT], kthi[TT];   // EXT: visible key ranges, key tile count
+  int slo1[TT], shi1[TT], slo2[TT], shi2[TT];         // MODE_STACK: the same for the self-causal layers
   f32x16 resid[TT][NT];
 
 #pragma unroll
@@ -361,6 +371,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
     const int tile = (blockIdx.x * kWaves + wave) * TT + tt;
     valid[tt] = false; inrange[tt] = false; usr[tt] = 0; Tu[tt] = 0; out_off[tt] = 0; tilebits[tt] = 0;
     lo1[tt] = hi1[tt] = lo2[tt] = hi2[tt] = kthi[tt] = 0;
+    slo1[tt] = shi1[tt] = slo2[tt] = shi2[tt] = 0;
     if (MODE == MODE_MERGE) {
       // K divides 32, so it is a power of two; the launcher keeps the slot count below 2^31
       const uint32_t slot = (uint32_t)tile * 32u + (uint32_t)j;
@@ -389,7 +400,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
       const int sf = first ? p.src0.f32 : p.src1.f32;
       const long long su = first ? p.src0.ustride : p.src1.ustride;
       load_rows<T, NT>(resid[tt], sp, sf, su * u + (long long)(first ? c : c - p.m0) * D, valid[tt], hi);
-    } else if (MODE == MODE_ATTN) {
+    } else if (ATTNLIKE) {
       const int u = tile / p.tiles_per_user, qt = tile - u * p.tiles_per_user;
       const int a = p.q0 + 32 * qt + j;
       inrange[tt] = u < p.B && (32 * qt + j) < p.rows_per_user;
@@ -418,6 +429,10 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
       if (!valid[tt]) { hi1[tt] = lo1[tt]; hi2[tt] = lo2[tt]; }
       kthi[tt] = (p.KG + (p.key_self ? p.k : tu) + 31) / 32;
       if (u >= p.B) kthi[tt] = 0;
+      if (STACK && valid[tt]) {   // keys of a self-causal layer: the user's own rows, key index = row index
+        if (glob) { slo1[tt] = p.gmask_causal ? a : 0; shi1[tt] = p.m; slo2[tt] = p.m + i0; shi2[tt] = p.m + p.k; }
+        else { slo2[tt] = p.m + i0; shi2[tt] = p.m + i + 1; }
+      }
     } else {  // MODE_SCORE
       const int u = blockIdx.y;
       const int a = 32 * tile + j;
@@ -452,8 +467,10 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
   }
 
   WStream<SEGV, PSEG, NB, MODE == MODE_KVPROJ> ws;
-  const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : (MODE == MODE_ATTN ? 2 * NT + 2 * NC : 4 * NT + 2 * NC));
-  ws.init(lds, p.wbase, steps * p.n_layers);
+  const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : (ATTNLIKE ? 2 * NT + 2 * NC : 4 * NT + 2 * NC));
+  // MODE_STACK: the cross block's attention sub-stream, then the self blocks in the fused
+  // layout, each followed by the unused segment that fills its slot in the packed buffer
+  ws.init(lds, p.wbase, STACK ? steps + (p.n_layers - 1) * (2 + 4 * NT + 2 * NC) : steps * p.n_layers);
 
   for (int layer = 0; layer < p.n_layers; ++layer) {
     // the block's first segment holds its fp32 vectors: keep a copy for the whole layer
@@ -468,6 +485,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
     grp xn[TT][NG];
     layer_norm<T, D, TT>(resid, vec + vl.ln1_g(), vec + vl.ln1_b(), p.eps, hi, xn);
     grp oop[TT][NG];
+    const bool selfl = STACK && layer > 0;   // a self-causal layer of the stack: K/V made here
 
 #pragma unroll
     for (int ft = 0; ft < NT; ++ft) {
@@ -483,7 +501,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
         }
         ws.advance();
       }
-      if (FUSED || MODE == MODE_KVPROJ) {
+      if (FUSED || MODE == MODE_KVPROJ || selfl) {
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) ak[tt] = bias_tile(vec + vl.bk(), ft, hi);
 #pragma unroll
@@ -503,6 +521,19 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
           for (int tt = 0; tt < TT; ++tt) av[tt] = E::mma(xn[tt][s], w, av[tt]);   // operands swapped: lane = feature
         }
         ws.advance();
+      }
+      if (selfl) {
+        // this wave's rows are key tile `wave`: hand its K and V fragments to the other waves.
+        // One barrier per feature tile is enough with two buffers: nobody can be two tiles
+        // ahead of a wave that still reads.
+        static_assert(!STACK || TT == 1, "one tile per wave in the stack kernel");
+        uint4* dstk = kvl + (size_t)(((ft & 1) * kWaves + wave) * 2) * GPT * 64 + lane;
+#pragma unroll
+        for (int g = 0; g < GPT; ++g) {
+          *reinterpret_cast<grp*>(dstk + g * 64) = E::pack(ak[0], g);
+          *reinterpret_cast<grp*>(dstk + (GPT + g) * 64) = E::pack(av[0], g);
+        }
+        __syncthreads();
       }
       if (MODE == MODE_KVPROJ) {
 #pragma unroll
@@ -543,9 +574,35 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
             for (int g = 0; g < GPT; ++g) acc[hh] = E::mma(vop[g], pop[g], acc[hh]);
           }
         }
-        if (EXT) {     // stored K/V fragments (all waves of a tile's user read the same ones)
+        if (selfl) {   // K/V fragments of the user's own rows, from LDS
+          const int nkt = (p.m + p.k + 31) / 32;
+          for (int kt = 0; kt < nkt; ++kt) {
+            const uint32_t bits = range_bits(slo1[tt], shi1[tt], 32 * kt) | range_bits(slo2[tt], shi2[tt], 32 * kt);
+            const uint32_t ab = bits >> (4 * hi);
+            const uint4* srck = kvl + (size_t)(((ft & 1) * kWaves + kt) * 2) * GPT * 64 + lane;
+            grp kfr[GPT], vfr[GPT];
+#pragma unroll
+            for (int g = 0; g < GPT; ++g) {
+              kfr[g] = *reinterpret_cast<const grp*>(srck + g * 64);
+              vfr[g] = *reinterpret_cast<const grp*>(srck + (GPT + g) * 64);
+            }
+#pragma unroll
+            for (int hh = 0; hh < HPT; ++hh) {
+              f32x16 S = splat16(0.f);
+#pragma unroll
+              for (int g2 = 0; g2 < GPH; ++g2) S = E::mma(kfr[hh * GPH + g2], qop[hh * GPH + g2], S);
+              grp pop[GPT];
+              const float alpha = softmax_step<T>(S, ab, p.scale_l2e, mrun[hh], lrun[hh], pop);
+#pragma unroll
+              for (int r = 0; r < 16; ++r) acc[hh][r] *= alpha;
+#pragma unroll
+              for (int g = 0; g < GPT; ++g) acc[hh] = E::mma(vfr[g], pop[g], acc[hh]);
+            }
+          }
+        }
+        if (EXT || (STACK && !selfl)) {     // stored K/V fragments (all waves of a tile's user read the same ones)
           const char* kb; const char* vb; int nkt, rlo, rhi;
-          if (MODE == MODE_ATTN) {
+          if (ATTNLIKE) {
             kb = p.kst + (size_t)usr[tt] * p.kv_ustride; vb = p.vst + (size_t)usr[tt] * p.kv_ustride;
             nkt = kthi[tt]; rlo = 0; rhi = 0;
           } else {
@@ -574,7 +631,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
           }
           for (int kt = 0; kt < nkt; ++kt) {
             uint32_t bits;
-            if (MODE == MODE_ATTN) bits = range_bits(lo1[tt], hi1[tt], 32 * kt) | range_bits(lo2[tt], hi2[tt], 32 * kt);
+            if (ATTNLIKE) bits = range_bits(lo1[tt], hi1[tt], 32 * kt) | range_bits(lo2[tt], hi2[tt], 32 * kt);
             else bits = range_bits(rlo, rhi, 32 * kt);
             const uint32_t ab = bits >> (4 * hi);
             grp kfr[GPT], vfr[GPT];
@@ -686,6 +743,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
       }
       ws.advance();
     }
+    if (selfl) ws.advance();   // the unused segment behind a fused block in the packed buffer
   }
 
   wait_vmcnt<0>();   // nothing of the weight stream may still be in flight when the wave ends
@@ -720,7 +778,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
           store_rows<T, NT>(resid[tt], p.M_out, p.M_f32, (long long)gidx * D, true, hi);
       }
     }
-  } else if (MODE == MODE_ATTN || MODE == MODE_SCORE) {
+  } else if (ATTNLIKE || MODE == MODE_SCORE) {
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       if (p.X_out && inrange[tt]) store_rows<T, NT>(resid[tt], p.X_out, p.X_f32, out_off[tt], valid[tt], hi);
@@ -729,7 +787,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
         const int tile = (blockIdx.x * kWaves + wave) * TT + tt;
         int a, width;       // row inside the head's m rows; lanes per logit
         bool take;
-        if (MODE == MODE_ATTN) {
+        if (ATTNLIKE) {
           const int qt = tile % p.tiles_per_user;
           a = p.q0 + 32 * qt + j; take = valid[tt] && a < p.m; width = 32;
         } else {
@@ -747,7 +805,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1) ? 2 : 1) block
         part = sum_halves(part);
         for (int sft = 1; sft < width; sft <<= 1) part += __shfl_xor(part, sft, 64);
         part += p.head[(size_t)p.m * D];
-        if (MODE == MODE_ATTN) {
+        if (ATTNLIKE) {
           if (lane == 0 && usr[tt] < p.B && (tile % p.tiles_per_user) == 0 && p.q0 == 0) p.logits[usr[tt]] = part;
         } else {
           const int cand = (32 * tile + j) / p.m;
@@ -778,6 +836,7 @@ int launch_block(int mode, int tt, int win, const BlockParams& p, dim3 grid, hip
         break;                                                                                        \
       case MODE_KVPROJ: LONGER_LAUNCH(T, D, DH, 1, MODE_KVPROJ, 16); break;                           \
       case MODE_ATTN: LONGER_LAUNCH(T, D, DH, 1, MODE_ATTN, 16); break;                               \
+      case MODE_STACK: LONGER_LAUNCH(T, D, DH, 1, MODE_STACK, 16); break;                             \
       case MODE_SCORE:                                                                                \
         if (win == 4) LONGER_LAUNCH(T, D, DH, 1, MODE_SCORE, 4);                                      \
         else if (win == 8) LONGER_LAUNCH(T, D, DH, 1, MODE_SCORE, 8);                                 \

@@ -354,6 +354,27 @@ static int run_layer(const longer_config* c, const Shape& s, const char* packed_
   return 0;
 }
 
+// The reduced stack of every user in one launch (one workgroup per user): the query side of
+// the cross layer over the K/V fragments that run_layer(.., do_attn = false) stored, then
+// all self layers.  `packed_cross` holds the cross block in the split layout, followed at
+// packed_block_bytes steps by the self blocks in the fused layout.  Needs m + k <= 128.
+static int run_stack(const longer_config* c, const Shape& s, const char* packed_cross, const int32_t* lens, int B, int L,
+                     const AttnIO& io, hipStream_t st) {
+  BlockParams p = base_params(c, s, lens, B, L, s.DH);
+  p.wbase = packed_cross + (size_t)kv_segs(s.D) * s.seg;
+  p.n_layers = 1 + c->n_self;
+  p.src0 = io.q0src; p.src1 = io.q1src;
+  p.rows_per_user = s.n; p.tiles_per_user = kWaves;
+  p.gather_recent = io.gather_recent; p.q0 = 0;
+  p.kst = io.kst; p.vst = io.vst; p.kv_ustride = io.kv_ustride;
+  p.KG = io.KG; p.key_self = 0;
+  p.X_out = io.X_out; p.X_f32 = io.X_f32; p.X_ustride = io.X_ustride;
+  p.logits = io.logits; p.head = io.head;
+  StageScope scope(ST_ATTN, st);
+  if (s.main_fn(MODE_STACK, 1, 16, p, dim3(B), st)) return fail(LONGER_ERR_HIP, "stack launch failed");
+  return 0;
+}
+
 }  // namespace longer
 
 using namespace longer;
@@ -488,11 +509,18 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
   if ((rc = pack_blocks(cfg, s, w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(s.D, s.FF) * s.seg, st))) return rc;
   char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
   if ((rc = pack_blocks(cfg, s, w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb, st))) return rc;
-  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, LAYOUT_SPLIT, pk_cross + s.pb, s.pb, st))) return rc;
+  const bool one_launch = s.n <= 32 * kWaves;   // a user's reduced rows fit one workgroup
+  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, one_launch ? LAYOUT_FUSED : LAYOUT_SPLIT, pk_cross + s.pb, s.pb, st))) return rc;
   float* head = (float*)(w8 + l.head);
   if (logits_out && (rc = pack_head(cfg, s, w, head, st))) return rc;
 
   if ((rc = run_merge(cfg, s, pk, H, lens, B, L, w8 + l.M, 1, nullptr, st))) return rc;
+  if (one_launch) {
+    AttnIO io = cross_io(cfg, s, l, w8, G, w8 + l.M, 1, B, L, Y_out, 0);
+    if (logits_out) { io.logits = logits_out; io.head = head; }
+    if ((rc = run_layer(cfg, s, pk_cross, lens, B, L, io, false, st))) return rc;
+    return run_stack(cfg, s, pk_cross, lens, B, L, io, st);
+  }
   void* xbuf[2] = {w8 + l.xa, w8 + l.xb};
   const bool last0 = cfg->n_self == 0;
   AttnIO io = cross_io(cfg, s, l, w8, G, w8 + l.M, 1, B, L, last0 ? Y_out : xbuf[0], last0 ? 0 : 1);
