@@ -218,51 +218,63 @@ __device__ __forceinline__ void layer_norm(const f32x16 (&x)[TT][D / 32], const 
   }
 }
 
-// One online-softmax step over a 32-key tile.  S holds, for this lane's query, the raw
-// scores of keys tile_row(r, hi); `ab` has bit (8 (r/4) + r%4) set iff that key is visible.
-// Updates the running max / sum, returns the rescale factor for the accumulators and the
-// probabilities as B-operand groups.
-template <typename T>
-__device__ __forceinline__ float softmax_step(const f32x16& S, uint32_t ab, float scale_l2e, float& m, float& l,
-                                              typename ET<T>::grp (&pop)[ET<T>::GPT]) {
+// bits of a tile's visibility word that correspond to accumulator registers
+constexpr uint32_t kTileBits = 0x0F0F0F0Fu;
+
+// Visibility of a 32-key tile as an additive score tile: 0 for a visible key, -infinity for a
+// hidden one (bit 8 (r/4) + r%4 of `ab` belongs to accumulator register r).  The score MFMA
+// starts from it, so masking costs nothing per head.
+__device__ __forceinline__ f32x16 mask_tile(uint32_t ab) {
+  f32x16 b;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) b[r] = ((ab >> (8 * (r / 4) + (r % 4))) & 1u) ? 0.f : -__builtin_inff();
+  return b;
+}
+
+// One online-softmax step over a 32-key tile.  S holds, for this lane's query, the scores of
+// keys tile_row(r, hi), already in units of log2(e) / sqrt(head width) (the factor rides on
+// Q); with MASKED, `ab` has bit (8 (r/4) + r%4) set iff that key is visible, and a hidden
+// key gets the score -infinity (below the running maximum's start value, so its probability
+// is an exact zero without a second test).  Updates the running maximum m and sum l,
+// rescales the accumulator and writes the probabilities as B-operand groups.
+template <typename T, bool MASKED>
+__device__ __forceinline__ void softmax_step(const f32x16& S, uint32_t ab, float& m, float& l, f32x16& acc,
+                                             typename ET<T>::grp (&pop)[ET<T>::GPT]) {
   float sc[16];
   float mt = kNegBig;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const bool ok = (ab >> (8 * (r / 4) + (r % 4))) & 1u;
-    sc[r] = ok ? S[r] * scale_l2e : kNegBig;
+    const bool ok = !MASKED || ((ab >> (8 * (r / 4) + (r % 4))) & 1u);
+    sc[r] = ok ? S[r] : -__builtin_inff();
     mt = fmaxf(mt, sc[r]);
   }
   mt = max_halves(mt);
   const float mnew = fmaxf(m, mt);
   const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+  m = mnew;
+  acc *= alpha;
   f32x16 pv;
   float lt = 0.f;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const bool ok = (ab >> (8 * (r / 4) + (r % 4))) & 1u;
-    const float pr = ok ? __builtin_amdgcn_exp2f(sc[r] - mnew) : 0.f;
-    pv[r] = pr;
-    lt += pr;
+    pv[r] = __builtin_amdgcn_exp2f(sc[r] - mnew);
+    lt += pv[r];
   }
-  lt = sum_halves(lt);
-  l = l * alpha + lt;
-  m = mnew;
+  l = fmaf(l, alpha, sum_halves(lt));
 #pragma unroll
   for (int g = 0; g < ET<T>::GPT; ++g) pop[g] = ET<T>::pack(pv, g);
-  return alpha;
 }
 
 // Softmax over the keys of the lane's own tile when only a window of W accumulator
 // registers can be visible (groups of at most 2 W adjacent tokens: register window
 // [W widx, W widx + W) with widx = (lane % 32) / (2 W)).  `wb` holds the visibility bits of
-// the window (bit 8 (c/4) + c%4 for window register c).  Same contract as softmax_step;
-// with W = 16 it is softmax_step.
+// the window (bit 8 (c/4) + c%4 for window register c).  It is the first step of a query's
+// softmax (m, l, acc at their start values); with W = 16 it is softmax_step.
 template <typename T, int W>
-__device__ __forceinline__ float softmax_window(const f32x16& S, int widx, const uint32_t (&wmask)[16 / W], uint32_t wb,
-                                                float scale_l2e, float& m, float& l,
-                                                typename ET<T>::grp (&pop)[ET<T>::GPT]) {
-  if (W == 16) return softmax_step<T>(S, wb, scale_l2e, m, l, pop);
+__device__ __forceinline__ void softmax_window(const f32x16& S, int widx, const uint32_t (&wmask)[16 / W], uint32_t wb,
+                                               float& m, float& l, f32x16& acc,
+                                               typename ET<T>::grp (&pop)[ET<T>::GPT]) {
+  if (W == 16) { softmax_step<T, true>(S, wb, m, l, acc, pop); return; }
   float x[W];
   const bool b0 = widx & 1, b1 = widx & 2;
   // each score goes through an opaque register copy so that the choice below stays a
@@ -285,7 +297,7 @@ __device__ __forceinline__ float softmax_window(const f32x16& S, int widx, const
 #pragma unroll
   for (int c = 0; c < W; ++c) {
     const bool ok = (wb >> (8 * (c / 4) + (c % 4))) & 1u;
-    x[c] = ok ? x[c] * scale_l2e : kNegBig;
+    x[c] = ok ? x[c] : -__builtin_inff();
     mt = fmaxf(mt, x[c]);
   }
   mt = max_halves(mt);
@@ -294,8 +306,7 @@ __device__ __forceinline__ float softmax_window(const f32x16& S, int widx, const
   float lt = 0.f;
 #pragma unroll
   for (int c = 0; c < W; ++c) {
-    const bool ok = (wb >> (8 * (c / 4) + (c % 4))) & 1u;
-    x[c] = ok ? __builtin_amdgcn_exp2f(x[c] - mnew) : 0.f;
+    x[c] = __builtin_amdgcn_exp2f(x[c] - mnew);
     lt += x[c];
   }
   lt = sum_halves(lt);
@@ -324,7 +335,6 @@ __device__ __forceinline__ float softmax_window(const f32x16& S, int widx, const
 #pragma unroll
     for (int g = 0; g < ET<T>::GPT; ++g) pop[g] = ET<T>::pack(pv, g);
   }
-  return alpha;
 }
 
 // ---------------------------------------------------------------------------- the kernel
@@ -551,7 +561,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) {
-        grp qop[GPT];
+        grp qop[GPT];   // Q carries log2(e) / sqrt(head width): the scores come out ready for exp2
+        aq[tt] *= p.scale_l2e;
 #pragma unroll
         for (int g = 0; g < GPT; ++g) qop[g] = E::pack(aq[tt], g);
         float mrun[HPT], lrun[HPT];
@@ -569,7 +580,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 #pragma unroll
             for (int g2 = 0; g2 < GPH; ++g2) S = E::mma(kop[hh * GPH + g2], qop[hh * GPH + g2], S);
             grp pop[GPT];
-            softmax_window<T, W>(S, widx, wmask, tilebits[tt], p.scale_l2e, mrun[hh], lrun[hh], pop);
+            softmax_window<T, W>(S, widx, wmask, tilebits[tt], mrun[hh], lrun[hh], acc[hh], pop);
 #pragma unroll
             for (int g = 0; g < GPT; ++g) acc[hh] = E::mma(vop[g], pop[g], acc[hh]);
           }
@@ -578,7 +589,10 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
           const int nkt = (p.m + p.k + 31) / 32;
           for (int kt = 0; kt < nkt; ++kt) {
             const uint32_t bits = range_bits(slo1[tt], shi1[tt], 32 * kt) | range_bits(slo2[tt], shi2[tt], 32 * kt);
-            const uint32_t ab = bits >> (4 * hi);
+            const uint32_t ab = (bits >> (4 * hi)) & kTileBits;
+            if (__builtin_amdgcn_ballot_w64(ab != 0) == 0) continue;      // no query of the tile sees any of these keys
+            const bool full = __builtin_amdgcn_ballot_w64(ab != kTileBits) == 0;   // every query sees all of them
+            const f32x16 vis = full ? splat16(0.f) : mask_tile(ab);
             const uint4* srck = kvl + (size_t)(((ft & 1) * kWaves + kt) * 2) * GPT * 64 + lane;
             grp kfr[GPT], vfr[GPT];
 #pragma unroll
@@ -588,13 +602,11 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
             }
 #pragma unroll
             for (int hh = 0; hh < HPT; ++hh) {
-              f32x16 S = splat16(0.f);
+              f32x16 S = vis;
 #pragma unroll
               for (int g2 = 0; g2 < GPH; ++g2) S = E::mma(kfr[hh * GPH + g2], qop[hh * GPH + g2], S);
               grp pop[GPT];
-              const float alpha = softmax_step<T>(S, ab, p.scale_l2e, mrun[hh], lrun[hh], pop);
-#pragma unroll
-              for (int r = 0; r < 16; ++r) acc[hh][r] *= alpha;
+              softmax_step<T, false>(S, 0u, mrun[hh], lrun[hh], acc[hh], pop);
 #pragma unroll
               for (int g = 0; g < GPT; ++g) acc[hh] = E::mma(vfr[g], pop[g], acc[hh]);
             }
@@ -633,7 +645,10 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
             uint32_t bits;
             if (ATTNLIKE) bits = range_bits(lo1[tt], hi1[tt], 32 * kt) | range_bits(lo2[tt], hi2[tt], 32 * kt);
             else bits = range_bits(rlo, rhi, 32 * kt);
-            const uint32_t ab = bits >> (4 * hi);
+            const uint32_t ab = (bits >> (4 * hi)) & kTileBits;
+            const bool none = __builtin_amdgcn_ballot_w64(ab != 0) == 0;           // nobody sees any of these keys
+            const bool full = __builtin_amdgcn_ballot_w64(ab != kTileBits) == 0;   // everybody sees all of them
+            if (!AHEAD && none) continue;
             grp kfr[GPT], vfr[GPT];
             if (AHEAD) {
 #pragma unroll
@@ -654,15 +669,15 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
                 vnx[g] = *reinterpret_cast<const grp*>(vb + fo + g * 1024);
               }
             }
+            if (AHEAD && none) continue;
+            const f32x16 vis = full ? splat16(0.f) : mask_tile(ab);
 #pragma unroll
             for (int hh = 0; hh < HPT; ++hh) {
-              f32x16 S = splat16(0.f);
+              f32x16 S = vis;
 #pragma unroll
               for (int g2 = 0; g2 < GPH; ++g2) S = E::mma(kfr[hh * GPH + g2], qop[hh * GPH + g2], S);
               grp pop[GPT];
-              const float alpha = softmax_step<T>(S, ab, p.scale_l2e, mrun[hh], lrun[hh], pop);
-#pragma unroll
-              for (int r = 0; r < 16; ++r) acc[hh][r] *= alpha;
+              softmax_step<T, false>(S, 0u, mrun[hh], lrun[hh], acc[hh], pop);
 #pragma unroll
               for (int g = 0; g < GPT; ++g) acc[hh] = E::mma(vfr[g], pop[g], acc[hh]);
             }
