@@ -13,8 +13,11 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblonger.so")
 
 # packed fp32 VALU ops are switched off on purpose ("build flags")
+# MFMA accumulators stay in the architectural VGPRs: kernels that may use more than 256
+# registers otherwise shuttle tiles between the two register classes around every VALU use
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wno-unused-command-line-argument"]
 
 
