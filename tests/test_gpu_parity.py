@@ -95,6 +95,29 @@ def test_fp32_d64():
     _entry_points(synth.make_case(cfg), TOL["f32"])
 
 
+@pytest.mark.parametrize("k_recent,gmask", [(124, "full"), (150, "causal")])
+def test_bf16_wide_query_sets(k_recent, gmask):
+    """m + k = 128 fills the one-workgroup-per-user stack kernel exactly; m + k = 154 does not
+    fit it, so longer_forward runs one K/V-projection + attention launch pair per layer.
+    Ragged lengths, some users with fewer merged tokens than query slots."""
+    cfg = synth.CONFIGS["C2"].replace(B=6, L=1400, K=8, m=4, k_recent=k_recent, n_self=2, gmask=gmask,
+                                      ragged=True, len_lo=40, len_hi=1400, index=13)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"][0] = 1400
+    case["lens"][1] = 300          # 38 merged tokens < k
+    case["H"][0] = synth.round_bf16(np.random.default_rng(7).standard_normal(case["H"][0].shape).astype(np.float32))
+    case["H"][1, 300:] = np.nan
+    _say("bf16 d=64, m + k = %d, gmask=%s" % (cfg.m + k_recent, gmask))
+    _entry_points(case, TOL["bf16"], with_inner=False)
+
+
+def test_fp32_single_user_single_group():
+    """B = 1 and L < K: one (ragged) group, one merged token, every query slot but one invalid."""
+    cfg = synth.CONFIGS["C1"].replace(B=1, L=3, K=4, index=14)
+    _say("fp32 B=1, L=3 < K=4")
+    _entry_points(synth.make_case(cfg), TOL["f32"])
+
+
 def test_c2_bf16_all_entry_points():
     _say("C2 bf16 (16 users)")
     _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
