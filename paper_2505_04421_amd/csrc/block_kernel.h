@@ -58,6 +58,7 @@ struct BlockParams {
   void* X_out; int X_f32; long long X_ustride;
   float* logits; const float* head;   // head: fp32 [m*D] weights then the bias
   // MODE_SCORE
+  int xcds, wg_per_user;   // workgroup index -> (user, group of tiles), see the kernel
   const void* Gc; int C;
   const char* cache;    // layer 0 K then V, then layers 1..N
   size_t c0_ustride, c0_voff, c1_off, c1_lstride, c1_ustride, c1_voff;
@@ -376,9 +377,21 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   int slo1[TT], shi1[TT], slo2[TT], shi2[TT];         // MODE_STACK: the same for the self-causal layers
   f32x16 resid[TT][NT];
 
+  // Which group of 4 x TT tiles this workgroup takes.  Scoring: workgroups are dealt to the
+  // chip's XCDs (each with its own L2) round-robin by their index, so the index is decoded
+  // such that all candidate tiles of a user run on one XCD and its L2 holds that user's
+  // cached K/V.
+  int wg = blockIdx.x, su = 0;
+  if (MODE == MODE_SCORE) {
+    const int x = (int)blockIdx.x % p.xcds, sq = (int)blockIdx.x / p.xcds;
+    su = x + p.xcds * (sq / p.wg_per_user);
+    wg = sq % p.wg_per_user;
+    if (su >= p.B) return;     // the grid is rounded up to whole XCD rows
+  }
+
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
-    const int tile = (blockIdx.x * kWaves + wave) * TT + tt;
+    const int tile = (wg * kWaves + wave) * TT + tt;
     valid[tt] = false; inrange[tt] = false; usr[tt] = 0; Tu[tt] = 0; out_off[tt] = 0; tilebits[tt] = 0;
     lo1[tt] = hi1[tt] = lo2[tt] = hi2[tt] = kthi[tt] = 0;
     slo1[tt] = shi1[tt] = slo2[tt] = shi2[tt] = 0;
@@ -444,7 +457,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
         else { slo2[tt] = p.m + i0; shi2[tt] = p.m + i + 1; }
       }
     } else {  // MODE_SCORE
-      const int u = blockIdx.y;
+      const int u = su;
       const int a = 32 * tile + j;
       const int cand = a / p.m, gi = a - cand * p.m;
       inrange[tt] = cand < p.C;
@@ -799,7 +812,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       if (p.X_out && inrange[tt]) store_rows<T, NT>(resid[tt], p.X_out, p.X_f32, out_off[tt], valid[tt], hi);
       if (p.logits) {
         // logit = <head_w, flatten(global rows)> + head_b
-        const int tile = (blockIdx.x * kWaves + wave) * TT + tt;
+        const int tile = (wg * kWaves + wave) * TT + tt;
         int a, width;       // row inside the head's m rows; lanes per logit
         bool take;
         if (ATTNLIKE) {

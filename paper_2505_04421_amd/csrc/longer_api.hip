@@ -212,6 +212,10 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
 
 static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 
+// MI355X: 8 accelerator dies (XCDs) of 32 compute units, each with its own L2; workgroups of a
+// launch are dealt to them round-robin
+constexpr int kXcds = 8;
+
 // workspace layout shared by all entry points
 struct Layout {
   size_t packed, head, M, kst, vst, xa, xb, total;
@@ -617,7 +621,8 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
   p.X_out = Yg_out; p.X_f32 = 0;
   p.logits = logits_out; p.head = head;
   const int tiles = cdiv((long long)C * cfg->m, 32);
-  dim3 grid(cdiv(tiles, kWaves), U);
+  p.xcds = kXcds; p.wg_per_user = cdiv(tiles, kWaves);
+  dim3 grid((unsigned)(kXcds * cdiv(U, kXcds) * p.wg_per_user));
   StageScope scope(ST_SCORE, st);
   const int win = cfg->m <= 8 ? 4 : (cfg->m <= 16 ? 8 : 16);
   if (s.main_fn(MODE_SCORE, 1, win, p, grid, st)) return fail(LONGER_ERR_HIP, "score kernel launch failed");
