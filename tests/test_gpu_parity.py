@@ -118,6 +118,37 @@ def test_fp32_single_user_single_group():
     _entry_points(synth.make_case(cfg), TOL["f32"])
 
 
+@pytest.mark.parametrize("base,users", [("C1", None), ("C2", 8)])
+def test_relu_activation(base, users):
+    cfg = synth.CONFIGS[base].replace(act="relu", index=15)
+    _say("%s with ReLU in the FFN" % base)
+    _entry_points(synth.make_case(cfg, users=users), TOL[cfg.dtype], with_inner=(base == "C1"))
+
+
+@pytest.mark.parametrize("K", [1, 2, 32])
+def test_fp32_merge_group_sizes(K):
+    """K = 1 (every token its own group), K = 2, and K = 32 (a whole tile is one group: the
+    in-tile softmax runs over all 16 accumulator registers)."""
+    cfg = synth.CONFIGS["C1"].replace(B=3, L=100, K=K, k_recent=3, ragged=True, len_lo=1, len_hi=100, index=16)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"][0] = 100
+    case["H"][0] = np.random.default_rng(9).standard_normal(case["H"][0].shape).astype(np.float32)
+    _say("fp32 merge with K = %d" % K)
+    _entry_points(case, TOL["f32"])
+
+
+@pytest.mark.parametrize("m", [1, 16, 32])
+def test_bf16_serving_global_set_sizes(m):
+    """Candidate scoring with 1, 16 and 32 global tokens per candidate (32, 2 and 1 candidates
+    per tile; the in-tile softmax windows of 4, 8 and 16 registers), ragged users."""
+    cfg = synth.CONFIGS["C2"].replace(B=3, L=400, m=m, k_recent=20, C=7, gmask="causal" if m == 16 else "full",
+                                      ragged=True, len_lo=30, len_hi=400, index=17)
+    case = synth.make_case(cfg)
+    case["lens"][0] = 37           # 5 merged tokens < k
+    _say("bf16 serving with m = %d global tokens" % m)
+    _serving(case, TOL["bf16"])
+
+
 def test_c2_bf16_all_entry_points():
     _say("C2 bf16 (16 users)")
     _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
