@@ -149,6 +149,15 @@ def test_bf16_serving_global_set_sizes(m):
     _serving(case, TOL["bf16"])
 
 
+def test_bf16_d256_forward_entry_points():
+    """The serving configuration's model (d = 256, head width 32) through the forward entry
+    points: the d = 256 instantiations of the merge, K/V projection, attention and stack kernels."""
+    cfg = synth.CONFIGS["C5"].replace(B=3, L=1200, C=0, ragged=True, len_lo=100, len_hi=1200, index=18)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    _say("bf16 d=256 forward (3 users, L=1200, K=16, k=64)")
+    _entry_points(case, TOL["bf16"], with_inner=False)
+
+
 def test_c2_bf16_all_entry_points():
     _say("C2 bf16 (16 users)")
     _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
