@@ -20,6 +20,7 @@
 // Every mode runs the same register-resident chain (see device.h); they differ in where
 // rows come from, which attention sources exist and what is written.
 #pragma once
+#include <type_traits>
 #include "device.h"
 
 namespace longer {
@@ -735,6 +736,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) resid[tt][nt] += b2;
     }
+    auto ffn = [&](auto relu_tag) {
+    constexpr bool RELU = decltype(relu_tag)::value;
 #pragma unroll 1
     for (int c = 0; c < NC; ++c) {
       f32x16 ah[TT];
@@ -747,30 +750,44 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
         for (int tt = 0; tt < TT; ++tt) ah[tt] = E::mma(w, xn[tt][s], ah[tt]);
       }
       ws.advance();
-      grp hop[TT][GPT];
+      // operand group by operand group: the second GEMM's MFMAs that use group g (one per
+      // output tile, independent accumulators) only need the activation of that group's
+      // registers, so the rest of the activation's VALU work can run under them
 #pragma unroll
-      for (int tt = 0; tt < TT; ++tt) {
-        if (p.act == 1) {
+      for (int g = 0; g < GPT; ++g) {
+        grp hop[TT];
 #pragma unroll
-          for (int r = 0; r < 16; ++r) ah[tt][r] = fmaxf(ah[tt][r], 0.f);
-        } else {
+        for (int tt = 0; tt < TT; ++tt) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) ah[tt][r] = gelu_fn<sizeof(T) == 4>(ah[tt][r]);
+          for (int e = 0; e < E::EPL; ++e) {
+            const float v = ah[tt][E::EPL * g + e];
+            ah[tt][E::EPL * g + e] = RELU ? fmaxf(v, 0.f) : gelu_fn<sizeof(T) == 4>(v);
+          }
+          hop[tt] = E::pack(ah[tt], g);
         }
 #pragma unroll
-        for (int g = 0; g < GPT; ++g) hop[tt][g] = E::pack(ah[tt], g);
-      }
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-        for (int g = 0; g < GPT; ++g) {
+        for (int nt = 0; nt < NT; ++nt) {
           const grp w = ws.template frag<grp>(nt * GPT + g);
 #pragma unroll
-          for (int tt = 0; tt < TT; ++tt) resid[tt][nt] = E::mma(w, hop[tt][g], resid[tt][nt]);
+          for (int tt = 0; tt < TT; ++tt) resid[tt][nt] = E::mma(w, hop[tt], resid[tt][nt]);
         }
+      }
+      if (sizeof(T) == 2 && TT == 1 && !RELU) {
+        // order within this stretch: activation of group 0, the weight fragments, then each
+        // MFMA of group 0 followed by a quarter of group 1's activation, then group 1's MFMAs
+        __builtin_amdgcn_sched_group_barrier(0x002, 60, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * NT, 0);
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 60 / NT, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);
       }
       ws.advance();
     }
+    };
+    if (p.act == 1) ffn(std::true_type{}); else ffn(std::false_type{});
     if (selfl) ws.advance();   // the unused segment behind a fused block in the packed buffer
   }
 
