@@ -627,19 +627,23 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
           }
         }
         if (EXT || (STACK && !selfl)) {     // stored K/V fragments (all waves of a tile's user read the same ones)
+          // all rows of a tile belong to one user in these modes: user, key tile count and the
+          // fragment base addresses are wave-uniform (scalar registers, scalar loop control)
+          const int uu = __builtin_amdgcn_readfirstlane(usr[tt]);
+          const int tuu = __builtin_amdgcn_readfirstlane(Tu[tt]);
           const char* kb; const char* vb; int nkt, rlo, rhi;
           if (ATTNLIKE) {
-            kb = p.kst + (size_t)usr[tt] * p.kv_ustride; vb = p.vst + (size_t)usr[tt] * p.kv_ustride;
-            nkt = kthi[tt]; rlo = 0; rhi = 0;
+            kb = p.kst + (size_t)uu * p.kv_ustride; vb = p.vst + (size_t)uu * p.kv_ustride;
+            nkt = __builtin_amdgcn_readfirstlane(kthi[tt]); rlo = 0; rhi = 0;
           } else {
-            const int i0 = max(p.k - Tu[tt], 0);
+            const int i0 = max(p.k - tuu, 0);
             if (layer == 0) {
-              kb = p.cache + (size_t)usr[tt] * p.c0_ustride; vb = kb + p.c0_voff;
-              nkt = min(p.kt0, (Tu[tt] + 31) / 32); rlo = 0; rhi = Tu[tt];
+              kb = p.cache + (size_t)uu * p.c0_ustride; vb = kb + p.c0_voff;
+              nkt = min(p.kt0, (tuu + 31) / 32); rlo = 0; rhi = tuu;
             } else {
-              kb = p.cache + p.c1_off + (size_t)(layer - 1) * p.c1_lstride + (size_t)usr[tt] * p.c1_ustride;
+              kb = p.cache + p.c1_off + (size_t)(layer - 1) * p.c1_lstride + (size_t)uu * p.c1_ustride;
               vb = kb + p.c1_voff;
-              nkt = Tu[tt] > 0 ? p.kt1 : 0; rlo = i0; rhi = p.k;
+              nkt = tuu > 0 ? p.kt1 : 0; rlo = i0; rhi = p.k;
             }
             if (!valid[tt]) rhi = rlo;
           }
