@@ -71,9 +71,24 @@ struct StageScope {
 // the block kernels stream them (see PackLayout in device.h), the small vectors as fp32.
 struct RawBlock { longer_block b; };
 
+// One launch packs up to kMaxPackJobs blocks: blockIdx.y picks the job.
+constexpr int kMaxPackJobs = 16;
+struct PackJob { RawBlock raw; char* dst; int layout; int pad_; };
+struct PackArgs { PackJob job[kMaxPackJobs]; };
+
 template <typename T>
-__global__ void pack_block_kernel(const RawBlock raw, char* dst, int D, int FF, int layout) {
+__global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
   using E = ET<T>;
+  // the job is picked with compile-time offsets into the kernel arguments and scalar selects
+  // (a run-time index made the compiler select between addresses inside the argument block,
+  // and the O-projection segment came out wrong)
+  PackJob jb = args.job[0];
+#pragma unroll
+  for (int i = 1; i < kMaxPackJobs; ++i)
+    if ((int)blockIdx.y == i) jb = args.job[i];
+  const RawBlock& raw = jb.raw;
+  char* dst = jb.dst;
+  const int layout = jb.layout;
   const int NT = D / 32, NC = FF / 32, NG = D / E::GF, SEGV = NG * 64;
   const int nseg = layout == LAYOUT_FUSED ? fused_segs(D, FF) : kv_segs(D) + attn_segs(D, FF);
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -259,23 +274,36 @@ static CacheLayout make_cache_layout(const longer_config* c, const Shape& s, int
   return cl;
 }
 
-static int pack_blocks(const longer_config* c, const Shape& s, const longer_block* blocks, int nb, int layout, char* dst,
-                       size_t stride, hipStream_t st) {
-  StageScope scope(ST_PACK, st);
-  for (int i = 0; i < nb; ++i) {
-    const longer_block& b = blocks[i];
-    const void* ptrs[16] = {b.ln1_g, b.ln1_b, b.wq, b.bq, b.wk, b.bk, b.wv, b.bv, b.wo, b.bo, b.ln2_g, b.ln2_b, b.w1, b.b1, b.w2, b.b2};
-    for (int j = 0; j < 16; ++j)
-      if (!ptrs[j]) return fail(LONGER_ERR_ARG, "block %d: parameter pointer %d is NULL", i, j);
-    RawBlock rb; rb.b = b;
-    const int nseg = layout == LAYOUT_FUSED ? fused_segs(s.D, s.FF) : kv_segs(s.D) + attn_segs(s.D, s.FF);
-    const long long n = (long long)nseg * (long long)(s.seg / 16);
-    const int grid = cdiv(n, 256);
-    if (c->dtype == LONGER_BF16) hipLaunchKernelGGL(pack_block_kernel<__bf16>, dim3(grid), dim3(256), 0, st, rb, dst + (size_t)i * stride, s.D, s.FF, layout);
-    else hipLaunchKernelGGL(pack_block_kernel<float>, dim3(grid), dim3(256), 0, st, rb, dst + (size_t)i * stride, s.D, s.FF, layout);
+// Collects the blocks an entry point has to pack and packs them with one launch (per
+// kMaxPackJobs blocks) when flushed.
+struct PackBatch {
+  const longer_config* c; const Shape& s; hipStream_t st;
+  PackArgs a; int n = 0;
+  PackBatch(const longer_config* c_, const Shape& s_, hipStream_t st_) : c(c_), s(s_), st(st_) { memset(&a, 0, sizeof(a)); }
+  int add(const longer_block* blocks, int nb, int layout, char* dst, size_t stride) {
+    for (int i = 0; i < nb; ++i) {
+      const longer_block& b = blocks[i];
+      const void* ptrs[16] = {b.ln1_g, b.ln1_b, b.wq, b.bq, b.wk, b.bk, b.wv, b.bv, b.wo, b.bo, b.ln2_g, b.ln2_b, b.w1, b.b1, b.w2, b.b2};
+      for (int j = 0; j < 16; ++j)
+        if (!ptrs[j]) return fail(LONGER_ERR_ARG, "block %d: parameter pointer %d is NULL", i, j);
+      if (n == kMaxPackJobs) { int rc = flush(); if (rc) return rc; }
+      a.job[n].raw.b = b; a.job[n].dst = dst + (size_t)i * stride; a.job[n].layout = layout;
+      ++n;
+    }
+    return 0;
   }
-  return hipGetLastError() == hipSuccess ? 0 : fail(LONGER_ERR_HIP, "pack kernel launch failed");
-}
+  int flush() {
+    if (n == 0) return 0;
+    StageScope scope(ST_PACK, st);
+    // the split layout has the most segments; threads past a job's own count return at once
+    const long long items = (long long)(kv_segs(s.D) + attn_segs(s.D, s.FF)) * (long long)(s.seg / 16);
+    const dim3 grid(cdiv(items, 256), n);
+    if (c->dtype == LONGER_BF16) hipLaunchKernelGGL(pack_block_kernel<__bf16>, grid, dim3(256), 0, st, a, s.D, s.FF);
+    else hipLaunchKernelGGL(pack_block_kernel<float>, grid, dim3(256), 0, st, a, s.D, s.FF);
+    n = 0;
+    return hipGetLastError() == hipSuccess ? 0 : fail(LONGER_ERR_HIP, "pack kernel launch failed");
+  }
+};
 
 static int pack_head(const longer_config* c, const Shape& s, const longer_weights* w, float* dst, hipStream_t st) {
   if (!w->head_w || !w->head_b) return fail(LONGER_ERR_ARG, "head_w / head_b is NULL but logits were asked for");
@@ -412,7 +440,9 @@ static int merge_entry(const longer_config* cfg, const longer_block* inner, cons
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
-  if ((rc = pack_blocks(cfg, s, inner, cfg->inner_layers, LAYOUT_FUSED, w8 + l.packed, (size_t)fused_segs(s.D, s.FF) * s.seg, st))) return rc;
+  PackBatch pk_batch(cfg, s, st);
+  if ((rc = pk_batch.add(inner, cfg->inner_layers, LAYOUT_FUSED, w8 + l.packed, (size_t)fused_segs(s.D, s.FF) * s.seg))) return rc;
+  if ((rc = pk_batch.flush())) return rc;
   return run_merge(cfg, s, w8 + l.packed, H, lens, B, L, M_out, 0, Z_out, st);
 }
 
@@ -471,7 +501,9 @@ int longer_hybrid_cross_attn(const longer_config* cfg, const longer_block* cross
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
-  if ((rc = pack_blocks(cfg, s, cross, 1, LAYOUT_SPLIT, w8 + l.packed, s.pb, st))) return rc;
+  PackBatch pk_batch(cfg, s, st);
+  if ((rc = pk_batch.add(cross, 1, LAYOUT_SPLIT, w8 + l.packed, s.pb))) return rc;
+  if ((rc = pk_batch.flush())) return rc;
   AttnIO io = cross_io(cfg, s, l, w8, G, M, 0, B, L, X_out, 0);
   return run_layer(cfg, s, w8 + l.packed, lens, B, L, io, true, st);
 }
@@ -487,7 +519,9 @@ int longer_self_attn_layer(const longer_config* cfg, const longer_block* blk, co
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
-  if ((rc = pack_blocks(cfg, s, blk, 1, LAYOUT_SPLIT, w8 + l.packed, s.pb, st))) return rc;
+  PackBatch pk_batch(cfg, s, st);
+  if ((rc = pk_batch.add(blk, 1, LAYOUT_SPLIT, w8 + l.packed, s.pb))) return rc;
+  if ((rc = pk_batch.flush())) return rc;
   AttnIO io = self_io(cfg, s, l, w8, X_in, 0, X_out, 0);
   return run_layer(cfg, s, w8 + l.packed, lens, B, L, io, true, st);
 }
@@ -510,11 +544,13 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
   char* pk = w8 + l.packed;
-  if ((rc = pack_blocks(cfg, s, w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(s.D, s.FF) * s.seg, st))) return rc;
+  PackBatch pk_batch(cfg, s, st);
+  if ((rc = pk_batch.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(s.D, s.FF) * s.seg))) return rc;
   char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
-  if ((rc = pack_blocks(cfg, s, w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb, st))) return rc;
+  if ((rc = pk_batch.add(w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb))) return rc;
   const bool one_launch = s.n <= 32 * kWaves;   // a user's reduced rows fit one workgroup
-  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, one_launch ? LAYOUT_FUSED : LAYOUT_SPLIT, pk_cross + s.pb, s.pb, st))) return rc;
+  if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, one_launch ? LAYOUT_FUSED : LAYOUT_SPLIT, pk_cross + s.pb, s.pb))) return rc;
+  if ((rc = pk_batch.flush())) return rc;
   float* head = (float*)(w8 + l.head);
   if (logits_out && (rc = pack_head(cfg, s, w, head, st))) return rc;
 
@@ -554,10 +590,12 @@ int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, con
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
   char* pk = w8 + l.packed;
-  if ((rc = pack_blocks(cfg, s, w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(s.D, s.FF) * s.seg, st))) return rc;
+  PackBatch pk_batch(cfg, s, st);
+  if ((rc = pk_batch.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(s.D, s.FF) * s.seg))) return rc;
   char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
-  if ((rc = pack_blocks(cfg, s, w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb, st))) return rc;
-  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, LAYOUT_SPLIT, pk_cross + s.pb, s.pb, st))) return rc;
+  if ((rc = pk_batch.add(w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb))) return rc;
+  if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, LAYOUT_SPLIT, pk_cross + s.pb, s.pb))) return rc;
+  if ((rc = pk_batch.flush())) return rc;
   if ((rc = run_merge(cfg, s, pk, H, lens, U, L, w8 + l.M, 1, nullptr, st))) return rc;
 
   const int T = cdiv(L, cfg->K);
@@ -608,8 +646,10 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
   char* w8 = (char*)ws;
   char* pk_cross = w8 + l.packed + (size_t)cfg->inner_layers * s.pb;
   const size_t fstride = (size_t)fused_segs(s.D, s.FF) * s.seg;   // scoring streams all layers back to back
-  if ((rc = pack_blocks(cfg, s, w->cross, 1, LAYOUT_FUSED, pk_cross, fstride, st))) return rc;
-  if (cfg->n_self && (rc = pack_blocks(cfg, s, w->self, cfg->n_self, LAYOUT_FUSED, pk_cross + fstride, fstride, st))) return rc;
+  PackBatch pk_batch(cfg, s, st);
+  if ((rc = pk_batch.add(w->cross, 1, LAYOUT_FUSED, pk_cross, fstride))) return rc;
+  if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, LAYOUT_FUSED, pk_cross + fstride, fstride))) return rc;
+  if ((rc = pk_batch.flush())) return rc;
   float* head = (float*)(w8 + l.head);
   if (logits_out && (rc = pack_head(cfg, s, w, head, st))) return rc;
 
