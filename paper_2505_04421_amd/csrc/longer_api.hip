@@ -73,6 +73,7 @@ struct RawBlock { longer_block b; };
 
 // One launch packs up to kMaxPackJobs blocks: blockIdx.y picks the job.
 constexpr int kMaxPackJobs = 16;
+constexpr int kLayoutHead = 2;     // a job that converts the head's weights instead of packing a block
 struct PackJob { RawBlock raw; char* dst; int layout; int pad_; };
 struct PackArgs { PackJob job[kMaxPackJobs]; };
 
@@ -89,6 +90,12 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
   const RawBlock& raw = jb.raw;
   char* dst = jb.dst;
   const int layout = jb.layout;
+  if (layout == kLayoutHead) {   // the scoring head: pad_ weights (ln1_g) then the bias (ln1_b), as fp32
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < jb.pad_) reinterpret_cast<float*>(dst)[i] = (float)reinterpret_cast<const T*>(raw.b.ln1_g)[i];
+    else if (i == jb.pad_) reinterpret_cast<float*>(dst)[i] = (float)reinterpret_cast<const T*>(raw.b.ln1_b)[0];
+    return;
+  }
   const int NT = D / 32, NC = FF / 32, NG = D / E::GF, SEGV = NG * 64;
   const int nseg = layout == LAYOUT_FUSED ? fused_segs(D, FF) : kv_segs(D) + attn_segs(D, FF);
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -158,13 +165,6 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
     out[e] = W[(size_t)k * ncols + 32 * nt + n_in];
   }
   reinterpret_cast<typename E::grp*>(dst)[idx] = out;
-}
-
-template <typename T>
-__global__ void pack_head_kernel(const T* hw, const T* hb, float* dst, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) dst[i] = (float)hw[i];
-  else if (i == n) dst[i] = (float)hb[0];
 }
 
 __global__ void probe_kernel(int32_t* out) {
@@ -292,6 +292,14 @@ struct PackBatch {
     }
     return 0;
   }
+  int add_head(const longer_weights* w, float* dst) {
+    if (!w->head_w || !w->head_b) return fail(LONGER_ERR_ARG, "head_w / head_b is NULL but logits were asked for");
+    if (n == kMaxPackJobs) { int rc = flush(); if (rc) return rc; }
+    a.job[n].raw.b.ln1_g = w->head_w; a.job[n].raw.b.ln1_b = w->head_b;
+    a.job[n].dst = (char*)dst; a.job[n].layout = kLayoutHead; a.job[n].pad_ = c->m * s.D;
+    ++n;
+    return 0;
+  }
   int flush() {
     if (n == 0) return 0;
     StageScope scope(ST_PACK, st);
@@ -304,14 +312,6 @@ struct PackBatch {
     return hipGetLastError() == hipSuccess ? 0 : fail(LONGER_ERR_HIP, "pack kernel launch failed");
   }
 };
-
-static int pack_head(const longer_config* c, const Shape& s, const longer_weights* w, float* dst, hipStream_t st) {
-  if (!w->head_w || !w->head_b) return fail(LONGER_ERR_ARG, "head_w / head_b is NULL but logits were asked for");
-  const int n = c->m * s.D;
-  if (c->dtype == LONGER_BF16) hipLaunchKernelGGL(pack_head_kernel<__bf16>, dim3(cdiv(n + 1, 256)), dim3(256), 0, st, (const __bf16*)w->head_w, (const __bf16*)w->head_b, dst, n);
-  else hipLaunchKernelGGL(pack_head_kernel<float>, dim3(cdiv(n + 1, 256)), dim3(256), 0, st, (const float*)w->head_w, (const float*)w->head_b, dst, n);
-  return hipGetLastError() == hipSuccess ? 0 : fail(LONGER_ERR_HIP, "head pack launch failed");
-}
 
 static BlockParams base_params(const longer_config* c, const Shape& s, const int32_t* lens, int B, int L, int DH) {
   BlockParams p;
@@ -550,9 +550,9 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
   if ((rc = pk_batch.add(w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb))) return rc;
   const bool one_launch = s.n <= 32 * kWaves;   // a user's reduced rows fit one workgroup
   if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, one_launch ? LAYOUT_FUSED : LAYOUT_SPLIT, pk_cross + s.pb, s.pb))) return rc;
-  if ((rc = pk_batch.flush())) return rc;
   float* head = (float*)(w8 + l.head);
-  if (logits_out && (rc = pack_head(cfg, s, w, head, st))) return rc;
+  if (logits_out && (rc = pk_batch.add_head(w, head))) return rc;
+  if ((rc = pk_batch.flush())) return rc;
 
   if ((rc = run_merge(cfg, s, pk, H, lens, B, L, w8 + l.M, 1, nullptr, st))) return rc;
   if (one_launch) {
@@ -649,9 +649,9 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
   PackBatch pk_batch(cfg, s, st);
   if ((rc = pk_batch.add(w->cross, 1, LAYOUT_FUSED, pk_cross, fstride))) return rc;
   if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, LAYOUT_FUSED, pk_cross + fstride, fstride))) return rc;
-  if ((rc = pk_batch.flush())) return rc;
   float* head = (float*)(w8 + l.head);
-  if (logits_out && (rc = pack_head(cfg, s, w, head, st))) return rc;
+  if (logits_out && (rc = pk_batch.add_head(w, head))) return rc;
+  if ((rc = pk_batch.flush())) return rc;
 
   BlockParams p = base_params(cfg, s, lens, U, L, s.DH);
   p.wbase = pk_cross; p.n_layers = 1 + cfg->n_self;
