@@ -204,7 +204,8 @@ __device__ __forceinline__ void layer_norm(const f32x16 (&x)[TT][D / 32], const 
       q = sum_halves(q);
       var = fmaxf(q * (1.0f / D) - mean * mean, 0.f);
     }
-    const float rstd = 1.0f / sqrtf(var + eps);
+    // (bf16 mode: the hardware reciprocal square root, 1 ulp, instead of the exact division)
+    const float rstd = EXACT ? 1.0f / sqrtf(var + eps) : __builtin_amdgcn_rsqf(var + eps);
     const float shift = -mean * rstd;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -527,7 +528,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       }
       if (FUSED || MODE == MODE_KVPROJ || selfl) {
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) ak[tt] = bias_tile(vec + vl.bk(), ft, hi);
+        for (int tt = 0; tt < TT; ++tt) ak[tt] = splat16(0.f);   // no b_K: a per-query constant in the scores, softmax drops it
 #pragma unroll
         for (int s = 0; s < NG; ++s) {
           const grp w = ws.template frag<grp>(s);
@@ -535,9 +536,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
           for (int tt = 0; tt < TT; ++tt) ak[tt] = E::mma(w, xn[tt][s], ak[tt]);
         }
         ws.advance();
-        const float bvl = vec[vl.bv() + 32 * ft + j];
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) av[tt] = splat16(bvl);
+        for (int tt = 0; tt < TT; ++tt) av[tt] = splat16(0.f);   // no b_V: probabilities sum to 1, so the pack kernel folds it into the output bias
 #pragma unroll
         for (int s = 0; s < NG; ++s) {
           const grp w = ws.template frag<grp>(s);

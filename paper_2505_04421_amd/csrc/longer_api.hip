@@ -135,7 +135,7 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
         else if (i < vl.bk()) { src = (const T*)raw.b.bq; off = i - vl.bq(); }
         else if (i < vl.bv()) { src = (const T*)raw.b.bk; off = i - vl.bk(); }
         else if (i < vl.bo()) { src = (const T*)raw.b.bv; off = i - vl.bv(); }
-        else if (i < vl.ln2_g()) { src = (const T*)raw.b.bo; off = i - vl.bo(); }
+        else if (i < vl.ln2_g()) { src = (const T*)raw.b.bo; off = i - vl.bo(); }   // replaced below
         else if (i < vl.ln2_b()) { src = (const T*)raw.b.ln2_g; off = i - vl.ln2_g(); }
         else if (i < vl.b2()) { src = (const T*)raw.b.ln2_b; off = i - vl.ln2_b(); }
         else if (i < vl.b1()) { src = (const T*)raw.b.b2; off = i - vl.b2(); }
@@ -144,7 +144,31 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
       }
       out[e] = v;
     }
-    reinterpret_cast<f32x4*>(dst)[idx] = out;
+    // (the output bias slot is written by the fold below, possibly from another workgroup)
+    if (within * 4 < vl.bo() || within * 4 >= vl.ln2_g()) reinterpret_cast<f32x4*>(dst)[idx] = out;
+    // The block kernels apply no value bias: softmax rows sum to 1, so
+    //   softmax(.)(V + 1 b_V^T) W_O + b_O = softmax(.) V W_O + (b_V W_O + b_O),
+    // and the output bias slot gets b_O + b_V W_O.  (The key bias only adds a per-query
+    // constant to the scores, which softmax drops.)  A workgroup folds 64 outputs: wave kp
+    // sums a quarter of the rows of W_O (coalesced along the row), LDS adds the four up.
+    // All threads of a workgroup belong to the same segment, so the barrier is uniform.
+    __shared__ float red[4][64];
+    const int wg_in_seg = within / 256;
+    if (wg_in_seg < (D + 63) / 64) {
+      const int t = threadIdx.x, o = 64 * wg_in_seg + (t & 63), kp = t >> 6;
+      float acc = 0.f;
+      if (o < D) {
+        const T* bvp = (const T*)raw.b.bv + kp * (D / 4);
+        const T* wop = (const T*)raw.b.wo + (size_t)kp * (D / 4) * D + o;
+#pragma unroll 8
+        for (int k = 0; k < D / 4; ++k) acc += (float)bvp[k] * (float)wop[(size_t)k * D];
+      }
+      red[kp][t & 63] = acc;
+      __syncthreads();
+      if (kp == 0 && o < D)
+        reinterpret_cast<float*>(dst)[(idx - within) * 4 + vl.bo() + o] =
+            (float)((const T*)raw.b.bo)[o] + ((red[0][t] + red[1][t]) + (red[2][t] + red[3][t]));
+    }
     return;
   }
   const int f = within / 64, lane = within % 64, n_in = lane & 31, hi = lane >> 5;
