@@ -354,8 +354,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   constexpr bool STACK = MODE == MODE_STACK;
   constexpr bool ATTNLIKE = MODE == MODE_ATTN || STACK;   // rows are [globals; recent slots] of a user
   constexpr bool BIGSEG = SEGV * 16 >= 16384;
-  constexpr int PSEG = BIGSEG ? 1 : 2;              // segments per panel of the weight stream (one barrier per panel)
-  constexpr int NB = BIGSEG ? 6 : 4;                // ring depth in panels
+  constexpr int PSEG = BIGSEG ? 1 : 4;              // segments per panel of the weight stream (one barrier per panel)
+  constexpr int NB = BIGSEG ? 6 : 2;                // ring depth in panels
   static_assert(DH == 16 || DH == 32, "head width");
   __shared__ uint4 lds[NB * PSEG * SEGV];
   __shared__ uint4 vecl[SEGV];          // the current block's fp32 vectors
