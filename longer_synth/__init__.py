@@ -62,10 +62,17 @@ class Config:
     len_lo: int = 0
     len_hi: int = 0
     C: int = 0             # candidates per user (serving config only)
+    merge: str = "mean"    # "mean": K outputs of a group pooled to one token of width d;
+                           # "concat": raw tokens of width d / K, a group's K outputs concatenated
 
     @property
     def T(self) -> int:
         return (self.L + self.K - 1) // self.K
+
+    @property
+    def d_in(self) -> int:
+        """Width of the raw tokens H and of the InnerTrans blocks."""
+        return self.d // self.K if self.merge == "concat" else self.d
 
     @property
     def n(self) -> int:
@@ -152,7 +159,7 @@ def draw_block(rng: np.random.Generator, d: int, ffn_mult: int = 4) -> Dict[str,
 def draw_weights(cfg: Config, rng: Optional[np.random.Generator] = None) -> Dict[str, object]:
     rng = _rng(cfg) if rng is None else rng
     w = {
-        "inner": [draw_block(rng, cfg.d, cfg.ffn_mult) for _ in range(cfg.inner_layers)],
+        "inner": [draw_block(rng, cfg.d_in, cfg.ffn_mult) for _ in range(cfg.inner_layers)],
         "cross": draw_block(rng, cfg.d, cfg.ffn_mult),
         "self": [draw_block(rng, cfg.d, cfg.ffn_mult) for _ in range(cfg.n_self)],
         "head_w": _uniform(rng, cfg.m * cfg.d, np.sqrt(6.0 / (cfg.m * cfg.d + 1))),
@@ -199,7 +206,7 @@ def make_case(cfg: Config, *, users: Optional[int] = None, candidates: Optional[
         cfg = cfg.replace(C=candidates)
     rng = _rng(cfg)
     w = draw_weights(cfg, rng)
-    H = _tokens(rng, (cfg.B, cfg.L, cfg.d), cfg.dist)
+    H = _tokens(rng, (cfg.B, cfg.L, cfg.d_in), cfg.dist)
     G = _tokens(rng, (cfg.B, cfg.m, cfg.d), cfg.dist)
     G_cand = None
     if cfg.C > 0:

@@ -26,8 +26,9 @@ What the paper fixes and where each function follows it
 Readings taken where the paper is silent or ambiguous (all listed in the design
 document as well):
 * the K InnerTrans outputs of a group become one token of width d by a mean
-  over the group's valid tokens;  InnerTrans attention is bidirectional inside
-  the group;
+  over the group's valid tokens (merge "mean"), or, with raw tokens of width
+  d / K, by concatenation (merge "concat", the paper's own width-K d form);
+  InnerTrans attention is bidirectional inside the group;
 * pre-LayerNorm residual blocks, biased variance, eps = 1e-5, no final norm;
   FFN activation exact-erf GELU (ReLU selectable);
 * multi-head attention with scale 1/sqrt(d_h); one head recovers Eq. 7;
@@ -232,14 +233,23 @@ def inner_transformer(cfg, inner_blocks: Sequence[dict], H: np.ndarray, lens=Non
 
 
 def token_merge(cfg, inner_blocks: Sequence[dict], H: np.ndarray, lens=None) -> np.ndarray:
-    """Merged tokens M [B, T, d]: mean of each group's valid InnerTrans outputs;
-    groups with no valid token are zero."""
+    """Merged tokens M [B, T, d].
+
+    merge "mean" (default): mean of each group's valid InnerTrans outputs; groups
+    with no valid token are zero.
+    merge "concat" (Section 3.4: grouped representations formed by concatenation,
+    after InnerTrans has let the group's tokens interact; the merged width K d is
+    what Eq. 4 and the complexity ratio count): raw tokens of width d / K, the K
+    InnerTrans outputs of a group laid side by side, oldest first; slots of
+    invalid (padded) tokens are zero."""
     H = np.asarray(H)
     B, L, d = H.shape
     K = cfg.K
     T = (L + K - 1) // K
     lens = _lens(lens, B, L)
     Z = inner_transformer(cfg, inner_blocks, H, lens)
+    if getattr(cfg, "merge", "mean") == "concat":
+        return Z.reshape(B, T, K * d)
     M = np.zeros((B, T, d), dtype=F64)
     for u in range(B):
         cnt = np.clip(lens[u] - np.arange(T) * K, 0, K)         # valid tokens per group
@@ -334,7 +344,7 @@ def kv_cache_build(cfg, weights: dict, H: np.ndarray, lens=None) -> dict:
     U, L, d = H.shape
     lens = _lens(lens, U, L)
     M = token_merge(cfg, weights["inner"], H, lens)
-    T = M.shape[1]
+    T, d = M.shape[1], M.shape[2]          # the main stack's width (K times the raw width after a concat merge)
     k = cfg.k_recent
     blocks = [_f64(weights["cross"])] + [_f64(b) for b in weights["self"]]
     cache = {"K": [[] for _ in blocks], "V": [[] for _ in blocks], "valid": [[] for _ in blocks]}
@@ -402,12 +412,14 @@ def algorithmic_flops(cfg, lens=None, B: Optional[int] = None, L: Optional[int] 
     f = cfg.ffn_mult
     per_tok_q = 2 * d * d + 2 * d * d + 4 * f * d * d      # W_Q, W_O, FFN
     per_tok_kv = 4 * d * d                                  # W_K, W_V
+    di = d // K if getattr(cfg, "merge", "mean") == "concat" else d   # InnerTrans width
+    per_tok_inner = (8 + 4 * f) * di * di
     inner = cross = selfl = 0
     for lu in lens:
         lu = int(lu)
         Tu = merged_len(lu, K)
         pairs = sum(min(K, lu - t * K) ** 2 for t in range(Tu))
-        inner += cfg.inner_layers * (lu * (per_tok_q + per_tok_kv) + 4 * d * pairs)
+        inner += cfg.inner_layers * (lu * per_tok_inner + 4 * di * pairs)
         kv = min(k, Tu)
         # cross layer: keys = m globals + Tu merged tokens; queries = m globals + kv slots
         gpairs = m * m if cfg.gmask == "full" else m * (m + 1) // 2

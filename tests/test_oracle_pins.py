@@ -309,6 +309,84 @@ def test_I6_identity_inner_pools_valid_rows():
     assert (M[1, 2] == 0).all()
 
 
+# --------------------------------------------------------------------------- merge by concatenation
+def test_concat_merge_lays_torch_group_outputs_side_by_side():
+    """Section 3.4, merge by concatenation after InnerTrans: the merged token of a group is its K
+    block outputs side by side, oldest first (the block itself against torch's encoder layer)."""
+    cfg = synth.tiny_config(B=2, L=16, d=32, K=4, inner_layers=2, inner_heads=2, merge="concat")
+    assert cfg.d_in == 8
+    blocks = [_blk(31, cfg.d_in), _blk(32, cfg.d_in)]
+    H = _rng(19).standard_normal((cfg.B, cfg.L, cfg.d_in))
+    x = torch.from_numpy(H.reshape(cfg.B * cfg.T, cfg.K, cfg.d_in))
+    with torch.no_grad():
+        for b in blocks:
+            x = _torch_layer(b, cfg.d_in, cfg.inner_heads)(x)
+    ref = x.numpy().reshape(cfg.B, cfg.T, cfg.K, cfg.d_in)
+    M = orc.token_merge(cfg, blocks, H)
+    assert M.shape == (cfg.B, cfg.T, cfg.d)
+    for j in range(cfg.K):      # slot j of the merged token = output of the group's j-th token
+        np.testing.assert_allclose(M[:, :, j * cfg.d_in:(j + 1) * cfg.d_in], ref[:, :, j], rtol=1e-10, atol=1e-11)
+
+
+def test_concat_merge_identity_inner_is_a_reshape_with_zero_padding():
+    cfg = synth.tiny_config(B=2, L=10, d=32, K=4, merge="concat")
+    H = _rng(2).standard_normal((2, 10, 8))
+    Hn = H.copy(); Hn[1, 5:] = np.nan
+    M = orc.token_merge(cfg, [_identity_block(8)], Hn, np.array([10, 5]))
+    assert np.array_equal(M[0, :2].reshape(8, 8), H[0, :8])
+    assert np.array_equal(M[0, 2, :16].reshape(2, 8), H[0, 8:10]) and (M[0, 2, 16:] == 0).all()   # ragged last group of L
+    assert np.array_equal(M[1, 1, :8], H[1, 4]) and (M[1, 1, 8:] == 0).all() and (M[1, 2] == 0).all()
+    # K = 1: concatenation of one token is the token
+    cfg1 = synth.tiny_config(B=2, L=7, d=8, K=1, merge="concat")
+    H1 = _rng(3).standard_normal((2, 7, 8))
+    assert np.array_equal(orc.token_merge(cfg1, [_identity_block(8)], H1), H1)
+
+
+def test_concat_main_stack_has_eq4_parameters_and_ratio_flops():
+    """Eq. 4: a layer of the main stack at the merged width K d owns 12 K^2 d^2 + 13 K d
+    parameters; the complexity ratio's numerator is Eq. 3 at (L / K, K d)."""
+    cfg = synth.tiny_config(B=1, L=2048, d=128, K=4, heads=2, merge="concat", inner_layers=1, n_self=1)
+    w = synth.draw_weights(cfg)
+    assert cfg.d_in == 32
+    assert orc.block_param_count(w["cross"]) == orc.params_merged_layer(cfg.d_in, cfg.K) == 12 * 16 * 1024 + 13 * 128
+    assert orc.block_param_count(w["inner"][0]) == orc.params_vanilla_layer(32)
+    assert orc.flops_vanilla_layer(2048 // 4, 4 * 32) == orc.flops_merged_layer(2048, 32, 4)
+    # the counter: a full-length user, all T merged tokens as queries of one self layer over
+    # [m globals; T tokens] -- compare its GEMM part with 24 (m + T) (K d)^2
+    cfgq = cfg.replace(k_recent=cfg.T)
+    fl = orc.algorithmic_flops(cfgq)
+    n = cfgq.m + cfgq.T
+    causal_pairs = cfgq.m * cfgq.m + cfgq.m * cfgq.T + cfgq.T * (cfgq.T + 1) // 2
+    assert fl["self_each"] == 24 * n * 128 * 128 + 4 * 128 * causal_pairs
+    assert fl["inner"] == 2048 * 24 * 32 * 32 + 4 * 32 * (2048 // 4) * 16
+
+
+def test_concat_forward_padding_and_cache_invariants():
+    cfg = synth.tiny_config(B=2, L=23, d=16, K=4, heads=2, m=2, k_recent=3, n_self=2, inner_heads=1, merge="concat")
+    w, H, G = _case(cfg)
+    assert H.shape[-1] == 4 and w["inner"][0]["wq"].shape == (4, 4) and w["cross"]["wq"].shape == (16, 16)
+    lens = np.array([23, 14])
+    Y, lg = orc.forward(cfg, w, H, G, lens)
+    Hn = H.copy(); Hn[1, 14:] = np.nan
+    Yn, lgn = orc.forward(cfg, w, Hn, G, lens)
+    assert np.array_equal(Y, Yn) and np.array_equal(lg, lgn)
+    # forward = merge, then the same cross / self layers as in mean mode over M
+    M = orc.token_merge(cfg, w["inner"], H, lens)
+    X = orc.hybrid_cross_attn(cfg.replace(merge="mean"), w["cross"], G, M, lens, L=cfg.L)
+    for blk in w["self"]:
+        X = orc.self_attn_layer(cfg.replace(merge="mean"), blk, X, lens, L=cfg.L)
+    assert np.array_equal(X, Y)
+    # serving: scoring against the cache equals the full forward pass per candidate
+    rng = _rng(5)
+    Gc = rng.standard_normal((cfg.B, 3, cfg.m, cfg.d))
+    cache = orc.kv_cache_build(cfg, w, H, lens)
+    Yg, lgs = orc.score_candidates(cfg, w, cache, Gc)
+    for c in range(3):
+        Yc, lc = orc.forward(cfg, w, H, Gc[:, c], lens)
+        np.testing.assert_allclose(Yg[:, c], Yc[:, :cfg.m], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(lgs[:, c], lc, rtol=1e-12, atol=1e-13)
+
+
 def test_I2_all_tokens_as_queries_is_self_attention():
     for gm in ("full", "causal"):
         cfg = synth.tiny_config(B=2, L=16, d=8, K=4, m=2, k_recent=4, gmask=gm)      # k = T
@@ -343,7 +421,7 @@ def test_I3_softmax_rows_sum_to_one_and_masked_are_zero():
 def _case(cfg, seed=0):
     rng = _rng(seed)
     w = synth.draw_weights(cfg, rng)
-    H = rng.standard_normal((cfg.B, cfg.L, cfg.d))
+    H = rng.standard_normal((cfg.B, cfg.L, cfg.d_in))
     G = rng.standard_normal((cfg.B, cfg.m, cfg.d))
     return w, H, G
 
