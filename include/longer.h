@@ -28,7 +28,8 @@
  *
  * Supported shapes: bf16 with d in {64, 128, 256} and head width d/heads in {16, 32};
  * fp32 with d in {32, 64} and head width 16; K and m must divide 32 (K for the merge,
- * m for candidate scoring); ffn hidden width ffn_mult*d a multiple of 32.
+ * m for candidate scoring); ffn hidden width ffn_mult*d a multiple of 32.  With
+ * LONGER_MERGE_CONCAT the InnerTrans width d / K must be one of these widths too.
  *
  * Mask (Eq. 8, applied by token type on chronologically stored data): a sequence query
  * sees sequence keys that are not newer than itself and never a global key; a global
@@ -54,6 +55,15 @@ extern "C" {
 typedef enum { LONGER_F32 = 0, LONGER_BF16 = 1 } longer_dtype;
 typedef enum { LONGER_GMASK_FULL = 0, LONGER_GMASK_CAUSAL = 1 } longer_gmask;
 typedef enum { LONGER_ACT_GELU_ERF = 0, LONGER_ACT_RELU = 1 } longer_act;
+/* How the K InnerTrans outputs of a group become one merged token (Section 3.4):
+ *   LONGER_MERGE_MEAN    raw tokens, InnerTrans blocks and the main stack all have width d;
+ *                        the merged token is the mean over the group's valid tokens;
+ *   LONGER_MERGE_CONCAT  the paper's concatenation (merged width K d_raw, the width Eq. 4
+ *                        counts): raw tokens H and the InnerTrans blocks have width d / K,
+ *                        the merged token is the group's K outputs side by side, oldest
+ *                        first, zeros in the slots of padded tokens; the main stack runs
+ *                        at width d.  Needs d / K to be a supported width. */
+typedef enum { LONGER_MERGE_MEAN = 0, LONGER_MERGE_CONCAT = 1 } longer_merge;
 
 /* Model shape.  Names follow the paper: d width, m global tokens (Section 3.3), K merge
  * group size (Section 3.4), k_recent sampled recent queries (Eq. 5), n_self = N stacked
@@ -66,6 +76,7 @@ typedef struct {
   int32_t gmask;    /* longer_gmask */
   float   ln_eps;
   int32_t dtype;    /* longer_dtype */
+  int32_t merge;    /* longer_merge */
 } longer_config;
 
 /* One pre-LayerNorm transformer block: 12 d^2 + 13 d scalars for ffn_mult = 4 (Eq. 3).
@@ -94,13 +105,15 @@ size_t longer_kv_cache_bytes(const longer_config* cfg, int U, int L);
 
 /* InnerTrans (Section 3.4, InnerTrans equation): cfg->inner_layers blocks applied inside
  * each group of K adjacent raw tokens, attention bidirectional inside the group, keys
- * masked by validity.  H [B, L, d] -> Z_out [B, T, K, d] with T = ceil(L / K). */
+ * masked by validity.  H [B, L, d] -> Z_out [B, T, K, d] with T = ceil(L / K)
+ * (LONGER_MERGE_CONCAT: H [B, L, d / K] -> Z_out [B, T, K, d / K], inner blocks of width d / K). */
 int longer_inner_transformer(const longer_config* cfg, const longer_block* inner, const void* H,
                              const int32_t* lens, int B, int L, void* Z_out,
                              void* ws, size_t ws_bytes, void* stream);
 
 /* Token merge (Section 3.4): InnerTrans fused with the group gather and a mean over each
- * group's valid tokens.  H [B, L, d] -> M_out [B, T, d]. */
+ * group's valid tokens.  H [B, L, d] -> M_out [B, T, d].
+ * LONGER_MERGE_CONCAT: H [B, L, d / K] -> M_out [B, T, d], the group's outputs side by side. */
 int longer_token_merge(const longer_config* cfg, const longer_block* inner, const void* H,
                        const int32_t* lens, int B, int L, void* M_out,
                        void* ws, size_t ws_bytes, void* stream);
@@ -120,7 +133,7 @@ int longer_self_attn_layer(const longer_config* cfg, const longer_block* blk, co
                            void* ws, size_t ws_bytes, void* stream);
 
 /* The whole stack CrossAttn(O, R) -> SelfAttn x N (Eq. 10) after the token merge.
- * H [B, L, d], G [B, m, d] -> Y_out [B, m+k, d]; logits_out [B] fp32 (or NULL):
+ * H [B, L, d] (LONGER_MERGE_CONCAT: [B, L, d / K]), G [B, m, d] -> Y_out [B, m+k, d]; logits_out [B] fp32 (or NULL):
  * logit = <head_w, flatten(Y[0:m])> + head_b. */
 int longer_forward(const longer_config* cfg, const longer_weights* w, const void* H, const void* G,
                    const int32_t* lens, int B, int L, void* Y_out, float* logits_out,
@@ -128,7 +141,8 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
 
 /* Serving stage 1 (Section 3.6.3): everything that depends on the user sequence only --
  * token merge, the sequence rows of every layer and their per-layer K/V -- written to
- * `cache` (longer_kv_cache_bytes, opaque layout, 256-byte aligned).  H [U, L, d]. */
+ * `cache` (longer_kv_cache_bytes, opaque layout, 256-byte aligned).  H [U, L, d]
+ * (LONGER_MERGE_CONCAT: [U, L, d / K]). */
 int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, const void* H,
                           const int32_t* lens, int U, int L, void* cache,
                           void* ws, size_t ws_bytes, void* stream);

@@ -42,7 +42,7 @@ struct BlockParams {
   // MODE_MERGE
   const void* H;
   void* M_out; int M_f32;
-  void* Z_out;
+  void* Z_out; int Z_f32;
   // MODE_KVPROJ / MODE_ATTN rows: rows [0, m0) of a user come from src0, the rest from src1
   RowSrc src0, src1;
   int m0;
@@ -483,7 +483,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) {
         if (!inrange[tt]) continue;
-        if (p.Z_out) store_rows<T, NT>(resid[tt], p.Z_out, 0, out_off[tt] * D, false, hi);
+        if (p.Z_out) store_rows<T, NT>(resid[tt], p.Z_out, p.Z_f32, out_off[tt] * D, false, hi);
         if (p.M_out && (out_off[tt] & (p.K - 1)) == 0)
           store_rows<T, NT>(resid[tt], p.M_out, p.M_f32, (out_off[tt] >> __builtin_ctz(p.K)) * D, false, hi);
       }
@@ -800,7 +800,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   if (MODE == MODE_MERGE) {
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-      if (p.Z_out && inrange[tt]) store_rows<T, NT>(resid[tt], p.Z_out, 0, out_off[tt] * D, valid[tt], hi);
+      if (p.Z_out && inrange[tt]) store_rows<T, NT>(resid[tt], p.Z_out, p.Z_f32, out_off[tt] * D, valid[tt], hi);
       if (p.M_out) {
         // mean over the valid tokens of each group: tokens of a group sit on K adjacent lanes
         const uint32_t gidx = (uint32_t)out_off[tt] >> __builtin_ctz(p.K);

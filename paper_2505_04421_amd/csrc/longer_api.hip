@@ -209,6 +209,7 @@ __global__ void probe_kernel(int32_t* out) {
 // ------------------------------------------------------------------------------------
 struct Shape {
   int D, DH, DHi, FF, es, n, NT, GPT;
+  int Di;             // width of the raw tokens and the InnerTrans blocks (D, or D / K for a concat merge)
   size_t pb;          // bytes reserved per packed block (either layout)
   size_t seg;         // bytes of one stream segment
   launch_fn main_fn, inner_fn;
@@ -219,6 +220,7 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
   if (c->dtype != LONGER_F32 && c->dtype != LONGER_BF16) return fail(LONGER_ERR_ARG, "dtype %d unknown", c->dtype);
   if (c->act != LONGER_ACT_GELU_ERF && c->act != LONGER_ACT_RELU) return fail(LONGER_ERR_ARG, "act %d unknown", c->act);
   if (c->gmask != LONGER_GMASK_FULL && c->gmask != LONGER_GMASK_CAUSAL) return fail(LONGER_ERR_ARG, "gmask %d unknown", c->gmask);
+  if (c->merge != LONGER_MERGE_MEAN && c->merge != LONGER_MERGE_CONCAT) return fail(LONGER_ERR_ARG, "merge %d unknown", c->merge);
   if (c->d <= 0 || c->d % 32) return fail(LONGER_ERR_ARG, "d=%d must be a positive multiple of 32", c->d);
   if (c->ffn_mult <= 0) return fail(LONGER_ERR_ARG, "ffn_mult=%d", c->ffn_mult);
   if (!(c->ln_eps > 0.f)) return fail(LONGER_ERR_ARG, "ln_eps must be positive");
@@ -233,6 +235,12 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
   s->seg = packed_seg_bytes(s->D, s->es);
   if ((size_t)(9 * s->D + s->FF) * 4 > s->seg) return fail(LONGER_ERR_ARG, "ffn_mult=%d too large for d=%d", c->ffn_mult, c->d);
   s->main_fn = s->inner_fn = nullptr; s->DH = s->DHi = 0;
+  s->Di = c->d;
+  if (c->merge == LONGER_MERGE_CONCAT) {
+    if (c->d % c->K || (c->d / c->K) % 32)
+      return fail(LONGER_ERR_ARG, "concat merge: d / K = %d / %d must be a multiple of 32", c->d, c->K);
+    s->Di = c->d / c->K;
+  }
   if (need_main) {
     if (c->heads <= 0 || c->d % c->heads) return fail(LONGER_ERR_ARG, "heads=%d does not divide d=%d", c->heads, c->d);
     s->DH = c->d / c->heads;
@@ -241,12 +249,24 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
   }
   if (need_inner) {
     if (c->inner_layers < 1) return fail(LONGER_ERR_ARG, "inner_layers=%d", c->inner_layers);
-    if (c->inner_heads <= 0 || c->d % c->inner_heads) return fail(LONGER_ERR_ARG, "inner_heads=%d does not divide d", c->inner_heads);
-    s->DHi = c->d / c->inner_heads;
-    s->inner_fn = find_launch(c->dtype, c->d, s->DHi);
-    if (!s->inner_fn) return fail(LONGER_ERR_ARG, "unsupported shape: dtype=%d d=%d inner head width=%d", c->dtype, c->d, s->DHi);
+    if (c->inner_heads <= 0 || s->Di % c->inner_heads) return fail(LONGER_ERR_ARG, "inner_heads=%d does not divide the InnerTrans width %d", c->inner_heads, s->Di);
+    s->DHi = s->Di / c->inner_heads;
+    s->inner_fn = find_launch(c->dtype, s->Di, s->DHi);
+    if (!s->inner_fn) return fail(LONGER_ERR_ARG, "unsupported shape: dtype=%d InnerTrans width=%d inner head width=%d", c->dtype, s->Di, s->DHi);
+    if ((size_t)(9 * s->Di + c->ffn_mult * s->Di) * 4 > packed_seg_bytes(s->Di, s->es))
+      return fail(LONGER_ERR_ARG, "ffn_mult=%d too large for the InnerTrans width %d", c->ffn_mult, s->Di);
   }
   return 0;
+}
+
+// the same shape record seen from the InnerTrans side: its width, FFN width and segment size
+static Shape inner_view(const longer_config* c, const Shape& s) {
+  Shape si = s;
+  si.D = s.Di; si.FF = c->ffn_mult * s.Di; si.NT = s.Di / 32;
+  si.pb = packed_block_bytes(si.D, si.FF, s.es);
+  si.seg = packed_seg_bytes(si.D, s.es);
+  si.main_fn = nullptr;
+  return si;
 }
 
 static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
@@ -357,10 +377,10 @@ static int check_common(const void* ws, size_t ws_bytes, size_t need, int B, int
 
 // -- stage launchers (packed parameters already in place) -----------------------------
 static int run_merge(const longer_config* c, const Shape& s, const char* packed, const void* H, const int32_t* lens,
-                     int B, int L, void* M_out, int M_f32, void* Z_out, hipStream_t st) {
+                     int B, int L, void* M_out, int M_f32, void* Z_out, int Z_f32, hipStream_t st) {
   BlockParams p = base_params(c, s, lens, B, L, s.DHi);
   p.wbase = packed; p.n_layers = c->inner_layers;
-  p.H = H; p.M_out = M_out; p.M_f32 = M_f32; p.Z_out = Z_out;
+  p.H = H; p.M_out = M_out; p.M_f32 = M_f32; p.Z_out = Z_out; p.Z_f32 = Z_f32;
   const int tt = 1;
   const int win = c->K <= 8 ? 4 : (c->K <= 16 ? 8 : 16);
   const long long slots = (long long)B * p.T * c->K;
@@ -464,10 +484,13 @@ static int merge_entry(const longer_config* cfg, const longer_block* inner, cons
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
-  PackBatch pk_batch(cfg, s, st);
-  if ((rc = pk_batch.add(inner, cfg->inner_layers, LAYOUT_FUSED, w8 + l.packed, (size_t)fused_segs(s.D, s.FF) * s.seg))) return rc;
+  const Shape si = inner_view(cfg, s);
+  PackBatch pk_batch(cfg, si, st);
+  if ((rc = pk_batch.add(inner, cfg->inner_layers, LAYOUT_FUSED, w8 + l.packed, (size_t)fused_segs(si.D, si.FF) * si.seg))) return rc;
   if ((rc = pk_batch.flush())) return rc;
-  return run_merge(cfg, s, w8 + l.packed, H, lens, B, L, M_out, 0, Z_out, st);
+  // a concat merge is the un-pooled output [B, T, K, d / K] read as [B, T, d]
+  if (cfg->merge == LONGER_MERGE_CONCAT && M_out) { Z_out = M_out; M_out = nullptr; }
+  return run_merge(cfg, si, w8 + l.packed, H, lens, B, L, M_out, 0, Z_out, 0, st);
 }
 
 int longer_inner_transformer(const longer_config* cfg, const longer_block* inner, const void* H, const int32_t* lens,
@@ -569,7 +592,15 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
   char* w8 = (char*)ws;
   char* pk = w8 + l.packed;
   PackBatch pk_batch(cfg, s, st);
-  if ((rc = pk_batch.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(s.D, s.FF) * s.seg))) return rc;
+  const Shape si = inner_view(cfg, s);
+  const bool concat = cfg->merge == LONGER_MERGE_CONCAT;
+  {
+    // InnerTrans blocks of another width than the main stack's are packed by a launch of their own
+    PackBatch pk_inner(cfg, si, st);
+    PackBatch& pb = concat ? pk_inner : pk_batch;
+    if ((rc = pb.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(si.D, si.FF) * si.seg))) return rc;
+    if ((rc = pk_inner.flush())) return rc;
+  }
   char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
   if ((rc = pk_batch.add(w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb))) return rc;
   const bool one_launch = s.n <= 32 * kWaves;   // a user's reduced rows fit one workgroup
@@ -578,7 +609,7 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
   if (logits_out && (rc = pk_batch.add_head(w, head))) return rc;
   if ((rc = pk_batch.flush())) return rc;
 
-  if ((rc = run_merge(cfg, s, pk, H, lens, B, L, w8 + l.M, 1, nullptr, st))) return rc;
+  if ((rc = run_merge(cfg, si, pk, H, lens, B, L, concat ? nullptr : w8 + l.M, 1, concat ? w8 + l.M : nullptr, 1, st))) return rc;
   if (one_launch) {
     AttnIO io = cross_io(cfg, s, l, w8, G, w8 + l.M, 1, B, L, Y_out, 0);
     if (logits_out) { io.logits = logits_out; io.head = head; }
@@ -615,12 +646,20 @@ int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, con
   char* w8 = (char*)ws;
   char* pk = w8 + l.packed;
   PackBatch pk_batch(cfg, s, st);
-  if ((rc = pk_batch.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(s.D, s.FF) * s.seg))) return rc;
+  const Shape si = inner_view(cfg, s);
+  const bool concat = cfg->merge == LONGER_MERGE_CONCAT;
+  {
+    // InnerTrans blocks of another width than the main stack's are packed by a launch of their own
+    PackBatch pk_inner(cfg, si, st);
+    PackBatch& pb = concat ? pk_inner : pk_batch;
+    if ((rc = pb.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(si.D, si.FF) * si.seg))) return rc;
+    if ((rc = pk_inner.flush())) return rc;
+  }
   char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
   if ((rc = pk_batch.add(w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb))) return rc;
   if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, LAYOUT_SPLIT, pk_cross + s.pb, s.pb))) return rc;
   if ((rc = pk_batch.flush())) return rc;
-  if ((rc = run_merge(cfg, s, pk, H, lens, U, L, w8 + l.M, 1, nullptr, st))) return rc;
+  if ((rc = run_merge(cfg, si, pk, H, lens, U, L, concat ? nullptr : w8 + l.M, 1, concat ? w8 + l.M : nullptr, 1, st))) return rc;
 
   const int T = cdiv(L, cfg->K);
   char* c8 = (char*)cache;

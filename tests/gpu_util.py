@@ -34,7 +34,7 @@ class Runner:
     def inner_transformer(self):
         c, m = self.cfg, self.model
         H = self.up(self.case["H"])
-        out = m.empty(self.B, c.T, c.K, c.d)
+        out = m.empty(self.B, c.T, c.K, c.d_in)
         lg.longer_inner_transformer(m.ccfg, m.inner, H, self.lens, self.B, self.L, out, self.ws)
         return self.host(out)
 

@@ -40,12 +40,20 @@ def test_size_queries():
 
 
 @pytest.mark.parametrize("field,value", [("d", 48), ("heads", 3), ("K", 5), ("m", 3), ("dtype", 7), ("act", 9),
-                                         ("gmask", 2), ("ln_eps", 0.0), ("ffn_mult", 0)])
+                                         ("gmask", 2), ("ln_eps", 0.0), ("ffn_mult", 0), ("merge", 2)])
 def test_bad_config_is_rejected(field, value):
     cfg = lg.make_config(synth.CONFIGS["C3"])
     setattr(cfg, field, value)
     assert lg.longer_workspace_bytes(cfg, 4, 64) == 0
     assert lg.longer_last_error() != ""
+
+
+def test_concat_merge_needs_a_supported_inner_width():
+    # d = 128, K = 8: the InnerTrans width would be 16, not a multiple of 32
+    cfg = lg.make_config(synth.CONFIGS["C3"].replace(merge="concat"))
+    assert lg.longer_workspace_bytes(cfg, 4, 64) == 0 and "concat" in lg.longer_last_error()
+    ok = lg.make_config(synth.CONFIGS["C5"].replace(merge="concat", K=4, inner_heads=4))   # 256 / 4 = 64
+    assert lg.longer_workspace_bytes(ok, 4, 64) > 0
 
 
 def test_entry_points_reject_null_and_small_workspace():

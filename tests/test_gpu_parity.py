@@ -158,6 +158,35 @@ def test_bf16_d256_forward_entry_points():
     _entry_points(case, TOL["bf16"], with_inner=False)
 
 
+def test_fp32_concat_merge_all_entry_points():
+    """Merge by concatenation: raw tokens and InnerTrans at width 32, K = 2 outputs side by side,
+    main stack at width 64.  Ragged lengths (a group with one valid token, a user of length 0),
+    NaN in the padding."""
+    cfg = synth.CONFIGS["C1"].replace(B=5, L=70, d=64, heads=4, K=2, m=4, k_recent=9, n_self=2, inner_layers=2,
+                                      inner_heads=2, merge="concat", ragged=True, len_lo=1, len_hi=70, index=21)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"] = np.array([70, 0, 3, 29, 41], dtype=np.int32)
+    H = np.random.default_rng(6).standard_normal(case["H"].shape).astype(np.float32)
+    pos = np.arange(cfg.L)[None, :, None]
+    case["H"] = np.where(pos < case["lens"][:, None, None], H, np.float32("nan")).astype(np.float32)
+    assert case["H"].shape[-1] == 32
+    _say("fp32 concat merge 32 x 2 -> 64")
+    _entry_points(case, TOL["f32"])
+
+
+def test_bf16_concat_merge_all_entry_points_and_serving():
+    """bf16, raw width 64, K = 4, main stack at 256 (the serving configuration's width)."""
+    cfg = synth.CONFIGS["C5"].replace(B=3, L=1000, K=4, k_recent=40, inner_layers=2, inner_heads=4, merge="concat",
+                                      ragged=True, len_lo=30, len_hi=1000, C=24, index=22)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"][0] = 1000
+    case["H"][0] = synth.round_bf16(np.random.default_rng(8).standard_normal(case["H"][0].shape).astype(np.float32))
+    assert case["H"].shape[-1] == 64
+    _say("bf16 concat merge 64 x 4 -> 256")
+    _entry_points(case, TOL["bf16"])
+    _serving(case, TOL["bf16"])
+
+
 def test_c2_bf16_all_entry_points():
     _say("C2 bf16 (16 users)")
     _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
