@@ -94,6 +94,10 @@ CONFIGS: Dict[str, Config] = {
                  inner_layers=1, inner_heads=8, dtype="bf16", ragged=True, len_lo=100, len_hi=5000),
     "C5": Config("C5", 4, B=16, L=10000, d=256, heads=8, m=8, K=16, k_recent=64, n_self=3,
                  inner_layers=1, inner_heads=8, dtype="bf16", C=1000),
+    # not a benchmark configuration: the paper's own typical shape (Section 3.4: L = 2000, raw width 32)
+    # merged by concatenation, K = 8 -> main stack at width 256
+    "P1": Config("P1", 5, B=256, L=2000, d=256, heads=8, m=8, K=8, k_recent=100, n_self=3,
+                 inner_layers=1, inner_heads=2, dtype="bf16", dist="lognormal_scaled", merge="concat"),
 }
 
 

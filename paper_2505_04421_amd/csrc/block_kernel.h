@@ -501,6 +501,9 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
     // the block's first segment holds its fp32 vectors: keep a copy for the whole layer
     // (barriers: nobody still reads the previous block's copy; everybody sees the new one)
     if (layer > 0) __syncthreads();
+    if (SEGV < kThreads) {     // bf16 at d = 32: the segment is smaller than the workgroup
+      if (tid < SEGV) vecl[tid] = ws.cur()[tid];
+    }
 #pragma unroll
     for (int i = 0; i < SEGV / kThreads; ++i) vecl[tid + kThreads * i] = ws.cur()[tid + kThreads * i];
     __syncthreads();

@@ -11,6 +11,7 @@
 namespace longer {
 
 // explicit specialisations defined in the inst_*.hip files
+template <> int launch_block<__bf16, 32, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_block<__bf16, 64, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_block<__bf16, 128, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_block<__bf16, 256, 32>(int, int, int, const BlockParams&, dim3, hipStream_t);
@@ -21,6 +22,7 @@ typedef int (*launch_fn)(int, int, int, const BlockParams&, dim3, hipStream_t);
 
 static launch_fn find_launch(int dtype, int D, int DH) {
   if (dtype == LONGER_BF16) {
+    if (D == 32 && DH == 16) return &launch_block<__bf16, 32, 16>;
     if (D == 64 && DH == 16) return &launch_block<__bf16, 64, 16>;
     if (D == 128 && DH == 16) return &launch_block<__bf16, 128, 16>;
     if (D == 256 && DH == 32) return &launch_block<__bf16, 256, 32>;
@@ -151,23 +153,27 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
     // and the output bias slot gets b_O + b_V W_O.  (The key bias only adds a per-query
     // constant to the scores, which softmax drops.)  A workgroup folds 64 outputs: wave kp
     // sums a quarter of the rows of W_O (coalesced along the row), LDS adds the four up.
-    // All threads of a workgroup belong to the same segment, so the barrier is uniform.
+    // All threads of a workgroup belong to the same segment (the launch uses workgroups no
+    // larger than a segment), so the barrier is uniform.
     __shared__ float red[4][64];
-    const int wg_in_seg = within / 256;
+    const int nw = (int)blockDim.x >> 6;           // waves that split the rows: 4, or 2 for bf16 at d = 32
+    const int wg_in_seg = within / (int)blockDim.x;
     if (wg_in_seg < (D + 63) / 64) {
       const int t = threadIdx.x, o = 64 * wg_in_seg + (t & 63), kp = t >> 6;
       float acc = 0.f;
       if (o < D) {
-        const T* bvp = (const T*)raw.b.bv + kp * (D / 4);
-        const T* wop = (const T*)raw.b.wo + (size_t)kp * (D / 4) * D + o;
+        const T* bvp = (const T*)raw.b.bv + kp * (D / nw);
+        const T* wop = (const T*)raw.b.wo + (size_t)kp * (D / nw) * D + o;
 #pragma unroll 8
-        for (int k = 0; k < D / 4; ++k) acc += (float)bvp[k] * (float)wop[(size_t)k * D];
+        for (int k = 0; k < D / nw; ++k) acc += (float)bvp[k] * (float)wop[(size_t)k * D];
       }
       red[kp][t & 63] = acc;
       __syncthreads();
-      if (kp == 0 && o < D)
-        reinterpret_cast<float*>(dst)[(idx - within) * 4 + vl.bo() + o] =
-            (float)((const T*)raw.b.bo)[o] + ((red[0][t] + red[1][t]) + (red[2][t] + red[3][t]));
+      if (kp == 0 && o < D) {
+        float sum = red[0][t];
+        for (int i = 1; i < nw; ++i) sum += red[i][t];
+        reinterpret_cast<float*>(dst)[(idx - within) * 4 + vl.bo() + o] = (float)((const T*)raw.b.bo)[o] + sum;
+      }
     }
     return;
   }
@@ -349,9 +355,12 @@ struct PackBatch {
     StageScope scope(ST_PACK, st);
     // the split layout has the most segments; threads past a job's own count return at once
     const long long items = (long long)(kv_segs(s.D) + attn_segs(s.D, s.FF)) * (long long)(s.seg / 16);
-    const dim3 grid(cdiv(items, 256), n);
-    if (c->dtype == LONGER_BF16) hipLaunchKernelGGL(pack_block_kernel<__bf16>, grid, dim3(256), 0, st, a, s.D, s.FF);
-    else hipLaunchKernelGGL(pack_block_kernel<float>, grid, dim3(256), 0, st, a, s.D, s.FF);
+    // a workgroup never straddles two segments (its bias fold has a barrier): 256 threads, or the
+    // 128 sixteen-byte items of a bf16 segment at d = 32
+    const int threads = s.seg / 16 < 256 ? (int)(s.seg / 16) : 256;
+    const dim3 grid(cdiv(items, threads), n);
+    if (c->dtype == LONGER_BF16) hipLaunchKernelGGL(pack_block_kernel<__bf16>, grid, dim3(threads), 0, st, a, s.D, s.FF);
+    else hipLaunchKernelGGL(pack_block_kernel<float>, grid, dim3(threads), 0, st, a, s.D, s.FF);
     n = 0;
     return hipGetLastError() == hipSuccess ? 0 : fail(LONGER_ERR_HIP, "pack kernel launch failed");
   }

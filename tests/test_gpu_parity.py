@@ -174,15 +174,17 @@ def test_fp32_concat_merge_all_entry_points():
     _entry_points(case, TOL["f32"])
 
 
-def test_bf16_concat_merge_all_entry_points_and_serving():
-    """bf16, raw width 64, K = 4, main stack at 256 (the serving configuration's width)."""
-    cfg = synth.CONFIGS["C5"].replace(B=3, L=1000, K=4, k_recent=40, inner_layers=2, inner_heads=4, merge="concat",
-                                      ragged=True, len_lo=30, len_hi=1000, C=24, index=22)
+@pytest.mark.parametrize("K,inner_heads", [(4, 4), (8, 2)])
+def test_bf16_concat_merge_all_entry_points_and_serving(K, inner_heads):
+    """bf16, raw width 64 with K = 4, and the paper's typical raw width 32 (Section 3.4) with K = 8;
+    main stack at 256 (the serving configuration's width)."""
+    cfg = synth.CONFIGS["C5"].replace(B=3, L=1000, K=K, k_recent=40, inner_layers=2, inner_heads=inner_heads,
+                                      merge="concat", ragged=True, len_lo=30, len_hi=1000, C=24, index=22)
     case = synth.make_case(cfg, pad_value=float("nan"))
     case["lens"][0] = 1000
     case["H"][0] = synth.round_bf16(np.random.default_rng(8).standard_normal(case["H"][0].shape).astype(np.float32))
-    assert case["H"].shape[-1] == 64
-    _say("bf16 concat merge 64 x 4 -> 256")
+    assert case["H"].shape[-1] == 256 // K
+    _say("bf16 concat merge %d x %d -> 256" % (256 // K, K))
     _entry_points(case, TOL["bf16"])
     _serving(case, TOL["bf16"])
 
@@ -276,6 +278,11 @@ def test_c4_full_size_sampled_users():
     case = synth.make_case(synth.CONFIGS["C4"])
     shortest, longest = int(np.argmin(case["lens"])), int(np.argmax(case["lens"]))
     _full_size_forward("C4", sorted({0, shortest, longest, 511}), pad_value=float("nan"))
+
+
+def test_concat_production_shape_full_size_sampled_users():
+    _say("P1 full size (256 users, raw width 32, K = 8, main stack at 256)")
+    _full_size_forward("P1", [0, 131, 255])
 
 
 def test_c5_full_size_sampled_candidates():
