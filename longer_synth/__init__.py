@@ -62,6 +62,7 @@ class Config:
     len_lo: int = 0
     len_hi: int = 0
     C: int = 0             # candidates per user (serving config only)
+    k_uniform: int = 0     # of the k_recent query slots, how many are sampled uniformly from the older tokens
     merge: str = "mean"    # "mean": K outputs of a group pooled to one token of width d;
                            # "concat": raw tokens of width d / K, a group's K outputs concatenated
 

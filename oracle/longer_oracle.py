@@ -39,6 +39,10 @@ document as well):
   read literally) only globals with index >= its own;
 * "recent k" = merged tokens T_u-k .. T_u-1, right-aligned in k slots; slots
   with a negative index are invalid;  invalid rows are returned as zeros;
+  the other sampling strategies of Section 3.5.1 / the ablation table put
+  uniformly sampled older tokens into the first ``k_uniform`` slots (each the
+  newest token of one of k_uniform equal shares of the older tokens) and keep the
+  most recent ones in the rest; slots stay in chronological order;
 * the prediction head is logit = <head_w, flatten(Y[:m])> + head_b.
 
 Parity status: every function below is pinned by tests/test_oracle_*.py to a
@@ -187,11 +191,27 @@ def merged_len(length: int, K: int) -> int:
     return (int(length) + K - 1) // K
 
 
-def query_tokens(m: int, k: int, Tu: int):
-    """Descriptors of O = [G; most recent k merged tokens] (Eq. 5): slot i holds
-    merged index Tu - k + i, invalid when negative."""
+def slot_index(i: int, k: int, Tu: int, k_uniform: int = 0) -> int:
+    """Merged index held by slot i of the k sampled sequence tokens H_S (Section 3.5.1:
+    a predefined sampling strategy; the ablation compares the most recent k, uniformly
+    sampled tokens, and recent ones plus the rest sampled uniformly).  The last
+    k - k_uniform slots hold the most recent tokens; the first k_uniform slots are spread
+    evenly, oldest first, over the tokens before those, each holding the newest token of
+    its share.  A user with no more than k tokens gets all of them, right-aligned (a
+    negative index is an invalid slot)."""
+    if Tu <= k or i >= k_uniform:
+        return Tu - k + i
+    rest = Tu - (k - k_uniform)          # tokens older than the recent part; more than k_uniform of them
+    return ((i + 1) * rest) // k_uniform - 1
+
+
+def query_tokens(m: int, k: int, Tu: int, k_uniform: int = 0):
+    """Descriptors of O = [G; H_S] (Eq. 5): slot i holds merged index
+    ``slot_index(i, ...)`` (Tu - k + i for the default, most recent k), invalid when negative."""
     toks = [(True, a, True) for a in range(m)]
-    toks += [(False, Tu - k + i, (Tu - k + i) >= 0) for i in range(k)]
+    for i in range(k):
+        t = slot_index(i, k, Tu, k_uniform)
+        toks.append((False, t, t >= 0))
     return toks
 
 
@@ -265,7 +285,7 @@ def gather_queries(cfg, G_u: np.ndarray, M_u: np.ndarray, Tu: int) -> np.ndarray
     O = np.zeros((cfg.m + cfg.k_recent, d), dtype=F64)
     O[:cfg.m] = G_u
     for i in range(cfg.k_recent):
-        t = Tu - cfg.k_recent + i
+        t = slot_index(i, cfg.k_recent, Tu, getattr(cfg, "k_uniform", 0))
         if t >= 0:
             O[cfg.m + i] = M_u[t]
     return O
@@ -287,7 +307,7 @@ def hybrid_cross_attn(cfg, cross_blk: dict, G: np.ndarray, M: np.ndarray, lens=N
         Mu = np.where((np.arange(T) < Tu)[:, None], M[u], 0.0)
         R = np.concatenate([G[u], Mu], axis=0)
         O = gather_queries(cfg, G[u], Mu, Tu)
-        qt = query_tokens(cfg.m, cfg.k_recent, Tu)
+        qt = query_tokens(cfg.m, cfg.k_recent, Tu, getattr(cfg, "k_uniform", 0))
         mask = _type_mask(qt, key_tokens(cfg.m, T, Tu), cfg.gmask)
         out = block(O, R, mask, blk, cfg.heads, cfg.ln_eps, cfg.act, probs_out)
         qvalid = np.array([t[2] for t in qt])
@@ -305,7 +325,7 @@ def self_attn_layer(cfg, blk: dict, X: np.ndarray, lens=None, L: Optional[int] =
     Y = np.zeros_like(X)
     for u in range(B):
         Tu = merged_len(lens[u], cfg.K)
-        toks = query_tokens(cfg.m, cfg.k_recent, Tu)
+        toks = query_tokens(cfg.m, cfg.k_recent, Tu, getattr(cfg, "k_uniform", 0))
         valid = np.array([t[2] for t in toks])
         Xu = np.where(valid[:, None], X[u], 0.0)
         mask = _type_mask(toks, toks, cfg.gmask)
@@ -353,7 +373,7 @@ def kv_cache_build(cfg, weights: dict, H: np.ndarray, lens=None) -> dict:
         Mu = np.where((np.arange(T) < Tu)[:, None], M[u], 0.0)
         # layer 0: keys are all merged tokens; queries are the k recent slots
         seq_keys = [(False, t, t < Tu) for t in range(T)]
-        slots = [(False, Tu - k + i, (Tu - k + i) >= 0) for i in range(k)]
+        slots = query_tokens(0, k, Tu, getattr(cfg, "k_uniform", 0))
         svalid = np.array([s[2] for s in slots])
         Kc, Vc = project_kv(Mu, blocks[0], cfg.ln_eps)
         cache["K"][0].append(Kc); cache["V"][0].append(Vc)
@@ -423,7 +443,8 @@ def algorithmic_flops(cfg, lens=None, B: Optional[int] = None, L: Optional[int] 
         kv = min(k, Tu)
         # cross layer: keys = m globals + Tu merged tokens; queries = m globals + kv slots
         gpairs = m * m if cfg.gmask == "full" else m * (m + 1) // 2
-        seqpairs = sum(Tu - kv + i + 1 for i in range(kv))
+        ku = getattr(cfg, "k_uniform", 0)
+        seqpairs = sum(slot_index(i, k, Tu, ku) + 1 for i in range(k - kv, k))
         cross += (m + Tu) * per_tok_kv + (m + kv) * per_tok_q + 4 * d * (gpairs + m * Tu + seqpairs)
         spairs = kv * (kv + 1) // 2
         selfl += (m + kv) * (per_tok_q + per_tok_kv) + 4 * d * (gpairs + m * kv + spairs)

@@ -387,6 +387,92 @@ def test_concat_forward_padding_and_cache_invariants():
         np.testing.assert_allclose(lgs[:, c], lc, rtol=1e-12, atol=1e-13)
 
 
+# --------------------------------------------------------------------------- query sampling strategies
+def test_uniform_slots_are_evenly_spaced_increasing_and_end_at_the_newest_older_token():
+    for Tu, k, ku in [(250, 100, 100), (250, 100, 50), (613, 64, 64), (101, 100, 37), (40, 8, 3)]:
+        idx = [orc.slot_index(i, k, Tu, ku) for i in range(k)]
+        r = k - ku
+        assert idx[ku:] == list(range(Tu - r, Tu))                   # the recent part
+        uni = np.array(idx[:ku])
+        rest = Tu - r
+        assert uni[-1] == rest - 1 and uni[0] >= 0 and (np.diff(uni) >= 1).all()
+        gaps = np.diff(np.concatenate([[-1], uni]))                  # share sizes
+        assert gaps.max() - gaps.min() <= 1 and gaps.sum() == rest
+    # closed form when the share size is a whole number: every (rest / ku)-th token
+    assert [orc.slot_index(i, 4, 20, 4) for i in range(4)] == [4, 9, 14, 19]
+    assert [orc.slot_index(i, 6, 23, 4) for i in range(6)] == [4, 9, 14, 20, 21, 22]
+    # no more tokens than slots: all of them, right-aligned, whatever the strategy
+    assert [orc.slot_index(i, 5, 3, 5) for i in range(5)] == [-2, -1, 0, 1, 2]
+    assert [orc.slot_index(i, 5, 5, 2) for i in range(5)] == [0, 1, 2, 3, 4]
+
+
+def test_sampled_queries_follow_the_scalar_rule_and_eq8():
+    """A uniformly sampled query sees exactly the keys Eq. 8 allows its token (mask rebuilt from the
+    printed rule in paper order); gather and mask against scalar loops."""
+    m, T, Tu, k, ku = 2, 11, 11, 4, 4
+    cfg = synth.tiny_config(B=1, L=T * 2, d=8, K=2, m=m, k_recent=k, k_uniform=ku, gmask="causal", heads=1)
+    q = orc.query_tokens(m, k, Tu, ku)
+    assert [t for (_, t, _) in q[m:]] == [1, 4, 7, 10]
+    keys = orc.key_tokens(m, T, Tu)
+    got = orc._type_mask(q, keys, "causal")
+    paper = _eq8_mask_paper_order(m, Tu)
+    pidx = lambda tok: tok[1] if tok[0] else m + (Tu - 1 - tok[1])
+    for qi, qq in enumerate(q):
+        for ki, kk in enumerate(keys):
+            exp = paper[pidx(qq), pidx(kk)] and not ((not qq[0]) and kk[0])
+            assert got[qi, ki] == exp
+    # the whole layer: each query row computed alone, one head, scalar softmax over its visible keys
+    blk = orc._f64(_blk(41, 8))
+    G = _rng(1).standard_normal((1, m, 8)); M = _rng(2).standard_normal((1, T, 8))
+    X = orc.hybrid_cross_attn(cfg, blk, G, M)
+    R = np.concatenate([G[0], M[0]], 0)
+    Rn = orc.layer_norm(R, blk["ln1_g"], blk["ln1_b"], 1e-5)
+    Kp, Vp = Rn @ blk["wk"] + blk["bk"], Rn @ blk["wv"] + blk["bv"]
+    for si, t in enumerate([1, 4, 7, 10]):
+        x = M[0, t]
+        qv = orc.layer_norm(x[None], blk["ln1_g"], blk["ln1_b"], 1e-5)[0] @ blk["wq"] + blk["bq"]
+        vis = [m + tt for tt in range(t + 1)]                         # own past and itself, no globals
+        sc = np.array([qv @ Kp[j] / math.sqrt(8) for j in vis])
+        pr = np.exp(sc - sc.max()); pr /= pr.sum()
+        a = sum(pj * Vp[j] for pj, j in zip(pr, vis))
+        y = x + a @ blk["wo"] + blk["bo"]
+        h = orc.activation(orc.layer_norm(y[None], blk["ln2_g"], blk["ln2_b"], 1e-5)[0] @ blk["w1"] + blk["b1"], "gelu_erf")
+        y = y + h @ blk["w2"] + blk["b2"]
+        np.testing.assert_allclose(X[0, m + si], y, rtol=1e-11, atol=1e-12)
+
+
+def test_sampling_strategies_reduce_to_recent_and_keep_the_invariants():
+    base = synth.tiny_config(B=2, L=46, d=8, K=2, m=2, k_recent=6, n_self=2)
+    w, H, G = _case(base)
+    lens = np.array([46, 9])                 # second user: 5 merged tokens < 6 slots
+    Y0, l0 = orc.forward(base, w, H, G, lens)
+    Yz, lz = orc.forward(base.replace(k_uniform=0), w, H, G, lens)
+    assert np.array_equal(Y0, Yz)
+    for ku in (6, 3):
+        cfg = base.replace(k_uniform=ku)
+        Y, lgt = orc.forward(cfg, w, H, G, lens)
+        assert not np.allclose(Y[0], Y0[0])
+        assert np.array_equal(Y[1], Y0[1])   # a user with no more tokens than slots keeps all of them
+        # a sampled row does not change when tokens newer than its own token change
+        t_first = orc.slot_index(0, 6, 23, ku)
+        H2 = H.copy(); H2[0, 2 * (t_first + 1):] += _rng(9).standard_normal(H2[0, 2 * (t_first + 1):].shape)
+        Y2, _ = orc.forward(cfg, w, H2, G, lens)
+        assert np.array_equal(Y2[0, cfg.m], Y[0, cfg.m]) and not np.allclose(Y2[0, cfg.m + 1], Y[0, cfg.m + 1])
+        # serving: cached scoring equals the full pass
+        Gc = _rng(4).standard_normal((2, 2, cfg.m, cfg.d))
+        cache = orc.kv_cache_build(cfg, w, H, lens)
+        Yg, lgs = orc.score_candidates(cfg, w, cache, Gc)
+        for c in range(2):
+            Yc, lc = orc.forward(cfg, w, H, Gc[:, c], lens)
+            np.testing.assert_allclose(Yg[:, c], Yc[:, :cfg.m], rtol=1e-12, atol=1e-13)
+    # every token sampled (k = T_u): the cross layer is a self layer, for any split
+    cfgT = synth.tiny_config(B=2, L=16, d=8, K=4, m=2, k_recent=4, k_uniform=4)
+    blk = _blk(3, 8)
+    Gt = _rng(1).standard_normal((2, 2, 8)); Mt = _rng(2).standard_normal((2, 4, 8))
+    np.testing.assert_allclose(orc.hybrid_cross_attn(cfgT, blk, Gt, Mt),
+                               orc.self_attn_layer(cfgT, blk, np.concatenate([Gt, Mt], 1)), rtol=1e-13, atol=1e-14)
+
+
 def test_I2_all_tokens_as_queries_is_self_attention():
     for gm in ("full", "causal"):
         cfg = synth.tiny_config(B=2, L=16, d=8, K=4, m=2, k_recent=4, gmask=gm)      # k = T
