@@ -77,6 +77,12 @@ typedef struct {
   float   ln_eps;
   int32_t dtype;    /* longer_dtype */
   int32_t merge;    /* longer_merge */
+  int32_t k_uniform; /* query sampling (Section 3.5.1): 0 = the k_recent most recent merged tokens (Eq. 5
+                        as evaluated); k_uniform > 0: the first k_uniform query slots hold uniformly
+                        sampled older tokens (slot i the newest token of the i-th of k_uniform equal
+                        shares of the tokens before the recent part), the other k_recent - k_uniform
+                        slots the most recent ones; k_uniform = k_recent samples all slots uniformly.
+                        A user with no more than k_recent merged tokens gets all of them either way. */
 } longer_config;
 
 /* One pre-LayerNorm transformer block: 12 d^2 + 13 d scalars for ffn_mult = 4 (Eq. 3).

@@ -26,7 +26,7 @@ class CConfig(ctypes.Structure):
                 ("m", ctypes.c_int32), ("K", ctypes.c_int32), ("k_recent", ctypes.c_int32),
                 ("n_self", ctypes.c_int32), ("inner_layers", ctypes.c_int32), ("inner_heads", ctypes.c_int32),
                 ("act", ctypes.c_int32), ("gmask", ctypes.c_int32), ("ln_eps", ctypes.c_float),
-                ("dtype", ctypes.c_int32), ("merge", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("merge", ctypes.c_int32), ("k_uniform", ctypes.c_int32)]
 
 
 class CBlock(ctypes.Structure):
@@ -101,7 +101,7 @@ def make_config(cfg) -> CConfig:
     return CConfig(d=cfg.d, heads=cfg.heads, ffn_mult=cfg.ffn_mult, m=cfg.m, K=cfg.K, k_recent=cfg.k_recent,
                    n_self=cfg.n_self, inner_layers=cfg.inner_layers, inner_heads=cfg.inner_heads,
                    act=_ACT[cfg.act], gmask=_GMASK[cfg.gmask], ln_eps=cfg.ln_eps, dtype=_DTYPE[cfg.dtype],
-                   merge=_MERGE[getattr(cfg, "merge", "mean")])
+                   merge=_MERGE[getattr(cfg, "merge", "mean")], k_uniform=getattr(cfg, "k_uniform", 0))
 
 
 def _ptr(t) -> Optional[int]:

@@ -47,7 +47,8 @@ struct BlockParams {
   RowSrc src0, src1;
   int m0;
   int rows_per_user, tiles_per_user;
-  int gather_recent;    // src1 row of slot i is T_u - k + i (cross layer) instead of i
+  int gather_recent;    // src1 row of slot i is its sampled merged token (cross layer) instead of i
+  int k_uni;            // the first k_uni of the k slots hold uniformly sampled older tokens
   int q0;               // MODE_ATTN: first query row (0: globals + slots, m: slots only)
   // stored K/V fragments: per user kt_per_user key tiles of NT*GPT fragments each
   char* kst; char* vst;
@@ -171,6 +172,16 @@ __device__ __forceinline__ float gelu_fn(float x) {
   float phi;
   asm("v_fma_f32 %0, %1, %2, 0.5 clamp" : "=v"(phi) : "v"(x), "v"(pl));
   return x * phi;
+}
+
+// Merged token held by slot i of the k sampled sequence queries of a user with tu merged tokens
+// (Section 3.5.1): the last k - k_uni slots hold the most recent tokens, the first k_uni slots the
+// newest token of each of k_uni equal shares of the older ones; a user with no more than k tokens
+// gets all of them, right-aligned (negative = invalid slot).
+__device__ __forceinline__ int slot_token(int i, int k, int tu, int k_uni) {
+  if (tu <= k || i >= k_uni) return tu - k + i;
+  const long long rest = tu - (k - k_uni);
+  return (int)(((long long)(i + 1) * rest) / k_uni) - 1;
 }
 
 // LayerNorm over the feature dimension of TT token tiles, result as B-operand groups.
@@ -440,7 +451,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       const void* sp = glob ? p.src0.p : p.src1.p;
       const int sf = glob ? p.src0.f32 : p.src1.f32;
       const long long su = glob ? p.src0.ustride : p.src1.ustride;
-      const int row = glob ? a : (p.gather_recent ? tu - p.k + i : i);
+      const int tok = glob ? 0 : slot_token(i, p.k, tu, p.k_uni);
+      const int row = glob ? a : (p.gather_recent ? tok : i);
       load_rows<T, NT>(resid[tt], sp, sf, su * u + (long long)row * D, valid[tt], hi);
       // visible key ranges (Eq. 8 by token type)
       const int s0 = p.key_self ? i0 : 0;
@@ -449,7 +461,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
         lo2[tt] = p.KG + s0; hi2[tt] = p.KG + (p.key_self ? p.k : tu);
       } else {
         lo1[tt] = 0; hi1[tt] = 0;
-        lo2[tt] = p.KG + s0; hi2[tt] = p.KG + (p.key_self ? i : tu - p.k + i) + 1;
+        lo2[tt] = p.KG + s0; hi2[tt] = p.KG + (p.key_self ? i : tok) + 1;
       }
       if (!valid[tt]) { hi1[tt] = lo1[tt]; hi2[tt] = lo2[tt]; }
       kthi[tt] = (p.KG + (p.key_self ? p.k : tu) + 31) / 32;

@@ -233,6 +233,7 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
   if (c->K <= 0 || 32 % c->K) return fail(LONGER_ERR_ARG, "K=%d must divide 32", c->K);
   if (c->m <= 0 || 32 % c->m) return fail(LONGER_ERR_ARG, "m=%d must divide 32", c->m);
   if (c->k_recent <= 0) return fail(LONGER_ERR_ARG, "k_recent=%d", c->k_recent);
+  if (c->k_uniform < 0 || c->k_uniform > c->k_recent) return fail(LONGER_ERR_ARG, "k_uniform=%d must lie in [0, k_recent]", c->k_uniform);
   if (c->n_self < 0 || c->inner_layers < 0 || c->n_self + c->inner_layers + 1 > 32)
     return fail(LONGER_ERR_ARG, "layer counts out of range");
   s->D = c->d; s->FF = c->ffn_mult * c->d; s->es = c->dtype == LONGER_BF16 ? 2 : 4;
@@ -372,7 +373,7 @@ static BlockParams base_params(const longer_config* c, const Shape& s, const int
   p.n_layers = 1; p.FF = s.FF; p.eps = c->ln_eps;
   p.scale_l2e = (float)(1.4426950408889634 / std::sqrt((double)DH));
   p.act = c->act; p.gmask_causal = c->gmask == LONGER_GMASK_CAUSAL;
-  p.lens = lens; p.B = B; p.L = L; p.K = c->K; p.T = cdiv(L, c->K); p.m = c->m; p.k = c->k_recent;
+  p.lens = lens; p.B = B; p.L = L; p.K = c->K; p.T = cdiv(L, c->K); p.m = c->m; p.k = c->k_recent; p.k_uni = c->k_uniform;
   return p;
 }
 

@@ -40,7 +40,7 @@ def test_size_queries():
 
 
 @pytest.mark.parametrize("field,value", [("d", 48), ("heads", 3), ("K", 5), ("m", 3), ("dtype", 7), ("act", 9),
-                                         ("gmask", 2), ("ln_eps", 0.0), ("ffn_mult", 0), ("merge", 2)])
+                                         ("gmask", 2), ("ln_eps", 0.0), ("ffn_mult", 0), ("merge", 2), ("k_uniform", 101), ("k_uniform", -1)])
 def test_bad_config_is_rejected(field, value):
     cfg = lg.make_config(synth.CONFIGS["C3"])
     setattr(cfg, field, value)

@@ -189,6 +189,38 @@ def test_bf16_concat_merge_all_entry_points_and_serving(K, inner_heads):
     _serving(case, TOL["bf16"])
 
 
+@pytest.mark.parametrize("k_uniform", [9, 4])
+def test_fp32_sampled_query_slots(k_uniform):
+    """Uniformly sampled query slots (all 9, or 4 older ones + the 5 most recent), ragged users
+    including one with fewer merged tokens than slots and one of length 0; serving as well."""
+    cfg = synth.CONFIGS["C1"].replace(B=5, L=70, k_recent=9, k_uniform=k_uniform, n_self=2, C=6,
+                                      ragged=True, len_lo=1, len_hi=70, index=23)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"] = np.array([70, 0, 13, 29, 41], dtype=np.int32)
+    H = np.random.default_rng(10).standard_normal(case["H"].shape).astype(np.float32)
+    pos = np.arange(cfg.L)[None, :, None]
+    case["H"] = np.where(pos < case["lens"][:, None, None], H, np.float32("nan")).astype(np.float32)
+    _say("fp32 sampled query slots, k_uniform=%d of 9" % k_uniform)
+    _entry_points(case, TOL["f32"], with_inner=False)
+    _serving(case, TOL["f32"])
+
+
+@pytest.mark.parametrize("k_recent,k_uniform", [(100, 100), (100, 50), (150, 75)])
+def test_bf16_sampled_query_slots(k_recent, k_uniform):
+    """The ablation's strategies at its query count: uniform 100, recent 50 + uniform 50 (one
+    workgroup per user runs the whole reduced stack), and 150 slots (one launch pair per layer)."""
+    cfg = synth.CONFIGS["C2"].replace(B=6, L=2000, K=8, m=4, k_recent=k_recent, k_uniform=k_uniform, n_self=2,
+                                      ragged=True, len_lo=40, len_hi=2000, C=10, index=24)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"][0] = 2000
+    case["lens"][1] = 300          # 38 merged tokens < slots
+    case["H"][0] = synth.round_bf16(np.random.default_rng(11).standard_normal(case["H"][0].shape).astype(np.float32))
+    case["H"][1, 300:] = np.nan
+    _say("bf16 sampled query slots, k=%d, k_uniform=%d" % (k_recent, k_uniform))
+    _entry_points(case, TOL["bf16"], with_inner=False)
+    _serving(case, TOL["bf16"])
+
+
 def test_c2_bf16_all_entry_points():
     _say("C2 bf16 (16 users)")
     _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
