@@ -184,6 +184,22 @@ __device__ __forceinline__ int slot_token(int i, int k, int tu, int k_uni) {
   return (int)(((long long)(i + 1) * rest) / k_uni) - 1;
 }
 
+// Scheduling hint for a stretch of N MFMAs that each consume one weight fragment read from LDS
+// (plus EXTRA other LDS reads ahead of them, e.g. a bias tile): the first AHEAD fragment reads go
+// out together, then one read per MFMA, so that an MFMA never waits out the LDS latency of its
+// own fragment.  Used by the kernels that run one wave per SIMD, where no other wave hides it.
+template <int N, int EXTRA>
+__device__ __forceinline__ void frag_pipeline_hint() {
+  constexpr int AHEAD = N < 6 ? N : 6;
+  __builtin_amdgcn_sched_group_barrier(0x100, EXTRA + AHEAD, 0);
+#pragma unroll
+  for (int i = 0; i < N - AHEAD; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, AHEAD, 0);
+}
+
 // LayerNorm over the feature dimension of TT token tiles, result as B-operand groups.
 // fp32 mode takes the variance in a second pass over the centred values; bf16 mode uses
 // E[x^2] - mean^2 in one pass (the result is rounded to bf16 anyway).
@@ -364,6 +380,11 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   constexpr bool EXT = (MODE == MODE_ATTN || MODE == MODE_SCORE);
   constexpr bool STACK = MODE == MODE_STACK;
   constexpr bool ATTNLIKE = MODE == MODE_ATTN || STACK;   // rows are [globals; recent slots] of a user
+  // kernels that run one wave per SIMD, where no other wave hides the LDS latency of a weight
+  // fragment: the d <= 128 stack kernel takes scheduling hints (frag_pipeline_hint); at d = 256 the
+  // compiler ignores them under its register pressure and the reads are placed ahead by hand
+  constexpr bool PIPE = sizeof(T) == 2 && TT == 1 && STACK && D < 256;
+  constexpr bool MANUAL = sizeof(T) == 2 && TT == 1 && D >= 256;
   constexpr bool BIGSEG = SEGV * 16 >= 16384;
   constexpr int PSEG = BIGSEG ? 1 : 4;              // segments per panel of the weight stream (one barrier per panel)
   constexpr int NB = BIGSEG ? 6 : 2;                // ring depth in panels
@@ -509,6 +530,28 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   // layout, each followed by the unused segment that fills its slot in the packed buffer
   ws.init(lds, p.wbase, STACK ? steps + (p.n_layers - 1) * (2 + 4 * NT + 2 * NC) : steps * p.n_layers);
 
+  // hands the NG weight fragments of the current segment to use(s, w) one by one; MANUAL keeps
+  // AH reads in flight in front of the MFMA that is being issued (the order is pinned)
+  auto for_frags = [&](auto&& use) {
+    if constexpr (!MANUAL) {
+#pragma unroll
+      for (int s = 0; s < NG; ++s) use(s, ws.template frag<grp>(s));
+    } else {
+      constexpr int AH = 4;
+      grp ring[AH];
+#pragma unroll
+      for (int s = 0; s < AH; ++s) ring[s] = ws.template frag<grp>(s);
+#pragma unroll
+      for (int s = 0; s < NG; ++s) {
+        __builtin_amdgcn_sched_barrier(0);
+        use(s, ring[s % AH]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (s + AH < NG) ring[s % AH] = ws.template frag<grp>(s + AH);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   for (int layer = 0; layer < p.n_layers; ++layer) {
     // the block's first segment holds its fp32 vectors: keep a copy for the whole layer
     // (barriers: nobody still reads the previous block's copy; everybody sees the new one)
@@ -533,32 +576,29 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       if (MODE != MODE_KVPROJ) {
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) aq[tt] = bias_tile(vec + vl.bq(), ft, hi);
-#pragma unroll
-        for (int s = 0; s < NG; ++s) {
-          const grp w = ws.template frag<grp>(s);
+        for_frags([&](int s, const grp w) {
 #pragma unroll
           for (int tt = 0; tt < TT; ++tt) aq[tt] = E::mma(w, xn[tt][s], aq[tt]);
-        }
+        });
+        if (PIPE) frag_pipeline_hint<NG, 4>();
         ws.advance();
       }
       if (FUSED || MODE == MODE_KVPROJ || selfl) {
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) ak[tt] = splat16(0.f);   // no b_K: a per-query constant in the scores, softmax drops it
-#pragma unroll
-        for (int s = 0; s < NG; ++s) {
-          const grp w = ws.template frag<grp>(s);
+        for_frags([&](int s, const grp w) {
 #pragma unroll
           for (int tt = 0; tt < TT; ++tt) ak[tt] = E::mma(w, xn[tt][s], ak[tt]);
-        }
+        });
+        if (PIPE) frag_pipeline_hint<NG, 0>();
         ws.advance();
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) av[tt] = splat16(0.f);   // no b_V: probabilities sum to 1, so the pack kernel folds it into the output bias
-#pragma unroll
-        for (int s = 0; s < NG; ++s) {
-          const grp w = ws.template frag<grp>(s);
+        for_frags([&](int s, const grp w) {
 #pragma unroll
           for (int tt = 0; tt < TT; ++tt) av[tt] = E::mma(xn[tt][s], w, av[tt]);   // operands swapped: lane = feature
-        }
+        });
+        if (PIPE) frag_pipeline_hint<NG, 0>();
         ws.advance();
       }
       if (selfl) {
@@ -738,12 +778,11 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       const f32x16 bo = bias_tile(vec + vl.bo(), nt, hi);
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) resid[tt][nt] += bo;
-#pragma unroll
-      for (int s = 0; s < NG; ++s) {
-        const grp w = ws.template frag<grp>(s);
+      for_frags([&](int s, const grp w) {
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) resid[tt][nt] = E::mma(w, oop[tt][s], resid[tt][nt]);
-      }
+      });
+      if (PIPE) frag_pipeline_hint<NG, 4>();
       ws.advance();
     }
 
@@ -762,12 +801,11 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       f32x16 ah[TT];
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) ah[tt] = bias_tile(vec + vl.b1(), c, hi);
-#pragma unroll
-      for (int s = 0; s < NG; ++s) {
-        const grp w = ws.template frag<grp>(s);
+      for_frags([&](int s, const grp w) {
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) ah[tt] = E::mma(w, xn[tt][s], ah[tt]);
-      }
+      });
+      if (PIPE) frag_pipeline_hint<NG, 4>();
       ws.advance();
       // operand group by operand group: the second GEMM's MFMAs that use group g (one per
       // output tile, independent accumulators) only need the activation of that group's
@@ -775,15 +813,37 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 #pragma unroll
       for (int g = 0; g < GPT; ++g) {
         grp hop[TT];
+        auto act_group = [&](int gg) {
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
+          for (int tt = 0; tt < TT; ++tt) {
 #pragma unroll
-          for (int e = 0; e < E::EPL; ++e) {
-            const float v = ah[tt][E::EPL * g + e];
-            ah[tt][E::EPL * g + e] = RELU ? fmaxf(v, 0.f) : gelu_fn<sizeof(T) == 4>(v);
+            for (int e = 0; e < E::EPL; ++e) {
+              const float v = ah[tt][E::EPL * gg + e];
+              ah[tt][E::EPL * gg + e] = RELU ? fmaxf(v, 0.f) : gelu_fn<sizeof(T) == 4>(v);
+            }
+            hop[tt] = E::pack(ah[tt], gg);
           }
-          hop[tt] = E::pack(ah[tt], g);
+        };
+        if constexpr (MANUAL) {
+          // the wide kernels: the group's first fragments are requested before its activation
+          // (their latency passes under the VALU work), the rest a fixed distance ahead
+          constexpr int AH = 4;
+          grp ring[AH];
+#pragma unroll
+          for (int nt = 0; nt < AH; ++nt) ring[nt] = ws.template frag<grp>(nt * GPT + g);
+          __builtin_amdgcn_sched_barrier(0);
+          act_group(g);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            __builtin_amdgcn_sched_barrier(0);
+            resid[0][nt] = E::mma(ring[nt % AH], hop[0], resid[0][nt]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (nt + AH < NT) ring[nt % AH] = ws.template frag<grp>((nt + AH) * GPT + g);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          continue;
         }
+        act_group(g);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
           const grp w = ws.template frag<grp>(nt * GPT + g);
@@ -791,7 +851,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
           for (int tt = 0; tt < TT; ++tt) resid[tt][nt] = E::mma(w, hop[tt], resid[tt][nt]);
         }
       }
-      if (sizeof(T) == 2 && TT == 1 && !RELU) {
+      if (sizeof(T) == 2 && TT == 1 && !RELU && !MANUAL) {
         // order within this stretch: activation of group 0, the weight fragments, then each
         // MFMA of group 0 followed by a quarter of group 1's activation, then group 1's MFMAs
         __builtin_amdgcn_sched_group_barrier(0x002, 60, 0);
