@@ -26,7 +26,7 @@
  *   - rows of invalid tokens (padded raw tokens, merged tokens past T_u = ceil(len/K),
  *     recent-query slots with a negative merged index) are written as exact zeros.
  *
- * Supported shapes: bf16 with d in {64, 128, 256} and head width d/heads in {16, 32};
+ * Supported shapes: bf16 with d in {32, 64, 128, 256} and head width d/heads in {16, 32};
  * fp32 with d in {32, 64} and head width 16; K and m must divide 32 (K for the merge,
  * m for candidate scoring); ffn hidden width ffn_mult*d a multiple of 32.  With
  * LONGER_MERGE_CONCAT the InnerTrans width d / K must be one of these widths too.

@@ -221,6 +221,18 @@ def test_bf16_sampled_query_slots(k_recent, k_uniform):
     _serving(case, TOL["bf16"])
 
 
+def test_bf16_d32_all_entry_points_and_serving():
+    """The narrowest bf16 width (the paper's typical raw width, Section 3.4) through every entry point."""
+    cfg = synth.CONFIGS["C1"].replace(B=6, L=200, dtype="bf16", k_recent=20, n_self=2, inner_layers=2, C=12,
+                                      ragged=True, len_lo=3, len_hi=200, index=25)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"][0] = 200
+    case["H"][0] = synth.round_bf16(np.random.default_rng(12).standard_normal(case["H"][0].shape).astype(np.float32))
+    _say("bf16 d=32")
+    _entry_points(case, TOL["bf16"])
+    _serving(case, TOL["bf16"])
+
+
 def test_c2_bf16_all_entry_points():
     _say("C2 bf16 (16 users)")
     _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
