@@ -26,10 +26,13 @@
  *   - rows of invalid tokens (padded raw tokens, merged tokens past T_u = ceil(len/K),
  *     recent-query slots with a negative merged index) are written as exact zeros.
  *
- * Supported shapes: bf16 with d in {32, 64, 128, 256} and head width d/heads in {16, 32};
- * fp32 with d in {32, 64} and head width 16; K and m must divide 32 (K for the merge,
- * m for candidate scoring); ffn hidden width ffn_mult*d a multiple of 32.  With
- * LONGER_MERGE_CONCAT the InnerTrans width d / K must be one of these widths too.
+ * Supported shapes, as (width, head width = width / heads): bf16 (32, 16), (64, 16), (128, 16),
+ * (256, 32); fp32 (32, 16), (64, 16).  The pair is checked for the main stack (d, d / heads) and
+ * for the InnerTrans blocks (their width, that width / inner_heads) separately; with
+ * LONGER_MERGE_CONCAT the InnerTrans width is d / K.  K and m must divide 32 (K for the merge,
+ * m for candidate scoring); the FFN hidden width is ffn_mult * width with (9 + ffn_mult) * width
+ * fp32 values fitting one 32-row weight segment (ffn_mult <= 7 in bf16, <= 23 in fp32).
+ * Anything else returns LONGER_ERR_ARG.
  *
  * Mask (Eq. 8, applied by token type on chronologically stored data): a sequence query
  * sees sequence keys that are not newer than itself and never a global key; a global
