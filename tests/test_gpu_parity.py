@@ -233,6 +233,13 @@ def test_bf16_d32_all_entry_points_and_serving():
     _serving(case, TOL["bf16"])
 
 
+@pytest.mark.parametrize("base,ffn_mult,users", [("C1", 2, None), ("C2", 6, 6)])
+def test_ffn_width_other_than_4d(base, ffn_mult, users):
+    cfg = synth.CONFIGS[base].replace(ffn_mult=ffn_mult, index=26)
+    _say("%s with FFN width %d d" % (base, ffn_mult))
+    _entry_points(synth.make_case(cfg, users=users), TOL[cfg.dtype])
+
+
 def test_c2_bf16_all_entry_points():
     _say("C2 bf16 (16 users)")
     _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
