@@ -26,8 +26,8 @@
  *   - rows of invalid tokens (padded raw tokens, merged tokens past T_u = ceil(len/K),
  *     recent-query slots with a negative merged index) are written as exact zeros.
  *
- * Supported shapes, as (width, head width = width / heads): bf16 (32, 16), (64, 16), (128, 16),
- * (256, 32); fp32 (32, 16), (64, 16).  The pair is checked for the main stack (d, d / heads) and
+ * Supported shapes, as (width, head width = width / heads): bf16 (32, 16), (64, 16), (64, 32),
+ * (128, 16), (128, 32), (256, 16), (256, 32); fp32 (32, 16), (64, 16).  The pair is checked for the main stack (d, d / heads) and
  * for the InnerTrans blocks (their width, that width / inner_heads) separately; with
  * LONGER_MERGE_CONCAT the InnerTrans width is d / K.  K and m must divide 32 (K for the merge,
  * m for candidate scoring); the FFN hidden width is ffn_mult * width with (9 + ffn_mult) * width

@@ -15,6 +15,9 @@ template <> int launch_block<__bf16, 32, 16>(int, int, int, const BlockParams&, 
 template <> int launch_block<__bf16, 64, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_block<__bf16, 128, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_block<__bf16, 256, 32>(int, int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<__bf16, 64, 32>(int, int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<__bf16, 128, 32>(int, int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<__bf16, 256, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_block<float, 32, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_block<float, 64, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 
@@ -26,6 +29,9 @@ static launch_fn find_launch(int dtype, int D, int DH) {
     if (D == 64 && DH == 16) return &launch_block<__bf16, 64, 16>;
     if (D == 128 && DH == 16) return &launch_block<__bf16, 128, 16>;
     if (D == 256 && DH == 32) return &launch_block<__bf16, 256, 32>;
+    if (D == 64 && DH == 32) return &launch_block<__bf16, 64, 32>;
+    if (D == 128 && DH == 32) return &launch_block<__bf16, 128, 32>;
+    if (D == 256 && DH == 16) return &launch_block<__bf16, 256, 16>;
   } else if (dtype == LONGER_F32) {
     if (D == 32 && DH == 16) return &launch_block<float, 32, 16>;
     if (D == 64 && DH == 16) return &launch_block<float, 64, 16>;

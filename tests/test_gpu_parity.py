@@ -240,6 +240,19 @@ def test_ffn_width_other_than_4d(base, ffn_mult, users):
     _entry_points(synth.make_case(cfg, users=users), TOL[cfg.dtype])
 
 
+@pytest.mark.parametrize("d,heads,K", [(64, 2, 8), (128, 4, 8), (256, 16, 16)])
+def test_bf16_other_head_widths(d, heads, K):
+    """Head width 32 at d = 64 and 128, head width 16 at d = 256 (main stack and InnerTrans)."""
+    cfg = synth.CONFIGS["C2"].replace(B=4, L=640, d=d, heads=heads, inner_heads=heads, K=K, m=8, k_recent=40, n_self=2,
+                                      C=8, ragged=True, len_lo=50, len_hi=640, index=27)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"][0] = 640
+    case["H"][0] = synth.round_bf16(np.random.default_rng(13).standard_normal(case["H"][0].shape).astype(np.float32))
+    _say("bf16 d=%d, %d heads of width %d" % (d, heads, d // heads))
+    _entry_points(case, TOL["bf16"])
+    _serving(case, TOL["bf16"])
+
+
 def test_c2_bf16_all_entry_points():
     _say("C2 bf16 (16 users)")
     _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
