@@ -169,8 +169,8 @@ __device__ __forceinline__ float gelu_fn(float x) {
   pl = fmaf(pl, u, 0.0064495445928312006f);
   pl = fmaf(pl, u, -0.05893596715178192f);
   pl = fmaf(pl, u, 0.3934098519357524f);
-  float phi;
-  asm("v_fma_f32 %0, %1, %2, 0.5 clamp" : "=v"(phi) : "v"(x), "v"(pl));
+  // (the compiler folds the median with 0 and 1 into the FMA's clamp modifier)
+  const float phi = __builtin_amdgcn_fmed3f(fmaf(x, pl, 0.5f), 0.f, 1.f);
   return x * phi;
 }
 
