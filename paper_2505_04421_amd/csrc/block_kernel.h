@@ -760,7 +760,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
         f32x16 o;
         float inv[HPT];
 #pragma unroll
-        for (int hh = 0; hh < HPT; ++hh) inv[hh] = lrun[hh] > 0.f ? 1.0f / lrun[hh] : 0.f;
+        for (int hh = 0; hh < HPT; ++hh)   // (bf16 mode: the hardware reciprocal, 1 ulp, instead of the exact division)
+          inv[hh] = lrun[hh] > 0.f ? (sizeof(T) == 4 ? 1.0f / lrun[hh] : __builtin_amdgcn_rcpf(lrun[hh])) : 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int hh = HPT == 1 ? 0 : r / 8;

@@ -144,6 +144,14 @@ __device__ __forceinline__ void gload_lds16(const void* g, unsigned lds_wave_bas
                "global_load_lds_dwordx4 %0, off\n\t"
                :: "v"(g), "s"(lds_wave_base) : "memory");
 }
+// The same with the global address given as a wave-uniform base (scalar registers) plus a 32-bit
+// per-lane byte offset, so that advancing the base costs scalar instructions only.
+__device__ __forceinline__ void gload_lds16(const void* g_uniform, unsigned lane_off, unsigned lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %2\n\t"
+               "s_nop 0\n\t"
+               "global_load_lds_dwordx4 %0, %1\n\t"
+               :: "v"(lane_off), "s"(g_uniform), "s"(lds_wave_base) : "memory");
+}
 
 // wait until at most N vector-memory operations of this wave are outstanding
 template <int N>
@@ -165,7 +173,8 @@ struct WStream {
   static constexpr int NPRE = NB - 1;
   static_assert(PANV % kThreads == 0 && NSTAGE >= 1, "panel must cover all threads");
   uint4* lds;
-  const uint4* gnext;    // this thread's 16 bytes of the next panel to fetch
+  const char* gnext;     // the next panel to fetch (wave-uniform); this thread takes the 16 bytes at lane_off
+  unsigned lane_off;
   unsigned lds_wave;     // LDS byte address of this wave's first 16-byte slot in ring buffer 0
   int total, step, sub, issued, slot_issue, slot_cur, lane;   // total / step / issued count panels
 
@@ -173,8 +182,14 @@ struct WStream {
     if (issued < total) {
       const unsigned dst = lds_wave + (unsigned)slot_issue * (PANV * 16);
 #pragma unroll
-      for (int i = 0; i < NSTAGE; ++i) gload_lds16(gnext + kThreads * i, dst + kThreads * 16 * i);
-      gnext += PANV;
+      for (int i = 0; i < NSTAGE; ++i) {
+        // multi-segment panels (d <= 128, two waves per SIMD): scalar base + lane offset keeps the
+        // address arithmetic off the VALU (-2.6 % on the merge kernel); the single-segment panels of
+        // the one-wave d = 256 kernels were 1 % faster with per-lane 64-bit addresses
+        if (PSEG > 1) gload_lds16(gnext + kThreads * 16 * i, lane_off, dst + kThreads * 16 * i);
+        else gload_lds16(gnext + kThreads * 16 * i + lane_off, dst + kThreads * 16 * i);
+      }
+      gnext += PANV * 16;
       ++issued;
       slot_issue = slot_issue + 1 == NB ? 0 : slot_issue + 1;
     }
@@ -185,7 +200,8 @@ struct WStream {
     lds = lds_; total = (total_segments + PSEG - 1) / PSEG; step = 0; sub = 0; issued = 0; slot_issue = 0; slot_cur = 0;
     const int tid = threadIdx.x;
     lane = tid & 63;
-    gnext = reinterpret_cast<const uint4*>(gbase) + tid;
+    gnext = reinterpret_cast<const char*>(gbase);
+    lane_off = (unsigned)tid * 16u;
     lds_wave = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)lds_ + (unsigned)(tid >> 6) * 1024u);
 #pragma unroll
     for (int s = 0; s < NB; ++s) issue();
