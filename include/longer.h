@@ -8,8 +8,9 @@
  * Eq. 9-10) and the two-stage KV-cache serving path of Section 3.6.3.
  *
  * Conventions (all entry points)
- *   - every tensor pointer is a DEVICE pointer owned by the caller; the config and weight
- *     structs themselves live in HOST memory and hold device pointers;
+ *   - every tensor pointer is a DEVICE pointer owned by the caller, 16-byte aligned for the
+ *     activations (H, G, M, X, Y, G_cand, Yg); the config and weight structs themselves live in
+ *     HOST memory and hold device pointers;
  *   - tensors are dense row-major; weights are stored [in, out] so that y = x W + b, the
  *     way Eq. 6 writes Q = O W_Q; element type is `dtype` of the config (fp32 or bf16)
  *     for every activation, weight, bias and LayerNorm vector; logits are always fp32;

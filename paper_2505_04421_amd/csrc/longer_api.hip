@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <initializer_list>
 #include <cstring>
 
 namespace longer {
@@ -383,6 +384,13 @@ static BlockParams base_params(const longer_config* c, const Shape& s, const int
   return p;
 }
 
+// rows are read and written with 8- and 16-byte vector accesses
+static int check_aligned(std::initializer_list<const void*> ptrs) {
+  for (const void* q : ptrs)
+    if (((uintptr_t)q & 15) != 0) return fail(LONGER_ERR_ARG, "tensor pointers must be 16-byte aligned");
+  return 0;
+}
+
 static int check_common(const void* ws, size_t ws_bytes, size_t need, int B, int L) {
   if (B <= 0 || L <= 0) return fail(LONGER_ERR_ARG, "B=%d, L=%d must be positive", B, L);
   if (!ws) return fail(LONGER_ERR_ARG, "workspace is NULL");
@@ -496,6 +504,7 @@ static int merge_entry(const longer_config* cfg, const longer_block* inner, cons
   int rc = check_cfg(cfg, &s, true, false);
   if (rc) return rc;
   if (!inner || !H || (!M_out && !Z_out)) return fail(LONGER_ERR_ARG, "NULL argument");
+  if ((rc = check_aligned({H, M_out, Z_out}))) return rc;
   const Layout l = make_layout(cfg, s, B, L);
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
@@ -560,6 +569,7 @@ int longer_hybrid_cross_attn(const longer_config* cfg, const longer_block* cross
   int rc = check_cfg(cfg, &s, false, true);
   if (rc) return rc;
   if (!cross || !G || !M || !X_out) return fail(LONGER_ERR_ARG, "NULL argument");
+  if ((rc = check_aligned({G, M, X_out}))) return rc;
   const Layout l = make_layout(cfg, s, B, L);
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
@@ -578,6 +588,7 @@ int longer_self_attn_layer(const longer_config* cfg, const longer_block* blk, co
   int rc = check_cfg(cfg, &s, false, true);
   if (rc) return rc;
   if (!blk || !X_in || !X_out || X_in == X_out) return fail(LONGER_ERR_ARG, "NULL or aliased argument");
+  if ((rc = check_aligned({X_in, X_out}))) return rc;
   const Layout l = make_layout(cfg, s, B, L);
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
@@ -602,6 +613,7 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
   if (rc) return rc;
   if ((rc = check_weights(cfg, w))) return rc;
   if (!H || !G || !Y_out) return fail(LONGER_ERR_ARG, "NULL argument");
+  if ((rc = check_aligned({H, G, Y_out}))) return rc;
   const Layout l = make_layout(cfg, s, B, L);
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
@@ -654,6 +666,7 @@ int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, con
   if (rc) return rc;
   if ((rc = check_weights(cfg, w))) return rc;
   if (!H || !cache) return fail(LONGER_ERR_ARG, "NULL argument");
+  if ((rc = check_aligned({H}))) return rc;
   if (((uintptr_t)cache & 255) != 0) return fail(LONGER_ERR_ARG, "cache must be 256-byte aligned");
   const Layout l = make_layout(cfg, s, U, L);
   if ((rc = check_common(ws, ws_bytes, l.total, U, L))) return rc;
@@ -717,6 +730,7 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
   if (rc) return rc;
   if (!w || !w->cross || (cfg->n_self > 0 && !w->self)) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
   if (!cache || !G_cand || (!Yg_out && !logits_out)) return fail(LONGER_ERR_ARG, "NULL argument");
+  if ((rc = check_aligned({G_cand, Yg_out}))) return rc;
   if (C <= 0) return fail(LONGER_ERR_ARG, "C=%d must be positive", C);
   const Layout l = make_layout(cfg, s, U, L);
   if ((rc = check_common(ws, ws_bytes, l.total, U, L))) return rc;
