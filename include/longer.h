@@ -33,7 +33,8 @@
  * LONGER_MERGE_CONCAT the InnerTrans width is d / K.  K and m must divide 32 (K for the merge,
  * m for candidate scoring); the FFN hidden width is ffn_mult * width with (9 + ffn_mult) * width
  * fp32 values fitting one 32-row weight segment (ffn_mult <= 7 in bf16, <= 23 in fp32).
- * Anything else returns LONGER_ERR_ARG.
+ * Anything else returns LONGER_ERR_ARG, and so does a call with B * ceil(L / K) * K >= 2^31 - 256
+ * raw token slots (the merge kernel indexes them in 32 bits; split the batch).
  *
  * Mask (Eq. 8, applied by token type on chronologically stored data): a sequence query
  * sees sequence keys that are not newer than itself and never a global key; a global

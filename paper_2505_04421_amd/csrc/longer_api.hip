@@ -399,6 +399,14 @@ static int check_common(const void* ws, size_t ws_bytes, size_t need, int B, int
   return 0;
 }
 
+// the merge kernel numbers its token slots (B * ceil(L / K) * K, rounded up to whole workgroups) in 32 bits
+static int check_slots(const longer_config* c, int B, int L) {
+  const long long slots = (long long)B * cdiv(L, c->K) * c->K;
+  if (slots + 32LL * 8 >= (1LL << 31))
+    return fail(LONGER_ERR_ARG, "B*ceil(L/K)*K = %lld token slots: at most 2^31 per call", slots);
+  return 0;
+}
+
 // -- stage launchers (packed parameters already in place) -----------------------------
 static int run_merge(const longer_config* c, const Shape& s, const char* packed, const void* H, const int32_t* lens,
                      int B, int L, void* M_out, int M_f32, void* Z_out, int Z_f32, hipStream_t st) {
@@ -507,6 +515,7 @@ static int merge_entry(const longer_config* cfg, const longer_block* inner, cons
   if ((rc = check_aligned({H, M_out, Z_out}))) return rc;
   const Layout l = make_layout(cfg, s, B, L);
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
+  if ((rc = check_slots(cfg, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
   const Shape si = inner_view(cfg, s);
@@ -616,6 +625,7 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
   if ((rc = check_aligned({H, G, Y_out}))) return rc;
   const Layout l = make_layout(cfg, s, B, L);
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
+  if ((rc = check_slots(cfg, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
   char* pk = w8 + l.packed;
@@ -670,6 +680,7 @@ int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, con
   if (((uintptr_t)cache & 255) != 0) return fail(LONGER_ERR_ARG, "cache must be 256-byte aligned");
   const Layout l = make_layout(cfg, s, U, L);
   if ((rc = check_common(ws, ws_bytes, l.total, U, L))) return rc;
+  if ((rc = check_slots(cfg, U, L))) return rc;
   const CacheLayout cl = make_cache_layout(cfg, s, U, L);
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;

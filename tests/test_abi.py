@@ -71,6 +71,9 @@ def test_entry_points_reject_null_and_small_workspace():
     assert rc == -1
     rc = lib.longer_token_merge(ctypes.byref(cfg), blk, ctypes.c_void_p(4096 + 4), None, 4, 64, fake, ctypes.c_void_p(4096), 1 << 30, None)
     assert rc == -1 and "aligned" in lg.longer_last_error()
+    # more token slots than the merge kernel's 32-bit slot index holds (checked before anything is launched)
+    rc = lib.longer_token_merge(ctypes.byref(cfg), blk, fake, None, 1 << 20, 4096, fake, ctypes.c_void_p(4096), 1 << 62, None)
+    assert rc == -1 and "2^31" in lg.longer_last_error()
     unsupported = lg.make_config(synth.CONFIGS["C1"].replace(d=96, heads=6, inner_heads=6))
     rc = lib.longer_token_merge(ctypes.byref(unsupported), blk, fake, None, 4, 64, fake, ctypes.c_void_p(4096), 1 << 30, None)
     assert rc == -1 and "unsupported" in lg.longer_last_error()
