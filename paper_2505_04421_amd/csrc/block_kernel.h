@@ -382,8 +382,9 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   constexpr bool ATTNLIKE = MODE == MODE_ATTN || STACK;   // rows are [globals; recent slots] of a user
   // kernels that run one wave per SIMD, where no other wave hides the LDS latency of a weight
   // fragment: the d <= 128 stack kernel takes scheduling hints (frag_pipeline_hint); at d = 256 the
-  // compiler ignores them under its register pressure and the reads are placed ahead by hand
-  constexpr bool PIPE = sizeof(T) == 2 && TT == 1 && STACK && D < 256;
+  // compiler ignores them under its register pressure and the reads are placed ahead by hand.
+  // The two-wave merge kernel takes the hints too (1 % faster)
+  constexpr bool PIPE = sizeof(T) == 2 && TT == 1 && (STACK || MODE == MODE_MERGE) && D < 256;
   constexpr bool MANUAL = sizeof(T) == 2 && TT == 1 && D >= 256;
   constexpr bool BIGSEG = SEGV * 16 >= 16384;
   constexpr int PSEG = BIGSEG ? 1 : 4;              // segments per panel of the weight stream (one barrier per panel)
