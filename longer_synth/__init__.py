@@ -173,6 +173,39 @@ def draw_weights(cfg: Config, rng: Optional[np.random.Generator] = None) -> Dict
     return w
 
 
+def draw_input_mlp(rng: np.random.Generator, cfg: "Config", d_e: int) -> Dict[str, np.ndarray]:
+    """Parameters of the input-generation stage (Section 3.5.1, Input Generation): a learnable
+    absolute positional embedding ``pos`` [L, d_e] added to the item embeddings, and a two-layer
+    MLP d -> ffn_mult d -> d over [item + position ; time-difference feature]."""
+    d, f = cfg.d, cfg.ffn_mult * cfg.d
+    return {
+        "pos": _uniform(rng, (cfg.L, d_e), 0.5),
+        "w1": _uniform(rng, (d, f), np.sqrt(6.0 / (d + f))),
+        "b1": _uniform(rng, f, 0.05),
+        "w2": _uniform(rng, (f, d), np.sqrt(6.0 / (d + f))),
+        "b2": _uniform(rng, d, 0.05),
+    }
+
+
+def make_input_case(cfg: "Config", d_e: int, seed_offset: int = 1000) -> Dict[str, object]:
+    """Item embeddings E [B, L, d_e], time-difference features tdiff [B, L, d - d_e], the
+    input-generation parameters and (ragged configurations) raw lengths; padded rows hold NaN."""
+    rng = np.random.Generator(np.random.Philox(SEED_BASE + seed_offset + cfg.index))
+    mlp = draw_input_mlp(rng, cfg, d_e)
+    E = rng.standard_normal(size=(cfg.B, cfg.L, d_e), dtype=np.float32)
+    tdiff = rng.standard_normal(size=(cfg.B, cfg.L, cfg.d - d_e), dtype=np.float32)
+    lens = None
+    if cfg.ragged:
+        lens = rng.integers(cfg.len_lo, cfg.len_hi + 1, size=cfg.B).astype(np.int32)
+        pos = np.arange(cfg.L)[None, :, None]
+        E = np.where(pos < lens[:, None, None], E, np.float32("nan")).astype(np.float32)
+        tdiff = np.where(pos < lens[:, None, None], tdiff, np.float32("nan")).astype(np.float32)
+    case = {"cfg": cfg, "mlp": mlp, "E": E, "tdiff": tdiff, "lens": lens}
+    if cfg.dtype == "bf16":
+        case = _map_tree(case, round_bf16)
+    return case
+
+
 def _tokens(rng, shape, dist) -> np.ndarray:
     x = rng.standard_normal(size=shape, dtype=np.float32)
     if dist == "lognormal_scaled":

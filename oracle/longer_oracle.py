@@ -43,7 +43,9 @@ document as well):
   uniformly sampled older tokens into the first ``k_uniform`` slots (each the
   newest token of one of k_uniform equal shares of the older tokens) and keep the
   most recent ones in the rest; slots stay in chronological order;
-* the prediction head is logit = <head_w, flatten(Y[:m])> + head_b.
+* the prediction head is logit = <head_w, flatten(Y[:m])> + head_b;
+* input generation (``input_generation``): widths and MLP depth are this build's
+  reading, see its docstring.
 
 Parity status: every function below is pinned by tests/test_oracle_*.py to a
 library routine, a closed form, brute force or one of the invariants, except
@@ -218,6 +220,26 @@ def query_tokens(m: int, k: int, Tu: int, k_uniform: int = 0):
 def key_tokens(m: int, T: int, Tu: int):
     """Descriptors of R = [G; M] (Section 3.5.1), merged tokens t >= Tu invalid."""
     return [(True, a, True) for a in range(m)] + [(False, t, t < Tu) for t in range(T)]
+
+
+# --------------------------------------------------------------------------- input generation
+def input_generation(cfg, mlp: dict, E: np.ndarray, tdiff: np.ndarray, lens=None) -> np.ndarray:
+    """Sequence-token representations H [B, L, d] (Section 3.5.1, Input Generation): the
+    learnable absolute positional embedding is added to each item embedding, the
+    time-difference side information is concatenated to it, and the result goes through an
+    MLP.  Readings (the paper fixes none of them): item and position width d_e, side
+    information width d - d_e, a two-layer MLP d -> ffn_mult d -> d with the block's
+    activation.  Rows of padded tokens are zero."""
+    E = np.asarray(E)
+    B, L, d_e = E.shape
+    lens = _lens(lens, B, L)
+    w1, b1, w2, b2, pos = (np.asarray(mlp[k], dtype=F64) for k in ("w1", "b1", "w2", "b2", "pos"))
+    H = np.zeros((B, L, w2.shape[1]), dtype=F64)
+    for u in range(B):
+        n = int(min(lens[u], L))
+        x = np.concatenate([np.asarray(E[u, :n], dtype=F64) + pos[:n], np.asarray(tdiff[u, :n], dtype=F64)], axis=1)
+        H[u, :n] = activation(x @ w1 + b1, cfg.act) @ w2 + b2
+    return H
 
 
 # --------------------------------------------------------------------------- token merge

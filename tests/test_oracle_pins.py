@@ -387,6 +387,32 @@ def test_concat_forward_padding_and_cache_invariants():
         np.testing.assert_allclose(lgs[:, c], lc, rtol=1e-12, atol=1e-13)
 
 
+# --------------------------------------------------------------------------- input generation
+def test_input_generation_equals_torch_mlp_on_concatenated_inputs():
+    """Section 3.5.1: position added to the item embedding, time-difference feature concatenated,
+    then an MLP -- rebuilt from torch.nn modules."""
+    cfg = synth.tiny_config(B=3, L=9, d=16, ragged=True, len_lo=0, len_hi=9)
+    case = synth.make_input_case(cfg, d_e=12)
+    mlp, E, td = case["mlp"], case["E"], case["tdiff"]
+    lens = np.array([9, 4, 0])
+    H = orc.input_generation(cfg, mlp, E, td, lens)
+    lin1, lin2 = torch.nn.Linear(16, 64).double(), torch.nn.Linear(64, 16).double()
+    with torch.no_grad():
+        lin1.weight.copy_(torch.from_numpy(mlp["w1"].astype(np.float64).T)); lin1.bias.copy_(torch.from_numpy(mlp["b1"].astype(np.float64)))
+        lin2.weight.copy_(torch.from_numpy(mlp["w2"].astype(np.float64).T)); lin2.bias.copy_(torch.from_numpy(mlp["b2"].astype(np.float64)))
+        net = torch.nn.Sequential(lin1, torch.nn.GELU(), lin2)
+        for u in range(3):
+            n = lens[u]
+            x = torch.cat([torch.from_numpy(E[u, :n].astype(np.float64)) + torch.from_numpy(mlp["pos"][:n].astype(np.float64)),
+                           torch.from_numpy(td[u, :n].astype(np.float64))], dim=1)
+            np.testing.assert_allclose(H[u, :n], net(x).numpy(), rtol=1e-12, atol=1e-13)
+            assert (H[u, n:] == 0).all()          # padded rows (NaN in the inputs) come out as zeros
+    assert np.isfinite(H).all()
+    # the position embedding is indexed by the token's position, not by anything user-specific
+    H2 = orc.input_generation(cfg, mlp, np.roll(E, 1, axis=0), np.roll(td, 1, axis=0), np.roll(lens, 1))
+    np.testing.assert_array_equal(H2, np.roll(H, 1, axis=0))
+
+
 # --------------------------------------------------------------------------- query sampling strategies
 def test_uniform_slots_are_evenly_spaced_increasing_and_end_at_the_newest_older_token():
     for Tu, k, ku in [(250, 100, 100), (250, 100, 50), (613, 64, 64), (101, 100, 37), (40, 8, 3)]:
