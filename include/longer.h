@@ -167,6 +167,20 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
                             void* Yg_out, float* logits_out,
                             void* ws, size_t ws_bytes, void* stream);
 
+/* Input generation (Section 3.5.1, "Input Generation"): the sequence-token representations
+ * H = MLP([item embedding + learnable absolute positional embedding ; time-difference side
+ * information]).  The paper fixes neither the widths nor the MLP; here the item and positional
+ * embeddings have width d_e (a multiple of 32, 0 < d_e < d), the side information d - d_e, and
+ * the MLP is d -> ffn_mult*d -> d with the config's activation:
+ * E [B, L, d_e], pos [L, d_e] (indexed by position), tdiff [B, L, d - d_e]
+ * -> H_out [B, L, d] = act([E + pos ; tdiff] w1 + b1) w2 + b2, w1 [d, f], w2 [f, d], f = ffn_mult*d.
+ * Rows of padded tokens are written as zeros.  H_out is what longer_token_merge / longer_forward
+ * take as H (merge mode LONGER_MERGE_MEAN). */
+typedef struct { const void *pos, *w1, *b1, *w2, *b2; } longer_input_weights;
+int longer_input_generation(const longer_config* cfg, const longer_input_weights* w, const void* E,
+                            const void* tdiff, const int32_t* lens, int B, int L, int d_e,
+                            void* H_out, void* ws, size_t ws_bytes, void* stream);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* longer_last_error(void);
 

@@ -12,7 +12,7 @@ BLOCK_FIELDS = ("ln1_g", "ln1_b", "wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo"
                 "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
 ENTRY_POINTS = ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_inner_transformer",
                 "longer_token_merge", "longer_hybrid_cross_attn", "longer_self_attn_layer",
-                "longer_forward", "longer_kv_cache_build", "longer_score_candidates",
+                "longer_forward", "longer_kv_cache_build", "longer_score_candidates", "longer_input_generation",
                 "longer_last_error", "longer_probe_mfma_layout", "longer_stage_timing",
                 "longer_stage_timing_read")
 
@@ -36,6 +36,10 @@ class CBlock(ctypes.Structure):
 class CWeights(ctypes.Structure):
     _fields_ = [("inner", ctypes.POINTER(CBlock)), ("cross", ctypes.POINTER(CBlock)),
                 ("self", ctypes.POINTER(CBlock)), ("head_w", ctypes.c_void_p), ("head_b", ctypes.c_void_p)]
+
+
+class CInputWeights(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_void_p) for f in ("pos", "w1", "b1", "w2", "b2")]
 
 
 def library_path() -> str:
@@ -65,6 +69,7 @@ def load_library() -> ctypes.CDLL:
     lib.longer_forward.argtypes = [cfgp, wp, vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.longer_kv_cache_build.argtypes = [cfgp, wp, vp, vp, i32, i32, vp, vp, sz, vp]
     lib.longer_score_candidates.argtypes = [cfgp, wp, vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+    lib.longer_input_generation.argtypes = [cfgp, ctypes.POINTER(CInputWeights), vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
     lib.longer_last_error.restype = ctypes.c_char_p
     lib.longer_probe_mfma_layout.argtypes = [vp, vp]
     lib.longer_stage_timing.argtypes = [i32]
@@ -231,6 +236,13 @@ def longer_score_candidates(ccfg, weights, cache, lens, U, L, G_cand, C, Yg_out,
     _check(load_library().longer_score_candidates(ctypes.byref(ccfg), ctypes.byref(weights), _ptr(cache), _ptr(lens), U, L,
                                                   _ptr(G_cand), C, _ptr(Yg_out), _ptr(logits_out), _ptr(ws), ws.numel(),
                                                   _stream(stream)), "longer_score_candidates")
+
+
+def longer_input_generation(ccfg, weights, E, tdiff, lens, B, L, d_e, H_out, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_input_generation(ctypes.byref(ccfg), ctypes.byref(weights), _ptr(E), _ptr(tdiff), _ptr(lens),
+                                                  B, L, d_e, _ptr(H_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "longer_input_generation")
 
 
 def longer_probe_mfma_layout(out, stream=None):

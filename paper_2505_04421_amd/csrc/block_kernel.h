@@ -59,6 +59,9 @@ struct BlockParams {
   // MODE_ATTN / MODE_SCORE outputs
   void* X_out; int X_f32; long long X_ustride;
   float* logits; const float* head;   // head: fp32 [m*D] weights then the bias
+  // MODE_INPUT: item embeddings [B, L, de], positional embedding [L, de], time-difference features
+  // [B, L, D - de] (element type T); the result goes to X_out [B, L, D]
+  const void* in_e; const void* in_pos; const void* in_td; int de;
   // MODE_SCORE
   int xcds, wg_per_user;   // workgroup index -> (user, group of tiles), see the kernel
   const void* Gc; int C;
@@ -492,6 +495,28 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
         if (glob) { slo1[tt] = p.gmask_causal ? a : 0; shi1[tt] = p.m; slo2[tt] = p.m + i0; shi2[tt] = p.m + p.k; }
         else { slo2[tt] = p.m + i0; shi2[tt] = p.m + i + 1; }
       }
+    } else if (MODE == MODE_INPUT) {
+      // row = one raw token; x = [item embedding + positional embedding ; time-difference feature]
+      const long long r = (long long)tile * 32 + j;
+      const int u = (int)(r / p.L), pos = (int)(r - (long long)u * p.L);
+      inrange[tt] = u < p.B;
+      int len = 0;
+      if (inrange[tt]) { len = p.lens ? p.lens[u] : p.L; len = min(max(len, 0), p.L); }
+      valid[tt] = inrange[tt] && pos < len;
+      usr[tt] = u; out_off[tt] = r * D;
+      const int nte = p.de / 32, dt = D - p.de;
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        f32x16 a[1], b[1];
+        if (t < nte) {
+          load_rows<T, 1>(a, p.in_e, 0, r * p.de + 32 * t, valid[tt], hi);
+          load_rows<T, 1>(b, p.in_pos, 0, (long long)pos * p.de + 32 * t, valid[tt], hi);
+          resid[tt][t] = a[0] + b[0];
+        } else {
+          load_rows<T, 1>(a, p.in_td, 0, r * dt + 32 * (t - nte), valid[tt], hi);
+          resid[tt][t] = a[0];
+        }
+      }
     } else {  // MODE_SCORE
       const int u = su;
       const int a = 32 * tile + j;
@@ -526,7 +551,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   }
 
   WStream<SEGV, PSEG, NB, MODE == MODE_KVPROJ> ws;
-  const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : (ATTNLIKE ? 2 * NT + 2 * NC : 4 * NT + 2 * NC));
+  const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : MODE == MODE_INPUT ? 2 * NC : (ATTNLIKE ? 2 * NT + 2 * NC : 4 * NT + 2 * NC));
   // MODE_STACK: the cross block's attention sub-stream, then the self blocks in the fused
   // layout, each followed by the unused segment that fills its slot in the packed buffer
   ws.init(lds, p.wbase, STACK ? steps + (p.n_layers - 1) * (2 + 4 * NT + 2 * NC) : steps * p.n_layers);
@@ -567,9 +592,21 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
     const float* vec = reinterpret_cast<const float*>(vecl);
     const VecLayout vl{D, p.FF};
     grp xn[TT][NG];
+    const bool selfl = STACK && layer > 0;   // a self-causal layer of the stack: K/V made here
+    if constexpr (MODE == MODE_INPUT) {
+      // input generation: no norm, no attention, no residual -- the rows themselves are the first
+      // GEMM's operand and the result starts from the output bias
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll
+          for (int g = 0; g < GPT; ++g) xn[tt][t * GPT + g] = E::pack(resid[tt][t], g);
+          resid[tt][t] = splat16(0.f);
+        }
+    } else {
     layer_norm<T, D, TT>(resid, vec + vl.ln1_g(), vec + vl.ln1_b(), p.eps, hi, xn);
     grp oop[TT][NG];
-    const bool selfl = STACK && layer > 0;   // a self-causal layer of the stack: K/V made here
 
 #pragma unroll
     for (int ft = 0; ft < NT; ++ft) {
@@ -790,6 +827,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 
     // FFN, 32 hidden features at a time: hidden chunk never leaves registers
     layer_norm<T, D, TT>(resid, vec + vl.ln2_g(), vec + vl.ln2_b(), p.eps, hi, xn);
+    }   // MODE != MODE_INPUT
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {      // FFN output bias goes in first: the vectors may be
       const f32x16 b2 = bias_tile(vec + vl.b2(), nt, hi);   // replaced right after the last segment
@@ -904,6 +942,10 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
           store_rows<T, NT>(resid[tt], p.M_out, p.M_f32, (long long)gidx * D, true, hi);
       }
     }
+  } else if (MODE == MODE_INPUT) {
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+      if (inrange[tt]) store_rows<T, NT>(resid[tt], p.X_out, 0, out_off[tt], valid[tt], hi);
   } else if (ATTNLIKE || MODE == MODE_SCORE) {
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
@@ -963,6 +1005,7 @@ int launch_block(int mode, int tt, int win, const BlockParams& p, dim3 grid, hip
       case MODE_KVPROJ: LONGER_LAUNCH(T, D, DH, 1, MODE_KVPROJ, 16); break;                           \
       case MODE_ATTN: LONGER_LAUNCH(T, D, DH, 1, MODE_ATTN, 16); break;                               \
       case MODE_STACK: LONGER_LAUNCH(T, D, DH, 1, MODE_STACK, 16); break;                             \
+      case MODE_INPUT: LONGER_LAUNCH(T, D, DH, 1, MODE_INPUT, 16); break;                             \
       case MODE_SCORE:                                                                                \
         if (win == 4) LONGER_LAUNCH(T, D, DH, 1, MODE_SCORE, 4);                                      \
         else if (win == 8) LONGER_LAUNCH(T, D, DH, 1, MODE_SCORE, 8);                                 \

@@ -123,7 +123,9 @@ __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size
 //   FUSED  [vec][q0 k0 v0 q1 k1 v1 ...][o0 ..][w1(0) w2(0) w1(1) w2(1) ...]      (merge, scoring)
 //   SPLIT  [vec][k0 v0 k1 v1 ...] then [vec][q0 q1 ..][o0 ..][w1(0) w2(0) ...]   (K/V projection, attention)
 // "vec" is one segment holding the block's fp32 vectors (VecLayout), zero padded.
-enum PackLayout { LAYOUT_FUSED = 0, LAYOUT_SPLIT = 1 };
+//   MLP    [vec][w1(0) w2(0) w1(1) w2(1) ...]                                      (input generation: biases b1, b2 only)
+enum PackLayout { LAYOUT_FUSED = 0, LAYOUT_SPLIT = 1, LAYOUT_MLP = 3 };
+__host__ __device__ inline int mlp_segs(int FF) { return 1 + 2 * (FF / 32); }
 __host__ __device__ inline size_t packed_seg_bytes(int D, int es) { return (size_t)D * 32 * es; }   // D/GF KiB, GF = 32/es
 __host__ __device__ inline int fused_segs(int D, int FF) { return 1 + 4 * (D / 32) + 2 * (FF / 32); }
 __host__ __device__ inline int kv_segs(int D) { return 1 + 2 * (D / 32); }
@@ -133,7 +135,7 @@ __host__ __device__ inline size_t packed_block_bytes(int D, int FF, int es) {
   return (size_t)(fused_segs(D, FF) + 1) * packed_seg_bytes(D, es);
 }
 
-enum Mode { MODE_MERGE = 0, MODE_KVPROJ = 1, MODE_ATTN = 2, MODE_SCORE = 3, MODE_STACK = 4 };
+enum Mode { MODE_MERGE = 0, MODE_KVPROJ = 1, MODE_ATTN = 2, MODE_SCORE = 3, MODE_STACK = 4, MODE_INPUT = 5 };
 
 // 16 bytes per lane from global memory straight into LDS (no VGPR round trip):
 // lane i of the wave writes LDS bytes [lds_wave_base + 16 i, +16).  lds_wave_base must be

@@ -106,14 +106,17 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
     return;
   }
   const int NT = D / 32, NC = FF / 32, NG = D / E::GF, SEGV = NG * 64;
-  const int nseg = layout == LAYOUT_FUSED ? fused_segs(D, FF) : kv_segs(D) + attn_segs(D, FF);
+  const int nseg = layout == LAYOUT_FUSED ? fused_segs(D, FF) : layout == LAYOUT_MLP ? mlp_segs(FF) : kv_segs(D) + attn_segs(D, FF);
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (long long)nseg * SEGV) return;
   int seg = (int)(idx / SEGV);
   const int within = (int)(idx - (long long)seg * SEGV);
   // decode the destination segment: kind 0 vec, 1 q, 2 k, 3 v, 4 o, 5 w1, 6 w2; tile/chunk index
   int kind, ti;
-  if (layout == LAYOUT_FUSED) {
+  if (layout == LAYOUT_MLP) {          // the input-generation MLP: biases, then (W1 chunk, W2 chunk) pairs
+    if (seg == 0) { kind = 0; ti = 0; }
+    else { kind = 5 + ((seg - 1) & 1); ti = (seg - 1) >> 1; }
+  } else if (layout == LAYOUT_FUSED) {
     if (seg == 0) { kind = 0; ti = 0; }
     else if (seg <= 3 * NT) { kind = 1 + (seg - 1) % 3; ti = (seg - 1) / 3; }
     else if (seg <= 4 * NT) { kind = 4; ti = seg - 1 - 3 * NT; }
@@ -129,6 +132,19 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
       else if (seg <= 2 * NT) { kind = 4; ti = seg - 1 - NT; }
       else { kind = 5 + ((seg - 1 - 2 * NT) & 1); ti = (seg - 1 - 2 * NT) >> 1; }
     }
+  }
+  if (kind == 0 && layout == LAYOUT_MLP) {
+    const VecLayout vl{D, FF};
+    f32x4 out;
+    for (int e = 0; e < 4; ++e) {
+      const int i = within * 4 + e;
+      float v = 0.f;
+      if (i >= vl.b2() && i < vl.b1()) v = (float)((const T*)raw.b.b2)[i - vl.b2()];
+      else if (i >= vl.b1() && i < vl.total()) v = (float)((const T*)raw.b.b1)[i - vl.b1()];
+      out[e] = v;
+    }
+    reinterpret_cast<f32x4*>(dst)[idx] = out;
+    return;
   }
   if (kind == 0) {
     const VecLayout vl{D, FF};
@@ -355,6 +371,16 @@ struct PackBatch {
     if (n == kMaxPackJobs) { int rc = flush(); if (rc) return rc; }
     a.job[n].raw.b.ln1_g = w->head_w; a.job[n].raw.b.ln1_b = w->head_b;
     a.job[n].dst = (char*)dst; a.job[n].layout = kLayoutHead; a.job[n].pad_ = c->m * s.D;
+    ++n;
+    return 0;
+  }
+  // the two-layer MLP of the input-generation stage (weights [d, f], [f, d] and their biases)
+  int add_mlp(const void* w1, const void* b1, const void* w2, const void* b2, void* dst) {
+    if (!w1 || !b1 || !w2 || !b2) return fail(LONGER_ERR_ARG, "input MLP has NULL members");
+    if (n == kMaxPackJobs) { int rc = flush(); if (rc) return rc; }
+    memset(&a.job[n], 0, sizeof(a.job[n]));
+    a.job[n].raw.b.w1 = w1; a.job[n].raw.b.b1 = b1; a.job[n].raw.b.w2 = w2; a.job[n].raw.b.b2 = b2;
+    a.job[n].dst = (char*)dst; a.job[n].layout = LAYOUT_MLP;
     ++n;
     return 0;
   }
@@ -770,6 +796,35 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
   StageScope scope(ST_SCORE, st);
   const int win = cfg->m <= 8 ? 4 : (cfg->m <= 16 ? 8 : 16);
   if (s.main_fn(MODE_SCORE, 1, win, p, grid, st)) return fail(LONGER_ERR_HIP, "score kernel launch failed");
+  return 0;
+}
+
+int longer_input_generation(const longer_config* cfg, const longer_input_weights* w, const void* E, const void* tdiff,
+                            const int32_t* lens, int B, int L, int d_e, void* H_out,
+                            void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  Shape s;
+  int rc = check_cfg(cfg, &s, false, true);
+  if (rc) return rc;
+  if (!w || !w->pos || !E || !tdiff || !H_out) return fail(LONGER_ERR_ARG, "NULL argument");
+  if (d_e <= 0 || d_e >= cfg->d || d_e % 32)
+    return fail(LONGER_ERR_ARG, "d_e=%d must be a multiple of 32 below d=%d (the rest is the time-difference width)", d_e, cfg->d);
+  if ((rc = check_aligned({E, tdiff, H_out, w->pos}))) return rc;
+  const Layout l = make_layout(cfg, s, B, L);
+  if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
+  if ((long long)B * L + 32LL * kWaves >= (1LL << 31)) return fail(LONGER_ERR_ARG, "B*L = %lld rows: at most 2^31 per call", (long long)B * L);
+  hipStream_t st = (hipStream_t)stream;
+  char* w8 = (char*)ws;
+  PackBatch pk_batch(cfg, s, st);
+  if ((rc = pk_batch.add_mlp(w->w1, w->b1, w->w2, w->b2, w8 + l.packed))) return rc;
+  if ((rc = pk_batch.flush())) return rc;
+  BlockParams p = base_params(cfg, s, lens, B, L, s.DH);
+  p.wbase = w8 + l.packed;
+  p.in_e = E; p.in_pos = w->pos; p.in_td = tdiff; p.de = d_e;
+  p.X_out = H_out;
+  const int grid = cdiv((long long)B * L, 32LL * kWaves);
+  StageScope scope(ST_MERGE, st);
+  if (s.main_fn(MODE_INPUT, 1, 16, p, dim3(grid), st)) return fail(LONGER_ERR_HIP, "input generation launch failed");
   return 0;
 }
 

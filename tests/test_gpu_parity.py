@@ -253,6 +253,36 @@ def test_bf16_other_head_widths(d, heads, K):
     _serving(case, TOL["bf16"])
 
 
+@pytest.mark.parametrize("base,d_e,B,L", [("C1", 32, 3, 75), ("C3", 96, 5, 333)])
+def test_input_generation(base, d_e, B, L):
+    """H = MLP([E + pos ; tdiff]) (fp32 d = 64 as 32 + 32, bf16 d = 128 as 96 + 32), ragged lengths
+    with NaN padding, then the library's own token merge over its output."""
+    import paper_2505_04421_amd as lg
+    import torch
+    cfg = synth.CONFIGS[base].replace(B=B, L=L, ragged=True, len_lo=0, len_hi=L, index=28)
+    if base == "C1":
+        cfg = cfg.replace(d=64, heads=4, inner_heads=4)
+    case = synth.make_input_case(cfg, d_e)
+    case["lens"][0] = L            # one full-length user: give it real values where the draw had padding
+    rnd = synth.round_bf16 if cfg.dtype == "bf16" else (lambda a: a)
+    g = np.random.default_rng(14)
+    case["E"][0] = rnd(g.standard_normal(case["E"][0].shape).astype(np.float32))
+    case["tdiff"][0] = rnd(g.standard_normal(case["tdiff"][0].shape).astype(np.float32))
+    tol = TOL[cfg.dtype]
+    model = lg.DeviceModel(cfg, synth.draw_weights(cfg))
+    mlp = {k: model.upload(v) for k, v in case["mlp"].items()}
+    wts = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
+    Ed, Td = model.upload(case["E"]), model.upload(case["tdiff"])
+    lens = torch.from_numpy(case["lens"].astype(np.int32)).to(model.device)
+    H = model.empty(B, L, cfg.d)
+    ws = model.workspace(B, L)
+    _say("input generation %s d=%d = %d + %d" % (cfg.dtype, cfg.d, d_e, cfg.d - d_e))
+    lg.longer_input_generation(model.ccfg, wts, Ed, Td, lens, B, L, d_e, H, ws)
+    torch.cuda.synchronize()
+    ref = orc.input_generation(cfg, case["mlp"], case["E"], case["tdiff"], case["lens"])
+    _check("longer_input_generation", H.float().cpu().numpy().astype(np.float64), ref, tol)
+
+
 def test_c2_bf16_all_entry_points():
     _say("C2 bf16 (16 users)")
     _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
