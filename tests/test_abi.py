@@ -85,3 +85,16 @@ def test_compute_calls_fail_loudly_without_a_gpu():
         pytest.skip("GPU present")
     with pytest.raises(lg.LongerError):
         lg.DeviceModel(synth.CONFIGS["C1"], synth.draw_weights(synth.CONFIGS["C1"]))
+
+
+def test_input_generation_rejects_bad_widths():
+    lib = lg.load_library()
+    cfg = lg.make_config(synth.CONFIGS["C3"])
+    w = lg.CInputWeights(pos=256, w1=256, b1=256, w2=256, b2=256)      # never dereferenced
+    fake = ctypes.c_void_p(256)
+    for d_e in (0, 48, 128, 160):                                       # not a multiple of 32, or no room for the time feature
+        rc = lib.longer_input_generation(ctypes.byref(cfg), ctypes.byref(w), fake, fake, None, 4, 64, d_e, fake,
+                                         ctypes.c_void_p(4096), 1 << 40, None)
+        assert rc == -1 and "d_e" in lg.longer_last_error()
+    rc = lib.longer_input_generation(ctypes.byref(cfg), ctypes.byref(w), fake, fake, None, 4, 64, 96, fake, None, 0, None)
+    assert rc == -1 and "workspace" in lg.longer_last_error()
