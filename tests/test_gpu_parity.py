@@ -283,6 +283,58 @@ def test_input_generation(base, d_e, B, L):
     _check("longer_input_generation", H.float().cpu().numpy().astype(np.float64), ref, tol)
 
 
+def _random_config(seed):
+    """A random small configuration over everything the library accepts (widths, head widths, group
+    sizes, global-set sizes, query counts and sampling, layer counts, merge modes, activations, masks)."""
+    rng = np.random.default_rng(4000 + seed)
+    dtype = str(rng.choice(["f32", "bf16"]))
+    if dtype == "f32":
+        d, dh = int(rng.choice([32, 64])), 16
+    else:
+        d, dh = [(32, 16), (64, 16), (64, 32), (128, 16), (128, 32), (256, 32), (256, 16)][int(rng.integers(0, 7))]
+    K = int(rng.choice([1, 2, 4, 8, 16, 32]))
+    m = int(rng.choice([1, 2, 4, 8, 16]))
+    merge = "mean"
+    if dtype == "bf16" and d == 256 and rng.random() < 0.5:
+        merge, K = "concat", int(rng.choice([4, 8]))
+    di = d // K if merge == "concat" else d
+    inner_heads = di // dh if di == d else di // 16
+    L = int(rng.integers(K, (40 if d < 256 else 12) * K))
+    T = (L + K - 1) // K
+    k = int(rng.integers(1, min(2 * T, 150 - m) + 1))
+    ku = int(rng.integers(0, k + 1)) if rng.random() < 0.5 else 0
+    return synth.Config("rnd", 600 + seed, B=int(rng.integers(1, 5)), L=L, d=d, heads=d // dh, m=m, K=K, k_recent=k,
+                        n_self=int(rng.integers(0, 3)), inner_layers=int(rng.integers(1, 3)), inner_heads=inner_heads,
+                        dtype=dtype, act=str(rng.choice(["gelu_erf", "relu"])), gmask=str(rng.choice(["full", "causal"])),
+                        ragged=True, len_lo=0, len_hi=L, merge=merge, k_uniform=ku, ffn_mult=int(rng.choice([2, 4])),
+                        C=int(rng.integers(1, 7)))
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_configurations_forward_and_serving(seed):
+    from gpu_util import rel_l2_per_user, assert_zero_where_ref_zero_rows
+    cfg = _random_config(seed)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    tol = TOL[cfg.dtype]
+    _say("random configuration %d: %s" % (seed, cfg))
+    r = _runner(case)
+    w = case["weights"]
+    Y_ref, lg_ref = orc.forward(cfg, w, case["H"], case["G"], case["lens"])
+    Y, logits = r.forward()
+    _check("longer_forward Y", Y, Y_ref, tol)
+    # a logit is a sum of m d signed terms: judge it against the size of those terms (a logit that
+    # happens to cancel to nearly zero has no meaningful relative error of its own)
+    hw = np.abs(np.asarray(w["head_w"], dtype=np.float64))
+    scale = (np.abs(Y_ref[:, :cfg.m].reshape(cfg.B, -1)) * hw[None, :]).sum(1) + 1e-30
+    assert np.isfinite(logits).all() and (np.abs(logits - lg_ref) / scale).max() <= tol
+    Yg, lgs = r.serve()
+    cache = orc.kv_cache_build(cfg, w, case["H"], case["lens"])
+    Yg_ref, lgs_ref = orc.score_candidates(cfg, w, cache, case["G_cand"])
+    _check("longer_score_candidates Yg", Yg.reshape(cfg.B * cfg.C, -1), Yg_ref.reshape(cfg.B * cfg.C, -1), tol)
+    sc2 = (np.abs(Yg_ref.reshape(cfg.B, cfg.C, -1)) * hw[None, None, :]).sum(2) + 1e-30
+    assert np.isfinite(lgs).all() and (np.abs(lgs - lgs_ref) / sc2).max() <= tol
+
+
 def test_c2_bf16_all_entry_points():
     _say("C2 bf16 (16 users)")
     _entry_points(synth.make_case(synth.CONFIGS["C2"], users=16), TOL["bf16"])
