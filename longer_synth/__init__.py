@@ -15,7 +15,8 @@ Conventions
 -----------
 * everything is drawn in fp32 from ``numpy.random.Philox`` (a counter-based
   generator) seeded with ``SEED_BASE + config_index``; draw order is fixed:
-  inner blocks, cross block, self blocks, head, then H, G, G_cand, lens.
+  inner blocks, cross block, self blocks, head, (learnable query tokens), then H, G,
+  G_cand, lens.
 * weights are stored ``[in, out]`` so that ``y = x @ W + b`` (Eq. 6 writes
   ``Q = O W_Q``).
 * in bf16 mode every tensor is rounded once to bf16 (round-to-nearest-even) and
@@ -65,6 +66,8 @@ class Config:
     k_uniform: int = 0     # of the k_recent query slots, how many are sampled uniformly from the older tokens
     merge: str = "mean"    # "mean": K outputs of a group pooled to one token of width d;
                            # "concat": raw tokens of width d / K, a group's K outputs concatenated
+    q_learnable: bool = False  # the k_recent query slots hold learnable tokens (a [k_recent, d] parameter
+                               # shared by all users) instead of tokens sampled from the sequence
 
     @property
     def T(self) -> int:
@@ -170,6 +173,8 @@ def draw_weights(cfg: Config, rng: Optional[np.random.Generator] = None) -> Dict
         "head_w": _uniform(rng, cfg.m * cfg.d, np.sqrt(6.0 / (cfg.m * cfg.d + 1))),
         "head_b": _uniform(rng, 1, 0.05),
     }
+    if cfg.q_learnable:      # drawn last, so that the other parameters do not depend on the query strategy
+        w["q_learn"] = rng.standard_normal(size=(cfg.k_recent, cfg.d), dtype=np.float32)
     return w
 
 

@@ -43,6 +43,9 @@ document as well):
   uniformly sampled older tokens into the first ``k_uniform`` slots (each the
   newest token of one of k_uniform equal shares of the older tokens) and keep the
   most recent ones in the rest; slots stay in chronological order;
+  ``q_learnable``: the k slots hold learnable query tokens (one [k, d] parameter for
+  all users) that see every valid sequence token in the first layer and each other
+  causally, in slot order, afterwards (see ``query_tokens``);
 * the prediction head is logit = <head_w, flatten(Y[:m])> + head_b;
 * input generation (``input_generation``): widths and MLP depth are this build's
   reading, see its docstring.
@@ -207,14 +210,29 @@ def slot_index(i: int, k: int, Tu: int, k_uniform: int = 0) -> int:
     return ((i + 1) * rest) // k_uniform - 1
 
 
-def query_tokens(m: int, k: int, Tu: int, k_uniform: int = 0):
+def query_tokens(m: int, k: int, Tu: int, k_uniform: int = 0, learnable: bool = False):
     """Descriptors of O = [G; H_S] (Eq. 5): slot i holds merged index
-    ``slot_index(i, ...)`` (Tu - k + i for the default, most recent k), invalid when negative."""
+    ``slot_index(i, ...)`` (Tu - k + i for the default, most recent k), invalid when negative.
+
+    ``learnable`` (Section 3.5.1: k learnable tokens as the query set, the strategy of the
+    compression models cited there): the slots hold parameters, not sequence tokens.  They
+    are placed after the user's newest token, in slot order: slot i carries the index
+    Tu + i, so that under Eq. 8 it sees every valid sequence token in the first layer and
+    the slots up to itself in the self-causal layers.  A user with no token at all has
+    nothing to compress: its slots are invalid."""
     toks = [(True, a, True) for a in range(m)]
     for i in range(k):
-        t = slot_index(i, k, Tu, k_uniform)
-        toks.append((False, t, t >= 0))
+        if learnable:
+            toks.append((False, Tu + i, Tu > 0))
+        else:
+            t = slot_index(i, k, Tu, k_uniform)
+            toks.append((False, t, t >= 0))
     return toks
+
+
+def _query_tokens(cfg, m: int, Tu: int):
+    """``query_tokens`` with the config's query strategy."""
+    return query_tokens(m, cfg.k_recent, Tu, getattr(cfg, "k_uniform", 0), getattr(cfg, "q_learnable", False))
 
 
 def key_tokens(m: int, T: int, Tu: int):
@@ -301,22 +319,27 @@ def token_merge(cfg, inner_blocks: Sequence[dict], H: np.ndarray, lens=None) -> 
 
 
 # --------------------------------------------------------------------------- hybrid attention
-def gather_queries(cfg, G_u: np.ndarray, M_u: np.ndarray, Tu: int) -> np.ndarray:
+def slot_rows(cfg, M_u: np.ndarray, Tu: int, q_learn=None) -> np.ndarray:
+    """The k sequence-side query rows of one user: the sampled merged tokens, or the
+    learnable query tokens ``q_learn`` [k, d] (the same for every user); invalid slots zero."""
+    k = cfg.k_recent
+    Xs = np.zeros((k, M_u.shape[-1]), dtype=F64)
+    for i, (_, t, v) in enumerate(_query_tokens(cfg, 0, Tu)):
+        if v:
+            Xs[i] = np.asarray(q_learn, dtype=F64)[i] if getattr(cfg, "q_learnable", False) else M_u[t]
+    return Xs
+
+
+def gather_queries(cfg, G_u: np.ndarray, M_u: np.ndarray, Tu: int, q_learn=None) -> np.ndarray:
     """O = [G; H_S] for one user (Eq. 5), invalid slots zero."""
-    d = G_u.shape[-1]
-    O = np.zeros((cfg.m + cfg.k_recent, d), dtype=F64)
-    O[:cfg.m] = G_u
-    for i in range(cfg.k_recent):
-        t = slot_index(i, cfg.k_recent, Tu, getattr(cfg, "k_uniform", 0))
-        if t >= 0:
-            O[cfg.m + i] = M_u[t]
-    return O
+    return np.concatenate([np.asarray(G_u, dtype=F64), slot_rows(cfg, M_u, Tu, q_learn)], axis=0)
 
 
 def hybrid_cross_attn(cfg, cross_blk: dict, G: np.ndarray, M: np.ndarray, lens=None,
-                      L: Optional[int] = None, probs_out: Optional[list] = None) -> np.ndarray:
+                      L: Optional[int] = None, probs_out: Optional[list] = None, q_learn=None) -> np.ndarray:
     """First layer (Section 3.5.2): queries O attend over R = [G; M].
-    ``lens`` are raw lengths (None = all L); returns X [B, m+k, d]."""
+    ``lens`` are raw lengths (None = all L); ``q_learn`` [k, d] are the learnable query
+    tokens of a ``q_learnable`` configuration; returns X [B, m+k, d]."""
     G = np.asarray(G, dtype=F64)
     M = np.asarray(M, dtype=F64)
     B, T, d = M.shape
@@ -328,8 +351,8 @@ def hybrid_cross_attn(cfg, cross_blk: dict, G: np.ndarray, M: np.ndarray, lens=N
         Tu = merged_len(lens[u], cfg.K)
         Mu = np.where((np.arange(T) < Tu)[:, None], M[u], 0.0)
         R = np.concatenate([G[u], Mu], axis=0)
-        O = gather_queries(cfg, G[u], Mu, Tu)
-        qt = query_tokens(cfg.m, cfg.k_recent, Tu, getattr(cfg, "k_uniform", 0))
+        O = gather_queries(cfg, G[u], Mu, Tu, q_learn)
+        qt = _query_tokens(cfg, cfg.m, Tu)
         mask = _type_mask(qt, key_tokens(cfg.m, T, Tu), cfg.gmask)
         out = block(O, R, mask, blk, cfg.heads, cfg.ln_eps, cfg.act, probs_out)
         qvalid = np.array([t[2] for t in qt])
@@ -347,7 +370,7 @@ def self_attn_layer(cfg, blk: dict, X: np.ndarray, lens=None, L: Optional[int] =
     Y = np.zeros_like(X)
     for u in range(B):
         Tu = merged_len(lens[u], cfg.K)
-        toks = query_tokens(cfg.m, cfg.k_recent, Tu, getattr(cfg, "k_uniform", 0))
+        toks = _query_tokens(cfg, cfg.m, Tu)
         valid = np.array([t[2] for t in toks])
         Xu = np.where(valid[:, None], X[u], 0.0)
         mask = _type_mask(toks, toks, cfg.gmask)
@@ -368,7 +391,7 @@ def forward(cfg, weights: dict, H: np.ndarray, G: np.ndarray, lens=None):
     H = np.asarray(H)
     B, L, d = H.shape
     M = token_merge(cfg, weights["inner"], H, lens)
-    X = hybrid_cross_attn(cfg, weights["cross"], G, M, lens, L=L)
+    X = hybrid_cross_attn(cfg, weights["cross"], G, M, lens, L=L, q_learn=weights.get("q_learn"))
     for blk in weights["self"]:
         X = self_attn_layer(cfg, blk, X, lens, L=L)
     logits = head_logits(cfg, weights["head_w"], weights["head_b"], X[:, :cfg.m])
@@ -395,15 +418,12 @@ def kv_cache_build(cfg, weights: dict, H: np.ndarray, lens=None) -> dict:
         Mu = np.where((np.arange(T) < Tu)[:, None], M[u], 0.0)
         # layer 0: keys are all merged tokens; queries are the k recent slots
         seq_keys = [(False, t, t < Tu) for t in range(T)]
-        slots = query_tokens(0, k, Tu, getattr(cfg, "k_uniform", 0))
+        slots = _query_tokens(cfg, 0, Tu)
         svalid = np.array([s[2] for s in slots])
         Kc, Vc = project_kv(Mu, blocks[0], cfg.ln_eps)
         cache["K"][0].append(Kc); cache["V"][0].append(Vc)
         cache["valid"][0].append(np.array([s[2] for s in seq_keys]))
-        Xs = np.zeros((k, d), dtype=F64)
-        for i, (_, t, v) in enumerate(slots):
-            if v:
-                Xs[i] = Mu[t]
+        Xs = slot_rows(cfg, Mu, Tu, weights.get("q_learn"))
         Xs = np.where(svalid[:, None],
                       attend_ffn(Xs, Kc, Vc, _type_mask(slots, seq_keys, cfg.gmask), blocks[0],
                                  cfg.heads, cfg.ln_eps, cfg.act), 0.0)
@@ -462,11 +482,11 @@ def algorithmic_flops(cfg, lens=None, B: Optional[int] = None, L: Optional[int] 
         Tu = merged_len(lu, K)
         pairs = sum(min(K, lu - t * K) ** 2 for t in range(Tu))
         inner += cfg.inner_layers * (lu * per_tok_inner + 4 * di * pairs)
-        kv = min(k, Tu)
+        slots = _query_tokens(cfg, 0, Tu)
+        kv = sum(1 for s in slots if s[2])             # valid sequence-side query slots
         # cross layer: keys = m globals + Tu merged tokens; queries = m globals + kv slots
         gpairs = m * m if cfg.gmask == "full" else m * (m + 1) // 2
-        ku = getattr(cfg, "k_uniform", 0)
-        seqpairs = sum(slot_index(i, k, Tu, ku) + 1 for i in range(k - kv, k))
+        seqpairs = sum(min(s[1] + 1, Tu) for s in slots if s[2])
         cross += (m + Tu) * per_tok_kv + (m + kv) * per_tok_q + 4 * d * (gpairs + m * Tu + seqpairs)
         spairs = kv * (kv + 1) // 2
         selfl += (m + kv) * (per_tok_q + per_tok_kv) + 4 * d * (gpairs + m * kv + spairs)
@@ -479,7 +499,7 @@ def algorithmic_flops_score(cfg, Tu: int) -> int:
     d, m, k = cfg.d, cfg.m, cfg.k_recent
     per_tok = (24 * d * d) if cfg.ffn_mult == 4 else (8 + 4 * cfg.ffn_mult) * d * d
     gp = m * m if cfg.gmask == "full" else m * (m + 1) // 2
-    kv = min(k, Tu)
+    kv = sum(1 for t in _query_tokens(cfg, 0, Tu) if t[2])
     tot = m * per_tok + 4 * d * (gp + m * Tu)
     tot += cfg.n_self * (m * per_tok + 4 * d * (gp + m * kv))
     return tot

@@ -499,6 +499,103 @@ def test_sampling_strategies_reduce_to_recent_and_keep_the_invariants():
                                orc.self_attn_layer(cfgT, blk, np.concatenate([Gt, Mt], 1)), rtol=1e-13, atol=1e-14)
 
 
+# --------------------------------------------------------------------------- learnable query tokens
+def _torch_block_with_mask(blk, d, heads, O, R, allow):
+    """One pre-LN block built from torch library modules: queries O [nq, d] over R [nk, d]
+    under the boolean visibility ``allow`` [nq, nk]."""
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    ln = lambda x, g, b: torch.nn.functional.layer_norm(x, (d,), t(g), t(b), 1e-5)
+    mha = torch.nn.MultiheadAttention(d, heads, dropout=0.0, bias=True, batch_first=True).double()
+    with torch.no_grad():
+        mha.in_proj_weight.copy_(torch.cat([t(blk["wq"]).T, t(blk["wk"]).T, t(blk["wv"]).T], 0))
+        mha.in_proj_bias.copy_(torch.cat([t(blk["bq"]), t(blk["bk"]), t(blk["bv"])]))
+        mha.out_proj.weight.copy_(t(blk["wo"]).T); mha.out_proj.bias.copy_(t(blk["bo"]))
+        On, Rn = ln(t(O), blk["ln1_g"], blk["ln1_b"]), ln(t(R), blk["ln1_g"], blk["ln1_b"])
+        a, _ = mha(On[None], Rn[None], Rn[None], attn_mask=torch.from_numpy(~np.asarray(allow)), need_weights=False)
+        x = t(O) + a[0]
+        hdn = torch.nn.functional.gelu(ln(x, blk["ln2_g"], blk["ln2_b"]) @ t(blk["w1"]) + t(blk["b1"]))
+        return (x + hdn @ t(blk["w2"]) + t(blk["b2"])).numpy()
+
+
+def test_learnable_queries_equal_torch_layers_with_the_masks_written_out():
+    """First layer: [G; P] over [G; the user's valid merged tokens] -- a learnable slot sees every
+    valid sequence token and no global; self layer: slots causal in slot order.  Both rebuilt
+    from torch modules on the valid tokens only, masks written by hand."""
+    m, k, d, K = 2, 3, 16, 4
+    cfg = synth.tiny_config(B=2, L=24, d=d, heads=2, m=m, K=K, k_recent=k, q_learnable=True)
+    blk, blk2 = _blk(31, d), _blk(32, d)
+    G = _rng(1).standard_normal((2, m, d)); M = _rng(2).standard_normal((2, cfg.T, d))
+    P = _rng(3).standard_normal((k, d))
+    lens = np.array([24, 10])                                   # 6 and 3 valid merged tokens
+    X = orc.hybrid_cross_attn(cfg, blk, G, M, lens, q_learn=P)
+    Y = orc.self_attn_layer(cfg, blk2, X, lens)
+    for u, Tu in enumerate((6, 3)):
+        R = np.concatenate([G[u], M[u, :Tu]], 0)
+        O = np.concatenate([G[u], P], 0)
+        allow = np.zeros((m + k, m + Tu), dtype=bool)
+        allow[:m, :] = True                                     # globals: everything (gmask full)
+        allow[m:, m:] = True                                    # learnable slots: every valid sequence token
+        ref = _torch_block_with_mask(blk, d, 2, O, R, allow)
+        np.testing.assert_allclose(X[u], ref, rtol=1e-10, atol=1e-11)
+        allow2 = np.zeros((m + k, m + k), dtype=bool)
+        allow2[:m, :] = True
+        for i in range(k):
+            allow2[m + i, m:m + i + 1] = True                   # slot i: slots 0..i
+        ref2 = _torch_block_with_mask(blk2, d, 2, ref, ref, allow2)
+        np.testing.assert_allclose(Y[u], ref2, rtol=1e-10, atol=1e-11)
+
+
+def test_learnable_query_descriptors_and_invariants():
+    # descriptors against the rule written out: Eq. 8 for a token placed after the newest one
+    q = orc.query_tokens(1, 3, 4, learnable=True)
+    assert q[1:] == [(False, 4, True), (False, 5, True), (False, 6, True)]
+    got = orc._type_mask(q, orc.key_tokens(1, 6, 4), "full")
+    exp = np.array([[1, 1, 1, 1, 1, 0, 0]] + [[0, 1, 1, 1, 1, 0, 0]] * 3, dtype=bool)
+    np.testing.assert_array_equal(got, exp)
+    np.testing.assert_array_equal(orc._type_mask(q, q, "full"),
+                                  np.array([[1, 1, 1, 1], [0, 1, 0, 0], [0, 1, 1, 0], [0, 1, 1, 1]], dtype=bool))
+    assert all(not t[2] for t in orc.query_tokens(0, 3, 0, learnable=True))
+
+    cfg = synth.tiny_config(B=3, L=24, d=8, K=4, m=2, k_recent=3, n_self=2, q_learnable=True)
+    w, H, G = _case(cfg)
+    assert w["q_learn"].shape == (3, 8)
+    lens = np.array([24, 9, 0])
+    Y, lg = orc.forward(cfg, w, H, G, lens)
+    assert (Y[2, cfg.m:] == 0).all() and np.abs(Y[:2, cfg.m:]).min() > 0     # an empty user has no valid slot
+    # the slots carry no position: their rows do not change when the valid merged tokens are reordered
+    blk = w["cross"]
+    M = _rng(5).standard_normal((1, 6, 8))
+    perm = np.array([3, 0, 5, 1, 4, 2])
+    Xa = orc.hybrid_cross_attn(cfg, blk, G[:1], M, q_learn=w["q_learn"])
+    Xb = orc.hybrid_cross_attn(cfg, blk, G[:1], M[:, perm], q_learn=w["q_learn"])
+    np.testing.assert_allclose(Xa, Xb, rtol=1e-12, atol=1e-13)
+    # ... nor with the global tokens; and they differ from the sampled queries' rows
+    Xc = orc.hybrid_cross_attn(cfg, blk, G[1:2], M, q_learn=w["q_learn"])
+    assert np.array_equal(Xa[0, cfg.m:], Xc[0, cfg.m:])
+    Xs = orc.hybrid_cross_attn(cfg.replace(q_learnable=False), blk, G[:1], M)
+    np.testing.assert_allclose(Xs[0, :cfg.m], Xa[0, :cfg.m], rtol=1e-12, atol=1e-13)   # globals see the same keys
+    assert not np.allclose(Xs[0, cfg.m:], Xa[0, cfg.m:])
+    # padded tokens are never read
+    H2 = H.copy(); H2[1, 9:] = np.nan
+    Y2, lg2 = orc.forward(cfg, w, H2, G, lens)
+    assert np.array_equal(Y2, Y) and np.array_equal(lg2, lg)
+    # serving: cached scoring equals the full pass
+    Gc = _rng(4).standard_normal((3, 2, cfg.m, cfg.d))
+    cache = orc.kv_cache_build(cfg, w, H, lens)
+    Yg, lgs = orc.score_candidates(cfg, w, cache, Gc)
+    for c in range(2):
+        Yc, lc = orc.forward(cfg, w, H, Gc[:, c], lens)
+        np.testing.assert_allclose(Yg[:, c], Yc[:, :cfg.m], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(lgs[:, c], lc, rtol=1e-12, atol=1e-13)
+    # FLOP count: k valid slots each paired with all T_u keys, for users with a token
+    f = orc.algorithmic_flops(cfg, lens)
+    f0 = orc.algorithmic_flops(cfg.replace(q_learnable=False), lens)
+    d, k = cfg.d, cfg.k_recent
+    extra_pairs = (3 * 6 - (4 + 5 + 6)) + 0 + 0            # user 0: recent slots see 4, 5, 6 keys; user 1: 3 tokens = 3 slots, sees 1, 2, 3
+    extra_pairs += (3 * 3 - (1 + 2 + 3))
+    assert f["cross"] - f0["cross"] == 4 * d * extra_pairs
+
+
 def test_I2_all_tokens_as_queries_is_self_attention():
     for gm in ("full", "causal"):
         cfg = synth.tiny_config(B=2, L=16, d=8, K=4, m=2, k_recent=4, gmask=gm)      # k = T
