@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--k-uniform", type=int, default=None,
                     help="sample this many of the k query slots uniformly from the older tokens instead of "
                          "taking the most recent k (Section 3.5.1); the default is the configuration's own")
+    ap.add_argument("--q-learnable", action="store_true",
+                    help="the k query slots hold learnable query tokens instead of sampled sequence tokens "
+                         "(Section 3.5.1)")
     ap.add_argument("--no-serving", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -98,6 +101,8 @@ def main():
     cfg = synth.CONFIGS[args.config]
     if args.k_uniform is not None:
         cfg = cfg.replace(k_uniform=args.k_uniform)
+    if args.q_learnable:
+        cfg = cfg.replace(q_learnable=True)
     case = synth.make_case(cfg)
     model = lg.DeviceModel(cfg, case["weights"], dev)
     B, L = cfg.B, cfg.L
@@ -172,7 +177,8 @@ def main():
         "config": {"workload": "%s: longer_forward, B=%d users, L=%d, d=%d, m=%d, K=%d (T=%d), N_in=%d, k=%d, N=%d, heads=%d%s"
                    % (cfg.name, B, L, cfg.d, cfg.m, cfg.K, cfg.T, cfg.inner_layers, cfg.k_recent, cfg.n_self, cfg.heads,
                       (", merge by concatenation of raw width %d" % cfg.d_in if cfg.merge == "concat" else "")
-                      + (", %d of the k query slots sampled uniformly" % cfg.k_uniform if cfg.k_uniform else "")),
+                      + (", %d of the k query slots sampled uniformly" % cfg.k_uniform if cfg.k_uniform else "")
+                      + (", learnable query tokens" if cfg.q_learnable else "")),
                    "lens": "none" if lens_np is None else "uniform[%d,%d]" % (cfg.len_lo, cfg.len_hi)},
         "algorithmic_gflop_per_step": fl["total"] / 1e9,
         "mfma_peak_frac_whole_step": total_tflops / PEAK_BF16_TFLOPS,

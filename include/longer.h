@@ -88,6 +88,16 @@ typedef struct {
                         shares of the tokens before the recent part), the other k_recent - k_uniform
                         slots the most recent ones; k_uniform = k_recent samples all slots uniformly.
                         A user with no more than k_recent merged tokens gets all of them either way. */
+  const void* q_learn; /* learnable query tokens (Section 3.5.1, the third query strategy of the ablation):
+                        NULL = the query slots are sampled from the sequence as above; else a DEVICE
+                        pointer to [k_recent, d] values of `dtype`, 16-byte aligned, the same for every
+                        user, that take the place of the sampled tokens in O (needs k_uniform = 0).  A
+                        learnable slot is not a sequence position: in the first layer it sees every
+                        valid merged token of the user (and, like all sequence-side rows, no global
+                        token); in the self-causal layers slot i sees slots 0..i.  A user without any
+                        token has no valid slot.  Every entry point that takes this config must be
+                        given the same pointer (the serving calls and longer_self_attn_layer use it
+                        only to tell which slots are valid). */
 } longer_config;
 
 /* One pre-LayerNorm transformer block: 12 d^2 + 13 d scalars for ffn_mult = 4 (Eq. 3).

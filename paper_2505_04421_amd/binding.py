@@ -26,7 +26,8 @@ class CConfig(ctypes.Structure):
                 ("m", ctypes.c_int32), ("K", ctypes.c_int32), ("k_recent", ctypes.c_int32),
                 ("n_self", ctypes.c_int32), ("inner_layers", ctypes.c_int32), ("inner_heads", ctypes.c_int32),
                 ("act", ctypes.c_int32), ("gmask", ctypes.c_int32), ("ln_eps", ctypes.c_float),
-                ("dtype", ctypes.c_int32), ("merge", ctypes.c_int32), ("k_uniform", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("merge", ctypes.c_int32), ("k_uniform", ctypes.c_int32),
+                ("q_learn", ctypes.c_void_p)]
 
 
 class CBlock(ctypes.Structure):
@@ -101,9 +102,10 @@ _DTYPE = {"f32": 0, "bf16": 1}
 _MERGE = {"mean": 0, "concat": 1}
 
 
-def make_config(cfg) -> CConfig:
-    """From any object with the config's attribute names (e.g. longer_synth.Config)."""
-    return CConfig(d=cfg.d, heads=cfg.heads, ffn_mult=cfg.ffn_mult, m=cfg.m, K=cfg.K, k_recent=cfg.k_recent,
+def make_config(cfg, q_learn=None) -> CConfig:
+    """From any object with the config's attribute names (e.g. longer_synth.Config); ``q_learn`` is the
+    device tensor [k_recent, d] of learnable query tokens (the caller keeps it alive), or None."""
+    return CConfig(q_learn=_ptr(q_learn), d=cfg.d, heads=cfg.heads, ffn_mult=cfg.ffn_mult, m=cfg.m, K=cfg.K, k_recent=cfg.k_recent,
                    n_self=cfg.n_self, inner_layers=cfg.inner_layers, inner_heads=cfg.inner_heads,
                    act=_ACT[cfg.act], gmask=_GMASK[cfg.gmask], ln_eps=cfg.ln_eps, dtype=_DTYPE[cfg.dtype],
                    merge=_MERGE[getattr(cfg, "merge", "mean")], k_uniform=getattr(cfg, "k_uniform", 0))
@@ -153,6 +155,9 @@ class DeviceModel:
         self._keep += [hw, hb]
         self.weights = CWeights(inner=self.inner, cross=self.cross, self=self.self_,
                                 head_w=hw.data_ptr(), head_b=hb.data_ptr())
+        if getattr(cfg, "q_learnable", False):
+            self.q_learn = self.upload(weights["q_learn"])
+            self.ccfg.q_learn = self.q_learn.data_ptr()
 
     def upload(self, a):
         import torch

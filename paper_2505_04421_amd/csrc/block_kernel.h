@@ -49,6 +49,7 @@ struct BlockParams {
   int rows_per_user, tiles_per_user;
   int gather_recent;    // src1 row of slot i is its sampled merged token (cross layer) instead of i
   int k_uni;            // the first k_uni of the k slots hold uniformly sampled older tokens
+  int q_learn;          // the k slots hold learnable query tokens (rows of src1, the same for every user)
   int q0;               // MODE_ATTN: first query row (0: globals + slots, m: slots only)
   // stored K/V fragments: per user kt_per_user key tiles of NT*GPT fragments each
   char* kst; char* vst;
@@ -175,6 +176,12 @@ __device__ __forceinline__ float gelu_fn(float x) {
   // (the compiler folds the median with 0 and 1 into the FMA's clamp modifier)
   const float phi = __builtin_amdgcn_fmed3f(fmaf(x, pl, 0.5f), 0.f, 1.f);
   return x * phi;
+}
+
+// First valid one of a user's k query slots: sampled tokens are right-aligned; learnable query
+// tokens (Section 3.5.1) are all valid as soon as the user has a token to attend to.
+__device__ __forceinline__ int first_slot(int k, int tu, int q_learn) {
+  return q_learn ? (tu > 0 ? 0 : k) : max(k - tu, 0);
 }
 
 // Merged token held by slot i of the k sampled sequence queries of a user with tu merged tokens
@@ -469,14 +476,15 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       if (u < p.B) { len = p.lens ? p.lens[u] : p.L; len = min(max(len, 0), p.L); }
       const int tu = (len + p.K - 1) / p.K;
       const bool glob = a < p.m;
-      const int i = a - p.m, i0 = max(p.k - tu, 0);
+      const int i = a - p.m, i0 = first_slot(p.k, tu, p.q_learn);
       valid[tt] = inrange[tt] && (glob || i >= i0);
       usr[tt] = u; Tu[tt] = tu;
       out_off[tt] = p.X_ustride * u + (long long)a * D;
       const void* sp = glob ? p.src0.p : p.src1.p;
       const int sf = glob ? p.src0.f32 : p.src1.f32;
       const long long su = glob ? p.src0.ustride : p.src1.ustride;
-      const int tok = glob ? 0 : slot_token(i, p.k, tu, p.k_uni);
+      // a learnable query token stands after the user's newest token: it sees all of them
+      const int tok = glob ? 0 : (p.q_learn ? tu - 1 : slot_token(i, p.k, tu, p.k_uni));
       const int row = glob ? a : (p.gather_recent ? tok : i);
       load_rows<T, NT>(resid[tt], sp, sf, su * u + (long long)row * D, valid[tt], hi);
       // visible key ranges (Eq. 8 by token type)
@@ -729,7 +737,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
             kb = p.kst + (size_t)uu * p.kv_ustride; vb = p.vst + (size_t)uu * p.kv_ustride;
             nkt = __builtin_amdgcn_readfirstlane(kthi[tt]); rlo = 0; rhi = 0;
           } else {
-            const int i0 = max(p.k - tuu, 0);
+            const int i0 = first_slot(p.k, tuu, p.q_learn);
             if (layer == 0) {
               kb = p.cache + (size_t)uu * p.c0_ustride; vb = kb + p.c0_voff;
               nkt = min(p.kt0, (tuu + 31) / 32); rlo = 0; rhi = tuu;

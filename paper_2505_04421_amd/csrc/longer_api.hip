@@ -257,6 +257,8 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
   if (c->m <= 0 || 32 % c->m) return fail(LONGER_ERR_ARG, "m=%d must divide 32", c->m);
   if (c->k_recent <= 0) return fail(LONGER_ERR_ARG, "k_recent=%d", c->k_recent);
   if (c->k_uniform < 0 || c->k_uniform > c->k_recent) return fail(LONGER_ERR_ARG, "k_uniform=%d must lie in [0, k_recent]", c->k_uniform);
+  if (c->q_learn && c->k_uniform) return fail(LONGER_ERR_ARG, "learnable query tokens exclude k_uniform=%d", c->k_uniform);
+  if (((uintptr_t)c->q_learn & 15) != 0) return fail(LONGER_ERR_ARG, "q_learn must be 16-byte aligned");
   if (c->n_self < 0 || c->inner_layers < 0 || c->n_self + c->inner_layers + 1 > 32)
     return fail(LONGER_ERR_ARG, "layer counts out of range");
   s->D = c->d; s->FF = c->ffn_mult * c->d; s->es = c->dtype == LONGER_BF16 ? 2 : 4;
@@ -407,6 +409,7 @@ static BlockParams base_params(const longer_config* c, const Shape& s, const int
   p.scale_l2e = (float)(1.4426950408889634 / std::sqrt((double)DH));
   p.act = c->act; p.gmask_causal = c->gmask == LONGER_GMASK_CAUSAL;
   p.lens = lens; p.B = B; p.L = L; p.K = c->K; p.T = cdiv(L, c->K); p.m = c->m; p.k = c->k_recent; p.k_uni = c->k_uniform;
+  p.q_learn = c->q_learn != nullptr;
   return p;
 }
 
@@ -577,6 +580,7 @@ static AttnIO cross_io(const longer_config* cfg, const Shape& s, const Layout& l
   io.q0 = 0; io.q_rows = s.n;
   io.kst = w8 + l.kst; io.vst = w8 + l.vst; io.kv_ustride = l.kv_ustride;
   io.q0src = io.src0; io.q1src = io.src1;
+  if (cfg->q_learn) { io.q1src = RowSrc{cfg->q_learn, 0, 0}; io.gather_recent = 0; }   // slot i = row i, every user
   io.X_out = X_out; io.X_f32 = X_f32; io.X_ustride = (long long)s.n * s.D;
   return io;
 }
@@ -739,6 +743,7 @@ int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, con
   io.q0 = cfg->m; io.q_rows = cfg->k_recent;
   io.kst = c8; io.vst = c8 + cl.c0_voff; io.kv_ustride = cl.c0_ustride;
   io.q0src = io.src0; io.q1src = io.src1;
+  if (cfg->q_learn) { io.q1src = RowSrc{cfg->q_learn, 0, 0}; io.gather_recent = 0; }
   io.X_out = xbuf[0]; io.X_f32 = 1; io.X_ustride = (long long)s.n * s.D;
   if ((rc = run_layer(cfg, s, pk_cross, lens, U, L, io, cfg->n_self > 0, st))) return rc;
   for (int i = 0; i < cfg->n_self; ++i) {

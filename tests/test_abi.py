@@ -48,6 +48,19 @@ def test_bad_config_is_rejected(field, value):
     assert lg.longer_last_error() != ""
 
 
+def test_learnable_query_pointer_checks():
+    import ctypes as ct
+    cfg = lg.make_config(synth.CONFIGS["C3"])
+    assert ct.sizeof(cfg) == 72 and type(cfg).q_learn.offset == 64     # 15 x 4 bytes, padding, one pointer
+    cfg.q_learn = 4096                     # never dereferenced: size queries and argument checks only
+    assert lg.longer_workspace_bytes(cfg, 4, 64) > 0
+    cfg.q_learn = 4096 + 8
+    assert lg.longer_workspace_bytes(cfg, 4, 64) == 0 and "q_learn" in lg.longer_last_error()
+    cfg.q_learn = 4096
+    cfg.k_uniform = 10
+    assert lg.longer_workspace_bytes(cfg, 4, 64) == 0 and "k_uniform" in lg.longer_last_error()
+
+
 def test_concat_merge_needs_a_supported_inner_width():
     # d = 128, K = 8: the InnerTrans width would be 16, not a multiple of 32
     cfg = lg.make_config(synth.CONFIGS["C3"].replace(merge="concat"))

@@ -58,7 +58,7 @@ def _entry_points(case, tol, with_inner=True):
     # entry point is compared in isolation, then end to end
     rnd = synth.round_bf16 if cfg.dtype == "bf16" else (lambda a: a.astype(np.float32))
     M_in = rnd(M_ref.astype(np.float32))
-    X1_ref = orc.hybrid_cross_attn(cfg, w["cross"], G, M_in, lens, L=cfg.L)
+    X1_ref = orc.hybrid_cross_attn(cfg, w["cross"], G, M_in, lens, L=cfg.L, q_learn=w.get("q_learn"))
     _check("longer_hybrid_cross_attn", r.cross(G, M_in), X1_ref, tol)
     if cfg.n_self:
         X_in = rnd(X1_ref.astype(np.float32))
@@ -217,6 +217,39 @@ def test_bf16_sampled_query_slots(k_recent, k_uniform):
     case["H"][0] = synth.round_bf16(np.random.default_rng(11).standard_normal(case["H"][0].shape).astype(np.float32))
     case["H"][1, 300:] = np.nan
     _say("bf16 sampled query slots, k=%d, k_uniform=%d" % (k_recent, k_uniform))
+    _entry_points(case, TOL["bf16"], with_inner=False)
+    _serving(case, TOL["bf16"])
+
+
+def test_fp32_learnable_query_tokens():
+    """Learnable query tokens in place of sampled ones: ragged users, one with fewer merged tokens
+    than slots (all slots still valid) and one of length 0 (no valid slot); serving as well."""
+    cfg = synth.CONFIGS["C1"].replace(B=5, L=70, k_recent=9, q_learnable=True, n_self=2, C=6,
+                                      ragged=True, len_lo=1, len_hi=70, index=25)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"] = np.array([70, 0, 13, 29, 41], dtype=np.int32)
+    H = np.random.default_rng(12).standard_normal(case["H"].shape).astype(np.float32)
+    pos = np.arange(cfg.L)[None, :, None]
+    case["H"] = np.where(pos < case["lens"][:, None, None], H, np.float32("nan")).astype(np.float32)
+    _say("fp32 learnable query tokens")
+    _entry_points(case, TOL["f32"], with_inner=False)
+    _serving(case, TOL["f32"])
+
+
+@pytest.mark.parametrize("k_recent,gmask", [(100, "full"), (150, "causal")])
+def test_bf16_learnable_query_tokens(k_recent, gmask):
+    """The ablation's 100 learnable queries (one workgroup per user runs the whole reduced stack)
+    and 150 of them (one launch pair per layer); forward, every entry point, serving."""
+    cfg = synth.CONFIGS["C2"].replace(B=6, L=2000, K=8, m=4, k_recent=k_recent, q_learnable=True, n_self=2,
+                                      gmask=gmask, ragged=True, len_lo=40, len_hi=2000, C=10, index=26)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"][0] = 2000
+    case["lens"][1] = 300          # 38 merged tokens < slots
+    case["lens"][2] = 0
+    case["H"][0] = synth.round_bf16(np.random.default_rng(13).standard_normal(case["H"][0].shape).astype(np.float32))
+    case["H"][1, 300:] = np.nan
+    case["H"][2] = np.nan
+    _say("bf16 learnable query tokens, k=%d, gmask %s" % (k_recent, gmask))
     _entry_points(case, TOL["bf16"], with_inner=False)
     _serving(case, TOL["bf16"])
 
