@@ -78,6 +78,10 @@ def main():
     ap.add_argument("--q-learnable", action="store_true",
                     help="the k query slots hold learnable query tokens instead of sampled sequence tokens "
                          "(Section 3.5.1)")
+    ap.add_argument("--from-inputs", type=int, default=0, metavar="D_E",
+                    help="time longer_forward_from_inputs (input generation inside the merge kernel, Section 3.5.1) "
+                         "on item embeddings of width D_E and time-difference features of width d - D_E, and "
+                         "report the two-call sequence longer_input_generation + longer_forward beside it")
     ap.add_argument("--no-serving", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -120,6 +124,35 @@ def main():
     def step(i):
         lg.longer_forward(model.ccfg, model.weights, Hs[i % nbuf], G, lens, B, L, Y, logits, ws)
 
+    two_call_ms = None
+    if args.from_inputs:
+        d_e = args.from_inputs
+        icase = synth.make_input_case(cfg.replace(ragged=False), d_e)
+        mlp = {k: model.upload(v) for k, v in icase["mlp"].items()}
+        iw = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
+        Es = [model.upload(icase["E"])]
+        Ts = [model.upload(icase["tdiff"])]
+        for i in range(1, nbuf):
+            Es.append(torch.roll(Es[0], shifts=i, dims=0).contiguous())
+            Ts.append(torch.roll(Ts[0], shifts=i, dims=0).contiguous())
+
+        def two_calls(i):
+            lg.longer_input_generation(model.ccfg, iw, Es[i % nbuf], Ts[i % nbuf], lens, B, L, d_e, Hs[i % nbuf], ws)
+            lg.longer_forward(model.ccfg, model.weights, Hs[i % nbuf], G, lens, B, L, Y, logits, ws)
+
+        for i in range(args.warmup):
+            two_calls(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            two_calls(i)
+        torch.cuda.synchronize()
+        two_call_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+        def step(i):
+            lg.longer_forward_from_inputs(model.ccfg, model.weights, iw, Es[i % nbuf], Ts[i % nbuf], d_e, G, lens, B, L,
+                                          Y, logits, ws)
+
     if args.copy_probe_mib > 0:
         src = torch.empty(args.copy_probe_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
@@ -148,6 +181,9 @@ def main():
     seq_per_s = B / (dt / args.steps)
 
     fl, _ = _oracle_flops(cfg, lens_np)
+    if args.from_inputs:       # the MLP's two GEMMs on every valid raw token run inside the merge launch
+        mlp_flop = 4.0 * cfg.d * cfg.ffn_mult * cfg.d * float(B * L if lens_np is None else lens_np.sum())
+        fl = dict(fl, inner=fl["inner"] + mlp_flop, total=fl["total"] + mlp_flop)
     merge_ms, merge_n = stages["merge"]
     merge_avg_ms = merge_ms / max(merge_n, 1)
     achieved = fl["inner"] / (merge_avg_ms * 1e-3) / 1e12
@@ -178,17 +214,23 @@ def main():
                    % (cfg.name, B, L, cfg.d, cfg.m, cfg.K, cfg.T, cfg.inner_layers, cfg.k_recent, cfg.n_self, cfg.heads,
                       (", merge by concatenation of raw width %d" % cfg.d_in if cfg.merge == "concat" else "")
                       + (", %d of the k query slots sampled uniformly" % cfg.k_uniform if cfg.k_uniform else "")
-                      + (", learnable query tokens" if cfg.q_learnable else "")),
+                      + (", learnable query tokens" if cfg.q_learnable else "")
+                      + (", from raw inputs (item width %d + time-difference width %d, MLP inside the merge kernel)"
+                         % (args.from_inputs, cfg.d - args.from_inputs) if args.from_inputs else "")),
                    "lens": "none" if lens_np is None else "uniform[%d,%d]" % (cfg.len_lo, cfg.len_hi)},
         "algorithmic_gflop_per_step": fl["total"] / 1e9,
         "mfma_peak_frac_whole_step": total_tflops / PEAK_BF16_TFLOPS,
         "stage_ms_per_step": {k: v[0] / args.steps for k, v in stages.items() if v[1]},
         "roofline": {"kernel": roof_kernel, "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(cfg),
+                     "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": None if args.from_inputs else measured_traffic(cfg),
                      "avg_launch_ms": roof_ms, "algorithmic_gflop_per_launch": roof_flop / 1e9,
                      "merge_algorithmic_hbm_GBs": merge_bytes / (merge_avg_ms * 1e-3) / 1e9},
     }
+
+    if two_call_ms is not None:
+        out["input_generation_then_forward_ms_per_step"] = two_call_ms
 
     if not args.no_serving:
         c5 = synth.CONFIGS["C5"]

@@ -191,6 +191,16 @@ int longer_input_generation(const longer_config* cfg, const longer_input_weights
                             const void* tdiff, const int32_t* lens, int B, int L, int d_e,
                             void* H_out, void* ws, size_t ws_bytes, void* stream);
 
+/* longer_forward on the raw inputs of the input-generation stage (Section 3.5.1 in front of
+ * Section 3.4): H = MLP([E + pos ; tdiff]) is formed inside the token-merge kernel, in front of
+ * the InnerTrans blocks, and never written to memory (it stays in fp32, where the two-call
+ * sequence longer_input_generation + longer_forward rounds it to `dtype` in between).
+ * Arguments as in longer_input_generation and longer_forward; merge mode LONGER_MERGE_MEAN only. */
+int longer_forward_from_inputs(const longer_config* cfg, const longer_weights* w, const longer_input_weights* iw,
+                               const void* E, const void* tdiff, int d_e, const void* G, const int32_t* lens,
+                               int B, int L, void* Y_out, float* logits_out,
+                               void* ws, size_t ws_bytes, void* stream);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* longer_last_error(void);
 

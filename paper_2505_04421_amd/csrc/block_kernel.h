@@ -1,4 +1,4 @@
-// The transformer-block kernel of the LONGER hot path, in four modes:
+// The transformer-block kernel of the LONGER hot path and its modes:
 //
 //   MODE_MERGE   token merge (Section 3.4): gather K-groups of raw tokens, run the
 //                InnerTrans blocks on them with attention inside each group, mean-pool
@@ -15,7 +15,12 @@
 //                (needs m + k <= 128 rows);
 //   MODE_SCORE   candidate scoring of the KV-cache serving path (Section 3.6.3): the m
 //                global tokens of each candidate through all 1 + N layers, attending to
-//                their own globals (inside the tile) and the cached sequence K/V.
+//                their own globals (inside the tile) and the cached sequence K/V;
+//   MODE_INPUT   input generation (Section 3.5.1): the FFN stage alone, as a two-layer MLP
+//                over rows built from item embedding + positional embedding and the
+//                time-difference features;
+//   MODE_MERGE_IN  MODE_INPUT and MODE_MERGE in one pass: the MLP's result stays in the
+//                registers as the rows the InnerTrans blocks start from.
 //
 // Every mode runs the same register-resident chain (see device.h); they differ in where
 // rows come from, which attention sources exist and what is written.
@@ -60,8 +65,9 @@ struct BlockParams {
   // MODE_ATTN / MODE_SCORE outputs
   void* X_out; int X_f32; long long X_ustride;
   float* logits; const float* head;   // head: fp32 [m*D] weights then the bias
-  // MODE_INPUT: item embeddings [B, L, de], positional embedding [L, de], time-difference features
-  // [B, L, D - de] (element type T); the result goes to X_out [B, L, D]
+  // MODE_INPUT / MODE_MERGE_IN: item embeddings [B, L, de], positional embedding [L, de],
+  // time-difference features [B, L, D - de] (element type T); MODE_INPUT writes the result to
+  // X_out [B, L, D]
   const void* in_e; const void* in_pos; const void* in_td; int de;
   // MODE_SCORE
   int xcds, wg_per_user;   // workgroup index -> (user, group of tiles), see the kernel
@@ -377,6 +383,25 @@ __device__ __forceinline__ void softmax_window(const f32x16& S, int widx, const 
   }
 }
 
+// Row `r` = (user, position) of the input-generation stage (Section 3.5.1): feature tiles below
+// de hold item embedding + positional embedding, the others the time-difference features.
+template <typename T, int NT>
+__device__ __forceinline__ void input_rows(f32x16 (&x)[NT], const BlockParams& p, long long r, int pos, bool valid, int hi) {
+  const int nte = p.de / 32, dt = NT * 32 - p.de;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    f32x16 a[1], b[1];
+    if (t < nte) {
+      load_rows<T, 1>(a, p.in_e, 0, r * p.de + 32 * t, valid, hi);
+      load_rows<T, 1>(b, p.in_pos, 0, (long long)pos * p.de + 32 * t, valid, hi);
+      x[t] = a[0] + b[0];
+    } else {
+      load_rows<T, 1>(a, p.in_td, 0, r * dt + 32 * (t - nte), valid, hi);
+      x[t] = a[0];
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------- the kernel
 template <typename T, int D, int DH, int TT, int MODE, int W>
 __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE_STACK) ? 2 : 1) block_kernel(const BlockParams p) {
@@ -386,7 +411,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   constexpr int SEGV = NG * 64;
   constexpr int HPT = 32 / DH;        // heads per 32-feature tile
   constexpr int GPH = DH / E::GF;     // operand groups per head
-  constexpr bool FUSED = (MODE == MODE_MERGE || MODE == MODE_SCORE);
+  constexpr bool MERGE = MODE == MODE_MERGE || MODE == MODE_MERGE_IN;
+  constexpr bool FUSED = (MERGE || MODE == MODE_SCORE);
   constexpr bool EXT = (MODE == MODE_ATTN || MODE == MODE_SCORE);
   constexpr bool STACK = MODE == MODE_STACK;
   constexpr bool ATTNLIKE = MODE == MODE_ATTN || STACK;   // rows are [globals; recent slots] of a user
@@ -394,7 +420,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   // fragment: the d <= 128 stack kernel takes scheduling hints (frag_pipeline_hint); at d = 256 the
   // compiler ignores them under its register pressure and the reads are placed ahead by hand.
   // The two-wave merge kernel takes the hints too (1 % faster)
-  constexpr bool PIPE = sizeof(T) == 2 && TT == 1 && (STACK || MODE == MODE_MERGE) && D < 256;
+  constexpr bool PIPE = sizeof(T) == 2 && TT == 1 && (STACK || MERGE) && D < 256;
   constexpr bool MANUAL = sizeof(T) == 2 && TT == 1 && D >= 256;
   constexpr bool BIGSEG = SEGV * 16 >= 16384;
   constexpr int PSEG = BIGSEG ? 1 : 4;              // segments per panel of the weight stream (one barrier per panel)
@@ -440,7 +466,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
     valid[tt] = false; inrange[tt] = false; usr[tt] = 0; Tu[tt] = 0; out_off[tt] = 0; tilebits[tt] = 0;
     lo1[tt] = hi1[tt] = lo2[tt] = hi2[tt] = kthi[tt] = 0;
     slo1[tt] = shi1[tt] = slo2[tt] = shi2[tt] = 0;
-    if (MODE == MODE_MERGE) {
+    if (MERGE) {
       // K divides 32, so it is a power of two; the launcher keeps the slot count below 2^31
       const uint32_t slot = (uint32_t)tile * 32u + (uint32_t)j;
       const uint32_t gidx = slot >> __builtin_ctz(p.K);
@@ -453,7 +479,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       valid[tt] = inrange[tt] && pos < len;
       usr[tt] = u; Tu[tt] = len;             // Tu holds the raw length here
       out_off[tt] = slot;                    // group-slot index; scaled when writing
-      load_rows<T, NT>(resid[tt], p.H, 0, ((long long)u * p.L + pos) * D, valid[tt], hi);
+      if (MODE == MODE_MERGE_IN) input_rows<T, NT>(resid[tt], p, (long long)u * p.L + pos, pos, valid[tt], hi);
+      else load_rows<T, NT>(resid[tt], p.H, 0, ((long long)u * p.L + pos) * D, valid[tt], hi);
       const uint32_t vb = (uint32_t)__ballot(valid[tt]);
       const uint32_t gb = (p.K >= 32 ? 0xffffffffu : ((1u << p.K) - 1u)) << (p.K * (j / p.K));
       tilebits[tt] = ((gb & vb) >> (4 * hi)) >> (2 * W * widx);
@@ -512,19 +539,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       if (inrange[tt]) { len = p.lens ? p.lens[u] : p.L; len = min(max(len, 0), p.L); }
       valid[tt] = inrange[tt] && pos < len;
       usr[tt] = u; out_off[tt] = r * D;
-      const int nte = p.de / 32, dt = D - p.de;
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        f32x16 a[1], b[1];
-        if (t < nte) {
-          load_rows<T, 1>(a, p.in_e, 0, r * p.de + 32 * t, valid[tt], hi);
-          load_rows<T, 1>(b, p.in_pos, 0, (long long)pos * p.de + 32 * t, valid[tt], hi);
-          resid[tt][t] = a[0] + b[0];
-        } else {
-          load_rows<T, 1>(a, p.in_td, 0, r * dt + 32 * (t - nte), valid[tt], hi);
-          resid[tt][t] = a[0];
-        }
-      }
+      input_rows<T, NT>(resid[tt], p, r, pos, valid[tt], hi);
     } else {  // MODE_SCORE
       const int u = su;
       const int a = 32 * tile + j;
@@ -541,7 +556,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
     }
   }
 
-  if (MODE == MODE_MERGE) {
+  if (MERGE) {
     // a workgroup whose tokens are all padding writes zeros and leaves
     bool any = false;
 #pragma unroll
@@ -561,8 +576,10 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   WStream<SEGV, PSEG, NB, MODE == MODE_KVPROJ> ws;
   const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : MODE == MODE_INPUT ? 2 * NC : (ATTNLIKE ? 2 * NT + 2 * NC : 4 * NT + 2 * NC));
   // MODE_STACK: the cross block's attention sub-stream, then the self blocks in the fused
-  // layout, each followed by the unused segment that fills its slot in the packed buffer
-  ws.init(lds, p.wbase, STACK ? steps + (p.n_layers - 1) * (2 + 4 * NT + 2 * NC) : steps * p.n_layers);
+  // layout, each followed by the unused segment that fills its slot in the packed buffer.
+  // MODE_MERGE_IN: the input MLP's segments, then the InnerTrans blocks (n_layers counts both)
+  ws.init(lds, p.wbase, STACK ? steps + (p.n_layers - 1) * (2 + 4 * NT + 2 * NC)
+                              : MODE == MODE_MERGE_IN ? 1 + 2 * NC + (p.n_layers - 1) * steps : steps * p.n_layers);
 
   // hands the NG weight fragments of the current segment to use(s, w) one by one; MANUAL keeps
   // AH reads in flight in front of the MFMA that is being issued (the order is pinned)
@@ -601,9 +618,11 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
     const VecLayout vl{D, p.FF};
     grp xn[TT][NG];
     const bool selfl = STACK && layer > 0;   // a self-causal layer of the stack: K/V made here
-    if constexpr (MODE == MODE_INPUT) {
-      // input generation: no norm, no attention, no residual -- the rows themselves are the first
-      // GEMM's operand and the result starts from the output bias
+    // input generation (alone, or as the pass in front of the InnerTrans blocks): no norm, no
+    // attention, no residual -- the rows themselves are the first GEMM's operand and the result
+    // starts from the output bias
+    const bool mlp_only = MODE == MODE_INPUT || (MODE == MODE_MERGE_IN && layer == 0);
+    if (mlp_only) {
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
@@ -835,7 +854,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 
     // FFN, 32 hidden features at a time: hidden chunk never leaves registers
     layer_norm<T, D, TT>(resid, vec + vl.ln2_g(), vec + vl.ln2_b(), p.eps, hi, xn);
-    }   // MODE != MODE_INPUT
+    }   // !mlp_only
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {      // FFN output bias goes in first: the vectors may be
       const f32x16 b2 = bias_tile(vec + vl.b2(), nt, hi);   // replaced right after the last segment
@@ -920,7 +939,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 
   wait_vmcnt<0>();   // nothing of the weight stream may still be in flight when the wave ends
   // ------------------------------------------------------------------ epilogues
-  if (MODE == MODE_MERGE) {
+  if (MERGE) {
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       if (p.Z_out && inrange[tt]) store_rows<T, NT>(resid[tt], p.Z_out, p.Z_f32, out_off[tt] * D, valid[tt], hi);
@@ -1014,6 +1033,11 @@ int launch_block(int mode, int tt, int win, const BlockParams& p, dim3 grid, hip
       case MODE_ATTN: LONGER_LAUNCH(T, D, DH, 1, MODE_ATTN, 16); break;                               \
       case MODE_STACK: LONGER_LAUNCH(T, D, DH, 1, MODE_STACK, 16); break;                             \
       case MODE_INPUT: LONGER_LAUNCH(T, D, DH, 1, MODE_INPUT, 16); break;                             \
+      case MODE_MERGE_IN:                                                                             \
+        if (win == 4) LONGER_LAUNCH(T, D, DH, 1, MODE_MERGE_IN, 4);                                   \
+        else if (win == 8) LONGER_LAUNCH(T, D, DH, 1, MODE_MERGE_IN, 8);                              \
+        else LONGER_LAUNCH(T, D, DH, 1, MODE_MERGE_IN, 16);                                           \
+        break;                                                                                        \
       case MODE_SCORE:                                                                                \
         if (win == 4) LONGER_LAUNCH(T, D, DH, 1, MODE_SCORE, 4);                                      \
         else if (win == 8) LONGER_LAUNCH(T, D, DH, 1, MODE_SCORE, 8);                                 \

@@ -135,7 +135,7 @@ __host__ __device__ inline size_t packed_block_bytes(int D, int FF, int es) {
   return (size_t)(fused_segs(D, FF) + 1) * packed_seg_bytes(D, es);
 }
 
-enum Mode { MODE_MERGE = 0, MODE_KVPROJ = 1, MODE_ATTN = 2, MODE_SCORE = 3, MODE_STACK = 4, MODE_INPUT = 5 };
+enum Mode { MODE_MERGE = 0, MODE_KVPROJ = 1, MODE_ATTN = 2, MODE_SCORE = 3, MODE_STACK = 4, MODE_INPUT = 5, MODE_MERGE_IN = 6 };
 
 // 16 bytes per lane from global memory straight into LDS (no VGPR round trip):
 // lane i of the wave writes LDS bytes [lds_wave_base + 16 i, +16).  lds_wave_base must be

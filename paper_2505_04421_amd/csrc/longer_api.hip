@@ -317,7 +317,7 @@ struct Layout {
 static Layout make_layout(const longer_config* c, const Shape& s, int B, int L) {
   Layout l;
   const int T = cdiv(L, c->K);
-  const int nblk = c->inner_layers + 1 + c->n_self;
+  const int nblk = c->inner_layers + 1 + c->n_self + 1;   // + the input MLP in front of the InnerTrans blocks
   size_t o = 0;
   l.packed = o; o += (size_t)nblk * s.pb + 4 * s.seg;   // a stream may read whole panels past its end
   l.head = o; o += align256(((size_t)c->m * s.D + 1) * 4);
@@ -437,18 +437,35 @@ static int check_slots(const longer_config* c, int B, int L) {
 }
 
 // -- stage launchers (packed parameters already in place) -----------------------------
+// Raw inputs of the input-generation stage when it runs inside the merge kernel
+struct MergeInput { const longer_input_weights* w; const void* E; const void* tdiff; int d_e; };
+
+static int check_input(const longer_config* cfg, const longer_input_weights* w, const void* E, const void* tdiff, int d_e) {
+  if (!w || !w->pos || !E || !tdiff) return fail(LONGER_ERR_ARG, "NULL argument");
+  if (d_e <= 0 || d_e >= cfg->d || d_e % 32)
+    return fail(LONGER_ERR_ARG, "d_e=%d must be a multiple of 32 below d=%d (the rest is the time-difference width)", d_e, cfg->d);
+  return check_aligned({E, tdiff, w->pos});
+}
+
+// `packed`: the InnerTrans blocks in the fused layout; with `in`, the input MLP's segments
+// followed directly by them, and the rows come from the raw inputs instead of H
 static int run_merge(const longer_config* c, const Shape& s, const char* packed, const void* H, const int32_t* lens,
-                     int B, int L, void* M_out, int M_f32, void* Z_out, int Z_f32, hipStream_t st) {
+                     int B, int L, void* M_out, int M_f32, void* Z_out, int Z_f32, hipStream_t st,
+                     const MergeInput* in = nullptr) {
   BlockParams p = base_params(c, s, lens, B, L, s.DHi);
   p.wbase = packed; p.n_layers = c->inner_layers;
   p.H = H; p.M_out = M_out; p.M_f32 = M_f32; p.Z_out = Z_out; p.Z_f32 = Z_f32;
+  if (in) {
+    p.in_e = in->E; p.in_pos = in->w->pos; p.in_td = in->tdiff; p.de = in->d_e;
+    p.n_layers = c->inner_layers + 1;
+  }
   const int tt = 1;
   const int win = c->K <= 8 ? 4 : (c->K <= 16 ? 8 : 16);
   const long long slots = (long long)B * p.T * c->K;
   if (slots + 32LL * tt * kWaves >= (1LL << 31)) return fail(LONGER_ERR_ARG, "B*ceil(L/K)*K = %lld token slots: at most 2^31 per call", slots);
   const int grid = cdiv(slots, 32LL * tt * kWaves);
   StageScope scope(ST_MERGE, st);
-  int rc = s.inner_fn(MODE_MERGE, tt, win, p, dim3(grid), st);
+  int rc = s.inner_fn(in ? MODE_MERGE_IN : MODE_MERGE, tt, win, p, dim3(grid), st);
   return rc ? fail(LONGER_ERR_HIP, "merge kernel launch failed") : 0;
 }
 
@@ -644,15 +661,20 @@ static int check_weights(const longer_config* cfg, const longer_weights* w) {
   return 0;
 }
 
-int longer_forward(const longer_config* cfg, const longer_weights* w, const void* H, const void* G, const int32_t* lens,
-                   int B, int L, void* Y_out, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
-  g_err[0] = 0;
+// longer_forward, on H or (in != NULL) on the raw inputs of the input-generation stage
+static int forward_impl(const longer_config* cfg, const longer_weights* w, const void* H, const MergeInput* in,
+                        const void* G, const int32_t* lens, int B, int L, void* Y_out, float* logits_out,
+                        void* ws, size_t ws_bytes, void* stream) {
   Shape s;
   int rc = check_cfg(cfg, &s, true, true);
   if (rc) return rc;
   if ((rc = check_weights(cfg, w))) return rc;
-  if (!H || !G || !Y_out) return fail(LONGER_ERR_ARG, "NULL argument");
+  if ((!H && !in) || !G || !Y_out) return fail(LONGER_ERR_ARG, "NULL argument");
   if ((rc = check_aligned({H, G, Y_out}))) return rc;
+  if (in) {
+    if (cfg->merge != LONGER_MERGE_MEAN) return fail(LONGER_ERR_ARG, "input generation produces tokens of width d: merge must be LONGER_MERGE_MEAN");
+    if ((rc = check_input(cfg, in->w, in->E, in->tdiff, in->d_e))) return rc;
+  }
   const Layout l = make_layout(cfg, s, B, L);
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   if ((rc = check_slots(cfg, B, L))) return rc;
@@ -662,14 +684,20 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
   PackBatch pk_batch(cfg, s, st);
   const Shape si = inner_view(cfg, s);
   const bool concat = cfg->merge == LONGER_MERGE_CONCAT;
+  // the merge kernel's stream: (the input MLP,) then the InnerTrans blocks, back to back
+  char* pk_inner0 = pk;
+  if (in) {
+    if ((rc = pk_batch.add_mlp(in->w->w1, in->w->b1, in->w->w2, in->w->b2, pk))) return rc;
+    pk_inner0 = pk + (size_t)mlp_segs(s.FF) * s.seg;
+  }
   {
     // InnerTrans blocks of another width than the main stack's are packed by a launch of their own
     PackBatch pk_inner(cfg, si, st);
     PackBatch& pb = concat ? pk_inner : pk_batch;
-    if ((rc = pb.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(si.D, si.FF) * si.seg))) return rc;
+    if ((rc = pb.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk_inner0, (size_t)fused_segs(si.D, si.FF) * si.seg))) return rc;
     if ((rc = pk_inner.flush())) return rc;
   }
-  char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
+  char* pk_cross = pk + (size_t)(cfg->inner_layers + 1) * s.pb;
   if ((rc = pk_batch.add(w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb))) return rc;
   const bool one_launch = s.n <= 32 * kWaves;   // a user's reduced rows fit one workgroup
   if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, one_launch ? LAYOUT_FUSED : LAYOUT_SPLIT, pk_cross + s.pb, s.pb))) return rc;
@@ -677,7 +705,7 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
   if (logits_out && (rc = pk_batch.add_head(w, head))) return rc;
   if ((rc = pk_batch.flush())) return rc;
 
-  if ((rc = run_merge(cfg, si, pk, H, lens, B, L, concat ? nullptr : w8 + l.M, 1, concat ? w8 + l.M : nullptr, 1, st))) return rc;
+  if ((rc = run_merge(cfg, si, pk, H, lens, B, L, concat ? nullptr : w8 + l.M, 1, concat ? w8 + l.M : nullptr, 1, st, in))) return rc;
   if (one_launch) {
     AttnIO io = cross_io(cfg, s, l, w8, G, w8 + l.M, 1, B, L, Y_out, 0);
     if (logits_out) { io.logits = logits_out; io.head = head; }
@@ -696,6 +724,22 @@ int longer_forward(const longer_config* cfg, const longer_weights* w, const void
     if ((rc = run_layer(cfg, s, pk_cross + (size_t)(i + 1) * s.pb, lens, B, L, si, true, st))) return rc;
   }
   return 0;
+}
+
+int longer_forward(const longer_config* cfg, const longer_weights* w, const void* H, const void* G, const int32_t* lens,
+                   int B, int L, void* Y_out, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  if (!H) return fail(LONGER_ERR_ARG, "NULL argument");
+  return forward_impl(cfg, w, H, nullptr, G, lens, B, L, Y_out, logits_out, ws, ws_bytes, stream);
+}
+
+int longer_forward_from_inputs(const longer_config* cfg, const longer_weights* w, const longer_input_weights* iw,
+                               const void* E, const void* tdiff, int d_e, const void* G, const int32_t* lens,
+                               int B, int L, void* Y_out, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  if (!iw) return fail(LONGER_ERR_ARG, "NULL argument");
+  const MergeInput in{iw, E, tdiff, d_e};
+  return forward_impl(cfg, w, nullptr, &in, G, lens, B, L, Y_out, logits_out, ws, ws_bytes, stream);
 }
 
 int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, const void* H, const int32_t* lens,
@@ -811,10 +855,9 @@ int longer_input_generation(const longer_config* cfg, const longer_input_weights
   Shape s;
   int rc = check_cfg(cfg, &s, false, true);
   if (rc) return rc;
-  if (!w || !w->pos || !E || !tdiff || !H_out) return fail(LONGER_ERR_ARG, "NULL argument");
-  if (d_e <= 0 || d_e >= cfg->d || d_e % 32)
-    return fail(LONGER_ERR_ARG, "d_e=%d must be a multiple of 32 below d=%d (the rest is the time-difference width)", d_e, cfg->d);
-  if ((rc = check_aligned({E, tdiff, H_out, w->pos}))) return rc;
+  if (!H_out) return fail(LONGER_ERR_ARG, "NULL argument");
+  if ((rc = check_input(cfg, w, E, tdiff, d_e))) return rc;
+  if ((rc = check_aligned({H_out}))) return rc;
   const Layout l = make_layout(cfg, s, B, L);
   if ((rc = check_common(ws, ws_bytes, l.total, B, L))) return rc;
   if ((long long)B * L + 32LL * kWaves >= (1LL << 31)) return fail(LONGER_ERR_ARG, "B*L = %lld rows: at most 2^31 per call", (long long)B * L);

@@ -111,3 +111,14 @@ def test_input_generation_rejects_bad_widths():
         assert rc == -1 and "d_e" in lg.longer_last_error()
     rc = lib.longer_input_generation(ctypes.byref(cfg), ctypes.byref(w), fake, fake, None, 4, 64, 96, fake, None, 0, None)
     assert rc == -1 and "workspace" in lg.longer_last_error()
+    # the same checks in front of the forward pass on raw inputs; a concat merge has no width-d raw tokens
+    blk = (lg.binding.CBlock * 2)()
+    wt = lg.binding.CWeights(inner=blk, cross=blk, self=blk, head_w=None, head_b=None)
+    args = (fake, None, 4, 64, fake, None, ctypes.c_void_p(4096), 1 << 40, None)
+    rc = lib.longer_forward_from_inputs(ctypes.byref(cfg), ctypes.byref(wt), ctypes.byref(w), fake, fake, 48, *args)
+    assert rc == -1 and "d_e" in lg.longer_last_error()
+    rc = lib.longer_forward_from_inputs(ctypes.byref(cfg), ctypes.byref(wt), None, fake, fake, 96, *args)
+    assert rc == -1 and "NULL" in lg.longer_last_error()
+    cc = lg.make_config(synth.CONFIGS["P1"])
+    rc = lib.longer_forward_from_inputs(ctypes.byref(cc), ctypes.byref(wt), ctypes.byref(w), fake, fake, 96, *args)
+    assert rc == -1 and "LONGER_MERGE_MEAN" in lg.longer_last_error()

@@ -316,6 +316,57 @@ def test_input_generation(base, d_e, B, L):
     _check("longer_input_generation", H.float().cpu().numpy().astype(np.float64), ref, tol)
 
 
+@pytest.mark.parametrize("base,d_e,B,L", [("C1", 32, 3, 75), ("C3", 96, 5, 333), ("C2", 32, 4, 520)])
+def test_forward_from_inputs(base, d_e, B, L):
+    """The forward pass on the raw inputs (input generation inside the merge kernel) against the
+    oracle's input_generation -> forward, and against the library's own two-call sequence.  Ragged
+    lengths incl. a ragged last group, NaN padding, K = 4 / 8 / 8, one and two InnerTrans layers."""
+    import paper_2505_04421_amd as lg
+    import torch
+    from gpu_util import rel_l2_per_user
+    cfg = synth.CONFIGS[base].replace(B=B, L=L, ragged=True, len_lo=0, len_hi=L, index=29)
+    if base == "C1":
+        cfg = cfg.replace(d=64, heads=4, inner_heads=4, inner_layers=2)
+    case = synth.make_input_case(cfg, d_e)
+    case["lens"][0] = L
+    case["lens"][1] = 0
+    rnd = synth.round_bf16 if cfg.dtype == "bf16" else (lambda a: a)
+    g = np.random.default_rng(15)
+    case["E"][0] = rnd(g.standard_normal(case["E"][0].shape).astype(np.float32))
+    case["tdiff"][0] = rnd(g.standard_normal(case["tdiff"][0].shape).astype(np.float32))
+    G = rnd(g.standard_normal((B, cfg.m, cfg.d)).astype(np.float32))
+    tol = TOL[cfg.dtype]
+    w = synth.draw_weights(cfg)
+    if cfg.dtype == "bf16":
+        w = synth._map_tree(w, synth.round_bf16)
+    model = lg.DeviceModel(cfg, w)
+    mlp = {k: model.upload(v) for k, v in case["mlp"].items()}
+    wts = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
+    Ed, Td, Gd = model.upload(case["E"]), model.upload(case["tdiff"]), model.upload(G)
+    lens = torch.from_numpy(case["lens"].astype(np.int32)).to(model.device)
+    ws = model.workspace(B, L)
+    Y = model.empty(B, cfg.n, cfg.d)
+    logits = model.empty(B, dtype=torch.float32)
+    _say("forward from raw inputs %s d=%d = %d + %d, K=%d, %d InnerTrans layers"
+         % (cfg.dtype, cfg.d, d_e, cfg.d - d_e, cfg.K, cfg.inner_layers))
+    lg.longer_forward_from_inputs(model.ccfg, model.weights, wts, Ed, Td, d_e, Gd, lens, B, L, Y, logits, ws)
+    torch.cuda.synchronize()
+    H_ref = orc.input_generation(cfg, case["mlp"], case["E"], case["tdiff"], case["lens"])
+    Y_ref, lg_ref = orc.forward(cfg, w, H_ref, G, case["lens"])
+    Yh, lh = Y.float().cpu().numpy().astype(np.float64), logits.cpu().numpy().astype(np.float64)
+    _check("longer_forward_from_inputs Y", Yh, Y_ref, tol)
+    _check("longer_forward_from_inputs logits", lh[None, :], lg_ref[None, :], tol)
+    # the two-call sequence (H rounded to the element type in between)
+    H = model.empty(B, L, cfg.d)
+    Y2 = model.empty(B, cfg.n, cfg.d)
+    lg.longer_input_generation(model.ccfg, wts, Ed, Td, lens, B, L, d_e, H, ws)
+    lg.longer_forward(model.ccfg, model.weights, H, Gd, lens, B, L, Y2, None, ws)
+    torch.cuda.synchronize()
+    err = rel_l2_per_user(Yh, Y2.float().cpu().numpy().astype(np.float64))
+    _say("  fused vs two calls (GPU)      rel-L2 max %.3e" % err)
+    assert err <= tol
+
+
 def _random_config(seed):
     """A random small configuration over everything the library accepts (widths, head widths, group
     sizes, global-set sizes, query counts and sampling, layer counts, merge modes, activations, masks)."""
@@ -462,6 +513,34 @@ def test_c4_full_size_sampled_users():
 def test_concat_production_shape_full_size_sampled_users():
     _say("P1 full size (256 users, raw width 32, K = 8, main stack at 256)")
     _full_size_forward("P1", [0, 131, 255])
+
+
+def test_forward_from_inputs_full_size_sampled_users():
+    """The C3 batch shape through longer_forward_from_inputs in the launch configuration the benchmark
+    times (bench.py --from-inputs 96); the oracle recomputes a sample of users from their raw inputs."""
+    import paper_2505_04421_amd as lg
+    cfg = synth.CONFIGS["C3"]
+    d_e = 96
+    _say("C3 full size from raw inputs (256 users x 2000, item width 96 + time-difference width 32)")
+    case = synth.make_case(cfg)
+    icase = synth.make_input_case(cfg, d_e)
+    w = case["weights"]
+    model = lg.DeviceModel(cfg, w)
+    mlp = {k: model.upload(v) for k, v in icase["mlp"].items()}
+    iw = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
+    Ed, Td, Gd = model.upload(icase["E"]), model.upload(icase["tdiff"]), model.upload(case["G"])
+    ws = model.workspace(cfg.B, cfg.L)
+    Y = model.empty(cfg.B, cfg.n, cfg.d)
+    logits = model.empty(cfg.B, dtype=torch.float32)
+    lg.longer_forward_from_inputs(model.ccfg, model.weights, iw, Ed, Td, d_e, Gd, None, cfg.B, cfg.L, Y, logits, ws)
+    torch.cuda.synchronize()
+    Yh, lh = Y.float().cpu().numpy().astype(np.float64), logits.cpu().numpy().astype(np.float64)
+    assert np.isfinite(Yh).all() and np.isfinite(lh).all()
+    idx = np.array([0, 77, 255])
+    H_ref = orc.input_generation(cfg, icase["mlp"], icase["E"][idx], icase["tdiff"][idx])
+    Y_ref, lg_ref = orc.forward(cfg, w, H_ref, case["G"][idx])
+    _check("from raw inputs, sampled users Y", Yh[idx], Y_ref, TOL["bf16"])
+    _check("from raw inputs, sampled logits", lh[idx][None, :], lg_ref[None, :], TOL["bf16"])
 
 
 def test_c5_full_size_sampled_candidates():
