@@ -206,7 +206,9 @@ const char* longer_last_error(void);
 
 /* Measurement aid: when enabled, every kernel launch group of the entry points is bracketed
  * by a pair of HIP events recorded on the caller's stream (at most 8192 pairs between two
- * reads; later launches go unrecorded).  longer_stage_timing_read waits for the recorded
+ * reads; later launches go unrecorded).  enable = 0: off; 1: every stage; any other value:
+ * bit (s + 1) selects stage s (an event pair costs a few microseconds of launch time, so a
+ * caller that wants one kernel's duration inside a timed loop selects that stage alone).  longer_stage_timing_read waits for the recorded
  * events, adds up the elapsed milliseconds and the number of launch groups per stage into
  * HOST arrays of LONGER_NUM_STAGES entries (0 parameter packing, 1 token merge, 2 K/V
  * projection, 3 attention + FFN, 4 candidate scoring) and clears the record.  Not

@@ -269,9 +269,13 @@ def longer_probe_mfma_layout(out, stream=None):
 STAGES = ("pack", "merge", "kvproj", "attn", "score")
 
 
-def longer_stage_timing(enable: bool):
+def longer_stage_timing(enable, stages=None):
+    """Switch the per-stage event timers on (all stages, or only the named ones of STAGES) or off."""
     _require_gpu()
-    _check(load_library().longer_stage_timing(1 if enable else 0), "longer_stage_timing")
+    code = 1 if enable else 0
+    if enable and stages is not None:
+        code = sum(2 << STAGES.index(s) for s in stages)
+    _check(load_library().longer_stage_timing(code), "longer_stage_timing")
 
 
 def longer_stage_timing_read():

@@ -56,7 +56,7 @@ enum Stage { ST_PACK = 0, ST_MERGE = 1, ST_KVPROJ = 2, ST_ATTN = 3, ST_SCORE = 4
 static_assert(LONGER_NUM_STAGES == 5, "stage table");
 struct StageTimer {
   static constexpr int kMaxPairs = 8192;
-  bool on = false;
+  unsigned mask = 0;             // bit s: stage s is timed
   int n = 0;
   hipEvent_t* ev = nullptr;      // 2 * kMaxPairs events, created on first enable
   unsigned char stage[kMaxPairs];
@@ -66,7 +66,7 @@ static StageTimer g_timer;
 struct StageScope {
   hipStream_t st; int idx;
   StageScope(int stage, hipStream_t s) : st(s), idx(-1) {
-    if (g_timer.on && g_timer.n < StageTimer::kMaxPairs) {
+    if ((g_timer.mask >> stage & 1u) && g_timer.n < StageTimer::kMaxPairs) {
       idx = g_timer.n++;
       g_timer.stage[idx] = (unsigned char)stage;
       (void)hipEventRecord(g_timer.ev[2 * idx], st);
@@ -883,7 +883,8 @@ int longer_stage_timing(int enable) {
     for (int i = 0; i < 2 * StageTimer::kMaxPairs; ++i)
       if (hipEventCreate(&g_timer.ev[i]) != hipSuccess) return fail(LONGER_ERR_HIP, "hipEventCreate failed");
   }
-  g_timer.on = enable != 0;
+  // 1 = every stage; any other non-zero value = bit (s + 1) selects stage s
+  g_timer.mask = enable == 1 ? ~0u : (unsigned)enable >> 1;
   g_timer.n = 0;
   return 0;
 }

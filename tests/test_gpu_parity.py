@@ -367,6 +367,50 @@ def test_forward_from_inputs(base, d_e, B, L):
     assert err <= tol
 
 
+def test_forward_and_scoring_under_hip_graph_capture():
+    """The entry points allocate nothing, never synchronise and enqueue kernels only, so a caller may
+    capture them into a HIP graph.  Replayed three times on new inputs, with eager work and
+    synchronisation in between; every replay must equal the eager call bit for bit."""
+    import paper_2505_04421_amd as lg
+    cfg = synth.CONFIGS["C2"].replace(B=16, C=12, ragged=True, len_lo=0, len_hi=512, index=31)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    model = lg.DeviceModel(cfg, case["weights"])
+    B, L = cfg.B, cfg.L
+    ws = model.workspace(B, L, cfg.C)
+    lens = torch.from_numpy(case["lens"].astype(np.int32)).to(model.device)
+    H, G, Gc = model.upload(case["H"]), model.upload(case["G"]), model.upload(case["G_cand"])
+    Y, logits = model.empty(B, cfg.n, cfg.d), model.empty(B, dtype=torch.float32)
+    cache = model.kv_cache(B, L)
+    sc = model.empty(B, cfg.C, dtype=torch.float32)
+
+    def run():
+        lg.longer_forward(model.ccfg, model.weights, H, G, lens, B, L, Y, logits, ws)
+        lg.longer_kv_cache_build(model.ccfg, model.weights, H, lens, B, L, cache, ws)
+        lg.longer_score_candidates(model.ccfg, model.weights, cache, lens, B, L, Gc, cfg.C, None, sc, ws)
+
+    run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(16)
+    for it in range(3):
+        Hn = np.where(np.isnan(case["H"]), np.float32("nan"), synth.round_bf16(rng.standard_normal(case["H"].shape).astype(np.float32)))
+        H.copy_(model.upload(Hn)); G.copy_(model.upload(synth.round_bf16(rng.standard_normal(case["G"].shape).astype(np.float32))))
+        Y.zero_(); logits.zero_(); sc.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (Y.clone(), logits.clone(), sc.clone())
+        Y.zero_(); logits.zero_(); sc.zero_()
+        run()                                   # eager, same buffers
+        torch.cuda.synchronize()
+        _say("  replay %d: |Y| %.3e" % (it, float(Y.float().abs().sum())))
+        assert torch.equal(got[0], Y) and torch.equal(got[1], logits) and torch.equal(got[2], sc)
+    Y_ref, lg_ref = orc.forward(cfg, case["weights"], Hn, G.float().cpu().numpy(), case["lens"])
+    _check("graph replay vs oracle Y", got[0].float().cpu().numpy().astype(np.float64), Y_ref, TOL["bf16"])
+
+
 def _random_config(seed):
     """A random small configuration over everything the library accepts (widths, head widths, group
     sizes, global-set sizes, query counts and sampling, layer counts, merge modes, activations, masks)."""
