@@ -85,6 +85,7 @@ def main():
                          "report the two-call sequence longer_input_generation + longer_forward beside it")
     ap.add_argument("--no-serving", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP graph replay measurement (profiler runs)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known HBM traffic that "
                          "calibrates the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -203,6 +204,8 @@ def main():
     # beside the eager figure, which stays the headline (the stage timers cannot run under capture)
     graph_ms = None
     try:
+        if args.no_graph:
+            raise RuntimeError("switched off with --no-graph")
         graphs = []
         for b in range(nbuf):
             g = torch.cuda.CUDAGraph()
