@@ -14,6 +14,10 @@
  *   - tensors are dense row-major; weights are stored [in, out] so that y = x W + b, the
  *     way Eq. 6 writes Q = O W_Q; element type is `dtype` of the config (fp32 or bf16)
  *     for every activation, weight, bias and LayerNorm vector; logits are always fp32;
+ *     arithmetic: fp32 accumulation, residual stream, LayerNorm and softmax in both modes; in
+ *     bf16 mode the matrix-core operands are bf16, except in the second FFN GEMM, whose
+ *     activated hidden values and weights are fp16 (W2 is converted when it is packed; exact
+ *     for 1.6e-5 <= |w| < 16376), and GELU is a polynomial evaluated in fp16;
  *   - `lens` is int32 [B] raw (un-merged) valid lengths, or NULL for "all L"; sequences are
  *     stored oldest-first and right-padded; padded values are never read into the result
  *     (they may hold NaN);

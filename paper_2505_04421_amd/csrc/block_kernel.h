@@ -170,6 +170,24 @@ __device__ __forceinline__ uint32_t range_bits(int lo, int hi, int base) {
 // degree 9 (minimax fit on [-3.5, 3.5], constrained to reach 1 at the interval end; it keeps
 // growing beyond it) and Phi clamped to [0, 1] by the output modifier of the last fma;
 // max abs error 1.3e-3, below the bf16 rounding step of the values it produces.
+// The same polynomial in packed fp16, two elements per instruction, on y = x / kFfnScale;
+// returns GELU(x) / kFfnScale.  Phi(4 y) - 1/2 = y (k0 + k1 v + ... + k4 v^4), v = y^2, with
+// k_i = 4 * 16^i * c_i of the fp32 coefficients below (all of order 1).  A square that
+// overflows gives an infinite polynomial of the right sign, which the clamp turns into 0 or 1.
+// A whole operand group (8 elements, 4 register pairs) goes through each step together, so that
+// an instruction never uses the result of the one right before it (which costs a wait state).
+__device__ __forceinline__ f16x8 gelu_quarter_h8(f16x8 y) {
+  const f16x8 v = y * y;
+  f16x8 pl = (f16x8)((_Float16)2.4554419175668456f);
+  pl = __builtin_elementwise_fma(pl, v, (f16x8)((_Float16)-6.304095499217479f));
+  pl = __builtin_elementwise_fma(pl, v, (f16x8)((_Float16)6.604333663059149f));
+  pl = __builtin_elementwise_fma(pl, v, (f16x8)((_Float16)-3.771901897714043f));
+  pl = __builtin_elementwise_fma(pl, v, (f16x8)((_Float16)1.5736394077430096f));
+  f16x8 phi = __builtin_elementwise_fma(y, pl, (f16x8)((_Float16)0.5f));
+  phi = __builtin_elementwise_min(__builtin_elementwise_max(phi, (f16x8)((_Float16)0.f)), (f16x8)((_Float16)1.f));
+  return y * phi;
+}
+
 template <bool EXACT>
 __device__ __forceinline__ float gelu_fn(float x) {
   if (EXACT) return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
@@ -879,16 +897,29 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       // registers, so the rest of the activation's VALU work can run under them
 #pragma unroll
       for (int g = 0; g < GPT; ++g) {
-        grp hop[TT];
+        typename E::hgrp hop[TT];
         auto act_group = [&](int gg) {
 #pragma unroll
           for (int tt = 0; tt < TT; ++tt) {
+            if constexpr (E::HALF_FFN) {
+              // ah holds x / kFfnScale; pairs of elements go to fp16 (toward zero: never to
+              // infinity) and through the packed activation
+              f16x8 y;
 #pragma unroll
-            for (int e = 0; e < E::EPL; ++e) {
-              const float v = ah[tt][E::EPL * gg + e];
-              ah[tt][E::EPL * gg + e] = RELU ? fmaxf(v, 0.f) : gelu_fn<sizeof(T) == 4>(v);
+              for (int e = 0; e < E::EPL / 2; ++e) {
+                const f16x2 y2 = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(ah[tt][E::EPL * gg + 2 * e],
+                                                                                      ah[tt][E::EPL * gg + 2 * e + 1]));
+                y[2 * e] = y2[0]; y[2 * e + 1] = y2[1];
+              }
+              hop[tt] = RELU ? __builtin_elementwise_max(y, (f16x8)((_Float16)0.f)) : gelu_quarter_h8(y);
+            } else {
+#pragma unroll
+              for (int e = 0; e < E::EPL; ++e) {
+                const float v = ah[tt][E::EPL * gg + e];
+                ah[tt][E::EPL * gg + e] = RELU ? fmaxf(v, 0.f) : gelu_fn<true>(v);
+              }
+              hop[tt] = E::pack(ah[tt], gg);
             }
-            hop[tt] = E::pack(ah[tt], gg);
           }
         };
         if constexpr (MANUAL) {
@@ -903,7 +934,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
             __builtin_amdgcn_sched_barrier(0);
-            resid[0][nt] = E::mma(ring[nt % AH], hop[0], resid[0][nt]);
+            resid[0][nt] = E::mma_h(ring[nt % AH], hop[0], resid[0][nt]);
             __builtin_amdgcn_sched_barrier(0);
             if (nt + AH < NT) ring[nt % AH] = ws.template frag<grp>((nt + AH) * GPT + g);
           }
@@ -915,18 +946,19 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
         for (int nt = 0; nt < NT; ++nt) {
           const grp w = ws.template frag<grp>(nt * GPT + g);
 #pragma unroll
-          for (int tt = 0; tt < TT; ++tt) resid[tt][nt] = E::mma(w, hop[tt], resid[tt][nt]);
+          for (int tt = 0; tt < TT; ++tt) resid[tt][nt] = E::mma_h(w, hop[tt], resid[tt][nt]);
         }
       }
       if (sizeof(T) == 2 && TT == 1 && !RELU && !MANUAL) {
         // order within this stretch: activation of group 0, the weight fragments, then each
         // MFMA of group 0 followed by a quarter of group 1's activation, then group 1's MFMAs
-        __builtin_amdgcn_sched_group_barrier(0x002, 60, 0);
+        constexpr int VG = 32;   // VALU instructions of one group's activation (4 conversions + 7 x 4 packed ops)
+        __builtin_amdgcn_sched_group_barrier(0x002, VG, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * NT, 0);
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x002, 60 / NT, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, VG / NT, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);
       }

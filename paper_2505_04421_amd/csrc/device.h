@@ -39,6 +39,17 @@ constexpr float kNegBig = -1.0e30f;
 // Element traits: one operand group = 16 bytes per lane.
 template <typename T> struct ET;
 
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// bf16 mode, second FFN GEMM: the activated hidden chunk and the W2 fragments are fp16 (same
+// matrix-core rate as bf16, 11 significand bits instead of 8), so that the activation can be
+// evaluated two elements per instruction in packed fp16.  The pack kernel stores W1 and b1
+// divided by kFfnScale and W2 multiplied by it (powers of two: exact), which keeps the
+// polynomial's argument and coefficients of order 1 in fp16:
+//   act(x) W2 = (act(4 y) / 4) (4 W2),  y = x / 4 = LN2(.) (W1 / 4) + b1 / 4.
+constexpr float kFfnScale = 4.0f;
+
 template <> struct ET<float> {
   typedef f32x4 grp;
   static constexpr int EPL = 4;   // elements per lane per group
@@ -57,6 +68,10 @@ template <> struct ET<float> {
   }
   static __device__ __forceinline__ float to_f32(float v) { return v; }
   static __device__ __forceinline__ float from_f32(float v) { return v; }
+  // the second FFN GEMM's activated operand: the same fp32 groups
+  static constexpr bool HALF_FFN = false;
+  typedef grp hgrp;
+  static __device__ __forceinline__ f32x16 mma_h(grp a, hgrp b, f32x16 c) { return mma(a, b, c); }
 };
 
 template <> struct ET<__bf16> {
@@ -75,6 +90,12 @@ template <> struct ET<__bf16> {
   }
   static __device__ __forceinline__ float to_f32(__bf16 v) { return (float)v; }
   static __device__ __forceinline__ __bf16 from_f32(float v) { return (__bf16)v; }
+  // the second FFN GEMM runs on fp16 operands (see kFfnScale): `a` holds fp16 bits
+  static constexpr bool HALF_FFN = true;
+  typedef f16x8 hgrp;
+  static __device__ __forceinline__ f32x16 mma_h(grp a, hgrp b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), b, c, 0, 0, 0);
+  }
 };
 
 // feature (inside a 32-wide tile) held by accumulator register r of lane half hi

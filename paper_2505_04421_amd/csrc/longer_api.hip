@@ -140,7 +140,7 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
       const int i = within * 4 + e;
       float v = 0.f;
       if (i >= vl.b2() && i < vl.b1()) v = (float)((const T*)raw.b.b2)[i - vl.b2()];
-      else if (i >= vl.b1() && i < vl.total()) v = (float)((const T*)raw.b.b1)[i - vl.b1()];
+      else if (i >= vl.b1() && i < vl.total()) v = (float)((const T*)raw.b.b1)[i - vl.b1()] * (E::HALF_FFN ? 1.0f / kFfnScale : 1.0f);
       out[e] = v;
     }
     reinterpret_cast<f32x4*>(dst)[idx] = out;
@@ -166,6 +166,7 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
         else if (i < vl.b1()) { src = (const T*)raw.b.b2; off = i - vl.b2(); }
         else { src = (const T*)raw.b.b1; off = i - vl.b1(); }
         v = (float)src[off];
+        if (E::HALF_FFN && i >= vl.b1()) v *= 1.0f / kFfnScale;     // the hidden pre-activation is kept as x / kFfnScale
       }
       out[e] = v;
     }
@@ -213,9 +214,20 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
   }
   const int t = sg / E::GPT, g = sg % E::GPT;
   typename E::grp out;
+  typename E::hgrp outh;
   for (int e = 0; e < E::EPL; ++e) {
     const int k = 32 * t + tile_row(E::EPL * g + e, hi);
-    out[e] = W[(size_t)k * ncols + 32 * nt + n_in];
+    const T w = W[(size_t)k * ncols + 32 * nt + n_in];
+    out[e] = w;
+    if constexpr (E::HALF_FFN) {
+      // bf16 mode: W1 / kFfnScale (exact), W2 * kFfnScale as fp16 (exact for 1.6e-5 <= |w| < 16376;
+      // smaller weights lose low bits as fp16 subnormals, larger ones saturate)
+      if (kind == 5) out[e] = (T)((float)w * (1.0f / kFfnScale));
+      outh[e] = (_Float16)fminf(fmaxf((float)w * kFfnScale, -65504.f), 65504.f);
+    }
+  }
+  if constexpr (E::HALF_FFN) {
+    if (kind == 6) out = __builtin_bit_cast(typename E::grp, outh);
   }
   reinterpret_cast<typename E::grp*>(dst)[idx] = out;
 }
