@@ -46,7 +46,17 @@ def _check(name, got, ref, tol):
     return err
 
 
-def _entry_points(case, tol, with_inner=True):
+def _check_logits_by_terms(name, logits, lg_ref, Yg_ref, head_w, tol):
+    """A logit is a sum of m d signed terms: judge it against the size of those terms (a logit that
+    happens to cancel to nearly zero has no meaningful relative error of its own)."""
+    hw = np.abs(np.asarray(head_w, dtype=np.float64))
+    terms = (np.abs(Yg_ref.reshape(-1, hw.size)) * hw[None, :]).sum(1).reshape(lg_ref.shape) + 1e-30
+    err = float((np.abs(logits - lg_ref) / terms).max())
+    _say("  %-28s max error / sum of |terms| %.3e (tol %.0e)" % (name, err, tol))
+    assert np.isfinite(logits).all() and err <= tol, (name, err)
+
+
+def _entry_points(case, tol, with_inner=True, logits_by_terms=False):
     cfg, w = case["cfg"], case["weights"]
     r = _runner(case)
     H, G, lens = case["H"], case["G"], case["lens"]
@@ -67,7 +77,10 @@ def _entry_points(case, tol, with_inner=True):
     Y_ref, lg_ref = orc.forward(cfg, w, H, G, lens)
     Y, logits = r.forward()
     _check("longer_forward Y", Y, Y_ref, tol)
-    _check("longer_forward logits", logits[None, :], lg_ref[None, :], tol)
+    if logits_by_terms:
+        _check_logits_by_terms("longer_forward logits", logits, lg_ref, Y_ref[:, :cfg.m], w["head_w"], tol)
+    else:
+        _check("longer_forward logits", logits[None, :], lg_ref[None, :], tol)
 
 
 def test_c1_fp32_all_entry_points():
@@ -411,6 +424,23 @@ def test_forward_and_scoring_under_hip_graph_capture():
     _check("graph replay vs oracle Y", got[0].float().cpu().numpy().astype(np.float64), Y_ref, TOL["bf16"])
 
 
+@pytest.mark.parametrize("scale", [16.0, 4096.0])
+def test_bf16_large_ffn_preactivations(scale):
+    """FFN pre-activations far outside the interval the bf16-mode GELU polynomial is fitted on (first
+    FFN matrix of every block scaled up, the second scaled down): the clamp has to give x or 0, also
+    where the fp16 square and the polynomial overflow (|x| of a few hundred at scale 16, of ten thousand
+    at scale 4096, where the entries of the second matrix also fall into fp16's subnormal range)."""
+    cfg = synth.CONFIGS["C2"].replace(B=4, L=200, n_self=1, ragged=True, len_lo=20, len_hi=200, C=5, index=33)
+    case = synth.make_case(cfg)
+    w = case["weights"]
+    for blk in w["inner"] + [w["cross"]] + w["self"]:
+        blk["w1"] = synth.round_bf16(blk["w1"] * np.float32(scale))
+        blk["w2"] = synth.round_bf16(blk["w2"] / np.float32(scale))
+    _say("bf16 FFN pre-activations x %g" % scale)
+    _entry_points(case, TOL["bf16"], logits_by_terms=True)
+    _serving(case, TOL["bf16"], logits_by_terms=True)
+
+
 def _random_config(seed):
     """A random small configuration over everything the library accepts (widths, head widths, group
     sizes, global-set sizes, query counts and sampling, layer counts, merge modes, activations, masks)."""
@@ -483,7 +513,7 @@ def test_c4_bf16_ragged_nan_padding():
     _entry_points(case, TOL["bf16"], with_inner=False)
 
 
-def _serving(case, tol):
+def _serving(case, tol, logits_by_terms=False):
     from gpu_util import rel_l2_per_user
     cfg, w = case["cfg"], case["weights"]
     r = _runner(case)
@@ -492,7 +522,10 @@ def _serving(case, tol):
     Yg_ref, lg_ref = orc.score_candidates(cfg, w, cache, case["G_cand"])
     U, C = cfg.B, cfg.C
     _check("longer_score_candidates Yg", Yg.reshape(U * C, -1), Yg_ref.reshape(U * C, -1), tol)
-    _check("longer_score_candidates logit", logits, lg_ref, tol)
+    if logits_by_terms:
+        _check_logits_by_terms("longer_score_candidates logit", logits, lg_ref, Yg_ref, w["head_w"], tol)
+    else:
+        _check("longer_score_candidates logit", logits, lg_ref, tol)
     # KV-cached scoring equals the full forward pass with that candidate's globals (GPU vs GPU)
     Yf, lf = r.forward(G=case["G_cand"][:, 0])
     err = rel_l2_per_user(Yg[:, 0], Yf[:, :cfg.m])
