@@ -421,7 +421,9 @@ __device__ __forceinline__ void input_rows(f32x16 (&x)[NT], const BlockParams& p
 }
 
 // ---------------------------------------------------------------------------- the kernel
-template <typename T, int D, int DH, int TT, int MODE, int W>
+// RELU: the FFN activation (a template parameter: with both activations' loops in one kernel the
+// compiler copies the residual registers in front of one of them)
+template <typename T, int D, int DH, int TT, int MODE, int W, bool RELU>
 __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE_STACK) ? 2 : 1) block_kernel(const BlockParams p) {
   using E = ET<T>;
   using grp = typename E::grp;
@@ -879,8 +881,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) resid[tt][nt] += b2;
     }
-    auto ffn = [&](auto relu_tag) {
-    constexpr bool RELU = decltype(relu_tag)::value;
+    {
 #pragma unroll 1
     for (int c = 0; c < NC; ++c) {
       f32x16 ah[TT];
@@ -964,8 +965,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       }
       ws.advance();
     }
-    };
-    if (p.act == 1) ffn(std::true_type{}); else ffn(std::false_type{});
+    }
     if (selfl) ws.advance();   // the unused segment behind a fused block in the packed buffer
   }
 
@@ -1049,7 +1049,12 @@ template <typename T, int D, int DH>
 int launch_block(int mode, int tt, int win, const BlockParams& p, dim3 grid, hipStream_t stream);
 
 #define LONGER_LAUNCH(T, D, DH, TTV, MODEV, WV) \
-  hipLaunchKernelGGL((block_kernel<T, D, DH, TTV, MODEV, WV>), grid, dim3(kThreads), 0, stream, p)
+  do {                                                                                                \
+    if (p.act == 1 && MODEV != MODE_KVPROJ)                                                           \
+      hipLaunchKernelGGL((block_kernel<T, D, DH, TTV, MODEV, WV, MODEV != MODE_KVPROJ>), grid, dim3(kThreads), 0, stream, p); \
+    else                                                                                              \
+      hipLaunchKernelGGL((block_kernel<T, D, DH, TTV, MODEV, WV, false>), grid, dim3(kThreads), 0, stream, p); \
+  } while (0)
 
 #define LONGER_INSTANTIATE(T, D, DH)                                                                  \
   template <>                                                                                         \
