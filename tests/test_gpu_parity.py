@@ -441,6 +441,38 @@ def test_bf16_large_ffn_preactivations(scale):
     _serving(case, TOL["bf16"], logits_by_terms=True)
 
 
+def test_forward_from_inputs_with_learnable_queries_and_wide_query_set():
+    """Raw inputs + learnable query tokens + 150 query slots (one launch pair per layer instead of the
+    one-workgroup stack): the combinations share one forward implementation and must compose."""
+    import paper_2505_04421_amd as lg
+    cfg = synth.CONFIGS["C2"].replace(B=3, L=300, k_recent=150, q_learnable=True, n_self=2, ragged=True,
+                                      len_lo=0, len_hi=300, index=34, gmask="causal")
+    d_e = 32
+    case = synth.make_input_case(cfg, d_e)
+    case["lens"][:] = [300, 0, 77]
+    g = np.random.default_rng(17)
+    for u, n in enumerate(case["lens"]):
+        case["E"][u, :n] = synth.round_bf16(g.standard_normal((n, d_e)).astype(np.float32))
+        case["tdiff"][u, :n] = synth.round_bf16(g.standard_normal((n, cfg.d - d_e)).astype(np.float32))
+    G = synth.round_bf16(g.standard_normal((cfg.B, cfg.m, cfg.d)).astype(np.float32))
+    w = synth._map_tree(synth.draw_weights(cfg), synth.round_bf16)
+    model = lg.DeviceModel(cfg, w)
+    mlp = {k: model.upload(v) for k, v in case["mlp"].items()}
+    iw = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
+    lens = torch.from_numpy(case["lens"].astype(np.int32)).to(model.device)
+    ws = model.workspace(cfg.B, cfg.L)
+    Y = model.empty(cfg.B, cfg.n, cfg.d)
+    logits = model.empty(cfg.B, dtype=torch.float32)
+    _say("raw inputs + learnable queries + 150 slots")
+    lg.longer_forward_from_inputs(model.ccfg, model.weights, iw, model.upload(case["E"]), model.upload(case["tdiff"]), d_e,
+                                  model.upload(G), lens, cfg.B, cfg.L, Y, logits, ws)
+    torch.cuda.synchronize()
+    H_ref = orc.input_generation(cfg, case["mlp"], case["E"], case["tdiff"], case["lens"])
+    Y_ref, lg_ref = orc.forward(cfg, w, H_ref, G, case["lens"])
+    _check("Y", Y.float().cpu().numpy().astype(np.float64), Y_ref, TOL["bf16"])
+    _check_logits_by_terms("logits", logits.cpu().numpy().astype(np.float64), lg_ref, Y_ref[:, :cfg.m], w["head_w"], TOL["bf16"])
+
+
 def _random_config(seed):
     """A random small configuration over everything the library accepts (widths, head widths, group
     sizes, global-set sizes, query counts and sampling, layer counts, merge modes, activations, masks)."""
