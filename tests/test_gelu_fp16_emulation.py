@@ -1,7 +1,7 @@
 """The bf16-mode GELU of the HIP path (a clamped odd polynomial evaluated in packed fp16 on x / 4),
-emulated step by step with numpy's float16 and compared with the erf form.  Checks the error
-figures the design notes quote and that the kernel's fp16 coefficients are the fp32 polynomial's,
-rescaled.  No GPU needed."""
+emulated step by step with numpy's float16 and compared with the erf form.  Checks its error
+(max abs below 8e-3, N(0,1)-weighted rms below 1.2e-3, exact saturation far outside the fitted
+interval) and that the kernel's fp16 coefficients are the fp32 polynomial's, rescaled.  No GPU needed."""
 import os
 import re
 
