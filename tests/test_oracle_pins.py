@@ -715,3 +715,74 @@ def test_cases_are_seeded_and_shaped():
     assert c4["lens"].min() >= 100 and c4["lens"].max() <= 5000
     assert np.isnan(c4["H"][0, c4["lens"][0]:]).all() and not np.isnan(c4["H"][0, :c4["lens"][0]]).any()
     assert np.array_equal(synth.round_bf16(c4["G"]), c4["G"])
+
+
+# --------------------------------------------------------------------------- invariants over random small configurations
+def _random_tiny(seed):
+    rng = np.random.default_rng(9000 + seed)
+    K = int(rng.choice([1, 2, 4]))
+    merge = "concat" if (K > 1 and rng.random() < 0.4) else "mean"
+    d_raw = int(rng.choice([4, 8]))
+    d = d_raw * K if merge == "concat" else d_raw
+    heads = int(rng.choice([1, 2]))
+    k = int(rng.integers(1, 7))
+    learn = bool(rng.random() < 0.3)
+    ku = 0 if learn else int(rng.integers(0, k + 1))
+    return synth.tiny_config(B=3, L=int(rng.integers(K, 9 * K)), d=d, heads=heads, inner_heads=int(rng.choice([1, 2])),
+                             m=int(rng.integers(1, 4)), K=K, k_recent=k, k_uniform=ku, q_learnable=learn, merge=merge,
+                             n_self=int(rng.integers(0, 3)), inner_layers=int(rng.integers(1, 3)),
+                             gmask=str(rng.choice(["full", "causal"])), act=str(rng.choice(["gelu_erf", "relu"])),
+                             ffn_mult=int(rng.choice([1, 4])), index=200 + seed)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_invariants_hold_for_random_small_configurations(seed):
+    """What must hold whatever the configuration (merge mode, query strategy, masks, layer counts):
+    users are independent, padded storage is never read, a token cannot see its future, and the
+    two-stage serving path equals the full pass."""
+    cfg = _random_tiny(seed)
+    rng = _rng(300 + seed)
+    w = synth.draw_weights(cfg, rng)
+    H = rng.standard_normal((cfg.B, cfg.L, cfg.d_in))
+    G = rng.standard_normal((cfg.B, cfg.m, cfg.d))
+    lens = rng.integers(0, cfg.L + 1, size=cfg.B)
+    lens[0] = cfg.L
+    Y, lg = orc.forward(cfg, w, H, G, lens)
+    assert np.isfinite(Y).all() and np.isfinite(lg).all()
+    # users are independent: any user alone gives the same rows
+    for u in range(cfg.B):
+        Yu, lu = orc.forward(cfg.replace(B=1), w, H[u:u + 1], G[u:u + 1], lens[u:u + 1])
+        np.testing.assert_allclose(Yu[0], Y[u], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(lu[0], lg[u], rtol=1e-12, atol=1e-13)
+    # padded storage is never read, and a longer padded length changes nothing
+    Hn = H.copy()
+    for u in range(cfg.B):
+        Hn[u, lens[u]:] = np.nan
+    Yn, _ = orc.forward(cfg, w, Hn, G, lens)
+    assert np.array_equal(Yn, Y)
+    Hp = np.concatenate([H, rng.standard_normal((cfg.B, 2 * cfg.K, cfg.d_in))], axis=1)
+    for u in range(cfg.B):
+        Hp[u, lens[u]:] = 0.0
+    Yp, lp = orc.forward(cfg.replace(L=cfg.L + 2 * cfg.K), w, Hp, G, lens)
+    np.testing.assert_allclose(Yp, Y, rtol=1e-12, atol=1e-13)
+    # sequence-side rows never depend on the global tokens (what makes the KV cache valid)
+    Y2, _ = orc.forward(cfg, w, H, G + 1.0, lens)
+    assert np.array_equal(Y2[:, cfg.m:], Y[:, cfg.m:])
+    # serving: cached scoring equals the full pass, candidate by candidate
+    Gc = rng.standard_normal((cfg.B, 2, cfg.m, cfg.d))
+    cache = orc.kv_cache_build(cfg, w, H, lens)
+    Yg, lgs = orc.score_candidates(cfg, w, cache, Gc)
+    for c in range(2):
+        Yc, lc = orc.forward(cfg, w, H, Gc[:, c], lens)
+        np.testing.assert_allclose(Yg[:, c], Yc[:, :cfg.m], rtol=1e-11, atol=1e-12)
+        np.testing.assert_allclose(lgs[:, c], lc, rtol=1e-11, atol=1e-12)
+    # causality of sampled sequence queries: changing the user's newest raw token leaves every slot that
+    # holds an older merged token unchanged (learnable slots see everything and are exempt)
+    if not cfg.q_learnable and lens[0] > cfg.K:
+        H3 = H.copy(); H3[0, lens[0] - 1] += 1.0
+        Y3, _ = orc.forward(cfg, w, H3, G, lens)
+        Tu = orc.merged_len(lens[0], cfg.K)
+        for i in range(cfg.k_recent):
+            t = orc.slot_index(i, cfg.k_recent, Tu, cfg.k_uniform)
+            if 0 <= t < Tu - 1:
+                assert np.array_equal(Y3[0, cfg.m + i], Y[0, cfg.m + i])
