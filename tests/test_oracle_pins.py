@@ -137,6 +137,27 @@ def test_inner_transformer_equals_torch_layer_per_group():
     np.testing.assert_allclose(M, x.numpy().reshape(cfg.B, cfg.T, cfg.K, cfg.d).mean(2), rtol=1e-10, atol=1e-11)
 
 
+def test_inner_transformer_on_a_ragged_last_group_equals_torch_on_its_valid_tokens():
+    """A group cut short by the user's length: its valid tokens attend to each other only, as if the
+    group had that many tokens (torch's layer on the valid tokens alone); the rest of the group is zero
+    and takes no part in the mean."""
+    cfg = synth.tiny_config(B=2, L=12, d=8, K=4, inner_layers=2, inner_heads=2)
+    blocks = [_blk(23, cfg.d), _blk(24, cfg.d)]
+    H = _rng(10).standard_normal((cfg.B, cfg.L, cfg.d))
+    lens = np.array([10, 5])                       # last groups hold 2 and 1 valid tokens
+    Z = orc.inner_transformer(cfg, blocks, H, lens)
+    M = orc.token_merge(cfg, blocks, H, lens)
+    for u, (t, n) in enumerate([(2, 2), (1, 1)]):
+        x = torch.from_numpy(H[u, t * cfg.K:t * cfg.K + n][None])
+        with torch.no_grad():
+            for b in blocks:
+                x = _torch_layer(b, cfg.d, cfg.inner_heads)(x)
+        np.testing.assert_allclose(Z[u, t, :n], x[0].numpy(), rtol=1e-10, atol=1e-11)
+        assert (Z[u, t, n:] == 0).all() and (Z[u, t + 1:] == 0).all()
+        np.testing.assert_allclose(M[u, t], x[0].numpy().mean(0), rtol=1e-10, atol=1e-11)
+        assert (M[u, t + 1:] == 0).all()
+
+
 def test_layernorm_and_gelu_equal_torch():
     x = _rng(2).standard_normal((5, 12)) * 3
     g, b = _rng(3).standard_normal(12), _rng(4).standard_normal(12)
