@@ -25,7 +25,6 @@
 // Every mode runs the same register-resident chain (see device.h); they differ in where
 // rows come from, which attention sources exist and what is written.
 #pragma once
-#include <type_traits>
 #include "device.h"
 
 namespace longer {
