@@ -205,6 +205,12 @@ int longer_forward_from_inputs(const longer_config* cfg, const longer_weights* w
                                int B, int L, void* Y_out, float* logits_out,
                                void* ws, size_t ws_bytes, void* stream);
 
+/* longer_kv_cache_build on the raw inputs, in the same way (serving stage 1 of Section 3.6.3 with
+ * the input generation of Section 3.5.1 inside its token-merge kernel). */
+int longer_kv_cache_build_from_inputs(const longer_config* cfg, const longer_weights* w, const longer_input_weights* iw,
+                                      const void* E, const void* tdiff, int d_e, const int32_t* lens, int U, int L,
+                                      void* cache, void* ws, size_t ws_bytes, void* stream);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* longer_last_error(void);
 

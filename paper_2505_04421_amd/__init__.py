@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     LongerError, DeviceModel, load_library, library_path, make_config, exported_symbols,
     longer_workspace_bytes, longer_kv_cache_bytes, longer_inner_transformer, longer_token_merge,
     longer_hybrid_cross_attn, longer_self_attn_layer, longer_forward, longer_kv_cache_build,
-    longer_score_candidates, longer_input_generation, longer_forward_from_inputs, CInputWeights, longer_probe_mfma_layout, longer_last_error,
+    longer_score_candidates, longer_input_generation, longer_forward_from_inputs, longer_kv_cache_build_from_inputs, CInputWeights, longer_probe_mfma_layout, longer_last_error,
     longer_stage_timing, longer_stage_timing_read, STAGES,
 )

@@ -13,7 +13,7 @@ BLOCK_FIELDS = ("ln1_g", "ln1_b", "wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo"
 ENTRY_POINTS = ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_inner_transformer",
                 "longer_token_merge", "longer_hybrid_cross_attn", "longer_self_attn_layer",
                 "longer_forward", "longer_kv_cache_build", "longer_score_candidates", "longer_input_generation",
-                "longer_forward_from_inputs",
+                "longer_forward_from_inputs", "longer_kv_cache_build_from_inputs",
                 "longer_last_error", "longer_probe_mfma_layout", "longer_stage_timing",
                 "longer_stage_timing_read")
 
@@ -74,6 +74,8 @@ def load_library() -> ctypes.CDLL:
     lib.longer_input_generation.argtypes = [cfgp, ctypes.POINTER(CInputWeights), vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
     lib.longer_forward_from_inputs.argtypes = [cfgp, wp, ctypes.POINTER(CInputWeights), vp, vp, i32, vp, vp, i32, i32,
                                                vp, vp, vp, sz, vp]
+    lib.longer_kv_cache_build_from_inputs.argtypes = [cfgp, wp, ctypes.POINTER(CInputWeights), vp, vp, i32, vp, i32, i32,
+                                                      vp, vp, sz, vp]
     lib.longer_last_error.restype = ctypes.c_char_p
     lib.longer_probe_mfma_layout.argtypes = [vp, vp]
     lib.longer_stage_timing.argtypes = [i32]
@@ -259,6 +261,14 @@ def longer_forward_from_inputs(ccfg, weights, iweights, E, tdiff, d_e, G, lens, 
                                                      _ptr(E), _ptr(tdiff), d_e, _ptr(G), _ptr(lens), B, L, _ptr(Y_out),
                                                      _ptr(logits_out), _ptr(ws), ws.numel(), _stream(stream)),
            "longer_forward_from_inputs")
+
+
+def longer_kv_cache_build_from_inputs(ccfg, weights, iweights, E, tdiff, d_e, lens, U, L, cache, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_kv_cache_build_from_inputs(ctypes.byref(ccfg), ctypes.byref(weights), ctypes.byref(iweights),
+                                                            _ptr(E), _ptr(tdiff), d_e, _ptr(lens), U, L, _ptr(cache),
+                                                            _ptr(ws), ws.numel(), _stream(stream)),
+           "longer_kv_cache_build_from_inputs")
 
 
 def longer_probe_mfma_layout(out, stream=None):

@@ -754,15 +754,19 @@ int longer_forward_from_inputs(const longer_config* cfg, const longer_weights* w
   return forward_impl(cfg, w, nullptr, &in, G, lens, B, L, Y_out, logits_out, ws, ws_bytes, stream);
 }
 
-int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, const void* H, const int32_t* lens,
-                          int U, int L, void* cache, void* ws, size_t ws_bytes, void* stream) {
-  g_err[0] = 0;
+// longer_kv_cache_build, on H or (in != NULL) on the raw inputs of the input-generation stage
+static int cache_build_impl(const longer_config* cfg, const longer_weights* w, const void* H, const MergeInput* in,
+                            const int32_t* lens, int U, int L, void* cache, void* ws, size_t ws_bytes, void* stream) {
   Shape s;
   int rc = check_cfg(cfg, &s, true, true);
   if (rc) return rc;
   if ((rc = check_weights(cfg, w))) return rc;
-  if (!H || !cache) return fail(LONGER_ERR_ARG, "NULL argument");
+  if ((!H && !in) || !cache) return fail(LONGER_ERR_ARG, "NULL argument");
   if ((rc = check_aligned({H}))) return rc;
+  if (in) {
+    if (cfg->merge != LONGER_MERGE_MEAN) return fail(LONGER_ERR_ARG, "input generation produces tokens of width d: merge must be LONGER_MERGE_MEAN");
+    if ((rc = check_input(cfg, in->w, in->E, in->tdiff, in->d_e))) return rc;
+  }
   if (((uintptr_t)cache & 255) != 0) return fail(LONGER_ERR_ARG, "cache must be 256-byte aligned");
   const Layout l = make_layout(cfg, s, U, L);
   if ((rc = check_common(ws, ws_bytes, l.total, U, L))) return rc;
@@ -774,18 +778,24 @@ int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, con
   PackBatch pk_batch(cfg, s, st);
   const Shape si = inner_view(cfg, s);
   const bool concat = cfg->merge == LONGER_MERGE_CONCAT;
+  // the merge kernel's stream: (the input MLP,) then the InnerTrans blocks, back to back
+  char* pk_inner0 = pk;
+  if (in) {
+    if ((rc = pk_batch.add_mlp(in->w->w1, in->w->b1, in->w->w2, in->w->b2, pk))) return rc;
+    pk_inner0 = pk + (size_t)mlp_segs(s.FF) * s.seg;
+  }
   {
     // InnerTrans blocks of another width than the main stack's are packed by a launch of their own
     PackBatch pk_inner(cfg, si, st);
     PackBatch& pb = concat ? pk_inner : pk_batch;
-    if ((rc = pb.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk, (size_t)fused_segs(si.D, si.FF) * si.seg))) return rc;
+    if ((rc = pb.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk_inner0, (size_t)fused_segs(si.D, si.FF) * si.seg))) return rc;
     if ((rc = pk_inner.flush())) return rc;
   }
-  char* pk_cross = pk + (size_t)cfg->inner_layers * s.pb;
+  char* pk_cross = pk + (size_t)(cfg->inner_layers + 1) * s.pb;
   if ((rc = pk_batch.add(w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb))) return rc;
   if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, LAYOUT_SPLIT, pk_cross + s.pb, s.pb))) return rc;
   if ((rc = pk_batch.flush())) return rc;
-  if ((rc = run_merge(cfg, si, pk, H, lens, U, L, concat ? nullptr : w8 + l.M, 1, concat ? w8 + l.M : nullptr, 1, st))) return rc;
+  if ((rc = run_merge(cfg, si, pk, H, lens, U, L, concat ? nullptr : w8 + l.M, 1, concat ? w8 + l.M : nullptr, 1, st, in))) return rc;
 
   const int T = cdiv(L, cfg->K);
   char* c8 = (char*)cache;
@@ -817,6 +827,22 @@ int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, con
     if ((rc = run_layer(cfg, s, pk_cross + (size_t)(i + 1) * s.pb, lens, U, L, si, i + 1 < cfg->n_self, st))) return rc;
   }
   return 0;
+}
+
+int longer_kv_cache_build(const longer_config* cfg, const longer_weights* w, const void* H, const int32_t* lens,
+                          int U, int L, void* cache, void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  if (!H) return fail(LONGER_ERR_ARG, "NULL argument");
+  return cache_build_impl(cfg, w, H, nullptr, lens, U, L, cache, ws, ws_bytes, stream);
+}
+
+int longer_kv_cache_build_from_inputs(const longer_config* cfg, const longer_weights* w, const longer_input_weights* iw,
+                                      const void* E, const void* tdiff, int d_e, const int32_t* lens, int U, int L,
+                                      void* cache, void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  if (!iw) return fail(LONGER_ERR_ARG, "NULL argument");
+  const MergeInput in{iw, E, tdiff, d_e};
+  return cache_build_impl(cfg, w, nullptr, &in, lens, U, L, cache, ws, ws_bytes, stream);
 }
 
 int longer_score_candidates(const longer_config* cfg, const longer_weights* w, const void* cache, const int32_t* lens,

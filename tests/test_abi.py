@@ -119,6 +119,9 @@ def test_input_generation_rejects_bad_widths():
     assert rc == -1 and "d_e" in lg.longer_last_error()
     rc = lib.longer_forward_from_inputs(ctypes.byref(cfg), ctypes.byref(wt), None, fake, fake, 96, *args)
     assert rc == -1 and "NULL" in lg.longer_last_error()
+    rc = lib.longer_kv_cache_build_from_inputs(ctypes.byref(cfg), ctypes.byref(wt), ctypes.byref(w), fake, fake, 48, None, 4, 64,
+                                               fake, ctypes.c_void_p(4096), 1 << 40, None)
+    assert rc == -1 and "d_e" in lg.longer_last_error()
     cc = lg.make_config(synth.CONFIGS["P1"])
     rc = lib.longer_forward_from_inputs(ctypes.byref(cc), ctypes.byref(wt), ctypes.byref(w), fake, fake, 96, *args)
     assert rc == -1 and "LONGER_MERGE_MEAN" in lg.longer_last_error()

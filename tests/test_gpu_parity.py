@@ -473,6 +473,47 @@ def test_forward_from_inputs_with_learnable_queries_and_wide_query_set():
     _check_logits_by_terms("logits", logits.cpu().numpy().astype(np.float64), lg_ref, Y_ref[:, :cfg.m], w["head_w"], TOL["bf16"])
 
 
+@pytest.mark.parametrize("base,d_e,U,L", [("C1", 32, 3, 75), ("C3", 96, 4, 333)])
+def test_serving_from_inputs(base, d_e, U, L):
+    """Cache build on the raw inputs (input generation inside its merge kernel), then candidate scoring:
+    against the oracle's input_generation -> kv_cache_build -> score_candidates, ragged users incl. an
+    empty one, NaN padding."""
+    import paper_2505_04421_amd as lg
+    cfg = synth.CONFIGS[base].replace(B=U, L=L, C=7, n_self=2, ragged=True, len_lo=0, len_hi=L, index=35)
+    if base == "C1":
+        cfg = cfg.replace(d=64, heads=4, inner_heads=4)
+    case = synth.make_input_case(cfg, d_e)
+    case["lens"][0] = L
+    case["lens"][1] = 0
+    rnd = synth.round_bf16 if cfg.dtype == "bf16" else (lambda a: a)
+    g = np.random.default_rng(18)
+    case["E"][0] = rnd(g.standard_normal(case["E"][0].shape).astype(np.float32))
+    case["tdiff"][0] = rnd(g.standard_normal(case["tdiff"][0].shape).astype(np.float32))
+    Gc = rnd(g.standard_normal((U, cfg.C, cfg.m, cfg.d)).astype(np.float32))
+    w = synth.draw_weights(cfg)
+    if cfg.dtype == "bf16":
+        w = synth._map_tree(w, synth.round_bf16)
+    tol = TOL[cfg.dtype]
+    model = lg.DeviceModel(cfg, w)
+    mlp = {k: model.upload(v) for k, v in case["mlp"].items()}
+    iw = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
+    lens = torch.from_numpy(case["lens"].astype(np.int32)).to(model.device)
+    ws = model.workspace(U, L, cfg.C)
+    cache = model.kv_cache(U, L)
+    Yg = model.empty(U, cfg.C, cfg.m, cfg.d)
+    logits = model.empty(U, cfg.C, dtype=torch.float32)
+    _say("serving from raw inputs %s d=%d = %d + %d" % (cfg.dtype, cfg.d, d_e, cfg.d - d_e))
+    lg.longer_kv_cache_build_from_inputs(model.ccfg, model.weights, iw, model.upload(case["E"]), model.upload(case["tdiff"]),
+                                         d_e, lens, U, L, cache, ws)
+    lg.longer_score_candidates(model.ccfg, model.weights, cache, lens, U, L, model.upload(Gc), cfg.C, Yg, logits, ws)
+    torch.cuda.synchronize()
+    H_ref = orc.input_generation(cfg, case["mlp"], case["E"], case["tdiff"], case["lens"])
+    ref_cache = orc.kv_cache_build(cfg, w, H_ref, case["lens"])
+    Yg_ref, lg_ref = orc.score_candidates(cfg, w, ref_cache, Gc)
+    _check("Yg", Yg.float().cpu().numpy().astype(np.float64).reshape(U * cfg.C, -1), Yg_ref.reshape(U * cfg.C, -1), tol)
+    _check_logits_by_terms("logits", logits.cpu().numpy().astype(np.float64), lg_ref, Yg_ref, w["head_w"], tol)
+
+
 def _random_config(seed):
     """A random small configuration over everything the library accepts (widths, head widths, group
     sizes, global-set sizes, query counts and sampling, layer counts, merge modes, activations, masks)."""
