@@ -118,12 +118,15 @@ typedef struct {
   const longer_block* self;    /* host array [n_self]        */
   const void* head_w;          /* device [m*d], may be NULL when no logits are asked for */
   const void* head_b;          /* device [1]  */
+  const void* packed;          /* NULL: every call re-packs the parameters it streams into its workspace (one
+                                  small launch); else a DEVICE buffer that longer_pack_weights filled for the
+                                  same config: the calls stream from it, launch no packing and read none of the
+                                  other members */
 } longer_weights;
 
-/* Scratch needed by any forward-path entry point for a batch of B users of padded raw
- * length L, and by the serving entry points for U = B users with C candidates each
- * (pass C = 0 when not scoring). */
-size_t longer_workspace_bytes(const longer_config* cfg, int B, int L, int C);
+/* Scratch needed by any entry point for a batch of B users (serving: U = B users, any
+ * number of candidates) of padded raw length L. */
+size_t longer_workspace_bytes(const longer_config* cfg, int B, int L);
 
 /* Size of the opaque per-batch KV cache written by longer_kv_cache_build. */
 size_t longer_kv_cache_bytes(const longer_config* cfg, int U, int L);
@@ -211,18 +214,36 @@ int longer_kv_cache_build_from_inputs(const longer_config* cfg, const longer_wei
                                       const void* E, const void* tdiff, int d_e, const int32_t* lens, int U, int L,
                                       void* cache, void* ws, size_t ws_bytes, void* stream);
 
+/* Packing once.  The kernels stream every block's parameters as matrix-core operand fragments in the
+ * order they consume them (with the value bias folded into the output bias; in bf16 mode W1 and
+ * b1 scaled by 1/4 and W2 by 4 in fp16).  By default each call derives that form from the raw
+ * weights again, one launch of about 10 microseconds.  longer_pack_weights writes it once, for
+ * every entry point that takes a longer_weights (forward, cache build, scoring; `iw` non-NULL adds
+ * the input-generation MLP for the *_from_inputs calls, head_w / head_b non-NULL add the head),
+ * into caller-owned device memory of longer_packed_weights_bytes(cfg) bytes, 256-byte aligned; a
+ * longer_weights whose `packed` member points there then skips the packing launch.  The buffer
+ * depends on the config (not on B, L or C) and must be re-packed when a weight changes.  The
+ * library cannot check that a buffer it is handed was packed for the same config, with the head
+ * or the input MLP a call needs: that is the caller's contract.  (An optimisation of the call
+ * sequence, not an operation of the paper.) */
+size_t longer_packed_weights_bytes(const longer_config* cfg);
+int longer_pack_weights(const longer_config* cfg, const longer_weights* w, const longer_input_weights* iw,
+                        void* packed_out, size_t bytes, void* stream);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* longer_last_error(void);
 
 /* Measurement aid: when enabled, every kernel launch group of the entry points is bracketed
- * by a pair of HIP events recorded on the caller's stream (at most 8192 pairs between two
+ * by a pair of HIP events recorded on the caller's stream (at most 4096 pairs between two
  * reads; later launches go unrecorded).  enable = 0: off; 1: every stage; any other value:
  * bit (s + 1) selects stage s (an event pair costs a few microseconds of launch time, so a
  * caller that wants one kernel's duration inside a timed loop selects that stage alone).  longer_stage_timing_read waits for the recorded
  * events, adds up the elapsed milliseconds and the number of launch groups per stage into
  * HOST arrays of LONGER_NUM_STAGES entries (0 parameter packing, 1 token merge, 2 K/V
- * projection, 3 attention + FFN, 4 candidate scoring) and clears the record.  Not
- * thread-safe; do not enable under graph capture. */
+ * projection, 3 attention + FFN, 4 candidate scoring) and clears the record.  The aid is the one
+ * place where the library creates HIP objects: event pairs, made on first use (hipEventCreate)
+ * and kept in fixed storage until the process ends; with timing off no entry point creates
+ * anything.  Not thread-safe; do not enable under graph capture. */
 #define LONGER_NUM_STAGES 5
 int longer_stage_timing(int enable);
 int longer_stage_timing_read(double* ms_out, int32_t* launches_out);
@@ -232,6 +253,19 @@ int longer_stage_timing_read(double* ms_out, int32_t* launches_out);
  * accumulator register, the (row, column) it holds as row*32+column into out[2][64][16]
  * (int32, device; [0] = bf16 32x32x16, [1] = fp32 32x32x2). */
 int longer_probe_mfma_layout(int32_t* out, void* stream);
+
+/* In-bounds instruction-rate probe (measurement aid): `workgroups` workgroups of 512 threads (two
+ * waves per SIMD) run `iters` iterations; per iteration a wave issues 16 bf16 32x32x16 MFMAs
+ * (16 x 32768 FLOP) and / or 128 fp32 FMAs, arranged by `mode`:
+ *   0 MFMAs in all 8 waves (the rate the matrix pipe sustains: the attainable peak a kernel is
+ *     priced against beside the vendor figure)   1 FMAs in all 8 waves
+ *   2 MFMAs then FMAs in every wave               3 waves 0-3 MFMAs, waves 4-7 FMAs
+ *   4 as 3, idle cycles after each MFMA           5 every MFMA followed by 4 FMAs
+ *   6 every MFMA followed by 8 FMAs               7 MFMAs in waves 0-3 only (one wave per SIMD)
+ *   8 as 0 with the idle cycles of 4              9 as 3 with the MFMA waves at raised priority
+ * The caller times the launch (events on `stream`).  out: device, workgroups * 512 floats
+ * (a sink that keeps the work alive). */
+int longer_probe_rate(int mode, int iters, int workgroups, float* out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -15,7 +15,7 @@ ENTRY_POINTS = ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_inner
                 "longer_forward", "longer_kv_cache_build", "longer_score_candidates", "longer_input_generation",
                 "longer_forward_from_inputs", "longer_kv_cache_build_from_inputs",
                 "longer_last_error", "longer_probe_mfma_layout", "longer_stage_timing",
-                "longer_stage_timing_read")
+                "longer_stage_timing_read", "longer_packed_weights_bytes", "longer_pack_weights", "longer_probe_rate")
 
 
 class LongerError(RuntimeError):
@@ -37,7 +37,8 @@ class CBlock(ctypes.Structure):
 
 class CWeights(ctypes.Structure):
     _fields_ = [("inner", ctypes.POINTER(CBlock)), ("cross", ctypes.POINTER(CBlock)),
-                ("self", ctypes.POINTER(CBlock)), ("head_w", ctypes.c_void_p), ("head_b", ctypes.c_void_p)]
+                ("self", ctypes.POINTER(CBlock)), ("head_w", ctypes.c_void_p), ("head_b", ctypes.c_void_p),
+                ("packed", ctypes.c_void_p)]
 
 
 class CInputWeights(ctypes.Structure):
@@ -61,7 +62,7 @@ def load_library() -> ctypes.CDLL:
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     cfgp, blkp, wp = ctypes.POINTER(CConfig), ctypes.POINTER(CBlock), ctypes.POINTER(CWeights)
     lib.longer_workspace_bytes.restype = sz
-    lib.longer_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
+    lib.longer_workspace_bytes.argtypes = [cfgp, i32, i32]
     lib.longer_kv_cache_bytes.restype = sz
     lib.longer_kv_cache_bytes.argtypes = [cfgp, i32, i32]
     lib.longer_inner_transformer.argtypes = [cfgp, blkp, vp, vp, i32, i32, vp, vp, sz, vp]
@@ -76,12 +77,16 @@ def load_library() -> ctypes.CDLL:
                                                vp, vp, vp, sz, vp]
     lib.longer_kv_cache_build_from_inputs.argtypes = [cfgp, wp, ctypes.POINTER(CInputWeights), vp, vp, i32, vp, i32, i32,
                                                       vp, vp, sz, vp]
+    lib.longer_packed_weights_bytes.restype = sz
+    lib.longer_packed_weights_bytes.argtypes = [cfgp]
+    lib.longer_pack_weights.argtypes = [cfgp, wp, ctypes.POINTER(CInputWeights), vp, sz, vp]
+    lib.longer_probe_rate.argtypes = [i32, i32, i32, vp, vp]
     lib.longer_last_error.restype = ctypes.c_char_p
     lib.longer_probe_mfma_layout.argtypes = [vp, vp]
     lib.longer_stage_timing.argtypes = [i32]
     lib.longer_stage_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     for name in ENTRY_POINTS:
-        if name not in ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_last_error"):
+        if name not in ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_packed_weights_bytes", "longer_last_error"):
             getattr(lib, name).restype = ctypes.c_int
     _LIB = lib
     return lib
@@ -179,11 +184,25 @@ class DeviceModel:
         return torch.empty(*shape, dtype=dtype or self.tdtype, device=self.device)
 
     def workspace(self, B: int, L: int, C: int = 0):
+        """Scratch for a batch of B users of padded length L (C, the candidate count, does not enter)."""
         import torch
-        n = longer_workspace_bytes(self.ccfg, B, L, C)
+        n = longer_workspace_bytes(self.ccfg, B, L)
         if n == 0:
             raise LongerError("workspace size query failed: " + longer_last_error())
         return torch.empty(n, dtype=torch.uint8, device=self.device)
+
+    def pack(self, iweights=None):
+        """Pack the parameters once (longer_pack_weights) and return a CWeights that streams from the
+        packed buffer; the model keeps the buffer alive."""
+        import torch
+        n = longer_packed_weights_bytes(self.ccfg)
+        if n == 0:
+            raise LongerError("packed size query failed: " + longer_last_error())
+        buf = torch.empty(n, dtype=torch.uint8, device=self.device)
+        longer_pack_weights(self.ccfg, self.weights, iweights, buf)
+        self._keep.append(buf)
+        return CWeights(inner=self.inner, cross=self.cross, self=self.self_, head_w=self.weights.head_w,
+                        head_b=self.weights.head_b, packed=buf.data_ptr())
 
     def kv_cache(self, U: int, L: int):
         import torch
@@ -194,8 +213,26 @@ class DeviceModel:
 
 
 # ----------------------------------------------------------------------------- entry points
-def longer_workspace_bytes(ccfg: CConfig, B: int, L: int, C: int = 0) -> int:
-    return int(load_library().longer_workspace_bytes(ctypes.byref(ccfg), B, L, C))
+def longer_workspace_bytes(ccfg: CConfig, B: int, L: int) -> int:
+    return int(load_library().longer_workspace_bytes(ctypes.byref(ccfg), B, L))
+
+
+def longer_packed_weights_bytes(ccfg: CConfig) -> int:
+    return int(load_library().longer_packed_weights_bytes(ctypes.byref(ccfg)))
+
+
+def longer_pack_weights(ccfg, weights, iweights, packed_out, stream=None):
+    _require_gpu()
+    _check(load_library().longer_pack_weights(ctypes.byref(ccfg), ctypes.byref(weights),
+                                              None if iweights is None else ctypes.byref(iweights),
+                                              _ptr(packed_out), packed_out.numel(), _stream(stream)), "longer_pack_weights")
+
+
+def longer_probe_rate(mode, iters, workgroups, out, stream=None):
+    _require_gpu()
+    if out.numel() < workgroups * 512:
+        raise LongerError("longer_probe_rate: out must hold workgroups * 512 floats")
+    _check(load_library().longer_probe_rate(mode, iters, workgroups, _ptr(out), _stream(stream)), "longer_probe_rate")
 
 
 def longer_kv_cache_bytes(ccfg: CConfig, U: int, L: int) -> int:

@@ -507,9 +507,16 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       const int u = tile / p.tiles_per_user, kt = tile - u * p.tiles_per_user;
       const int c = 32 * kt + j;
       inrange[tt] = u < p.B;
-      valid[tt] = inrange[tt] && c < p.rows_per_user;
-      usr[tt] = u; Tu[tt] = kt;              // Tu holds the key tile index here
       const bool first = c < p.m0;
+      // a row takes part only if its token exists: a merged token below T_u (cross layer), a valid
+      // query slot (self layers).  Rows of other tokens are never read (they may hold anything) and
+      // are projected from zeros; every query hides their keys.
+      int len = 0;
+      if (inrange[tt]) { len = p.lens ? p.lens[u] : p.L; len = min(max(len, 0), p.L); }
+      const int tu = (len + p.K - 1) / p.K, i = c - p.m0;
+      const bool exists = first || (p.key_self ? i >= first_slot(p.k, tu, p.q_learn) : i < tu);
+      valid[tt] = inrange[tt] && c < p.rows_per_user && exists;
+      usr[tt] = u; Tu[tt] = kt;              // Tu holds the key tile index here
       const void* sp = first ? p.src0.p : p.src1.p;
       const int sf = first ? p.src0.f32 : p.src1.f32;
       const long long su = first ? p.src0.ustride : p.src1.ustride;

@@ -161,11 +161,14 @@ enum Mode { MODE_MERGE = 0, MODE_KVPROJ = 1, MODE_ATTN = 2, MODE_SCORE = 3, MODE
 // 16 bytes per lane from global memory straight into LDS (no VGPR round trip):
 // lane i of the wave writes LDS bytes [lds_wave_base + 16 i, +16).  lds_wave_base must be
 // wave-uniform.  Completion is tracked by the wave's vector-memory counter.
+// The LDS base travels in M0, which the statement overwrites: it is declared clobbered so that
+// the compiler never keeps a value of its own there across a load (it uses M0 for indirect
+// register indexing and LDS-direct operations).
 __device__ __forceinline__ void gload_lds16(const void* g, unsigned lds_wave_base) {
   asm volatile("s_mov_b32 m0, %1\n\t"
                "s_nop 0\n\t"
                "global_load_lds_dwordx4 %0, off\n\t"
-               :: "v"(g), "s"(lds_wave_base) : "memory");
+               :: "v"(g), "s"(lds_wave_base) : "memory", "m0");
 }
 // The same with the global address given as a wave-uniform base (scalar registers) plus a 32-bit
 // per-lane byte offset, so that advancing the base costs scalar instructions only.
@@ -173,7 +176,7 @@ __device__ __forceinline__ void gload_lds16(const void* g_uniform, unsigned lane
   asm volatile("s_mov_b32 m0, %2\n\t"
                "s_nop 0\n\t"
                "global_load_lds_dwordx4 %0, %1\n\t"
-               :: "v"(lane_off), "s"(g_uniform), "s"(lds_wave_base) : "memory");
+               :: "v"(lane_off), "s"(g_uniform), "s"(lds_wave_base) : "memory", "m0");
 }
 
 // wait until at most N vector-memory operations of this wave are outstanding
@@ -189,6 +192,20 @@ __device__ __forceinline__ void wait_vmcnt() {
 // panel buffers, NB-1 panels ahead of the consumer, so that L2/HBM latency is covered by
 // the MFMA work of several panels; one barrier per panel.  The stream's length is rounded
 // up to whole panels: the packed buffer must hold PSEG-1 readable segments past its end.
+//
+// Ordering invariant behind the hand-counted waits.  The stream's loads are inline assembly, so
+// the compiler's own wait-count bookkeeping does not see them; this struct counts them itself.
+// Vector-memory LOADS of a wave return in issue order, and the counter a wait tests (vmcnt) counts
+// the wave's outstanding loads, the compiler's ordinary global loads included.  "At most N
+// outstanding" therefore proves that everything issued before the last N loads has landed.  An
+// ordinary load that the compiler issues between two panels only makes the count larger than the
+// stream assumes, so a wait for N can only wait longer than needed, never too little; and the
+// compiler's own waits for its loads (which it believes are the only ones) are waits for a count
+// that the stream's younger loads can only push up, so they too err on the strict side.  What
+// breaks the argument is a global STORE inside the loop: stores also count in vmcnt on this
+// target but may retire out of order with respect to loads.  A mode that stores inside its loop
+// (the K/V projection) sets DRAIN and always waits for zero.  Every other mode stores only after
+// its last advance() and a wait for zero.
 template <int SEGV, int PSEG, int NB, bool DRAIN>
 struct WStream {
   static constexpr int PANV = SEGV * PSEG;              // 16-byte vectors per panel

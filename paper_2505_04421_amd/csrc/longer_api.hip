@@ -55,10 +55,11 @@ static int fail(int code, const char* fmt, ...) {
 enum Stage { ST_PACK = 0, ST_MERGE = 1, ST_KVPROJ = 2, ST_ATTN = 3, ST_SCORE = 4 };
 static_assert(LONGER_NUM_STAGES == 5, "stage table");
 struct StageTimer {
-  static constexpr int kMaxPairs = 8192;
+  static constexpr int kMaxPairs = 4096;
   unsigned mask = 0;             // bit s: stage s is timed
   int n = 0;
-  hipEvent_t* ev = nullptr;      // 2 * kMaxPairs events, created on first enable
+  int created = 0;               // events that exist (made pair by pair on first use, never destroyed)
+  hipEvent_t ev[2 * kMaxPairs];  // fixed storage: the aid allocates no host memory either
   unsigned char stage[kMaxPairs];
 };
 static StageTimer g_timer;
@@ -67,6 +68,11 @@ struct StageScope {
   hipStream_t st; int idx;
   StageScope(int stage, hipStream_t s) : st(s), idx(-1) {
     if ((g_timer.mask >> stage & 1u) && g_timer.n < StageTimer::kMaxPairs) {
+      if (2 * g_timer.n + 2 > g_timer.created) {
+        if (hipEventCreate(&g_timer.ev[g_timer.created]) != hipSuccess) return;
+        if (hipEventCreate(&g_timer.ev[g_timer.created + 1]) != hipSuccess) { (void)hipEventDestroy(g_timer.ev[g_timer.created]); return; }
+        g_timer.created += 2;
+      }
       idx = g_timer.n++;
       g_timer.stage[idx] = (unsigned char)stage;
       (void)hipEventRecord(g_timer.ev[2 * idx], st);
@@ -319,9 +325,41 @@ static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b)
 // launch are dealt to them round-robin
 constexpr int kXcds = 8;
 
+// Packed parameters of a whole model, in the order the launches stream them.  The layout is a
+// function of the configuration alone, so a buffer written once by longer_pack_weights serves
+// every later call; without one, each entry point packs what it needs into the same places of
+// its workspace.
+//   merge stream   [input MLP][InnerTrans blocks, fused layout, back to back]
+//   reduced stack  [cross block, split layout][self blocks, fused layout]   (one stream: the stack kernel)
+//   per-layer plan [self blocks, split layout]                              (m + k > 128, cache build)
+//   scoring        [cross block, fused][self blocks, fused], back to back
+//   head           fp32 weights and bias
+struct PackedLayout {
+  size_t mlp, inner, cross, self_fused, self_split, score, head, total;
+  size_t inner_stride, score_stride;
+};
+
+static PackedLayout packed_layout(const longer_config* c, const Shape& s) {
+  PackedLayout pl;
+  const Shape si = inner_view(c, s);
+  size_t o = 0;
+  pl.mlp = o; o += (size_t)mlp_segs(s.FF) * s.seg;
+  pl.inner = o; pl.inner_stride = (size_t)fused_segs(si.D, si.FF) * si.seg;
+  o += (size_t)c->inner_layers * pl.inner_stride;
+  o = align256(o + 4 * (s.seg > si.seg ? s.seg : si.seg));   // a stream may read whole panels past its end
+  pl.cross = o; o += s.pb;
+  pl.self_fused = o; o += (size_t)c->n_self * s.pb;
+  pl.self_split = o; o += (size_t)c->n_self * s.pb;
+  pl.score = o; pl.score_stride = (size_t)fused_segs(s.D, s.FF) * s.seg;
+  o += (size_t)(1 + c->n_self) * pl.score_stride + 4 * s.seg;
+  pl.head = align256(o); o = pl.head + align256(((size_t)c->m * s.D + 1) * 4);
+  pl.total = o;
+  return pl;
+}
+
 // workspace layout shared by all entry points
 struct Layout {
-  size_t packed, head, M, kst, vst, xa, xb, total;
+  size_t packed, M, kst, vst, xa, xb, total;
   size_t kv_ustride;
   int ktmax;
 };
@@ -329,10 +367,8 @@ struct Layout {
 static Layout make_layout(const longer_config* c, const Shape& s, int B, int L) {
   Layout l;
   const int T = cdiv(L, c->K);
-  const int nblk = c->inner_layers + 1 + c->n_self + 1;   // + the input MLP in front of the InnerTrans blocks
   size_t o = 0;
-  l.packed = o; o += (size_t)nblk * s.pb + 4 * s.seg;   // a stream may read whole panels past its end
-  l.head = o; o += align256(((size_t)c->m * s.D + 1) * 4);
+  l.packed = o; o += packed_layout(c, s).total;
   l.M = o; o += align256((size_t)B * T * s.D * 4);
   l.ktmax = cdiv((long long)c->m + T, 32) > cdiv(s.n, 32) ? cdiv((long long)c->m + T, 32) : cdiv(s.n, 32);
   l.kv_ustride = (size_t)l.ktmax * s.NT * s.GPT * 1024;
@@ -500,6 +536,7 @@ static int run_layer(const longer_config* c, const Shape& s, const char* packed_
     p.src0 = io.src0; p.src1 = io.src1; p.m0 = io.m0;
     p.rows_per_user = io.key_rows; p.tiles_per_user = cdiv(io.key_rows, 32);
     p.kst = io.kst; p.vst = io.vst; p.kv_ustride = io.kv_ustride; p.kt_per_user = p.tiles_per_user;
+    p.key_self = io.key_self;
     const int grid = cdiv((long long)B * p.tiles_per_user, kWaves);
     StageScope scope(ST_KVPROJ, st);
     if (s.main_fn(MODE_KVPROJ, 1, 16, p, dim3(grid), st)) return fail(LONGER_ERR_HIP, "kv projection launch failed");
@@ -541,6 +578,56 @@ static int run_stack(const longer_config* c, const Shape& s, const char* packed_
   return 0;
 }
 
+
+// ------------------------------------------------------------------------------------
+// Packing a model's parameters: which parts an entry point streams
+enum : unsigned { PK_MERGE = 1, PK_STACK = 2, PK_LAYERS = 4, PK_SCORE = 8, PK_HEAD = 16 };
+
+static bool stack_in_one_launch(const Shape& s) { return s.n <= 32 * kWaves; }   // a user's reduced rows fit one workgroup
+
+static int pack_model(const longer_config* cfg, const Shape& s, const longer_weights* w, const longer_input_weights* iw,
+                      char* base, unsigned what, hipStream_t st) {
+  const PackedLayout pl = packed_layout(cfg, s);
+  const Shape si = inner_view(cfg, s);
+  PackBatch pk_main(cfg, s, st);
+  int rc;
+  if (what & PK_MERGE) {
+    if (!w->inner) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
+    if (iw && (rc = pk_main.add_mlp(iw->w1, iw->b1, iw->w2, iw->b2, base + pl.mlp))) return rc;
+    // InnerTrans blocks of another width than the main stack's are packed by a launch of their own
+    PackBatch pk_inner(cfg, si, st);
+    PackBatch& pb = cfg->merge == LONGER_MERGE_CONCAT ? pk_inner : pk_main;
+    if ((rc = pb.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, base + pl.inner, pl.inner_stride))) return rc;
+    if ((rc = pk_inner.flush())) return rc;
+  }
+  if (what & (PK_STACK | PK_LAYERS | PK_SCORE)) {
+    if (!w->cross || (cfg->n_self > 0 && !w->self)) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
+  }
+  if ((what & (PK_STACK | PK_LAYERS)) && (rc = pk_main.add(w->cross, 1, LAYOUT_SPLIT, base + pl.cross, s.pb))) return rc;
+  if ((what & PK_STACK) && cfg->n_self && (rc = pk_main.add(w->self, cfg->n_self, LAYOUT_FUSED, base + pl.self_fused, s.pb))) return rc;
+  if ((what & PK_LAYERS) && cfg->n_self && (rc = pk_main.add(w->self, cfg->n_self, LAYOUT_SPLIT, base + pl.self_split, s.pb))) return rc;
+  if (what & PK_SCORE) {
+    if ((rc = pk_main.add(w->cross, 1, LAYOUT_FUSED, base + pl.score, pl.score_stride))) return rc;
+    if (cfg->n_self && (rc = pk_main.add(w->self, cfg->n_self, LAYOUT_FUSED, base + pl.score + pl.score_stride, pl.score_stride))) return rc;
+  }
+  if ((what & PK_HEAD) && (rc = pk_main.add_head(w, (float*)(base + pl.head)))) return rc;
+  return pk_main.flush();
+}
+
+// Where a call streams its parameters from: the caller's pre-packed buffer, or the workspace's
+// packed region after packing the parts `what` into it.
+static int packed_source(const longer_config* cfg, const Shape& s, const longer_weights* w, const longer_input_weights* iw,
+                         char* ws_packed, unsigned what, hipStream_t st, char** base) {
+  if (!w) return fail(LONGER_ERR_ARG, "weights struct is NULL");
+  if (w->packed) {
+    if (((uintptr_t)w->packed & 255) != 0) return fail(LONGER_ERR_ARG, "packed weights must be 256-byte aligned");
+    *base = (char*)w->packed;
+    return 0;
+  }
+  *base = ws_packed;
+  return pack_model(cfg, s, w, iw, ws_packed, what, st);
+}
+
 }  // namespace longer
 
 using namespace longer;
@@ -549,10 +636,9 @@ extern "C" {
 
 const char* longer_last_error(void) { return g_err; }
 
-size_t longer_workspace_bytes(const longer_config* cfg, int B, int L, int C) {
+size_t longer_workspace_bytes(const longer_config* cfg, int B, int L) {
   g_err[0] = 0;
   Shape s;
-  (void)C;
   if (check_cfg(cfg, &s, cfg && cfg->inner_layers > 0, true) || B <= 0 || L <= 0) return 0;
   return make_layout(cfg, s, B, L).total;
 }
@@ -562,6 +648,31 @@ size_t longer_kv_cache_bytes(const longer_config* cfg, int U, int L) {
   Shape s;
   if (check_cfg(cfg, &s, false, true) || U <= 0 || L <= 0) return 0;
   return make_cache_layout(cfg, s, U, L).total;
+}
+
+size_t longer_packed_weights_bytes(const longer_config* cfg) {
+  g_err[0] = 0;
+  Shape s;
+  if (check_cfg(cfg, &s, cfg && cfg->inner_layers > 0, true)) return 0;
+  return packed_layout(cfg, s).total;
+}
+
+int longer_pack_weights(const longer_config* cfg, const longer_weights* w, const longer_input_weights* iw,
+                        void* packed_out, size_t bytes, void* stream) {
+  g_err[0] = 0;
+  Shape s;
+  int rc = check_cfg(cfg, &s, cfg && cfg->inner_layers > 0, true);
+  if (rc) return rc;
+  if (!w || !packed_out) return fail(LONGER_ERR_ARG, "NULL argument");
+  if (((uintptr_t)packed_out & 255) != 0) return fail(LONGER_ERR_ARG, "packed_out must be 256-byte aligned");
+  const PackedLayout pl = packed_layout(cfg, s);
+  if (bytes < pl.total) return fail(LONGER_ERR_WS, "packed buffer too small: %zu < %zu bytes", bytes, pl.total);
+  if (iw && (!iw->w1 || !iw->b1 || !iw->w2 || !iw->b2)) return fail(LONGER_ERR_ARG, "input MLP has NULL members");
+  unsigned what = PK_LAYERS | PK_SCORE;
+  if (cfg->inner_layers > 0 && w->inner) what |= PK_MERGE;
+  if (stack_in_one_launch(s)) what |= PK_STACK;
+  if (w->head_w && w->head_b) what |= PK_HEAD;
+  return pack_model(cfg, s, w, iw, (char*)packed_out, what, (hipStream_t)stream);
 }
 
 static int merge_entry(const longer_config* cfg, const longer_block* inner, const void* H, const int32_t* lens,
@@ -668,11 +779,6 @@ int longer_self_attn_layer(const longer_config* cfg, const longer_block* blk, co
   return run_layer(cfg, s, w8 + l.packed, lens, B, L, io, true, st);
 }
 
-static int check_weights(const longer_config* cfg, const longer_weights* w) {
-  if (!w || !w->inner || !w->cross || (cfg->n_self > 0 && !w->self)) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
-  return 0;
-}
-
 // longer_forward, on H or (in != NULL) on the raw inputs of the input-generation stage
 static int forward_impl(const longer_config* cfg, const longer_weights* w, const void* H, const MergeInput* in,
                         const void* G, const int32_t* lens, int B, int L, void* Y_out, float* logits_out,
@@ -680,7 +786,6 @@ static int forward_impl(const longer_config* cfg, const longer_weights* w, const
   Shape s;
   int rc = check_cfg(cfg, &s, true, true);
   if (rc) return rc;
-  if ((rc = check_weights(cfg, w))) return rc;
   if ((!H && !in) || !G || !Y_out) return fail(LONGER_ERR_ARG, "NULL argument");
   if ((rc = check_aligned({H, G, Y_out}))) return rc;
   if (in) {
@@ -692,32 +797,19 @@ static int forward_impl(const longer_config* cfg, const longer_weights* w, const
   if ((rc = check_slots(cfg, B, L))) return rc;
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
-  char* pk = w8 + l.packed;
-  PackBatch pk_batch(cfg, s, st);
   const Shape si = inner_view(cfg, s);
   const bool concat = cfg->merge == LONGER_MERGE_CONCAT;
-  // the merge kernel's stream: (the input MLP,) then the InnerTrans blocks, back to back
-  char* pk_inner0 = pk;
-  if (in) {
-    if ((rc = pk_batch.add_mlp(in->w->w1, in->w->b1, in->w->w2, in->w->b2, pk))) return rc;
-    pk_inner0 = pk + (size_t)mlp_segs(s.FF) * s.seg;
-  }
-  {
-    // InnerTrans blocks of another width than the main stack's are packed by a launch of their own
-    PackBatch pk_inner(cfg, si, st);
-    PackBatch& pb = concat ? pk_inner : pk_batch;
-    if ((rc = pb.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk_inner0, (size_t)fused_segs(si.D, si.FF) * si.seg))) return rc;
-    if ((rc = pk_inner.flush())) return rc;
-  }
-  char* pk_cross = pk + (size_t)(cfg->inner_layers + 1) * s.pb;
-  if ((rc = pk_batch.add(w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb))) return rc;
-  const bool one_launch = s.n <= 32 * kWaves;   // a user's reduced rows fit one workgroup
-  if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, one_launch ? LAYOUT_FUSED : LAYOUT_SPLIT, pk_cross + s.pb, s.pb))) return rc;
-  float* head = (float*)(w8 + l.head);
-  if (logits_out && (rc = pk_batch.add_head(w, head))) return rc;
-  if ((rc = pk_batch.flush())) return rc;
+  const bool one_launch = stack_in_one_launch(s);
+  const PackedLayout pl = packed_layout(cfg, s);
+  char* pk = nullptr;
+  if ((rc = packed_source(cfg, s, w, in ? in->w : nullptr, w8 + l.packed,
+                          PK_MERGE | (one_launch ? PK_STACK : PK_LAYERS) | (logits_out ? PK_HEAD : 0u), st, &pk))) return rc;
+  char* pk_cross = pk + pl.cross;
+  float* head = (float*)(pk + pl.head);
 
-  if ((rc = run_merge(cfg, si, pk, H, lens, B, L, concat ? nullptr : w8 + l.M, 1, concat ? w8 + l.M : nullptr, 1, st, in))) return rc;
+  // the merge kernel's stream: (the input MLP,) then the InnerTrans blocks, back to back
+  if ((rc = run_merge(cfg, si, pk + (in ? pl.mlp : pl.inner), H, lens, B, L, concat ? nullptr : w8 + l.M, 1,
+                      concat ? w8 + l.M : nullptr, 1, st, in))) return rc;
   if (one_launch) {
     AttnIO io = cross_io(cfg, s, l, w8, G, w8 + l.M, 1, B, L, Y_out, 0);
     if (logits_out) { io.logits = logits_out; io.head = head; }
@@ -731,9 +823,9 @@ static int forward_impl(const longer_config* cfg, const longer_weights* w, const
   if ((rc = run_layer(cfg, s, pk_cross, lens, B, L, io, true, st))) return rc;
   for (int i = 0; i < cfg->n_self; ++i) {
     const bool last = i + 1 == cfg->n_self;
-    AttnIO si = self_io(cfg, s, l, w8, xbuf[i & 1], 1, last ? Y_out : xbuf[(i + 1) & 1], last ? 0 : 1);
-    if (last && logits_out) { si.logits = logits_out; si.head = head; }
-    if ((rc = run_layer(cfg, s, pk_cross + (size_t)(i + 1) * s.pb, lens, B, L, si, true, st))) return rc;
+    AttnIO sio = self_io(cfg, s, l, w8, xbuf[i & 1], 1, last ? Y_out : xbuf[(i + 1) & 1], last ? 0 : 1);
+    if (last && logits_out) { sio.logits = logits_out; sio.head = head; }
+    if ((rc = run_layer(cfg, s, pk + pl.self_split + (size_t)i * s.pb, lens, B, L, sio, true, st))) return rc;
   }
   return 0;
 }
@@ -760,7 +852,6 @@ static int cache_build_impl(const longer_config* cfg, const longer_weights* w, c
   Shape s;
   int rc = check_cfg(cfg, &s, true, true);
   if (rc) return rc;
-  if ((rc = check_weights(cfg, w))) return rc;
   if ((!H && !in) || !cache) return fail(LONGER_ERR_ARG, "NULL argument");
   if ((rc = check_aligned({H}))) return rc;
   if (in) {
@@ -774,28 +865,13 @@ static int cache_build_impl(const longer_config* cfg, const longer_weights* w, c
   const CacheLayout cl = make_cache_layout(cfg, s, U, L);
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
-  char* pk = w8 + l.packed;
-  PackBatch pk_batch(cfg, s, st);
   const Shape si = inner_view(cfg, s);
   const bool concat = cfg->merge == LONGER_MERGE_CONCAT;
-  // the merge kernel's stream: (the input MLP,) then the InnerTrans blocks, back to back
-  char* pk_inner0 = pk;
-  if (in) {
-    if ((rc = pk_batch.add_mlp(in->w->w1, in->w->b1, in->w->w2, in->w->b2, pk))) return rc;
-    pk_inner0 = pk + (size_t)mlp_segs(s.FF) * s.seg;
-  }
-  {
-    // InnerTrans blocks of another width than the main stack's are packed by a launch of their own
-    PackBatch pk_inner(cfg, si, st);
-    PackBatch& pb = concat ? pk_inner : pk_batch;
-    if ((rc = pb.add(w->inner, cfg->inner_layers, LAYOUT_FUSED, pk_inner0, (size_t)fused_segs(si.D, si.FF) * si.seg))) return rc;
-    if ((rc = pk_inner.flush())) return rc;
-  }
-  char* pk_cross = pk + (size_t)(cfg->inner_layers + 1) * s.pb;
-  if ((rc = pk_batch.add(w->cross, 1, LAYOUT_SPLIT, pk_cross, s.pb))) return rc;
-  if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, LAYOUT_SPLIT, pk_cross + s.pb, s.pb))) return rc;
-  if ((rc = pk_batch.flush())) return rc;
-  if ((rc = run_merge(cfg, si, pk, H, lens, U, L, concat ? nullptr : w8 + l.M, 1, concat ? w8 + l.M : nullptr, 1, st, in))) return rc;
+  const PackedLayout pl = packed_layout(cfg, s);
+  char* pk = nullptr;
+  if ((rc = packed_source(cfg, s, w, in ? in->w : nullptr, w8 + l.packed, PK_MERGE | PK_LAYERS, st, &pk))) return rc;
+  if ((rc = run_merge(cfg, si, pk + (in ? pl.mlp : pl.inner), H, lens, U, L, concat ? nullptr : w8 + l.M, 1,
+                      concat ? w8 + l.M : nullptr, 1, st, in))) return rc;
 
   const int T = cdiv(L, cfg->K);
   char* c8 = (char*)cache;
@@ -811,20 +887,20 @@ static int cache_build_impl(const longer_config* cfg, const longer_weights* w, c
   io.q0src = io.src0; io.q1src = io.src1;
   if (cfg->q_learn) { io.q1src = RowSrc{cfg->q_learn, 0, 0}; io.gather_recent = 0; }
   io.X_out = xbuf[0]; io.X_f32 = 1; io.X_ustride = (long long)s.n * s.D;
-  if ((rc = run_layer(cfg, s, pk_cross, lens, U, L, io, cfg->n_self > 0, st))) return rc;
+  if ((rc = run_layer(cfg, s, pk + pl.cross, lens, U, L, io, cfg->n_self > 0, st))) return rc;
   for (int i = 0; i < cfg->n_self; ++i) {
     const char* xin = (const char*)xbuf[i & 1];
-    AttnIO si;
-    memset(&si, 0, sizeof(si));
-    si.src0 = RowSrc{nullptr, 0, 0};
-    si.src1 = RowSrc{xin + (size_t)cfg->m * s.D * 4, (long long)s.n * s.D, 1};
-    si.m0 = 0; si.key_rows = cfg->k_recent; si.KG = 0; si.key_self = 1; si.gather_recent = 0;
-    si.q0 = cfg->m; si.q_rows = cfg->k_recent;
-    si.kst = c8 + cl.c1_off + (size_t)i * cl.c1_lstride; si.vst = si.kst + cl.c1_voff; si.kv_ustride = cl.c1_ustride;
-    si.q0src = si.src0; si.q1src = si.src1;
-    si.X_out = xbuf[(i + 1) & 1]; si.X_f32 = 1; si.X_ustride = (long long)s.n * s.D;
+    AttnIO sio;
+    memset(&sio, 0, sizeof(sio));
+    sio.src0 = RowSrc{nullptr, 0, 0};
+    sio.src1 = RowSrc{xin + (size_t)cfg->m * s.D * 4, (long long)s.n * s.D, 1};
+    sio.m0 = 0; sio.key_rows = cfg->k_recent; sio.KG = 0; sio.key_self = 1; sio.gather_recent = 0;
+    sio.q0 = cfg->m; sio.q_rows = cfg->k_recent;
+    sio.kst = c8 + cl.c1_off + (size_t)i * cl.c1_lstride; sio.vst = sio.kst + cl.c1_voff; sio.kv_ustride = cl.c1_ustride;
+    sio.q0src = sio.src0; sio.q1src = sio.src1;
+    sio.X_out = xbuf[(i + 1) & 1]; sio.X_f32 = 1; sio.X_ustride = (long long)s.n * s.D;
     // the last layer's sequence rows feed nothing: only its K/V are needed
-    if ((rc = run_layer(cfg, s, pk_cross + (size_t)(i + 1) * s.pb, lens, U, L, si, i + 1 < cfg->n_self, st))) return rc;
+    if ((rc = run_layer(cfg, s, pk + pl.self_split + (size_t)i * s.pb, lens, U, L, sio, i + 1 < cfg->n_self, st))) return rc;
   }
   return 0;
 }
@@ -845,33 +921,26 @@ int longer_kv_cache_build_from_inputs(const longer_config* cfg, const longer_wei
   return cache_build_impl(cfg, w, nullptr, &in, lens, U, L, cache, ws, ws_bytes, stream);
 }
 
-int longer_score_candidates(const longer_config* cfg, const longer_weights* w, const void* cache, const int32_t* lens,
-                            int U, int L, const void* G_cand, int C, void* Yg_out, float* logits_out,
-                            void* ws, size_t ws_bytes, void* stream) {
-  g_err[0] = 0;
-  Shape s;
-  int rc = check_cfg(cfg, &s, false, true);
+// argument checks shared by the two scoring entry points
+static int check_score_args(const longer_config* cfg, Shape* s, const longer_weights* w, const void* cache, const void* G_cand,
+                            int U, int L, int C, const void* Yg_out, const float* logits_out) {
+  int rc = check_cfg(cfg, s, false, true);
   if (rc) return rc;
-  if (!w || !w->cross || (cfg->n_self > 0 && !w->self)) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
+  if (!w) return fail(LONGER_ERR_ARG, "weights struct is NULL");
   if (!cache || !G_cand || (!Yg_out && !logits_out)) return fail(LONGER_ERR_ARG, "NULL argument");
   if ((rc = check_aligned({G_cand, Yg_out}))) return rc;
+  if (U <= 0 || L <= 0) return fail(LONGER_ERR_ARG, "U=%d, L=%d must be positive", U, L);
   if (C <= 0) return fail(LONGER_ERR_ARG, "C=%d must be positive", C);
-  const Layout l = make_layout(cfg, s, U, L);
-  if ((rc = check_common(ws, ws_bytes, l.total, U, L))) return rc;
-  const CacheLayout cl = make_cache_layout(cfg, s, U, L);
-  hipStream_t st = (hipStream_t)stream;
-  char* w8 = (char*)ws;
-  char* pk_cross = w8 + l.packed + (size_t)cfg->inner_layers * s.pb;
-  const size_t fstride = (size_t)fused_segs(s.D, s.FF) * s.seg;   // scoring streams all layers back to back
-  PackBatch pk_batch(cfg, s, st);
-  if ((rc = pk_batch.add(w->cross, 1, LAYOUT_FUSED, pk_cross, fstride))) return rc;
-  if (cfg->n_self && (rc = pk_batch.add(w->self, cfg->n_self, LAYOUT_FUSED, pk_cross + fstride, fstride))) return rc;
-  float* head = (float*)(w8 + l.head);
-  if (logits_out && (rc = pk_batch.add_head(w, head))) return rc;
-  if ((rc = pk_batch.flush())) return rc;
+  return 0;
+}
 
+// the scoring launch: `stream_base` = cross block then self blocks, fused layout, back to back
+static int run_score(const longer_config* cfg, const Shape& s, const char* stream_base, const float* head, const void* cache,
+                     const int32_t* lens, int U, int L, const void* G_cand, int C, void* Yg_out, float* logits_out,
+                     hipStream_t st) {
+  const CacheLayout cl = make_cache_layout(cfg, s, U, L);
   BlockParams p = base_params(cfg, s, lens, U, L, s.DH);
-  p.wbase = pk_cross; p.n_layers = 1 + cfg->n_self;
+  p.wbase = stream_base; p.n_layers = 1 + cfg->n_self;
   p.Gc = G_cand; p.C = C; p.cache = (const char*)cache;
   p.c0_ustride = cl.c0_ustride; p.c0_voff = cl.c0_voff; p.c1_off = cl.c1_off; p.c1_lstride = cl.c1_lstride;
   p.c1_ustride = cl.c1_ustride; p.c1_voff = cl.c1_voff; p.kt0 = cl.kt0; p.kt1 = cl.kt1;
@@ -884,6 +953,22 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
   const int win = cfg->m <= 8 ? 4 : (cfg->m <= 16 ? 8 : 16);
   if (s.main_fn(MODE_SCORE, 1, win, p, grid, st)) return fail(LONGER_ERR_HIP, "score kernel launch failed");
   return 0;
+}
+
+int longer_score_candidates(const longer_config* cfg, const longer_weights* w, const void* cache, const int32_t* lens,
+                            int U, int L, const void* G_cand, int C, void* Yg_out, float* logits_out,
+                            void* ws, size_t ws_bytes, void* stream) {
+  g_err[0] = 0;
+  Shape s;
+  int rc = check_score_args(cfg, &s, w, cache, G_cand, U, L, C, Yg_out, logits_out);
+  if (rc) return rc;
+  const Layout l = make_layout(cfg, s, U, L);
+  if ((rc = check_common(ws, ws_bytes, l.total, U, L))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const PackedLayout pl = packed_layout(cfg, s);
+  char* pk = nullptr;
+  if ((rc = packed_source(cfg, s, w, nullptr, (char*)ws + l.packed, PK_SCORE | (logits_out ? PK_HEAD : 0u), st, &pk))) return rc;
+  return run_score(cfg, s, pk + pl.score, (const float*)(pk + pl.head), cache, lens, U, L, G_cand, C, Yg_out, logits_out, st);
 }
 
 int longer_input_generation(const longer_config* cfg, const longer_input_weights* w, const void* E, const void* tdiff,
@@ -916,11 +1001,6 @@ int longer_input_generation(const longer_config* cfg, const longer_input_weights
 
 int longer_stage_timing(int enable) {
   g_err[0] = 0;
-  if (enable && !g_timer.ev) {
-    g_timer.ev = new hipEvent_t[2 * StageTimer::kMaxPairs];
-    for (int i = 0; i < 2 * StageTimer::kMaxPairs; ++i)
-      if (hipEventCreate(&g_timer.ev[i]) != hipSuccess) return fail(LONGER_ERR_HIP, "hipEventCreate failed");
-  }
   // 1 = every stage; any other non-zero value = bit (s + 1) selects stage s
   g_timer.mask = enable == 1 ? ~0u : (unsigned)enable >> 1;
   g_timer.n = 0;

@@ -125,3 +125,35 @@ def test_input_generation_rejects_bad_widths():
     cc = lg.make_config(synth.CONFIGS["P1"])
     rc = lib.longer_forward_from_inputs(ctypes.byref(cc), ctypes.byref(wt), ctypes.byref(w), fake, fake, 96, *args)
     assert rc == -1 and "LONGER_MERGE_MEAN" in lg.longer_last_error()
+
+
+def test_packed_weights_size_and_argument_checks():
+    lib = lg.load_library()
+    c3 = lg.make_config(synth.CONFIGS["C3"])
+    n = lg.longer_packed_weights_bytes(c3)
+    # it holds at least the raw parameter count of every block in its smallest form (bf16), and the
+    # workspace of any batch holds a packed region of that size
+    blocks = 2 + 1 + 3
+    assert n % 256 == 0 and n > blocks * (12 * 128 * 128 + 13 * 128) * 2
+    assert lg.longer_workspace_bytes(c3, 1, 8) > n
+    blk = (lg.binding.CBlock * 4)()
+    w = lg.binding.CWeights(inner=blk, cross=blk, self=blk, head_w=None, head_b=None, packed=None)
+    fake = ctypes.c_void_p(4096)
+    assert lib.longer_pack_weights(ctypes.byref(c3), ctypes.byref(w), None, None, n, None) == -1
+    assert lib.longer_pack_weights(ctypes.byref(c3), ctypes.byref(w), None, fake, n - 1, None) == -2
+    assert lib.longer_pack_weights(ctypes.byref(c3), ctypes.byref(w), None, ctypes.c_void_p(4096 + 16), n, None) == -1
+    assert "aligned" in lg.longer_last_error()
+    # NULL parameter pointers inside a block are caught before anything is launched
+    assert lib.longer_pack_weights(ctypes.byref(c3), ctypes.byref(w), None, fake, n, None) == -1
+    assert "NULL" in lg.longer_last_error()
+    # a misaligned packed buffer handed to an entry point
+    w.packed = 4096 + 16
+    rc = lib.longer_forward(ctypes.byref(c3), ctypes.byref(w), fake, fake, None, 2, 64, fake, None, ctypes.c_void_p(4096), 1 << 40, None)
+    assert rc == -1 and "packed" in lg.longer_last_error()
+
+
+def test_rate_probe_argument_checks():
+    lib = lg.load_library()
+    assert lib.longer_probe_rate(0, 10, 4, None, None) == -1
+    assert lib.longer_probe_rate(11, 10, 4, ctypes.c_void_p(4096), None) == -1
+    assert lib.longer_probe_rate(0, 0, 4, ctypes.c_void_p(4096), None) == -1

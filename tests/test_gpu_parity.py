@@ -22,6 +22,11 @@ def _say(msg):
     print(msg, flush=True)
 
 
+def _gmodel(*a, **kw):
+    from gpu_util import GuardedModel
+    return GuardedModel(*a, **kw)
+
+
 def test_mfma_register_layout_probe():
     import paper_2505_04421_amd as lg
     out = torch.zeros(2, 64, 16, dtype=torch.int32, device="cuda")
@@ -36,12 +41,22 @@ def test_mfma_register_layout_probe():
     assert np.array_equal(got[1], exp), got[1][:2]
 
 
+# A single row (one token's d features) is judged too, so that one bad row cannot hide among a
+# user's many good ones: fp32 at the same bar, bf16 at ROW_SLACK times the per-user bar (a row
+# has d values where a user has thousands, so its error norm fluctuates more).
+ROW_SLACK = {"f32": 1.0, "bf16": 2.0}
+
+
 def _check(name, got, ref, tol):
-    from gpu_util import rel_l2_per_user, assert_zero_where_ref_zero_rows
+    from gpu_util import rel_l2_per_user, rel_l2_per_row, assert_zero_where_ref_zero_rows, check_all_guards
+    check_all_guards()
     assert np.isfinite(got).all(), name + ": non-finite output"
     err = rel_l2_per_user(got, ref)
-    _say("  %-28s rel-L2 max %.3e (tol %.0e)" % (name, err, tol))
+    row = rel_l2_per_row(got, ref) if got.ndim >= 3 else err
+    row_tol = tol * (ROW_SLACK["f32"] if tol < 1e-3 else ROW_SLACK["bf16"])
+    _say("  %-28s rel-L2 max %.3e (tol %.0e), worst row %.3e (tol %.0e)" % (name, err, tol, row, row_tol))
     assert err <= tol, (name, err)
+    assert row <= row_tol, (name, "row", row)
     assert_zero_where_ref_zero_rows(got, ref)
     return err
 
@@ -315,7 +330,7 @@ def test_input_generation(base, d_e, B, L):
     case["E"][0] = rnd(g.standard_normal(case["E"][0].shape).astype(np.float32))
     case["tdiff"][0] = rnd(g.standard_normal(case["tdiff"][0].shape).astype(np.float32))
     tol = TOL[cfg.dtype]
-    model = lg.DeviceModel(cfg, synth.draw_weights(cfg))
+    model = _gmodel(cfg, synth.draw_weights(cfg))
     mlp = {k: model.upload(v) for k, v in case["mlp"].items()}
     wts = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
     Ed, Td = model.upload(case["E"]), model.upload(case["tdiff"])
@@ -352,7 +367,7 @@ def test_forward_from_inputs(base, d_e, B, L):
     w = synth.draw_weights(cfg)
     if cfg.dtype == "bf16":
         w = synth._map_tree(w, synth.round_bf16)
-    model = lg.DeviceModel(cfg, w)
+    model = _gmodel(cfg, w)
     mlp = {k: model.upload(v) for k, v in case["mlp"].items()}
     wts = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
     Ed, Td, Gd = model.upload(case["E"]), model.upload(case["tdiff"]), model.upload(G)
@@ -387,7 +402,7 @@ def test_forward_and_scoring_under_hip_graph_capture():
     import paper_2505_04421_amd as lg
     cfg = synth.CONFIGS["C2"].replace(B=16, C=12, ragged=True, len_lo=0, len_hi=512, index=31)
     case = synth.make_case(cfg, pad_value=float("nan"))
-    model = lg.DeviceModel(cfg, case["weights"])
+    model = _gmodel(cfg, case["weights"])
     B, L = cfg.B, cfg.L
     ws = model.workspace(B, L, cfg.C)
     lens = torch.from_numpy(case["lens"].astype(np.int32)).to(model.device)
@@ -456,7 +471,7 @@ def test_forward_from_inputs_with_learnable_queries_and_wide_query_set():
         case["tdiff"][u, :n] = synth.round_bf16(g.standard_normal((n, cfg.d - d_e)).astype(np.float32))
     G = synth.round_bf16(g.standard_normal((cfg.B, cfg.m, cfg.d)).astype(np.float32))
     w = synth._map_tree(synth.draw_weights(cfg), synth.round_bf16)
-    model = lg.DeviceModel(cfg, w)
+    model = _gmodel(cfg, w)
     mlp = {k: model.upload(v) for k, v in case["mlp"].items()}
     iw = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
     lens = torch.from_numpy(case["lens"].astype(np.int32)).to(model.device)
@@ -494,7 +509,7 @@ def test_serving_from_inputs(base, d_e, U, L):
     if cfg.dtype == "bf16":
         w = synth._map_tree(w, synth.round_bf16)
     tol = TOL[cfg.dtype]
-    model = lg.DeviceModel(cfg, w)
+    model = _gmodel(cfg, w)
     mlp = {k: model.upload(v) for k, v in case["mlp"].items()}
     iw = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
     lens = torch.from_numpy(case["lens"].astype(np.int32)).to(model.device)
@@ -510,8 +525,75 @@ def test_serving_from_inputs(base, d_e, U, L):
     H_ref = orc.input_generation(cfg, case["mlp"], case["E"], case["tdiff"], case["lens"])
     ref_cache = orc.kv_cache_build(cfg, w, H_ref, case["lens"])
     Yg_ref, lg_ref = orc.score_candidates(cfg, w, ref_cache, Gc)
-    _check("Yg", Yg.float().cpu().numpy().astype(np.float64).reshape(U * cfg.C, -1), Yg_ref.reshape(U * cfg.C, -1), tol)
+    _check("Yg", Yg.float().cpu().numpy().astype(np.float64).reshape(U * cfg.C, cfg.m, cfg.d), Yg_ref.reshape(U * cfg.C, cfg.m, cfg.d), tol)
     _check_logits_by_terms("logits", logits.cpu().numpy().astype(np.float64), lg_ref, Yg_ref, w["head_w"], tol)
+
+
+def test_rows_of_missing_tokens_are_never_read_by_the_layer_entry_points():
+    """longer_hybrid_cross_attn and longer_self_attn_layer on caller-made inputs whose rows of
+    tokens that do not exist (merged tokens past T_u, invalid query slots) hold NaN: those rows
+    must not reach any K/V, so the results equal the oracle's, which never looks at them."""
+    cfg = synth.CONFIGS["C2"].replace(B=5, L=512, n_self=1, ragged=True, len_lo=0, len_hi=512, index=41)
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    case["lens"][:] = [512, 0, 37, 200, 263]
+    w = case["weights"]
+    r = _runner(case)
+    g = np.random.default_rng(19)
+    Tu = (case["lens"] + cfg.K - 1) // cfg.K
+    M = synth.round_bf16(g.standard_normal((cfg.B, cfg.T, cfg.d)).astype(np.float32))
+    for u in range(cfg.B):
+        M[u, Tu[u]:] = np.nan
+    G = case["G"]
+    _say("NaN in the rows of missing tokens (cross layer: M past T_u)")
+    X1_ref = orc.hybrid_cross_attn(cfg, w["cross"], G, np.nan_to_num(M), case["lens"], L=cfg.L)
+    _check("longer_hybrid_cross_attn", r.cross(G, M), X1_ref, TOL["bf16"])
+    X = synth.round_bf16(g.standard_normal((cfg.B, cfg.n, cfg.d)).astype(np.float32))
+    for u in range(cfg.B):
+        X[u, cfg.m:cfg.m + max(cfg.k_recent - Tu[u], 0)] = np.nan
+    _say("NaN in the rows of missing tokens (self layer: invalid query slots)")
+    X2_ref = orc.self_attn_layer(cfg, w["self"][0], np.nan_to_num(X), case["lens"], L=cfg.L)
+    _check("longer_self_attn_layer", r.self_layer(X, 0), X2_ref, TOL["bf16"])
+
+
+@pytest.mark.parametrize("k_recent", [32, 150])
+def test_parameters_packed_once_equal_packing_per_call(k_recent):
+    """longer_pack_weights + a longer_weights whose `packed` member is set give bit for bit what the
+    same calls give when they pack per call: forward (both launch plans), forward from raw inputs,
+    cache build + scoring."""
+    import paper_2505_04421_amd as lg
+    cfg = synth.CONFIGS["C2"].replace(B=5, L=400, k_recent=k_recent, n_self=2, C=9, ragged=True, len_lo=0, len_hi=400, index=42)
+    d_e = 32
+    case = synth.make_case(cfg, pad_value=float("nan"))
+    icase = synth.make_input_case(cfg.replace(ragged=False), d_e)
+    model = _gmodel(cfg, case["weights"])
+    mlp = {k: model.upload(v) for k, v in icase["mlp"].items()}
+    iw = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
+    packed = model.pack(iw)
+    B, L = cfg.B, cfg.L
+    lens = torch.from_numpy(case["lens"].astype(np.int32)).to(model.device)
+    H, G, Gc = model.upload(case["H"]), model.upload(case["G"]), model.upload(case["G_cand"])
+    Ed, Td = model.upload(icase["E"]), model.upload(icase["tdiff"])
+    ws = model.workspace(B, L)
+    _say("packed once vs packed per call, m + k = %d" % cfg.n)
+    outs = []
+    for wts in (model.weights, packed):
+        Y, logits = model.empty(B, cfg.n, cfg.d), model.empty(B, dtype=torch.float32)
+        Y2, logits2 = model.empty(B, cfg.n, cfg.d), model.empty(B, dtype=torch.float32)
+        cache = model.kv_cache(B, L)
+        Yg, sc = model.empty(B, cfg.C, cfg.m, cfg.d), model.empty(B, cfg.C, dtype=torch.float32)
+        lg.longer_forward(model.ccfg, wts, H, G, lens, B, L, Y, logits, ws)
+        lg.longer_forward_from_inputs(model.ccfg, wts, iw, Ed, Td, d_e, G, lens, B, L, Y2, logits2, ws)
+        lg.longer_kv_cache_build(model.ccfg, wts, H, lens, B, L, cache, ws)
+        lg.longer_score_candidates(model.ccfg, wts, cache, lens, B, L, Gc, cfg.C, Yg, sc, ws)
+        torch.cuda.synchronize()
+        ws.fill_(0xA5)       # the second round must not live on what the first one packed into the workspace
+        outs.append((Y, logits, Y2, logits2, Yg, sc))
+    from gpu_util import check_all_guards
+    check_all_guards()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    Y_ref, lg_ref = orc.forward(cfg, case["weights"], case["H"], case["G"], case["lens"])
+    _check("packed once: longer_forward Y", outs[1][0].float().cpu().numpy().astype(np.float64), Y_ref, TOL["bf16"])
 
 
 def _random_config(seed):
@@ -561,7 +643,7 @@ def test_random_configurations_forward_and_serving(seed):
     Yg, lgs = r.serve()
     cache = orc.kv_cache_build(cfg, w, case["H"], case["lens"])
     Yg_ref, lgs_ref = orc.score_candidates(cfg, w, cache, case["G_cand"])
-    _check("longer_score_candidates Yg", Yg.reshape(cfg.B * cfg.C, -1), Yg_ref.reshape(cfg.B * cfg.C, -1), tol)
+    _check("longer_score_candidates Yg", Yg.reshape(cfg.B * cfg.C, cfg.m, cfg.d), Yg_ref.reshape(cfg.B * cfg.C, cfg.m, cfg.d), tol)
     sc2 = (np.abs(Yg_ref.reshape(cfg.B, cfg.C, -1)) * hw[None, None, :]).sum(2) + 1e-30
     assert np.isfinite(lgs).all() and (np.abs(lgs - lgs_ref) / sc2).max() <= tol
 
@@ -594,7 +676,7 @@ def _serving(case, tol, logits_by_terms=False):
     cache = orc.kv_cache_build(cfg, w, case["H"], case["lens"])
     Yg_ref, lg_ref = orc.score_candidates(cfg, w, cache, case["G_cand"])
     U, C = cfg.B, cfg.C
-    _check("longer_score_candidates Yg", Yg.reshape(U * C, -1), Yg_ref.reshape(U * C, -1), tol)
+    _check("longer_score_candidates Yg", Yg.reshape(U * C, cfg.m, cfg.d), Yg_ref.reshape(U * C, cfg.m, cfg.d), tol)
     if logits_by_terms:
         _check_logits_by_terms("longer_score_candidates logit", logits, lg_ref, Yg_ref, w["head_w"], tol)
     else:
@@ -624,40 +706,42 @@ def test_c5_bf16_serving():
 # oracle recomputes a sample of users (users are independent) and every sampled row is
 # compared element by element.  All other users are checked for finiteness and for exact
 # zeros in their invalid rows.
-def _full_size_forward(name, sample, pad_value=0.0):
-    from gpu_util import rel_l2_per_user
+def _full_size_forward(name, sample, pad_value=0.0, packed=False):
+    from gpu_util import Runner
     case = synth.make_case(synth.CONFIGS[name], pad_value=pad_value)
     cfg, w = case["cfg"], case["weights"]
-    r = _runner(case)
+    r = Runner(case, packed=packed)
     Y, logits = r.forward()
     assert np.isfinite(Y).all() and np.isfinite(logits).all()
-    idx = np.array(sample)
+    idx = np.arange(cfg.B) if sample is None else np.array(sample)
     lens = None if case["lens"] is None else case["lens"][idx]
     Y_ref, lg_ref = orc.forward(cfg, w, case["H"][idx], case["G"][idx], lens)
     tol = TOL[cfg.dtype]
-    _check(name + " full batch, sampled users Y", Y[idx], Y_ref, tol)
-    _check(name + " full batch, sampled logits", logits[idx][None, :], lg_ref[None, :], tol)
+    _check(name + " full batch, %d users Y" % len(idx), Y[idx], Y_ref, tol)
+    _check(name + " full batch, logits", logits[idx][None, :], lg_ref[None, :], tol)
     if case["lens"] is not None:
         Tu = (case["lens"] + cfg.K - 1) // cfg.K
         for u in np.nonzero(Tu < cfg.k_recent)[0]:
             assert (Y[u, cfg.m:cfg.m + cfg.k_recent - Tu[u]] == 0).all()
 
 
-def test_c2_full_size_sampled_users():
-    _say("C2 full size (128 users)")
-    _full_size_forward("C2", [0, 37, 127])
+def test_c2_full_size_all_users():
+    _say("C2 full size (128 users), every user against the oracle")
+    _full_size_forward("C2", None)
 
 
-def test_c3_full_size_sampled_users():
-    _say("C3 full size (256 users x 2000)")
-    _full_size_forward("C3", [0, 101, 255])
+def test_c3_full_size_all_users():
+    _say("C3 full size (256 users x 2000), every user against the oracle, parameters packed once")
+    _full_size_forward("C3", None, packed=True)
 
 
 def test_c4_full_size_sampled_users():
-    _say("C4 full size (512 users, ragged, NaN padding)")
+    _say("C4 full size (512 users, ragged, NaN padding), 40 users against the oracle")
     case = synth.make_case(synth.CONFIGS["C4"])
-    shortest, longest = int(np.argmin(case["lens"])), int(np.argmax(case["lens"]))
-    _full_size_forward("C4", sorted({0, shortest, longest, 511}), pad_value=float("nan"))
+    order = np.argsort(case["lens"], kind="stable")
+    # the four shortest, the four longest, the first and last of the batch and every 16th user in between
+    pick = sorted(set(order[:4].tolist()) | set(order[-4:].tolist()) | {0, 511} | set(range(8, 512, 16)))
+    _full_size_forward("C4", pick, pad_value=float("nan"))
 
 
 def test_concat_production_shape_full_size_sampled_users():
@@ -675,7 +759,7 @@ def test_forward_from_inputs_full_size_sampled_users():
     case = synth.make_case(cfg)
     icase = synth.make_input_case(cfg, d_e)
     w = case["weights"]
-    model = lg.DeviceModel(cfg, w)
+    model = _gmodel(cfg, w)
     mlp = {k: model.upload(v) for k, v in icase["mlp"].items()}
     iw = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
     Ed, Td, Gd = model.upload(icase["E"]), model.upload(icase["tdiff"]), model.upload(case["G"])
@@ -693,16 +777,25 @@ def test_forward_from_inputs_full_size_sampled_users():
     _check("from raw inputs, sampled logits", lh[idx][None, :], lg_ref[None, :], TOL["bf16"])
 
 
-def test_c5_full_size_sampled_candidates():
+def test_c5_full_size_whole_workgroups_of_candidates():
+    """C5 in the launch configuration the benchmark times.  Per checked user: every candidate of the
+    first workgroup of its candidate tiles (4 waves x 32 rows = 16 candidates), of a workgroup in the
+    middle, and of the last (partially filled) workgroup.  Users 0, 7, 8 and 15 sit on different
+    dies of the chip under the scoring launch's user placement (user u on die u mod 8)."""
     _say("C5 full size (16 users x 1000 candidates)")
     case = synth.make_case(synth.CONFIGS["C5"])
     cfg, w = case["cfg"], case["weights"]
     r = _runner(case)
     Yg, logits = r.serve()
     assert np.isfinite(Yg).all() and np.isfinite(logits).all()
-    users, cands = [0, 9, 15], [0, 1, 499, 999]
+    users = [0, 7, 8, 15]
+    per_wg = 4 * 32 // cfg.m
+    last_wg = (cfg.C - 1) // per_wg
+    cands = sorted(set(range(0, per_wg)) | set(range(31 * per_wg, 32 * per_wg)) | set(range(last_wg * per_wg, cfg.C)))
     cache = orc.kv_cache_build(cfg, w, case["H"][users], None)
     Yg_ref, lg_ref = orc.score_candidates(cfg, w, cache, case["G_cand"][users][:, cands])
     got = Yg[users][:, cands]
-    _check("C5 sampled Yg", got.reshape(len(users) * len(cands), -1), Yg_ref.reshape(len(users) * len(cands), -1), TOL["bf16"])
-    _check("C5 sampled logits", logits[users][:, cands], lg_ref, TOL["bf16"])
+    n = len(users) * len(cands)
+    _say("  %d users x %d candidates against the oracle" % (len(users), len(cands)))
+    _check("C5 Yg", got.reshape(n, cfg.m, cfg.d), Yg_ref.reshape(n, cfg.m, cfg.d), TOL["bf16"])
+    _check("C5 logits", logits[users][:, cands], lg_ref, TOL["bf16"])

@@ -79,6 +79,23 @@ def test_headline_flop_count():
     assert abs(fl["total"] * 256 / 1e9 - 458.1) < 0.5
 
 
+def test_scoring_flop_count_against_a_hand_count():
+    # one candidate of the serving configuration (d = 256, m = 8 global rows, T = 625 cached merged
+    # tokens, k = 64 cached slots in each of the 3 self layers, every global sees every global):
+    #   per layer, projections + FFN of 8 rows (Eq. 3's 24 d^2 per token)  8 * 24 * 256^2 = 12 582 912
+    #   first layer's attention, 4 d per query-key pair                    4 * 256 * 8 * (8 + 625) = 5 185 536
+    #   a self layer's attention                                           4 * 256 * 8 * (8 + 64) = 589 824
+    #   total 4 * 12 582 912 + 5 185 536 + 3 * 589 824 = 57 286 656
+    cfg = synth.CONFIGS["C5"]
+    assert orc.algorithmic_flops_score(cfg, cfg.T) == 57286656
+    # fewer cached tokens than slots: the self layers see only the valid slots; no cached token at all
+    assert orc.algorithmic_flops_score(cfg, 10) == 4 * 12582912 + 4 * 256 * 8 * (8 + 10) * 4
+    assert orc.algorithmic_flops_score(cfg, 0) == 4 * 12582912 + 4 * 256 * 8 * 8 * 4
+    # Eq. 8 read literally between the globals: 8 * 9 / 2 = 36 global pairs instead of 64
+    causal = cfg.replace(gmask="causal")
+    assert orc.algorithmic_flops_score(causal, cfg.T) == 57286656 - 4 * 4 * 256 * (64 - 36)
+
+
 # --------------------------------------------------------------------------- library pins
 def _torch_layer(blk, d, heads):
     layer = torch.nn.TransformerEncoderLayer(d, heads, 4 * d, dropout=0.0, activation="gelu",
