@@ -230,6 +230,21 @@ size_t longer_packed_weights_bytes(const longer_config* cfg);
 int longer_pack_weights(const longer_config* cfg, const longer_weights* w, const longer_input_weights* iw,
                         void* packed_out, size_t bytes, void* stream);
 
+/* longer_score_candidates for callers that cannot allocate or carry a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without
+ * `ws`, same results.  The packed parameters of the scoring launch go to a file-scope device
+ * array of LONGER_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs on holds its
+ * own copy until the process ends; its address is looked up on the first call on a device, with
+ * that device current, and the call must be made with the stream's device current).  A model
+ * whose packed cross + self blocks and head exceed that size (d = 256 with ffn_mult = 4: more
+ * than 1 + 4 layers) is rejected with LONGER_ERR_WS.  The call allocates nothing and calls no
+ * allocating routine.  Every call on a GPU shares that GPU's array and overwrites it: calls that
+ * overlap on one GPU (two streams, two threads) race; order them on one stream. */
+#define LONGER_STATIC_SCRATCH_BYTES (8u << 20)
+int longer_score_candidates_static(const longer_config* cfg, const longer_weights* w, const void* cache,
+                                   const int32_t* lens, int U, int L, const void* G_cand, int C,
+                                   void* Yg_out, float* logits_out, void* stream);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* longer_last_error(void);
 

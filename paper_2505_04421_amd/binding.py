@@ -15,7 +15,8 @@ ENTRY_POINTS = ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_inner
                 "longer_forward", "longer_kv_cache_build", "longer_score_candidates", "longer_input_generation",
                 "longer_forward_from_inputs", "longer_kv_cache_build_from_inputs",
                 "longer_last_error", "longer_probe_mfma_layout", "longer_stage_timing",
-                "longer_stage_timing_read", "longer_packed_weights_bytes", "longer_pack_weights", "longer_probe_rate")
+                "longer_stage_timing_read", "longer_packed_weights_bytes", "longer_pack_weights",
+                "longer_score_candidates_static", "longer_probe_rate")
 
 
 class LongerError(RuntimeError):
@@ -80,6 +81,7 @@ def load_library() -> ctypes.CDLL:
     lib.longer_packed_weights_bytes.restype = sz
     lib.longer_packed_weights_bytes.argtypes = [cfgp]
     lib.longer_pack_weights.argtypes = [cfgp, wp, ctypes.POINTER(CInputWeights), vp, sz, vp]
+    lib.longer_score_candidates_static.argtypes = [cfgp, wp, vp, vp, i32, i32, vp, i32, vp, vp, vp]
     lib.longer_probe_rate.argtypes = [i32, i32, i32, vp, vp]
     lib.longer_last_error.restype = ctypes.c_char_p
     lib.longer_probe_mfma_layout.argtypes = [vp, vp]
@@ -226,6 +228,13 @@ def longer_pack_weights(ccfg, weights, iweights, packed_out, stream=None):
     _check(load_library().longer_pack_weights(ctypes.byref(ccfg), ctypes.byref(weights),
                                               None if iweights is None else ctypes.byref(iweights),
                                               _ptr(packed_out), packed_out.numel(), _stream(stream)), "longer_pack_weights")
+
+
+def longer_score_candidates_static(ccfg, weights, cache, lens, U, L, G_cand, C, Yg_out, logits_out, stream=None):
+    _require_gpu()
+    _check(load_library().longer_score_candidates_static(ctypes.byref(ccfg), ctypes.byref(weights), _ptr(cache), _ptr(lens),
+                                                         U, L, _ptr(G_cand), C, _ptr(Yg_out), _ptr(logits_out),
+                                                         _stream(stream)), "longer_score_candidates_static")
 
 
 def longer_probe_rate(mode, iters, workgroups, out, stream=None):

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <initializer_list>
+#include <mutex>
 #include <cstring>
 
 namespace longer {
@@ -632,6 +633,32 @@ static int packed_source(const longer_config* cfg, const Shape& s, const longer_
 
 using namespace longer;
 
+// ------------------------------------------------------------------------------------
+// Device memory of the entry point that takes no workspace (longer_score_candidates_static): the
+// packed parameters of the scoring launch.  Every device the library runs on holds its own copy at
+// its own address; host code uses the address hipGetSymbolAddress returns for the current device,
+// never the symbol itself.
+static constexpr size_t kScratchBytes = (size_t)LONGER_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+static constexpr int kMaxDevices = 64;
+static char* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mu;
+
+static int scratch_of_current_device(char** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return fail(LONGER_ERR_HIP, "hipGetDevice failed or device index %d beyond %d", dev, kMaxDevices);
+  std::lock_guard<std::mutex> guard(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return fail(LONGER_ERR_HIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = (char*)ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return 0;
+}
+
 extern "C" {
 
 const char* longer_last_error(void) { return g_err; }
@@ -969,6 +996,30 @@ int longer_score_candidates(const longer_config* cfg, const longer_weights* w, c
   char* pk = nullptr;
   if ((rc = packed_source(cfg, s, w, nullptr, (char*)ws + l.packed, PK_SCORE | (logits_out ? PK_HEAD : 0u), st, &pk))) return rc;
   return run_score(cfg, s, pk + pl.score, (const float*)(pk + pl.head), cache, lens, U, L, G_cand, C, Yg_out, logits_out, st);
+}
+
+int longer_score_candidates_static(const longer_config* cfg, const longer_weights* w, const void* cache, const int32_t* lens,
+                                   int U, int L, const void* G_cand, int C, void* Yg_out, float* logits_out, void* stream) {
+  g_err[0] = 0;
+  Shape s;
+  int rc = check_score_args(cfg, &s, w, cache, G_cand, U, L, C, Yg_out, logits_out);
+  if (rc) return rc;
+  // the scratch holds what the scoring launch streams: [cross, self blocks (fused)][panel overrun][head]
+  const size_t stride = (size_t)fused_segs(s.D, s.FF) * s.seg;
+  const size_t head_off = align256((size_t)(1 + cfg->n_self) * stride + 4 * s.seg);
+  const size_t need = head_off + align256(((size_t)cfg->m * s.D + 1) * 4);
+  if (need > kScratchBytes)
+    return fail(LONGER_ERR_WS, "model too large for the static scratch: %zu > %zu bytes (use longer_score_candidates)", need, kScratchBytes);
+  char* base = nullptr;
+  if ((rc = scratch_of_current_device(&base))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  if (!w->cross || (cfg->n_self > 0 && !w->self)) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
+  PackBatch pk(cfg, s, st);
+  if ((rc = pk.add(w->cross, 1, LAYOUT_FUSED, base, stride))) return rc;
+  if (cfg->n_self && (rc = pk.add(w->self, cfg->n_self, LAYOUT_FUSED, base + stride, stride))) return rc;
+  if (logits_out && (rc = pk.add_head(w, (float*)(base + head_off)))) return rc;
+  if ((rc = pk.flush())) return rc;
+  return run_score(cfg, s, base, (const float*)(base + head_off), cache, lens, U, L, G_cand, C, Yg_out, logits_out, st);
 }
 
 int longer_input_generation(const longer_config* cfg, const longer_input_weights* w, const void* E, const void* tdiff,

@@ -152,6 +152,21 @@ def test_packed_weights_size_and_argument_checks():
     assert rc == -1 and "packed" in lg.longer_last_error()
 
 
+def test_static_scoring_argument_checks():
+    lib = lg.load_library()
+    c5 = lg.make_config(synth.CONFIGS["C5"])
+    blk = (lg.binding.CBlock * 8)()
+    w = lg.binding.CWeights(inner=blk, cross=blk, self=blk, head_w=None, head_b=None, packed=None)
+    fake = ctypes.c_void_p(4096)
+    rc = lib.longer_score_candidates_static(ctypes.byref(c5), ctypes.byref(w), None, None, 2, 100, fake, 3, fake, fake, None)
+    assert rc == -1 and "NULL" in lg.longer_last_error()
+    rc = lib.longer_score_candidates_static(ctypes.byref(c5), ctypes.byref(w), fake, None, 2, 100, fake, 0, fake, fake, None)
+    assert rc == -1 and "C=" in lg.longer_last_error()
+    big = lg.make_config(synth.CONFIGS["C5"].replace(n_self=6))     # 7 packed blocks of 1.5 MiB: beyond the 8 MiB array
+    rc = lib.longer_score_candidates_static(ctypes.byref(big), ctypes.byref(w), fake, None, 2, 100, fake, 3, fake, fake, None)
+    assert rc == -2 and "static scratch" in lg.longer_last_error()
+
+
 def test_rate_probe_argument_checks():
     lib = lg.load_library()
     assert lib.longer_probe_rate(0, 10, 4, None, None) == -1
