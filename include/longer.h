@@ -278,6 +278,10 @@ int longer_probe_mfma_layout(int32_t* out, void* stream);
  *   4 as 3, idle cycles after each MFMA           5 every MFMA followed by 4 FMAs
  *   6 every MFMA followed by 8 FMAs               7 MFMAs in waves 0-3 only (one wave per SIMD)
  *   8 as 0 with the idle cycles of 4              9 as 3 with the MFMA waves at raised priority
+ *   10 / 12 every MFMA followed by 4 / 2 packed fp16 FMAs       11 packed fp16 FMAs alone (128)
+ *   13 every MFMA followed by 2 v_exp_f32         14 v_exp_f32 alone (128)
+ *   15 every MFMA followed by one 16-byte LDS read per lane
+ *   16 every MFMA followed by 4 fp32 -> bf16 pair conversions    17 every MFMA followed by 6 FMAs
  * The caller times the launch (events on `stream`).  out: device, workgroups * 512 floats
  * (a sink that keeps the work alive). */
 int longer_probe_rate(int mode, int iters, int workgroups, float* out, void* stream);

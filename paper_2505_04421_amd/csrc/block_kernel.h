@@ -26,6 +26,7 @@
 // rows come from, which attention sources exist and what is written.
 #pragma once
 #include "device.h"
+#include <type_traits>
 
 namespace longer {
 
@@ -442,6 +443,10 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   constexpr bool PIPE = sizeof(T) == 2 && TT == 1 && (STACK || MERGE) && D < 256;
   constexpr bool MANUAL = sizeof(T) == 2 && TT == 1 && D >= 256;
   constexpr bool BIGSEG = SEGV * 16 >= 16384;
+  // bf16 kernels up to d = 128: the FFN loop is software pipelined over its hidden chunks and reads
+  // the packed stream's FFN part in the skewed order (device.h)
+  constexpr bool SKEW = ffn_skewed((int)sizeof(T), D);
+  static_assert(!SKEW || TT == 1, "the pipelined FFN loop handles one tile per wave");
   constexpr int PSEG = BIGSEG ? 1 : 4;              // segments per panel of the weight stream (one barrier per panel)
   constexpr int NB = BIGSEG ? 6 : 2;                // ring depth in panels
   static_assert(DH == 16 || DH == 32, "head width");
@@ -600,12 +605,13 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
   }
 
   WStream<SEGV, PSEG, NB, MODE == MODE_KVPROJ> ws;
-  const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : MODE == MODE_INPUT ? 2 * NC : (ATTNLIKE ? 2 * NT + 2 * NC : 4 * NT + 2 * NC));
+  const int NF = 2 * NC + 1;     // segments of a block's FFN part (device.h)
+  const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : MODE == MODE_INPUT ? NF : (ATTNLIKE ? 2 * NT + NF : 4 * NT + NF));
   // MODE_STACK: the cross block's attention sub-stream, then the self blocks in the fused
-  // layout, each followed by the unused segment that fills its slot in the packed buffer.
+  // layout, back to back (every part has an even number of segments).
   // MODE_MERGE_IN: the input MLP's segments, then the InnerTrans blocks (n_layers counts both)
-  ws.init(lds, p.wbase, STACK ? steps + (p.n_layers - 1) * (2 + 4 * NT + 2 * NC)
-                              : MODE == MODE_MERGE_IN ? 1 + 2 * NC + (p.n_layers - 1) * steps : steps * p.n_layers);
+  ws.init(lds, p.wbase, STACK ? steps + (p.n_layers - 1) * (1 + 4 * NT + NF)
+                              : MODE == MODE_MERGE_IN ? 1 + NF + (p.n_layers - 1) * steps : steps * p.n_layers);
 
   // hands the NG weight fragments of the current segment to use(s, w) one by one; MANUAL keeps
   // AH reads in flight in front of the MFMA that is being issued (the order is pinned)
@@ -887,7 +893,143 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) resid[tt][nt] += b2;
     }
-    {
+    if constexpr (SKEW) {
+      // Software-pipelined FFN.  The matrix pipe and the vector ALU overlap only inside one wave's
+      // instruction stream, at about four VALU instructions per MFMA (an MFMA followed by another
+      // MFMA keeps the issue port until the pipe is free, and another wave's VALU work waits with
+      // it).  The activation of chunk i is therefore issued between the MFMAs of two GEMMs that do
+      // not depend on it, the first GEMM of chunk i + 1 and the second GEMM of chunk i - 1, one
+      // stage of its polynomial (four packed instructions that do not depend on each other) behind
+      // each MFMA.  ah[i & 1] holds chunk i's hidden pre-activations, hop[i & 1] its activated
+      // operand groups; the packed stream brings the pair {W2(i-1), W1(i+1)} side by side (device.h).
+      // The order is written out and pinned (sched_barrier): under this kernel's register pressure
+      // the compiler's scheduler does not follow group hints here.
+      f32x16 ah[2];
+      typename E::hgrp hop[2][GPT];
+      constexpr int NS = RELU ? 2 : 8;          // stages of one operand group's activation
+      constexpr int NP = GPT * NS;              // stages of a chunk
+      f16x8 ay, av, ap;                         // the group in flight: y = x / kFfnScale, y^2, the polynomial
+      // stage st of operand group gg of the chunk in `a`; the last stage delivers the group
+      // A stage's first operand passes through an empty volatile asm statement: the stage then
+      // cannot be moved ahead of the MFMA it is written behind (pure arithmetic is otherwise free
+      // to move across the pinned points, and the compiler gathers it in front of the MFMAs).
+      auto pin = [&](f16x8& x) {
+        u32x4 t = __builtin_bit_cast(u32x4, x);
+        asm volatile("" : "+v"(t));
+        x = __builtin_bit_cast(f16x8, t);
+      };
+      auto act_stage = [&](const f32x16& a, int gg, int st, typename E::hgrp& out) {
+        if (st == 0) {          // pairs of elements to fp16 (toward zero: never to infinity)
+#pragma unroll
+          for (int e = 0; e < E::EPL / 2; ++e) {
+            float lo = a[E::EPL * gg + 2 * e], up = a[E::EPL * gg + 2 * e + 1];
+            asm volatile("" : "+v"(lo), "+v"(up));
+            const f16x2 y2 = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(lo, up));
+            ay[2 * e] = y2[0]; ay[2 * e + 1] = y2[1];
+          }
+          return;
+        }
+        if (st == 1 || RELU) pin(ay); else if (st == 2) pin(av); else pin(ap);
+        if (RELU) {
+          out = __builtin_elementwise_max(ay, (f16x8)((_Float16)0.f));
+        } else if (st == 1) {   // the polynomial of gelu_quarter_h8, one Horner step per stage
+          av = ay * ay;
+        } else if (st == 2) {
+          ap = __builtin_elementwise_fma((f16x8)((_Float16)2.4554419175668456f), av, (f16x8)((_Float16)-6.304095499217479f));
+        } else if (st == 3) {
+          ap = __builtin_elementwise_fma(ap, av, (f16x8)((_Float16)6.604333663059149f));
+        } else if (st == 4) {
+          ap = __builtin_elementwise_fma(ap, av, (f16x8)((_Float16)-3.771901897714043f));
+        } else if (st == 5) {
+          ap = __builtin_elementwise_fma(ap, av, (f16x8)((_Float16)1.5736394077430096f));
+        } else if (st == 6) {
+          ap = __builtin_elementwise_fma(ay, ap, (f16x8)((_Float16)0.5f));
+          ap = __builtin_elementwise_min(__builtin_elementwise_max(ap, (f16x8)((_Float16)0.f)), (f16x8)((_Float16)1.f));
+        } else {
+          out = ay * ap;
+        }
+      };
+      // One pipeline step on chunk i (PA = i & 1).  F2: the second GEMM of chunk i - 1 from the
+      // pair's first segment; F1: the first GEMM of chunk i + 1 from its second segment (the first,
+      // without F2); ACT: the activation of chunk i.  The MFMAs of the two GEMMs alternate.
+      auto step = [&](auto pa_, auto f1_, auto f2_, auto act_, int i) {
+        constexpr int PA = decltype(pa_)::value, PB = PA ^ 1;
+        constexpr bool F1 = decltype(f1_)::value, F2 = decltype(f2_)::value, ACT = decltype(act_)::value;
+        constexpr int NM = (F1 ? NG : 0) + (F2 ? NG : 0);      // GPT * NT = NG MFMAs in either GEMM
+        constexpr int AH = 3;                                    // fragment reads in flight
+        if constexpr (F1) ah[PB] = bias_tile(vec + vl.b1(), i + 1, hi);
+        // MFMA q of the step: which GEMM, which fragment
+        auto is_f2 = [&](int q) { return F2 && (!F1 || (q & 1) == 0); };
+        auto load = [&](int q) -> grp {
+          const int j = (F1 && F2) ? q / 2 : q;
+          if (is_f2(q)) return ws.template frag_at<grp>(0, (j % NT) * GPT + j / NT);   // output tile j % NT, operand group j / NT
+          return ws.template frag_at<grp>(F2 ? 1 : 0, j);
+        };
+        grp fr[AH];
+#pragma unroll
+        for (int q = 0; q < AH && q < NM; ++q) fr[q] = load(q);
+#pragma unroll
+        for (int q = 0; q < NM; ++q) {
+          __builtin_amdgcn_sched_barrier(0);
+          const int j = (F1 && F2) ? q / 2 : q;
+          if (is_f2(q)) resid[0][j % NT] = E::mma_h(fr[q % AH], hop[PB][j / NT], resid[0][j % NT]);
+          else ah[PB] = E::mma(fr[q % AH], xn[0][j], ah[PB]);
+          if (q + AH < NM) fr[q % AH] = load(q + AH);
+          if constexpr (ACT) {
+#pragma unroll
+            for (int pc = q * NP / NM; pc < (q + 1) * NP / NM; ++pc) act_stage(ah[PA], pc / NS, pc % NS, hop[PA][pc / NS]);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        ws.advance();
+        ws.advance();
+      };
+      using std::integral_constant;
+      typedef integral_constant<int, 0> I0; typedef integral_constant<int, 1> I1;
+      typedef integral_constant<bool, true> Yes; typedef integral_constant<bool, false> No;
+      // chunk 0's first GEMM alone
+      ah[0] = bias_tile(vec + vl.b1(), 0, hi);
+      for_frags([&](int sg, const grp w) { ah[0] = E::mma(w, xn[0][sg], ah[0]); });
+      if (PIPE) frag_pipeline_hint<NG, 4>();
+      ws.advance();
+      step(I0{}, Yes{}, No{}, Yes{}, 0);                    // {W1(1), unused}: activation of chunk 0 under chunk 1's first GEMM
+      int i = 1;
+#pragma unroll 1
+      for (; i + 1 <= NC - 2; i += 2) {
+        step(I1{}, Yes{}, Yes{}, Yes{}, i);
+        step(I0{}, Yes{}, Yes{}, Yes{}, i + 1);
+      }
+      // the last pair {W2(NC-2), W2(NC-1)}: second GEMM of chunk NC - 2 under the activation of
+      // chunk NC - 1, then the second GEMM of chunk NC - 1 alone
+      auto last = [&](auto pa_) {
+        constexpr int PA = decltype(pa_)::value;
+        constexpr int AH = 3;
+        grp fr[AH];
+        auto load = [&](int q) -> grp { const int j = q % NG; return ws.template frag_at<grp>(q / NG, (j % NT) * GPT + j / NT); };
+#pragma unroll
+        for (int q = 0; q < AH; ++q) fr[q] = load(q);
+#pragma unroll
+        for (int q = 0; q < 2 * NG; ++q) {
+          __builtin_amdgcn_sched_barrier(0);
+          const int j = q % NG;
+          resid[0][j % NT] = E::mma_h(fr[q % AH], hop[q < NG ? (PA ^ 1) : PA][j / NT], resid[0][j % NT]);
+          if (q + AH < 2 * NG) fr[q % AH] = load(q + AH);
+          if (q < NG) {
+#pragma unroll
+            for (int pc = q * NP / NG; pc < (q + 1) * NP / NG; ++pc) act_stage(ah[PA], pc / NS, pc % NS, hop[PA][pc / NS]);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        ws.advance();
+        ws.advance();
+      };
+      if (i <= NC - 2) {                                    // an odd number of middle steps: chunk NC - 1 is even
+        step(I1{}, Yes{}, Yes{}, Yes{}, i);
+        last(I0{});
+      } else {
+        last(I1{});
+      }
+    } else {
 #pragma unroll 1
     for (int c = 0; c < NC; ++c) {
       f32x16 ah[TT];
@@ -971,8 +1113,8 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
       }
       ws.advance();
     }
+    ws.advance();   // the unused segment that ends the FFN part
     }
-    if (selfl) ws.advance();   // the unused segment behind a fused block in the packed buffer
   }
 
   wait_vmcnt<0>();   // nothing of the weight stream may still be in flight when the wave ends

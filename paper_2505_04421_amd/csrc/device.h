@@ -139,21 +139,47 @@ struct VecLayout {
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Packed parameters of one block travel as "segments" of D/GF fragments (1 KiB each: 64
-// lanes x 16 B).  Two layouts, both in exactly the order a kernel consumes them so that a
-// launch reads one linear stream:
-//   FUSED  [vec][q0 k0 v0 q1 k1 v1 ...][o0 ..][w1(0) w2(0) w1(1) w2(1) ...]      (merge, scoring)
-//   SPLIT  [vec][k0 v0 k1 v1 ...] then [vec][q0 q1 ..][o0 ..][w1(0) w2(0) ...]   (K/V projection, attention)
-// "vec" is one segment holding the block's fp32 vectors (VecLayout), zero padded.
-//   MLP    [vec][w1(0) w2(0) w1(1) w2(1) ...]                                      (input generation: biases b1, b2 only)
+// lanes x 16 B).  Layouts, all in exactly the order a kernel consumes them so that a launch
+// reads one linear stream ("ffn" = the FFN part, see below; "vec" = one segment holding the
+// block's fp32 vectors (VecLayout), zero padded):
+//   FUSED  [vec][q0 k0 v0 q1 k1 v1 ...][o0 ..][ffn]                     (merge, scoring)
+//   SPLIT  [vec][k0 v0 k1 v1 ...] then [vec][q0 q1 ..][o0 ..][ffn]      (K/V projection, attention)
+//   MLP    [vec][ffn]                                (input generation: biases b1, b2 only)
+// The FFN part holds the NC = FF/32 chunk pairs (W1 chunk c: d x 32, W2 chunk c: 32 x d) and one
+// unused segment, 2 NC + 1 in all, in one of two orders:
+//   plain   w1(0) w2(0) w1(1) w2(1) ... w1(NC-1) w2(NC-1) [unused]
+//   skewed  w1(0) w1(1) [unused] {w2(0) w1(2)} {w2(1) w1(3)} ... {w2(NC-3) w1(NC-1)} {w2(NC-2) w2(NC-1)}
+// The skewed order serves the software-pipelined FFN loop (bf16 kernels up to d = 128): iteration
+// i runs the second GEMM of chunk i-1 and the first GEMM of chunk i+1 under the activation of
+// chunk i, so it reads the pair {w2(i-1), w1(i+1)} at once.  The FFN part starts at an odd
+// segment index of every stream (after vec and an even number of projection segments), so the
+// unused segment puts each pair at an even index: both of its segments lie in one panel of the
+// weight stream.
 enum PackLayout { LAYOUT_FUSED = 0, LAYOUT_SPLIT = 1, LAYOUT_MLP = 3 };
-__host__ __device__ inline int mlp_segs(int FF) { return 1 + 2 * (FF / 32); }
+__host__ __device__ constexpr bool ffn_skewed(int es, int D) { return es == 2 && D <= 128; }
+__host__ __device__ inline int ffn_segs(int FF) { return 2 * (FF / 32) + 1; }
+// which matrix chunk sits at index q of the FFN part: kind 5 = W1, 6 = W2, 7 = the unused segment
+__host__ __device__ inline void ffn_seg_decode(int q, int NC, bool skewed, int& kind, int& chunk) {
+  if (!skewed) {
+    if (q == 2 * NC) { kind = 7; chunk = 0; }
+    else { kind = 5 + (q & 1); chunk = q >> 1; }
+    return;
+  }
+  if (q < 2) { kind = 5; chunk = q; return; }
+  if (q == 2) { kind = 7; chunk = 0; return; }
+  const int r = q - 3, i = 1 + r / 2;          // pair of iteration i
+  if ((r & 1) == 0) { kind = 6; chunk = i - 1; }
+  else if (i + 1 < NC) { kind = 5; chunk = i + 1; }
+  else { kind = 6; chunk = NC - 1; }
+}
+__host__ __device__ inline int mlp_segs(int FF) { return 1 + ffn_segs(FF); }
 __host__ __device__ inline size_t packed_seg_bytes(int D, int es) { return (size_t)D * 32 * es; }   // D/GF KiB, GF = 32/es
-__host__ __device__ inline int fused_segs(int D, int FF) { return 1 + 4 * (D / 32) + 2 * (FF / 32); }
+__host__ __device__ inline int fused_segs(int D, int FF) { return 1 + 4 * (D / 32) + ffn_segs(FF); }
 __host__ __device__ inline int kv_segs(int D) { return 1 + 2 * (D / 32); }
-__host__ __device__ inline int attn_segs(int D, int FF) { return 1 + 2 * (D / 32) + 2 * (FF / 32); }
-// room for either layout
+__host__ __device__ inline int attn_segs(int D, int FF) { return 1 + 2 * (D / 32) + ffn_segs(FF); }
+// room for either layout (the split one is the longer)
 __host__ __device__ inline size_t packed_block_bytes(int D, int FF, int es) {
-  return (size_t)(fused_segs(D, FF) + 1) * packed_seg_bytes(D, es);
+  return (size_t)(kv_segs(D) + attn_segs(D, FF)) * packed_seg_bytes(D, es);
 }
 
 enum Mode { MODE_MERGE = 0, MODE_KVPROJ = 1, MODE_ATTN = 2, MODE_SCORE = 3, MODE_STACK = 4, MODE_INPUT = 5, MODE_MERGE_IN = 6 };
@@ -265,6 +291,11 @@ struct WStream {
   template <typename G>
   __device__ __forceinline__ G frag(int f) const {
     return *reinterpret_cast<const G*>(&lds[slot_cur * PANV + sub * SEGV + f * 64 + lane]);
+  }
+  // fragment f of the segment `ahead` places after the current one, which must lie in the same panel
+  template <typename G>
+  __device__ __forceinline__ G frag_at(int ahead, int f) const {
+    return *reinterpret_cast<const G*>(&lds[slot_cur * PANV + (sub + ahead) * SEGV + f * 64 + lane]);
   }
   __device__ __forceinline__ const uint4* cur() const { return &lds[slot_cur * PANV + sub * SEGV]; }
 };

@@ -118,16 +118,17 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
   if (idx >= (long long)nseg * SEGV) return;
   int seg = (int)(idx / SEGV);
   const int within = (int)(idx - (long long)seg * SEGV);
-  // decode the destination segment: kind 0 vec, 1 q, 2 k, 3 v, 4 o, 5 w1, 6 w2; tile/chunk index
+  // decode the destination segment: kind 0 vec, 1 q, 2 k, 3 v, 4 o, 5 w1, 6 w2, 7 unused; tile/chunk index
   int kind, ti;
-  if (layout == LAYOUT_MLP) {          // the input-generation MLP: biases, then (W1 chunk, W2 chunk) pairs
+  const bool skewed = ffn_skewed((int)sizeof(T), D);
+  if (layout == LAYOUT_MLP) {          // the input-generation MLP: biases, then the FFN part
     if (seg == 0) { kind = 0; ti = 0; }
-    else { kind = 5 + ((seg - 1) & 1); ti = (seg - 1) >> 1; }
+    else ffn_seg_decode(seg - 1, NC, skewed, kind, ti);
   } else if (layout == LAYOUT_FUSED) {
     if (seg == 0) { kind = 0; ti = 0; }
     else if (seg <= 3 * NT) { kind = 1 + (seg - 1) % 3; ti = (seg - 1) / 3; }
     else if (seg <= 4 * NT) { kind = 4; ti = seg - 1 - 3 * NT; }
-    else { kind = 5 + ((seg - 1 - 4 * NT) & 1); ti = (seg - 1 - 4 * NT) >> 1; }
+    else ffn_seg_decode(seg - 1 - 4 * NT, NC, skewed, kind, ti);
   } else {
     if (seg < kv_segs(D)) {
       if (seg == 0) { kind = 0; ti = 0; }
@@ -137,8 +138,12 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
       if (seg == 0) { kind = 0; ti = 0; }
       else if (seg <= NT) { kind = 1; ti = seg - 1; }
       else if (seg <= 2 * NT) { kind = 4; ti = seg - 1 - NT; }
-      else { kind = 5 + ((seg - 1 - 2 * NT) & 1); ti = (seg - 1 - 2 * NT) >> 1; }
+      else ffn_seg_decode(seg - 1 - 2 * NT, NC, skewed, kind, ti);
     }
+  }
+  if (kind == 7) {                     // the unused segment of the FFN part
+    reinterpret_cast<uint4*>(dst)[idx] = make_uint4(0u, 0u, 0u, 0u);
+    return;
   }
   if (kind == 0 && layout == LAYOUT_MLP) {
     const VecLayout vl{D, FF};
@@ -285,6 +290,7 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
   s->pb = packed_block_bytes(s->D, s->FF, s->es);
   s->seg = packed_seg_bytes(s->D, s->es);
   if ((size_t)(9 * s->D + s->FF) * 4 > s->seg) return fail(LONGER_ERR_ARG, "ffn_mult=%d too large for d=%d", c->ffn_mult, c->d);
+  if (ffn_skewed(s->es, s->D) && s->FF < 64) return fail(LONGER_ERR_ARG, "ffn_mult * d = %d: the bf16 FFN needs a hidden width of at least 64", s->FF);
   s->main_fn = s->inner_fn = nullptr; s->DH = s->DHi = 0;
   s->Di = c->d;
   if (c->merge == LONGER_MERGE_CONCAT) {
@@ -306,6 +312,8 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
     if (!s->inner_fn) return fail(LONGER_ERR_ARG, "unsupported shape: dtype=%d InnerTrans width=%d inner head width=%d", c->dtype, s->Di, s->DHi);
     if ((size_t)(9 * s->Di + c->ffn_mult * s->Di) * 4 > packed_seg_bytes(s->Di, s->es))
       return fail(LONGER_ERR_ARG, "ffn_mult=%d too large for the InnerTrans width %d", c->ffn_mult, s->Di);
+    if (ffn_skewed(s->es, s->Di) && c->ffn_mult * s->Di < 64)
+      return fail(LONGER_ERR_ARG, "ffn_mult * InnerTrans width = %d: the bf16 FFN needs a hidden width of at least 64", c->ffn_mult * s->Di);
   }
   return 0;
 }
@@ -331,7 +339,7 @@ constexpr int kXcds = 8;
 // every later call; without one, each entry point packs what it needs into the same places of
 // its workspace.
 //   merge stream   [input MLP][InnerTrans blocks, fused layout, back to back]
-//   reduced stack  [cross block, split layout][self blocks, fused layout]   (one stream: the stack kernel)
+//   reduced stack  [cross block, split layout][self blocks, fused layout, back to back]   (one stream: the stack kernel)
 //   per-layer plan [self blocks, split layout]                              (m + k > 128, cache build)
 //   scoring        [cross block, fused][self blocks, fused], back to back
 //   head           fp32 weights and bias
@@ -348,10 +356,11 @@ static PackedLayout packed_layout(const longer_config* c, const Shape& s) {
   pl.inner = o; pl.inner_stride = (size_t)fused_segs(si.D, si.FF) * si.seg;
   o += (size_t)c->inner_layers * pl.inner_stride;
   o = align256(o + 4 * (s.seg > si.seg ? s.seg : si.seg));   // a stream may read whole panels past its end
-  pl.cross = o; o += s.pb;
-  pl.self_fused = o; o += (size_t)c->n_self * s.pb;
+  pl.score_stride = (size_t)fused_segs(s.D, s.FF) * s.seg;
+  pl.cross = o; o += s.pb;                                  // the split layout fills its slot exactly:
+  pl.self_fused = o; o += (size_t)c->n_self * pl.score_stride;   // the stack kernel's stream runs on into these
   pl.self_split = o; o += (size_t)c->n_self * s.pb;
-  pl.score = o; pl.score_stride = (size_t)fused_segs(s.D, s.FF) * s.seg;
+  pl.score = o;
   o += (size_t)(1 + c->n_self) * pl.score_stride + 4 * s.seg;
   pl.head = align256(o); o = pl.head + align256(((size_t)c->m * s.D + 1) * 4);
   pl.total = o;
@@ -560,8 +569,8 @@ static int run_layer(const longer_config* c, const Shape& s, const char* packed_
 
 // The reduced stack of every user in one launch (one workgroup per user): the query side of
 // the cross layer over the K/V fragments that run_layer(.., do_attn = false) stored, then
-// all self layers.  `packed_cross` holds the cross block in the split layout, followed at
-// packed_block_bytes steps by the self blocks in the fused layout.  Needs m + k <= 128.
+// all self layers.  `packed_cross` holds the cross block in the split layout, followed directly
+// by the self blocks in the fused layout, back to back.  Needs m + k <= 128.
 static int run_stack(const longer_config* c, const Shape& s, const char* packed_cross, const int32_t* lens, int B, int L,
                      const AttnIO& io, hipStream_t st) {
   BlockParams p = base_params(c, s, lens, B, L, s.DH);
@@ -605,7 +614,7 @@ static int pack_model(const longer_config* cfg, const Shape& s, const longer_wei
     if (!w->cross || (cfg->n_self > 0 && !w->self)) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
   }
   if ((what & (PK_STACK | PK_LAYERS)) && (rc = pk_main.add(w->cross, 1, LAYOUT_SPLIT, base + pl.cross, s.pb))) return rc;
-  if ((what & PK_STACK) && cfg->n_self && (rc = pk_main.add(w->self, cfg->n_self, LAYOUT_FUSED, base + pl.self_fused, s.pb))) return rc;
+  if ((what & PK_STACK) && cfg->n_self && (rc = pk_main.add(w->self, cfg->n_self, LAYOUT_FUSED, base + pl.self_fused, pl.score_stride))) return rc;
   if ((what & PK_LAYERS) && cfg->n_self && (rc = pk_main.add(w->self, cfg->n_self, LAYOUT_SPLIT, base + pl.self_split, s.pb))) return rc;
   if (what & PK_SCORE) {
     if ((rc = pk_main.add(w->cross, 1, LAYOUT_FUSED, base + pl.score, pl.score_stride))) return rc;

@@ -19,12 +19,21 @@ namespace longer {
 //   mode 7  M in waves 0-3, waves 4-7 leave at once    (one wave per SIMD)
 //   mode 8  M with the idle cycles of mode 4 in all 8 waves
 //   mode 9  as 3 with the M waves at raised priority
+//   mode 10 every wave: each MFMA followed by 4 packed fp16 FMAs    mode 11 packed fp16 FMAs alone (128)
+//   mode 12 every wave: each MFMA followed by 2 packed fp16 FMAs    mode 13 each MFMA followed by 2 v_exp_f32
+//   mode 14 v_exp_f32 alone (128)        mode 15 each MFMA followed by one 16-byte LDS read per lane
+//   mode 16 each MFMA followed by 4 v_cvt_pk_bf16_f32               mode 17 each MFMA followed by 6 FMAs
 __device__ __forceinline__ void mm(f32x16& c, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void ff(float& x, float m, float ad) {
   asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x) : "v"(m), "v"(ad));
 }
+__device__ __forceinline__ void pk(float& x, float m, float ad) {      // two fp16 FMAs per lane
+  asm volatile("v_pk_fma_f16 %0, %0, %1, %2" : "+v"(x) : "v"(m), "v"(ad));
+}
+__device__ __forceinline__ void ex(float& x) { asm volatile("v_exp_f32 %0, %0" : "+v"(x)); }
+__device__ __forceinline__ void cv(float& x, float y) { asm volatile("v_cvt_pk_bf16_f32 %0, %0, %1" : "+v"(x) : "v"(y)); }
 
 template <int MODE>
 __global__ void __launch_bounds__(512, 1) rate_kernel(float* out, int iters) {
@@ -47,6 +56,30 @@ __global__ void __launch_bounds__(512, 1) rate_kernel(float* out, int iters) {
   for (int it = 0; it < iters; ++it) {
     const bool do_m = MODE == 0 || MODE == 2 || MODE == 7 || MODE == 8 || ((MODE == 3 || MODE == 4 || MODE == 9) && first4);
     const bool do_v = MODE == 1 || MODE == 2 || ((MODE == 3 || MODE == 4 || MODE == 9) && !first4);
+    if (MODE >= 10) {
+      __shared__ uint4 lbuf[512];
+      if (MODE == 11 || MODE == 14) {
+#pragma unroll
+        for (int sidx = 0; sidx < 128; ++sidx) { if (MODE == 11) pk(v[sidx & 15], m, ad); else ex(v[sidx & 15]); }
+        continue;
+      }
+#pragma unroll
+      for (int s = 0; s < 16; ++s) {
+        mm(c[s & 3], a, b);
+        if (MODE == 10) { for (int i2 = 0; i2 < 4; ++i2) pk(v[(s * 4 + i2) & 15], m, ad); }
+        if (MODE == 12) { for (int i2 = 0; i2 < 2; ++i2) pk(v[(s * 2 + i2) & 15], m, ad); }
+        if (MODE == 13) { for (int i2 = 0; i2 < 2; ++i2) ex(v[(s * 2 + i2) & 15]); }
+        if (MODE == 15) {     // one 16-byte LDS read per lane and MFMA (the shape of a weight-fragment read)
+          const unsigned addr = (unsigned)(unsigned long long)&lbuf[0] + (unsigned)tid * 16u;
+          u32x4 t;
+          asm volatile("ds_read_b128 %0, %1" : "=v"(t) : "v"(addr));
+          if ((s & 3) == 3) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        if (MODE == 16) { for (int i2 = 0; i2 < 4; ++i2) cv(v[(s * 4 + i2) & 15], ad); }
+        if (MODE == 17) { for (int i2 = 0; i2 < 6; ++i2) ff(v[(s * 6 + i2) & 15], m, ad); }
+      }
+      continue;
+    }
     if (MODE == 5 || MODE == 6) {
 #pragma unroll
       for (int s = 0; s < 16; ++s) {
@@ -82,7 +115,7 @@ __global__ void __launch_bounds__(512, 1) rate_kernel(float* out, int iters) {
 using namespace longer;
 
 extern "C" int longer_probe_rate(int mode, int iters, int workgroups, float* out, void* stream) {
-  if (!out || iters <= 0 || workgroups <= 0 || workgroups > 65536 || mode < 0 || mode > 9) return LONGER_ERR_ARG;
+  if (!out || iters <= 0 || workgroups <= 0 || workgroups > 65536 || mode < 0 || mode > 17) return LONGER_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   const dim3 g(workgroups), t(512);
   switch (mode) {
@@ -95,7 +128,15 @@ extern "C" int longer_probe_rate(int mode, int iters, int workgroups, float* out
     case 6: hipLaunchKernelGGL(rate_kernel<6>, g, t, 0, st, out, iters); break;
     case 7: hipLaunchKernelGGL(rate_kernel<7>, g, t, 0, st, out, iters); break;
     case 8: hipLaunchKernelGGL(rate_kernel<8>, g, t, 0, st, out, iters); break;
-    default: hipLaunchKernelGGL(rate_kernel<9>, g, t, 0, st, out, iters); break;
+    case 9: hipLaunchKernelGGL(rate_kernel<9>, g, t, 0, st, out, iters); break;
+    case 10: hipLaunchKernelGGL(rate_kernel<10>, g, t, 0, st, out, iters); break;
+    case 11: hipLaunchKernelGGL(rate_kernel<11>, g, t, 0, st, out, iters); break;
+    case 12: hipLaunchKernelGGL(rate_kernel<12>, g, t, 0, st, out, iters); break;
+    case 13: hipLaunchKernelGGL(rate_kernel<13>, g, t, 0, st, out, iters); break;
+    case 14: hipLaunchKernelGGL(rate_kernel<14>, g, t, 0, st, out, iters); break;
+    case 15: hipLaunchKernelGGL(rate_kernel<15>, g, t, 0, st, out, iters); break;
+    case 16: hipLaunchKernelGGL(rate_kernel<16>, g, t, 0, st, out, iters); break;
+    default: hipLaunchKernelGGL(rate_kernel<17>, g, t, 0, st, out, iters); break;
   }
   return hipGetLastError() == hipSuccess ? LONGER_OK : LONGER_ERR_HIP;
 }

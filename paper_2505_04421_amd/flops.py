@@ -1,0 +1,67 @@
+"""Algorithmic FLOP counts of the LONGER forward and scoring passes (bookkeeping for the
+benchmark's roofline figures; nothing here runs on the data).
+
+Counted the way Eq. 3 of the paper counts a transformer layer: 2 FLOP per multiply-add of every
+projection / FFN GEMM (24 d^2 per token of a block with a 4d FFN) and 4 d per unmasked query-key
+pair, on valid tokens only.  LayerNorm, softmax, the activation, pooling and the head are not
+counted.
+"""
+from __future__ import annotations
+
+from typing import Optional, Sequence
+
+
+def _slot_tokens(k: int, tu: int, k_uniform: int, q_learnable: bool):
+    """(newest merged token a valid query slot sees) for every valid one of a user's k slots
+    (Section 3.5.1): learnable tokens see all tu tokens; sampled slots hold a token and see the
+    tokens up to it."""
+    if tu <= 0:
+        return []
+    if q_learnable:
+        return [tu - 1] * k
+    out = []
+    for i in range(k):
+        if tu <= k or i >= k_uniform:
+            t = tu - k + i
+        else:
+            rest = tu - (k - k_uniform)
+            t = ((i + 1) * rest) // k_uniform - 1
+        if t >= 0:
+            out.append(t)
+    return out
+
+
+def forward_flops(cfg, lens: Optional[Sequence[int]] = None, B: Optional[int] = None, L: Optional[int] = None) -> dict:
+    """{"inner", "cross", "self_each", "kv_cross", "total"} for one longer_forward call."""
+    B = cfg.B if B is None else B
+    L = cfg.L if L is None else L
+    lens = [L] * B if lens is None else [int(x) for x in lens]
+    d, m, k, K, f = cfg.d, cfg.m, cfg.k_recent, cfg.K, cfg.ffn_mult
+    q_side = (4 + 4 * f) * d * d            # W_Q, W_O and the FFN per query row
+    kv_side = 4 * d * d                     # W_K, W_V per key row
+    di = d // K if getattr(cfg, "merge", "mean") == "concat" else d
+    inner_tok = (8 + 4 * f) * di * di
+    gpairs = m * m if cfg.gmask == "full" else m * (m + 1) // 2
+    inner = cross = selfl = kv_cross = 0
+    for lu in lens:
+        lu = min(max(lu, 0), L)
+        tu = (lu + K - 1) // K
+        full, rem = divmod(lu, K)
+        inner += cfg.inner_layers * (lu * inner_tok + 4 * di * (full * K * K + rem * rem))
+        slots = _slot_tokens(k, tu, getattr(cfg, "k_uniform", 0), getattr(cfg, "q_learnable", False))
+        kv = len(slots)
+        seqpairs = sum(min(t + 1, tu) for t in slots)
+        kv_cross += (m + tu) * kv_side
+        cross += (m + tu) * kv_side + (m + kv) * q_side + 4 * d * (gpairs + m * tu + seqpairs)
+        selfl += (m + kv) * (q_side + kv_side) + 4 * d * (gpairs + m * kv + kv * (kv + 1) // 2)
+    return {"inner": inner, "cross": cross, "self_each": selfl, "kv_cross": kv_cross,
+            "total": inner + cross + cfg.n_self * selfl}
+
+
+def score_flops(cfg, tu: int) -> int:
+    """One candidate scored against a cache with tu valid merged tokens (Section 3.6.3, stage 2)."""
+    d, m, f = cfg.d, cfg.m, cfg.ffn_mult
+    per_row = (8 + 4 * f) * d * d
+    gpairs = m * m if cfg.gmask == "full" else m * (m + 1) // 2
+    kv = len(_slot_tokens(cfg.k_recent, tu, getattr(cfg, "k_uniform", 0), getattr(cfg, "q_learnable", False)))
+    return m * per_row + 4 * d * (gpairs + m * tu) + cfg.n_self * (m * per_row + 4 * d * (gpairs + m * kv))

@@ -170,5 +170,5 @@ def test_static_scoring_argument_checks():
 def test_rate_probe_argument_checks():
     lib = lg.load_library()
     assert lib.longer_probe_rate(0, 10, 4, None, None) == -1
-    assert lib.longer_probe_rate(11, 10, 4, ctypes.c_void_p(4096), None) == -1
+    assert lib.longer_probe_rate(99, 10, 4, ctypes.c_void_p(4096), None) == -1
     assert lib.longer_probe_rate(0, 0, 4, ctypes.c_void_p(4096), None) == -1

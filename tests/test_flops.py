@@ -1,0 +1,30 @@
+"""The benchmark's own FLOP counter (paper_2505_04421_amd.flops) against the oracle's counter, which
+the paper's printed FLOP example pins (tests/test_oracle_pins.py).  No GPU needed."""
+import numpy as np
+
+import longer_synth as synth
+from oracle import longer_oracle as orc
+
+
+def test_benchmark_flop_counter_agrees_with_the_oracle_counter():
+    """The benchmark prices its roofline figures with a counter of its own (the package's flops module,
+    so that the product path never touches the oracle); the two counters are written independently
+    and must agree on every configuration, query strategy and ragged length mix."""
+    from paper_2505_04421_amd import flops
+    rng = np.random.default_rng(77)
+    cases = [(synth.CONFIGS[n], None) for n in ("C1", "C2", "C3", "C5", "P1")]
+    c4 = synth.CONFIGS["C4"]
+    cases.append((c4.replace(B=40), rng.integers(0, 5001, 40)))
+    cases.append((synth.CONFIGS["C3"].replace(B=7, k_uniform=50), rng.integers(0, 2001, 7)))
+    cases.append((synth.CONFIGS["C3"].replace(B=7, k_uniform=100, gmask="causal"), rng.integers(0, 2001, 7)))
+    cases.append((synth.CONFIGS["C3"].replace(B=7, q_learnable=True), np.array([0, 1, 7, 8, 9, 1999, 2000])))
+    cases.append((synth.CONFIGS["C2"].replace(B=5, ffn_mult=2, k_recent=150), np.array([512, 0, 100, 37, 511])))
+    for cfg, lens in cases:
+        a = orc.algorithmic_flops(cfg, lens)
+        b = flops.forward_flops(cfg, lens)
+        for key in ("inner", "cross", "self_each", "total"):
+            assert a[key] == b[key], (cfg.name, key)
+        for tu in (0, 1, cfg.k_recent - 1, cfg.k_recent, cfg.T):
+            assert orc.algorithmic_flops_score(cfg, tu) == flops.score_flops(cfg, tu), (cfg.name, tu)
+    # the K/V share of the cross layer, by hand at the headline shape: (8 + 250) key rows x 4 d^2
+    assert flops.forward_flops(synth.CONFIGS["C3"], B=1)["kv_cross"] == 258 * 4 * 128 * 128

@@ -43,3 +43,13 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_benchmark_touches_the_oracle_only_in_its_cpu_baseline_leg():
+    text = open(os.path.join(ROOT, "bench.py")).read()
+    imports = [m.start() for m in re.finditer(r"from oracle import|import oracle", text)]
+    assert len(imports) == 1
+    leg = text.index("def cpu_oracle_leg(")
+    nxt = text.index("\ndef ", leg + 1)
+    assert leg < imports[0] < nxt
+    assert "orc." not in text[:leg] and "orc." not in text[nxt:]
