@@ -145,6 +145,14 @@ __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size
 //   FUSED  [vec][q0 k0 v0 q1 k1 v1 ...][o0 ..][ffn]                     (merge, scoring)
 //   SPLIT  [vec][k0 v0 k1 v1 ...] then [vec][q0 q1 ..][o0 ..][ffn]      (K/V projection, attention)
 //   MLP    [vec][ffn]                                (input generation: biases b1, b2 only)
+// Pair layouts, for the kernels that give a 32-row tile to a pair of waves which split every GEMM
+// by output tile (even tiles to one wave, odd tiles to the other): the same segments, each
+// consecutive two being one even and one odd tile of the same matrix, after [vec][unused]:
+//   PAIR_FUSED  [vec][unused][q0 q1][k0 k1][v0 v1][q2 q3][k2 k3][v2 v3] ... [o0 o1][o2 o3] ...
+//               [w1(0) w1(1)][w2(0) w2(1)][w1(2) w1(3)][w2(2) w2(3)] ...
+//   PAIR_ATTN   [vec][unused][q0 q1][q2 q3] ... [o0 o1] ... then the FFN part as above
+// (as many segments as FUSED and the attention half of SPLIT; the weight stream's panels hold two
+// segments there, so each panel has one segment of work for either wave).
 // The FFN part holds the NC = FF/32 chunk pairs (W1 chunk c: d x 32, W2 chunk c: 32 x d) and one
 // unused segment, 2 NC + 1 in all, in one of two orders:
 //   plain   w1(0) w2(0) w1(1) w2(1) ... w1(NC-1) w2(NC-1) [unused]
@@ -155,7 +163,7 @@ __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size
 // segment index of every stream (after vec and an even number of projection segments), so the
 // unused segment puts each pair at an even index: both of its segments lie in one panel of the
 // weight stream.
-enum PackLayout { LAYOUT_FUSED = 0, LAYOUT_SPLIT = 1, LAYOUT_MLP = 3 };
+enum PackLayout { LAYOUT_FUSED = 0, LAYOUT_SPLIT = 1, LAYOUT_MLP = 3, LAYOUT_PAIR_FUSED = 4, LAYOUT_PAIR_ATTN = 5 };
 __host__ __device__ constexpr bool ffn_skewed(int es, int D) { return es == 2 && D <= 128; }
 __host__ __device__ inline int ffn_segs(int FF) { return 2 * (FF / 32) + 1; }
 // which matrix chunk sits at index q of the FFN part: kind 5 = W1, 6 = W2, 7 = the unused segment
@@ -232,12 +240,12 @@ __device__ __forceinline__ void wait_vmcnt() {
 // target but may retire out of order with respect to loads.  A mode that stores inside its loop
 // (the K/V projection) sets DRAIN and always waits for zero.  Every other mode stores only after
 // its last advance() and a wait for zero.
-template <int SEGV, int PSEG, int NB, bool DRAIN>
+template <int SEGV, int PSEG, int NB, bool DRAIN, int NTHR = kThreads>
 struct WStream {
   static constexpr int PANV = SEGV * PSEG;              // 16-byte vectors per panel
-  static constexpr int NSTAGE = PANV / kThreads;
+  static constexpr int NSTAGE = PANV / NTHR;
   static constexpr int NPRE = NB - 1;
-  static_assert(PANV % kThreads == 0 && NSTAGE >= 1, "panel must cover all threads");
+  static_assert(PANV % NTHR == 0 && NSTAGE >= 1, "panel must cover all threads");
   uint4* lds;
   const char* gnext;     // the next panel to fetch (wave-uniform); this thread takes the 16 bytes at lane_off
   unsigned lane_off;
@@ -252,8 +260,8 @@ struct WStream {
         // multi-segment panels (d <= 128, two waves per SIMD): scalar base + lane offset keeps the
         // address arithmetic off the VALU (-2.6 % on the merge kernel); the single-segment panels of
         // the one-wave d = 256 kernels were 1 % faster with per-lane 64-bit addresses
-        if (PSEG > 1) gload_lds16(gnext + kThreads * 16 * i, lane_off, dst + kThreads * 16 * i);
-        else gload_lds16(gnext + kThreads * 16 * i + lane_off, dst + kThreads * 16 * i);
+        if (PSEG > 1) gload_lds16(gnext + NTHR * 16 * i, lane_off, dst + NTHR * 16 * i);
+        else gload_lds16(gnext + NTHR * 16 * i + lane_off, dst + NTHR * 16 * i);
       }
       gnext += PANV * 16;
       ++issued;

@@ -1,7 +1,7 @@
 // C ABI of the library (declared in include/longer.h): argument checks, workspace
 // layout, parameter packing and the launch sequence of each entry point.
 #include "../../include/longer.h"
-#include "block_kernel.h"
+#include "pair_kernel.h"
 
 #include <cmath>
 #include <cstdarg>
@@ -9,6 +9,7 @@
 #include <initializer_list>
 #include <mutex>
 #include <cstring>
+#include <cstdlib>
 
 namespace longer {
 
@@ -23,7 +24,26 @@ template <> int launch_block<__bf16, 256, 16>(int, int, int, const BlockParams&,
 template <> int launch_block<float, 32, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_block<float, 64, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 
+template <> int launch_pair<128, 16>(int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_pair<128, 32>(int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_pair<256, 16>(int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_pair<256, 32>(int, int, const BlockParams&, dim3, hipStream_t);
+
 typedef int (*launch_fn)(int, int, int, const BlockParams&, dim3, hipStream_t);
+typedef int (*pair_fn)(int, int, const BlockParams&, dim3, hipStream_t);
+
+// The kernels that give a tile to a pair of waves (pair_kernel.h): bf16, d = 128 / 256.  The
+// environment variable LONGER_DISABLE_PAIR_KERNELS=1 (read once) keeps every launch on the
+// one-wave-per-tile kernels: a measurement aid for comparing the two.
+static pair_fn find_pair(int dtype, int D, int DH) {
+  static const bool off = [] { const char* e = getenv("LONGER_DISABLE_PAIR_KERNELS"); return e && e[0] == '1'; }();
+  if (off || dtype != LONGER_BF16) return nullptr;
+  if (D == 128 && DH == 16) return &launch_pair<128, 16>;
+  if (D == 128 && DH == 32) return &launch_pair<128, 32>;
+  if (D == 256 && DH == 16) return &launch_pair<256, 16>;
+  if (D == 256 && DH == 32) return &launch_pair<256, 32>;
+  return nullptr;
+}
 
 static launch_fn find_launch(int dtype, int D, int DH) {
   if (dtype == LONGER_BF16) {
@@ -113,7 +133,8 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
     return;
   }
   const int NT = D / 32, NC = FF / 32, NG = D / E::GF, SEGV = NG * 64;
-  const int nseg = layout == LAYOUT_FUSED ? fused_segs(D, FF) : layout == LAYOUT_MLP ? mlp_segs(FF) : kv_segs(D) + attn_segs(D, FF);
+  const int nseg = (layout == LAYOUT_FUSED || layout == LAYOUT_PAIR_FUSED) ? fused_segs(D, FF)
+                 : layout == LAYOUT_MLP ? mlp_segs(FF) : layout == LAYOUT_PAIR_ATTN ? attn_segs(D, FF) : kv_segs(D) + attn_segs(D, FF);
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (long long)nseg * SEGV) return;
   int seg = (int)(idx / SEGV);
@@ -121,7 +142,17 @@ __global__ void pack_block_kernel(const PackArgs args, int D, int FF) {
   // decode the destination segment: kind 0 vec, 1 q, 2 k, 3 v, 4 o, 5 w1, 6 w2, 7 unused; tile/chunk index
   int kind, ti;
   const bool skewed = ffn_skewed((int)sizeof(T), D);
-  if (layout == LAYOUT_MLP) {          // the input-generation MLP: biases, then the FFN part
+  if (layout == LAYOUT_PAIR_FUSED || layout == LAYOUT_PAIR_ATTN) {     // two-wave kernels (device.h)
+    const int nqkv = layout == LAYOUT_PAIR_FUSED ? 3 * NT : NT;
+    const int q = seg - 2;
+    if (seg == 0) { kind = 0; ti = 0; }
+    else if (seg == 1) { kind = 7; ti = 0; }
+    else if (q < nqkv) {
+      if (layout == LAYOUT_PAIR_FUSED) { kind = 1 + (q % 6) / 2; ti = 2 * (q / 6) + (q & 1); }
+      else { kind = 1; ti = q; }
+    } else if (q < nqkv + NT) { kind = 4; ti = q - nqkv; }
+    else { const int f = q - nqkv - NT; kind = 5 + (f % 4) / 2; ti = 2 * (f / 4) + (f & 1); }
+  } else if (layout == LAYOUT_MLP) {          // the input-generation MLP: biases, then the FFN part
     if (seg == 0) { kind = 0; ti = 0; }
     else ffn_seg_decode(seg - 1, NC, skewed, kind, ti);
   } else if (layout == LAYOUT_FUSED) {
@@ -266,6 +297,7 @@ struct Shape {
   size_t pb;          // bytes reserved per packed block (either layout)
   size_t seg;         // bytes of one stream segment
   launch_fn main_fn, inner_fn;
+  pair_fn pair;       // the main stack's two-wave kernels, or NULL
 };
 
 static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool need_main) {
@@ -291,7 +323,7 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
   s->seg = packed_seg_bytes(s->D, s->es);
   if ((size_t)(9 * s->D + s->FF) * 4 > s->seg) return fail(LONGER_ERR_ARG, "ffn_mult=%d too large for d=%d", c->ffn_mult, c->d);
   if (ffn_skewed(s->es, s->D) && s->FF < 64) return fail(LONGER_ERR_ARG, "ffn_mult * d = %d: the bf16 FFN needs a hidden width of at least 64", s->FF);
-  s->main_fn = s->inner_fn = nullptr; s->DH = s->DHi = 0;
+  s->main_fn = s->inner_fn = nullptr; s->pair = nullptr; s->DH = s->DHi = 0;
   s->Di = c->d;
   if (c->merge == LONGER_MERGE_CONCAT) {
     if (c->d % c->K || (c->d / c->K) % 32)
@@ -303,6 +335,7 @@ static int check_cfg(const longer_config* c, Shape* s, bool need_inner, bool nee
     s->DH = c->d / c->heads;
     s->main_fn = find_launch(c->dtype, c->d, s->DH);
     if (!s->main_fn) return fail(LONGER_ERR_ARG, "unsupported shape: dtype=%d d=%d head width=%d", c->dtype, c->d, s->DH);
+    s->pair = find_pair(c->dtype, c->d, s->DH);
   }
   if (need_inner) {
     if (c->inner_layers < 1) return fail(LONGER_ERR_ARG, "inner_layers=%d", c->inner_layers);
@@ -339,14 +372,21 @@ constexpr int kXcds = 8;
 // every later call; without one, each entry point packs what it needs into the same places of
 // its workspace.
 //   merge stream   [input MLP][InnerTrans blocks, fused layout, back to back]
-//   reduced stack  [cross block, split layout][self blocks, fused layout, back to back]   (one stream: the stack kernel)
+//   reduced stack  [cross block, split layout]([its attention half, pair layout])[self blocks, fused layout, back to back]
+//                  (one stream: the stack kernel; the two-wave stack kernel starts at the pair copy and
+//                  its self blocks are in the pair layout)
 //   per-layer plan [self blocks, split layout]                              (m + k > 128, cache build)
 //   scoring        [cross block, fused][self blocks, fused], back to back
 //   head           fp32 weights and bias
 struct PackedLayout {
-  size_t mlp, inner, cross, self_fused, self_split, score, head, total;
+  size_t mlp, inner, cross, cross_pair, self_fused, self_split, score, head, total;
   size_t inner_stride, score_stride;
 };
+
+static bool stack_in_one_launch(const Shape& s) { return s.n <= 32 * kWaves; }   // a user's reduced rows fit one workgroup
+// which launches run on the two-wave kernels (their parts of the packed parameters are in the pair layouts)
+static bool pair_stack(const Shape& s) { return s.pair && s.D == 128 && stack_in_one_launch(s); }   // (LDS: the K/V hand-over area fits at d = 128)
+static bool pair_score(const Shape& s) { return s.pair != nullptr; }
 
 static PackedLayout packed_layout(const longer_config* c, const Shape& s) {
   PackedLayout pl;
@@ -358,6 +398,8 @@ static PackedLayout packed_layout(const longer_config* c, const Shape& s) {
   o = align256(o + 4 * (s.seg > si.seg ? s.seg : si.seg));   // a stream may read whole panels past its end
   pl.score_stride = (size_t)fused_segs(s.D, s.FF) * s.seg;
   pl.cross = o; o += s.pb;                                  // the split layout fills its slot exactly:
+  // (two-wave stack kernel: a copy of the cross block's attention half in the pair layout heads the stream)
+  pl.cross_pair = o; if (pair_stack(s)) o += (size_t)attn_segs(s.D, s.FF) * s.seg;
   pl.self_fused = o; o += (size_t)c->n_self * pl.score_stride;   // the stack kernel's stream runs on into these
   pl.self_split = o; o += (size_t)c->n_self * s.pb;
   pl.score = o;
@@ -571,10 +613,10 @@ static int run_layer(const longer_config* c, const Shape& s, const char* packed_
 // the cross layer over the K/V fragments that run_layer(.., do_attn = false) stored, then
 // all self layers.  `packed_cross` holds the cross block in the split layout, followed directly
 // by the self blocks in the fused layout, back to back.  Needs m + k <= 128.
-static int run_stack(const longer_config* c, const Shape& s, const char* packed_cross, const int32_t* lens, int B, int L,
-                     const AttnIO& io, hipStream_t st) {
+static int run_stack(const longer_config* c, const Shape& s, const char* packed_cross, const char* packed_pair,
+                     const int32_t* lens, int B, int L, const AttnIO& io, hipStream_t st) {
   BlockParams p = base_params(c, s, lens, B, L, s.DH);
-  p.wbase = packed_cross + (size_t)kv_segs(s.D) * s.seg;
+  p.wbase = pair_stack(s) ? packed_pair : packed_cross + (size_t)kv_segs(s.D) * s.seg;
   p.n_layers = 1 + c->n_self;
   p.src0 = io.q0src; p.src1 = io.q1src;
   p.rows_per_user = s.n; p.tiles_per_user = kWaves;
@@ -584,7 +626,8 @@ static int run_stack(const longer_config* c, const Shape& s, const char* packed_
   p.X_out = io.X_out; p.X_f32 = io.X_f32; p.X_ustride = io.X_ustride;
   p.logits = io.logits; p.head = io.head;
   StageScope scope(ST_ATTN, st);
-  if (s.main_fn(MODE_STACK, 1, 16, p, dim3(B), st)) return fail(LONGER_ERR_HIP, "stack launch failed");
+  if (pair_stack(s) ? s.pair(MODE_STACK, 16, p, dim3(B), st) : s.main_fn(MODE_STACK, 1, 16, p, dim3(B), st))
+    return fail(LONGER_ERR_HIP, "stack launch failed");
   return 0;
 }
 
@@ -592,8 +635,6 @@ static int run_stack(const longer_config* c, const Shape& s, const char* packed_
 // ------------------------------------------------------------------------------------
 // Packing a model's parameters: which parts an entry point streams
 enum : unsigned { PK_MERGE = 1, PK_STACK = 2, PK_LAYERS = 4, PK_SCORE = 8, PK_HEAD = 16 };
-
-static bool stack_in_one_launch(const Shape& s) { return s.n <= 32 * kWaves; }   // a user's reduced rows fit one workgroup
 
 static int pack_model(const longer_config* cfg, const Shape& s, const longer_weights* w, const longer_input_weights* iw,
                       char* base, unsigned what, hipStream_t st) {
@@ -614,11 +655,14 @@ static int pack_model(const longer_config* cfg, const Shape& s, const longer_wei
     if (!w->cross || (cfg->n_self > 0 && !w->self)) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
   }
   if ((what & (PK_STACK | PK_LAYERS)) && (rc = pk_main.add(w->cross, 1, LAYOUT_SPLIT, base + pl.cross, s.pb))) return rc;
-  if ((what & PK_STACK) && cfg->n_self && (rc = pk_main.add(w->self, cfg->n_self, LAYOUT_FUSED, base + pl.self_fused, pl.score_stride))) return rc;
+  if ((what & PK_STACK) && pair_stack(s) && (rc = pk_main.add(w->cross, 1, LAYOUT_PAIR_ATTN, base + pl.cross_pair, s.pb))) return rc;
+  if ((what & PK_STACK) && cfg->n_self &&
+      (rc = pk_main.add(w->self, cfg->n_self, pair_stack(s) ? LAYOUT_PAIR_FUSED : LAYOUT_FUSED, base + pl.self_fused, pl.score_stride))) return rc;
   if ((what & PK_LAYERS) && cfg->n_self && (rc = pk_main.add(w->self, cfg->n_self, LAYOUT_SPLIT, base + pl.self_split, s.pb))) return rc;
   if (what & PK_SCORE) {
-    if ((rc = pk_main.add(w->cross, 1, LAYOUT_FUSED, base + pl.score, pl.score_stride))) return rc;
-    if (cfg->n_self && (rc = pk_main.add(w->self, cfg->n_self, LAYOUT_FUSED, base + pl.score + pl.score_stride, pl.score_stride))) return rc;
+    const int lay = pair_score(s) ? LAYOUT_PAIR_FUSED : LAYOUT_FUSED;
+    if ((rc = pk_main.add(w->cross, 1, lay, base + pl.score, pl.score_stride))) return rc;
+    if (cfg->n_self && (rc = pk_main.add(w->self, cfg->n_self, lay, base + pl.score + pl.score_stride, pl.score_stride))) return rc;
   }
   if ((what & PK_HEAD) && (rc = pk_main.add_head(w, (float*)(base + pl.head)))) return rc;
   return pk_main.flush();
@@ -850,7 +894,7 @@ static int forward_impl(const longer_config* cfg, const longer_weights* w, const
     AttnIO io = cross_io(cfg, s, l, w8, G, w8 + l.M, 1, B, L, Y_out, 0);
     if (logits_out) { io.logits = logits_out; io.head = head; }
     if ((rc = run_layer(cfg, s, pk_cross, lens, B, L, io, false, st))) return rc;
-    return run_stack(cfg, s, pk_cross, lens, B, L, io, st);
+    return run_stack(cfg, s, pk_cross, pk + pl.cross_pair, lens, B, L, io, st);
   }
   void* xbuf[2] = {w8 + l.xa, w8 + l.xb};
   const bool last0 = cfg->n_self == 0;
@@ -987,7 +1031,8 @@ static int run_score(const longer_config* cfg, const Shape& s, const char* strea
   dim3 grid((unsigned)(kXcds * cdiv(U, kXcds) * p.wg_per_user));
   StageScope scope(ST_SCORE, st);
   const int win = cfg->m <= 8 ? 4 : (cfg->m <= 16 ? 8 : 16);
-  if (s.main_fn(MODE_SCORE, 1, win, p, grid, st)) return fail(LONGER_ERR_HIP, "score kernel launch failed");
+  if (pair_score(s) ? s.pair(MODE_SCORE, win, p, grid, st) : s.main_fn(MODE_SCORE, 1, win, p, grid, st))
+    return fail(LONGER_ERR_HIP, "score kernel launch failed");
   return 0;
 }
 
@@ -1024,8 +1069,9 @@ int longer_score_candidates_static(const longer_config* cfg, const longer_weight
   hipStream_t st = (hipStream_t)stream;
   if (!w->cross || (cfg->n_self > 0 && !w->self)) return fail(LONGER_ERR_ARG, "weights struct has NULL members");
   PackBatch pk(cfg, s, st);
-  if ((rc = pk.add(w->cross, 1, LAYOUT_FUSED, base, stride))) return rc;
-  if (cfg->n_self && (rc = pk.add(w->self, cfg->n_self, LAYOUT_FUSED, base + stride, stride))) return rc;
+  const int lay = pair_score(s) ? LAYOUT_PAIR_FUSED : LAYOUT_FUSED;
+  if ((rc = pk.add(w->cross, 1, lay, base, stride))) return rc;
+  if (cfg->n_self && (rc = pk.add(w->self, cfg->n_self, lay, base + stride, stride))) return rc;
   if (logits_out && (rc = pk.add_head(w, (float*)(base + head_off)))) return rc;
   if ((rc = pk.flush())) return rc;
   return run_score(cfg, s, base, (const float*)(base + head_off), cache, lens, U, L, G_cand, C, Yg_out, logits_out, st);
