@@ -282,6 +282,8 @@ int longer_probe_mfma_layout(int32_t* out, void* stream);
  *   13 every MFMA followed by 2 v_exp_f32         14 v_exp_f32 alone (128)
  *   15 every MFMA followed by one 16-byte LDS read per lane
  *   16 every MFMA followed by 4 fp32 -> bf16 pair conversions    17 every MFMA followed by 6 FMAs
+ *   18-21 (128 instructions alone) packed fp16 FMA with a scalar-register constant / with the clamp
+ *   modifier / packed fp16 multiply / fp32 -> fp16 pair conversion toward zero
  * The caller times the launch (events on `stream`).  out: device, workgroups * 512 floats
  * (a sink that keeps the work alive). */
 int longer_probe_rate(int mode, int iters, int workgroups, float* out, void* stream);

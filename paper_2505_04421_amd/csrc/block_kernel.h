@@ -423,8 +423,12 @@ __device__ __forceinline__ void input_rows(f32x16 (&x)[NT], const BlockParams& p
 // ---------------------------------------------------------------------------- the kernel
 // RELU: the FFN activation (a template parameter: with both activations' loops in one kernel the
 // compiler copies the residual registers in front of one of them)
-template <typename T, int D, int DH, int TT, int MODE, int W, bool RELU>
-__global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE_STACK) ? 2 : 1) block_kernel(const BlockParams p) {
+// NW: waves (= tiles) per workgroup.  (One workgroup of 8 waves per compute unit instead of two of 4
+// was measured for the d = 128 merge kernels, so that the two waves of a SIMD move through the
+// block's phases together: 0.475-0.482 against 0.473-0.476 ms on one box, not kept.)
+template <typename T, int D, int DH, int TT, int MODE, int W, bool RELU, int NW = kWaves>
+__global__ void __launch_bounds__(64 * NW, (NW == kWaves && D <= 128 && TT == 1 && MODE != MODE_STACK) ? 2 : 1) block_kernel(const BlockParams p) {
+  constexpr int kThreads = 64 * NW, kWaves = NW;   // (shadow the namespace-wide defaults)
   using E = ET<T>;
   using grp = typename E::grp;
   constexpr int NT = D / 32, NG = D / E::GF, GPT = E::GPT;
@@ -604,7 +608,7 @@ __global__ void __launch_bounds__(kThreads, (D <= 128 && TT == 1 && MODE != MODE
     }
   }
 
-  WStream<SEGV, PSEG, NB, MODE == MODE_KVPROJ> ws;
+  WStream<SEGV, PSEG, NB, MODE == MODE_KVPROJ, kThreads> ws;
   const int NF = 2 * NC + 1;     // segments of a block's FFN part (device.h)
   const int steps = 1 + (MODE == MODE_KVPROJ ? 2 * NT : MODE == MODE_INPUT ? NF : (ATTNLIKE ? 2 * NT + NF : 4 * NT + NF));
   // MODE_STACK: the cross block's attention sub-stream, then the self blocks in the fused
@@ -1198,10 +1202,11 @@ int launch_block(int mode, int tt, int win, const BlockParams& p, dim3 grid, hip
 
 #define LONGER_LAUNCH(T, D, DH, TTV, MODEV, WV) \
   do {                                                                                                \
+    constexpr int NWV = kWaves;                                                                       \
     if (p.act == 1 && MODEV != MODE_KVPROJ)                                                           \
-      hipLaunchKernelGGL((block_kernel<T, D, DH, TTV, MODEV, WV, MODEV != MODE_KVPROJ>), grid, dim3(kThreads), 0, stream, p); \
+      hipLaunchKernelGGL((block_kernel<T, D, DH, TTV, MODEV, WV, MODEV != MODE_KVPROJ, NWV>), grid, dim3(64 * NWV), 0, stream, p); \
     else                                                                                              \
-      hipLaunchKernelGGL((block_kernel<T, D, DH, TTV, MODEV, WV, false>), grid, dim3(kThreads), 0, stream, p); \
+      hipLaunchKernelGGL((block_kernel<T, D, DH, TTV, MODEV, WV, false, NWV>), grid, dim3(64 * NWV), 0, stream, p); \
   } while (0)
 
 #define LONGER_INSTANTIATE(T, D, DH)                                                                  \

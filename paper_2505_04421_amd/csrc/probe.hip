@@ -23,6 +23,8 @@ namespace longer {
 //   mode 12 every wave: each MFMA followed by 2 packed fp16 FMAs    mode 13 each MFMA followed by 2 v_exp_f32
 //   mode 14 v_exp_f32 alone (128)        mode 15 each MFMA followed by one 16-byte LDS read per lane
 //   mode 16 each MFMA followed by 4 v_cvt_pk_bf16_f32               mode 17 each MFMA followed by 6 FMAs
+//   modes 18-21, 128 instructions alone: packed fp16 FMA with a scalar-register constant / with the
+//   clamp modifier and an inline constant / packed fp16 multiply / v_cvt_pkrtz_f16_f32
 __device__ __forceinline__ void mm(f32x16& c, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
 }
@@ -32,6 +34,14 @@ __device__ __forceinline__ void ff(float& x, float m, float ad) {
 __device__ __forceinline__ void pk(float& x, float m, float ad) {      // two fp16 FMAs per lane
   asm volatile("v_pk_fma_f16 %0, %0, %1, %2" : "+v"(x) : "v"(m), "v"(ad));
 }
+__device__ __forceinline__ void pks(float& x, float m) {               // with a scalar-register constant, low half broadcast
+  asm volatile("v_pk_fma_f16 %0, %0, %1, s8 op_sel_hi:[1,1,0]" : "+v"(x) : "v"(m));
+}
+__device__ __forceinline__ void pkc(float& x, float m) {               // with the clamp modifier and an inline constant
+  asm volatile("v_pk_fma_f16 %0, %0, %1, 0.5 op_sel_hi:[1,1,0] clamp" : "+v"(x) : "v"(m));
+}
+__device__ __forceinline__ void pkm(float& x, float m) { asm volatile("v_pk_mul_f16 %0, %0, %1" : "+v"(x) : "v"(m)); }
+__device__ __forceinline__ void rtz(float& x, float y) { asm volatile("v_cvt_pkrtz_f16_f32 %0, %0, %1" : "+v"(x) : "v"(y)); }
 __device__ __forceinline__ void ex(float& x) { asm volatile("v_exp_f32 %0, %0" : "+v"(x)); }
 __device__ __forceinline__ void cv(float& x, float y) { asm volatile("v_cvt_pk_bf16_f32 %0, %0, %1" : "+v"(x) : "v"(y)); }
 
@@ -58,9 +68,16 @@ __global__ void __launch_bounds__(512, 1) rate_kernel(float* out, int iters) {
     const bool do_v = MODE == 1 || MODE == 2 || ((MODE == 3 || MODE == 4 || MODE == 9) && !first4);
     if (MODE >= 10) {
       __shared__ uint4 lbuf[512];
-      if (MODE == 11 || MODE == 14) {
+      if (MODE == 11 || MODE == 14 || MODE >= 18) {
 #pragma unroll
-        for (int sidx = 0; sidx < 128; ++sidx) { if (MODE == 11) pk(v[sidx & 15], m, ad); else ex(v[sidx & 15]); }
+        for (int sidx = 0; sidx < 128; ++sidx) {
+          if (MODE == 11) pk(v[sidx & 15], m, ad);
+          else if (MODE == 14) ex(v[sidx & 15]);
+          else if (MODE == 18) pks(v[sidx & 15], m);
+          else if (MODE == 19) pkc(v[sidx & 15], m);
+          else if (MODE == 20) pkm(v[sidx & 15], m);
+          else rtz(v[sidx & 15], ad);
+        }
         continue;
       }
 #pragma unroll
@@ -115,7 +132,7 @@ __global__ void __launch_bounds__(512, 1) rate_kernel(float* out, int iters) {
 using namespace longer;
 
 extern "C" int longer_probe_rate(int mode, int iters, int workgroups, float* out, void* stream) {
-  if (!out || iters <= 0 || workgroups <= 0 || workgroups > 65536 || mode < 0 || mode > 17) return LONGER_ERR_ARG;
+  if (!out || iters <= 0 || workgroups <= 0 || workgroups > 65536 || mode < 0 || mode > 21) return LONGER_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   const dim3 g(workgroups), t(512);
   switch (mode) {
@@ -136,7 +153,11 @@ extern "C" int longer_probe_rate(int mode, int iters, int workgroups, float* out
     case 14: hipLaunchKernelGGL(rate_kernel<14>, g, t, 0, st, out, iters); break;
     case 15: hipLaunchKernelGGL(rate_kernel<15>, g, t, 0, st, out, iters); break;
     case 16: hipLaunchKernelGGL(rate_kernel<16>, g, t, 0, st, out, iters); break;
-    default: hipLaunchKernelGGL(rate_kernel<17>, g, t, 0, st, out, iters); break;
+    case 17: hipLaunchKernelGGL(rate_kernel<17>, g, t, 0, st, out, iters); break;
+    case 18: hipLaunchKernelGGL(rate_kernel<18>, g, t, 0, st, out, iters); break;
+    case 19: hipLaunchKernelGGL(rate_kernel<19>, g, t, 0, st, out, iters); break;
+    case 20: hipLaunchKernelGGL(rate_kernel<20>, g, t, 0, st, out, iters); break;
+    default: hipLaunchKernelGGL(rate_kernel<21>, g, t, 0, st, out, iters); break;
   }
   return hipGetLastError() == hipSuccess ? LONGER_OK : LONGER_ERR_HIP;
 }
