@@ -80,14 +80,13 @@ def cpu_oracle_leg(cfg, case_full, gpu_Y, seconds_target):
     return out
 
 
-def probe_rates(lg, torch):
+def probe_rates(lg, torch, modes=None, iters=2000):
     """Instruction-rate probes of the library: ns per iteration (per SIMD: the MFMA modes issue 16
     MFMAs per wave, the VALU modes 128 FMAs per wave) and the MFMA rate of mode 0."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     sink = torch.zeros(cus * 512, device="cuda")
-    iters = 2000
     res = {}
-    for mode, name in PROBE_MODES.items():
+    for mode, name in (modes or PROBE_MODES).items():
         lg.longer_probe_rate(mode, 50, cus, sink)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -296,6 +295,9 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the other forward configurations (all_configs)")
     ap.add_argument("--no-probe", action="store_true", help="skip the instruction-rate probes")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP graph replay measurement (profiler runs)")
+    ap.add_argument("--probe-all", action="store_true",
+                    help="run every mode of the instruction-rate probe (include/longer.h lists them), print "
+                         "{mode: ns per iteration} as one JSON line and exit")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known HBM traffic that "
                          "calibrates the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -330,6 +332,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.probe_all:
+        modes = {0: PROBE_MODES[0]}
+        modes.update({m: "mode_%d" % m for m in range(1, 22)})
+        micro, attainable = probe_rates(lg, torch, modes, iters=4000)
+        micro["attainable_mfma_tflops"] = attainable
+        print(json.dumps(micro))
+        return
     micro, attainable = (None, None)
     if not args.no_probe:
         micro, attainable = probe_rates(lg, torch)
