@@ -248,6 +248,34 @@ int longer_score_candidates_static(const longer_config* cfg, const longer_weight
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* longer_last_error(void);
 
+/* Backward pass of the token merge (Section 3.4) under the training set-up of Section 3.6.2:
+ * activation recomputation (nothing is kept from a forward call: the pass reads the raw tokens,
+ * recomputes the chain of InnerTrans block inputs, then, block by block from the last to the
+ * first, the block's intermediates) and mixed precision (bf16 matrix-core operands and stored
+ * activations, fp32 accumulation, residual stream, LayerNorm / softmax statistics and parameter
+ * gradients).  The function differentiated is longer_token_merge with exact-erf GELU (or ReLU).
+ *   H [B, L, w] raw tokens and the InnerTrans blocks `inner` as for longer_token_merge, in bf16
+ *     (cfg->dtype must be LONGER_BF16); w = d, or d / K for LONGER_MERGE_CONCAT;
+ *   dM [B, T, d] fp32: gradient of the loss (Eq. 2) with respect to the merged tokens; entries of
+ *     merged tokens past T_u, and of the slots of padded tokens in a concatenated token, are ignored;
+ *   dH_out [B, L, w] fp32: gradient with respect to the raw tokens, exact zeros for padded tokens;
+ *   grads_out fp32 [inner_layers][longer_block_grad_floats(cfg)]: gradient of every parameter of every
+ *     InnerTrans block, dense, in the order and with the shapes of the longer_block members
+ *     (ln1_g [w], ln1_b [w], wq [w, w], bq [w], wk, bk, wv, bv, wo, bo, ln2_g, ln2_b, w1 [w, f], b1 [f],
+ *     w2 [f, w], b2 [w], f = ffn_mult * w), summed over all users of the batch; overwritten, not
+ *     accumulated into.
+ * ws: device scratch of at least longer_backward_workspace_bytes(cfg, B, L), 256-byte aligned; all
+ * pointers (parameters included) 16-byte aligned.  Supports head width 16 or 32, w a multiple of 32
+ * up to 512, f <= 2048.  Parameter gradients are accumulated with fp32 atomics, so their last bits
+ * depend on the order in which workgroups finish.  Same stream, error and ownership rules as the
+ * forward entry points; returns 0 from both size queries for an unsupported configuration. */
+size_t longer_backward_workspace_bytes(const longer_config* cfg, int B, int L);
+size_t longer_block_grad_floats(const longer_config* cfg);
+int longer_token_merge_backward(const longer_config* cfg, const longer_block* inner, const void* H,
+                                const int32_t* lens, int B, int L, const float* dM,
+                                float* dH_out, float* grads_out,
+                                void* ws, size_t ws_bytes, void* stream);
+
 /* Measurement aid: when enabled, every kernel launch group of the entry points is bracketed
  * by a pair of HIP events recorded on the caller's stream (at most 4096 pairs between two
  * reads; later launches go unrecorded).  enable = 0: off; 1: every stage; any other value:

@@ -26,7 +26,7 @@ Conventions
 from __future__ import annotations
 
 import dataclasses
-from typing import Dict, List, Optional
+from typing import Dict, List, Optional, Sequence
 
 import numpy as np
 
@@ -271,3 +271,16 @@ def tiny_config(**kw) -> Config:
                 inner_layers=1, inner_heads=2, dtype="f32")
     base.update(kw)
     return Config(**base)
+
+
+def draw_merge_gradient(cfg: Config, seed_offset: int = 7000, users: Optional[Sequence[int]] = None) -> np.ndarray:
+    """Upstream gradient dM [B, T, d] (fp32, N(0, 1)) for the backward pass of the token merge: what the
+    loss would hand back for the merged tokens.  ``users``: only these users get a non-zero gradient
+    (the parameter gradients of a batch are then those of the chosen users alone)."""
+    rng = np.random.default_rng(2505_04421 + 7919 * cfg.index + seed_offset)
+    dM = rng.standard_normal((cfg.B, cfg.T, cfg.d)).astype(np.float32)
+    if users is not None:
+        keep = np.zeros(cfg.B, dtype=bool)
+        keep[list(users)] = True
+        dM[~keep] = 0.0
+    return dM

@@ -14,4 +14,5 @@ from .binding import (  # noqa: F401
     longer_score_candidates, longer_input_generation, longer_forward_from_inputs, longer_kv_cache_build_from_inputs, CInputWeights, longer_probe_mfma_layout, longer_last_error,
     longer_stage_timing, longer_stage_timing_read, STAGES,
     longer_packed_weights_bytes, longer_pack_weights, longer_score_candidates_static, longer_probe_rate, CWeights,
+    longer_backward_workspace_bytes, longer_block_grad_floats, longer_token_merge_backward, block_grad_views,
 )

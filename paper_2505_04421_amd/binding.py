@@ -16,7 +16,8 @@ ENTRY_POINTS = ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_inner
                 "longer_forward_from_inputs", "longer_kv_cache_build_from_inputs",
                 "longer_last_error", "longer_probe_mfma_layout", "longer_stage_timing",
                 "longer_stage_timing_read", "longer_packed_weights_bytes", "longer_pack_weights",
-                "longer_score_candidates_static", "longer_probe_rate")
+                "longer_score_candidates_static", "longer_probe_rate",
+                "longer_backward_workspace_bytes", "longer_block_grad_floats", "longer_token_merge_backward")
 
 
 class LongerError(RuntimeError):
@@ -83,12 +84,18 @@ def load_library() -> ctypes.CDLL:
     lib.longer_pack_weights.argtypes = [cfgp, wp, ctypes.POINTER(CInputWeights), vp, sz, vp]
     lib.longer_score_candidates_static.argtypes = [cfgp, wp, vp, vp, i32, i32, vp, i32, vp, vp, vp]
     lib.longer_probe_rate.argtypes = [i32, i32, i32, vp, vp]
+    lib.longer_backward_workspace_bytes.restype = sz
+    lib.longer_backward_workspace_bytes.argtypes = [cfgp, i32, i32]
+    lib.longer_block_grad_floats.restype = sz
+    lib.longer_block_grad_floats.argtypes = [cfgp]
+    lib.longer_token_merge_backward.argtypes = [cfgp, blkp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.longer_last_error.restype = ctypes.c_char_p
     lib.longer_probe_mfma_layout.argtypes = [vp, vp]
     lib.longer_stage_timing.argtypes = [i32]
     lib.longer_stage_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     for name in ENTRY_POINTS:
-        if name not in ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_packed_weights_bytes", "longer_last_error"):
+        if name not in ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_packed_weights_bytes", "longer_last_error",
+                        "longer_backward_workspace_bytes", "longer_block_grad_floats"):
             getattr(lib, name).restype = ctypes.c_int
     _LIB = lib
     return lib
@@ -315,6 +322,41 @@ def longer_kv_cache_build_from_inputs(ccfg, weights, iweights, E, tdiff, d_e, le
                                                             _ptr(E), _ptr(tdiff), d_e, _ptr(lens), U, L, _ptr(cache),
                                                             _ptr(ws), ws.numel(), _stream(stream)),
            "longer_kv_cache_build_from_inputs")
+
+
+def longer_backward_workspace_bytes(ccfg: CConfig, B: int, L: int) -> int:
+    return int(load_library().longer_backward_workspace_bytes(ctypes.byref(ccfg), B, L))
+
+
+def longer_block_grad_floats(ccfg: CConfig) -> int:
+    return int(load_library().longer_block_grad_floats(ctypes.byref(ccfg)))
+
+
+def block_grad_views(cfg, grads):
+    """Split the flat fp32 gradient buffer of longer_token_merge_backward into one
+    {parameter: tensor view} per InnerTrans block (the order and shapes of the longer_block members)."""
+    d = cfg.d // cfg.K if getattr(cfg, "merge", "mean") == "concat" else cfg.d
+    f = cfg.ffn_mult * d
+    shapes = {"ln1_g": (d,), "ln1_b": (d,), "wq": (d, d), "bq": (d,), "wk": (d, d), "bk": (d,), "wv": (d, d), "bv": (d,),
+              "wo": (d, d), "bo": (d,), "ln2_g": (d,), "ln2_b": (d,), "w1": (d, f), "b1": (f,), "w2": (f, d), "b2": (d,)}
+    out, o = [], 0
+    for _ in range(cfg.inner_layers):
+        views = {}
+        for name in BLOCK_FIELDS:
+            n = 1
+            for e in shapes[name]:
+                n *= e
+            views[name] = grads[o:o + n].view(*shapes[name])
+            o += n
+        out.append(views)
+    return out
+
+
+def longer_token_merge_backward(ccfg, inner, H, lens, B, L, dM, dH_out, grads_out, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_token_merge_backward(ctypes.byref(ccfg), inner, _ptr(H), _ptr(lens), B, L, _ptr(dM),
+                                                      _ptr(dH_out), _ptr(grads_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "longer_token_merge_backward")
 
 
 def longer_probe_mfma_layout(out, stream=None):

@@ -1,0 +1,861 @@
+// Backward pass of the token merge (Section 3.4) with activation recomputation and mixed
+// precision (Section 3.6.2): longer_token_merge_backward and its size queries.
+//
+// Nothing is kept from a forward call: the pass reads the raw tokens H, recomputes the chain of
+// block inputs (fp32), then walks the InnerTrans blocks from the last to the first; for each
+// block it recomputes the block's intermediates from the block's input and takes the
+// gradients.  Precision policy: every GEMM runs on the matrix cores with bf16 operands and
+// fp32 accumulation; the residual stream, its gradient, LayerNorm and softmax statistics and
+// every parameter gradient are fp32; activations and activation gradients between two GEMMs
+// are stored as bf16.
+//
+// Unlike the forward kernels this pass is not fused per tile: a parameter gradient is a sum
+// over every token of the batch, i.e. a GEMM whose contraction runs over the tokens, so the
+// activations it contracts have to exist for the whole batch.  They are row-major
+// [token, feature] tensors in the workspace, and three kinds of kernels work on them:
+//   * one bf16 MFMA GEMM (bw_gemm_kernel) whose operands may each be stored with the
+//     contraction index contiguous or strided, which covers y = x W (+ epilogues),
+//     dx = dy W^T and dW = x^T dy (split over the tokens, fp32 atomic accumulation);
+//   * row kernels: LayerNorm forward / backward (+ gain / shift gradients), pooling backward,
+//     column sums (bias gradients);
+//   * the attention inside a group of K tokens, forward and backward, one thread per
+//     (token, head): the groups are tiny (K x K scores per head), so this is plain fp32 code.
+#include "../../include/longer.h"
+#include "device.h"
+
+#include <cstdio>
+
+namespace longer {
+
+int api_error(int code, const char* fmt, ...);   // longer_api.hip
+
+namespace bw {
+
+constexpr int kMaxGroup = 32;   // K <= 32
+
+// ------------------------------------------------------------------------------------
+// GEMM  C[M, N] = A[M, Kc] B[Kc, N]  (bf16 operands, fp32 accumulation)
+//   A_KC: A is stored [M][Kc] (contraction contiguous), else [Kc][M];
+//   B_KC: B is stored [N][Kc] (contraction contiguous), else [Kc][N].
+// Workgroup tile 128 x 128, contraction step 32, four waves in 2 x 2, each 64 x 64 (2 x 2 MFMA
+// tiles of 32 x 32).  Requirements checked by the host: strides multiples of 8 elements,
+// 16-byte aligned bases; a contiguous contraction dimension is a multiple of 32; the
+// non-contracted extent of a strided operand is a multiple of 8.  Rows / columns / contraction
+// slices past the extents read as zeros.
+enum Epilogue {
+  EPI_BF16 = 0,      // out[m][n] = bf16(acc + bias[n])
+  EPI_RES_F32 = 1,   // outf[m][n] = res[m][n] + acc + bias[n]
+  EPI_ACT = 2,       // out[m][n] = bf16(v), out2[m][n] = bf16(act(v)), v = acc + bias[n]
+  EPI_DACT = 3,      // out[m][n] = bf16(acc * act'(pre[m][n]))
+  EPI_ATOMIC = 4     // outf[m][n] += acc   (fp32 atomics; blockIdx.z = slice of the contraction)
+};
+
+struct GemmArgs {
+  const __bf16* A; const __bf16* B;
+  int lda, ldb;
+  int M, N, Kc;
+  int kslice;                 // contraction range of one blockIdx.z (multiple of 32)
+  int epi, act;
+  void* out; void* out2; int ldo;
+  const __bf16* bias; const float* res; const __bf16* pre;
+};
+
+__device__ __forceinline__ float act_fwd(float v, int act) {
+  if (act == LONGER_ACT_RELU) return v > 0.f ? v : 0.f;
+  return 0.5f * v * (1.f + erff(v * 0.70710678118654752f));
+}
+__device__ __forceinline__ float act_grad(float v, int act) {
+  if (act == LONGER_ACT_RELU) return v > 0.f ? 1.f : 0.f;
+  return 0.5f * (1.f + erff(v * 0.70710678118654752f)) + v * 0.39894228040143268f * __expf(-0.5f * v * v);
+}
+
+constexpr int kPitchKC = 40;            // elements per row of a contraction-contiguous LDS tile (32 + 8 pad)
+constexpr int kTileElems = 128 * kPitchKC;   // >= 32 * 128 of the strided form
+
+template <bool A_KC, bool B_KC>
+__global__ __launch_bounds__(256) void bw_gemm_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) __bf16 sA[2][kTileElems];
+  __shared__ __attribute__((aligned(16))) __bf16 sB[2][kTileElems];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int wm = w & 1, wn = w >> 1, hi = lane >> 5, l32 = lane & 31;
+  const int m0 = blockIdx.x * 128, n0 = blockIdx.y * 128;
+  const int kbeg = blockIdx.z * g.kslice;
+  const int kend = min(g.Kc, kbeg + g.kslice);
+  const int nk = kend > kbeg ? (kend - kbeg + 31) / 32 : 0;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  bf16x8 ra[2], rb[2];
+  // one operand tile = 512 chunks of 16 bytes, two per thread
+  auto gload = [&](int kt) {
+    const int k0 = kbeg + kt * 32;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = tid + 256 * i;
+      bf16x8 z;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.f;
+      ra[i] = z; rb[i] = z;
+      if (A_KC) {
+        const int row = c >> 2, kc = c & 3;
+        const int gr = m0 + row, gk = k0 + 8 * kc;
+        if (gr < g.M && gk < kend) ra[i] = *(const bf16x8*)(g.A + (size_t)gr * g.lda + gk);
+      } else {
+        const int kr = c >> 4, xc = c & 15;
+        const int gk = k0 + kr, gx = m0 + 8 * xc;
+        if (gk < kend && gx < g.M) ra[i] = *(const bf16x8*)(g.A + (size_t)gk * g.lda + gx);
+      }
+      if (B_KC) {
+        const int row = c >> 2, kc = c & 3;
+        const int gr = n0 + row, gk = k0 + 8 * kc;
+        if (gr < g.N && gk < kend) rb[i] = *(const bf16x8*)(g.B + (size_t)gr * g.ldb + gk);
+      } else {
+        const int kr = c >> 4, xc = c & 15;
+        const int gk = k0 + kr, gx = n0 + 8 * xc;
+        if (gk < kend && gx < g.N) rb[i] = *(const bf16x8*)(g.B + (size_t)gk * g.ldb + gx);
+      }
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = tid + 256 * i;
+      if (A_KC) *(bf16x8*)&sA[buf][(c >> 2) * kPitchKC + 8 * (c & 3)] = ra[i];
+      else      *(bf16x8*)&sA[buf][(c >> 4) * 128 + 8 * (c & 15)] = ra[i];
+      if (B_KC) *(bf16x8*)&sB[buf][(c >> 2) * kPitchKC + 8 * (c & 3)] = rb[i];
+      else      *(bf16x8*)&sB[buf][(c >> 4) * 128 + 8 * (c & 15)] = rb[i];
+    }
+  };
+  // fragment of the 32 x 16 operand slice: lane (x = l32, hi) holds contraction slots 8 hi .. 8 hi + 7
+  auto frag = [&](const __bf16* s, bool kc, int x, int ks) -> bf16x8 {
+    bf16x8 f;
+    if (kc) {
+      f = *(const bf16x8*)&s[x * kPitchKC + 16 * ks + 8 * hi];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = s[(16 * ks + 8 * hi + e) * 128 + x];
+    }
+    return f;
+  };
+
+  if (nk > 0) {
+    gload(0);
+    sstore(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) gload(kt + 1);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        fa[t] = frag(sA[buf], A_KC, 64 * wm + 32 * t + l32, ks);
+        fb[t] = frag(sB[buf], B_KC, 64 * wn + 32 * t + l32, ks);
+      }
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+    }
+    if (kt + 1 < nk) sstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: acc[a][b][r] = C[m0 + 64 wm + 32 a + tile_row(r, hi)][n0 + 64 wn + 32 b + l32]
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const int n = n0 + 64 * wn + 32 * b + l32;
+    if (n >= g.N) continue;
+    const float bias = g.bias ? (float)g.bias[n] : 0.f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + 64 * wm + 32 * a + tile_row(r, hi);
+        if (m >= g.M) continue;
+        const size_t o = (size_t)m * g.ldo + n;
+        const float v = acc[a][b][r] + bias;
+        switch (g.epi) {
+          case EPI_BF16: ((__bf16*)g.out)[o] = (__bf16)v; break;
+          case EPI_RES_F32: ((float*)g.out)[o] = g.res[o] + v; break;
+          case EPI_ACT:
+            ((__bf16*)g.out)[o] = (__bf16)v;
+            ((__bf16*)g.out2)[o] = (__bf16)act_fwd(v, g.act);
+            break;
+          case EPI_DACT: ((__bf16*)g.out)[o] = (__bf16)(v * act_grad((float)g.pre[o], g.act)); break;
+          default: if (nk > 0) unsafeAtomicAdd((float*)g.out + o, v); break;
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Row kernels.  A token row r = u L + pos is valid when pos < min(lens[u], L).
+struct RowGeom { const int32_t* lens; int L, K, ntok; };
+
+__device__ __forceinline__ int row_len(const RowGeom& q, int u) {
+  int l = q.lens ? q.lens[u] : q.L;
+  return l < 0 ? 0 : (l > q.L ? q.L : l);
+}
+
+// x0[r][:] = valid ? H[r][:] : 0   (fp32 copy of the raw tokens: the first block's input)
+__global__ __launch_bounds__(256) void bw_load_x0_kernel(const __bf16* H, float* x0, RowGeom q, int d) {
+  const size_t n = (size_t)q.ntok * d;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const int r = (int)(i / d);
+    const int u = r / q.L, pos = r - u * q.L;
+    x0[i] = pos < row_len(q, u) ? (float)H[i] : 0.f;
+  }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+constexpr int kMaxPerLane = 8;   // widths up to 512
+
+// n[r][:] = bf16(LN(x[r][:]) g + b): one wave per row, lane e holds features e, e + 64, ...
+__global__ __launch_bounds__(256) void bw_ln_fwd_kernel(const float* x, const __bf16* gam, const __bf16* bet,
+                                                        __bf16* out, int ntok, int d, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), nw = gridDim.x * 4;
+  float gv[kMaxPerLane], bv[kMaxPerLane];
+#pragma unroll
+  for (int i = 0; i < kMaxPerLane; ++i) {
+    const int e = lane + 64 * i;
+    gv[i] = e < d ? (float)gam[e] : 0.f;
+    bv[i] = e < d ? (float)bet[e] : 0.f;
+  }
+  for (int r = wave; r < ntok; r += nw) {
+    float v[kMaxPerLane], s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxPerLane; ++i) {
+      const int e = lane + 64 * i;
+      v[i] = e < d ? x[(size_t)r * d + e] : 0.f;
+      s += v[i];
+    }
+    const float mean = wave_sum(s) / d;
+    float s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxPerLane; ++i) {
+      const int e = lane + 64 * i;
+      const float c = e < d ? v[i] - mean : 0.f;
+      s2 += c * c;
+    }
+    const float rstd = 1.f / sqrtf(wave_sum(s2) / d + eps);
+#pragma unroll
+    for (int i = 0; i < kMaxPerLane; ++i) {
+      const int e = lane + 64 * i;
+      if (e < d) out[(size_t)r * d + e] = (__bf16)((v[i] - mean) * rstd * gv[i] + bv[i]);
+    }
+  }
+}
+
+// LayerNorm backward for y = LN(x) g + b with upstream dn = dL/dy (bf16) and the gradient dres that
+// reaches x through the residual connection: dx_out = dres + dLN, also stored as bf16 (dxb, may be
+// NULL); dg[e] += sum_r dn xhat, db[e] += sum_r dn (fp32 atomics, one per wave and feature).
+__global__ __launch_bounds__(256) void bw_ln_bwd_kernel(const __bf16* dn, const float* x, const __bf16* gam,
+                                                        const float* dres, float* dx_out, __bf16* dxb,
+                                                        float* dg, float* db, int ntok, int d, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), nw = gridDim.x * 4;
+  float gv[kMaxPerLane], ag[kMaxPerLane], ab[kMaxPerLane];
+#pragma unroll
+  for (int i = 0; i < kMaxPerLane; ++i) {
+    const int e = lane + 64 * i;
+    gv[i] = e < d ? (float)gam[e] : 0.f;
+    ag[i] = 0.f; ab[i] = 0.f;
+  }
+  for (int r = wave; r < ntok; r += nw) {
+    float v[kMaxPerLane], t[kMaxPerLane], s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxPerLane; ++i) {
+      const int e = lane + 64 * i;
+      v[i] = e < d ? x[(size_t)r * d + e] : 0.f;
+      t[i] = e < d ? (float)dn[(size_t)r * d + e] : 0.f;
+      s += v[i];
+    }
+    const float mean = wave_sum(s) / d;
+    float s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxPerLane; ++i) {
+      const int e = lane + 64 * i;
+      v[i] = e < d ? v[i] - mean : 0.f;
+      s2 += v[i] * v[i];
+    }
+    const float rstd = 1.f / sqrtf(wave_sum(s2) / d + eps);
+    float c1 = 0.f, c2 = 0.f;     // sum of dn g, sum of dn g xhat
+#pragma unroll
+    for (int i = 0; i < kMaxPerLane; ++i) {
+      v[i] *= rstd;                              // xhat
+      ab[i] += t[i];
+      ag[i] += t[i] * v[i];
+      t[i] *= gv[i];                             // dL/dxhat
+      c1 += t[i];
+      c2 += t[i] * v[i];
+    }
+    c1 = wave_sum(c1) / d;
+    c2 = wave_sum(c2) / d;
+#pragma unroll
+    for (int i = 0; i < kMaxPerLane; ++i) {
+      const int e = lane + 64 * i;
+      if (e < d) {
+        const size_t o = (size_t)r * d + e;
+        const float dx = dres[o] + rstd * (t[i] - c1 - v[i] * c2);
+        dx_out[o] = dx;
+        if (dxb) dxb[o] = (__bf16)dx;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kMaxPerLane; ++i) {
+    const int e = lane + 64 * i;
+    if (e < d) {
+      unsafeAtomicAdd(dg + e, ag[i]);
+      unsafeAtomicAdd(db + e, ab[i]);
+    }
+  }
+}
+
+// Gradient of the merge (Section 3.4) into the last block's output rows:
+//   mean:   dZ[r][:] = dM[u][t][:] / n_{u,t} for the group's n valid tokens;
+//   concat: dZ[r][:] = dM[u][t][j d : (j + 1) d] for the token in slot j of its group;
+// zeros for padded tokens.  Written as fp32 and as bf16.
+__global__ __launch_bounds__(256) void bw_merge_bwd_kernel(const float* dM, float* dy, __bf16* dyb, RowGeom q,
+                                                           int d, int T, int concat) {
+  const size_t n = (size_t)q.ntok * d;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const int r = (int)(i / d), e = (int)(i - (size_t)r * d);
+    const int u = r / q.L, pos = r - u * q.L;
+    const int len = row_len(q, u);
+    float v = 0.f;
+    if (pos < len) {
+      const int t = pos / q.K, j = pos - t * q.K;
+      if (concat) {
+        v = dM[((size_t)u * T + t) * ((size_t)q.K * d) + (size_t)j * d + e];
+      } else {
+        const int cnt = min(q.K, len - t * q.K);
+        v = dM[((size_t)u * T + t) * d + e] / (float)cnt;
+      }
+    }
+    dy[i] = v;
+    dyb[i] = (__bf16)v;
+  }
+}
+
+// out[c] += sum over rows of G[r * pitch + c], c < W (W a multiple of 8): bias gradients.
+__global__ __launch_bounds__(256) void bw_colsum_kernel(const __bf16* G, int pitch, int W, int ntok, int rows_per_block,
+                                                        float* out) {
+  __shared__ float red[256 * 8];
+  const int nch = W / 8;                   // 16-byte chunks per row
+  const int rl = 256 / nch;                // rows handled side by side
+  const int ch = threadIdx.x % nch, rlane = threadIdx.x / nch;
+  float s[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s[e] = 0.f;
+  const int rbeg = blockIdx.x * rows_per_block, rend = min(ntok, rbeg + rows_per_block);
+  if (rlane < rl) {
+    for (int r = rbeg + rlane; r < rend; r += rl) {
+      const bf16x8 v = *(const bf16x8*)(G + (size_t)r * pitch + 8 * ch);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s[e] += (float)v[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[threadIdx.x * 8 + e] = s[e];
+  __syncthreads();
+  if (threadIdx.x < W) {
+    const int c = threadIdx.x;               // column c: chunk c / 8, element c % 8
+    float t = 0.f;
+    for (int k = 0; k < rl; ++k) t += red[(k * nch + c / 8) * 8 + (c & 7)];
+    unsafeAtomicAdd(out + c, t);
+  }
+  // columns 256 .. W - 1 (W up to 2048)
+  for (int c = threadIdx.x + 256; c < W; c += 256) {
+    float t = 0.f;
+    for (int k = 0; k < rl; ++k) t += red[(k * nch + c / 8) * 8 + (c & 7)];
+    unsafeAtomicAdd(out + c, t);
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Attention inside a group of K adjacent tokens (InnerTrans, Section 3.4): bidirectional, keys
+// masked by validity.  qkv [ntok][3 d] = [q | k | v]; one thread per (row, head).
+struct GroupOf {
+  int first;      // first row of the group
+  int n;          // valid tokens in it (they are its first n rows)
+};
+__device__ __forceinline__ bool group_of(const RowGeom& q, int r, GroupOf* g) {
+  const int u = r / q.L, pos = r - u * q.L;
+  const int len = row_len(q, u);
+  const int t = pos / q.K;
+  g->first = u * q.L + t * q.K;
+  g->n = max(0, min(q.K, len - t * q.K));
+  return pos < len;
+}
+
+template <int DH>
+__device__ __forceinline__ void load_head(const __bf16* p, float* v) {
+#pragma unroll
+  for (int c = 0; c < DH; c += 8) {
+    const bf16x8 t = *(const bf16x8*)(p + c);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[c + e] = (float)t[e];
+  }
+}
+template <int DH>
+__device__ __forceinline__ void store_head(__bf16* p, const float* v) {
+#pragma unroll
+  for (int c = 0; c < DH; c += 8) {
+    bf16x8 t;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t[e] = (__bf16)v[c + e];
+    *(bf16x8*)(p + c) = t;
+  }
+}
+template <int DH>
+__device__ __forceinline__ float dot(const float* a, const float* b) {
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < DH; ++c) s += a[c] * b[c];
+  return s;
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void bw_attn_fwd_kernel(const __bf16* qkv, __bf16* o, RowGeom q, int d, int heads) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)q.ntok * heads) return;
+  const int r = (int)(idx / heads), h = (int)(idx - (long long)r * heads);
+  GroupOf g;
+  float acc[DH];
+#pragma unroll
+  for (int c = 0; c < DH; ++c) acc[c] = 0.f;
+  if (group_of(q, r, &g)) {
+    const float scale = rsqrtf((float)DH);
+    float qv[DH], kv[DH], s[kMaxGroup];
+    load_head<DH>(qkv + (size_t)r * 3 * d + h * DH, qv);
+    float mx = -3.0e38f;
+    for (int j = 0; j < g.n; ++j) {
+      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + d + h * DH, kv);
+      s[j] = scale * dot<DH>(qv, kv);
+      mx = fmaxf(mx, s[j]);
+    }
+    float l = 0.f;
+    for (int j = 0; j < g.n; ++j) {
+      s[j] = __expf(s[j] - mx);
+      l += s[j];
+    }
+    const float inv = 1.f / l;
+    for (int j = 0; j < g.n; ++j) {
+      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + 2 * d + h * DH, kv);
+      const float p = s[j] * inv;
+#pragma unroll
+      for (int c = 0; c < DH; ++c) acc[c] += p * kv[c];
+    }
+  }
+  store_head<DH>(o + (size_t)r * d + h * DH, acc);
+}
+
+// Query side of the attention backward: for query row i, P_i. is recomputed, dP_ij = do_i . v_j,
+// D_i = sum_j P_ij dP_ij, dS_ij = P_ij (dP_ij - D_i), dq_i = scale sum_j dS_ij k_j.  Writes dq into
+// dqkv[:, 0:d) and the row's softmax statistics (log-sum-exp of the scaled scores, D_i) into stat.
+template <int DH>
+__global__ __launch_bounds__(256) void bw_attn_bwd_q_kernel(const __bf16* qkv, const __bf16* dob, __bf16* dqkv,
+                                                            float2* stat, RowGeom q, int d, int heads) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)q.ntok * heads) return;
+  const int r = (int)(idx / heads), h = (int)(idx - (long long)r * heads);
+  GroupOf g;
+  float acc[DH];
+#pragma unroll
+  for (int c = 0; c < DH; ++c) acc[c] = 0.f;
+  float2 st = make_float2(0.f, 0.f);
+  if (group_of(q, r, &g)) {
+    const float scale = rsqrtf((float)DH);
+    float qv[DH], dov[DH], kv[DH], s[kMaxGroup], dp[kMaxGroup];
+    load_head<DH>(qkv + (size_t)r * 3 * d + h * DH, qv);
+    load_head<DH>(dob + (size_t)r * d + h * DH, dov);
+    float mx = -3.0e38f;
+    for (int j = 0; j < g.n; ++j) {
+      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + d + h * DH, kv);
+      s[j] = scale * dot<DH>(qv, kv);
+      mx = fmaxf(mx, s[j]);
+      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + 2 * d + h * DH, kv);
+      dp[j] = dot<DH>(dov, kv);
+    }
+    float l = 0.f;
+    for (int j = 0; j < g.n; ++j) {
+      s[j] = __expf(s[j] - mx);
+      l += s[j];
+    }
+    const float inv = 1.f / l;
+    float D = 0.f;
+    for (int j = 0; j < g.n; ++j) {
+      s[j] *= inv;
+      D += s[j] * dp[j];
+    }
+    for (int j = 0; j < g.n; ++j) {
+      const float ds = scale * s[j] * (dp[j] - D);
+      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + d + h * DH, kv);
+#pragma unroll
+      for (int c = 0; c < DH; ++c) acc[c] += ds * kv[c];
+    }
+    st = make_float2(mx + __logf(l), D);
+  }
+  store_head<DH>(dqkv + (size_t)r * 3 * d + h * DH, acc);
+  stat[(size_t)r * heads + h] = st;
+}
+
+// Key side: for key row j, over the group's valid queries i: P_ij = exp(s_ij - lse_i),
+// dv_j = sum_i P_ij do_i, dk_j = scale sum_i P_ij (do_i . v_j - D_i) q_i.  Writes dqkv[:, d:3d).
+template <int DH>
+__global__ __launch_bounds__(256) void bw_attn_bwd_kv_kernel(const __bf16* qkv, const __bf16* dob, __bf16* dqkv,
+                                                             const float2* stat, RowGeom q, int d, int heads) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)q.ntok * heads) return;
+  const int r = (int)(idx / heads), h = (int)(idx - (long long)r * heads);
+  GroupOf g;
+  float dk[DH], dv[DH];
+#pragma unroll
+  for (int c = 0; c < DH; ++c) { dk[c] = 0.f; dv[c] = 0.f; }
+  if (group_of(q, r, &g)) {
+    const float scale = rsqrtf((float)DH);
+    float kv[DH], vv[DH], qi[DH], doi[DH];
+    load_head<DH>(qkv + (size_t)r * 3 * d + d + h * DH, kv);
+    load_head<DH>(qkv + (size_t)r * 3 * d + 2 * d + h * DH, vv);
+    for (int i = 0; i < g.n; ++i) {
+      const int ri = g.first + i;
+      load_head<DH>(qkv + (size_t)ri * 3 * d + h * DH, qi);
+      load_head<DH>(dob + (size_t)ri * d + h * DH, doi);
+      const float2 st = stat[(size_t)ri * heads + h];
+      const float p = __expf(scale * dot<DH>(qi, kv) - st.x);
+      const float ds = scale * p * (dot<DH>(doi, vv) - st.y);
+#pragma unroll
+      for (int c = 0; c < DH; ++c) {
+        dv[c] += p * doi[c];
+        dk[c] += ds * qi[c];
+      }
+    }
+  }
+  store_head<DH>(dqkv + (size_t)r * 3 * d + d + h * DH, dk);
+  store_head<DH>(dqkv + (size_t)r * 3 * d + 2 * d + h * DH, dv);
+}
+
+// [wq | wk | wv] side by side: cat[i][j d + c] = w_j[i][c]; biases the same way
+__global__ __launch_bounds__(256) void bw_concat_qkv_kernel(const __bf16* wq, const __bf16* wk, const __bf16* wv,
+                                                            const __bf16* bq, const __bf16* bk, const __bf16* bv,
+                                                            __bf16* cat, __bf16* bcat, int d) {
+  const int n = d * 3 * d;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n + 3 * d; i += gridDim.x * 256) {
+    if (i < n) {
+      const int row = i / (3 * d), col = i - row * 3 * d;
+      const int j = col / d, c = col - j * d;
+      const __bf16* w = j == 0 ? wq : (j == 1 ? wk : wv);
+      cat[i] = w[row * d + c];
+    } else {
+      const int col = i - n;
+      const int j = col / d, c = col - j * d;
+      const __bf16* b = j == 0 ? bq : (j == 1 ? bk : bv);
+      bcat[col] = b[c];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void bw_zero_kernel(float* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
+}
+
+// ------------------------------------------------------------------------------------ host side
+static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Parameter gradients of one block: fp32, in the order of the longer_block members.
+struct GradLayout { size_t ln1_g, ln1_b, wq, bq, wk, bk, wv, bv, wo, bo, ln2_g, ln2_b, w1, b1, w2, b2, total; };
+static GradLayout grad_layout(int d, int f) {
+  GradLayout g;
+  size_t o = 0;
+  auto take = [&](size_t n) { size_t at = o; o += n; return at; };
+  g.ln1_g = take(d); g.ln1_b = take(d);
+  g.wq = take((size_t)d * d); g.bq = take(d);
+  g.wk = take((size_t)d * d); g.bk = take(d);
+  g.wv = take((size_t)d * d); g.bv = take(d);
+  g.wo = take((size_t)d * d); g.bo = take(d);
+  g.ln2_g = take(d); g.ln2_b = take(d);
+  g.w1 = take((size_t)d * f); g.b1 = take(f);
+  g.w2 = take((size_t)f * d); g.b2 = take(d);
+  g.total = o;
+  return g;
+}
+
+struct Workspace {
+  size_t wcat, bcat;                       // per layer: [d][3d] bf16, [3d] bf16
+  size_t xin;                              // per layer: fp32 [ntok][d]
+  size_t n1, qkv, o, xmid, n2, h, a;       // one block's recomputed intermediates
+  size_t dy, dyb, dh, dn, dxm, dxmb, dob, dqkv, stat;
+  size_t total;
+};
+static Workspace workspace(int layers, size_t ntok, int d, int f, int heads) {
+  Workspace w;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
+  w.wcat = take((size_t)layers * d * 3 * d * 2);
+  w.bcat = take((size_t)layers * up256((size_t)3 * d * 2));
+  w.xin = take((size_t)layers * ntok * d * 4);
+  w.n1 = take(ntok * d * 2);
+  w.qkv = take(ntok * 3 * d * 2);
+  w.o = take(ntok * d * 2);
+  w.xmid = take(ntok * d * 4);
+  w.n2 = take(ntok * d * 2);
+  w.h = take(ntok * f * 2);
+  w.a = take(ntok * f * 2);
+  w.dy = take(ntok * d * 4);
+  w.dyb = take(ntok * d * 2);
+  w.dh = take(ntok * f * 2);
+  w.dn = take(ntok * d * 2);
+  w.dxm = take(ntok * d * 4);
+  w.dxmb = take(ntok * d * 2);
+  w.dob = take(ntok * d * 2);
+  w.dqkv = take(ntok * 3 * d * 2);
+  w.stat = take(ntok * heads * 8);
+  w.total = o;
+  return w;
+}
+
+struct Dims { int d, f, heads, dh, layers, K, T; size_t ntok; };
+
+static int check(const longer_config* c, int B, int L, Dims* s) {
+  if (!c) return api_error(LONGER_ERR_ARG, "config is NULL");
+  if (c->dtype != LONGER_BF16) return api_error(LONGER_ERR_ARG, "the backward pass is mixed precision: dtype must be LONGER_BF16");
+  if (c->act != LONGER_ACT_GELU_ERF && c->act != LONGER_ACT_RELU) return api_error(LONGER_ERR_ARG, "act %d unknown", c->act);
+  if (c->merge != LONGER_MERGE_MEAN && c->merge != LONGER_MERGE_CONCAT) return api_error(LONGER_ERR_ARG, "merge %d unknown", c->merge);
+  if (c->K <= 0 || c->K > kMaxGroup || 32 % c->K) return api_error(LONGER_ERR_ARG, "K=%d must divide 32", c->K);
+  if (c->d <= 0 || c->d % 32) return api_error(LONGER_ERR_ARG, "d=%d must be a positive multiple of 32", c->d);
+  int d = c->d;
+  if (c->merge == LONGER_MERGE_CONCAT) {
+    if (d % c->K) return api_error(LONGER_ERR_ARG, "concat merge: K=%d must divide d=%d", c->K, d);
+    d /= c->K;
+  }
+  if (d % 32 || d > 64 * kMaxPerLane) return api_error(LONGER_ERR_ARG, "InnerTrans width %d must be a multiple of 32, at most %d", d, 64 * kMaxPerLane);
+  if (c->inner_layers <= 0 || c->inner_layers > 32) return api_error(LONGER_ERR_ARG, "inner_layers=%d out of range", c->inner_layers);
+  if (c->inner_heads <= 0 || d % c->inner_heads) return api_error(LONGER_ERR_ARG, "inner_heads=%d must divide the InnerTrans width %d", c->inner_heads, d);
+  const int dh = d / c->inner_heads;
+  if (dh != 16 && dh != 32) return api_error(LONGER_ERR_ARG, "head width %d unsupported (16 or 32)", dh);
+  if (c->ffn_mult <= 0 || c->ffn_mult * d > 2048) return api_error(LONGER_ERR_ARG, "ffn_mult=%d: the FFN hidden width must be at most 2048", c->ffn_mult);
+  if (!(c->ln_eps > 0.f)) return api_error(LONGER_ERR_ARG, "ln_eps must be positive");
+  if (B <= 0 || L <= 0) return api_error(LONGER_ERR_ARG, "B=%d, L=%d must be positive", B, L);
+  const long long ntok = (long long)B * L;
+  if (ntok * c->inner_heads >= (1ll << 31) - 256 || ntok * d * c->ffn_mult >= (1ll << 40))
+    return api_error(LONGER_ERR_ARG, "B * L = %lld token rows are too many for one call; split the batch", ntok);
+  s->d = d; s->f = c->ffn_mult * d; s->heads = c->inner_heads; s->dh = dh; s->layers = c->inner_layers;
+  s->K = c->K; s->T = (L + c->K - 1) / c->K; s->ntok = (size_t)ntok;
+  return 0;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+static int launched(const char* what) {
+  return hipGetLastError() == hipSuccess ? 0 : api_error(LONGER_ERR_HIP, "%s launch failed", what);
+}
+
+static int gemm(hipStream_t st, bool a_kc, bool b_kc, GemmArgs g, int splits) {
+  if (!aligned16(g.A) || !aligned16(g.B) || g.lda % 8 || g.ldb % 8) return api_error(LONGER_ERR_ARG, "backward GEMM operand misaligned");
+  dim3 grid((g.M + 127) / 128, (g.N + 127) / 128, splits);
+  if (a_kc && b_kc) bw_gemm_kernel<true, true><<<grid, 256, 0, st>>>(g);
+  else if (a_kc && !b_kc) bw_gemm_kernel<true, false><<<grid, 256, 0, st>>>(g);
+  else if (!a_kc && !b_kc) bw_gemm_kernel<false, false><<<grid, 256, 0, st>>>(g);
+  else return api_error(LONGER_ERR_ARG, "backward GEMM form not built");
+  return launched("backward GEMM");
+}
+
+// y = x W (+ epilogue): x [ntok][kc] row-major, W [kc][n] row-major
+static int gemm_rows(hipStream_t st, const __bf16* x, int kc, const __bf16* W, int n, size_t ntok, int epi, int act,
+                     void* out, void* out2, const __bf16* bias, const float* res, const __bf16* pre) {
+  GemmArgs g = {};
+  g.A = x; g.lda = kc; g.B = W; g.ldb = n; g.M = (int)ntok; g.N = n; g.Kc = kc; g.kslice = kc;
+  g.epi = epi; g.act = act; g.out = out; g.out2 = out2; g.ldo = n; g.bias = bias; g.res = res; g.pre = pre;
+  return gemm(st, true, false, g, 1);
+}
+// dx = dy W^T: dy [ntok][kc], W [n][kc] row-major (the forward's [in = n][out = kc])
+static int gemm_rows_t(hipStream_t st, const __bf16* dy, int kc, const __bf16* W, int n, size_t ntok, int epi, int act,
+                       void* out, const __bf16* pre) {
+  GemmArgs g = {};
+  g.A = dy; g.lda = kc; g.B = W; g.ldb = kc; g.M = (int)ntok; g.N = n; g.Kc = kc; g.kslice = kc;
+  g.epi = epi; g.act = act; g.out = out; g.ldo = n; g.pre = pre;
+  return gemm(st, true, true, g, 1);
+}
+// dW [m][n] += x^T dy: x [ntok][.. m columns, pitch lda], dy [ntok][.. n columns, pitch ldb]
+static int gemm_wgrad(hipStream_t st, const __bf16* x, int lda, int m, const __bf16* dy, int ldb, int n, size_t ntok, float* dW) {
+  GemmArgs g = {};
+  g.A = x; g.lda = lda; g.B = dy; g.ldb = ldb; g.M = m; g.N = n; g.Kc = (int)ntok;
+  const int tiles = ((m + 127) / 128) * ((n + 127) / 128);
+  int splits = 2048 / tiles;
+  const int most = (int)((ntok + 255) / 256);
+  if (splits > most) splits = most;
+  if (splits < 1) splits = 1;
+  g.kslice = (int)(((ntok + splits - 1) / splits + 31) / 32 * 32);
+  splits = (int)((ntok + g.kslice - 1) / g.kslice);
+  g.epi = EPI_ATOMIC; g.out = dW; g.ldo = n;
+  return gemm(st, false, false, g, splits);
+}
+
+static int colsum(hipStream_t st, const __bf16* G, int pitch, int W, size_t ntok, float* out) {
+  const int rows = 1024;
+  bw_colsum_kernel<<<(unsigned)((ntok + rows - 1) / rows), 256, 0, st>>>(G, pitch, W, (int)ntok, rows, out);
+  return launched("column sum");
+}
+
+static unsigned flat_grid(size_t n) {
+  size_t b = (n + 255) / 256;
+  return (unsigned)(b > 65536 ? 65536 : (b ? b : 1));
+}
+
+#define BW_TRY(x) do { int rc_ = (x); if (rc_) return rc_; } while (0)
+
+static int run(const longer_config* c, const longer_block* inner, const void* H, const int32_t* lens, int B, int L,
+               const float* dM, float* dH, float* grads, char* ws, hipStream_t st, const Dims& s) {
+  const int d = s.d, f = s.f;
+  const size_t nt = s.ntok;
+  const Workspace w = workspace(s.layers, nt, d, f, s.heads);
+  const GradLayout gl = grad_layout(d, f);
+  const RowGeom q = {lens, L, s.K, (int)nt};
+  auto xin = [&](int l) { return (float*)(ws + w.xin) + (size_t)l * nt * d; };
+  auto wcat = [&](int l) { return (__bf16*)(ws + w.wcat) + (size_t)l * d * 3 * d; };
+  auto bcat = [&](int l) { return (__bf16*)(ws + w.bcat + (size_t)l * up256((size_t)3 * d * 2)); };
+  __bf16* n1 = (__bf16*)(ws + w.n1);   __bf16* qkv = (__bf16*)(ws + w.qkv); __bf16* o = (__bf16*)(ws + w.o);
+  float* xmid = (float*)(ws + w.xmid); __bf16* n2 = (__bf16*)(ws + w.n2);   __bf16* h = (__bf16*)(ws + w.h);
+  __bf16* a = (__bf16*)(ws + w.a);     float* dy = (float*)(ws + w.dy);     __bf16* dyb = (__bf16*)(ws + w.dyb);
+  __bf16* dh = (__bf16*)(ws + w.dh);   __bf16* dn = (__bf16*)(ws + w.dn);   float* dxm = (float*)(ws + w.dxm);
+  __bf16* dxmb = (__bf16*)(ws + w.dxmb); __bf16* dob = (__bf16*)(ws + w.dob); __bf16* dqkv = (__bf16*)(ws + w.dqkv);
+  float2* stat = (float2*)(ws + w.stat);
+  const unsigned ln_grid = (unsigned)((nt + 3) / 4 > 4096 ? 4096 : (nt + 3) / 4);
+  const unsigned ah_grid = (unsigned)((nt * s.heads + 255) / 256);
+
+  bw_zero_kernel<<<flat_grid(gl.total * s.layers), 256, 0, st>>>(grads, gl.total * s.layers);
+  BW_TRY(launched("zero fill"));
+  for (int l = 0; l < s.layers; ++l) {
+    const longer_block& b = inner[l];
+    bw_concat_qkv_kernel<<<64, 256, 0, st>>>((const __bf16*)b.wq, (const __bf16*)b.wk, (const __bf16*)b.wv, (const __bf16*)b.bq,
+                                             (const __bf16*)b.bk, (const __bf16*)b.bv, wcat(l), bcat(l), d);
+    BW_TRY(launched("weight concatenation"));
+  }
+  bw_load_x0_kernel<<<flat_grid(nt * d), 256, 0, st>>>((const __bf16*)H, xin(0), q, d);
+  BW_TRY(launched("input load"));
+
+  // one block forward from its input x: intermediates into the workspace, output (fp32) into y_out
+  // unless that is NULL (the last block's output is not needed)
+  auto forward = [&](int l, float* y_out) -> int {
+    const longer_block& b = inner[l];
+    const float* x = xin(l);
+    bw_ln_fwd_kernel<<<ln_grid, 256, 0, st>>>(x, (const __bf16*)b.ln1_g, (const __bf16*)b.ln1_b, n1, (int)nt, d, c->ln_eps);
+    BW_TRY(launched("LayerNorm"));
+    BW_TRY(gemm_rows(st, n1, d, wcat(l), 3 * d, nt, EPI_BF16, 0, qkv, nullptr, bcat(l), nullptr, nullptr));
+    if (s.dh == 16) bw_attn_fwd_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, o, q, d, s.heads);
+    else bw_attn_fwd_kernel<32><<<ah_grid, 256, 0, st>>>(qkv, o, q, d, s.heads);
+    BW_TRY(launched("group attention"));
+    BW_TRY(gemm_rows(st, o, d, (const __bf16*)b.wo, d, nt, EPI_RES_F32, 0, xmid, nullptr, (const __bf16*)b.bo, x, nullptr));
+    bw_ln_fwd_kernel<<<ln_grid, 256, 0, st>>>(xmid, (const __bf16*)b.ln2_g, (const __bf16*)b.ln2_b, n2, (int)nt, d, c->ln_eps);
+    BW_TRY(launched("LayerNorm"));
+    BW_TRY(gemm_rows(st, n2, d, (const __bf16*)b.w1, f, nt, EPI_ACT, c->act, h, a, (const __bf16*)b.b1, nullptr, nullptr));
+    if (y_out)
+      BW_TRY(gemm_rows(st, a, f, (const __bf16*)b.w2, d, nt, EPI_RES_F32, 0, y_out, nullptr, (const __bf16*)b.b2, xmid, nullptr));
+    return 0;
+  };
+
+  // the chain of block inputs (recomputed: nothing is kept from a forward call)
+  for (int l = 0; l + 1 < s.layers; ++l) BW_TRY(forward(l, xin(l + 1)));
+
+  bw_merge_bwd_kernel<<<flat_grid(nt * d), 256, 0, st>>>(dM, dy, dyb, q, d, s.T, c->merge == LONGER_MERGE_CONCAT);
+  BW_TRY(launched("merge gradient"));
+
+  for (int l = s.layers - 1; l >= 0; --l) {
+    const longer_block& b = inner[l];
+    float* g = grads + (size_t)l * gl.total;
+    BW_TRY(forward(l, nullptr));                 // this block's intermediates, from its input alone
+    // FFN: y = xmid + act(n2 W1 + b1) W2 + b2
+    BW_TRY(gemm_wgrad(st, a, f, f, dyb, d, d, nt, g + gl.w2));
+    BW_TRY(colsum(st, dyb, d, d, nt, g + gl.b2));
+    BW_TRY(gemm_rows_t(st, dyb, d, (const __bf16*)b.w2, f, nt, EPI_DACT, c->act, dh, h));
+    BW_TRY(gemm_wgrad(st, n2, d, d, dh, f, f, nt, g + gl.w1));
+    BW_TRY(colsum(st, dh, f, f, nt, g + gl.b1));
+    BW_TRY(gemm_rows_t(st, dh, f, (const __bf16*)b.w1, d, nt, EPI_BF16, 0, dn, nullptr));
+    bw_ln_bwd_kernel<<<ln_grid, 256, 0, st>>>(dn, xmid, (const __bf16*)b.ln2_g, dy, dxm, dxmb, g + gl.ln2_g, g + gl.ln2_b,
+                                              (int)nt, d, c->ln_eps);
+    BW_TRY(launched("LayerNorm backward"));
+    // attention: xmid = x + att W_O + b_O
+    BW_TRY(gemm_wgrad(st, o, d, d, dxmb, d, d, nt, g + gl.wo));
+    BW_TRY(colsum(st, dxmb, d, d, nt, g + gl.bo));
+    BW_TRY(gemm_rows_t(st, dxmb, d, (const __bf16*)b.wo, d, nt, EPI_BF16, 0, dob, nullptr));
+    if (s.dh == 16) {
+      bw_attn_bwd_q_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
+      bw_attn_bwd_kv_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
+    } else {
+      bw_attn_bwd_q_kernel<32><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
+      bw_attn_bwd_kv_kernel<32><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
+    }
+    BW_TRY(launched("group attention backward"));
+    const size_t wofs[3] = {gl.wq, gl.wk, gl.wv}, bofs[3] = {gl.bq, gl.bk, gl.bv};
+    for (int j = 0; j < 3; ++j) {
+      BW_TRY(gemm_wgrad(st, n1, d, d, dqkv + (size_t)j * d, 3 * d, d, nt, g + wofs[j]));
+      BW_TRY(colsum(st, dqkv + (size_t)j * d, 3 * d, d, nt, g + bofs[j]));
+    }
+    BW_TRY(gemm_rows_t(st, dqkv, 3 * d, wcat(l), d, nt, EPI_BF16, 0, dn, nullptr));
+    // the gradient of this block's input is the upstream gradient of the block before it
+    float* dx = l ? dy : dH;
+    bw_ln_bwd_kernel<<<ln_grid, 256, 0, st>>>(dn, xin(l), (const __bf16*)b.ln1_g, dxm, dx, l ? dyb : nullptr,
+                                              g + gl.ln1_g, g + gl.ln1_b, (int)nt, d, c->ln_eps);
+    BW_TRY(launched("LayerNorm backward"));
+  }
+  return 0;
+}
+
+}  // namespace bw
+}  // namespace longer
+
+using namespace longer;
+
+extern "C" {
+
+size_t longer_backward_workspace_bytes(const longer_config* cfg, int B, int L) {
+  bw::Dims s;
+  if (bw::check(cfg, B, L, &s)) return 0;
+  return bw::workspace(s.layers, s.ntok, s.d, s.f, s.heads).total;
+}
+
+size_t longer_block_grad_floats(const longer_config* cfg) {
+  bw::Dims s;
+  if (bw::check(cfg, 1, 1, &s)) return 0;
+  return bw::grad_layout(s.d, s.f).total;
+}
+
+int longer_token_merge_backward(const longer_config* cfg, const longer_block* inner, const void* H,
+                                const int32_t* lens, int B, int L, const float* dM,
+                                float* dH_out, float* grads_out,
+                                void* ws, size_t ws_bytes, void* stream) {
+  bw::Dims s;
+  int rc = bw::check(cfg, B, L, &s);
+  if (rc) return rc;
+  if (!inner || !H || !dM || !dH_out || !grads_out || !ws) return api_error(LONGER_ERR_ARG, "null pointer argument");
+  if (!bw::aligned16(H) || !bw::aligned16(dM) || !bw::aligned16(dH_out) || !bw::aligned16(grads_out) || ((uintptr_t)ws & 255))
+    return api_error(LONGER_ERR_ARG, "H, dM, dH_out, grads_out must be 16-byte aligned and ws 256-byte aligned");
+  for (int l = 0; l < s.layers; ++l) {
+    const void* const* p = (const void* const*)&inner[l];
+    for (int i = 0; i < 16; ++i)
+      if (!p[i] || !bw::aligned16(p[i])) return api_error(LONGER_ERR_ARG, "InnerTrans block %d: parameter %d is NULL or not 16-byte aligned", l, i);
+  }
+  const size_t need = bw::workspace(s.layers, s.ntok, s.d, s.f, s.heads).total;
+  if (ws_bytes < need) return api_error(LONGER_ERR_WS, "workspace too small: %zu < %zu bytes", ws_bytes, need);
+  return bw::run(cfg, inner, H, lens, B, L, dM, dH_out, grads_out, (char*)ws, (hipStream_t)stream, s);
+}
+
+}  // extern "C"

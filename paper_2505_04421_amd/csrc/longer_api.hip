@@ -71,6 +71,15 @@ static int fail(int code, const char* fmt, ...) {
   return code;
 }
 
+// the same for the library's other translation units (backward.hip): sets the thread's message
+__attribute__((visibility("hidden"))) int api_error(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
 // ------------------------------------------------------------------------------------
 // Optional per-stage timing with HIP events on the caller's stream (measurement aid).
 enum Stage { ST_PACK = 0, ST_MERGE = 1, ST_KVPROJ = 2, ST_ATTN = 3, ST_SCORE = 4 };

@@ -1,0 +1,159 @@
+"""GPU parity of longer_token_merge_backward (backward pass of the token merge with recomputation,
+mixed precision) against the fp64 oracle ``oracle.longer_oracle_grad.token_merge_backward``.
+
+Tolerance.  The oracle differentiates in fp64; the GPU pass rounds every GEMM operand and every stored
+activation / activation gradient to bf16 (2^-9 relative, about 1.1e-3 rms per rounding).  A gradient
+passes through about a dozen such roundings per InnerTrans block, independent of each other, so the
+expected relative L2 error is sqrt(12) x 1.1e-3 = 4e-3 per block and 6e-3 over two; the bar is 2e-2
+for the gradient of the raw tokens (per user) and for every parameter.  With ReLU the derivative is
+a step: a hidden unit whose pre-activation lies within the forward pass's own rounding error of zero
+(a few in a thousand) takes the other branch than in fp64, which is a difference of that unit's whole
+contribution, not of a rounding; the bar there is 5e-2."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import longer_synth as synth
+from oracle import longer_oracle_grad as org
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+TOL_RELU = 5e-2
+PARAMS = org.PARAMS
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _rel(a, b):
+    den = float(np.linalg.norm(b))
+    return float(np.linalg.norm(a - b)) / (den if den > 0 else 1.0)
+
+
+def _run_gpu(case, dM):
+    import paper_2505_04421_amd as lg
+    from gpu_util import guarded_empty
+    cfg = case["cfg"]
+    model = lg.DeviceModel(cfg, case["weights"])
+    dev = model.device
+    B, L = cfg.B, cfg.L
+    H = model.upload(case["H"])
+    lens = None if case["lens"] is None else torch.from_numpy(case["lens"].astype(np.int32)).to(dev)
+    n_ws = lg.longer_backward_workspace_bytes(model.ccfg, B, L)
+    nf = lg.longer_block_grad_floats(model.ccfg)
+    assert n_ws > 0 and nf > 0, lg.longer_last_error()
+    ws, g_ws = guarded_empty(dev, (n_ws,), torch.uint8)
+    dH, g_dh = guarded_empty(dev, (B, L, cfg.d_in), torch.float32)
+    grads, g_gr = guarded_empty(dev, (cfg.inner_layers * nf,), torch.float32)
+    dM_t = torch.from_numpy(np.ascontiguousarray(dM, dtype=np.float32)).to(dev)
+    lg.longer_token_merge_backward(model.ccfg, model.inner, H, lens, B, L, dM_t, dH, grads, ws)
+    torch.cuda.synchronize()
+    for g, what in ((g_ws, "workspace"), (g_dh, "dH_out"), (g_gr, "grads_out")):
+        g.check(what)
+    views = lg.block_grad_views(cfg, grads)
+    return dH.cpu().numpy().astype(np.float64), [{k: v.cpu().numpy().astype(np.float64) for k, v in blk.items()} for blk in views]
+
+
+def _compare(name, case, dM, users=None):
+    cfg = case["cfg"]
+    _say("backward case %s: B=%d L=%d d_in=%d K=%d inner_layers=%d merge=%s act=%s" %
+         (name, cfg.B, cfg.L, cfg.d_in, cfg.K, cfg.inner_layers, cfg.merge, cfg.act))
+    dH, grads = _run_gpu(case, dM)
+    assert np.isfinite(dH).all()
+    TOL = TOL_RELU if cfg.act == "relu" else globals()["TOL"]
+    sel = list(range(cfg.B)) if users is None else list(users)
+    lens = case["lens"]
+    sub_lens = None if lens is None else lens[sel]
+    sub_cfg = cfg.replace(B=len(sel))
+    dH_ref, g_ref = org.token_merge_backward(sub_cfg, case["weights"]["inner"], case["H"][sel], sub_lens, dM[sel],
+                                             keep="input_only")
+    worst = 0.0
+    for i, u in enumerate(sel):
+        if np.linalg.norm(dH_ref[i]) == 0:
+            assert not dH[u].any(), "user %d: gradient must be zero" % u
+            continue
+        e = _rel(dH[u], dH_ref[i])
+        worst = max(worst, e)
+        assert e <= TOL, ("dH", u, e)
+        # padded tokens: exact zeros
+        ln = cfg.L if lens is None else int(min(lens[u], cfg.L))
+        assert not dH[u, ln:].any(), "user %d: padded rows of dH are not zero" % u
+    if users is not None:
+        rest = np.setdiff1d(np.arange(cfg.B), sel)
+        assert not dH[rest].any(), "users without an upstream gradient must get a zero gradient"
+    _say("  dH: worst per-user rel-L2 %.3e (tol %.0e)" % (worst, TOL))
+    for l in range(cfg.inner_layers):
+        for k in PARAMS:
+            got, ref = grads[l][k], g_ref[l][k]
+            assert np.isfinite(got).all(), (l, k)
+            if k == "bk":
+                # zero in exact arithmetic (a shift of every key moves all scores of a query alike, and
+                # softmax does not see it): judged against the size of b_Q's gradient, a sum of the
+                # same kind over the same tokens
+                e = float(np.linalg.norm(got - ref)) / (float(np.linalg.norm(g_ref[l]["bq"])) or 1.0)
+            else:
+                e = _rel(got, ref)
+            _say("  block %d %-6s rel-L2 %.3e" % (l, k, e))
+            assert e <= TOL, ("grad", l, k, e)
+
+
+def _bf16_case(base, **kw):
+    users = kw.pop("users", None)
+    cfg = synth.CONFIGS[base].replace(dtype="bf16", **kw)
+    return synth.make_case(cfg, users=users)
+
+
+def test_backward_small_width32_one_block():
+    case = _bf16_case("C1")
+    _compare("C1 as bf16", case, synth.draw_merge_gradient(case["cfg"]))
+
+
+def test_backward_c2_shape_ragged():
+    case = _bf16_case("C2", users=6, L=203, ragged=True, len_lo=0, len_hi=203)
+    case["lens"][0] = 0
+    case["lens"][1] = 203
+    case["lens"][2] = 5
+    _compare("C2, 6 ragged users incl. an empty one", case, synth.draw_merge_gradient(case["cfg"]))
+
+
+def test_backward_c3_shape_two_blocks():
+    case = _bf16_case("C3", users=3, L=333, ragged=True, len_lo=1, len_hi=333)
+    _compare("C3, 3 ragged users, two blocks", case, synth.draw_merge_gradient(case["cfg"]))
+
+
+def test_backward_relu_and_head_width_32():
+    case = _bf16_case("C2", users=4, L=130, act="relu", inner_heads=2)
+    _compare("C2 with ReLU, head width 32", case, synth.draw_merge_gradient(case["cfg"]))
+
+
+def test_backward_concat_merge():
+    case = _bf16_case("P1", users=3, L=100, ragged=True, len_lo=3, len_hi=100)
+    _compare("P1 (concat merge, raw width 32)", case, synth.draw_merge_gradient(case["cfg"]))
+
+
+@pytest.mark.parametrize("K", [1, 16, 32])
+def test_backward_group_sizes(K):
+    case = _bf16_case("C2", users=3, L=97, K=K, ragged=True, len_lo=0, len_hi=97)
+    _compare("C2 with K=%d" % K, case, synth.draw_merge_gradient(case["cfg"]))
+
+
+def test_backward_c3_full_size_sampled_users():
+    """The launch configuration the benchmark times (256 users x 2000 tokens): only four users get an
+    upstream gradient, so every gradient of the batch is theirs and the oracle can compute it."""
+    cfg = synth.CONFIGS["C3"]
+    case = synth.make_case(cfg)
+    users = [0, 100, 171, 255]
+    _compare("C3 full size, upstream gradient on 4 users", case, synth.draw_merge_gradient(cfg, users=users), users=users)
+
+
+def test_backward_argument_errors():
+    import paper_2505_04421_amd as lg
+    cfg = synth.CONFIGS["C1"]                      # fp32: no mixed-precision backward
+    ccfg = lg.make_config(cfg)
+    assert lg.longer_backward_workspace_bytes(ccfg, 4, 64) == 0
+    assert "LONGER_BF16" in lg.longer_last_error()
