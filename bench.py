@@ -102,6 +102,44 @@ def probe_rates(lg, torch, modes=None, iters=2000):
                     "one per compute unit"}, attainable
 
 
+def run_merge_backward(lg, torch, cfg, case, steps):
+    """Time longer_token_merge_backward (gradients of the token merge with recomputation) on the
+    configuration's batch; inputs and the upstream gradient resident in HBM."""
+    import numpy as np
+    import longer_synth as synth
+    from paper_2505_04421_amd import flops
+    dev = "cuda:0"
+    model = lg.DeviceModel(cfg, case["weights"], dev)
+    B, L = cfg.B, cfg.L
+    n_ws = lg.longer_backward_workspace_bytes(model.ccfg, B, L)
+    nf = lg.longer_block_grad_floats(model.ccfg)
+    if n_ws == 0 or nf == 0:
+        return {"error": lg.longer_last_error()}
+    ws = torch.empty(n_ws, dtype=torch.uint8, device=dev)
+    H = model.upload(case["H"])
+    lens = None if case["lens"] is None else torch.from_numpy(case["lens"].astype(np.int32)).to(dev)
+    dM = torch.from_numpy(synth.draw_merge_gradient(cfg)).to(dev)
+    dH = torch.empty(B, L, cfg.d_in, dtype=torch.float32, device=dev)
+    grads = torch.empty(cfg.inner_layers * nf, dtype=torch.float32, device=dev)
+    for _ in range(2):
+        lg.longer_token_merge_backward(model.ccfg, model.inner, H, lens, B, L, dM, dH, grads, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        lg.longer_token_merge_backward(model.ccfg, model.inner, H, lens, B, L, dM, dH, grads, ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    fl = flops.forward_flops(cfg, None if case["lens"] is None else case["lens"])
+    grad_gflop = 2.0 * fl["inner"] / 1e9          # d/d input and d/d parameter of every forward product
+    return {"workload": "%s: longer_token_merge_backward, B=%d users, L=%d, InnerTrans width %d, %d block(s), K=%d"
+                        % (cfg.name, B, L, cfg.d_in, cfg.inner_layers, cfg.K),
+            "ms_per_step": ms, "steps": steps, "user_sequences_per_s": B / (ms * 1e-3),
+            "gradient_gflop_per_step": grad_gflop,
+            "recompute": "block inputs and every block's intermediates, from the raw tokens",
+            "mfma_peak_frac_gradient_flops": grad_gflop / 1e3 / (ms * 1e-3) / PEAK_BF16_TFLOPS,
+            "workspace_bytes": n_ws}
+
+
 def run_forward(lg, torch, synth, cfg, args, steps, warmup, want_graph=True):
     """Time longer_forward (or, with --from-inputs, longer_forward_from_inputs) on one configuration."""
     import numpy as np
@@ -294,6 +332,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other forward configurations (all_configs)")
     ap.add_argument("--no-probe", action="store_true", help="skip the instruction-rate probes")
+    ap.add_argument("--no-backward", action="store_true", help="skip the backward pass of the token merge")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP graph replay measurement (profiler runs)")
     ap.add_argument("--probe-all", action="store_true",
                     help="run every mode of the instruction-rate probe (include/longer.h lists them), print "
@@ -425,6 +464,9 @@ def main():
                           "score_mfma_peak_frac": score_tflops / PEAK_BF16_TFLOPS,
                           "score_mfma_attainable_frac": None if not attainable else score_tflops / attainable}
         del m5, ws5, H5, Gc5, cache
+
+    if not args.no_backward and cfg.dtype == "bf16" and not r["from_inputs"]:
+        out["merge_backward"] = run_merge_backward(lg, torch, cfg, r["case"], max(3, args.steps // 5))
 
     out["cpu_baseline"] = None if args.no_cpu else cpu_oracle_leg(cfg, r["case"], None if r["from_inputs"] else r["Y_host"], 15.0)
     print(json.dumps(out))

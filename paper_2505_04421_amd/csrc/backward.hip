@@ -15,7 +15,7 @@
 // [token, feature] tensors in the workspace, and three kinds of kernels work on them:
 //   * one bf16 MFMA GEMM (bw_gemm_kernel) whose operands may each be stored with the
 //     contraction index contiguous or strided, which covers y = x W (+ epilogues),
-//     dx = dy W^T and dW = x^T dy (split over the tokens, fp32 atomic accumulation);
+//     dx = dy W^T and dW = x^T dy (cut into slices of tokens whose partial results a second kernel sums);
 //   * row kernels: LayerNorm forward / backward (+ gain / shift gradients), pooling backward,
 //     column sums (bias gradients);
 //   * the attention inside a group of K tokens, forward and backward, one thread per
@@ -47,39 +47,69 @@ enum Epilogue {
   EPI_RES_F32 = 1,   // outf[m][n] = res[m][n] + acc + bias[n]
   EPI_ACT = 2,       // out[m][n] = bf16(v), out2[m][n] = bf16(act(v)), v = acc + bias[n]
   EPI_DACT = 3,      // out[m][n] = bf16(acc * act'(pre[m][n]))
-  EPI_ATOMIC = 4     // outf[m][n] += acc   (fp32 atomics; blockIdx.z = slice of the contraction)
+  EPI_PARTIAL = 4    // parameter gradients: the contraction (over the tokens) is cut into slices, one workgroup
+                     // per tile and slice; outf[slice][m][n] = acc, summed afterwards by bw_reduce_kernel
 };
 
 struct GemmArgs {
   const __bf16* A; const __bf16* B;
   int lda, ldb;
   int M, N, Kc;
-  int kslice;                 // contraction range of one blockIdx.z (multiple of 32)
+  int kslice, nsplit;         // split GEMM: contraction range of one slice (multiple of 32), slices
   int epi, act;
   void* out; void* out2; int ldo;
   const __bf16* bias; const float* res; const __bf16* pre;
 };
 
+// Phi(v) = (1 + erf(v / sqrt 2)) / 2 and exp(-v^2 / 2) from one exponential: for z >= 0,
+// erf(z) = 1 - (a1 t + a2 t^2 + a3 t^3 + a4 t^4 + a5 t^5) exp(-z^2), t = 1 / (1 + p z), absolute error
+// below 1.5e-7 (the classic five-term approximation; odd extension for z < 0).
+__device__ __forceinline__ void gauss_cdf(float v, float* cdf, float* ex) {
+  const float z = fabsf(v) * 0.70710678118654752f;
+  const float e = __expf(-z * z);
+  const float t = __frcp_rn(1.f + 0.3275911f * z);
+  const float poly = ((((1.061405429f * t - 1.453152027f) * t + 1.421413741f) * t - 0.284496736f) * t + 0.254829592f) * t;
+  const float half_erfc = 0.5f * poly * e;                 // (1 - erf(|z|)) / 2
+  *cdf = v >= 0.f ? 1.f - half_erfc : half_erfc;
+  *ex = e;
+}
 __device__ __forceinline__ float act_fwd(float v, int act) {
   if (act == LONGER_ACT_RELU) return v > 0.f ? v : 0.f;
-  return 0.5f * v * (1.f + erff(v * 0.70710678118654752f));
+  float c, e;
+  gauss_cdf(v, &c, &e);
+  return v * c;
 }
 __device__ __forceinline__ float act_grad(float v, int act) {
   if (act == LONGER_ACT_RELU) return v > 0.f ? 1.f : 0.f;
-  return 0.5f * (1.f + erff(v * 0.70710678118654752f)) + v * 0.39894228040143268f * __expf(-0.5f * v * v);
+  float c, e;
+  gauss_cdf(v, &c, &e);
+  return c + v * 0.39894228040143268f * e;
 }
 
 constexpr int kPitchKC = 40;            // elements per row of a contraction-contiguous LDS tile (32 + 8 pad)
 constexpr int kTileElems = 128 * kPitchKC;   // >= 32 * 128 of the strided form
+constexpr int kStagePitch = 68;         // floats per row of the epilogue's staging area (64 + 4 pad)
 
 template <bool A_KC, bool B_KC>
 __global__ __launch_bounds__(256) void bw_gemm_kernel(GemmArgs g) {
-  __shared__ __attribute__((aligned(16))) __bf16 sA[2][kTileElems];
-  __shared__ __attribute__((aligned(16))) __bf16 sB[2][kTileElems];
+  __shared__ __attribute__((aligned(16))) __bf16 smem[4 * kTileElems];
+  auto sA = [&](int buf) { return smem + buf * kTileElems; };          // two buffers per operand
+  auto sB = [&](int buf) { return smem + (2 + buf) * kTileElems; };
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int wm = w & 1, wn = w >> 1, hi = lane >> 5, l32 = lane & 31;
-  const int m0 = blockIdx.x * 128, n0 = blockIdx.y * 128;
-  const int kbeg = blockIdx.z * g.kslice;
+  // Tile order.  Workgroups go to the 8 accelerator dies round-robin by index, each die with an L2 of
+  // its own.  Row GEMMs: the N tiles of one M tile (which share the A rows) get consecutive slots
+  // on one die.  Split GEMMs (parameter gradients): all tiles of one slice of the contraction
+  // (which share both operands' rows) do, and the slices are spread over the dies.
+  const int ntn = (g.N + 127) / 128, ntm = (g.M + 127) / 128;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const bool split = g.epi == EPI_PARTIAL;
+  const int inner = split ? ntm * ntn : ntn;
+  const int outer = (slot / inner) * 8 + xcd, in = slot % inner;
+  if (outer >= (split ? g.nsplit : ntm)) return;
+  const int mt = split ? in / ntn : outer, nt_ = in % ntn;
+  const int m0 = mt * 128, n0 = nt_ * 128;
+  const int kbeg = split ? outer * g.kslice : 0;
   const int kend = min(g.Kc, kbeg + g.kslice);
   const int nk = kend > kbeg ? (kend - kbeg + 31) / 32 : 0;
 
@@ -126,10 +156,10 @@ __global__ __launch_bounds__(256) void bw_gemm_kernel(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int c = tid + 256 * i;
-      if (A_KC) *(bf16x8*)&sA[buf][(c >> 2) * kPitchKC + 8 * (c & 3)] = ra[i];
-      else      *(bf16x8*)&sA[buf][(c >> 4) * 128 + 8 * (c & 15)] = ra[i];
-      if (B_KC) *(bf16x8*)&sB[buf][(c >> 2) * kPitchKC + 8 * (c & 3)] = rb[i];
-      else      *(bf16x8*)&sB[buf][(c >> 4) * 128 + 8 * (c & 15)] = rb[i];
+      if (A_KC) *(bf16x8*)&sA(buf)[(c >> 2) * kPitchKC + 8 * (c & 3)] = ra[i];
+      else      *(bf16x8*)&sA(buf)[(c >> 4) * 128 + 8 * (c & 15)] = ra[i];
+      if (B_KC) *(bf16x8*)&sB(buf)[(c >> 2) * kPitchKC + 8 * (c & 3)] = rb[i];
+      else      *(bf16x8*)&sB(buf)[(c >> 4) * 128 + 8 * (c & 15)] = rb[i];
     }
   };
   // fragment of the 32 x 16 operand slice: lane (x = l32, hi) holds contraction slots 8 hi .. 8 hi + 7
@@ -157,8 +187,8 @@ __global__ __launch_bounds__(256) void bw_gemm_kernel(GemmArgs g) {
       bf16x8 fa[2], fb[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        fa[t] = frag(sA[buf], A_KC, 64 * wm + 32 * t + l32, ks);
-        fb[t] = frag(sB[buf], B_KC, 64 * wn + 32 * t + l32, ks);
+        fa[t] = frag(sA(buf), A_KC, 64 * wm + 32 * t + l32, ks);
+        fb[t] = frag(sB(buf), B_KC, 64 * wn + 32 * t + l32, ks);
       }
 #pragma unroll
       for (int a = 0; a < 2; ++a)
@@ -170,30 +200,61 @@ __global__ __launch_bounds__(256) void bw_gemm_kernel(GemmArgs g) {
     __syncthreads();
   }
 
-  // epilogue: acc[a][b][r] = C[m0 + 64 wm + 32 a + tile_row(r, hi)][n0 + 64 wn + 32 b + l32]
+  // epilogue: acc[a][b][r] = C[m0 + 64 wm + 32 a + tile_row(r, hi)][n0 + 64 wn + 32 b + l32].  Each wave
+  // turns its 64 x 64 result, 32 rows at a time, through a private LDS area (the operand buffers are
+  // free after the loop's last barrier) so that a lane reads and writes 8 consecutive columns of a
+  // row: 16-byte accesses, 8 lanes per row.
+  float* stage = (float*)smem + w * (32 * kStagePitch);
+  static_assert(4 * 32 * kStagePitch * 4 <= 4 * kTileElems * 2, "staging area fits the operand buffers");
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    const int n = n0 + 64 * wn + 32 * b + l32;
-    if (n >= g.N) continue;
-    const float bias = g.bias ? (float)g.bias[n] : 0.f;
+  for (int a = 0; a < 2; ++a) {
+    __syncthreads();
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + 64 * wm + 32 * a + tile_row(r, hi);
-        if (m >= g.M) continue;
-        const size_t o = (size_t)m * g.ldo + n;
-        const float v = acc[a][b][r] + bias;
-        switch (g.epi) {
-          case EPI_BF16: ((__bf16*)g.out)[o] = (__bf16)v; break;
-          case EPI_RES_F32: ((float*)g.out)[o] = g.res[o] + v; break;
-          case EPI_ACT:
-            ((__bf16*)g.out)[o] = (__bf16)v;
-            ((__bf16*)g.out2)[o] = (__bf16)act_fwd(v, g.act);
-            break;
-          case EPI_DACT: ((__bf16*)g.out)[o] = (__bf16)(v * act_grad((float)g.pre[o], g.act)); break;
-          default: if (nk > 0) unsafeAtomicAdd((float*)g.out + o, v); break;
-        }
+      for (int r = 0; r < 16; ++r) stage[tile_row(r, hi) * kStagePitch + 32 * b + l32] = acc[a][b][r];
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int id = it * 64 + lane, row = id >> 3, cc = id & 7;
+      const int m = m0 + 64 * wm + 32 * a + row, n = n0 + 64 * wn + 8 * cc;
+      if (m >= g.M || n >= g.N) continue;
+      float v[8];
+      *(f32x4*)&v[0] = *(const f32x4*)&stage[row * kStagePitch + 8 * cc];
+      *(f32x4*)&v[4] = *(const f32x4*)&stage[row * kStagePitch + 8 * cc + 4];
+      if (g.bias) {
+        const bf16x8 bv = *(const bf16x8*)(g.bias + n);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += (float)bv[e];
+      }
+      const size_t o = (size_t)m * g.ldo + n;
+      bf16x8 ob;
+      if (g.epi == EPI_BF16) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ob[e] = (__bf16)v[e];
+        *(bf16x8*)((__bf16*)g.out + o) = ob;
+      } else if (g.epi == EPI_RES_F32) {
+        const f32x4 r0 = *(const f32x4*)(g.res + o), r1 = *(const f32x4*)(g.res + o + 4);
+        f32x4 o0, o1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { o0[e] = r0[e] + v[e]; o1[e] = r1[e] + v[4 + e]; }
+        *(f32x4*)((float*)g.out + o) = o0;
+        *(f32x4*)((float*)g.out + o + 4) = o1;
+      } else if (g.epi == EPI_ACT) {
+        bf16x8 oa;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { ob[e] = (__bf16)v[e]; oa[e] = (__bf16)act_fwd(v[e], g.act); }
+        *(bf16x8*)((__bf16*)g.out + o) = ob;
+        *(bf16x8*)((__bf16*)g.out2 + o) = oa;
+      } else if (g.epi == EPI_DACT) {
+        const bf16x8 pv = *(const bf16x8*)(g.pre + o);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ob[e] = (__bf16)(v[e] * act_grad((float)pv[e], g.act));
+        *(bf16x8*)((__bf16*)g.out + o) = ob;
+      } else {
+        float* po = (float*)g.out + (size_t)outer * g.M * g.N + o;
+        *(f32x4*)po = *(const f32x4*)&v[0];
+        *(f32x4*)(po + 4) = *(const f32x4*)&v[4];
       }
     }
   }
@@ -208,13 +269,20 @@ __device__ __forceinline__ int row_len(const RowGeom& q, int u) {
   return l < 0 ? 0 : (l > q.L ? q.L : l);
 }
 
-// x0[r][:] = valid ? H[r][:] : 0   (fp32 copy of the raw tokens: the first block's input)
-__global__ __launch_bounds__(256) void bw_load_x0_kernel(const __bf16* H, float* x0, RowGeom q, int d) {
-  const size_t n = (size_t)q.ntok * d;
+// x0[r][:] = valid ? H[r][:] : 0   (fp32 copy of the raw tokens: the first block's input); four
+// features per thread (d is a multiple of 4)
+__global__ __launch_bounds__(256) void bw_load_x0_kernel(const __bf16* __restrict__ H, float* __restrict__ x0, RowGeom q, int d) {
+  const size_t n = (size_t)q.ntok * d / 4;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
-    const int r = (int)(i / d);
+    const int r = (int)(i * 4 / d);
     const int u = r / q.L, pos = r - u * q.L;
-    x0[i] = pos < row_len(q, u) ? (float)H[i] : 0.f;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (pos < row_len(q, u)) {
+      const bf16x4 t = *(const bf16x4*)(H + i * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (float)t[e];
+    }
+    *(f32x4*)(x0 + i * 4) = v;
   }
 }
 
@@ -224,108 +292,112 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-constexpr int kMaxPerLane = 8;   // widths up to 512
+// LayerNorm kernels: a row of width D = 4 LPR is held by LPR adjacent lanes, four consecutive
+// features each (16-byte loads), so a wave works on 64 / LPR rows at a time.
+template <int LPR>
+__device__ __forceinline__ float row_sum(float v) {
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ f32x4 load_bf16x4(const __bf16* p) {
+  const bf16x4 t = *(const bf16x4*)p;
+  f32x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (float)t[e];
+  return o;
+}
+__device__ __forceinline__ void store_bf16x4(__bf16* p, f32x4 v) {
+  bf16x4 t;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) t[e] = (__bf16)v[e];
+  *(bf16x4*)p = t;
+}
 
-// n[r][:] = bf16(LN(x[r][:]) g + b): one wave per row, lane e holds features e, e + 64, ...
-__global__ __launch_bounds__(256) void bw_ln_fwd_kernel(const float* x, const __bf16* gam, const __bf16* bet,
-                                                        __bf16* out, int ntok, int d, float eps) {
-  const int lane = threadIdx.x & 63;
+// n[r][:] = bf16(LN(x[r][:]) g + b)
+template <int LPR>
+__global__ __launch_bounds__(256) void bw_ln_fwd_kernel(const float* __restrict__ x, const __bf16* __restrict__ gam,
+                                                        const __bf16* __restrict__ bet, __bf16* __restrict__ out,
+                                                        int ntok, float eps) {
+  constexpr int RPW = 64 / LPR, D = 4 * LPR;
+  const int lane = threadIdx.x & 63, sub = lane % LPR, rsub = lane / LPR;
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), nw = gridDim.x * 4;
-  float gv[kMaxPerLane], bv[kMaxPerLane];
-#pragma unroll
-  for (int i = 0; i < kMaxPerLane; ++i) {
-    const int e = lane + 64 * i;
-    gv[i] = e < d ? (float)gam[e] : 0.f;
-    bv[i] = e < d ? (float)bet[e] : 0.f;
-  }
-  for (int r = wave; r < ntok; r += nw) {
-    float v[kMaxPerLane], s = 0.f;
-#pragma unroll
-    for (int i = 0; i < kMaxPerLane; ++i) {
-      const int e = lane + 64 * i;
-      v[i] = e < d ? x[(size_t)r * d + e] : 0.f;
-      s += v[i];
-    }
-    const float mean = wave_sum(s) / d;
-    float s2 = 0.f;
-#pragma unroll
-    for (int i = 0; i < kMaxPerLane; ++i) {
-      const int e = lane + 64 * i;
-      const float c = e < d ? v[i] - mean : 0.f;
-      s2 += c * c;
-    }
-    const float rstd = 1.f / sqrtf(wave_sum(s2) / d + eps);
-#pragma unroll
-    for (int i = 0; i < kMaxPerLane; ++i) {
-      const int e = lane + 64 * i;
-      if (e < d) out[(size_t)r * d + e] = (__bf16)((v[i] - mean) * rstd * gv[i] + bv[i]);
-    }
+  const f32x4 gv = load_bf16x4(gam + 4 * sub), bv = load_bf16x4(bet + 4 * sub);
+  const int ngroups = (ntok + RPW - 1) / RPW;
+#pragma unroll 2
+  for (int grp = wave; grp < ngroups; grp += nw) {
+    const int r = grp * RPW + rsub;
+    const bool ok = r < ntok;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (ok) v = *(const f32x4*)(x + (size_t)r * D + 4 * sub);
+    const float mean = row_sum<LPR>(v[0] + v[1] + v[2] + v[3]) * (1.f / D);
+    v -= mean;
+    const float rstd = 1.f / sqrtf(row_sum<LPR>(v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3]) * (1.f / D) + eps);
+    if (ok) store_bf16x4(out + (size_t)r * D + 4 * sub, v * rstd * gv + bv);
   }
 }
 
 // LayerNorm backward for y = LN(x) g + b with upstream dn = dL/dy (bf16) and the gradient dres that
 // reaches x through the residual connection: dx_out = dres + dLN, also stored as bf16 (dxb, may be
-// NULL); dg[e] += sum_r dn xhat, db[e] += sum_r dn (fp32 atomics, one per wave and feature).
-__global__ __launch_bounds__(256) void bw_ln_bwd_kernel(const __bf16* dn, const float* x, const __bf16* gam,
-                                                        const float* dres, float* dx_out, __bf16* dxb,
-                                                        float* dg, float* db, int ntok, int d, float eps) {
-  const int lane = threadIdx.x & 63;
+// NULL); the block's share of dg[e] = sum_r dn xhat and db[e] = sum_r dn goes to part[block][2][D]
+// (bw_reduce_kernel sums the blocks).
+template <int LPR>
+__global__ __launch_bounds__(256) void bw_ln_bwd_kernel(const __bf16* __restrict__ dn, const float* __restrict__ x,
+                                                        const __bf16* __restrict__ gam, const float* __restrict__ dres,
+                                                        float* __restrict__ dx_out, __bf16* __restrict__ dxb,
+                                                        float* __restrict__ part, int ntok, float eps) {
+  constexpr int RPW = 64 / LPR, D = 4 * LPR;
+  const int lane = threadIdx.x & 63, sub = lane % LPR, rsub = lane / LPR;
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), nw = gridDim.x * 4;
-  float gv[kMaxPerLane], ag[kMaxPerLane], ab[kMaxPerLane];
-#pragma unroll
-  for (int i = 0; i < kMaxPerLane; ++i) {
-    const int e = lane + 64 * i;
-    gv[i] = e < d ? (float)gam[e] : 0.f;
-    ag[i] = 0.f; ab[i] = 0.f;
-  }
-  for (int r = wave; r < ntok; r += nw) {
-    float v[kMaxPerLane], t[kMaxPerLane], s = 0.f;
-#pragma unroll
-    for (int i = 0; i < kMaxPerLane; ++i) {
-      const int e = lane + 64 * i;
-      v[i] = e < d ? x[(size_t)r * d + e] : 0.f;
-      t[i] = e < d ? (float)dn[(size_t)r * d + e] : 0.f;
-      s += v[i];
+  const f32x4 gv = load_bf16x4(gam + 4 * sub);
+  f32x4 ag = {0.f, 0.f, 0.f, 0.f}, ab = {0.f, 0.f, 0.f, 0.f};
+  const int ngroups = (ntok + RPW - 1) / RPW;
+#pragma unroll 2
+  for (int grp = wave; grp < ngroups; grp += nw) {
+    const int r = grp * RPW + rsub;
+    const bool ok = r < ntok;
+    const size_t o = (size_t)r * D + 4 * sub;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f}, t = v, res = v;
+    if (ok) {
+      v = *(const f32x4*)(x + o);
+      t = load_bf16x4(dn + o);
+      res = *(const f32x4*)(dres + o);
     }
-    const float mean = wave_sum(s) / d;
-    float s2 = 0.f;
-#pragma unroll
-    for (int i = 0; i < kMaxPerLane; ++i) {
-      const int e = lane + 64 * i;
-      v[i] = e < d ? v[i] - mean : 0.f;
-      s2 += v[i] * v[i];
-    }
-    const float rstd = 1.f / sqrtf(wave_sum(s2) / d + eps);
-    float c1 = 0.f, c2 = 0.f;     // sum of dn g, sum of dn g xhat
-#pragma unroll
-    for (int i = 0; i < kMaxPerLane; ++i) {
-      v[i] *= rstd;                              // xhat
-      ab[i] += t[i];
-      ag[i] += t[i] * v[i];
-      t[i] *= gv[i];                             // dL/dxhat
-      c1 += t[i];
-      c2 += t[i] * v[i];
-    }
-    c1 = wave_sum(c1) / d;
-    c2 = wave_sum(c2) / d;
-#pragma unroll
-    for (int i = 0; i < kMaxPerLane; ++i) {
-      const int e = lane + 64 * i;
-      if (e < d) {
-        const size_t o = (size_t)r * d + e;
-        const float dx = dres[o] + rstd * (t[i] - c1 - v[i] * c2);
-        dx_out[o] = dx;
-        if (dxb) dxb[o] = (__bf16)dx;
-      }
+    const float mean = row_sum<LPR>(v[0] + v[1] + v[2] + v[3]) * (1.f / D);
+    v -= mean;
+    const float rstd = 1.f / sqrtf(row_sum<LPR>(v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3]) * (1.f / D) + eps);
+    v *= rstd;                                   // xhat
+    ab += t;
+    ag += t * v;
+    t *= gv;                                     // dL/dxhat
+    const float c1 = row_sum<LPR>(t[0] + t[1] + t[2] + t[3]) * (1.f / D);
+    const float c2 = row_sum<LPR>(t[0] * v[0] + t[1] * v[1] + t[2] * v[2] + t[3] * v[3]) * (1.f / D);
+    if (ok) {
+      const f32x4 dx = res + rstd * (t - c1 - v * c2);
+      *(f32x4*)(dx_out + o) = dx;
+      if (dxb) store_bf16x4(dxb + o, dx);
     }
   }
+  // rows handled side by side in the wave, then the block's four waves (LDS)
 #pragma unroll
-  for (int i = 0; i < kMaxPerLane; ++i) {
-    const int e = lane + 64 * i;
-    if (e < d) {
-      unsafeAtomicAdd(dg + e, ag[i]);
-      unsafeAtomicAdd(db + e, ab[i]);
+  for (int e = 0; e < 4; ++e) {
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) {
+      ag[e] += __shfl_xor(ag[e], o, 64);
+      ab[e] += __shfl_xor(ab[e], o, 64);
     }
+  }
+  __shared__ f32x4 red[2][4][LPR];
+  const int wv = threadIdx.x >> 6;
+  if (rsub == 0) {
+    red[0][wv][sub] = ag;
+    red[1][wv][sub] = ab;
+  }
+  __syncthreads();
+  if (threadIdx.x < 2 * LPR) {
+    const int which = threadIdx.x / LPR, c = threadIdx.x % LPR;
+    *(f32x4*)(part + (size_t)blockIdx.x * 2 * D + which * D + 4 * c) =
+        red[which][0][c] + red[which][1][c] + red[which][2][c] + red[which][3][c];
   }
 }
 
@@ -333,25 +405,25 @@ __global__ __launch_bounds__(256) void bw_ln_bwd_kernel(const __bf16* dn, const 
 //   mean:   dZ[r][:] = dM[u][t][:] / n_{u,t} for the group's n valid tokens;
 //   concat: dZ[r][:] = dM[u][t][j d : (j + 1) d] for the token in slot j of its group;
 // zeros for padded tokens.  Written as fp32 and as bf16.
-__global__ __launch_bounds__(256) void bw_merge_bwd_kernel(const float* dM, float* dy, __bf16* dyb, RowGeom q,
-                                                           int d, int T, int concat) {
-  const size_t n = (size_t)q.ntok * d;
+__global__ __launch_bounds__(256) void bw_merge_bwd_kernel(const float* __restrict__ dM, float* __restrict__ dy,
+                                                           __bf16* __restrict__ dyb, RowGeom q, int d, int T, int concat) {
+  const size_t n = (size_t)q.ntok * d / 4;      // four features per thread
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
-    const int r = (int)(i / d), e = (int)(i - (size_t)r * d);
+    const int r = (int)(i * 4 / d), e = (int)(i * 4 - (size_t)r * d);
     const int u = r / q.L, pos = r - u * q.L;
     const int len = row_len(q, u);
-    float v = 0.f;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
     if (pos < len) {
       const int t = pos / q.K, j = pos - t * q.K;
       if (concat) {
-        v = dM[((size_t)u * T + t) * ((size_t)q.K * d) + (size_t)j * d + e];
+        v = *(const f32x4*)(dM + ((size_t)u * T + t) * ((size_t)q.K * d) + (size_t)j * d + e);
       } else {
         const int cnt = min(q.K, len - t * q.K);
-        v = dM[((size_t)u * T + t) * d + e] / (float)cnt;
+        v = *(const f32x4*)(dM + ((size_t)u * T + t) * d + e) / (float)cnt;
       }
     }
-    dy[i] = v;
-    dyb[i] = (__bf16)v;
+    *(f32x4*)(dy + i * 4) = v;
+    store_bf16x4(dyb + i * 4, v);
   }
 }
 
@@ -573,6 +645,34 @@ __global__ __launch_bounds__(256) void bw_concat_qkv_kernel(const __bf16* wq, co
   }
 }
 
+// out[i] += sum over the slices s of part[s][i], i < count (count a multiple of 4; out starts at zero).
+// Thread (x, y) of a 64 x 4 block sums every fourth slice of four adjacent outputs inside the block's
+// share of the slices (blockIdx.y of gridDim.y shares), the four partial sums meet in LDS, and the
+// block adds its sum with one atomic per output (a plain store when there is one share).
+__global__ __launch_bounds__(256) void bw_reduce_kernel(const float* __restrict__ part, int nsplit, int count, float* out) {
+  __shared__ f32x4 red[4][64];
+  const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
+  const int i = (blockIdx.x * 64 + x) * 4;
+  const int per = (nsplit + gridDim.y - 1) / gridDim.y;
+  const int s0 = blockIdx.y * per, s1 = min(nsplit, s0 + per);
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+  if (i < count) {
+#pragma unroll 4
+    for (int sl = s0 + y; sl < s1; sl += 4) s += *(const f32x4*)(part + (size_t)sl * count + i);
+  }
+  red[y][x] = s;
+  __syncthreads();
+  if (y == 0 && i < count) {
+    const f32x4 t = red[0][x] + red[1][x] + red[2][x] + red[3][x];
+    if (gridDim.y == 1) {
+      *(f32x4*)(out + i) = t;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) unsafeAtomicAdd(out + i + e, t[e]);
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void bw_zero_kernel(float* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
 }
@@ -595,14 +695,19 @@ static GradLayout grad_layout(int d, int f) {
   g.w1 = take((size_t)d * f); g.b1 = take(f);
   g.w2 = take((size_t)f * d); g.b2 = take(d);
   g.total = o;
-  return g;
+  return g;      // ln*_b follows ln*_g directly: ln_bwd writes the two as one vector
 }
+
+// tiles x slices of a split GEMM <= kMaxPartials, each a 128 x 128 fp32 tile
+constexpr int kMaxPartials = 512;
+constexpr size_t kPartialBytes = (size_t)kMaxPartials * 128 * 128 * 4;
 
 struct Workspace {
   size_t wcat, bcat;                       // per layer: [d][3d] bf16, [3d] bf16
   size_t xin;                              // per layer: fp32 [ntok][d]
   size_t n1, qkv, o, xmid, n2, h, a;       // one block's recomputed intermediates
   size_t dy, dyb, dh, dn, dxm, dxmb, dob, dqkv, stat;
+  size_t part;                             // partial parameter gradients of one split GEMM
   size_t total;
 };
 static Workspace workspace(int layers, size_t ntok, int d, int f, int heads) {
@@ -628,6 +733,7 @@ static Workspace workspace(int layers, size_t ntok, int d, int f, int heads) {
   w.dob = take(ntok * d * 2);
   w.dqkv = take(ntok * 3 * d * 2);
   w.stat = take(ntok * heads * 8);
+  w.part = take(kPartialBytes);
   w.total = o;
   return w;
 }
@@ -646,7 +752,7 @@ static int check(const longer_config* c, int B, int L, Dims* s) {
     if (d % c->K) return api_error(LONGER_ERR_ARG, "concat merge: K=%d must divide d=%d", c->K, d);
     d /= c->K;
   }
-  if (d % 32 || d > 64 * kMaxPerLane) return api_error(LONGER_ERR_ARG, "InnerTrans width %d must be a multiple of 32, at most %d", d, 64 * kMaxPerLane);
+  if (d != 32 && d != 64 && d != 128 && d != 256) return api_error(LONGER_ERR_ARG, "InnerTrans width %d unsupported (32, 64, 128 or 256)", d);
   if (c->inner_layers <= 0 || c->inner_layers > 32) return api_error(LONGER_ERR_ARG, "inner_layers=%d out of range", c->inner_layers);
   if (c->inner_heads <= 0 || d % c->inner_heads) return api_error(LONGER_ERR_ARG, "inner_heads=%d must divide the InnerTrans width %d", c->inner_heads, d);
   const int dh = d / c->inner_heads;
@@ -668,9 +774,19 @@ static int launched(const char* what) {
   return hipGetLastError() == hipSuccess ? 0 : api_error(LONGER_ERR_HIP, "%s launch failed", what);
 }
 
+static int reduce(hipStream_t st, const float* part, int nsplit, int count, float* out) {
+  int shares = nsplit / 32;                 // at least 32 slices per block
+  shares = shares < 1 ? 1 : (shares > 64 ? 64 : shares);
+  bw_reduce_kernel<<<dim3((count / 4 + 63) / 64, shares), 256, 0, st>>>(part, nsplit, count, out);
+  return launched("gradient reduction");
+}
+
 static int gemm(hipStream_t st, bool a_kc, bool b_kc, GemmArgs g, int splits) {
   if (!aligned16(g.A) || !aligned16(g.B) || g.lda % 8 || g.ldb % 8) return api_error(LONGER_ERR_ARG, "backward GEMM operand misaligned");
-  dim3 grid((g.M + 127) / 128, (g.N + 127) / 128, splits);
+  const int ntm = (g.M + 127) / 128, ntn = (g.N + 127) / 128;
+  g.nsplit = splits;
+  const int outer = g.epi == EPI_PARTIAL ? splits : ntm, inner = g.epi == EPI_PARTIAL ? ntm * ntn : ntn;
+  dim3 grid((unsigned)(((outer + 7) / 8) * 8 * inner));            // see the tile order in the kernel
   if (a_kc && b_kc) bw_gemm_kernel<true, true><<<grid, 256, 0, st>>>(g);
   else if (a_kc && !b_kc) bw_gemm_kernel<true, false><<<grid, 256, 0, st>>>(g);
   else if (!a_kc && !b_kc) bw_gemm_kernel<false, false><<<grid, 256, 0, st>>>(g);
@@ -694,19 +810,44 @@ static int gemm_rows_t(hipStream_t st, const __bf16* dy, int kc, const __bf16* W
   g.epi = epi; g.act = act; g.out = out; g.ldo = n; g.pre = pre;
   return gemm(st, true, true, g, 1);
 }
-// dW [m][n] += x^T dy: x [ntok][.. m columns, pitch lda], dy [ntok][.. n columns, pitch ldb]
-static int gemm_wgrad(hipStream_t st, const __bf16* x, int lda, int m, const __bf16* dy, int ldb, int n, size_t ntok, float* dW) {
+// dW [m][n] = x^T dy: x [ntok][.. m columns, pitch lda], dy [ntok][.. n columns, pitch ldb]
+static int gemm_wgrad(hipStream_t st, const __bf16* x, int lda, int m, const __bf16* dy, int ldb, int n, size_t ntok,
+                      float* part, float* dW) {
   GemmArgs g = {};
   g.A = x; g.lda = lda; g.B = dy; g.ldb = ldb; g.M = m; g.N = n; g.Kc = (int)ntok;
   const int tiles = ((m + 127) / 128) * ((n + 127) / 128);
-  int splits = 2048 / tiles;
+  if (tiles > kMaxPartials) return api_error(LONGER_ERR_ARG, "parameter matrix %d x %d too large for the backward pass", m, n);
+  int splits = kMaxPartials / tiles;
   const int most = (int)((ntok + 255) / 256);
   if (splits > most) splits = most;
-  if (splits < 1) splits = 1;
   g.kslice = (int)(((ntok + splits - 1) / splits + 31) / 32 * 32);
   splits = (int)((ntok + g.kslice - 1) / g.kslice);
-  g.epi = EPI_ATOMIC; g.out = dW; g.ldo = n;
-  return gemm(st, false, false, g, splits);
+  g.epi = EPI_PARTIAL; g.out = part; g.ldo = n;
+  int rc = gemm(st, false, false, g, splits);
+  if (rc) return rc;
+  return reduce(st, part, splits, m * n, dW);
+}
+
+static void ln_fwd(hipStream_t st, unsigned grid, int d, const float* x, const __bf16* g, const __bf16* b, __bf16* out,
+                   int ntok, float eps) {
+  switch (d) {
+    case 32: bw_ln_fwd_kernel<8><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps); break;
+    case 64: bw_ln_fwd_kernel<16><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps); break;
+    case 128: bw_ln_fwd_kernel<32><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps); break;
+    default: bw_ln_fwd_kernel<64><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps); break;
+  }
+}
+// dgb: the gain gradient [d] followed directly by the shift gradient [d]
+static int ln_bwd(hipStream_t st, unsigned grid, int d, const __bf16* dn, const float* x, const __bf16* g, const float* dres,
+                  float* dx, __bf16* dxb, float* part, float* dgb, int ntok, float eps) {
+  switch (d) {
+    case 32: bw_ln_bwd_kernel<8><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
+    case 64: bw_ln_bwd_kernel<16><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
+    case 128: bw_ln_bwd_kernel<32><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
+    default: bw_ln_bwd_kernel<64><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
+  }
+  if (hipGetLastError() != hipSuccess) return api_error(LONGER_ERR_HIP, "LayerNorm backward launch failed");
+  return reduce(st, part, (int)grid, 2 * d, dgb);
 }
 
 static int colsum(hipStream_t st, const __bf16* G, int pitch, int W, size_t ntok, float* out) {
@@ -738,7 +879,8 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
   __bf16* dh = (__bf16*)(ws + w.dh);   __bf16* dn = (__bf16*)(ws + w.dn);   float* dxm = (float*)(ws + w.dxm);
   __bf16* dxmb = (__bf16*)(ws + w.dxmb); __bf16* dob = (__bf16*)(ws + w.dob); __bf16* dqkv = (__bf16*)(ws + w.dqkv);
   float2* stat = (float2*)(ws + w.stat);
-  const unsigned ln_grid = (unsigned)((nt + 3) / 4 > 4096 ? 4096 : (nt + 3) / 4);
+  float* part = (float*)(ws + w.part);
+  const unsigned ln_grid = (unsigned)((nt + 3) / 4 > 4096 ? 4096 : (nt + 3) / 4);   // 4096 x 2 x 256 floats fit `part`
   const unsigned ah_grid = (unsigned)((nt * s.heads + 255) / 256);
 
   bw_zero_kernel<<<flat_grid(gl.total * s.layers), 256, 0, st>>>(grads, gl.total * s.layers);
@@ -749,7 +891,7 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
                                              (const __bf16*)b.bk, (const __bf16*)b.bv, wcat(l), bcat(l), d);
     BW_TRY(launched("weight concatenation"));
   }
-  bw_load_x0_kernel<<<flat_grid(nt * d), 256, 0, st>>>((const __bf16*)H, xin(0), q, d);
+  bw_load_x0_kernel<<<flat_grid(nt * d / 4), 256, 0, st>>>((const __bf16*)H, xin(0), q, d);
   BW_TRY(launched("input load"));
 
   // one block forward from its input x: intermediates into the workspace, output (fp32) into y_out
@@ -757,14 +899,14 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
   auto forward = [&](int l, float* y_out) -> int {
     const longer_block& b = inner[l];
     const float* x = xin(l);
-    bw_ln_fwd_kernel<<<ln_grid, 256, 0, st>>>(x, (const __bf16*)b.ln1_g, (const __bf16*)b.ln1_b, n1, (int)nt, d, c->ln_eps);
+    ln_fwd(st, ln_grid, d, x, (const __bf16*)b.ln1_g, (const __bf16*)b.ln1_b, n1, (int)nt, c->ln_eps);
     BW_TRY(launched("LayerNorm"));
     BW_TRY(gemm_rows(st, n1, d, wcat(l), 3 * d, nt, EPI_BF16, 0, qkv, nullptr, bcat(l), nullptr, nullptr));
     if (s.dh == 16) bw_attn_fwd_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, o, q, d, s.heads);
     else bw_attn_fwd_kernel<32><<<ah_grid, 256, 0, st>>>(qkv, o, q, d, s.heads);
     BW_TRY(launched("group attention"));
     BW_TRY(gemm_rows(st, o, d, (const __bf16*)b.wo, d, nt, EPI_RES_F32, 0, xmid, nullptr, (const __bf16*)b.bo, x, nullptr));
-    bw_ln_fwd_kernel<<<ln_grid, 256, 0, st>>>(xmid, (const __bf16*)b.ln2_g, (const __bf16*)b.ln2_b, n2, (int)nt, d, c->ln_eps);
+    ln_fwd(st, ln_grid, d, xmid, (const __bf16*)b.ln2_g, (const __bf16*)b.ln2_b, n2, (int)nt, c->ln_eps);
     BW_TRY(launched("LayerNorm"));
     BW_TRY(gemm_rows(st, n2, d, (const __bf16*)b.w1, f, nt, EPI_ACT, c->act, h, a, (const __bf16*)b.b1, nullptr, nullptr));
     if (y_out)
@@ -775,7 +917,7 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
   // the chain of block inputs (recomputed: nothing is kept from a forward call)
   for (int l = 0; l + 1 < s.layers; ++l) BW_TRY(forward(l, xin(l + 1)));
 
-  bw_merge_bwd_kernel<<<flat_grid(nt * d), 256, 0, st>>>(dM, dy, dyb, q, d, s.T, c->merge == LONGER_MERGE_CONCAT);
+  bw_merge_bwd_kernel<<<flat_grid(nt * d / 4), 256, 0, st>>>(dM, dy, dyb, q, d, s.T, c->merge == LONGER_MERGE_CONCAT);
   BW_TRY(launched("merge gradient"));
 
   for (int l = s.layers - 1; l >= 0; --l) {
@@ -783,17 +925,15 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     float* g = grads + (size_t)l * gl.total;
     BW_TRY(forward(l, nullptr));                 // this block's intermediates, from its input alone
     // FFN: y = xmid + act(n2 W1 + b1) W2 + b2
-    BW_TRY(gemm_wgrad(st, a, f, f, dyb, d, d, nt, g + gl.w2));
+    BW_TRY(gemm_wgrad(st, a, f, f, dyb, d, d, nt, part, g + gl.w2));
     BW_TRY(colsum(st, dyb, d, d, nt, g + gl.b2));
     BW_TRY(gemm_rows_t(st, dyb, d, (const __bf16*)b.w2, f, nt, EPI_DACT, c->act, dh, h));
-    BW_TRY(gemm_wgrad(st, n2, d, d, dh, f, f, nt, g + gl.w1));
+    BW_TRY(gemm_wgrad(st, n2, d, d, dh, f, f, nt, part, g + gl.w1));
     BW_TRY(colsum(st, dh, f, f, nt, g + gl.b1));
     BW_TRY(gemm_rows_t(st, dh, f, (const __bf16*)b.w1, d, nt, EPI_BF16, 0, dn, nullptr));
-    bw_ln_bwd_kernel<<<ln_grid, 256, 0, st>>>(dn, xmid, (const __bf16*)b.ln2_g, dy, dxm, dxmb, g + gl.ln2_g, g + gl.ln2_b,
-                                              (int)nt, d, c->ln_eps);
-    BW_TRY(launched("LayerNorm backward"));
+    BW_TRY(ln_bwd(st, ln_grid, d, dn, xmid, (const __bf16*)b.ln2_g, dy, dxm, dxmb, part, g + gl.ln2_g, (int)nt, c->ln_eps));
     // attention: xmid = x + att W_O + b_O
-    BW_TRY(gemm_wgrad(st, o, d, d, dxmb, d, d, nt, g + gl.wo));
+    BW_TRY(gemm_wgrad(st, o, d, d, dxmb, d, d, nt, part, g + gl.wo));
     BW_TRY(colsum(st, dxmb, d, d, nt, g + gl.bo));
     BW_TRY(gemm_rows_t(st, dxmb, d, (const __bf16*)b.wo, d, nt, EPI_BF16, 0, dob, nullptr));
     if (s.dh == 16) {
@@ -806,15 +946,14 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     BW_TRY(launched("group attention backward"));
     const size_t wofs[3] = {gl.wq, gl.wk, gl.wv}, bofs[3] = {gl.bq, gl.bk, gl.bv};
     for (int j = 0; j < 3; ++j) {
-      BW_TRY(gemm_wgrad(st, n1, d, d, dqkv + (size_t)j * d, 3 * d, d, nt, g + wofs[j]));
+      BW_TRY(gemm_wgrad(st, n1, d, d, dqkv + (size_t)j * d, 3 * d, d, nt, part, g + wofs[j]));
       BW_TRY(colsum(st, dqkv + (size_t)j * d, 3 * d, d, nt, g + bofs[j]));
     }
     BW_TRY(gemm_rows_t(st, dqkv, 3 * d, wcat(l), d, nt, EPI_BF16, 0, dn, nullptr));
     // the gradient of this block's input is the upstream gradient of the block before it
     float* dx = l ? dy : dH;
-    bw_ln_bwd_kernel<<<ln_grid, 256, 0, st>>>(dn, xin(l), (const __bf16*)b.ln1_g, dxm, dx, l ? dyb : nullptr,
-                                              g + gl.ln1_g, g + gl.ln1_b, (int)nt, d, c->ln_eps);
-    BW_TRY(launched("LayerNorm backward"));
+    BW_TRY(ln_bwd(st, ln_grid, d, dn, xin(l), (const __bf16*)b.ln1_g, dxm, dx, l ? dyb : nullptr, part, g + gl.ln1_g,
+                  (int)nt, c->ln_eps));
   }
   return 0;
 }
