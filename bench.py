@@ -129,14 +129,20 @@ def run_merge_backward(lg, torch, cfg, case, steps):
         lg.longer_token_merge_backward(model.ccfg, model.inner, H, lens, B, L, dM, dH, grads, ws)
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
-    fl = flops.forward_flops(cfg, None if case["lens"] is None else case["lens"])
-    grad_gflop = 2.0 * fl["inner"] / 1e9          # d/d input and d/d parameter of every forward product
+    work = flops.merge_backward_work(cfg, None if case["lens"] is None else case["lens"])
+    grad_gflop = work["gradient_flops"] / 1e9     # d/d input and d/d parameter of every forward product
     return {"workload": "%s: longer_token_merge_backward, B=%d users, L=%d, InnerTrans width %d, %d block(s), K=%d"
                         % (cfg.name, B, L, cfg.d_in, cfg.inner_layers, cfg.K),
             "ms_per_step": ms, "steps": steps, "user_sequences_per_s": B / (ms * 1e-3),
             "gradient_gflop_per_step": grad_gflop,
             "recompute": "block inputs and every block's intermediates, from the raw tokens",
+            "recompute_gflop_per_step": work["recompute_flops"] / 1e9,
             "mfma_peak_frac_gradient_flops": grad_gflop / 1e3 / (ms * 1e-3) / PEAK_BF16_TFLOPS,
+            "roofline": {"bound": "hbm", "achieved": work["hbm_bytes"] / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                         "frac": work["hbm_bytes"] / (ms * 1e-3) / 1e9 / 8000.0,
+                         "bytes_per_step": work["hbm_bytes"],
+                         "note": "unfused pass: every activation makes one trip through memory per use (tally in "
+                                 "paper_2505_04421_amd/flops.py)"},
             "workspace_bytes": n_ws}
 
 

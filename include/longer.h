@@ -265,10 +265,11 @@ const char* longer_last_error(void);
  *     w2 [f, w], b2 [w], f = ffn_mult * w), summed over all users of the batch; overwritten, not
  *     accumulated into.
  * ws: device scratch of at least longer_backward_workspace_bytes(cfg, B, L), 256-byte aligned; all
- * pointers (parameters included) 16-byte aligned.  Supports head width 16 or 32, w a multiple of 32
- * up to 512, f <= 2048.  Parameter gradients are accumulated with fp32 atomics, so their last bits
- * depend on the order in which workgroups finish.  Same stream, error and ownership rules as the
- * forward entry points; returns 0 from both size queries for an unsupported configuration. */
+ * pointers (parameters included) 16-byte aligned.  Supports head width 16 or 32, w one
+ * of 32, 64, 128 or 256, f <= 2048.  A parameter gradient is a sum over the batch: slices of the
+ * tokens are summed in a fixed order, the last step adds up to 64 such partial sums with fp32 atomics,
+ * so the last bits may differ between two calls.  Same stream, error and ownership rules as the forward
+ * entry points; both size queries return 0 for an unsupported configuration. */
 size_t longer_backward_workspace_bytes(const longer_config* cfg, int B, int L);
 size_t longer_block_grad_floats(const longer_config* cfg);
 int longer_token_merge_backward(const longer_config* cfg, const longer_block* inner, const void* H,

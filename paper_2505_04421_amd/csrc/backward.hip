@@ -16,8 +16,8 @@
 //   * one bf16 MFMA GEMM (bw_gemm_kernel) whose operands may each be stored with the
 //     contraction index contiguous or strided, which covers y = x W (+ epilogues),
 //     dx = dy W^T and dW = x^T dy (cut into slices of tokens whose partial results a second kernel sums);
-//   * row kernels: LayerNorm forward / backward (+ gain / shift gradients), pooling backward,
-//     column sums (bias gradients);
+//   * row kernels: LayerNorm forward / backward (+ gain / shift gradients), pooling backward
+//     (bias gradients are column sums, taken by the dW GEMM as one more product with a row of ones);
 //   * the attention inside a group of K tokens, forward and backward, one thread per
 //     (token, head): the groups are tiny (K x K scores per head), so this is plain fp32 code.
 #include "../../include/longer.h"
@@ -47,7 +47,7 @@ enum Epilogue {
   EPI_RES_F32 = 1,   // outf[m][n] = res[m][n] + acc + bias[n]
   EPI_ACT = 2,       // out[m][n] = bf16(v), out2[m][n] = bf16(act(v)), v = acc + bias[n]
   EPI_DACT = 3,      // out[m][n] = bf16(acc * act'(pre[m][n]))
-  EPI_PARTIAL = 4    // parameter gradients: the contraction (over the tokens) is cut into slices, one workgroup
+  EPI_PARTIAL = 4    // parameter gradients (out2, if given: [slice][n] column sums of B, the bias gradient's partials): the contraction (over the tokens) is cut into slices, one workgroup
                      // per tile and slice; outf[slice][m][n] = acc, summed afterwards by bw_reduce_kernel
 };
 
@@ -88,10 +88,11 @@ __device__ __forceinline__ float act_grad(float v, int act) {
 
 constexpr int kPitchKC = 40;            // elements per row of a contraction-contiguous LDS tile (32 + 8 pad)
 constexpr int kTileElems = 128 * kPitchKC;   // >= 32 * 128 of the strided form
+constexpr int kDepth = 1;               // contraction steps whose global loads are in flight (more costs registers, and occupancy matters more)
 constexpr int kStagePitch = 68;         // floats per row of the epilogue's staging area (64 + 4 pad)
 
 template <bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256) void bw_gemm_kernel(GemmArgs g) {
+__global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(16))) __bf16 smem[4 * kTileElems];
   auto sA = [&](int buf) { return smem + buf * kTileElems; };          // two buffers per operand
   auto sB = [&](int buf) { return smem + (2 + buf) * kTileElems; };
@@ -121,9 +122,24 @@ __global__ __launch_bounds__(256) void bw_gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  bf16x8 ra[2], rb[2];
-  // one operand tile = 512 chunks of 16 bytes, two per thread
-  auto gload = [&](int kt) {
+  // Split GEMM with a bias gradient asked for (out2): the column sums of B over the slice are one more
+  // product, ones[32, Kc] B, taken by the waves that hold the first 32 rows of the first M tile;
+  // every row of its result is the column sum.
+  const bool bias_sum = split && g.out2 != nullptr && mt == 0 && wm == 0;
+  f32x16 accb[2];
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.f;
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) accb[b][r] = 0.f;
+
+  // Operand tiles travel global -> registers -> LDS.  One tile = 512 chunks of 16 bytes, two per
+  // thread; the loads of kDepth contraction steps are in flight at once (a step's eight MFMAs per wave
+  // are far shorter than a load's latency), in a register ring indexed statically.
+  bf16x8 ra[kDepth][2], rb[kDepth][2];
+  auto gload = [&](int kt, bf16x8* pa, bf16x8* pb) {
     const int k0 = kbeg + kt * 32;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -131,35 +147,35 @@ __global__ __launch_bounds__(256) void bw_gemm_kernel(GemmArgs g) {
       bf16x8 z;
 #pragma unroll
       for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.f;
-      ra[i] = z; rb[i] = z;
+      pa[i] = z; pb[i] = z;
       if (A_KC) {
         const int row = c >> 2, kc = c & 3;
         const int gr = m0 + row, gk = k0 + 8 * kc;
-        if (gr < g.M && gk < kend) ra[i] = *(const bf16x8*)(g.A + (size_t)gr * g.lda + gk);
+        if (gr < g.M && gk < kend) pa[i] = *(const bf16x8*)(g.A + (size_t)gr * g.lda + gk);
       } else {
         const int kr = c >> 4, xc = c & 15;
         const int gk = k0 + kr, gx = m0 + 8 * xc;
-        if (gk < kend && gx < g.M) ra[i] = *(const bf16x8*)(g.A + (size_t)gk * g.lda + gx);
+        if (gk < kend && gx < g.M) pa[i] = *(const bf16x8*)(g.A + (size_t)gk * g.lda + gx);
       }
       if (B_KC) {
         const int row = c >> 2, kc = c & 3;
         const int gr = n0 + row, gk = k0 + 8 * kc;
-        if (gr < g.N && gk < kend) rb[i] = *(const bf16x8*)(g.B + (size_t)gr * g.ldb + gk);
+        if (gr < g.N && gk < kend) pb[i] = *(const bf16x8*)(g.B + (size_t)gr * g.ldb + gk);
       } else {
         const int kr = c >> 4, xc = c & 15;
         const int gk = k0 + kr, gx = n0 + 8 * xc;
-        if (gk < kend && gx < g.N) rb[i] = *(const bf16x8*)(g.B + (size_t)gk * g.ldb + gx);
+        if (gk < kend && gx < g.N) pb[i] = *(const bf16x8*)(g.B + (size_t)gk * g.ldb + gx);
       }
     }
   };
-  auto sstore = [&](int buf) {
+  auto sstore = [&](int buf, const bf16x8* pa, const bf16x8* pb) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int c = tid + 256 * i;
-      if (A_KC) *(bf16x8*)&sA(buf)[(c >> 2) * kPitchKC + 8 * (c & 3)] = ra[i];
-      else      *(bf16x8*)&sA(buf)[(c >> 4) * 128 + 8 * (c & 15)] = ra[i];
-      if (B_KC) *(bf16x8*)&sB(buf)[(c >> 2) * kPitchKC + 8 * (c & 3)] = rb[i];
-      else      *(bf16x8*)&sB(buf)[(c >> 4) * 128 + 8 * (c & 15)] = rb[i];
+      if (A_KC) *(bf16x8*)&sA(buf)[(c >> 2) * kPitchKC + 8 * (c & 3)] = pa[i];
+      else      *(bf16x8*)&sA(buf)[(c >> 4) * 128 + 8 * (c & 15)] = pa[i];
+      if (B_KC) *(bf16x8*)&sB(buf)[(c >> 2) * kPitchKC + 8 * (c & 3)] = pb[i];
+      else      *(bf16x8*)&sB(buf)[(c >> 4) * 128 + 8 * (c & 15)] = pb[i];
     }
   };
   // fragment of the 32 x 16 operand slice: lane (x = l32, hi) holds contraction slots 8 hi .. 8 hi + 7
@@ -174,36 +190,49 @@ __global__ __launch_bounds__(256) void bw_gemm_kernel(GemmArgs g) {
     return f;
   };
 
-  if (nk > 0) {
-    gload(0);
-    sstore(0);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) gload(kt + 1);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 fa[2], fb[2];
+  for (int p = 0; p < kDepth; ++p)
+    if (p < nk) gload(p, ra[p], rb[p]);
+  // step kt: its tile goes to LDS buffer kt & 1 (last read in step kt - 2, which every thread left before
+  // the barrier of step kt - 1), the ring slot is refilled with step kt + kDepth, barrier, MFMAs
+  for (int kt0 = 0; kt0 < nk; kt0 += kDepth) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        fa[t] = frag(sA(buf), A_KC, 64 * wm + 32 * t + l32, ks);
-        fb[t] = frag(sB(buf), B_KC, 64 * wn + 32 * t + l32, ks);
+    for (int p = 0; p < kDepth; ++p) {
+      const int kt = kt0 + p;
+      if (kt < nk) {
+        const int buf = kt & 1;
+        sstore(buf, ra[p], rb[p]);
+        if (kt + kDepth < nk) gload(kt + kDepth, ra[p], rb[p]);
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          bf16x8 fa[2], fb[2];
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            fa[t] = frag(sA(buf), A_KC, 64 * wm + 32 * t + l32, ks);
+            fb[t] = frag(sB(buf), B_KC, 64 * wn + 32 * t + l32, ks);
+          }
+#pragma unroll
+          for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+          if (!A_KC && !B_KC && bias_sum) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b) accb[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fb[b], accb[b], 0, 0, 0);
+          }
+        }
       }
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
     }
-    if (kt + 1 < nk) sstore(buf ^ 1);
-    __syncthreads();
   }
 
-  // epilogue: acc[a][b][r] = C[m0 + 64 wm + 32 a + tile_row(r, hi)][n0 + 64 wn + 32 b + l32].  Each wave
-  // turns its 64 x 64 result, 32 rows at a time, through a private LDS area (the operand buffers are
-  // free after the loop's last barrier) so that a lane reads and writes 8 consecutive columns of a
-  // row: 16-byte accesses, 8 lanes per row.
+  if (!A_KC && !B_KC && bias_sum && hi == 0) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int n = n0 + 64 * wn + 32 * b + l32;
+      if (n < g.N) ((float*)g.out2)[(size_t)outer * g.N + n] = accb[b][0];     // row 0 of the ones product
+    }
+  }
   float* stage = (float*)smem + w * (32 * kStagePitch);
   static_assert(4 * 32 * kStagePitch * 4 <= 4 * kTileElems * 2, "staging area fits the operand buffers");
 #pragma unroll
@@ -424,41 +453,6 @@ __global__ __launch_bounds__(256) void bw_merge_bwd_kernel(const float* __restri
     }
     *(f32x4*)(dy + i * 4) = v;
     store_bf16x4(dyb + i * 4, v);
-  }
-}
-
-// out[c] += sum over rows of G[r * pitch + c], c < W (W a multiple of 8): bias gradients.
-__global__ __launch_bounds__(256) void bw_colsum_kernel(const __bf16* G, int pitch, int W, int ntok, int rows_per_block,
-                                                        float* out) {
-  __shared__ float red[256 * 8];
-  const int nch = W / 8;                   // 16-byte chunks per row
-  const int rl = 256 / nch;                // rows handled side by side
-  const int ch = threadIdx.x % nch, rlane = threadIdx.x / nch;
-  float s[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) s[e] = 0.f;
-  const int rbeg = blockIdx.x * rows_per_block, rend = min(ntok, rbeg + rows_per_block);
-  if (rlane < rl) {
-    for (int r = rbeg + rlane; r < rend; r += rl) {
-      const bf16x8 v = *(const bf16x8*)(G + (size_t)r * pitch + 8 * ch);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) s[e] += (float)v[e];
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < 8; ++e) red[threadIdx.x * 8 + e] = s[e];
-  __syncthreads();
-  if (threadIdx.x < W) {
-    const int c = threadIdx.x;               // column c: chunk c / 8, element c % 8
-    float t = 0.f;
-    for (int k = 0; k < rl; ++k) t += red[(k * nch + c / 8) * 8 + (c & 7)];
-    unsafeAtomicAdd(out + c, t);
-  }
-  // columns 256 .. W - 1 (W up to 2048)
-  for (int c = threadIdx.x + 256; c < W; c += 256) {
-    float t = 0.f;
-    for (int k = 0; k < rl; ++k) t += red[(k * nch + c / 8) * 8 + (c & 7)];
-    unsafeAtomicAdd(out + c, t);
   }
 }
 
@@ -707,7 +701,7 @@ struct Workspace {
   size_t xin;                              // per layer: fp32 [ntok][d]
   size_t n1, qkv, o, xmid, n2, h, a;       // one block's recomputed intermediates
   size_t dy, dyb, dh, dn, dxm, dxmb, dob, dqkv, stat;
-  size_t part;                             // partial parameter gradients of one split GEMM
+  size_t part, bpart;                      // partial parameter gradients of one split GEMM (matrix, bias)
   size_t total;
 };
 static Workspace workspace(int layers, size_t ntok, int d, int f, int heads) {
@@ -734,6 +728,7 @@ static Workspace workspace(int layers, size_t ntok, int d, int f, int heads) {
   w.dqkv = take(ntok * 3 * d * 2);
   w.stat = take(ntok * heads * 8);
   w.part = take(kPartialBytes);
+  w.bpart = take((size_t)kMaxPartials * 2048 * 4);
   w.total = o;
   return w;
 }
@@ -811,8 +806,9 @@ static int gemm_rows_t(hipStream_t st, const __bf16* dy, int kc, const __bf16* W
   return gemm(st, true, true, g, 1);
 }
 // dW [m][n] = x^T dy: x [ntok][.. m columns, pitch lda], dy [ntok][.. n columns, pitch ldb]
+// and db [n] = column sums of dy
 static int gemm_wgrad(hipStream_t st, const __bf16* x, int lda, int m, const __bf16* dy, int ldb, int n, size_t ntok,
-                      float* part, float* dW) {
+                      float* part, float* bpart, float* dW, float* db) {
   GemmArgs g = {};
   g.A = x; g.lda = lda; g.B = dy; g.ldb = ldb; g.M = m; g.N = n; g.Kc = (int)ntok;
   const int tiles = ((m + 127) / 128) * ((n + 127) / 128);
@@ -822,10 +818,12 @@ static int gemm_wgrad(hipStream_t st, const __bf16* x, int lda, int m, const __b
   if (splits > most) splits = most;
   g.kslice = (int)(((ntok + splits - 1) / splits + 31) / 32 * 32);
   splits = (int)((ntok + g.kslice - 1) / g.kslice);
-  g.epi = EPI_PARTIAL; g.out = part; g.ldo = n;
+  g.epi = EPI_PARTIAL; g.out = part; g.out2 = bpart; g.ldo = n;
   int rc = gemm(st, false, false, g, splits);
   if (rc) return rc;
-  return reduce(st, part, splits, m * n, dW);
+  rc = reduce(st, part, splits, m * n, dW);
+  if (rc) return rc;
+  return reduce(st, bpart, splits, n, db);
 }
 
 static void ln_fwd(hipStream_t st, unsigned grid, int d, const float* x, const __bf16* g, const __bf16* b, __bf16* out,
@@ -848,12 +846,6 @@ static int ln_bwd(hipStream_t st, unsigned grid, int d, const __bf16* dn, const 
   }
   if (hipGetLastError() != hipSuccess) return api_error(LONGER_ERR_HIP, "LayerNorm backward launch failed");
   return reduce(st, part, (int)grid, 2 * d, dgb);
-}
-
-static int colsum(hipStream_t st, const __bf16* G, int pitch, int W, size_t ntok, float* out) {
-  const int rows = 1024;
-  bw_colsum_kernel<<<(unsigned)((ntok + rows - 1) / rows), 256, 0, st>>>(G, pitch, W, (int)ntok, rows, out);
-  return launched("column sum");
 }
 
 static unsigned flat_grid(size_t n) {
@@ -880,6 +872,7 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
   __bf16* dxmb = (__bf16*)(ws + w.dxmb); __bf16* dob = (__bf16*)(ws + w.dob); __bf16* dqkv = (__bf16*)(ws + w.dqkv);
   float2* stat = (float2*)(ws + w.stat);
   float* part = (float*)(ws + w.part);
+  float* bpart = (float*)(ws + w.bpart);
   const unsigned ln_grid = (unsigned)((nt + 3) / 4 > 4096 ? 4096 : (nt + 3) / 4);   // 4096 x 2 x 256 floats fit `part`
   const unsigned ah_grid = (unsigned)((nt * s.heads + 255) / 256);
 
@@ -925,16 +918,13 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     float* g = grads + (size_t)l * gl.total;
     BW_TRY(forward(l, nullptr));                 // this block's intermediates, from its input alone
     // FFN: y = xmid + act(n2 W1 + b1) W2 + b2
-    BW_TRY(gemm_wgrad(st, a, f, f, dyb, d, d, nt, part, g + gl.w2));
-    BW_TRY(colsum(st, dyb, d, d, nt, g + gl.b2));
+    BW_TRY(gemm_wgrad(st, a, f, f, dyb, d, d, nt, part, bpart, g + gl.w2, g + gl.b2));
     BW_TRY(gemm_rows_t(st, dyb, d, (const __bf16*)b.w2, f, nt, EPI_DACT, c->act, dh, h));
-    BW_TRY(gemm_wgrad(st, n2, d, d, dh, f, f, nt, part, g + gl.w1));
-    BW_TRY(colsum(st, dh, f, f, nt, g + gl.b1));
+    BW_TRY(gemm_wgrad(st, n2, d, d, dh, f, f, nt, part, bpart, g + gl.w1, g + gl.b1));
     BW_TRY(gemm_rows_t(st, dh, f, (const __bf16*)b.w1, d, nt, EPI_BF16, 0, dn, nullptr));
     BW_TRY(ln_bwd(st, ln_grid, d, dn, xmid, (const __bf16*)b.ln2_g, dy, dxm, dxmb, part, g + gl.ln2_g, (int)nt, c->ln_eps));
     // attention: xmid = x + att W_O + b_O
-    BW_TRY(gemm_wgrad(st, o, d, d, dxmb, d, d, nt, part, g + gl.wo));
-    BW_TRY(colsum(st, dxmb, d, d, nt, g + gl.bo));
+    BW_TRY(gemm_wgrad(st, o, d, d, dxmb, d, d, nt, part, bpart, g + gl.wo, g + gl.bo));
     BW_TRY(gemm_rows_t(st, dxmb, d, (const __bf16*)b.wo, d, nt, EPI_BF16, 0, dob, nullptr));
     if (s.dh == 16) {
       bw_attn_bwd_q_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
@@ -946,8 +936,7 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     BW_TRY(launched("group attention backward"));
     const size_t wofs[3] = {gl.wq, gl.wk, gl.wv}, bofs[3] = {gl.bq, gl.bk, gl.bv};
     for (int j = 0; j < 3; ++j) {
-      BW_TRY(gemm_wgrad(st, n1, d, d, dqkv + (size_t)j * d, 3 * d, d, nt, part, g + wofs[j]));
-      BW_TRY(colsum(st, dqkv + (size_t)j * d, 3 * d, d, nt, g + bofs[j]));
+      BW_TRY(gemm_wgrad(st, n1, d, d, dqkv + (size_t)j * d, 3 * d, d, nt, part, bpart, g + wofs[j], g + bofs[j]));
     }
     BW_TRY(gemm_rows_t(st, dqkv, 3 * d, wcat(l), d, nt, EPI_BF16, 0, dn, nullptr));
     // the gradient of this block's input is the upstream gradient of the block before it

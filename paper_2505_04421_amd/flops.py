@@ -65,3 +65,29 @@ def score_flops(cfg, tu: int) -> int:
     gpairs = m * m if cfg.gmask == "full" else m * (m + 1) // 2
     kv = len(_slot_tokens(cfg.k_recent, tu, getattr(cfg, "k_uniform", 0), getattr(cfg, "q_learnable", False)))
     return m * per_row + 4 * d * (gpairs + m * tu) + cfg.n_self * (m * per_row + 4 * d * (gpairs + m * kv))
+
+
+def merge_backward_work(cfg, lens: Optional[Sequence[int]] = None, B: Optional[int] = None, L: Optional[int] = None) -> dict:
+    """Work of one longer_token_merge_backward call (Section 3.6.2: recomputation, mixed precision).
+
+    ``gradient_flops``: the products a backward pass adds to the forward ones, two per forward
+    product (the gradient of its input and of its weight): 2 x the InnerTrans forward count, on
+    valid tokens.  ``recompute_flops``: the forward products that are computed again (the chain of
+    block inputs: all blocks but the last; then every block's intermediates, without its second
+    FFN product).  ``hbm_bytes``: what the pass's kernels read and write when every tensor makes one
+    trip per use, over all B L token rows (padded rows are computed too): per token and block
+    40 w + 4 f bytes for the recomputed intermediates (+ 8 w + 2 f when the block's output is needed),
+    90 w + 10 f for the gradients, 12 w once for the input copy and the merge gradient."""
+    B = cfg.B if B is None else B
+    L = cfg.L if L is None else L
+    w = cfg.d // cfg.K if getattr(cfg, "merge", "mean") == "concat" else cfg.d
+    f = cfg.ffn_mult * w
+    n = cfg.inner_layers
+    inner = forward_flops(cfg, lens, B, L)["inner"]
+    ffn2 = 4 * w * f // 2                                   # 2 w f FLOP per token: the second FFN product
+    lens_ = [L] * B if lens is None else [min(max(int(x), 0), L) for x in lens]
+    valid = sum(lens_)
+    per_block = inner // max(n, 1)
+    recompute = (n - 1) * per_block + n * (per_block - ffn2 * valid)
+    per_token = (n - 1) * (48 * w + 6 * f) + n * (40 * w + 4 * f) + n * (90 * w + 10 * f) + 12 * w
+    return {"gradient_flops": 2 * inner, "recompute_flops": recompute, "hbm_bytes": per_token * B * L}

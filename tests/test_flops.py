@@ -28,3 +28,22 @@ def test_benchmark_flop_counter_agrees_with_the_oracle_counter():
             assert orc.algorithmic_flops_score(cfg, tu) == flops.score_flops(cfg, tu), (cfg.name, tu)
     # the K/V share of the cross layer, by hand at the headline shape: (8 + 250) key rows x 4 d^2
     assert flops.forward_flops(synth.CONFIGS["C3"], B=1)["kv_cross"] == 258 * 4 * 128 * 128
+
+
+def test_backward_work_tally_by_hand_at_the_headline_shape():
+    """C3: 512 000 tokens, width 128, FFN width 512, two InnerTrans blocks (Eq. 3: 24 d^2 per token and
+    block + 4 K d of attention inside a group of K)."""
+    from paper_2505_04421_amd import flops
+    w = flops.merge_backward_work(synth.CONFIGS["C3"])
+    tokens = 256 * 2000
+    block = tokens * (24 * 128 * 128 + 4 * 8 * 128)
+    assert w["gradient_flops"] == 2 * 2 * block
+    # recomputed: block 0 in full (the chain of block inputs), then both blocks without the second FFN product
+    assert w["recompute_flops"] == block + 2 * (block - tokens * 2 * 128 * 512)
+    # bytes per token: chain 48 w + 6 f, per block 40 w + 4 f recomputed and 90 w + 10 f of gradients, 12 w once
+    assert w["hbm_bytes"] == tokens * ((48 * 128 + 6 * 512) + 2 * (40 * 128 + 4 * 512) + 2 * (90 * 128 + 10 * 512) + 12 * 128)
+    # a ragged batch: FLOPs follow the valid tokens, bytes every row
+    c = synth.CONFIGS["C2"].replace(B=3)
+    r = flops.merge_backward_work(c, [0, 100, 512])
+    assert r["gradient_flops"] == 2 * flops.forward_flops(c, [0, 100, 512])["inner"]
+    assert r["hbm_bytes"] == flops.merge_backward_work(c)["hbm_bytes"]
