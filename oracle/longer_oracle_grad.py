@@ -1,9 +1,10 @@
-"""CPU oracle for the backward pass of the LONGER token merge (one InnerTrans block stack and the
-group pooling) with activation recomputation.
+"""CPU oracle for the backward pass of LONGER with activation recomputation: the token merge (one
+InnerTrans block stack and the group pooling), and the whole model (merge, cross-causal layer,
+self-causal layers, head, loss).
 
 TEST INFRASTRUCTURE ONLY, like ``longer_oracle``: plain fp64 numpy, written from the definitions;
-never imported by the product path.  No HIP kernel computes a backward pass yet; this module is the
-statement of what such a kernel will have to reproduce.
+never imported by the product path.  It states what the HIP backward pass (csrc/backward.hip) has to
+reproduce.
 
 What the paper fixes
 --------------------
@@ -234,3 +235,84 @@ def token_merge_backward(cfg, inner_blocks: Sequence[dict], H: np.ndarray, lens,
                 grads[i][k] += g[k]
         dH[u, :nv] = dE.reshape(T * K, d)[:nv]
     return dH, grads
+
+
+# --------------------------------------------------------------------------- whole model
+def model_backward(cfg, weights: dict, H: np.ndarray, G: np.ndarray, lens, labels: np.ndarray, keep: str = "input_only"):
+    """Loss (Eq. 2) of ``longer_oracle.forward`` (token merge, cross-causal layer over R = [G; M] with
+    the query set O of Eq. 5, N self-causal layers, linear head on the global rows, Eq. 1) and its
+    gradient with respect to every input and parameter:
+
+        returns (loss, logits [B], dH [B, L, d_raw], dG [B, m, d],
+                 {"inner": [per block], "cross": {...}, "self": [per block], "head_w", "head_b"}).
+
+    Sampled query slots only (``q_learnable`` configurations are not differentiated here).  The
+    reduced stack keeps the input rows of every layer and recomputes a layer's intermediates when its
+    gradient is taken; the token merge is differentiated by ``token_merge_backward(keep=...)``."""
+    if getattr(cfg, "q_learnable", False):
+        raise ValueError("learnable query tokens are not differentiated")
+    H = np.asarray(H)
+    G = np.asarray(G, dtype=F64)
+    B, L, _ = H.shape
+    m, k, d, T = cfg.m, cfg.k_recent, cfg.d, cfg.T
+    lens_ = fwd._lens(lens, B, L)
+    labels = np.asarray(labels, dtype=F64)
+    cross = fwd._f64(weights["cross"])
+    selfs = [fwd._f64(b) for b in weights["self"]]
+    head_w = np.asarray(weights["head_w"], dtype=F64)
+    head_b = float(np.asarray(weights["head_b"]).reshape(-1)[0])
+
+    # ---- forward, keeping each layer's input rows per user
+    M = fwd.token_merge(cfg, weights["inner"], H, lens)
+    per_user = []
+    logits = np.zeros(B, dtype=F64)
+    for u in range(B):
+        Tu = fwd.merged_len(lens_[u], cfg.K)
+        Mu = np.where((np.arange(T) < Tu)[:, None], M[u], 0.0)
+        R = np.concatenate([G[u], Mu], axis=0)
+        qt = fwd._query_tokens(cfg, m, Tu)
+        qvalid = np.array([t[2] for t in qt])
+        O = fwd.gather_queries(cfg, G[u], Mu, Tu)
+        mask_c = fwd._type_mask(qt, fwd.key_tokens(m, T, Tu), cfg.gmask)
+        mask_s = fwd._type_mask(qt, qt, cfg.gmask)
+        X = np.where(qvalid[:, None], fwd.block(O, R, mask_c, cross, cfg.heads, cfg.ln_eps, cfg.act), 0.0)
+        xs = []
+        for blk in selfs:
+            xs.append(X)
+            X = np.where(qvalid[:, None], fwd.block(X, X, mask_s, blk, cfg.heads, cfg.ln_eps, cfg.act), 0.0)
+        logits[u] = X[:m].reshape(-1) @ head_w + head_b
+        per_user.append((Tu, qt, qvalid, O, R, mask_c, mask_s, xs, X))
+    loss = bce_loss(logits, labels)
+
+    # ---- backward
+    dlogit = bce_loss_grad(logits, labels)
+    g_cross = {p: np.zeros_like(cross[p]) for p in PARAMS}
+    g_self = [{p: np.zeros_like(b[p]) for p in PARAMS} for b in selfs]
+    g_hw = np.zeros_like(head_w)
+    dG = np.zeros((B, m, d), dtype=F64)
+    dM = np.zeros((B, T, d), dtype=F64)
+    for u in range(B):
+        Tu, qt, qvalid, O, R, mask_c, mask_s, xs, Y = per_user[u]
+        g_hw += dlogit[u] * Y[:m].reshape(-1)
+        dX = np.zeros((m + k, d), dtype=F64)
+        dX[:m] = dlogit[u] * head_w.reshape(m, d)
+        for i in reversed(range(len(selfs))):
+            dX = np.where(qvalid[:, None], dX, 0.0)                # invalid rows were written as zeros
+            dxq, dxkv, g = block_backward(dX, xs[i], xs[i], mask_s, selfs[i], cfg.heads, cfg.ln_eps, cfg.act)
+            dX = dxq + dxkv                                         # queries and keys are the same rows
+            for p in PARAMS:
+                g_self[i][p] += g[p]
+        dX = np.where(qvalid[:, None], dX, 0.0)
+        dO, dR, g = block_backward(dX, O, R, mask_c, cross, cfg.heads, cfg.ln_eps, cfg.act)
+        for p in PARAMS:
+            g_cross[p] += g[p]
+        dG[u] = dO[:m] + dR[:m]                                     # a global token is a query row and a key row
+        dMu = dR[m:].copy()
+        for i in range(k):
+            t, v = qt[m + i][1], qt[m + i][2]
+            if v:
+                dMu[t] += dO[m + i]                                 # slot i holds merged token t
+        dM[u] = np.where((np.arange(T) < Tu)[:, None], dMu, 0.0)    # merged tokens past T_u were zeroed
+    dH, g_inner = token_merge_backward(cfg, weights["inner"], H, lens, dM, keep=keep)
+    grads = {"inner": g_inner, "cross": g_cross, "self": g_self, "head_w": g_hw, "head_b": np.array([dlogit.sum()])}
+    return loss, logits, dH, dG, grads

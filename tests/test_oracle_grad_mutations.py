@@ -40,6 +40,13 @@ MUTANTS = [
     ("recomputation from the wrong block's input", "                kept[i] = E\n", "                kept[i] = E0\n"),
     ("loss gradient not averaged over the samples", "    return (sig - y) / z.size", "    return sig - y"),
     ("w1 gradient from the un-normalised rows", "g[\"w1\"] = _matT(c[\"u\"], da)", "g[\"w1\"] = _matT(c[\"x\"], da)"),
+    ("model: a global token's gradient as a key row forgotten", "        dG[u] = dO[:m] + dR[:m]", "        dG[u] = dO[:m] + 0.0"),
+    ("model: the query slots' gradient not returned to the merged tokens", "                dMu[t] += dO[m + i]", "                pass"),
+    ("model: self layers, the key rows' gradient forgotten",
+     "            dX = dxq + dxkv                                         # queries and keys are the same rows",
+     "            dX = dxq"),
+    ("model: head weights read feature-major", "        dX[:m] = dlogit[u] * head_w.reshape(m, d)",
+     "        dX[:m] = dlogit[u] * head_w.reshape(d, m).T"),
 ]
 
 

@@ -229,3 +229,77 @@ def test_bce_loss_and_gradient_against_the_library():
     # Eq. 2 written out on unsaturated predictions
     p = 1.0 / (1.0 + np.exp(-z[2:]))
     assert abs(grd.bce_loss(z[2:], y[2:]) + np.mean(y[2:] * np.log(p) + (1 - y[2:]) * np.log(1 - p))) <= 1e-12
+
+
+@pytest.mark.parametrize("k_uniform,gmask", [(0, "full"), (2, "causal")])
+def test_model_backward_against_finite_differences_of_the_forward_oracle(k_uniform, gmask):
+    """The whole model (merge, cross-causal layer, two self-causal layers, head, Eq. 1-2) on a tiny ragged
+    batch with an empty user and a user shorter than the query set: every input and a sample of every
+    parameter group against central differences of the loss computed by the forward oracle."""
+    cfg = synth.tiny_config(B=4, L=22, d=8, heads=2, m=2, K=4, k_recent=4, n_self=2, inner_layers=1,
+                            k_uniform=k_uniform, gmask=gmask, ragged=True, len_lo=0, len_hi=22)
+    case = synth.make_case(cfg)
+    case["lens"][:] = [22, 0, 5, 17]
+    rng = np.random.default_rng(5 + k_uniform)
+    w = case["weights"]
+    w = {"inner": [{k: np.asarray(v, dtype=np.float64) for k, v in b.items()} for b in w["inner"]],
+         "cross": {k: np.asarray(v, dtype=np.float64) for k, v in w["cross"].items()},
+         "self": [{k: np.asarray(v, dtype=np.float64) for k, v in b.items()} for b in w["self"]],
+         "head_w": np.asarray(w["head_w"], dtype=np.float64), "head_b": np.asarray(w["head_b"], dtype=np.float64)}
+    H = np.asarray(case["H"], dtype=np.float64)
+    G = np.asarray(case["G"], dtype=np.float64)
+    lens = case["lens"]
+    labels = np.array([1.0, 0.0, 1.0, 0.0])
+
+    def loss():
+        _, logits = orc.forward(cfg, w, H, G, lens)
+        return grd.bce_loss(logits, labels)
+
+    val, logits, dH, dG, grads = grd.model_backward(cfg, w, H, G, lens, labels)
+    assert abs(val - loss()) <= 1e-12
+    assert np.allclose(logits, orc.forward(cfg, w, H, G, lens)[1], atol=1e-12)
+    pos = np.arange(cfg.L)[None, :]
+    assert (dH[pos >= lens[:, None]] == 0).all()
+
+    def close(a, num):      # step 1e-7: LayerNorm over 8 features bends sharply, 1e-6 leaves 3e-6 of truncation error
+        return abs(a - num) <= 2e-6 * max(1e-2, abs(num))
+
+    for u in (0, 2, 3):
+        for _ in range(6):
+            t, j = int(rng.integers(0, lens[u])), int(rng.integers(0, H.shape[-1]))
+            num = _fd(loss, H, (u, t, j), h=1e-7)
+            assert close(dH[u, t, j], num), ("dH", u, t, j, dH[u, t, j], num)
+    for u in range(cfg.B):
+        for _ in range(4):
+            i, j = int(rng.integers(0, cfg.m)), int(rng.integers(0, cfg.d))
+            num = _fd(loss, G, (u, i, j), h=1e-7)
+            assert close(dG[u, i, j], num), ("dG", u, i, j, dG[u, i, j], num)
+    groups = [("inner0", w["inner"][0], grads["inner"][0]), ("cross", w["cross"], grads["cross"]),
+              ("self0", w["self"][0], grads["self"][0]), ("self1", w["self"][1], grads["self"][1])]
+    for name, params, g in groups:
+        for key in ("wq", "wk", "wv", "wo", "w1", "w2", "ln1_g", "ln1_b", "ln2_g", "bq", "bv", "bo", "b1", "b2"):
+            p = params[key]
+            idx = tuple(int(rng.integers(0, s)) for s in p.shape)
+            num = _fd(loss, p, idx, h=1e-7)
+            assert close(g[key][idx], num), (name, key, idx, g[key][idx], num)
+    for _ in range(5):
+        idx = (int(rng.integers(0, w["head_w"].size)),)
+        num = _fd(loss, w["head_w"], idx, h=1e-7)
+        assert close(grads["head_w"][idx], num), ("head_w", idx)
+    num = _fd(loss, w["head_b"], (0,), h=1e-7)
+    assert close(grads["head_b"][0], num)
+
+
+def test_model_backward_a_token_outside_every_query_set_still_gets_its_gradient_through_the_keys():
+    """A merged token older than the k sampled ones is not a query, but it is a key of the cross layer:
+    its raw tokens' gradient is not zero; and a user's gradient does not depend on the other users."""
+    cfg = synth.tiny_config(B=2, L=24, d=8, heads=2, m=2, K=4, k_recent=2, n_self=1, inner_layers=1)
+    case = synth.make_case(cfg)
+    w, H, G = case["weights"], case["H"], case["G"]
+    labels = np.array([1.0, 0.0])
+    _, _, dH, dG, _ = grd.model_backward(cfg, w, H, G, None, labels)
+    assert np.abs(dH[0, :4]).max() > 0          # merged token 0 of 6: only ever a key
+    one = cfg.replace(B=1)
+    _, _, dH1, dG1, _ = grd.model_backward(one, w, H[1:], G[1:], None, labels[1:])
+    # the mean of Eq. 2 runs over the batch: a batch of one user weighs it twice as much
+    assert np.allclose(dH1[0], 2 * dH[1], rtol=1e-10, atol=1e-14) and np.allclose(dG1[0], 2 * dG[1], rtol=1e-10, atol=1e-14)
