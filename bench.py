@@ -146,6 +146,44 @@ def run_merge_backward(lg, torch, cfg, case, steps):
             "workspace_bytes": n_ws}
 
 
+def run_forward_backward(lg, torch, cfg, case, steps):
+    """Time longer_forward_backward: loss and every gradient of the whole model for one batch."""
+    import numpy as np
+    import longer_synth as synth
+    from paper_2505_04421_amd import flops
+    dev = "cuda:0"
+    model = lg.DeviceModel(cfg, case["weights"], dev)
+    B, L = cfg.B, cfg.L
+    n_ws = lg.longer_forward_backward_workspace_bytes(model.ccfg, B, L)
+    nf = lg.longer_model_grad_floats(model.ccfg)
+    if n_ws == 0 or nf == 0:
+        return {"error": lg.longer_last_error()}
+    ws = torch.empty(n_ws, dtype=torch.uint8, device=dev)
+    H, G = model.upload(case["H"]), model.upload(case["G"])
+    lens = None if case["lens"] is None else torch.from_numpy(case["lens"].astype(np.int32)).to(dev)
+    labels = torch.from_numpy(synth.draw_labels(cfg)).to(dev)
+    dH = torch.empty(B, L, cfg.d_in, dtype=torch.float32, device=dev)
+    dG = torch.empty(B, cfg.m, cfg.d, dtype=torch.float32, device=dev)
+    grads = torch.empty(nf, dtype=torch.float32, device=dev)
+    loss = torch.empty(4, dtype=torch.float32, device=dev)
+    logits = torch.empty(B, dtype=torch.float32, device=dev)
+    call = lambda: lg.longer_forward_backward(model.ccfg, model.weights, H, G, lens, B, L, labels, loss, logits, dH, dG, grads, ws)
+    for _ in range(2):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        call()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    fl = flops.forward_flops(cfg, None if case["lens"] is None else case["lens"])
+    return {"workload": "%s: longer_forward_backward (loss of Eq. 2 and every gradient), B=%d users, L=%d" % (cfg.name, B, L),
+            "ms_per_step": ms, "steps": steps, "user_sequences_per_s": B / (ms * 1e-3), "loss": float(loss[0].item()),
+            "forward_plus_gradient_gflop_per_step": 3.0 * fl["total"] / 1e9,
+            "mfma_peak_frac_forward_plus_gradient_flops": 3.0 * fl["total"] / 1e12 / (ms * 1e-3) / PEAK_BF16_TFLOPS,
+            "workspace_bytes": n_ws}
+
+
 def run_forward(lg, torch, synth, cfg, args, steps, warmup, want_graph=True):
     """Time longer_forward (or, with --from-inputs, longer_forward_from_inputs) on one configuration."""
     import numpy as np
@@ -473,6 +511,8 @@ def main():
 
     if not args.no_backward and cfg.dtype == "bf16" and not r["from_inputs"]:
         out["merge_backward"] = run_merge_backward(lg, torch, cfg, r["case"], max(3, args.steps // 5))
+        if not getattr(cfg, "q_learnable", False):
+            out["forward_backward"] = run_forward_backward(lg, torch, cfg, r["case"], max(3, args.steps // 5))
 
     out["cpu_baseline"] = None if args.no_cpu else cpu_oracle_leg(cfg, r["case"], None if r["from_inputs"] else r["Y_host"], 15.0)
     print(json.dumps(out))

@@ -277,6 +277,28 @@ int longer_token_merge_backward(const longer_config* cfg, const longer_block* in
                                 float* dH_out, float* grads_out,
                                 void* ws, size_t ws_bytes, void* stream);
 
+/* Loss and gradients of the whole model (Section 3.6.2 applied to the forward pass of longer_forward):
+ * token merge, cross-causal layer, N self-causal layers, the linear head on the global rows (Eq. 1) and
+ * the binary cross-entropy of Eq. 2, mean over the B users of the batch.  Recomputation and precision
+ * as for longer_token_merge_backward, applied selectively: the token merge (nine tenths of the
+ * activations) keeps nothing and is recomputed, block by block, when its gradients are taken; the reduced
+ * stack (B (m + k) query rows, B (m + T) key rows) keeps its layers' intermediates.
+ *   H, G, lens, B, L as for longer_forward (bf16 only; sampled query slots: cfg->q_learn must be NULL);
+ *   labels [B] fp32 (0 or 1);
+ *   loss_out [1] fp32; logits_out [B] fp32 or NULL;
+ *   dH_out [B, L, w] fp32, dG_out [B, m, d] fp32: gradients of the loss with respect to the inputs;
+ *   grads_out fp32 [longer_model_grad_floats(cfg)]: parameter gradients, dense, in this order: the
+ *     InnerTrans blocks, the cross block, the self blocks (each block as for
+ *     longer_token_merge_backward, at its own width), head_w [m d], head_b [1] (+ padding to a multiple
+ *     of 4 floats).
+ * ws: at least longer_forward_backward_workspace_bytes(cfg, B, L). */
+size_t longer_model_grad_floats(const longer_config* cfg);
+size_t longer_forward_backward_workspace_bytes(const longer_config* cfg, int B, int L);
+int longer_forward_backward(const longer_config* cfg, const longer_weights* w, const void* H, const void* G,
+                            const int32_t* lens, int B, int L, const float* labels,
+                            float* loss_out, float* logits_out, float* dH_out, float* dG_out, float* grads_out,
+                            void* ws, size_t ws_bytes, void* stream);
+
 /* Measurement aid: when enabled, every kernel launch group of the entry points is bracketed
  * by a pair of HIP events recorded on the caller's stream (at most 4096 pairs between two
  * reads; later launches go unrecorded).  enable = 0: off; 1: every stage; any other value:

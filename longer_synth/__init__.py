@@ -284,3 +284,9 @@ def draw_merge_gradient(cfg: Config, seed_offset: int = 7000, users: Optional[Se
         keep[list(users)] = True
         dM[~keep] = 0.0
     return dM
+
+
+def draw_labels(cfg: Config, seed_offset: int = 9000) -> np.ndarray:
+    """Binary labels [B] (fp32 0 / 1) for the loss of Eq. 2."""
+    rng = np.random.default_rng(2505_04421 + 7919 * cfg.index + seed_offset)
+    return (rng.random(cfg.B) < 0.5).astype(np.float32)

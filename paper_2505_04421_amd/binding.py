@@ -17,7 +17,8 @@ ENTRY_POINTS = ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_inner
                 "longer_last_error", "longer_probe_mfma_layout", "longer_stage_timing",
                 "longer_stage_timing_read", "longer_packed_weights_bytes", "longer_pack_weights",
                 "longer_score_candidates_static", "longer_probe_rate",
-                "longer_backward_workspace_bytes", "longer_block_grad_floats", "longer_token_merge_backward")
+                "longer_backward_workspace_bytes", "longer_block_grad_floats", "longer_token_merge_backward",
+                "longer_model_grad_floats", "longer_forward_backward_workspace_bytes", "longer_forward_backward")
 
 
 class LongerError(RuntimeError):
@@ -89,13 +90,19 @@ def load_library() -> ctypes.CDLL:
     lib.longer_block_grad_floats.restype = sz
     lib.longer_block_grad_floats.argtypes = [cfgp]
     lib.longer_token_merge_backward.argtypes = [cfgp, blkp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.longer_model_grad_floats.restype = sz
+    lib.longer_model_grad_floats.argtypes = [cfgp]
+    lib.longer_forward_backward_workspace_bytes.restype = sz
+    lib.longer_forward_backward_workspace_bytes.argtypes = [cfgp, i32, i32]
+    lib.longer_forward_backward.argtypes = [cfgp, wp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.longer_last_error.restype = ctypes.c_char_p
     lib.longer_probe_mfma_layout.argtypes = [vp, vp]
     lib.longer_stage_timing.argtypes = [i32]
     lib.longer_stage_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     for name in ENTRY_POINTS:
         if name not in ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_packed_weights_bytes", "longer_last_error",
-                        "longer_backward_workspace_bytes", "longer_block_grad_floats"):
+                        "longer_backward_workspace_bytes", "longer_block_grad_floats", "longer_model_grad_floats",
+                        "longer_forward_backward_workspace_bytes"):
             getattr(lib, name).restype = ctypes.c_int
     _LIB = lib
     return lib
@@ -332,24 +339,63 @@ def longer_block_grad_floats(ccfg: CConfig) -> int:
     return int(load_library().longer_block_grad_floats(ctypes.byref(ccfg)))
 
 
+def _block_views(grads, o, d, f):
+    shapes = {"ln1_g": (d,), "ln1_b": (d,), "wq": (d, d), "bq": (d,), "wk": (d, d), "bk": (d,), "wv": (d, d), "bv": (d,),
+              "wo": (d, d), "bo": (d,), "ln2_g": (d,), "ln2_b": (d,), "w1": (d, f), "b1": (f,), "w2": (f, d), "b2": (d,)}
+    views = {}
+    for name in BLOCK_FIELDS:
+        n = 1
+        for e in shapes[name]:
+            n *= e
+        views[name] = grads[o:o + n].view(*shapes[name])
+        o += n
+    return views, o
+
+
 def block_grad_views(cfg, grads):
     """Split the flat fp32 gradient buffer of longer_token_merge_backward into one
     {parameter: tensor view} per InnerTrans block (the order and shapes of the longer_block members)."""
     d = cfg.d // cfg.K if getattr(cfg, "merge", "mean") == "concat" else cfg.d
-    f = cfg.ffn_mult * d
-    shapes = {"ln1_g": (d,), "ln1_b": (d,), "wq": (d, d), "bq": (d,), "wk": (d, d), "bk": (d,), "wv": (d, d), "bv": (d,),
-              "wo": (d, d), "bo": (d,), "ln2_g": (d,), "ln2_b": (d,), "w1": (d, f), "b1": (f,), "w2": (f, d), "b2": (d,)}
     out, o = [], 0
     for _ in range(cfg.inner_layers):
-        views = {}
-        for name in BLOCK_FIELDS:
-            n = 1
-            for e in shapes[name]:
-                n *= e
-            views[name] = grads[o:o + n].view(*shapes[name])
-            o += n
-        out.append(views)
+        v, o = _block_views(grads, o, d, cfg.ffn_mult * d)
+        out.append(v)
     return out
+
+
+def model_grad_views(cfg, grads):
+    """Split the gradient buffer of longer_forward_backward: {"inner": [...], "cross": {...}, "self": [...],
+    "head_w": [m d], "head_b": [1]} of tensor views."""
+    di = cfg.d // cfg.K if getattr(cfg, "merge", "mean") == "concat" else cfg.d
+    out = {"inner": [], "self": []}
+    o = 0
+    for _ in range(cfg.inner_layers):
+        v, o = _block_views(grads, o, di, cfg.ffn_mult * di)
+        out["inner"].append(v)
+    out["cross"], o = _block_views(grads, o, cfg.d, cfg.ffn_mult * cfg.d)
+    for _ in range(cfg.n_self):
+        v, o = _block_views(grads, o, cfg.d, cfg.ffn_mult * cfg.d)
+        out["self"].append(v)
+    out["head_w"] = grads[o:o + cfg.m * cfg.d]
+    out["head_b"] = grads[o + cfg.m * cfg.d:o + cfg.m * cfg.d + 1]
+    return out
+
+
+def longer_model_grad_floats(ccfg: CConfig) -> int:
+    return int(load_library().longer_model_grad_floats(ctypes.byref(ccfg)))
+
+
+def longer_forward_backward_workspace_bytes(ccfg: CConfig, B: int, L: int) -> int:
+    return int(load_library().longer_forward_backward_workspace_bytes(ctypes.byref(ccfg), B, L))
+
+
+def longer_forward_backward(ccfg, weights, H, G, lens, B, L, labels, loss_out, logits_out, dH_out, dG_out, grads_out, ws,
+                            stream=None):
+    _require_gpu()
+    _check(load_library().longer_forward_backward(ctypes.byref(ccfg), ctypes.byref(weights), _ptr(H), _ptr(G), _ptr(lens), B, L,
+                                                  _ptr(labels), _ptr(loss_out), _ptr(logits_out), _ptr(dH_out), _ptr(dG_out),
+                                                  _ptr(grads_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "longer_forward_backward")
 
 
 def longer_token_merge_backward(ccfg, inner, H, lens, B, L, dM, dH_out, grads_out, ws, stream=None):

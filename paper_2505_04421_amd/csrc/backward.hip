@@ -367,7 +367,7 @@ __global__ __launch_bounds__(256) void bw_ln_fwd_kernel(const float* __restrict_
 }
 
 // LayerNorm backward for y = LN(x) g + b with upstream dn = dL/dy (bf16) and the gradient dres that
-// reaches x through the residual connection: dx_out = dres + dLN, also stored as bf16 (dxb, may be
+// reaches x through the residual connection (NULL: none): dx_out = dres + dLN, also stored as bf16 (dxb, may be
 // NULL); the block's share of dg[e] = sum_r dn xhat and db[e] = sum_r dn goes to part[block][2][D]
 // (bw_reduce_kernel sums the blocks).
 template <int LPR>
@@ -390,7 +390,7 @@ __global__ __launch_bounds__(256) void bw_ln_bwd_kernel(const __bf16* __restrict
     if (ok) {
       v = *(const f32x4*)(x + o);
       t = load_bf16x4(dn + o);
-      res = *(const f32x4*)(dres + o);
+      if (dres) res = *(const f32x4*)(dres + o);
     }
     const float mean = row_sum<LPR>(v[0] + v[1] + v[2] + v[3]) * (1.f / D);
     v -= mean;
@@ -642,8 +642,10 @@ __global__ __launch_bounds__(256) void bw_concat_qkv_kernel(const __bf16* wq, co
 // out[i] += sum over the slices s of part[s][i], i < count (count a multiple of 4; out starts at zero).
 // Thread (x, y) of a 64 x 4 block sums every fourth slice of four adjacent outputs inside the block's
 // share of the slices (blockIdx.y of gridDim.y shares), the four partial sums meet in LDS, and the
-// block adds its sum with one atomic per output (a plain store when there is one share).
-__global__ __launch_bounds__(256) void bw_reduce_kernel(const float* __restrict__ part, int nsplit, int count, float* out) {
+// block adds its sum with one atomic per output (a plain store when there is one share and the result
+// is not to be added to what out holds).
+__global__ __launch_bounds__(256) void bw_reduce_kernel(const float* __restrict__ part, int nsplit, int count, float* out,
+                                                        int accumulate) {
   __shared__ f32x4 red[4][64];
   const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
   const int i = (blockIdx.x * 64 + x) * 4;
@@ -658,7 +660,7 @@ __global__ __launch_bounds__(256) void bw_reduce_kernel(const float* __restrict_
   __syncthreads();
   if (y == 0 && i < count) {
     const f32x4 t = red[0][x] + red[1][x] + red[2][x] + red[3][x];
-    if (gridDim.y == 1) {
+    if (gridDim.y == 1 && !accumulate) {
       *(f32x4*)(out + i) = t;
     } else {
 #pragma unroll
@@ -669,6 +671,318 @@ __global__ __launch_bounds__(256) void bw_reduce_kernel(const float* __restrict_
 
 __global__ __launch_bounds__(256) void bw_zero_kernel(float* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
+}
+
+
+// ------------------------------------------------------------------------------------
+// The reduced stack (Section 3.5): cross-causal layer over R = [G; M] with the query set O of Eq. 5,
+// self-causal layers over O's rows.  Every row carries a descriptor of its token: -1 invalid, a for
+// global token a, kSeq + t for the sequence token with merged index t; visibility is the rule of
+// Eq. 8 on those descriptors.
+constexpr int kSeq = 1 << 24;
+
+__device__ __forceinline__ bool visible(int qd, int kd, int gmask) {
+  if (qd < 0 || kd < 0) return false;
+  if (qd >= kSeq) return kd >= kSeq && kd <= qd;          // a sequence query: sequence keys not newer than itself
+  if (kd >= kSeq) return true;                            // a global query: every valid sequence key
+  return gmask == LONGER_GMASK_FULL || kd >= qd;          // and the global keys of its set
+}
+
+// merged index held by query slot i of a user with tu merged tokens (Section 3.5.1): the last
+// k - k_uniform slots the most recent tokens, the first k_uniform spread evenly over the older ones
+// (each the newest token of its share); negative: the slot is empty
+__device__ __forceinline__ int slot_merged_index(int i, int k, int tu, int k_uniform) {
+  if (tu <= k || i >= k_uniform) return tu - k + i;
+  const int rest = tu - (k - k_uniform);
+  return (int)(((long long)(i + 1) * rest) / k_uniform) - 1;
+}
+
+struct StackGeom { const int32_t* lens; int L, K, T, m, k, k_uniform, B; };
+
+__device__ __forceinline__ int merged_len(const StackGeom& g, int u) {
+  int l = g.lens ? g.lens[u] : g.L;
+  l = l < 0 ? 0 : (l > g.L ? g.L : l);
+  return (l + g.K - 1) / g.K;
+}
+
+// descriptors of the query rows [B][m + k] and of the cross layer's key rows [B][m + T]
+__global__ __launch_bounds__(256) void bw_desc_kernel(StackGeom g, int* qdesc, int* kdesc) {
+  const int n = g.m + g.k, nk = g.m + g.T;
+  const int total = g.B * (n + nk);
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+    if (i < g.B * n) {
+      const int u = i / n, r = i - u * n;
+      int dsc = r;
+      if (r >= g.m) {
+        const int t = slot_merged_index(r - g.m, g.k, merged_len(g, u), g.k_uniform);
+        dsc = t >= 0 ? kSeq + t : -1;
+      }
+      qdesc[i] = dsc;
+    } else {
+      const int j = i - g.B * n;
+      const int u = j / nk, r = j - u * nk;
+      kdesc[j] = r < g.m ? r : (r - g.m < merged_len(g, u) ? kSeq + (r - g.m) : -1);
+    }
+  }
+}
+
+// R = [G; M] (merged tokens past T_u as zeros) and O = [G; the slots' merged tokens] as fp32 rows
+__global__ __launch_bounds__(256) void bw_build_rows_kernel(StackGeom g, int d, const __bf16* __restrict__ G,
+                                                            const __bf16* __restrict__ M, const int* __restrict__ qdesc,
+                                                            const int* __restrict__ kdesc, float* __restrict__ Ox,
+                                                            float* __restrict__ Rx) {
+  const int n = g.m + g.k, nk = g.m + g.T, d4 = d / 4;
+  const size_t total = (size_t)g.B * (n + nk) * d4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const int c = (int)(i % d4) * 4;
+    size_t row = i / d4;
+    const bool isq = row < (size_t)g.B * n;
+    if (!isq) row -= (size_t)g.B * n;
+    const int per = isq ? n : nk;
+    const int u = (int)(row / per), r = (int)(row - (size_t)u * per);
+    const int dsc = isq ? qdesc[row] : kdesc[row];
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (dsc >= 0) {
+      const __bf16* src = dsc < kSeq ? G + ((size_t)u * g.m + dsc) * d : M + ((size_t)u * g.T + (dsc - kSeq)) * d;
+      v = load_bf16x4(src + c);
+    }
+    (void)r;
+    *(f32x4*)((isq ? Ox : Rx) + row * d + c) = v;
+  }
+}
+
+// x[row][:] = valid(row) ? x[row][:] : 0, and its bf16 copy (xb may be NULL)
+__global__ __launch_bounds__(256) void bw_mask_rows_kernel(float* __restrict__ x, __bf16* __restrict__ xb,
+                                                           const int* __restrict__ desc, size_t rows, int d) {
+  const int d4 = d / 4;
+  const size_t total = rows * d4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t row = i / d4;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (desc[row] >= 0) v = *(const f32x4*)(x + i * 4);
+    *(f32x4*)(x + i * 4) = v;
+    if (xb) store_bf16x4(xb + i * 4, v);
+  }
+}
+
+struct SetAttn {
+  const __bf16* q; int qpitch;          // [B nq][..]
+  const __bf16* k; const __bf16* v; int kvpitch;   // [B nk][..]
+  const int* qdesc; const int* kdesc;
+  int nq, nk, B, heads, gmask;
+};
+
+// The set-attention kernels give a (row, head) pair to kSplit adjacent lanes, each taking every kSplit-th
+// key (query) of the loop, and combine the lanes' partial results with cross-lane shuffles: the loops
+// are short chains of dependent loads, and there are only B (m + k) heads rows to spread over the chip.
+constexpr int kSplit = 1;   // measured at the headline batch: 8 lanes per pair were no faster (the kernels are bound by
+                            // their instruction count), and slower in the two backward kernels
+__device__ __forceinline__ float split_sum(float v) {
+#pragma unroll
+  for (int o = 1; o < kSplit; o <<= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float split_max(float v) {
+#pragma unroll
+  for (int o = 1; o < kSplit; o <<= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// o[row][h] = softmax over the visible keys of the row's user (q . k / sqrt(dh)) v; stat[row][h].x = the
+// log-sum-exp of the scaled scores.  One pass with a running maximum per lane.
+template <int DH>
+__global__ __launch_bounds__(256) void bw_set_attn_fwd_kernel(SetAttn a, __bf16* __restrict__ o, int d, float2* __restrict__ stat) {
+  const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) / kSplit;
+  const int sub = threadIdx.x % kSplit;
+  if (idx >= (long long)a.B * a.nq * a.heads) return;
+  const int row = (int)(idx / a.heads), h = (int)(idx - (long long)row * a.heads);
+  const int u = row / a.nq, qd = a.qdesc[row];
+  float acc[DH];
+#pragma unroll
+  for (int c = 0; c < DH; ++c) acc[c] = 0.f;
+  float mx = -3.0e38f, l = 0.f;
+  if (qd >= 0) {
+    const float scale = rsqrtf((float)DH);
+    float qv[DH], kv[DH];
+    load_head<DH>(a.q + (size_t)row * a.qpitch + h * DH, qv);
+    for (int j = sub; j < a.nk; j += kSplit) {
+      const size_t kr = (size_t)u * a.nk + j;
+      if (!visible(qd, a.kdesc[kr], a.gmask)) continue;
+      load_head<DH>(a.k + kr * a.kvpitch + h * DH, kv);
+      const float sc = scale * dot<DH>(qv, kv);
+      const float mn = fmaxf(mx, sc);
+      const float corr = __expf(mx - mn), p = __expf(sc - mn);
+      load_head<DH>(a.v + kr * a.kvpitch + h * DH, kv);
+      l = l * corr + p;
+#pragma unroll
+      for (int c = 0; c < DH; ++c) acc[c] = acc[c] * corr + p * kv[c];
+      mx = mn;
+    }
+  }
+  const float mall = split_max(mx);
+  const float corr = __expf(mx - mall);          // a lane without a visible key: l = 0, acc = 0
+  l = split_sum(l * corr);
+  const float inv = l > 0.f ? 1.f / l : 0.f;
+#pragma unroll
+  for (int c = 0; c < DH; ++c) acc[c] = split_sum(acc[c] * corr) * inv;
+  if (sub == 0) {
+    store_head<DH>(o + (size_t)row * d + h * DH, acc);
+    stat[(size_t)row * a.heads + h] = make_float2(l > 0.f ? mall + __logf(l) : 0.f, 0.f);
+  }
+}
+
+// Query side of the backward: with P_ij = exp(s_ij - lse_i) and dP_ij = do_i . v_j,
+// D_i = sum_j P_ij dP_ij and dq_i = scale (sum_j P_ij dP_ij k_j - D_i sum_j P_ij k_j), one pass.
+template <int DH>
+__global__ __launch_bounds__(256) void bw_set_attn_bwd_q_kernel(SetAttn a, const __bf16* __restrict__ dob, int d,
+                                                                __bf16* __restrict__ dq, int dqpitch, float2* __restrict__ stat) {
+  const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) / kSplit;
+  const int sub = threadIdx.x % kSplit;
+  if (idx >= (long long)a.B * a.nq * a.heads) return;
+  const int row = (int)(idx / a.heads), h = (int)(idx - (long long)row * a.heads);
+  const int u = row / a.nq, qd = a.qdesc[row];
+  float A[DH], Bv[DH];
+#pragma unroll
+  for (int c = 0; c < DH; ++c) { A[c] = 0.f; Bv[c] = 0.f; }
+  float D = 0.f;
+  const float scale = rsqrtf((float)DH);
+  const float lse = stat[(size_t)row * a.heads + h].x;
+  if (qd >= 0) {
+    float qv[DH], dov[DH], kv[DH], vv[DH];
+    load_head<DH>(a.q + (size_t)row * a.qpitch + h * DH, qv);
+    load_head<DH>(dob + (size_t)row * d + h * DH, dov);
+    for (int j = sub; j < a.nk; j += kSplit) {
+      const size_t kr = (size_t)u * a.nk + j;
+      if (!visible(qd, a.kdesc[kr], a.gmask)) continue;
+      load_head<DH>(a.k + kr * a.kvpitch + h * DH, kv);
+      load_head<DH>(a.v + kr * a.kvpitch + h * DH, vv);
+      const float p = __expf(scale * dot<DH>(qv, kv) - lse);
+      const float pd = p * dot<DH>(dov, vv);
+      D += pd;
+#pragma unroll
+      for (int c = 0; c < DH; ++c) { A[c] += pd * kv[c]; Bv[c] += p * kv[c]; }
+    }
+  }
+  D = split_sum(D);
+#pragma unroll
+  for (int c = 0; c < DH; ++c) A[c] = scale * (split_sum(A[c]) - D * split_sum(Bv[c]));
+  if (sub == 0) {
+    store_head<DH>(dq + (size_t)row * dqpitch + h * DH, A);
+    stat[(size_t)row * a.heads + h].y = D;
+  }
+}
+
+// Key side: dv_j = sum_i P_ij do_i, dk_j = scale sum_i P_ij (do_i . v_j - D_i) q_i over the user's query
+// rows that see key j.
+template <int DH>
+__global__ __launch_bounds__(256) void bw_set_attn_bwd_kv_kernel(SetAttn a, const __bf16* __restrict__ dob, int d,
+                                                                 __bf16* __restrict__ dk, __bf16* __restrict__ dv, int dkvpitch,
+                                                                 const float2* __restrict__ stat) {
+  const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) / kSplit;
+  const int sub = threadIdx.x % kSplit;
+  if (idx >= (long long)a.B * a.nk * a.heads) return;
+  const int kr = (int)(idx / a.heads), h = (int)(idx - (long long)kr * a.heads);
+  const int u = kr / a.nk, kd = a.kdesc[kr];
+  float gk[DH], gv[DH];
+#pragma unroll
+  for (int c = 0; c < DH; ++c) { gk[c] = 0.f; gv[c] = 0.f; }
+  if (kd >= 0) {
+    const float scale = rsqrtf((float)DH);
+    float kv[DH], vv[DH], qi[DH], doi[DH];
+    load_head<DH>(a.k + (size_t)kr * a.kvpitch + h * DH, kv);
+    load_head<DH>(a.v + (size_t)kr * a.kvpitch + h * DH, vv);
+    for (int i = sub; i < a.nq; i += kSplit) {
+      const size_t qr = (size_t)u * a.nq + i;
+      if (!visible(a.qdesc[qr], kd, a.gmask)) continue;
+      load_head<DH>(a.q + qr * a.qpitch + h * DH, qi);
+      load_head<DH>(dob + qr * d + h * DH, doi);
+      const float2 st = stat[qr * a.heads + h];
+      const float p = __expf(scale * dot<DH>(qi, kv) - st.x);
+      const float ds = scale * p * (dot<DH>(doi, vv) - st.y);
+#pragma unroll
+      for (int c = 0; c < DH; ++c) { gv[c] += p * doi[c]; gk[c] += ds * qi[c]; }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < DH; ++c) { gk[c] = split_sum(gk[c]); gv[c] = split_sum(gv[c]); }
+  if (sub == 0) {
+    store_head<DH>(dk + (size_t)kr * dkvpitch + h * DH, gk);
+    store_head<DH>(dv + (size_t)kr * dkvpitch + h * DH, gv);
+  }
+}
+
+// Head and loss (Eq. 1-2) for one user per block: logit = <head_w, the m global rows of Y> + head_b,
+// loss += (softplus form of the cross-entropy) / B, dlogit = (sigmoid(logit) - label) / B, and the
+// gradients that follow: dY (global rows dlogit head_w, the other rows zero; fp32 and bf16), head_w, head_b.
+__global__ __launch_bounds__(256) void bw_head_kernel(const float* __restrict__ Y, const __bf16* __restrict__ hw,
+                                                      const __bf16* __restrict__ hb, const float* __restrict__ labels,
+                                                      int B, int n, int m, int d, float* __restrict__ logits,
+                                                      float* loss, float* __restrict__ dY, __bf16* __restrict__ dYb,
+                                                      float* dhw, float* dhb) {
+  __shared__ float red[4];
+  __shared__ float dl_s;
+  const int u = blockIdx.x;
+  const float* y = Y + (size_t)u * n * d;
+  float s = 0.f;
+  for (int j = threadIdx.x; j < m * d; j += 256) s += y[j] * (float)hw[j];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float z = red[0] + red[1] + red[2] + red[3] + (float)hb[0];
+    const float lab = labels[u];
+    const float e = __expf(-fabsf(z));
+    const float sig = z >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
+    const float dl = (sig - lab) / (float)B;
+    if (logits) logits[u] = z;
+    unsafeAtomicAdd(loss, (fmaxf(z, 0.f) - z * lab + log1pf(e)) / (float)B);
+    unsafeAtomicAdd(dhb, dl);
+    dl_s = dl;
+  }
+  __syncthreads();
+  const float dl = dl_s;
+  for (int j = threadIdx.x; j < n * d; j += 256) {
+    const float g = j < m * d ? dl * (float)hw[j] : 0.f;
+    dY[(size_t)u * n * d + j] = g;
+    dYb[(size_t)u * n * d + j] = (__bf16)g;
+    if (j < m * d) unsafeAtomicAdd(dhw + j, dl * y[j]);
+  }
+}
+
+// dG = the global rows of dO + the global rows of dR; dM[u][t] = dR's row of merged token t (zeros past T_u)
+__global__ __launch_bounds__(256) void bw_split_grad_kernel(StackGeom g, int d, const float* __restrict__ dO,
+                                                            const float* __restrict__ dR, float* __restrict__ dG,
+                                                            float* __restrict__ dM) {
+  const int n = g.m + g.k, nk = g.m + g.T, d4 = d / 4;
+  const size_t total = (size_t)g.B * nk * d4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const int c = (int)(i % d4) * 4;
+    const size_t row = i / d4;
+    const int u = (int)(row / nk), r = (int)(row - (size_t)u * nk);
+    const f32x4 v = *(const f32x4*)(dR + row * d + c);
+    if (r < g.m) {
+      *(f32x4*)(dG + ((size_t)u * g.m + r) * d + c) = v + *(const f32x4*)(dO + ((size_t)u * n + r) * d + c);
+    } else {
+      const int t = r - g.m;
+      f32x4 z = {0.f, 0.f, 0.f, 0.f};
+      *(f32x4*)(dM + ((size_t)u * g.T + t) * d + c) = t < merged_len(g, u) ? v : z;
+    }
+  }
+}
+// dM[u][t_i] += dO's row of query slot i (each slot of a user holds a different merged token)
+__global__ __launch_bounds__(256) void bw_slot_grad_kernel(StackGeom g, int d, const float* __restrict__ dO,
+                                                           const int* __restrict__ qdesc, float* __restrict__ dM) {
+  const int n = g.m + g.k, d4 = d / 4;
+  const size_t total = (size_t)g.B * g.k * d4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const int c = (int)(i % d4) * 4;
+    const size_t s = i / d4;
+    const int u = (int)(s / g.k), sl = (int)(s - (size_t)u * g.k);
+    const int dsc = qdesc[(size_t)u * n + g.m + sl];
+    if (dsc < kSeq) continue;
+    float* dst = dM + ((size_t)u * g.T + (dsc - kSeq)) * d + c;
+    *(f32x4*)dst = *(const f32x4*)dst + *(const f32x4*)(dO + ((size_t)u * n + g.m + sl) * d + c);
+  }
 }
 
 // ------------------------------------------------------------------------------------ host side
@@ -769,10 +1083,10 @@ static int launched(const char* what) {
   return hipGetLastError() == hipSuccess ? 0 : api_error(LONGER_ERR_HIP, "%s launch failed", what);
 }
 
-static int reduce(hipStream_t st, const float* part, int nsplit, int count, float* out) {
+static int reduce(hipStream_t st, const float* part, int nsplit, int count, float* out, bool accumulate = false) {
   int shares = nsplit / 32;                 // at least 32 slices per block
   shares = shares < 1 ? 1 : (shares > 64 ? 64 : shares);
-  bw_reduce_kernel<<<dim3((count / 4 + 63) / 64, shares), 256, 0, st>>>(part, nsplit, count, out);
+  bw_reduce_kernel<<<dim3((count / 4 + 63) / 64, shares), 256, 0, st>>>(part, nsplit, count, out, accumulate ? 1 : 0);
   return launched("gradient reduction");
 }
 
@@ -789,19 +1103,20 @@ static int gemm(hipStream_t st, bool a_kc, bool b_kc, GemmArgs g, int splits) {
   return launched("backward GEMM");
 }
 
-// y = x W (+ epilogue): x [ntok][kc] row-major, W [kc][n] row-major
+// y = x W (+ epilogue): x [ntok][kc] row-major, W [kc][.. n columns, pitch ldb] row-major; outputs,
+// residual and pre-activation [ntok][n]
 static int gemm_rows(hipStream_t st, const __bf16* x, int kc, const __bf16* W, int n, size_t ntok, int epi, int act,
-                     void* out, void* out2, const __bf16* bias, const float* res, const __bf16* pre) {
+                     void* out, void* out2, const __bf16* bias, const float* res, const __bf16* pre, int ldb = 0) {
   GemmArgs g = {};
-  g.A = x; g.lda = kc; g.B = W; g.ldb = n; g.M = (int)ntok; g.N = n; g.Kc = kc; g.kslice = kc;
+  g.A = x; g.lda = kc; g.B = W; g.ldb = ldb ? ldb : n; g.M = (int)ntok; g.N = n; g.Kc = kc; g.kslice = kc;
   g.epi = epi; g.act = act; g.out = out; g.out2 = out2; g.ldo = n; g.bias = bias; g.res = res; g.pre = pre;
   return gemm(st, true, false, g, 1);
 }
-// dx = dy W^T: dy [ntok][kc], W [n][kc] row-major (the forward's [in = n][out = kc])
+// dx = dy W^T: dy [ntok][kc], W [n][.. kc columns, pitch ldb] row-major (the forward's [in = n][out = kc])
 static int gemm_rows_t(hipStream_t st, const __bf16* dy, int kc, const __bf16* W, int n, size_t ntok, int epi, int act,
-                       void* out, const __bf16* pre) {
+                       void* out, const __bf16* pre, int ldb = 0) {
   GemmArgs g = {};
-  g.A = dy; g.lda = kc; g.B = W; g.ldb = kc; g.M = (int)ntok; g.N = n; g.Kc = kc; g.kslice = kc;
+  g.A = dy; g.lda = kc; g.B = W; g.ldb = ldb ? ldb : kc; g.M = (int)ntok; g.N = n; g.Kc = kc; g.kslice = kc;
   g.epi = epi; g.act = act; g.out = out; g.ldo = n; g.pre = pre;
   return gemm(st, true, true, g, 1);
 }
@@ -837,7 +1152,7 @@ static void ln_fwd(hipStream_t st, unsigned grid, int d, const float* x, const _
 }
 // dgb: the gain gradient [d] followed directly by the shift gradient [d]
 static int ln_bwd(hipStream_t st, unsigned grid, int d, const __bf16* dn, const float* x, const __bf16* g, const float* dres,
-                  float* dx, __bf16* dxb, float* part, float* dgb, int ntok, float eps) {
+                  float* dx, __bf16* dxb, float* part, float* dgb, int ntok, float eps, bool accumulate = false) {
   switch (d) {
     case 32: bw_ln_bwd_kernel<8><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
     case 64: bw_ln_bwd_kernel<16><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
@@ -845,7 +1160,7 @@ static int ln_bwd(hipStream_t st, unsigned grid, int d, const __bf16* dn, const 
     default: bw_ln_bwd_kernel<64><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
   }
   if (hipGetLastError() != hipSuccess) return api_error(LONGER_ERR_HIP, "LayerNorm backward launch failed");
-  return reduce(st, part, (int)grid, 2 * d, dgb);
+  return reduce(st, part, (int)grid, 2 * d, dgb, accumulate);
 }
 
 static unsigned flat_grid(size_t n) {
@@ -947,6 +1262,257 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
   return 0;
 }
 
+
+// ------------------------------------------------------------------------------------
+// Whole model: loss and every gradient (longer_forward_backward)
+struct StackDims { int d, f, heads, dh, m, k, n, T, B, layers; size_t rq, rk; };   // layers = 1 + n_self
+
+struct StackWs {
+  size_t fwd_ws, Mb, dM;                  // forward token merge: its scratch, M (bf16), and the gradient handed to the merge
+  size_t qdesc, kdesc, wcat, bcat;
+  size_t Rx, xs;                          // cross-layer key rows; the layers' input rows ([layers + 1][rq][d], [0] = O)
+  size_t n1q, n1k, qkv, kv, o, xmid, n2, h, a, stat;    // every layer's intermediates are kept (per_layer bytes apart):
+  size_t per_layer;                                     // the reduced stack is small, only the merge is recomputed
+  size_t dy, dyb, dh, dnq, dnk, dxm, dxmb, dob, dqkv, dkv, dR, part, bpart;
+  size_t total;
+};
+static StackWs stack_ws(const StackDims& s, size_t fwd_bytes) {
+  StackWs w;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
+  const size_t rq = s.rq, rk = s.rk, d = s.d, f = s.f;
+  w.fwd_ws = take(fwd_bytes);
+  w.Mb = take((size_t)s.B * s.T * d * 2);
+  w.dM = take((size_t)s.B * s.T * d * 4);
+  w.qdesc = take(rq * 4);
+  w.kdesc = take(rk * 4);
+  w.wcat = take((size_t)s.layers * d * 3 * d * 2);
+  w.bcat = take((size_t)s.layers * up256(3 * d * 2));
+  w.Rx = take(rk * d * 4);
+  w.xs = take((size_t)(s.layers + 1) * rq * d * 4);
+  const size_t layer0 = o;
+  w.n1q = take(rq * d * 2);
+  w.n1k = take(rk * d * 2);
+  w.qkv = take(rq * 3 * d * 2);
+  w.kv = take(rk * 2 * d * 2);
+  w.o = take(rq * d * 2);
+  w.xmid = take(rq * d * 4);
+  w.n2 = take(rq * d * 2);
+  w.h = take(rq * f * 2);
+  w.a = take(rq * f * 2);
+  w.stat = take(rq * s.heads * 8);
+  w.per_layer = o - layer0;
+  o += (size_t)(s.layers - 1) * w.per_layer;
+  w.dy = take(rq * d * 4);
+  w.dyb = take(rq * d * 2);
+  w.dh = take(rq * f * 2);
+  w.dnq = take(rq * d * 2);
+  w.dnk = take(rk * d * 2);
+  w.dxm = take(rq * d * 4);
+  w.dxmb = take(rq * d * 2);
+  w.dob = take(rq * d * 2);
+  w.dqkv = take(rq * 3 * d * 2);
+  w.dkv = take(rk * 2 * d * 2);
+  w.dR = take(rk * d * 4);
+  w.part = take(kPartialBytes);
+  w.bpart = take((size_t)kMaxPartials * 2048 * 4);
+  w.total = o;
+  return w;
+}
+
+static int check_stack(const longer_config* c, int B, int L, StackDims* s) {
+  if (c->q_learn) return api_error(LONGER_ERR_ARG, "learnable query tokens are not differentiated");
+  if (c->gmask != LONGER_GMASK_FULL && c->gmask != LONGER_GMASK_CAUSAL) return api_error(LONGER_ERR_ARG, "gmask %d unknown", c->gmask);
+  const int d = c->d;
+  if (d != 32 && d != 64 && d != 128 && d != 256) return api_error(LONGER_ERR_ARG, "width %d unsupported (32, 64, 128 or 256)", d);
+  if (c->heads <= 0 || d % c->heads || (d / c->heads != 16 && d / c->heads != 32))
+    return api_error(LONGER_ERR_ARG, "heads=%d: head width must be 16 or 32", c->heads);
+  if (c->ffn_mult * d > 2048) return api_error(LONGER_ERR_ARG, "ffn_mult=%d: the FFN hidden width must be at most 2048", c->ffn_mult);
+  if (c->m <= 0 || c->k_recent <= 0 || c->n_self < 0 || c->n_self > 30) return api_error(LONGER_ERR_ARG, "m, k_recent, n_self out of range");
+  if (c->k_uniform < 0 || c->k_uniform > c->k_recent) return api_error(LONGER_ERR_ARG, "k_uniform=%d must lie in [0, k_recent]", c->k_uniform);
+  s->d = d; s->f = c->ffn_mult * d; s->heads = c->heads; s->dh = d / c->heads; s->m = c->m; s->k = c->k_recent;
+  s->n = c->m + c->k_recent; s->T = (L + c->K - 1) / c->K; s->B = B; s->layers = 1 + c->n_self;
+  s->rq = (size_t)B * s->n; s->rk = (size_t)B * (c->m + s->T);
+  if (s->rk * (size_t)s->heads * kSplit >= ((size_t)1 << 31) - 256) return api_error(LONGER_ERR_ARG, "too many key rows for one call; split the batch");
+  return 0;
+}
+
+// layout of the gradient buffer: [InnerTrans blocks][cross block][self blocks][head_w (m d)][head_b (1)]
+struct ModelGrads { size_t inner, cross, self0, head_w, head_b, total, per_main; };
+static ModelGrads model_grads(const Dims& mi, const StackDims& s) {
+  ModelGrads g;
+  g.inner = 0;
+  g.cross = (size_t)mi.layers * grad_layout(mi.d, mi.f).total;
+  g.per_main = grad_layout(s.d, s.f).total;
+  g.self0 = g.cross + g.per_main;
+  g.head_w = g.self0 + (size_t)(s.layers - 1) * g.per_main;
+  g.head_b = g.head_w + (size_t)s.m * s.d;
+  g.total = (g.head_b + 1 + 3) & ~(size_t)3;
+  return g;
+}
+
+template <int DH>
+static void set_attn_launch(hipStream_t st, int which, const SetAttn& a, const __bf16* dob, int d, __bf16* o_or_dq, int pitch,
+                            __bf16* dk, __bf16* dv, float2* stat) {
+  const unsigned gq = (unsigned)(((size_t)a.B * a.nq * a.heads * kSplit + 255) / 256);
+  const unsigned gk = (unsigned)(((size_t)a.B * a.nk * a.heads * kSplit + 255) / 256);
+  if (which == 0) bw_set_attn_fwd_kernel<DH><<<gq, 256, 0, st>>>(a, o_or_dq, d, stat);
+  else if (which == 1) bw_set_attn_bwd_q_kernel<DH><<<gq, 256, 0, st>>>(a, dob, d, o_or_dq, pitch, stat);
+  else bw_set_attn_bwd_kv_kernel<DH><<<gk, 256, 0, st>>>(a, dob, d, dk, dv, pitch, stat);
+}
+
+static int run_model(const longer_config* c, const longer_weights* wts, const void* H, const void* G, const int32_t* lens,
+                     int B, int L, const float* labels, float* loss, float* logits, float* dH, float* dG, float* grads,
+                     char* ws, size_t fwd_bytes, hipStream_t st, const Dims& mi, const StackDims& s) {
+  const int d = s.d, f = s.f;
+  const size_t rq = s.rq, rk = s.rk;
+  const StackWs w = stack_ws(s, fwd_bytes);
+  const ModelGrads mg = model_grads(mi, s);
+  const GradLayout gl = grad_layout(d, f);
+  const StackGeom geo = {lens, L, c->K, s.T, s.m, s.k, c->k_uniform, B};
+  int* qdesc = (int*)(ws + w.qdesc);   int* kdesc = (int*)(ws + w.kdesc);
+  __bf16* Mb = (__bf16*)(ws + w.Mb);   float* dM = (float*)(ws + w.dM);     float* Rx = (float*)(ws + w.Rx);
+  auto xs = [&](int l) { return (float*)(ws + w.xs) + (size_t)l * rq * d; };
+  auto wcat = [&](int l) { return (__bf16*)(ws + w.wcat) + (size_t)l * d * 3 * d; };
+  auto bcat = [&](int l) { return (__bf16*)(ws + w.bcat + (size_t)l * up256((size_t)3 * d * 2)); };
+  auto blk = [&](int l) -> const longer_block& { return l == 0 ? wts->cross[0] : wts->self[l - 1]; };
+  __bf16 *n1q, *n1k, *qkv, *kv, *o, *n2, *h, *a;      // the current layer's intermediates
+  float* xmid;
+  float2* stat;
+  auto use_layer = [&](int l) {
+    char* base = ws + (size_t)l * w.per_layer;
+    n1q = (__bf16*)(base + w.n1q); n1k = (__bf16*)(base + w.n1k); qkv = (__bf16*)(base + w.qkv); kv = (__bf16*)(base + w.kv);
+    o = (__bf16*)(base + w.o); xmid = (float*)(base + w.xmid); n2 = (__bf16*)(base + w.n2); h = (__bf16*)(base + w.h);
+    a = (__bf16*)(base + w.a); stat = (float2*)(base + w.stat);
+  };
+  float* dy = (float*)(ws + w.dy);     __bf16* dyb = (__bf16*)(ws + w.dyb); __bf16* dh = (__bf16*)(ws + w.dh);
+  __bf16* dnq = (__bf16*)(ws + w.dnq); __bf16* dnk = (__bf16*)(ws + w.dnk); float* dxm = (float*)(ws + w.dxm);
+  __bf16* dxmb = (__bf16*)(ws + w.dxmb); __bf16* dob = (__bf16*)(ws + w.dob); __bf16* dqkv = (__bf16*)(ws + w.dqkv);
+  __bf16* dkv = (__bf16*)(ws + w.dkv); float* dR = (float*)(ws + w.dR);
+  float* part = (float*)(ws + w.part); float* bpart = (float*)(ws + w.bpart);
+  auto ln_grid = [&](size_t rows) { return (unsigned)((rows + 3) / 4 > 4096 ? 4096 : (rows + 3) / 4); };
+
+  bw_zero_kernel<<<flat_grid(mg.total + 1), 256, 0, st>>>(grads, mg.total);
+  bw_zero_kernel<<<1, 256, 0, st>>>(loss, 1);
+  BW_TRY(launched("zero fill"));
+
+  // ---- forward from the inputs: merged tokens (the fused forward kernel; the merge's intermediates are
+  // recomputed later by its own backward pass), then the stack, keeping every layer's intermediates
+  int rc = longer_token_merge(c, wts->inner, H, lens, B, L, Mb, ws + w.fwd_ws, fwd_bytes, st);
+  if (rc) return rc;
+  bw_desc_kernel<<<flat_grid(rq + rk), 256, 0, st>>>(geo, qdesc, kdesc);
+  bw_build_rows_kernel<<<flat_grid((rq + rk) * d / 4), 256, 0, st>>>(geo, d, (const __bf16*)G, Mb, qdesc, kdesc, xs(0), Rx);
+  BW_TRY(launched("row build"));
+  for (int l = 0; l < s.layers; ++l) {
+    const longer_block& b = blk(l);
+    bw_concat_qkv_kernel<<<64, 256, 0, st>>>((const __bf16*)b.wq, (const __bf16*)b.wk, (const __bf16*)b.wv, (const __bf16*)b.bq,
+                                             (const __bf16*)b.bk, (const __bf16*)b.bv, wcat(l), bcat(l), d);
+    BW_TRY(launched("weight concatenation"));
+  }
+
+  auto attn = [&](int l) {
+    SetAttn t;
+    t.qdesc = qdesc; t.nq = s.n; t.B = B; t.heads = s.heads; t.gmask = c->gmask;
+    if (l == 0) { t.q = qkv; t.qpitch = d; t.k = kv; t.v = kv + d; t.kvpitch = 2 * d; t.kdesc = kdesc; t.nk = s.m + s.T; }
+    else { t.q = qkv; t.qpitch = 3 * d; t.k = qkv + d; t.v = qkv + 2 * d; t.kvpitch = 3 * d; t.kdesc = qdesc; t.nk = s.n; }
+    return t;
+  };
+  // layer l forward from its input rows xs(l) (layer 0: and the key rows Rx), intermediates into the
+  // layer's own buffers; output into y_out (masked to the valid rows)
+  auto forward = [&](int l, float* y_out) -> int {
+    const longer_block& b = blk(l);
+    const float* x = xs(l);
+    use_layer(l);
+    ln_fwd(st, ln_grid(rq), d, x, (const __bf16*)b.ln1_g, (const __bf16*)b.ln1_b, n1q, (int)rq, c->ln_eps);
+    if (l == 0) {
+      ln_fwd(st, ln_grid(rk), d, Rx, (const __bf16*)b.ln1_g, (const __bf16*)b.ln1_b, n1k, (int)rk, c->ln_eps);
+      BW_TRY(launched("LayerNorm"));
+      BW_TRY(gemm_rows(st, n1q, d, wcat(l), d, rq, EPI_BF16, 0, qkv, nullptr, bcat(l), nullptr, nullptr, 3 * d));
+      BW_TRY(gemm_rows(st, n1k, d, wcat(l) + d, 2 * d, rk, EPI_BF16, 0, kv, nullptr, bcat(l) + d, nullptr, nullptr, 3 * d));
+    } else {
+      BW_TRY(launched("LayerNorm"));
+      BW_TRY(gemm_rows(st, n1q, d, wcat(l), 3 * d, rq, EPI_BF16, 0, qkv, nullptr, bcat(l), nullptr, nullptr));
+    }
+    const SetAttn t = attn(l);
+    if (s.dh == 16) set_attn_launch<16>(st, 0, t, nullptr, d, o, 0, nullptr, nullptr, stat);
+    else set_attn_launch<32>(st, 0, t, nullptr, d, o, 0, nullptr, nullptr, stat);
+    BW_TRY(launched("attention"));
+    BW_TRY(gemm_rows(st, o, d, (const __bf16*)b.wo, d, rq, EPI_RES_F32, 0, xmid, nullptr, (const __bf16*)b.bo, x, nullptr));
+    ln_fwd(st, ln_grid(rq), d, xmid, (const __bf16*)b.ln2_g, (const __bf16*)b.ln2_b, n2, (int)rq, c->ln_eps);
+    BW_TRY(launched("LayerNorm"));
+    BW_TRY(gemm_rows(st, n2, d, (const __bf16*)b.w1, f, rq, EPI_ACT, c->act, h, a, (const __bf16*)b.b1, nullptr, nullptr));
+    if (y_out) {
+      BW_TRY(gemm_rows(st, a, f, (const __bf16*)b.w2, d, rq, EPI_RES_F32, 0, y_out, nullptr, (const __bf16*)b.b2, xmid, nullptr));
+      bw_mask_rows_kernel<<<flat_grid(rq * d / 4), 256, 0, st>>>(y_out, nullptr, qdesc, rq, d);
+      BW_TRY(launched("row mask"));
+    }
+    return 0;
+  };
+  for (int l = 0; l < s.layers; ++l) BW_TRY(forward(l, xs(l + 1)));
+
+  // ---- head and loss (Eq. 1-2), and the gradient of the stack's output
+  bw_head_kernel<<<B, 256, 0, st>>>(xs(s.layers), (const __bf16*)wts->head_w, (const __bf16*)wts->head_b, labels, B, s.n, s.m, d,
+                                    logits, loss, dy, dyb, grads + mg.head_w, grads + mg.head_b);
+  BW_TRY(launched("head"));
+
+  // ---- back through the layers
+  for (int l = s.layers - 1; l >= 0; --l) {
+    const longer_block& b = blk(l);
+    float* g = grads + (l == 0 ? mg.cross : mg.self0 + (size_t)(l - 1) * mg.per_main);
+    // rows that were written as zeros pass no gradient
+    bw_mask_rows_kernel<<<flat_grid(rq * d / 4), 256, 0, st>>>(dy, dyb, qdesc, rq, d);
+    BW_TRY(launched("row mask"));
+    use_layer(l);                                  // kept by the forward pass above
+    BW_TRY(gemm_wgrad(st, a, f, f, dyb, d, d, rq, part, bpart, g + gl.w2, g + gl.b2));
+    BW_TRY(gemm_rows_t(st, dyb, d, (const __bf16*)b.w2, f, rq, EPI_DACT, c->act, dh, h));
+    BW_TRY(gemm_wgrad(st, n2, d, d, dh, f, f, rq, part, bpart, g + gl.w1, g + gl.b1));
+    BW_TRY(gemm_rows_t(st, dh, f, (const __bf16*)b.w1, d, rq, EPI_BF16, 0, dnq, nullptr));
+    BW_TRY(ln_bwd(st, ln_grid(rq), d, dnq, xmid, (const __bf16*)b.ln2_g, dy, dxm, dxmb, part, g + gl.ln2_g, (int)rq, c->ln_eps));
+    BW_TRY(gemm_wgrad(st, o, d, d, dxmb, d, d, rq, part, bpart, g + gl.wo, g + gl.bo));
+    BW_TRY(gemm_rows_t(st, dxmb, d, (const __bf16*)b.wo, d, rq, EPI_BF16, 0, dob, nullptr));
+    const SetAttn t = attn(l);
+    if (l == 0) {
+      if (s.dh == 16) {
+        set_attn_launch<16>(st, 1, t, dob, d, dqkv, d, nullptr, nullptr, stat);
+        set_attn_launch<16>(st, 2, t, dob, d, nullptr, 2 * d, dkv, dkv + d, stat);
+      } else {
+        set_attn_launch<32>(st, 1, t, dob, d, dqkv, d, nullptr, nullptr, stat);
+        set_attn_launch<32>(st, 2, t, dob, d, nullptr, 2 * d, dkv, dkv + d, stat);
+      }
+      BW_TRY(launched("attention backward"));
+      BW_TRY(gemm_wgrad(st, n1q, d, d, dqkv, d, d, rq, part, bpart, g + gl.wq, g + gl.bq));
+      BW_TRY(gemm_wgrad(st, n1k, d, d, dkv, 2 * d, d, rk, part, bpart, g + gl.wk, g + gl.bk));
+      BW_TRY(gemm_wgrad(st, n1k, d, d, dkv + d, 2 * d, d, rk, part, bpart, g + gl.wv, g + gl.bv));
+      BW_TRY(gemm_rows_t(st, dqkv, d, wcat(l), d, rq, EPI_BF16, 0, dnq, nullptr, 3 * d));
+      BW_TRY(gemm_rows_t(st, dkv, 2 * d, wcat(l) + d, d, rk, EPI_BF16, 0, dnk, nullptr, 3 * d));
+      // LN1 normalises the query rows and the key rows: its gain / shift gradient is the sum of both;
+      // dO goes to dy (the query rows' gradient), dR to its own buffer
+      BW_TRY(ln_bwd(st, ln_grid(rq), d, dnq, xs(0), (const __bf16*)b.ln1_g, dxm, dy, nullptr, part, g + gl.ln1_g, (int)rq, c->ln_eps, true));
+      BW_TRY(ln_bwd(st, ln_grid(rk), d, dnk, Rx, (const __bf16*)b.ln1_g, nullptr, dR, nullptr, part, g + gl.ln1_g, (int)rk, c->ln_eps, true));
+    } else {
+      if (s.dh == 16) {
+        set_attn_launch<16>(st, 1, t, dob, d, dqkv, 3 * d, nullptr, nullptr, stat);
+        set_attn_launch<16>(st, 2, t, dob, d, nullptr, 3 * d, dqkv + d, dqkv + 2 * d, stat);
+      } else {
+        set_attn_launch<32>(st, 1, t, dob, d, dqkv, 3 * d, nullptr, nullptr, stat);
+        set_attn_launch<32>(st, 2, t, dob, d, nullptr, 3 * d, dqkv + d, dqkv + 2 * d, stat);
+      }
+      BW_TRY(launched("attention backward"));
+      const size_t wofs[3] = {gl.wq, gl.wk, gl.wv}, bofs[3] = {gl.bq, gl.bk, gl.bv};
+      for (int j = 0; j < 3; ++j)
+        BW_TRY(gemm_wgrad(st, n1q, d, d, dqkv + (size_t)j * d, 3 * d, d, rq, part, bpart, g + wofs[j], g + bofs[j]));
+      BW_TRY(gemm_rows_t(st, dqkv, 3 * d, wcat(l), d, rq, EPI_BF16, 0, dnq, nullptr));
+      BW_TRY(ln_bwd(st, ln_grid(rq), d, dnq, xs(l), (const __bf16*)b.ln1_g, dxm, dy, dyb, part, g + gl.ln1_g, (int)rq, c->ln_eps));
+    }
+  }
+  // ---- gradients of the stack's inputs: global tokens (query rows and key rows), merged tokens (key
+  // rows, plus the query slots that hold them)
+  bw_split_grad_kernel<<<flat_grid(rk * d / 4), 256, 0, st>>>(geo, d, dy, dR, dG, dM);
+  bw_slot_grad_kernel<<<flat_grid((size_t)B * s.k * d / 4), 256, 0, st>>>(geo, d, dy, qdesc, dM);
+  BW_TRY(launched("gradient routing"));
+  return 0;
+}
+
 }  // namespace bw
 }  // namespace longer
 
@@ -984,6 +1550,58 @@ int longer_token_merge_backward(const longer_config* cfg, const longer_block* in
   const size_t need = bw::workspace(s.layers, s.ntok, s.d, s.f, s.heads).total;
   if (ws_bytes < need) return api_error(LONGER_ERR_WS, "workspace too small: %zu < %zu bytes", ws_bytes, need);
   return bw::run(cfg, inner, H, lens, B, L, dM, dH_out, grads_out, (char*)ws, (hipStream_t)stream, s);
+}
+
+size_t longer_model_grad_floats(const longer_config* cfg) {
+  bw::Dims mi;
+  bw::StackDims s;
+  if (bw::check(cfg, 1, 1, &mi) || bw::check_stack(cfg, 1, 1, &s)) return 0;
+  return bw::model_grads(mi, s).total;
+}
+
+size_t longer_forward_backward_workspace_bytes(const longer_config* cfg, int B, int L) {
+  bw::Dims mi;
+  bw::StackDims s;
+  if (bw::check(cfg, B, L, &mi) || bw::check_stack(cfg, B, L, &s)) return 0;
+  const size_t fwd = longer_workspace_bytes(cfg, B, L);
+  if (fwd == 0) return 0;
+  return bw::stack_ws(s, fwd).total + bw::workspace(mi.layers, mi.ntok, mi.d, mi.f, mi.heads).total;
+}
+
+int longer_forward_backward(const longer_config* cfg, const longer_weights* w, const void* H, const void* G,
+                            const int32_t* lens, int B, int L, const float* labels,
+                            float* loss_out, float* logits_out, float* dH_out, float* dG_out, float* grads_out,
+                            void* ws, size_t ws_bytes, void* stream) {
+  bw::Dims mi;
+  bw::StackDims s;
+  int rc = bw::check(cfg, B, L, &mi);
+  if (rc) return rc;
+  rc = bw::check_stack(cfg, B, L, &s);
+  if (rc) return rc;
+  if (!w || !w->inner || !w->cross || (cfg->n_self && !w->self) || !w->head_w || !w->head_b || !H || !G || !labels || !loss_out ||
+      !dH_out || !dG_out || !grads_out || !ws)
+    return api_error(LONGER_ERR_ARG, "null pointer argument");
+  const void* ptrs[] = {H, G, labels, loss_out, dH_out, dG_out, grads_out, w->head_w};
+  for (const void* p : ptrs)
+    if (!bw::aligned16(p)) return api_error(LONGER_ERR_ARG, "H, G, labels, loss_out, dH_out, dG_out, grads_out, head_w must be 16-byte aligned");
+  if ((uintptr_t)ws & 255) return api_error(LONGER_ERR_ARG, "ws must be 256-byte aligned");
+  for (int l = 0; l < mi.layers + s.layers; ++l) {
+    const longer_block* b = l < mi.layers ? &w->inner[l] : (l == mi.layers ? &w->cross[0] : &w->self[l - mi.layers - 1]);
+    const void* const* p = (const void* const*)b;
+    for (int i = 0; i < 16; ++i)
+      if (!p[i] || !bw::aligned16(p[i])) return api_error(LONGER_ERR_ARG, "block %d: parameter %d is NULL or not 16-byte aligned", l, i);
+  }
+  const size_t fwd = longer_workspace_bytes(cfg, B, L);
+  if (fwd == 0) return LONGER_ERR_ARG;
+  const size_t stack_bytes = bw::stack_ws(s, fwd).total;
+  const size_t need = stack_bytes + bw::workspace(mi.layers, mi.ntok, mi.d, mi.f, mi.heads).total;
+  if (ws_bytes < need) return api_error(LONGER_ERR_WS, "workspace too small: %zu < %zu bytes", ws_bytes, need);
+  hipStream_t st = (hipStream_t)stream;
+  rc = bw::run_model(cfg, w, H, G, lens, B, L, labels, loss_out, logits_out, dH_out, dG_out, grads_out, (char*)ws, fwd, st, mi, s);
+  if (rc) return rc;
+  // the merge's gradients: dM was left in the stack's workspace; the InnerTrans blocks come first in grads_out
+  const float* dM = (const float*)((char*)ws + bw::stack_ws(s, fwd).dM);
+  return bw::run(cfg, w->inner, H, lens, B, L, dM, dH_out, grads_out, (char*)ws + stack_bytes, st, mi);
 }
 
 }  // extern "C"

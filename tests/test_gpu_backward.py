@@ -157,3 +157,120 @@ def test_backward_argument_errors():
     ccfg = lg.make_config(cfg)
     assert lg.longer_backward_workspace_bytes(ccfg, 4, 64) == 0
     assert "LONGER_BF16" in lg.longer_last_error()
+
+
+# --------------------------------------------------------------------------- whole model
+def _run_model_gpu(case, labels):
+    import paper_2505_04421_amd as lg
+    from gpu_util import guarded_empty
+    cfg = case["cfg"]
+    model = lg.DeviceModel(cfg, case["weights"])
+    dev = model.device
+    B, L = cfg.B, cfg.L
+    H, G = model.upload(case["H"]), model.upload(case["G"])
+    lens = None if case["lens"] is None else torch.from_numpy(case["lens"].astype(np.int32)).to(dev)
+    n_ws = lg.longer_forward_backward_workspace_bytes(model.ccfg, B, L)
+    nf = lg.longer_model_grad_floats(model.ccfg)
+    assert n_ws > 0 and nf > 0, lg.longer_last_error()
+    ws, g_ws = guarded_empty(dev, (n_ws,), torch.uint8)
+    dH, g_dh = guarded_empty(dev, (B, L, cfg.d_in), torch.float32)
+    dG, g_dg = guarded_empty(dev, (B, cfg.m, cfg.d), torch.float32)
+    grads, g_gr = guarded_empty(dev, (nf,), torch.float32)
+    logits, g_lg = guarded_empty(dev, (B,), torch.float32)
+    loss, g_ls = guarded_empty(dev, (4,), torch.float32)
+    lab = torch.from_numpy(labels.astype(np.float32)).to(dev)
+    lg.longer_forward_backward(model.ccfg, model.weights, H, G, lens, B, L, lab, loss, logits, dH, dG, grads, ws)
+    torch.cuda.synchronize()
+    for g, what in ((g_ws, "workspace"), (g_dh, "dH_out"), (g_dg, "dG_out"), (g_gr, "grads_out"), (g_lg, "logits"), (g_ls, "loss")):
+        g.check(what)
+    views = lg.model_grad_views(cfg, grads)
+    f64 = lambda t: t.cpu().numpy().astype(np.float64)
+    host = {"inner": [{k: f64(v) for k, v in b.items()} for b in views["inner"]],
+            "cross": {k: f64(v) for k, v in views["cross"].items()},
+            "self": [{k: f64(v) for k, v in b.items()} for b in views["self"]],
+            "head_w": f64(views["head_w"]), "head_b": f64(views["head_b"])}
+    return float(loss[0].item()), f64(logits), f64(dH), f64(dG), host
+
+
+def _compare_model(name, case):
+    cfg = case["cfg"]
+    labels = synth.draw_labels(cfg)
+    _say("model backward case %s: B=%d L=%d d=%d m=%d k=%d n_self=%d inner_layers=%d k_uniform=%d gmask=%s" %
+         (name, cfg.B, cfg.L, cfg.d, cfg.m, cfg.k_recent, cfg.n_self, cfg.inner_layers, cfg.k_uniform, cfg.gmask))
+    loss, logits, dH, dG, grads = _run_model_gpu(case, labels)
+    ref_loss, ref_logits, dH_ref, dG_ref, g_ref = org.model_backward(cfg, case["weights"], case["H"], case["G"], case["lens"], labels)
+    scale = float(np.abs(ref_logits).max()) + 1.0
+    assert np.abs(logits - ref_logits).max() <= 2e-2 * scale, (logits, ref_logits)
+    assert abs(loss - ref_loss) <= 2e-2 * max(1.0, abs(ref_loss)), (loss, ref_loss)
+    _say("  loss %.6f (oracle %.6f), logits max error %.3e" % (loss, ref_loss, np.abs(logits - ref_logits).max()))
+    # The gradients are judged for the batch as a whole and per user: the loss gradient of a user is
+    # (sigmoid(logit) - label) / B times its logit's gradient, so a logit that is 1e-2 off moves that
+    # user's whole gradient by up to that share on top of the rounding of the backward pass itself.
+    TOLM = 1e-1 if cfg.act == "relu" else 4e-2      # ReLU: units that take the other branch of the step, see the top
+    e = _rel(dH, dH_ref)
+    _say("  dH rel-L2 %.3e, dG rel-L2 %.3e" % (e, _rel(dG, dG_ref)))
+    assert e <= TOLM and _rel(dG, dG_ref) <= TOLM
+    lens = case["lens"]
+    for u in range(cfg.B):
+        ln = cfg.L if lens is None else int(min(lens[u], cfg.L))
+        assert not dH[u, ln:].any(), "user %d: padded rows of dH are not zero" % u
+        if np.linalg.norm(dH_ref[u]) > 0:
+            assert _rel(dH[u], dH_ref[u]) <= 2 * TOLM, ("dH", u, _rel(dH[u], dH_ref[u]))
+    groups = [("inner%d" % i, grads["inner"][i], g_ref["inner"][i]) for i in range(cfg.inner_layers)]
+    groups.append(("cross", grads["cross"], g_ref["cross"]))
+    groups += [("self%d" % i, grads["self"][i], g_ref["self"][i]) for i in range(cfg.n_self)]
+    for gname, got, ref in groups:
+        worst = 0.0
+        for k in PARAMS:
+            assert np.isfinite(got[k]).all(), (gname, k)
+            if k == "bk":       # zero in exact arithmetic: judged against b_Q's size
+                e = float(np.linalg.norm(got[k] - ref[k])) / (float(np.linalg.norm(ref["bq"])) or 1.0)
+            else:
+                e = _rel(got[k], ref[k])
+            worst = max(worst, e)
+            assert e <= TOLM, ("grad", gname, k, e)
+        _say("  %-7s worst parameter rel-L2 %.3e" % (gname, worst))
+    assert _rel(grads["head_w"], g_ref["head_w"]) <= TOLM
+    assert abs(grads["head_b"][0] - g_ref["head_b"][0]) <= TOLM * (abs(g_ref["head_b"][0]) + 1.0 / cfg.B)
+
+
+def test_model_backward_c2_shape_ragged():
+    case = _bf16_case("C2", users=6, L=203, ragged=True, len_lo=0, len_hi=203)
+    case["lens"][:3] = [0, 203, 5]
+    _compare_model("C2, 6 ragged users", case)
+
+
+def test_model_backward_c3_shape_sampled_queries_causal_globals():
+    case = _bf16_case("C3", users=3, L=1010, k_uniform=40, gmask="causal", ragged=True, len_lo=500, len_hi=1010)
+    _compare_model("C3, 3 users, recent 60 + uniform 40, causal globals", case)
+
+
+def test_model_backward_head_width_32_relu():
+    case = _bf16_case("C2", users=4, L=130, heads=2, inner_heads=2, act="relu", n_self=1)
+    _compare_model("C2 with head width 32, ReLU", case)
+
+
+def test_model_backward_concat_merge_d256():
+    case = _bf16_case("P1", users=2, L=120, k_recent=12, n_self=1)
+    _compare_model("P1 (concat merge into width 256)", case)
+
+
+def test_model_backward_c3_full_size_sampled_users():
+    """The headline batch (256 users x 2000 tokens): a user's input gradients and logit depend on that
+    user alone (times 1 / B from the mean of Eq. 2), so the oracle computes them user by user."""
+    cfg = synth.CONFIGS["C3"]
+    case = synth.make_case(cfg)
+    labels = synth.draw_labels(cfg)
+    _say("model backward case C3 full size: B=%d L=%d" % (cfg.B, cfg.L))
+    loss, logits, dH, dG, grads = _run_model_gpu(case, labels)
+    assert np.isfinite(dH).all() and np.isfinite(dG).all() and np.isfinite(loss)
+    for k, v in grads["cross"].items():
+        assert np.isfinite(v).all(), k
+    one = cfg.replace(B=1)
+    for u in (0, 101, 255):
+        _, lg_ref, dH_ref, dG_ref, _ = org.model_backward(one, case["weights"], case["H"][u:u + 1], case["G"][u:u + 1], None,
+                                                          labels[u:u + 1])
+        e_h, e_g = _rel(dH[u] * cfg.B, dH_ref[0]), _rel(dG[u] * cfg.B, dG_ref[0])
+        _say("  user %3d: logit %.4f (oracle %.4f), dH rel-L2 %.3e, dG rel-L2 %.3e" % (u, logits[u], lg_ref[0], e_h, e_g))
+        assert abs(logits[u] - lg_ref[0]) <= 2e-2 * (abs(lg_ref[0]) + 1.0)
+        assert e_h <= 8e-2 and e_g <= 8e-2
