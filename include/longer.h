@@ -32,7 +32,8 @@
  *     recent-query slots with a negative merged index) are written as exact zeros.
  *
  * Supported shapes, as (width, head width = width / heads): bf16 (32, 16), (64, 16), (64, 32),
- * (128, 16), (128, 32), (256, 16), (256, 32); fp32 (32, 16), (64, 16).  The pair is checked for the main stack (d, d / heads) and
+ * (128, 16), (128, 32), (256, 16), (256, 32); fp32 (32, 16), (64, 16), (128, 16) (the last as a check of the headline
+ * width without bf16 rounding: one workgroup per compute unit, the reduced stack one launch pair per layer).  The pair is checked for the main stack (d, d / heads) and
  * for the InnerTrans blocks (their width, that width / inner_heads) separately; with
  * LONGER_MERGE_CONCAT the InnerTrans width is d / K.  K and m must divide 32 (K for the merge,
  * m for candidate scoring); the FFN hidden width is ffn_mult * width with (9 + ffn_mult) * width

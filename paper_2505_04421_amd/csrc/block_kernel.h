@@ -1209,6 +1209,22 @@ int launch_block(int mode, int tt, int win, const BlockParams& p, dim3 grid, hip
       hipLaunchKernelGGL((block_kernel<T, D, DH, TTV, MODEV, WV, false, NWV>), grid, dim3(64 * NWV), 0, stream, p); \
   } while (0)
 
+// The one-launch stack keeps a user's K/V hand-over area in LDS beside the weight ring; in fp32 at
+// d >= 128 the two do not fit, and the layers run one launch pair each (the caller's plan knows:
+// stack_in_one_launch in longer_api.hip).
+template <typename T, int D>
+constexpr bool kHasStackKernel = !(sizeof(T) == 4 && D >= 128);
+
+template <typename T, int D, int DH>
+static int launch_stack_mode(const BlockParams& p, dim3 grid, hipStream_t stream) {
+  if constexpr (kHasStackKernel<T, D>) {
+    LONGER_LAUNCH(T, D, DH, 1, MODE_STACK, 16);
+    return 0;
+  } else {
+    return -1;
+  }
+}
+
 #define LONGER_INSTANTIATE(T, D, DH)                                                                  \
   template <>                                                                                         \
   int launch_block<T, D, DH>(int mode, int tt, int win, const BlockParams& p, dim3 grid, hipStream_t stream) { \
@@ -1221,7 +1237,7 @@ int launch_block(int mode, int tt, int win, const BlockParams& p, dim3 grid, hip
         break;                                                                                        \
       case MODE_KVPROJ: LONGER_LAUNCH(T, D, DH, 1, MODE_KVPROJ, 16); break;                           \
       case MODE_ATTN: LONGER_LAUNCH(T, D, DH, 1, MODE_ATTN, 16); break;                               \
-      case MODE_STACK: LONGER_LAUNCH(T, D, DH, 1, MODE_STACK, 16); break;                             \
+      case MODE_STACK: if (launch_stack_mode<T, D, DH>(p, grid, stream)) return -1; break;           \
       case MODE_INPUT: LONGER_LAUNCH(T, D, DH, 1, MODE_INPUT, 16); break;                             \
       case MODE_MERGE_IN:                                                                             \
         if (win == 4) LONGER_LAUNCH(T, D, DH, 1, MODE_MERGE_IN, 4);                                   \

@@ -23,6 +23,7 @@ template <> int launch_block<__bf16, 128, 32>(int, int, int, const BlockParams&,
 template <> int launch_block<__bf16, 256, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_block<float, 32, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_block<float, 64, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
+template <> int launch_block<float, 128, 16>(int, int, int, const BlockParams&, dim3, hipStream_t);
 
 template <> int launch_pair<128, 16>(int, int, const BlockParams&, dim3, hipStream_t);
 template <> int launch_pair<128, 32>(int, int, const BlockParams&, dim3, hipStream_t);
@@ -57,6 +58,7 @@ static launch_fn find_launch(int dtype, int D, int DH) {
   } else if (dtype == LONGER_F32) {
     if (D == 32 && DH == 16) return &launch_block<float, 32, 16>;
     if (D == 64 && DH == 16) return &launch_block<float, 64, 16>;
+    if (D == 128 && DH == 16) return &launch_block<float, 128, 16>;   // every mode but the one-launch stack
   }
   return nullptr;
 }
@@ -392,7 +394,8 @@ struct PackedLayout {
   size_t inner_stride, score_stride;
 };
 
-static bool stack_in_one_launch(const Shape& s) { return s.n <= 32 * kWaves; }   // a user's reduced rows fit one workgroup
+// a user's reduced rows fit one workgroup, and the stack kernel exists for the shape (block_kernel.h: kHasStackKernel)
+static bool stack_in_one_launch(const Shape& s) { return s.n <= 32 * kWaves && !(s.es == 4 && s.D >= 128); }
 // which launches run on the two-wave kernels (their parts of the packed parameters are in the pair layouts)
 static bool pair_stack(const Shape& s) { return s.pair && s.D == 128 && stack_in_one_launch(s); }   // (LDS: the K/V hand-over area fits at d = 128)
 static bool pair_score(const Shape& s) { return s.pair != nullptr; }

@@ -123,6 +123,20 @@ def test_fp32_d64():
     _entry_points(synth.make_case(cfg), TOL["f32"])
 
 
+def test_fp32_headline_width_d128():
+    """The headline model shape (d = 128, 8 heads, two InnerTrans blocks, three self layers, m = 8, k = 100,
+    K = 8) in fp32 on a few ragged users: the same kernels without bf16 rounding, so that an error of the
+    logic at this width cannot hide inside the bf16 tolerance.  Forward entry points and serving."""
+    cfg = synth.CONFIGS["C3"].replace(dtype="f32", B=3, L=333, ragged=True, len_lo=1, len_hi=333, index=31)
+    case = synth.make_case(cfg)
+    case["lens"][0] = 333
+    _say("fp32 d=128 (C3's model shape, 3 ragged users)")
+    _entry_points(case, TOL["f32"])
+    scfg = cfg.replace(C=5, index=32)
+    _say("fp32 d=128 serving")
+    _serving(synth.make_case(scfg), TOL["f32"])
+
+
 @pytest.mark.parametrize("k_recent,gmask", [(124, "full"), (150, "causal")])
 def test_bf16_wide_query_sets(k_recent, gmask):
     """m + k = 128 fills the one-workgroup-per-user stack kernel exactly; m + k = 154 does not
