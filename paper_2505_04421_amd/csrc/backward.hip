@@ -770,7 +770,19 @@ struct SetAttn {
   const __bf16* k; const __bf16* v; int kvpitch;   // [B nk][..]
   const int* qdesc; const int* kdesc;
   int nq, nk, B, heads, gmask;
+  int m, self;                          // global rows come first in both sets; self: the key rows are the query rows
 };
+
+// Keys a query row can see at all lie in [lo, hi) of its user's key rows: a sequence query sees no global
+// row and nothing newer than itself (its own row in a self layer, its merged token's row in the cross
+// layer); the visibility test inside the loops still decides each pair.
+__device__ __forceinline__ void key_range(const SetAttn& a, int qd, int i, int* lo, int* hi) {
+  *lo = 0; *hi = a.nk;
+  if (qd >= kSeq) {
+    *lo = a.m;
+    *hi = min(a.nk, a.self ? i + 1 : a.m + (qd - kSeq) + 1);
+  }
+}
 
 // The set-attention kernels give a (row, head) pair to kSplit adjacent lanes, each taking every kSplit-th
 // key (query) of the loop, and combine the lanes' partial results with cross-lane shuffles: the loops
@@ -805,17 +817,23 @@ __global__ __launch_bounds__(256) void bw_set_attn_fwd_kernel(SetAttn a, __bf16*
     const float scale = rsqrtf((float)DH);
     float qv[DH], kv[DH];
     load_head<DH>(a.q + (size_t)row * a.qpitch + h * DH, qv);
-    for (int j = sub; j < a.nk; j += kSplit) {
+    int lo, hi;
+    key_range(a, qd, row - u * a.nq, &lo, &hi);
+    // every row of the range is loaded, a hidden key weighs nothing: no branch in the loop, so that the
+    // loads of several keys are in flight at once
+    float vv[DH];
+#pragma unroll(DH == 16 ? 4 : 2)
+    for (int j = lo + sub; j < hi; j += kSplit) {
       const size_t kr = (size_t)u * a.nk + j;
-      if (!visible(qd, a.kdesc[kr], a.gmask)) continue;
+      const bool vis = visible(qd, a.kdesc[kr], a.gmask);
       load_head<DH>(a.k + kr * a.kvpitch + h * DH, kv);
-      const float sc = scale * dot<DH>(qv, kv);
+      load_head<DH>(a.v + kr * a.kvpitch + h * DH, vv);
+      const float sc = vis ? scale * dot<DH>(qv, kv) : -3.0e38f;
       const float mn = fmaxf(mx, sc);
-      const float corr = __expf(mx - mn), p = __expf(sc - mn);
-      load_head<DH>(a.v + kr * a.kvpitch + h * DH, kv);
+      const float corr = __expf(mx - mn), p = vis ? __expf(sc - mn) : 0.f;
       l = l * corr + p;
 #pragma unroll
-      for (int c = 0; c < DH; ++c) acc[c] = acc[c] * corr + p * kv[c];
+      for (int c = 0; c < DH; ++c) acc[c] = acc[c] * corr + p * vv[c];
       mx = mn;
     }
   }
@@ -851,7 +869,10 @@ __global__ __launch_bounds__(256) void bw_set_attn_bwd_q_kernel(SetAttn a, const
     float qv[DH], dov[DH], kv[DH], vv[DH];
     load_head<DH>(a.q + (size_t)row * a.qpitch + h * DH, qv);
     load_head<DH>(dob + (size_t)row * d + h * DH, dov);
-    for (int j = sub; j < a.nk; j += kSplit) {
+    int lo, hi;
+    key_range(a, qd, row - u * a.nq, &lo, &hi);
+    // (branch-free, unrolled loops as in the forward kernel were slower here: more live registers)
+    for (int j = lo + sub; j < hi; j += kSplit) {
       const size_t kr = (size_t)u * a.nk + j;
       if (!visible(qd, a.kdesc[kr], a.gmask)) continue;
       load_head<DH>(a.k + kr * a.kvpitch + h * DH, kv);
@@ -891,7 +912,11 @@ __global__ __launch_bounds__(256) void bw_set_attn_bwd_kv_kernel(SetAttn a, cons
     float kv[DH], vv[DH], qi[DH], doi[DH];
     load_head<DH>(a.k + (size_t)kr * a.kvpitch + h * DH, kv);
     load_head<DH>(a.v + (size_t)kr * a.kvpitch + h * DH, vv);
-    for (int i = sub; i < a.nq; i += kSplit) {
+    // a sequence key of a self layer is seen by the global rows and by the slots from its own on
+    const int own = kr - u * a.nk;
+    const int skip_lo = a.m, skip_hi = (a.self && kd >= kSeq) ? max(a.m, own) : a.m;
+    for (int i0 = sub; i0 < a.nq - (skip_hi - skip_lo); i0 += kSplit) {
+      const int i = i0 < skip_lo ? i0 : i0 + (skip_hi - skip_lo);      // the rows outside [skip_lo, skip_hi)
       const size_t qr = (size_t)u * a.nq + i;
       if (!visible(a.qdesc[qr], kd, a.gmask)) continue;
       load_head<DH>(a.q + qr * a.qpitch + h * DH, qi);
@@ -1412,7 +1437,7 @@ static int run_model(const longer_config* c, const longer_weights* wts, const vo
 
   auto attn = [&](int l) {
     SetAttn t;
-    t.qdesc = qdesc; t.nq = s.n; t.B = B; t.heads = s.heads; t.gmask = c->gmask;
+    t.qdesc = qdesc; t.nq = s.n; t.B = B; t.heads = s.heads; t.gmask = c->gmask; t.m = s.m; t.self = l != 0;
     if (l == 0) { t.q = qkv; t.qpitch = d; t.k = kv; t.v = kv + d; t.kvpitch = 2 * d; t.kdesc = kdesc; t.nk = s.m + s.T; }
     else { t.q = qkv; t.qpitch = 3 * d; t.k = qkv + d; t.v = qkv + 2 * d; t.kvpitch = 3 * d; t.kdesc = qdesc; t.nk = s.n; }
     return t;
