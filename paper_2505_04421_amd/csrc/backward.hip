@@ -28,6 +28,8 @@
 namespace longer {
 
 int api_error(int code, const char* fmt, ...);   // longer_api.hip
+int inner_chain_f32(const longer_config* cfg, const longer_block* inner, int layers, const void* H, const int32_t* lens,
+                    int B, int L, float* Z_out, void* ws, size_t ws_bytes, void* stream);   // longer_api.hip
 
 namespace bw {
 
@@ -669,6 +671,16 @@ __global__ __launch_bounds__(256) void bw_reduce_kernel(const float* __restrict_
   }
 }
 
+// rows [B][T K][d] -> [B][L][d] (the first L rows of every user)
+__global__ __launch_bounds__(256) void bw_take_rows_kernel(const float* __restrict__ src, float* __restrict__ dst, int B, int L,
+                                                           int TK, int d) {
+  const size_t per = (size_t)L * d / 4, total = per * B;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t u = i / per, r = i - u * per;
+    *(f32x4*)(dst + (u * L * d + r * 4)) = *(const f32x4*)(src + (u * TK * d + r * 4));
+  }
+}
+
 __global__ __launch_bounds__(256) void bw_zero_kernel(float* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
 }
@@ -1041,9 +1053,10 @@ struct Workspace {
   size_t n1, qkv, o, xmid, n2, h, a;       // one block's recomputed intermediates
   size_t dy, dyb, dh, dn, dxm, dxmb, dob, dqkv, stat;
   size_t part, bpart;                      // partial parameter gradients of one split GEMM (matrix, bias)
+  size_t fwd, fwd_bytes, ztmp;             // the fused forward kernel's scratch and output when it recomputes block inputs
   size_t total;
 };
-static Workspace workspace(int layers, size_t ntok, int d, int f, int heads) {
+static Workspace workspace(int layers, size_t ntok, int d, int f, int heads, size_t fwd_bytes, size_t ztmp_bytes) {
   Workspace w;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
@@ -1068,11 +1081,26 @@ static Workspace workspace(int layers, size_t ntok, int d, int f, int heads) {
   w.stat = take(ntok * heads * 8);
   w.part = take(kPartialBytes);
   w.bpart = take((size_t)kMaxPartials * 2048 * 4);
+  w.fwd = take(fwd_bytes);
+  w.fwd_bytes = fwd_bytes;
+  w.ztmp = take(ztmp_bytes);
   w.total = o;
   return w;
 }
 
 struct Dims { int d, f, heads, dh, layers, K, T; size_t ntok; };
+
+// the merge backward's workspace for a batch: with more than one block the fused forward kernel
+// recomputes the block inputs (its scratch; a staging copy when L is not a multiple of K, whose rows
+// then sit at [B, T K] instead of [B, L])
+static Workspace merge_workspace(const longer_config* c, const Dims& s, int B, int L) {
+  size_t fwd = 0, zt = 0;
+  if (s.layers > 1) {
+    fwd = longer_workspace_bytes(c, B, L);
+    if (L % s.K) zt = (size_t)B * s.T * s.K * s.d * 4;
+  }
+  return workspace(s.layers, s.ntok, s.d, s.f, s.heads, fwd, zt);
+}
 
 static int check(const longer_config* c, int B, int L, Dims* s) {
   if (!c) return api_error(LONGER_ERR_ARG, "config is NULL");
@@ -1199,7 +1227,7 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
                const float* dM, float* dH, float* grads, char* ws, hipStream_t st, const Dims& s) {
   const int d = s.d, f = s.f;
   const size_t nt = s.ntok;
-  const Workspace w = workspace(s.layers, nt, d, f, s.heads);
+  const Workspace w = merge_workspace(c, s, B, L);
   const GradLayout gl = grad_layout(d, f);
   const RowGeom q = {lens, L, s.K, (int)nt};
   auto xin = [&](int l) { return (float*)(ws + w.xin) + (size_t)l * nt * d; };
@@ -1247,8 +1275,17 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     return 0;
   };
 
-  // the chain of block inputs (recomputed: nothing is kept from a forward call)
-  for (int l = 0; l + 1 < s.layers; ++l) BW_TRY(forward(l, xin(l + 1)));
+  // the chain of block inputs (recomputed: nothing is kept from a forward call), by the fused forward
+  // kernel: its fp32 residual stream after l + 1 blocks is block l + 1's input
+  for (int l = 0; l + 1 < s.layers; ++l) {
+    const bool direct = L % s.K == 0;
+    float* z = direct ? xin(l + 1) : (float*)(ws + w.ztmp);
+    BW_TRY(inner_chain_f32(c, inner, l + 1, H, lens, B, L, z, ws + w.fwd, w.fwd_bytes, st));
+    if (!direct) {
+      bw_take_rows_kernel<<<flat_grid(nt * d / 4), 256, 0, st>>>(z, xin(l + 1), B, L, s.T * s.K, d);
+      BW_TRY(launched("row copy"));
+    }
+  }
 
   bw_merge_bwd_kernel<<<flat_grid(nt * d / 4), 256, 0, st>>>(dM, dy, dyb, q, d, s.T, c->merge == LONGER_MERGE_CONCAT);
   BW_TRY(launched("merge gradient"));
@@ -1548,7 +1585,7 @@ extern "C" {
 size_t longer_backward_workspace_bytes(const longer_config* cfg, int B, int L) {
   bw::Dims s;
   if (bw::check(cfg, B, L, &s)) return 0;
-  return bw::workspace(s.layers, s.ntok, s.d, s.f, s.heads).total;
+  return bw::merge_workspace(cfg, s, B, L).total;
 }
 
 size_t longer_block_grad_floats(const longer_config* cfg) {
@@ -1572,7 +1609,7 @@ int longer_token_merge_backward(const longer_config* cfg, const longer_block* in
     for (int i = 0; i < 16; ++i)
       if (!p[i] || !bw::aligned16(p[i])) return api_error(LONGER_ERR_ARG, "InnerTrans block %d: parameter %d is NULL or not 16-byte aligned", l, i);
   }
-  const size_t need = bw::workspace(s.layers, s.ntok, s.d, s.f, s.heads).total;
+  const size_t need = bw::merge_workspace(cfg, s, B, L).total;
   if (ws_bytes < need) return api_error(LONGER_ERR_WS, "workspace too small: %zu < %zu bytes", ws_bytes, need);
   return bw::run(cfg, inner, H, lens, B, L, dM, dH_out, grads_out, (char*)ws, (hipStream_t)stream, s);
 }
@@ -1590,7 +1627,7 @@ size_t longer_forward_backward_workspace_bytes(const longer_config* cfg, int B, 
   if (bw::check(cfg, B, L, &mi) || bw::check_stack(cfg, B, L, &s)) return 0;
   const size_t fwd = longer_workspace_bytes(cfg, B, L);
   if (fwd == 0) return 0;
-  return bw::stack_ws(s, fwd).total + bw::workspace(mi.layers, mi.ntok, mi.d, mi.f, mi.heads).total;
+  return bw::stack_ws(s, fwd).total + bw::merge_workspace(cfg, mi, B, L).total;
 }
 
 int longer_forward_backward(const longer_config* cfg, const longer_weights* w, const void* H, const void* G,
@@ -1619,7 +1656,7 @@ int longer_forward_backward(const longer_config* cfg, const longer_weights* w, c
   const size_t fwd = longer_workspace_bytes(cfg, B, L);
   if (fwd == 0) return LONGER_ERR_ARG;
   const size_t stack_bytes = bw::stack_ws(s, fwd).total;
-  const size_t need = stack_bytes + bw::workspace(mi.layers, mi.ntok, mi.d, mi.f, mi.heads).total;
+  const size_t need = stack_bytes + bw::merge_workspace(cfg, mi, B, L).total;
   if (ws_bytes < need) return api_error(LONGER_ERR_WS, "workspace too small: %zu < %zu bytes", ws_bytes, need);
   hipStream_t st = (hipStream_t)stream;
   rc = bw::run_model(cfg, w, H, G, lens, B, L, labels, loss_out, logits_out, dH_out, dG_out, grads_out, (char*)ws, fwd, st, mi, s);

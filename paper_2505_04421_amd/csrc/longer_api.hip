@@ -768,7 +768,7 @@ int longer_pack_weights(const longer_config* cfg, const longer_weights* w, const
 }
 
 static int merge_entry(const longer_config* cfg, const longer_block* inner, const void* H, const int32_t* lens,
-                       int B, int L, void* M_out, void* Z_out, void* ws, size_t ws_bytes, void* stream) {
+                       int B, int L, void* M_out, void* Z_out, void* ws, size_t ws_bytes, void* stream, int z_f32 = 0) {
   Shape s;
   int rc = check_cfg(cfg, &s, true, false);
   if (rc) return rc;
@@ -785,7 +785,7 @@ static int merge_entry(const longer_config* cfg, const longer_block* inner, cons
   if ((rc = pk_batch.flush())) return rc;
   // a concat merge is the un-pooled output [B, T, K, d / K] read as [B, T, d]
   if (cfg->merge == LONGER_MERGE_CONCAT && M_out) { Z_out = M_out; M_out = nullptr; }
-  return run_merge(cfg, si, w8 + l.packed, H, lens, B, L, M_out, 0, Z_out, 0, st);
+  return run_merge(cfg, si, w8 + l.packed, H, lens, B, L, M_out, 0, Z_out, z_f32, st);
 }
 
 int longer_inner_transformer(const longer_config* cfg, const longer_block* inner, const void* H, const int32_t* lens,
@@ -1149,3 +1149,16 @@ int longer_probe_mfma_layout(int32_t* out, void* stream) {
 }
 
 }  // extern "C"
+
+namespace longer {
+// For the backward pass (backward.hip): the output rows of the first `layers` InnerTrans blocks as fp32,
+// Z [B, T, K, w] (the fp32 residual stream of the fused kernel, zeros for padded tokens): the input rows
+// of block `layers`, recomputed by the forward kernel.
+__attribute__((visibility("hidden"))) int inner_chain_f32(const longer_config* cfg, const longer_block* inner, int layers,
+                                                          const void* H, const int32_t* lens, int B, int L, float* Z_out,
+                                                          void* ws, size_t ws_bytes, void* stream) {
+  longer_config c = *cfg;
+  c.inner_layers = layers;
+  return merge_entry(&c, inner, H, lens, B, L, nullptr, Z_out, ws, ws_bytes, stream, 1);
+}
+}  // namespace longer

@@ -76,8 +76,9 @@ def merge_backward_work(cfg, lens: Optional[Sequence[int]] = None, B: Optional[i
     block inputs: all blocks but the last; then every block's intermediates, without its second
     FFN product).  ``hbm_bytes``: what the pass's kernels read and write when every tensor makes one
     trip per use, over all B L token rows (padded rows are computed too): per token and block
-    40 w + 4 f bytes for the recomputed intermediates (+ 8 w + 2 f when the block's output is needed),
-    90 w + 10 f for the gradients, 12 w once for the input copy and the merge gradient."""
+    40 w + 4 f bytes for the recomputed intermediates and 90 w + 10 f for the gradients, 6 w for every
+    block input that the fused forward kernel recomputes (it reads the raw tokens and writes fp32 rows),
+    12 w once for the input copy and the merge gradient."""
     B = cfg.B if B is None else B
     L = cfg.L if L is None else L
     w = cfg.d // cfg.K if getattr(cfg, "merge", "mean") == "concat" else cfg.d
@@ -89,5 +90,5 @@ def merge_backward_work(cfg, lens: Optional[Sequence[int]] = None, B: Optional[i
     valid = sum(lens_)
     per_block = inner // max(n, 1)
     recompute = (n - 1) * per_block + n * (per_block - ffn2 * valid)
-    per_token = (n - 1) * (48 * w + 6 * f) + n * (40 * w + 4 * f) + n * (90 * w + 10 * f) + 12 * w
+    per_token = (n - 1) * 6 * w + n * (40 * w + 4 * f) + n * (90 * w + 10 * f) + 12 * w
     return {"gradient_flops": 2 * inner, "recompute_flops": recompute, "hbm_bytes": per_token * B * L}

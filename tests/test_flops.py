@@ -40,8 +40,8 @@ def test_backward_work_tally_by_hand_at_the_headline_shape():
     assert w["gradient_flops"] == 2 * 2 * block
     # recomputed: block 0 in full (the chain of block inputs), then both blocks without the second FFN product
     assert w["recompute_flops"] == block + 2 * (block - tokens * 2 * 128 * 512)
-    # bytes per token: chain 48 w + 6 f, per block 40 w + 4 f recomputed and 90 w + 10 f of gradients, 12 w once
-    assert w["hbm_bytes"] == tokens * ((48 * 128 + 6 * 512) + 2 * (40 * 128 + 4 * 512) + 2 * (90 * 128 + 10 * 512) + 12 * 128)
+    # bytes per token: 6 w for block 1's input, per block 40 w + 4 f recomputed and 90 w + 10 f of gradients, 12 w once
+    assert w["hbm_bytes"] == tokens * (6 * 128 + 2 * (40 * 128 + 4 * 512) + 2 * (90 * 128 + 10 * 512) + 12 * 128)
     # a ragged batch: FLOPs follow the valid tokens, bytes every row
     c = synth.CONFIGS["C2"].replace(B=3)
     r = flops.merge_backward_work(c, [0, 100, 512])
