@@ -551,35 +551,35 @@ __global__ __launch_bounds__(256) void bw_attn_bwd_q_kernel(const __bf16* qkv, c
   for (int c = 0; c < DH; ++c) acc[c] = 0.f;
   float2 st = make_float2(0.f, 0.f);
   if (group_of(q, r, &g)) {
+    // one pass over the group's keys with a running maximum: with e_j = exp(s_j - max), l = sum e_j,
+    // dp_j = do . v_j:  D = sum e_j dp_j / l  and  dq = scale (sum e_j dp_j k_j - D sum e_j k_j) / l
     const float scale = rsqrtf((float)DH);
-    float qv[DH], dov[DH], kv[DH], s[kMaxGroup], dp[kMaxGroup];
+    float qv[DH], dov[DH], kv[DH], vv[DH], Bv[DH];
+#pragma unroll
+    for (int c = 0; c < DH; ++c) Bv[c] = 0.f;
     load_head<DH>(qkv + (size_t)r * 3 * d + h * DH, qv);
     load_head<DH>(dob + (size_t)r * d + h * DH, dov);
-    float mx = -3.0e38f;
+    float mx = -3.0e38f, l = 0.f, Dn = 0.f;
     for (int j = 0; j < g.n; ++j) {
       load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + d + h * DH, kv);
-      s[j] = scale * dot<DH>(qv, kv);
-      mx = fmaxf(mx, s[j]);
-      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + 2 * d + h * DH, kv);
-      dp[j] = dot<DH>(dov, kv);
-    }
-    float l = 0.f;
-    for (int j = 0; j < g.n; ++j) {
-      s[j] = __expf(s[j] - mx);
-      l += s[j];
+      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + 2 * d + h * DH, vv);
+      const float sc = scale * dot<DH>(qv, kv);
+      const float mn = fmaxf(mx, sc);
+      const float corr = __expf(mx - mn), e = __expf(sc - mn);
+      const float ed = e * dot<DH>(dov, vv);
+      l = l * corr + e;
+      Dn = Dn * corr + ed;
+#pragma unroll
+      for (int c = 0; c < DH; ++c) {
+        acc[c] = acc[c] * corr + ed * kv[c];
+        Bv[c] = Bv[c] * corr + e * kv[c];
+      }
+      mx = mn;
     }
     const float inv = 1.f / l;
-    float D = 0.f;
-    for (int j = 0; j < g.n; ++j) {
-      s[j] *= inv;
-      D += s[j] * dp[j];
-    }
-    for (int j = 0; j < g.n; ++j) {
-      const float ds = scale * s[j] * (dp[j] - D);
-      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + d + h * DH, kv);
+    const float D = Dn * inv;
 #pragma unroll
-      for (int c = 0; c < DH; ++c) acc[c] += ds * kv[c];
-    }
+    for (int c = 0; c < DH; ++c) acc[c] = scale * inv * (acc[c] - D * Bv[c]);
     st = make_float2(mx + __logf(l), D);
   }
   store_head<DH>(dqkv + (size_t)r * 3 * d + h * DH, acc);
