@@ -274,3 +274,53 @@ def test_model_backward_c3_full_size_sampled_users():
         _say("  user %3d: logit %.4f (oracle %.4f), dH rel-L2 %.3e, dG rel-L2 %.3e" % (u, logits[u], lg_ref[0], e_h, e_g))
         assert abs(logits[u] - lg_ref[0]) <= 2e-2 * (abs(lg_ref[0]) + 1.0)
         assert e_h <= 8e-2 and e_g <= 8e-2
+
+
+def test_forward_backward_under_hip_graph_capture():
+    """longer_forward_backward allocates nothing, never synchronises and enqueues kernels only: captured
+    into a HIP graph and replayed three times on new inputs (eager work and synchronisation in between),
+    it gives the eager call's input gradients bit for bit and its parameter gradients up to the order of
+    their last atomic additions."""
+    import paper_2505_04421_amd as lg
+    cfg = synth.CONFIGS["C2"].replace(B=12, L=260, ragged=True, len_lo=0, len_hi=260, index=41)
+    case = synth.make_case(cfg)
+    model = lg.DeviceModel(cfg, case["weights"])
+    dev = model.device
+    B, L = cfg.B, cfg.L
+    H, G = model.upload(case["H"]), model.upload(case["G"])
+    lens = torch.from_numpy(case["lens"].astype(np.int32)).to(dev)
+    labels = torch.from_numpy(synth.draw_labels(cfg)).to(dev)
+    ws = torch.empty(lg.longer_forward_backward_workspace_bytes(model.ccfg, B, L), dtype=torch.uint8, device=dev)
+    nf = lg.longer_model_grad_floats(model.ccfg)
+    dH = torch.empty(B, L, cfg.d_in, dtype=torch.float32, device=dev)
+    dG = torch.empty(B, cfg.m, cfg.d, dtype=torch.float32, device=dev)
+    grads = torch.empty(nf, dtype=torch.float32, device=dev)
+    loss = torch.empty(4, dtype=torch.float32, device=dev)
+    logits = torch.empty(B, dtype=torch.float32, device=dev)
+
+    def run():
+        lg.longer_forward_backward(model.ccfg, model.weights, H, G, lens, B, L, labels, loss, logits, dH, dG, grads, ws)
+
+    run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(43)
+    for it in range(3):
+        H.copy_(model.upload(synth.round_bf16(rng.standard_normal(case["H"].shape).astype(np.float32))))
+        G.copy_(model.upload(synth.round_bf16(rng.standard_normal(case["G"].shape).astype(np.float32))))
+        for t in (dH, dG, grads, loss, logits):
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (dH, dG, grads, loss, logits)]
+        for t in (dH, dG, grads, loss, logits):
+            t.zero_()
+        run()
+        torch.cuda.synchronize()
+        _say("  replay %d: loss %.6f (eager %.6f)" % (it, float(got[3][0]), float(loss[0])))
+        assert torch.equal(got[0], dH) and torch.equal(got[1], dG) and torch.equal(got[4], logits)
+        assert torch.allclose(got[2], grads, rtol=1e-4, atol=1e-6 * float(grads.abs().max()))
+        assert abs(float(got[3][0]) - float(loss[0])) <= 1e-5 * max(1.0, abs(float(loss[0])))
