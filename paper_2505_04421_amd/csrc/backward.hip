@@ -53,11 +53,32 @@ enum Epilogue {
                      // per tile and slice; outf[slice][m][n] = acc, summed afterwards by bw_reduce_kernel
 };
 
+// Padded token rows (row r = u L + pos with pos >= the user's length) carry no gradient.  With the
+// batch's geometry at hand a kernel leaves them out: row GEMMs skip tiles without a valid row, the
+// gradient GEMMs read them as zeros, the LayerNorm kernels write zeros for them.  rows_L = 0: every
+// row counts (the reduced stack's rows).
+struct RowsValid { const int32_t* lens; int L; };
+__device__ __forceinline__ bool row_valid(const RowsValid& v, int r) {
+  if (v.L == 0 || v.lens == nullptr) return true;
+  const int u = r / v.L;
+  return r - u * v.L < v.lens[u];
+}
+// any valid row in [r0, r1)?
+__device__ __forceinline__ bool rows_any_valid(const RowsValid& v, int r0, int r1) {
+  if (v.L == 0 || v.lens == nullptr) return true;
+  for (int u = r0 / v.L; u * v.L < r1; ++u) {
+    const int first = max(r0, u * v.L) - u * v.L;
+    if (first < v.lens[u]) return true;
+  }
+  return false;
+}
+
 struct GemmArgs {
+  RowsValid rows;             // of the token dimension (M of a row GEMM, the contraction of a gradient GEMM)
   const __bf16* A; const __bf16* B;
   int lda, ldb;
   int M, N, Kc;
-  int kslice, nsplit;         // split GEMM: contraction range of one slice (multiple of 32), slices
+  int kslice, nsplit;         // split GEMM: number of slices of the contraction (kslice unused)
   int epi, act;
   void* out; void* out2; int ldo;
   const __bf16* bias; const float* res; const __bf16* pre;
@@ -90,7 +111,6 @@ __device__ __forceinline__ float act_grad(float v, int act) {
 
 constexpr int kPitchKC = 40;            // elements per row of a contraction-contiguous LDS tile (32 + 8 pad)
 constexpr int kTileElems = 128 * kPitchKC;   // >= 32 * 128 of the strided form
-constexpr int kDepth = 1;               // contraction steps whose global loads are in flight (more costs registers, and occupancy matters more)
 constexpr int kStagePitch = 68;         // floats per row of the epilogue's staging area (64 + 4 pad)
 
 template <bool A_KC, bool B_KC>
@@ -112,9 +132,13 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
   if (outer >= (split ? g.nsplit : ntm)) return;
   const int mt = split ? in / ntn : outer, nt_ = in % ntn;
   const int m0 = mt * 128, n0 = nt_ * 128;
-  const int kbeg = split ? outer * g.kslice : 0;
-  const int kend = min(g.Kc, kbeg + g.kslice);
-  const int nk = kend > kbeg ? (kend - kbeg + 31) / 32 : 0;
+  // contraction steps of 32: a row GEMM takes them all; slice `outer` of a gradient GEMM takes every
+  // nsplit-th step, so that every slice samples the whole batch (long and short users alike)
+  const int kstride = split ? g.nsplit : 1, kfirst = split ? outer : 0;
+  const int ksteps = (g.Kc + 31) / 32;
+  const int kend = g.Kc;
+  if (!split && !rows_any_valid(g.rows, m0, min(g.M, m0 + 128))) return;   // a tile of padded rows: nobody reads its result
+  const int nk = ksteps > kfirst ? (ksteps - kfirst + kstride - 1) / kstride : 0;
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -138,11 +162,11 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
     for (int r = 0; r < 16; ++r) accb[b][r] = 0.f;
 
   // Operand tiles travel global -> registers -> LDS.  One tile = 512 chunks of 16 bytes, two per
-  // thread; the loads of kDepth contraction steps are in flight at once (a step's eight MFMAs per wave
-  // are far shorter than a load's latency), in a register ring indexed statically.
-  bf16x8 ra[kDepth][2], rb[kDepth][2];
+  // thread.  (Keeping the loads of four steps in flight was measured: 188 registers, two waves per
+  // SIMD instead of four, every GEMM slower.)
+  bf16x8 ra[1][2], rb[1][2];
   auto gload = [&](int kt, bf16x8* pa, bf16x8* pb) {
-    const int k0 = kbeg + kt * 32;
+    const int k0 = (kfirst + kt * kstride) * 32;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int c = tid + 256 * i;
@@ -157,7 +181,7 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
       } else {
         const int kr = c >> 4, xc = c & 15;
         const int gk = k0 + kr, gx = m0 + 8 * xc;
-        if (gk < kend && gx < g.M) pa[i] = *(const bf16x8*)(g.A + (size_t)gk * g.lda + gx);
+        if (gk < kend && gx < g.M && (!split || row_valid(g.rows, gk))) pa[i] = *(const bf16x8*)(g.A + (size_t)gk * g.lda + gx);
       }
       if (B_KC) {
         const int row = c >> 2, kc = c & 3;
@@ -166,7 +190,7 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
       } else {
         const int kr = c >> 4, xc = c & 15;
         const int gk = k0 + kr, gx = n0 + 8 * xc;
-        if (gk < kend && gx < g.N) pb[i] = *(const bf16x8*)(g.B + (size_t)gk * g.ldb + gx);
+        if (gk < kend && gx < g.N && (!split || row_valid(g.rows, gk))) pb[i] = *(const bf16x8*)(g.B + (size_t)gk * g.ldb + gx);
       }
     }
   };
@@ -192,40 +216,42 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
     return f;
   };
 
+  // Contraction steps, two LDS buffers: step's tile goes to LDS (the buffer was last read two steps ago,
+  // which every thread left before the previous step's barrier), the registers are refilled with the
+  // next step's tile, barrier, MFMAs.  A gradient GEMM passes over steps whose 32 token rows are all
+  // padding (the test is the same for the whole workgroup).
+  auto next_step = [&](int kt) {
+    if (split)
+      while (kt < nk && !rows_any_valid(g.rows, (kfirst + kt * kstride) * 32, min(kend, (kfirst + kt * kstride) * 32 + 32))) ++kt;
+    return kt;
+  };
+  int kt = next_step(0), buf = 0;
+  if (kt < nk) gload(kt, ra[0], rb[0]);
+  while (kt < nk) {
+    sstore(buf, ra[0], rb[0]);
+    const int kn = next_step(kt + 1);
+    if (kn < nk) gload(kn, ra[0], rb[0]);
+    __syncthreads();
 #pragma unroll
-  for (int p = 0; p < kDepth; ++p)
-    if (p < nk) gload(p, ra[p], rb[p]);
-  // step kt: its tile goes to LDS buffer kt & 1 (last read in step kt - 2, which every thread left before
-  // the barrier of step kt - 1), the ring slot is refilled with step kt + kDepth, barrier, MFMAs
-  for (int kt0 = 0; kt0 < nk; kt0 += kDepth) {
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 fa[2], fb[2];
 #pragma unroll
-    for (int p = 0; p < kDepth; ++p) {
-      const int kt = kt0 + p;
-      if (kt < nk) {
-        const int buf = kt & 1;
-        sstore(buf, ra[p], rb[p]);
-        if (kt + kDepth < nk) gload(kt + kDepth, ra[p], rb[p]);
-        __syncthreads();
+      for (int t = 0; t < 2; ++t) {
+        fa[t] = frag(sA(buf), A_KC, 64 * wm + 32 * t + l32, ks);
+        fb[t] = frag(sB(buf), B_KC, 64 * wn + 32 * t + l32, ks);
+      }
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-          bf16x8 fa[2], fb[2];
+      for (int a = 0; a < 2; ++a)
 #pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            fa[t] = frag(sA(buf), A_KC, 64 * wm + 32 * t + l32, ks);
-            fb[t] = frag(sB(buf), B_KC, 64 * wn + 32 * t + l32, ks);
-          }
+        for (int b = 0; b < 2; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+      if (!A_KC && !B_KC && bias_sum) {
 #pragma unroll
-          for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
-          if (!A_KC && !B_KC && bias_sum) {
-#pragma unroll
-            for (int b = 0; b < 2; ++b) accb[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fb[b], accb[b], 0, 0, 0);
-          }
-        }
+        for (int b = 0; b < 2; ++b) accb[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fb[b], accb[b], 0, 0, 0);
       }
     }
+    buf ^= 1;
+    kt = kn;
   }
 
   if (!A_KC && !B_KC && bias_sum && hi == 0) {
@@ -349,7 +375,7 @@ __device__ __forceinline__ void store_bf16x4(__bf16* p, f32x4 v) {
 template <int LPR>
 __global__ __launch_bounds__(256) void bw_ln_fwd_kernel(const float* __restrict__ x, const __bf16* __restrict__ gam,
                                                         const __bf16* __restrict__ bet, __bf16* __restrict__ out,
-                                                        int ntok, float eps) {
+                                                        int ntok, float eps, RowsValid rows) {
   constexpr int RPW = 64 / LPR, D = 4 * LPR;
   const int lane = threadIdx.x & 63, sub = lane % LPR, rsub = lane / LPR;
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), nw = gridDim.x * 4;
@@ -359,12 +385,14 @@ __global__ __launch_bounds__(256) void bw_ln_fwd_kernel(const float* __restrict_
   for (int grp = wave; grp < ngroups; grp += nw) {
     const int r = grp * RPW + rsub;
     const bool ok = r < ntok;
+    const bool live = ok && row_valid(rows, r);       // a padded row is written as zeros and not read
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
-    if (ok) v = *(const f32x4*)(x + (size_t)r * D + 4 * sub);
+    if (live) v = *(const f32x4*)(x + (size_t)r * D + 4 * sub);
     const float mean = row_sum<LPR>(v[0] + v[1] + v[2] + v[3]) * (1.f / D);
     v -= mean;
     const float rstd = 1.f / sqrtf(row_sum<LPR>(v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3]) * (1.f / D) + eps);
-    if (ok) store_bf16x4(out + (size_t)r * D + 4 * sub, v * rstd * gv + bv);
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    if (ok) store_bf16x4(out + (size_t)r * D + 4 * sub, live ? v * rstd * gv + bv : zero);
   }
 }
 
@@ -376,7 +404,7 @@ template <int LPR>
 __global__ __launch_bounds__(256) void bw_ln_bwd_kernel(const __bf16* __restrict__ dn, const float* __restrict__ x,
                                                         const __bf16* __restrict__ gam, const float* __restrict__ dres,
                                                         float* __restrict__ dx_out, __bf16* __restrict__ dxb,
-                                                        float* __restrict__ part, int ntok, float eps) {
+                                                        float* __restrict__ part, int ntok, float eps, RowsValid rows) {
   constexpr int RPW = 64 / LPR, D = 4 * LPR;
   const int lane = threadIdx.x & 63, sub = lane % LPR, rsub = lane / LPR;
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), nw = gridDim.x * 4;
@@ -387,9 +415,10 @@ __global__ __launch_bounds__(256) void bw_ln_bwd_kernel(const __bf16* __restrict
   for (int grp = wave; grp < ngroups; grp += nw) {
     const int r = grp * RPW + rsub;
     const bool ok = r < ntok;
+    const bool live = ok && row_valid(rows, r);       // a padded row: zero gradient, nothing read
     const size_t o = (size_t)r * D + 4 * sub;
     f32x4 v = {0.f, 0.f, 0.f, 0.f}, t = v, res = v;
-    if (ok) {
+    if (live) {
       v = *(const f32x4*)(x + o);
       t = load_bf16x4(dn + o);
       if (dres) res = *(const f32x4*)(dres + o);
@@ -404,7 +433,8 @@ __global__ __launch_bounds__(256) void bw_ln_bwd_kernel(const __bf16* __restrict
     const float c1 = row_sum<LPR>(t[0] + t[1] + t[2] + t[3]) * (1.f / D);
     const float c2 = row_sum<LPR>(t[0] * v[0] + t[1] * v[1] + t[2] * v[2] + t[3] * v[3]) * (1.f / D);
     if (ok) {
-      const f32x4 dx = res + rstd * (t - c1 - v * c2);
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      const f32x4 dx = live ? res + rstd * (t - c1 - v * c2) : zero;
       *(f32x4*)(dx_out + o) = dx;
       if (dxb) store_bf16x4(dxb + o, dx);
     }
@@ -1159,16 +1189,19 @@ static int gemm(hipStream_t st, bool a_kc, bool b_kc, GemmArgs g, int splits) {
 // y = x W (+ epilogue): x [ntok][kc] row-major, W [kc][.. n columns, pitch ldb] row-major; outputs,
 // residual and pre-activation [ntok][n]
 static int gemm_rows(hipStream_t st, const __bf16* x, int kc, const __bf16* W, int n, size_t ntok, int epi, int act,
-                     void* out, void* out2, const __bf16* bias, const float* res, const __bf16* pre, int ldb = 0) {
+                     void* out, void* out2, const __bf16* bias, const float* res, const __bf16* pre, int ldb = 0,
+                     RowsValid rows = RowsValid{nullptr, 0}) {
   GemmArgs g = {};
+  g.rows = rows;
   g.A = x; g.lda = kc; g.B = W; g.ldb = ldb ? ldb : n; g.M = (int)ntok; g.N = n; g.Kc = kc; g.kslice = kc;
   g.epi = epi; g.act = act; g.out = out; g.out2 = out2; g.ldo = n; g.bias = bias; g.res = res; g.pre = pre;
   return gemm(st, true, false, g, 1);
 }
 // dx = dy W^T: dy [ntok][kc], W [n][.. kc columns, pitch ldb] row-major (the forward's [in = n][out = kc])
 static int gemm_rows_t(hipStream_t st, const __bf16* dy, int kc, const __bf16* W, int n, size_t ntok, int epi, int act,
-                       void* out, const __bf16* pre, int ldb = 0) {
+                       void* out, const __bf16* pre, int ldb = 0, RowsValid rows = RowsValid{nullptr, 0}) {
   GemmArgs g = {};
+  g.rows = rows;
   g.A = dy; g.lda = kc; g.B = W; g.ldb = ldb ? ldb : kc; g.M = (int)ntok; g.N = n; g.Kc = kc; g.kslice = kc;
   g.epi = epi; g.act = act; g.out = out; g.ldo = n; g.pre = pre;
   return gemm(st, true, true, g, 1);
@@ -1176,16 +1209,17 @@ static int gemm_rows_t(hipStream_t st, const __bf16* dy, int kc, const __bf16* W
 // dW [m][n] = x^T dy: x [ntok][.. m columns, pitch lda], dy [ntok][.. n columns, pitch ldb]
 // and db [n] = column sums of dy
 static int gemm_wgrad(hipStream_t st, const __bf16* x, int lda, int m, const __bf16* dy, int ldb, int n, size_t ntok,
-                      float* part, float* bpart, float* dW, float* db) {
+                      float* part, float* bpart, float* dW, float* db, RowsValid rows = RowsValid{nullptr, 0}) {
   GemmArgs g = {};
+  g.rows = rows;
   g.A = x; g.lda = lda; g.B = dy; g.ldb = ldb; g.M = m; g.N = n; g.Kc = (int)ntok;
   const int tiles = ((m + 127) / 128) * ((n + 127) / 128);
   if (tiles > kMaxPartials) return api_error(LONGER_ERR_ARG, "parameter matrix %d x %d too large for the backward pass", m, n);
   int splits = kMaxPartials / tiles;
   const int most = (int)((ntok + 255) / 256);
   if (splits > most) splits = most;
-  g.kslice = (int)(((ntok + splits - 1) / splits + 31) / 32 * 32);
-  splits = (int)((ntok + g.kslice - 1) / g.kslice);
+  const int steps = (int)((ntok + 31) / 32);
+  if (splits > steps) splits = steps;
   g.epi = EPI_PARTIAL; g.out = part; g.out2 = bpart; g.ldo = n;
   int rc = gemm(st, false, false, g, splits);
   if (rc) return rc;
@@ -1195,22 +1229,23 @@ static int gemm_wgrad(hipStream_t st, const __bf16* x, int lda, int m, const __b
 }
 
 static void ln_fwd(hipStream_t st, unsigned grid, int d, const float* x, const __bf16* g, const __bf16* b, __bf16* out,
-                   int ntok, float eps) {
+                   int ntok, float eps, RowsValid rows = RowsValid{nullptr, 0}) {
   switch (d) {
-    case 32: bw_ln_fwd_kernel<8><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps); break;
-    case 64: bw_ln_fwd_kernel<16><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps); break;
-    case 128: bw_ln_fwd_kernel<32><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps); break;
-    default: bw_ln_fwd_kernel<64><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps); break;
+    case 32: bw_ln_fwd_kernel<8><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps, rows); break;
+    case 64: bw_ln_fwd_kernel<16><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps, rows); break;
+    case 128: bw_ln_fwd_kernel<32><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps, rows); break;
+    default: bw_ln_fwd_kernel<64><<<grid, 256, 0, st>>>(x, g, b, out, ntok, eps, rows); break;
   }
 }
 // dgb: the gain gradient [d] followed directly by the shift gradient [d]
 static int ln_bwd(hipStream_t st, unsigned grid, int d, const __bf16* dn, const float* x, const __bf16* g, const float* dres,
-                  float* dx, __bf16* dxb, float* part, float* dgb, int ntok, float eps, bool accumulate = false) {
+                  float* dx, __bf16* dxb, float* part, float* dgb, int ntok, float eps, bool accumulate = false,
+                  RowsValid rows = RowsValid{nullptr, 0}) {
   switch (d) {
-    case 32: bw_ln_bwd_kernel<8><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
-    case 64: bw_ln_bwd_kernel<16><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
-    case 128: bw_ln_bwd_kernel<32><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
-    default: bw_ln_bwd_kernel<64><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps); break;
+    case 32: bw_ln_bwd_kernel<8><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps, rows); break;
+    case 64: bw_ln_bwd_kernel<16><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps, rows); break;
+    case 128: bw_ln_bwd_kernel<32><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps, rows); break;
+    default: bw_ln_bwd_kernel<64><<<grid, 256, 0, st>>>(dn, x, g, dres, dx, dxb, part, ntok, eps, rows); break;
   }
   if (hipGetLastError() != hipSuccess) return api_error(LONGER_ERR_HIP, "LayerNorm backward launch failed");
   return reduce(st, part, (int)grid, 2 * d, dgb, accumulate);
@@ -1230,6 +1265,7 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
   const Workspace w = merge_workspace(c, s, B, L);
   const GradLayout gl = grad_layout(d, f);
   const RowGeom q = {lens, L, s.K, (int)nt};
+  const RowsValid rv = {lens, L};            // padded token rows are left out (lens NULL: there are none)
   auto xin = [&](int l) { return (float*)(ws + w.xin) + (size_t)l * nt * d; };
   auto wcat = [&](int l) { return (__bf16*)(ws + w.wcat) + (size_t)l * d * 3 * d; };
   auto bcat = [&](int l) { return (__bf16*)(ws + w.bcat + (size_t)l * up256((size_t)3 * d * 2)); };
@@ -1260,18 +1296,18 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
   auto forward = [&](int l, float* y_out) -> int {
     const longer_block& b = inner[l];
     const float* x = xin(l);
-    ln_fwd(st, ln_grid, d, x, (const __bf16*)b.ln1_g, (const __bf16*)b.ln1_b, n1, (int)nt, c->ln_eps);
+    ln_fwd(st, ln_grid, d, x, (const __bf16*)b.ln1_g, (const __bf16*)b.ln1_b, n1, (int)nt, c->ln_eps, rv);
     BW_TRY(launched("LayerNorm"));
-    BW_TRY(gemm_rows(st, n1, d, wcat(l), 3 * d, nt, EPI_BF16, 0, qkv, nullptr, bcat(l), nullptr, nullptr));
+    BW_TRY(gemm_rows(st, n1, d, wcat(l), 3 * d, nt, EPI_BF16, 0, qkv, nullptr, bcat(l), nullptr, nullptr, 0, rv));
     if (s.dh == 16) bw_attn_fwd_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, o, q, d, s.heads);
     else bw_attn_fwd_kernel<32><<<ah_grid, 256, 0, st>>>(qkv, o, q, d, s.heads);
     BW_TRY(launched("group attention"));
-    BW_TRY(gemm_rows(st, o, d, (const __bf16*)b.wo, d, nt, EPI_RES_F32, 0, xmid, nullptr, (const __bf16*)b.bo, x, nullptr));
-    ln_fwd(st, ln_grid, d, xmid, (const __bf16*)b.ln2_g, (const __bf16*)b.ln2_b, n2, (int)nt, c->ln_eps);
+    BW_TRY(gemm_rows(st, o, d, (const __bf16*)b.wo, d, nt, EPI_RES_F32, 0, xmid, nullptr, (const __bf16*)b.bo, x, nullptr, 0, rv));
+    ln_fwd(st, ln_grid, d, xmid, (const __bf16*)b.ln2_g, (const __bf16*)b.ln2_b, n2, (int)nt, c->ln_eps, rv);
     BW_TRY(launched("LayerNorm"));
-    BW_TRY(gemm_rows(st, n2, d, (const __bf16*)b.w1, f, nt, EPI_ACT, c->act, h, a, (const __bf16*)b.b1, nullptr, nullptr));
+    BW_TRY(gemm_rows(st, n2, d, (const __bf16*)b.w1, f, nt, EPI_ACT, c->act, h, a, (const __bf16*)b.b1, nullptr, nullptr, 0, rv));
     if (y_out)
-      BW_TRY(gemm_rows(st, a, f, (const __bf16*)b.w2, d, nt, EPI_RES_F32, 0, y_out, nullptr, (const __bf16*)b.b2, xmid, nullptr));
+      BW_TRY(gemm_rows(st, a, f, (const __bf16*)b.w2, d, nt, EPI_RES_F32, 0, y_out, nullptr, (const __bf16*)b.b2, xmid, nullptr, 0, rv));
     return 0;
   };
 
@@ -1295,14 +1331,14 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     float* g = grads + (size_t)l * gl.total;
     BW_TRY(forward(l, nullptr));                 // this block's intermediates, from its input alone
     // FFN: y = xmid + act(n2 W1 + b1) W2 + b2
-    BW_TRY(gemm_wgrad(st, a, f, f, dyb, d, d, nt, part, bpart, g + gl.w2, g + gl.b2));
-    BW_TRY(gemm_rows_t(st, dyb, d, (const __bf16*)b.w2, f, nt, EPI_DACT, c->act, dh, h));
-    BW_TRY(gemm_wgrad(st, n2, d, d, dh, f, f, nt, part, bpart, g + gl.w1, g + gl.b1));
-    BW_TRY(gemm_rows_t(st, dh, f, (const __bf16*)b.w1, d, nt, EPI_BF16, 0, dn, nullptr));
-    BW_TRY(ln_bwd(st, ln_grid, d, dn, xmid, (const __bf16*)b.ln2_g, dy, dxm, dxmb, part, g + gl.ln2_g, (int)nt, c->ln_eps));
+    BW_TRY(gemm_wgrad(st, a, f, f, dyb, d, d, nt, part, bpart, g + gl.w2, g + gl.b2, rv));
+    BW_TRY(gemm_rows_t(st, dyb, d, (const __bf16*)b.w2, f, nt, EPI_DACT, c->act, dh, h, 0, rv));
+    BW_TRY(gemm_wgrad(st, n2, d, d, dh, f, f, nt, part, bpart, g + gl.w1, g + gl.b1, rv));
+    BW_TRY(gemm_rows_t(st, dh, f, (const __bf16*)b.w1, d, nt, EPI_BF16, 0, dn, nullptr, 0, rv));
+    BW_TRY(ln_bwd(st, ln_grid, d, dn, xmid, (const __bf16*)b.ln2_g, dy, dxm, dxmb, part, g + gl.ln2_g, (int)nt, c->ln_eps, false, rv));
     // attention: xmid = x + att W_O + b_O
-    BW_TRY(gemm_wgrad(st, o, d, d, dxmb, d, d, nt, part, bpart, g + gl.wo, g + gl.bo));
-    BW_TRY(gemm_rows_t(st, dxmb, d, (const __bf16*)b.wo, d, nt, EPI_BF16, 0, dob, nullptr));
+    BW_TRY(gemm_wgrad(st, o, d, d, dxmb, d, d, nt, part, bpart, g + gl.wo, g + gl.bo, rv));
+    BW_TRY(gemm_rows_t(st, dxmb, d, (const __bf16*)b.wo, d, nt, EPI_BF16, 0, dob, nullptr, 0, rv));
     if (s.dh == 16) {
       bw_attn_bwd_q_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
       bw_attn_bwd_kv_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
@@ -1313,13 +1349,13 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     BW_TRY(launched("group attention backward"));
     const size_t wofs[3] = {gl.wq, gl.wk, gl.wv}, bofs[3] = {gl.bq, gl.bk, gl.bv};
     for (int j = 0; j < 3; ++j) {
-      BW_TRY(gemm_wgrad(st, n1, d, d, dqkv + (size_t)j * d, 3 * d, d, nt, part, bpart, g + wofs[j], g + bofs[j]));
+      BW_TRY(gemm_wgrad(st, n1, d, d, dqkv + (size_t)j * d, 3 * d, d, nt, part, bpart, g + wofs[j], g + bofs[j], rv));
     }
-    BW_TRY(gemm_rows_t(st, dqkv, 3 * d, wcat(l), d, nt, EPI_BF16, 0, dn, nullptr));
+    BW_TRY(gemm_rows_t(st, dqkv, 3 * d, wcat(l), d, nt, EPI_BF16, 0, dn, nullptr, 0, rv));
     // the gradient of this block's input is the upstream gradient of the block before it
     float* dx = l ? dy : dH;
     BW_TRY(ln_bwd(st, ln_grid, d, dn, xin(l), (const __bf16*)b.ln1_g, dxm, dx, l ? dyb : nullptr, part, g + gl.ln1_g,
-                  (int)nt, c->ln_eps));
+                  (int)nt, c->ln_eps, false, rv));
   }
   return 0;
 }

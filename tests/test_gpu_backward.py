@@ -35,7 +35,7 @@ def _rel(a, b):
     return float(np.linalg.norm(a - b)) / (den if den > 0 else 1.0)
 
 
-def _run_gpu(case, dM):
+def _run_gpu(case, dM, ws_fill=None):
     import paper_2505_04421_amd as lg
     from gpu_util import guarded_empty
     cfg = case["cfg"]
@@ -51,6 +51,8 @@ def _run_gpu(case, dM):
     dH, g_dh = guarded_empty(dev, (B, L, cfg.d_in), torch.float32)
     grads, g_gr = guarded_empty(dev, (cfg.inner_layers * nf,), torch.float32)
     dM_t = torch.from_numpy(np.ascontiguousarray(dM, dtype=np.float32)).to(dev)
+    if ws_fill is not None:
+        ws.fill_(ws_fill)
     lg.longer_token_merge_backward(model.ccfg, model.inner, H, lens, B, L, dM_t, dH, grads, ws)
     torch.cuda.synchronize()
     for g, what in ((g_ws, "workspace"), (g_dh, "dH_out"), (g_gr, "grads_out")):
@@ -59,11 +61,11 @@ def _run_gpu(case, dM):
     return dH.cpu().numpy().astype(np.float64), [{k: v.cpu().numpy().astype(np.float64) for k, v in blk.items()} for blk in views]
 
 
-def _compare(name, case, dM, users=None):
+def _compare(name, case, dM, users=None, ws_fill=None):
     cfg = case["cfg"]
     _say("backward case %s: B=%d L=%d d_in=%d K=%d inner_layers=%d merge=%s act=%s" %
          (name, cfg.B, cfg.L, cfg.d_in, cfg.K, cfg.inner_layers, cfg.merge, cfg.act))
-    dH, grads = _run_gpu(case, dM)
+    dH, grads = _run_gpu(case, dM, ws_fill)
     assert np.isfinite(dH).all()
     TOL = TOL_RELU if cfg.act == "relu" else globals()["TOL"]
     sel = list(range(cfg.B)) if users is None else list(users)
@@ -124,6 +126,17 @@ def test_backward_c2_shape_ragged():
 def test_backward_c3_shape_two_blocks():
     case = _bf16_case("C3", users=3, L=333, ragged=True, len_lo=1, len_hi=333)
     _compare("C3, 3 ragged users, two blocks", case, synth.draw_merge_gradient(case["cfg"]))
+
+
+def test_backward_padded_rows_are_left_out_whatever_the_workspace_holds():
+    """Tiles of padded rows are skipped and padded rows are never read: with a workspace full of NaN bit
+    patterns (0xFF bytes) and NaN in the padded part of H, a ragged batch with long padded stretches (whole
+    128-row tiles of padding, users of length 0) gives the same gradients."""
+    cfg = synth.CONFIGS["C3"].replace(dtype="bf16", B=5, L=700, index=44)
+    case = synth.make_case(cfg)                       # every row drawn; the lengths are set here
+    case["lens"] = np.array([700, 0, 130, 3, 411], dtype=np.int32)
+    case["H"] = np.where(np.arange(cfg.L)[None, :, None] < case["lens"][:, None, None], case["H"], np.float32("nan"))
+    _compare("C3 shape, 5 ragged users, NaN workspace", case, synth.draw_merge_gradient(case["cfg"]), ws_fill=0xFF)
 
 
 def test_backward_relu_and_head_width_32():
