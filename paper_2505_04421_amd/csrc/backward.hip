@@ -1,13 +1,17 @@
-// Backward pass of the token merge (Section 3.4) with activation recomputation and mixed
-// precision (Section 3.6.2): longer_token_merge_backward and its size queries.
+// Backward pass with activation recomputation and mixed precision (Section 3.6.2):
+// longer_token_merge_backward (the token merge of Section 3.4 alone), longer_forward_backward
+// (the whole model: loss of Eq. 1-2 and the gradient of every input and parameter) and their
+// size queries.
 //
-// Nothing is kept from a forward call: the pass reads the raw tokens H, recomputes the chain of
-// block inputs (fp32), then walks the InnerTrans blocks from the last to the first; for each
-// block it recomputes the block's intermediates from the block's input and takes the
-// gradients.  Precision policy: every GEMM runs on the matrix cores with bf16 operands and
-// fp32 accumulation; the residual stream, its gradient, LayerNorm and softmax statistics and
-// every parameter gradient are fp32; activations and activation gradients between two GEMMs
-// are stored as bf16.
+// Token merge: nothing is kept from a forward call.  The pass reads the raw tokens H, gets every
+// block's input rows (fp32) from the fused forward kernel, then walks the InnerTrans blocks from
+// the last to the first; for each block it recomputes the block's intermediates from the block's
+// input and takes the gradients.  Reduced stack (cross-causal and self-causal layers on B (m + k)
+// query rows): its intermediates are a twentieth of the merge's and are kept.
+// Precision policy: every GEMM runs on the matrix cores with bf16 operands and fp32
+// accumulation; the residual stream, its gradient, LayerNorm and softmax statistics and every
+// parameter gradient are fp32; activations and activation gradients between two GEMMs are
+// stored as bf16.
 //
 // Unlike the forward kernels this pass is not fused per tile: a parameter gradient is a sum
 // over every token of the batch, i.e. a GEMM whose contraction runs over the tokens, so the
@@ -15,11 +19,14 @@
 // [token, feature] tensors in the workspace, and three kinds of kernels work on them:
 //   * one bf16 MFMA GEMM (bw_gemm_kernel) whose operands may each be stored with the
 //     contraction index contiguous or strided, which covers y = x W (+ epilogues),
-//     dx = dy W^T and dW = x^T dy (cut into slices of tokens whose partial results a second kernel sums);
-//   * row kernels: LayerNorm forward / backward (+ gain / shift gradients), pooling backward
-//     (bias gradients are column sums, taken by the dW GEMM as one more product with a row of ones);
-//   * the attention inside a group of K tokens, forward and backward, one thread per
-//     (token, head): the groups are tiny (K x K scores per head), so this is plain fp32 code.
+//     dx = dy W^T and dW = x^T dy (the tokens dealt to slices whose partial results a second
+//     kernel sums; the bias gradient, a column sum, rides along as one more product with ones);
+//   * row kernels: LayerNorm forward / backward (+ gain / shift gradients), the merge's
+//     backward, the reduced stack's row build, masks, head and loss, gradient routing;
+//   * attention, forward and backward, one thread per (row, head) in plain fp32 code: inside a
+//     group of K tokens (InnerTrans: K x K scores per head), and over a user's own rows under
+//     the mask of Eq. 8 (reduced stack).
+// Padded token rows are never read and cost only the zeros written for them.
 #include "../../include/longer.h"
 #include "device.h"
 
@@ -49,14 +56,15 @@ enum Epilogue {
   EPI_RES_F32 = 1,   // outf[m][n] = res[m][n] + acc + bias[n]
   EPI_ACT = 2,       // out[m][n] = bf16(v), out2[m][n] = bf16(act(v)), v = acc + bias[n]
   EPI_DACT = 3,      // out[m][n] = bf16(acc * act'(pre[m][n]))
-  EPI_PARTIAL = 4    // parameter gradients (out2, if given: [slice][n] column sums of B, the bias gradient's partials): the contraction (over the tokens) is cut into slices, one workgroup
-                     // per tile and slice; outf[slice][m][n] = acc, summed afterwards by bw_reduce_kernel
+  EPI_PARTIAL = 4    // parameter gradients: the contraction (over the tokens) is dealt to slices, one workgroup per
+                     // tile and slice; outf[slice][m][n] = acc, summed afterwards by bw_reduce_kernel (out2, if
+                     // given: [slice][n] column sums of B, the bias gradient's partials)
 };
 
 // Padded token rows (row r = u L + pos with pos >= the user's length) carry no gradient.  With the
 // batch's geometry at hand a kernel leaves them out: row GEMMs skip tiles without a valid row, the
-// gradient GEMMs read them as zeros, the LayerNorm kernels write zeros for them.  rows_L = 0: every
-// row counts (the reduced stack's rows).
+// gradient GEMMs read them as zeros and pass over steps that hold nothing else, the LayerNorm kernels
+// write zeros for them.  L = 0: every row counts (the reduced stack's rows).
 struct RowsValid { const int32_t* lens; int L; };
 __device__ __forceinline__ bool row_valid(const RowsValid& v, int r) {
   if (v.L == 0 || v.lens == nullptr) return true;
@@ -78,7 +86,7 @@ struct GemmArgs {
   const __bf16* A; const __bf16* B;
   int lda, ldb;
   int M, N, Kc;
-  int kslice, nsplit;         // split GEMM: number of slices of the contraction (kslice unused)
+  int nsplit;                 // gradient GEMM: number of slices the contraction steps are dealt to
   int epi, act;
   void* out; void* out2; int ldo;
   const __bf16* bias; const float* res; const __bf16* pre;
@@ -1193,7 +1201,7 @@ static int gemm_rows(hipStream_t st, const __bf16* x, int kc, const __bf16* W, i
                      RowsValid rows = RowsValid{nullptr, 0}) {
   GemmArgs g = {};
   g.rows = rows;
-  g.A = x; g.lda = kc; g.B = W; g.ldb = ldb ? ldb : n; g.M = (int)ntok; g.N = n; g.Kc = kc; g.kslice = kc;
+  g.A = x; g.lda = kc; g.B = W; g.ldb = ldb ? ldb : n; g.M = (int)ntok; g.N = n; g.Kc = kc;
   g.epi = epi; g.act = act; g.out = out; g.out2 = out2; g.ldo = n; g.bias = bias; g.res = res; g.pre = pre;
   return gemm(st, true, false, g, 1);
 }
@@ -1202,7 +1210,7 @@ static int gemm_rows_t(hipStream_t st, const __bf16* dy, int kc, const __bf16* W
                        void* out, const __bf16* pre, int ldb = 0, RowsValid rows = RowsValid{nullptr, 0}) {
   GemmArgs g = {};
   g.rows = rows;
-  g.A = dy; g.lda = kc; g.B = W; g.ldb = ldb ? ldb : kc; g.M = (int)ntok; g.N = n; g.Kc = kc; g.kslice = kc;
+  g.A = dy; g.lda = kc; g.B = W; g.ldb = ldb ? ldb : kc; g.M = (int)ntok; g.N = n; g.Kc = kc;
   g.epi = epi; g.act = act; g.out = out; g.ldo = n; g.pre = pre;
   return gemm(st, true, true, g, 1);
 }
