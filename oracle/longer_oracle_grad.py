@@ -246,11 +246,13 @@ def model_backward(cfg, weights: dict, H: np.ndarray, G: np.ndarray, lens, label
         returns (loss, logits [B], dH [B, L, d_raw], dG [B, m, d],
                  {"inner": [per block], "cross": {...}, "self": [per block], "head_w", "head_b"}).
 
-    Sampled query slots only (``q_learnable`` configurations are not differentiated here).  The
+    With learnable query tokens (``q_learnable``) the slots' rows are the parameter ``q_learn`` [k, d]:
+    the dict then holds its gradient ("q_learn": the sum over the users with at least one token of the
+    slots' row gradients) and no gradient flows from the slots into the merged tokens.  The
     reduced stack keeps the input rows of every layer and recomputes a layer's intermediates when its
     gradient is taken; the token merge is differentiated by ``token_merge_backward(keep=...)``."""
-    if getattr(cfg, "q_learnable", False):
-        raise ValueError("learnable query tokens are not differentiated")
+    learn = bool(getattr(cfg, "q_learnable", False))
+    q_learn = np.asarray(weights["q_learn"], dtype=F64) if learn else None
     H = np.asarray(H)
     G = np.asarray(G, dtype=F64)
     B, L, _ = H.shape
@@ -272,7 +274,7 @@ def model_backward(cfg, weights: dict, H: np.ndarray, G: np.ndarray, lens, label
         R = np.concatenate([G[u], Mu], axis=0)
         qt = fwd._query_tokens(cfg, m, Tu)
         qvalid = np.array([t[2] for t in qt])
-        O = fwd.gather_queries(cfg, G[u], Mu, Tu)
+        O = fwd.gather_queries(cfg, G[u], Mu, Tu, q_learn)
         mask_c = fwd._type_mask(qt, fwd.key_tokens(m, T, Tu), cfg.gmask)
         mask_s = fwd._type_mask(qt, qt, cfg.gmask)
         X = np.where(qvalid[:, None], fwd.block(O, R, mask_c, cross, cfg.heads, cfg.ln_eps, cfg.act), 0.0)
@@ -289,6 +291,7 @@ def model_backward(cfg, weights: dict, H: np.ndarray, G: np.ndarray, lens, label
     g_cross = {p: np.zeros_like(cross[p]) for p in PARAMS}
     g_self = [{p: np.zeros_like(b[p]) for p in PARAMS} for b in selfs]
     g_hw = np.zeros_like(head_w)
+    g_ql = np.zeros((k, d), dtype=F64)
     dG = np.zeros((B, m, d), dtype=F64)
     dM = np.zeros((B, T, d), dtype=F64)
     for u in range(B):
@@ -310,9 +313,13 @@ def model_backward(cfg, weights: dict, H: np.ndarray, G: np.ndarray, lens, label
         dMu = dR[m:].copy()
         for i in range(k):
             t, v = qt[m + i][1], qt[m + i][2]
-            if v:
+            if v and learn:
+                g_ql[i] += dO[m + i]                                # slot i holds row i of the parameter
+            elif v:
                 dMu[t] += dO[m + i]                                 # slot i holds merged token t
         dM[u] = np.where((np.arange(T) < Tu)[:, None], dMu, 0.0)    # merged tokens past T_u were zeroed
     dH, g_inner = token_merge_backward(cfg, weights["inner"], H, lens, dM, keep=keep)
     grads = {"inner": g_inner, "cross": g_cross, "self": g_self, "head_w": g_hw, "head_b": np.array([dlogit.sum()])}
+    if learn:
+        grads["q_learn"] = g_ql
     return loss, logits, dH, dG, grads

@@ -45,6 +45,8 @@ MUTANTS = [
     ("model: self layers, the key rows' gradient forgotten",
      "            dX = dxq + dxkv                                         # queries and keys are the same rows",
      "            dX = dxq"),
+    ("model: learnable query tokens, gradient taken from users without any token too",
+     "            if v and learn:\n                g_ql[i] += dO[m + i]", "            if learn:\n                g_ql[i] += dO[m + i] + 1.0 * (not v)"),
     ("model: head weights read feature-major", "        dX[:m] = dlogit[u] * head_w.reshape(m, d)",
      "        dX[:m] = dlogit[u] * head_w.reshape(d, m).T"),
 ]

@@ -303,3 +303,47 @@ def test_model_backward_a_token_outside_every_query_set_still_gets_its_gradient_
     _, _, dH1, dG1, _ = grd.model_backward(one, w, H[1:], G[1:], None, labels[1:])
     # the mean of Eq. 2 runs over the batch: a batch of one user weighs it twice as much
     assert np.allclose(dH1[0], 2 * dH[1], rtol=1e-10, atol=1e-14) and np.allclose(dG1[0], 2 * dG[1], rtol=1e-10, atol=1e-14)
+
+
+def test_model_backward_with_learnable_query_tokens_against_finite_differences():
+    """Learnable query tokens (Section 3.5.1): the slots' rows are a parameter shared by all users; its
+    gradient, and the gradients that reach H only through the keys of the cross layer."""
+    cfg = synth.tiny_config(B=3, L=22, d=8, heads=2, m=2, K=4, k_recent=3, n_self=2, inner_layers=1,
+                            q_learnable=True, ragged=True, len_lo=0, len_hi=22)
+    case = synth.make_case(cfg)
+    case["lens"][:] = [22, 0, 9]
+    rng = np.random.default_rng(11)
+    w = case["weights"]
+    w = {"inner": [{k: np.asarray(v, dtype=np.float64) for k, v in b.items()} for b in w["inner"]],
+         "cross": {k: np.asarray(v, dtype=np.float64) for k, v in w["cross"].items()},
+         "self": [{k: np.asarray(v, dtype=np.float64) for k, v in b.items()} for b in w["self"]],
+         "head_w": np.asarray(w["head_w"], dtype=np.float64), "head_b": np.asarray(w["head_b"], dtype=np.float64),
+         "q_learn": np.asarray(w["q_learn"], dtype=np.float64)}
+    H = np.asarray(case["H"], dtype=np.float64)
+    G = np.asarray(case["G"], dtype=np.float64)
+    lens = case["lens"]
+    labels = np.array([1.0, 0.0, 1.0])
+
+    def loss():
+        return grd.bce_loss(orc.forward(cfg, w, H, G, lens)[1], labels)
+
+    val, _, dH, dG, grads = grd.model_backward(cfg, w, H, G, lens, labels)
+    assert abs(val - loss()) <= 1e-12
+
+    def close(a, num):
+        return abs(a - num) <= 2e-6 * max(1e-2, abs(num))
+
+    for i in range(cfg.k_recent):
+        for _ in range(3):
+            j = int(rng.integers(0, cfg.d))
+            num = _fd(loss, w["q_learn"], (i, j), h=1e-7)
+            assert close(grads["q_learn"][i, j], num), ("q_learn", i, j, grads["q_learn"][i, j], num)
+    for u in (0, 2):
+        for _ in range(5):
+            t, j = int(rng.integers(0, lens[u])), int(rng.integers(0, cfg.d))
+            num = _fd(loss, H, (u, t, j), h=1e-7)
+            assert close(dH[u, t, j], num), ("dH", u, t, j, dH[u, t, j], num)
+    for key in ("wq", "wk", "wv", "w1"):
+        p = w["cross"][key]
+        idx = tuple(int(rng.integers(0, s)) for s in p.shape)
+        assert close(grads["cross"][key][idx], _fd(loss, p, idx, h=1e-7)), key
