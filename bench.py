@@ -511,8 +511,7 @@ def main():
 
     if not args.no_backward and cfg.dtype == "bf16" and not r["from_inputs"]:
         out["merge_backward"] = run_merge_backward(lg, torch, cfg, r["case"], max(3, args.steps // 5))
-        if not getattr(cfg, "q_learnable", False):
-            out["forward_backward"] = run_forward_backward(lg, torch, cfg, r["case"], max(3, args.steps // 5))
+        out["forward_backward"] = run_forward_backward(lg, torch, cfg, r["case"], max(3, args.steps // 5))
 
     out["cpu_baseline"] = None if args.no_cpu else cpu_oracle_leg(cfg, r["case"], None if r["from_inputs"] else r["Y_host"], 15.0)
     print(json.dumps(out))

@@ -284,14 +284,14 @@ int longer_token_merge_backward(const longer_config* cfg, const longer_block* in
  * as for longer_token_merge_backward, applied selectively: the token merge (nine tenths of the
  * activations) keeps nothing and is recomputed, block by block, when its gradients are taken; the reduced
  * stack (B (m + k) query rows, B (m + T) key rows) keeps its layers' intermediates.
- *   H, G, lens, B, L as for longer_forward (bf16 only; sampled query slots: cfg->q_learn must be NULL);
+ *   H, G, lens, B, L as for longer_forward (bf16 only);
  *   labels [B] fp32 (0 or 1);
  *   loss_out [1] fp32; logits_out [B] fp32 or NULL;
  *   dH_out [B, L, w] fp32, dG_out [B, m, d] fp32: gradients of the loss with respect to the inputs;
  *   grads_out fp32 [longer_model_grad_floats(cfg)]: parameter gradients, dense, in this order: the
  *     InnerTrans blocks, the cross block, the self blocks (each block as for
  *     longer_token_merge_backward, at its own width), head_w [m d], head_b [1] (+ padding to a multiple
- *     of 4 floats).
+ *     of 4 floats), and, when cfg->q_learn is set, the learnable query tokens [k_recent, d].
  * ws: at least longer_forward_backward_workspace_bytes(cfg, B, L). */
 size_t longer_model_grad_floats(const longer_config* cfg);
 size_t longer_forward_backward_workspace_bytes(const longer_config* cfg, int B, int L);

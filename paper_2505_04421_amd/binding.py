@@ -365,7 +365,7 @@ def block_grad_views(cfg, grads):
 
 def model_grad_views(cfg, grads):
     """Split the gradient buffer of longer_forward_backward: {"inner": [...], "cross": {...}, "self": [...],
-    "head_w": [m d], "head_b": [1]} of tensor views."""
+    "head_w": [m d], "head_b": [1] (, "q_learn": [k, d])} of tensor views."""
     di = cfg.d // cfg.K if getattr(cfg, "merge", "mean") == "concat" else cfg.d
     out = {"inner": [], "self": []}
     o = 0
@@ -378,6 +378,9 @@ def model_grad_views(cfg, grads):
         out["self"].append(v)
     out["head_w"] = grads[o:o + cfg.m * cfg.d]
     out["head_b"] = grads[o + cfg.m * cfg.d:o + cfg.m * cfg.d + 1]
+    o = (o + cfg.m * cfg.d + 1 + 3) // 4 * 4
+    if getattr(cfg, "q_learnable", False):
+        out["q_learn"] = grads[o:o + cfg.k_recent * cfg.d].view(cfg.k_recent, cfg.d)
     return out
 
 

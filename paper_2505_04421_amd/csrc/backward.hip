@@ -747,7 +747,7 @@ __device__ __forceinline__ int slot_merged_index(int i, int k, int tu, int k_uni
   return (int)(((long long)(i + 1) * rest) / k_uniform) - 1;
 }
 
-struct StackGeom { const int32_t* lens; int L, K, T, m, k, k_uniform, B; };
+struct StackGeom { const int32_t* lens; int L, K, T, m, k, k_uniform, B, learn; };   // learn: the slots hold learnable query tokens
 
 __device__ __forceinline__ int merged_len(const StackGeom& g, int u) {
   int l = g.lens ? g.lens[u] : g.L;
@@ -764,7 +764,10 @@ __global__ __launch_bounds__(256) void bw_desc_kernel(StackGeom g, int* qdesc, i
       const int u = i / n, r = i - u * n;
       int dsc = r;
       if (r >= g.m) {
-        const int t = slot_merged_index(r - g.m, g.k, merged_len(g, u), g.k_uniform);
+        const int tu = merged_len(g, u);
+        // a learnable query token stands after the user's newest token, in slot order (it sees every valid
+        // merged token in the cross layer and the slots up to itself in the self layers); no token, no slot
+        const int t = g.learn ? (tu > 0 ? tu + (r - g.m) : -1) : slot_merged_index(r - g.m, g.k, tu, g.k_uniform);
         dsc = t >= 0 ? kSeq + t : -1;
       }
       qdesc[i] = dsc;
@@ -778,7 +781,8 @@ __global__ __launch_bounds__(256) void bw_desc_kernel(StackGeom g, int* qdesc, i
 
 // R = [G; M] (merged tokens past T_u as zeros) and O = [G; the slots' merged tokens] as fp32 rows
 __global__ __launch_bounds__(256) void bw_build_rows_kernel(StackGeom g, int d, const __bf16* __restrict__ G,
-                                                            const __bf16* __restrict__ M, const int* __restrict__ qdesc,
+                                                            const __bf16* __restrict__ M, const __bf16* __restrict__ qlearn,
+                                                            const int* __restrict__ qdesc,
                                                             const int* __restrict__ kdesc, float* __restrict__ Ox,
                                                             float* __restrict__ Rx) {
   const int n = g.m + g.k, nk = g.m + g.T, d4 = d / 4;
@@ -793,10 +797,11 @@ __global__ __launch_bounds__(256) void bw_build_rows_kernel(StackGeom g, int d, 
     const int dsc = isq ? qdesc[row] : kdesc[row];
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
     if (dsc >= 0) {
-      const __bf16* src = dsc < kSeq ? G + ((size_t)u * g.m + dsc) * d : M + ((size_t)u * g.T + (dsc - kSeq)) * d;
+      const __bf16* src = dsc < kSeq ? G + ((size_t)u * g.m + dsc) * d
+                        : (isq && g.learn) ? qlearn + (size_t)(r - g.m) * d       // slot i: row i of the parameter
+                                           : M + ((size_t)u * g.T + (dsc - kSeq)) * d;
       v = load_bf16x4(src + c);
     }
-    (void)r;
     *(f32x4*)((isq ? Ox : Rx) + row * d + c) = v;
   }
 }
@@ -1045,8 +1050,10 @@ __global__ __launch_bounds__(256) void bw_split_grad_kernel(StackGeom g, int d, 
   }
 }
 // dM[u][t_i] += dO's row of query slot i (each slot of a user holds a different merged token)
+// (learnable query tokens: the slot's gradient belongs to row sl of the parameter instead, summed over the users)
 __global__ __launch_bounds__(256) void bw_slot_grad_kernel(StackGeom g, int d, const float* __restrict__ dO,
-                                                           const int* __restrict__ qdesc, float* __restrict__ dM) {
+                                                           const int* __restrict__ qdesc, float* __restrict__ dM,
+                                                           float* dql) {
   const int n = g.m + g.k, d4 = d / 4;
   const size_t total = (size_t)g.B * g.k * d4;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
@@ -1055,8 +1062,14 @@ __global__ __launch_bounds__(256) void bw_slot_grad_kernel(StackGeom g, int d, c
     const int u = (int)(s / g.k), sl = (int)(s - (size_t)u * g.k);
     const int dsc = qdesc[(size_t)u * n + g.m + sl];
     if (dsc < kSeq) continue;
-    float* dst = dM + ((size_t)u * g.T + (dsc - kSeq)) * d + c;
-    *(f32x4*)dst = *(const f32x4*)dst + *(const f32x4*)(dO + ((size_t)u * n + g.m + sl) * d + c);
+    const f32x4 v = *(const f32x4*)(dO + ((size_t)u * n + g.m + sl) * d + c);
+    if (g.learn) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dql + (size_t)sl * d + c + e, v[e]);
+    } else {
+      float* dst = dM + ((size_t)u * g.T + (dsc - kSeq)) * d + c;
+      *(f32x4*)dst = *(const f32x4*)dst + v;
+    }
   }
 }
 
@@ -1427,7 +1440,7 @@ static StackWs stack_ws(const StackDims& s, size_t fwd_bytes) {
 }
 
 static int check_stack(const longer_config* c, int B, int L, StackDims* s) {
-  if (c->q_learn) return api_error(LONGER_ERR_ARG, "learnable query tokens are not differentiated");
+  if (c->q_learn && (c->k_uniform || ((uintptr_t)c->q_learn & 15))) return api_error(LONGER_ERR_ARG, "q_learn needs k_uniform = 0 and 16-byte alignment");
   if (c->gmask != LONGER_GMASK_FULL && c->gmask != LONGER_GMASK_CAUSAL) return api_error(LONGER_ERR_ARG, "gmask %d unknown", c->gmask);
   const int d = c->d;
   if (d != 32 && d != 64 && d != 128 && d != 256) return api_error(LONGER_ERR_ARG, "width %d unsupported (32, 64, 128 or 256)", d);
@@ -1443,9 +1456,10 @@ static int check_stack(const longer_config* c, int B, int L, StackDims* s) {
   return 0;
 }
 
-// layout of the gradient buffer: [InnerTrans blocks][cross block][self blocks][head_w (m d)][head_b (1)]
-struct ModelGrads { size_t inner, cross, self0, head_w, head_b, total, per_main; };
-static ModelGrads model_grads(const Dims& mi, const StackDims& s) {
+// layout of the gradient buffer: [InnerTrans blocks][cross block][self blocks][head_w (m d)][head_b (1), padded to 4]
+// [learnable query tokens (k d), if the configuration has them]
+struct ModelGrads { size_t inner, cross, self0, head_w, head_b, q_learn, total, per_main; };
+static ModelGrads model_grads(const Dims& mi, const StackDims& s, bool learn) {
   ModelGrads g;
   g.inner = 0;
   g.cross = (size_t)mi.layers * grad_layout(mi.d, mi.f).total;
@@ -1453,7 +1467,8 @@ static ModelGrads model_grads(const Dims& mi, const StackDims& s) {
   g.self0 = g.cross + g.per_main;
   g.head_w = g.self0 + (size_t)(s.layers - 1) * g.per_main;
   g.head_b = g.head_w + (size_t)s.m * s.d;
-  g.total = (g.head_b + 1 + 3) & ~(size_t)3;
+  g.q_learn = (g.head_b + 1 + 3) & ~(size_t)3;
+  g.total = g.q_learn + (learn ? (size_t)s.k * s.d : 0);
   return g;
 }
 
@@ -1473,9 +1488,9 @@ static int run_model(const longer_config* c, const longer_weights* wts, const vo
   const int d = s.d, f = s.f;
   const size_t rq = s.rq, rk = s.rk;
   const StackWs w = stack_ws(s, fwd_bytes);
-  const ModelGrads mg = model_grads(mi, s);
+  const ModelGrads mg = model_grads(mi, s, c->q_learn != nullptr);
   const GradLayout gl = grad_layout(d, f);
-  const StackGeom geo = {lens, L, c->K, s.T, s.m, s.k, c->k_uniform, B};
+  const StackGeom geo = {lens, L, c->K, s.T, s.m, s.k, c->k_uniform, B, c->q_learn != nullptr};
   int* qdesc = (int*)(ws + w.qdesc);   int* kdesc = (int*)(ws + w.kdesc);
   __bf16* Mb = (__bf16*)(ws + w.Mb);   float* dM = (float*)(ws + w.dM);     float* Rx = (float*)(ws + w.Rx);
   auto xs = [&](int l) { return (float*)(ws + w.xs) + (size_t)l * rq * d; };
@@ -1507,7 +1522,7 @@ static int run_model(const longer_config* c, const longer_weights* wts, const vo
   int rc = longer_token_merge(c, wts->inner, H, lens, B, L, Mb, ws + w.fwd_ws, fwd_bytes, st);
   if (rc) return rc;
   bw_desc_kernel<<<flat_grid(rq + rk), 256, 0, st>>>(geo, qdesc, kdesc);
-  bw_build_rows_kernel<<<flat_grid((rq + rk) * d / 4), 256, 0, st>>>(geo, d, (const __bf16*)G, Mb, qdesc, kdesc, xs(0), Rx);
+  bw_build_rows_kernel<<<flat_grid((rq + rk) * d / 4), 256, 0, st>>>(geo, d, (const __bf16*)G, Mb, (const __bf16*)c->q_learn, qdesc, kdesc, xs(0), Rx);
   BW_TRY(launched("row build"));
   for (int l = 0; l < s.layers; ++l) {
     const longer_block& b = blk(l);
@@ -1614,7 +1629,7 @@ static int run_model(const longer_config* c, const longer_weights* wts, const vo
   // ---- gradients of the stack's inputs: global tokens (query rows and key rows), merged tokens (key
   // rows, plus the query slots that hold them)
   bw_split_grad_kernel<<<flat_grid(rk * d / 4), 256, 0, st>>>(geo, d, dy, dR, dG, dM);
-  bw_slot_grad_kernel<<<flat_grid((size_t)B * s.k * d / 4), 256, 0, st>>>(geo, d, dy, qdesc, dM);
+  bw_slot_grad_kernel<<<flat_grid((size_t)B * s.k * d / 4), 256, 0, st>>>(geo, d, dy, qdesc, dM, grads + mg.q_learn);
   BW_TRY(launched("gradient routing"));
   return 0;
 }
@@ -1662,7 +1677,7 @@ size_t longer_model_grad_floats(const longer_config* cfg) {
   bw::Dims mi;
   bw::StackDims s;
   if (bw::check(cfg, 1, 1, &mi) || bw::check_stack(cfg, 1, 1, &s)) return 0;
-  return bw::model_grads(mi, s).total;
+  return bw::model_grads(mi, s, cfg->q_learn != nullptr).total;
 }
 
 size_t longer_forward_backward_workspace_bytes(const longer_config* cfg, int B, int L) {

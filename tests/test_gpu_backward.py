@@ -203,6 +203,8 @@ def _run_model_gpu(case, labels):
             "cross": {k: f64(v) for k, v in views["cross"].items()},
             "self": [{k: f64(v) for k, v in b.items()} for b in views["self"]],
             "head_w": f64(views["head_w"]), "head_b": f64(views["head_b"])}
+    if "q_learn" in views:
+        host["q_learn"] = f64(views["q_learn"])
     return float(loss[0].item()), f64(logits), f64(dH), f64(dG), host
 
 
@@ -244,6 +246,10 @@ def _compare_model(name, case):
             worst = max(worst, e)
             assert e <= TOLM, ("grad", gname, k, e)
         _say("  %-7s worst parameter rel-L2 %.3e" % (gname, worst))
+    if cfg.q_learnable:
+        e = _rel(grads["q_learn"], g_ref["q_learn"])
+        _say("  learnable query tokens rel-L2 %.3e" % e)
+        assert e <= TOLM
     assert _rel(grads["head_w"], g_ref["head_w"]) <= TOLM
     assert abs(grads["head_b"][0] - g_ref["head_b"][0]) <= TOLM * (abs(g_ref["head_b"][0]) + 1.0 / cfg.B)
 
@@ -257,6 +263,13 @@ def test_model_backward_c2_shape_ragged():
 def test_model_backward_c3_shape_sampled_queries_causal_globals():
     case = _bf16_case("C3", users=3, L=1010, k_uniform=40, gmask="causal", ragged=True, len_lo=500, len_hi=1010)
     _compare_model("C3, 3 users, recent 60 + uniform 40, causal globals", case)
+
+
+@pytest.mark.parametrize("gmask", ["full", "causal"])
+def test_model_backward_learnable_query_tokens(gmask):
+    case = _bf16_case("C2", users=5, L=203, q_learnable=True, gmask=gmask, ragged=True, len_lo=0, len_hi=203)
+    case["lens"][:2] = [0, 203]
+    _compare_model("C2 with learnable query tokens, %s globals" % gmask, case)
 
 
 def test_model_backward_head_width_32_relu():
