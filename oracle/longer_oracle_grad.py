@@ -323,3 +323,36 @@ def model_backward(cfg, weights: dict, H: np.ndarray, G: np.ndarray, lens, label
     if learn:
         grads["q_learn"] = g_ql
     return loss, logits, dH, dG, grads
+
+
+# --------------------------------------------------------------------------- input generation
+def input_generation_backward(cfg, mlp: dict, E: np.ndarray, tdiff: np.ndarray, lens, dH: np.ndarray):
+    """Gradients of ``longer_oracle.input_generation`` (Section 3.5.1, Input Generation:
+    H = act([E + pos ; tdiff] w1 + b1) w2 + b2 on the valid tokens) for an upstream gradient dH [B, L, d]:
+    returns (dE [B, L, d_e], dtdiff [B, L, d - d_e], {"pos", "w1", "b1", "w2", "b2"}); padded tokens get
+    exact zeros, the positional embedding's gradient is summed over the users that reach a position."""
+    E = np.asarray(E)
+    B, L, d_e = E.shape
+    lens = fwd._lens(lens, B, L)
+    w1, b1, w2, b2, pos = (np.asarray(mlp[k], dtype=F64) for k in ("w1", "b1", "w2", "b2", "pos"))
+    dH = np.asarray(dH, dtype=F64)
+    dE = np.zeros((B, L, d_e), dtype=F64)
+    dtd = np.zeros((B, L, w1.shape[0] - d_e), dtype=F64)
+    g = {"pos": np.zeros_like(pos), "w1": np.zeros_like(w1), "b1": np.zeros_like(b1), "w2": np.zeros_like(w2),
+         "b2": np.zeros_like(b2)}
+    for u in range(B):
+        n = int(min(lens[u], L))
+        x = np.concatenate([np.asarray(E[u, :n], dtype=F64) + pos[:n], np.asarray(tdiff[u, :n], dtype=F64)], axis=1)
+        a = x @ w1 + b1
+        hdn = fwd.activation(a, cfg.act)
+        dy = dH[u, :n]
+        g["w2"] += hdn.T @ dy
+        g["b2"] += dy.sum(axis=0)
+        da = (dy @ w2.T) * activation_grad(a, cfg.act)
+        g["w1"] += x.T @ da
+        g["b1"] += da.sum(axis=0)
+        dx = da @ w1.T
+        dE[u, :n] = dx[:, :d_e]
+        g["pos"][:n] += dx[:, :d_e]          # the same embedding row serves every user at that position
+        dtd[u, :n] = dx[:, d_e:]
+    return dE, dtd, g

@@ -47,6 +47,10 @@ MUTANTS = [
      "            dX = dxq"),
     ("model: learnable query tokens, gradient taken from users without any token too",
      "            if v and learn:\n                g_ql[i] += dO[m + i]", "            if learn:\n                g_ql[i] += dO[m + i] + 1.0 * (not v)"),
+    ("input generation: the positional embedding's gradient not summed over the users",
+     "        g[\"pos\"][:n] += dx[:, :d_e]", "        g[\"pos\"][:n] = dx[:, :d_e]"),
+    ("input generation: the activation's derivative at the activated value",
+     "        da = (dy @ w2.T) * activation_grad(a, cfg.act)", "        da = (dy @ w2.T) * activation_grad(hdn, cfg.act)"),
     ("model: head weights read feature-major", "        dX[:m] = dlogit[u] * head_w.reshape(m, d)",
      "        dX[:m] = dlogit[u] * head_w.reshape(d, m).T"),
 ]

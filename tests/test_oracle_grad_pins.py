@@ -347,3 +347,36 @@ def test_model_backward_with_learnable_query_tokens_against_finite_differences()
         p = w["cross"][key]
         idx = tuple(int(rng.integers(0, s)) for s in p.shape)
         assert close(grads["cross"][key][idx], _fd(loss, p, idx, h=1e-7)), key
+
+
+def test_input_generation_backward_against_finite_differences():
+    """Ragged users (one empty), NaN in the padding: every input and parameter of the input-generation
+    stage against central differences of <input_generation(.), dH>."""
+    cfg = synth.tiny_config(B=3, L=9, d=8, ragged=True, len_lo=0, len_hi=9)
+    case = synth.make_input_case(cfg, 5)
+    case["lens"][:] = [9, 0, 4]
+    rng = np.random.default_rng(3)
+    mlp = {k: np.asarray(v, dtype=np.float64) for k, v in case["mlp"].items()}
+    E = np.asarray(case["E"], dtype=np.float64)
+    td = np.asarray(case["tdiff"], dtype=np.float64)
+    pos = np.arange(cfg.L)[None, :, None]
+    E = np.where(pos < case["lens"][:, None, None], np.nan_to_num(E) + rng.standard_normal(E.shape), np.nan)
+    td = np.where(pos < case["lens"][:, None, None], np.nan_to_num(td) + rng.standard_normal(td.shape), np.nan)
+    lens = case["lens"]
+    dH = rng.standard_normal((cfg.B, cfg.L, cfg.d))
+    loss = lambda: float((orc.input_generation(cfg, mlp, E, td, lens) * dH).sum())
+    dE, dtd, g = grd.input_generation_backward(cfg, mlp, E, td, lens, dH)
+    assert (dE[1] == 0).all() and (dtd[1] == 0).all() and (dE[2, 4:] == 0).all() and (dtd[2, 4:] == 0).all()
+    close = lambda a, num: abs(a - num) <= 2e-6 * max(1e-2, abs(num))
+    for u in (0, 2):
+        for _ in range(6):
+            t = int(rng.integers(0, lens[u]))
+            j = int(rng.integers(0, E.shape[-1])); k = int(rng.integers(0, td.shape[-1]))
+            assert close(dE[u, t, j], _fd(loss, E, (u, t, j), h=1e-6)), ("dE", u, t, j)
+            assert close(dtd[u, t, k], _fd(loss, td, (u, t, k), h=1e-6)), ("dtdiff", u, t, k)
+    for key in ("pos", "w1", "b1", "w2", "b2"):
+        p = mlp[key]
+        for _ in range(4):
+            idx = tuple(int(rng.integers(0, s)) for s in p.shape)
+            assert close(g[key][idx], _fd(loss, p, idx, h=1e-6)), (key, idx, g[key][idx])
+    assert (g["pos"][4:] != 0).any() and np.allclose(g["pos"][:4], dE[0, :4] + dE[2, :4])   # two users share positions 0..3
