@@ -300,6 +300,29 @@ int longer_forward_backward(const longer_config* cfg, const longer_weights* w, c
                             float* loss_out, float* logits_out, float* dH_out, float* dG_out, float* grads_out,
                             void* ws, size_t ws_bytes, void* stream);
 
+/* Gradients of the input-generation stage (Section 3.5.1, Input Generation, under the mixed
+ * precision training of Section 3.6.2): for H = act([E + pos ; tdiff] w1 + b1) w2 + b2 on the valid
+ * tokens and an upstream gradient dH [B, L, d] (fp32, device; what longer_forward_backward
+ * writes to dH_out), the call writes dE_out [B, L, d_e], dtdiff_out [B, L, d - d_e] (fp32, exact
+ * zeros at padded tokens) and grads_out, longer_input_grad_floats(cfg, L, d_e) fp32 values in the
+ * order pos [L, d_e] | w1 [d, f] | b1 [f] | w2 [f, d] | b2 [d] (f = ffn_mult d; overwritten, not
+ * accumulated; the positional embedding's row p sums over the users whose sequence reaches p).
+ * The hidden layer is recomputed from E and tdiff (bf16 operands, fp32 accumulation, as in the
+ * forward call); padded tokens are neither read nor written beyond those zeros.
+ * cfg: dtype LONGER_BF16, merge LONGER_MERGE_MEAN, d a multiple of 32 (at most 512), f at most
+ * 2048, d_e a multiple of 32 below d.  E, tdiff, w: device, bf16, as for longer_input_generation;
+ * lens: device int32 [B] or NULL.  ws: device, 256-byte aligned, at least
+ * longer_input_backward_workspace_bytes(cfg, B, L, d_e) bytes (0 = unsupported configuration).
+ * Nothing is allocated; every launch goes to `stream`; parameter gradients add their last partial
+ * sums with fp32 atomics as in longer_token_merge_backward (last-bit differences from run to run).
+ * Errors: LONGER_ERR_ARG (shape, alignment, NULL), LONGER_ERR_WS, LONGER_ERR_HIP. */
+size_t longer_input_backward_workspace_bytes(const longer_config* cfg, int B, int L, int d_e);
+size_t longer_input_grad_floats(const longer_config* cfg, int L, int d_e);
+int longer_input_generation_backward(const longer_config* cfg, const longer_input_weights* w, const void* E,
+                                     const void* tdiff, const int32_t* lens, int B, int L, int d_e, const float* dH,
+                                     float* dE_out, float* dtdiff_out, float* grads_out,
+                                     void* ws, size_t ws_bytes, void* stream);
+
 /* Measurement aid: when enabled, every kernel launch group of the entry points is bracketed
  * by a pair of HIP events recorded on the caller's stream (at most 4096 pairs between two
  * reads; later launches go unrecorded).  enable = 0: off; 1: every stage; any other value:

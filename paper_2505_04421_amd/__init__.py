@@ -16,4 +16,5 @@ from .binding import (  # noqa: F401
     longer_packed_weights_bytes, longer_pack_weights, longer_score_candidates_static, longer_probe_rate, CWeights,
     longer_backward_workspace_bytes, longer_block_grad_floats, longer_token_merge_backward, block_grad_views,
     longer_model_grad_floats, longer_forward_backward_workspace_bytes, longer_forward_backward, model_grad_views,
+    longer_input_backward_workspace_bytes, longer_input_grad_floats, longer_input_generation_backward, input_grad_views,
 )

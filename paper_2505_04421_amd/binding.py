@@ -18,7 +18,8 @@ ENTRY_POINTS = ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_inner
                 "longer_stage_timing_read", "longer_packed_weights_bytes", "longer_pack_weights",
                 "longer_score_candidates_static", "longer_probe_rate",
                 "longer_backward_workspace_bytes", "longer_block_grad_floats", "longer_token_merge_backward",
-                "longer_model_grad_floats", "longer_forward_backward_workspace_bytes", "longer_forward_backward")
+                "longer_model_grad_floats", "longer_forward_backward_workspace_bytes", "longer_forward_backward",
+                "longer_input_backward_workspace_bytes", "longer_input_grad_floats", "longer_input_generation_backward")
 
 
 class LongerError(RuntimeError):
@@ -95,6 +96,12 @@ def load_library() -> ctypes.CDLL:
     lib.longer_forward_backward_workspace_bytes.restype = sz
     lib.longer_forward_backward_workspace_bytes.argtypes = [cfgp, i32, i32]
     lib.longer_forward_backward.argtypes = [cfgp, wp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.longer_input_backward_workspace_bytes.restype = sz
+    lib.longer_input_backward_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
+    lib.longer_input_grad_floats.restype = sz
+    lib.longer_input_grad_floats.argtypes = [cfgp, i32, i32]
+    lib.longer_input_generation_backward.argtypes = [cfgp, ctypes.POINTER(CInputWeights), vp, vp, vp, i32, i32, i32, vp, vp, vp, vp,
+                                                     vp, sz, vp]
     lib.longer_last_error.restype = ctypes.c_char_p
     lib.longer_probe_mfma_layout.argtypes = [vp, vp]
     lib.longer_stage_timing.argtypes = [i32]
@@ -102,7 +109,8 @@ def load_library() -> ctypes.CDLL:
     for name in ENTRY_POINTS:
         if name not in ("longer_workspace_bytes", "longer_kv_cache_bytes", "longer_packed_weights_bytes", "longer_last_error",
                         "longer_backward_workspace_bytes", "longer_block_grad_floats", "longer_model_grad_floats",
-                        "longer_forward_backward_workspace_bytes"):
+                        "longer_forward_backward_workspace_bytes", "longer_input_backward_workspace_bytes",
+                        "longer_input_grad_floats"):
             getattr(lib, name).restype = ctypes.c_int
     _LIB = lib
     return lib
@@ -431,3 +439,32 @@ def longer_stage_timing_read():
     n = (ctypes.c_int32 * len(STAGES))()
     _check(load_library().longer_stage_timing_read(ms, n), "longer_stage_timing_read")
     return {s: (ms[i], n[i]) for i, s in enumerate(STAGES)}
+
+
+def longer_input_backward_workspace_bytes(ccfg: CConfig, B: int, L: int, d_e: int) -> int:
+    return int(load_library().longer_input_backward_workspace_bytes(ctypes.byref(ccfg), B, L, d_e))
+
+
+def longer_input_grad_floats(ccfg: CConfig, L: int, d_e: int) -> int:
+    return int(load_library().longer_input_grad_floats(ctypes.byref(ccfg), L, d_e))
+
+
+def input_grad_views(ccfg: CConfig, L: int, d_e: int, flat):
+    """Split the gradient buffer of longer_input_generation_backward into {"pos", "w1", "b1", "w2", "b2"}."""
+    d, f = ccfg.d, ccfg.ffn_mult * ccfg.d
+    out, o = {}, 0
+    for name, shape in (("pos", (L, d_e)), ("w1", (d, f)), ("b1", (f,)), ("w2", (f, d)), ("b2", (d,))):
+        n = 1
+        for v in shape:
+            n *= v
+        out[name] = flat[o:o + n].reshape(shape)
+        o += n
+    return out
+
+
+def longer_input_generation_backward(ccfg, weights, E, tdiff, lens, B, L, d_e, dH, dE_out, dtdiff_out, grads_out, ws, stream=None):
+    _require_gpu()
+    _check(load_library().longer_input_generation_backward(ctypes.byref(ccfg), ctypes.byref(weights), _ptr(E), _ptr(tdiff),
+                                                           _ptr(lens), B, L, d_e, _ptr(dH), _ptr(dE_out), _ptr(dtdiff_out),
+                                                           _ptr(grads_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "longer_input_generation_backward")

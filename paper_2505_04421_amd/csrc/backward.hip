@@ -56,6 +56,7 @@ enum Epilogue {
   EPI_RES_F32 = 1,   // outf[m][n] = res[m][n] + acc + bias[n]
   EPI_ACT = 2,       // out[m][n] = bf16(v), out2[m][n] = bf16(act(v)), v = acc + bias[n]
   EPI_DACT = 3,      // out[m][n] = bf16(acc * act'(pre[m][n]))
+  EPI_F32 = 5,       // outf[m][n] = acc + bias[n]
   EPI_PARTIAL = 4    // parameter gradients: the contraction (over the tokens) is dealt to slices, one workgroup per
                      // tile and slice; outf[slice][m][n] = acc, summed afterwards by bw_reduce_kernel (out2, if
                      // given: [slice][n] column sums of B, the bias gradient's partials)
@@ -316,6 +317,9 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
 #pragma unroll
         for (int e = 0; e < 8; ++e) ob[e] = (__bf16)(v[e] * act_grad((float)pv[e], g.act));
         *(bf16x8*)((__bf16*)g.out + o) = ob;
+      } else if (g.epi == EPI_F32) {
+        *(f32x4*)((float*)g.out + o) = *(const f32x4*)&v[0];
+        *(f32x4*)((float*)g.out + o + 4) = *(const f32x4*)&v[4];
       } else {
         float* po = (float*)g.out + (size_t)outer * g.M * g.N + o;
         *(f32x4*)po = *(const f32x4*)&v[0];
@@ -1073,6 +1077,62 @@ __global__ __launch_bounds__(256) void bw_slot_grad_kernel(StackGeom g, int d, c
   }
 }
 
+
+// ------------------------------------------------------------------------------------
+// Input generation (Section 3.5.1): x = [E + pos ; tdiff] per valid token, H = act(x w1 + b1) w2 + b2.
+// x[r][:] as bf16, zeros for padded tokens
+__global__ __launch_bounds__(256) void bw_input_rows_kernel(const __bf16* __restrict__ E, const __bf16* __restrict__ pos,
+                                                            const __bf16* __restrict__ td, __bf16* __restrict__ x,
+                                                            RowGeom q, int d, int de) {
+  const size_t n = (size_t)q.ntok * d / 4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const int r = (int)(i * 4 / d), c = (int)(i * 4 - (size_t)r * d);
+    const int u = r / q.L, p = r - u * q.L;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (p < row_len(q, u)) {
+      if (c < de) v = load_bf16x4(E + (size_t)r * de + c) + load_bf16x4(pos + (size_t)p * de + c);
+      else v = load_bf16x4(td + (size_t)r * (d - de) + (c - de));
+    }
+    store_bf16x4(x + i * 4, v);
+  }
+}
+// the upstream gradient as bf16, zeros for padded tokens
+__global__ __launch_bounds__(256) void bw_cast_rows_kernel(const float* __restrict__ g, __bf16* __restrict__ gb, RowGeom q, int d) {
+  const size_t n = (size_t)q.ntok * d / 4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const int r = (int)(i * 4 / d);
+    const int u = r / q.L, p = r - u * q.L;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (p < row_len(q, u)) v = *(const f32x4*)(g + i * 4);
+    store_bf16x4(gb + i * 4, v);
+  }
+}
+// dx [ntok][d] -> dE [ntok][de] and dtdiff [ntok][d - de], zeros for padded tokens
+__global__ __launch_bounds__(256) void bw_split_input_grad_kernel(const float* __restrict__ dx, float* __restrict__ dE,
+                                                                  float* __restrict__ dtd, RowGeom q, int d, int de) {
+  const size_t n = (size_t)q.ntok * d / 4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const int r = (int)(i * 4 / d), c = (int)(i * 4 - (size_t)r * d);
+    const int u = r / q.L, p = r - u * q.L;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (p < row_len(q, u)) v = *(const f32x4*)(dx + i * 4);
+    if (c < de) *(f32x4*)(dE + (size_t)r * de + c) = v;
+    else *(f32x4*)(dtd + (size_t)r * (d - de) + (c - de)) = v;
+  }
+}
+// dpos[p][c] = sum over the users whose sequence reaches position p of dx[u L + p][c], c < de
+__global__ __launch_bounds__(256) void bw_pos_grad_kernel(const float* __restrict__ dx, float* __restrict__ dpos, RowGeom q,
+                                                          int B, int d, int de) {
+  const size_t n = (size_t)q.L * de / 4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const int p = (int)(i * 4 / de), c = (int)(i * 4 - (size_t)p * de);
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int u = 0; u < B; ++u)
+      if (p < row_len(q, u)) s += *(const f32x4*)(dx + ((size_t)u * q.L + p) * d + c);
+    *(f32x4*)(dpos + i * 4) = s;
+  }
+}
+
 // ------------------------------------------------------------------------------------ host side
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -1634,6 +1694,46 @@ static int run_model(const longer_config* c, const longer_weights* wts, const vo
   return 0;
 }
 
+
+// ------------------------------------------------------------------------------------
+// Input generation backward (longer_input_generation_backward)
+struct InputWs { size_t x, h, a, dyb, dh, dx, part, bpart, total; };
+static InputWs input_ws(size_t ntok, int d, int f) {
+  InputWs w;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
+  w.x = take(ntok * d * 2);
+  w.h = take(ntok * f * 2);
+  w.a = take(ntok * f * 2);
+  w.dyb = take(ntok * d * 2);
+  w.dh = take(ntok * f * 2);
+  w.dx = take(ntok * d * 4);
+  w.part = take(kPartialBytes);
+  w.bpart = take((size_t)kMaxPartials * 2048 * 4);
+  w.total = o;
+  return w;
+}
+// gradient buffer: [pos L de][w1 d f][b1 f][w2 f d][b2 d]
+struct InputGrads { size_t pos, w1, b1, w2, b2, total; };
+static InputGrads input_grads(int L, int d, int f, int de) {
+  InputGrads g;
+  g.pos = 0; g.w1 = (size_t)L * de; g.b1 = g.w1 + (size_t)d * f; g.w2 = g.b1 + f; g.b2 = g.w2 + (size_t)f * d;
+  g.total = g.b2 + d;
+  return g;
+}
+static int check_input_bw(const longer_config* c, int B, int L, int de, int* d, int* f) {
+  if (!c) return api_error(LONGER_ERR_ARG, "config is NULL");
+  if (c->dtype != LONGER_BF16) return api_error(LONGER_ERR_ARG, "the backward pass is mixed precision: dtype must be LONGER_BF16");
+  if (c->merge != LONGER_MERGE_MEAN) return api_error(LONGER_ERR_ARG, "input generation feeds the mean merge (H of width d)");
+  if (c->act != LONGER_ACT_GELU_ERF && c->act != LONGER_ACT_RELU) return api_error(LONGER_ERR_ARG, "act %d unknown", c->act);
+  if (c->d <= 0 || c->d % 32 || c->d > 512) return api_error(LONGER_ERR_ARG, "d=%d must be a multiple of 32, at most 512", c->d);
+  if (c->ffn_mult <= 0 || c->ffn_mult * c->d > 2048) return api_error(LONGER_ERR_ARG, "ffn_mult=%d: the hidden width must be at most 2048", c->ffn_mult);
+  if (de <= 0 || de >= c->d || de % 32) return api_error(LONGER_ERR_ARG, "d_e=%d must be a multiple of 32 below d=%d", de, c->d);
+  if (B <= 0 || L <= 0 || (long long)B * L >= (1ll << 31) / 8) return api_error(LONGER_ERR_ARG, "B=%d, L=%d out of range", B, L);
+  *d = c->d; *f = c->ffn_mult * c->d;
+  return 0;
+}
+
 }  // namespace bw
 }  // namespace longer
 
@@ -1723,6 +1823,59 @@ int longer_forward_backward(const longer_config* cfg, const longer_weights* w, c
   // the merge's gradients: dM was left in the stack's workspace; the InnerTrans blocks come first in grads_out
   const float* dM = (const float*)((char*)ws + bw::stack_ws(s, fwd).dM);
   return bw::run(cfg, w->inner, H, lens, B, L, dM, dH_out, grads_out, (char*)ws + stack_bytes, st, mi);
+}
+
+size_t longer_input_backward_workspace_bytes(const longer_config* cfg, int B, int L, int d_e) {
+  int d, f;
+  if (bw::check_input_bw(cfg, B, L, d_e, &d, &f)) return 0;
+  return bw::input_ws((size_t)B * L, d, f).total;
+}
+
+size_t longer_input_grad_floats(const longer_config* cfg, int L, int d_e) {
+  int d, f;
+  if (bw::check_input_bw(cfg, 1, L, d_e, &d, &f)) return 0;
+  return bw::input_grads(L, d, f, d_e).total;
+}
+
+int longer_input_generation_backward(const longer_config* cfg, const longer_input_weights* w, const void* E,
+                                     const void* tdiff, const int32_t* lens, int B, int L, int d_e, const float* dH,
+                                     float* dE_out, float* dtdiff_out, float* grads_out,
+                                     void* ws, size_t ws_bytes, void* stream) {
+  int d, f;
+  int rc = bw::check_input_bw(cfg, B, L, d_e, &d, &f);
+  if (rc) return rc;
+  if (!w || !w->pos || !w->w1 || !w->b1 || !w->w2 || !w->b2 || !E || !tdiff || !dH || !dE_out || !dtdiff_out || !grads_out || !ws)
+    return api_error(LONGER_ERR_ARG, "null pointer argument");
+  const void* ptrs[] = {w->pos, w->w1, w->b1, w->w2, w->b2, E, tdiff, dH, dE_out, dtdiff_out, grads_out};
+  for (const void* p : ptrs)
+    if (!bw::aligned16(p)) return api_error(LONGER_ERR_ARG, "every pointer must be 16-byte aligned");
+  if ((uintptr_t)ws & 255) return api_error(LONGER_ERR_ARG, "ws must be 256-byte aligned");
+  const size_t nt = (size_t)B * L;
+  const bw::InputWs l = bw::input_ws(nt, d, f);
+  if (ws_bytes < l.total) return api_error(LONGER_ERR_WS, "workspace too small: %zu < %zu bytes", ws_bytes, l.total);
+  const bw::InputGrads gl = bw::input_grads(L, d, f, d_e);
+  hipStream_t st = (hipStream_t)stream;
+  char* w8 = (char*)ws;
+  __bf16* x = (__bf16*)(w8 + l.x);   __bf16* h = (__bf16*)(w8 + l.h);   __bf16* a = (__bf16*)(w8 + l.a);
+  __bf16* dyb = (__bf16*)(w8 + l.dyb); __bf16* dh = (__bf16*)(w8 + l.dh); float* dx = (float*)(w8 + l.dx);
+  float* part = (float*)(w8 + l.part); float* bpart = (float*)(w8 + l.bpart);
+  const bw::RowGeom q = {lens, L, 1, (int)nt};
+  const bw::RowsValid rv = {lens, L};
+  const unsigned eg = bw::flat_grid(nt * d / 4);
+  bw::bw_zero_kernel<<<bw::flat_grid(gl.total), 256, 0, st>>>(grads_out, gl.total);
+  bw::bw_input_rows_kernel<<<eg, 256, 0, st>>>((const __bf16*)E, (const __bf16*)w->pos, (const __bf16*)tdiff, x, q, d, d_e);
+  bw::bw_cast_rows_kernel<<<eg, 256, 0, st>>>(dH, dyb, q, d);
+  if ((rc = bw::launched("input rows"))) return rc;
+  // forward, recomputed: hidden pre-activation and activation
+  if ((rc = bw::gemm_rows(st, x, d, (const __bf16*)w->w1, f, nt, bw::EPI_ACT, cfg->act, h, a, (const __bf16*)w->b1, nullptr, nullptr, 0, rv))) return rc;
+  // H = a w2 + b2
+  if ((rc = bw::gemm_wgrad(st, a, f, f, dyb, d, d, nt, part, bpart, grads_out + gl.w2, grads_out + gl.b2, rv))) return rc;
+  if ((rc = bw::gemm_rows_t(st, dyb, d, (const __bf16*)w->w2, f, nt, bw::EPI_DACT, cfg->act, dh, h, 0, rv))) return rc;
+  if ((rc = bw::gemm_wgrad(st, x, d, d, dh, f, f, nt, part, bpart, grads_out + gl.w1, grads_out + gl.b1, rv))) return rc;
+  if ((rc = bw::gemm_rows_t(st, dh, f, (const __bf16*)w->w1, d, nt, bw::EPI_F32, 0, dx, nullptr, 0, rv))) return rc;
+  bw::bw_split_input_grad_kernel<<<eg, 256, 0, st>>>(dx, dE_out, dtdiff_out, q, d, d_e);
+  bw::bw_pos_grad_kernel<<<bw::flat_grid((size_t)L * d_e / 4), 256, 0, st>>>(dx, grads_out + gl.pos, q, B, d, d_e);
+  return bw::launched("input gradient");
 }
 
 }  // extern "C"

@@ -1,0 +1,197 @@
+"""GPU parity of longer_input_generation_backward (gradients of the input-generation stage of
+Section 3.5.1 under mixed precision) against the fp64 oracle
+``oracle.longer_oracle_grad.input_generation_backward``.
+
+Tolerance.  The GPU pass rounds the MLP's input, hidden pre-activation, activated hidden values, the
+upstream gradient and the hidden gradient to bf16 (2^-9 relative each, about 1.1e-3 rms), five
+independent roundings on the longest path, so the expected relative L2 error is about 2.5e-3; the bar
+is 1e-2 (GELU).  With ReLU the derivative is a step and a hidden unit within the forward's rounding
+error of zero takes the other branch (a difference of that unit's whole contribution): 1e-1 there,
+the bar of the other backward tests with ReLU (observed 5e-2 per user at width 64, 256 hidden units)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import longer_synth as synth
+from oracle import longer_oracle_grad as org
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2
+TOL_RELU = 1e-1
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _rel(a, b):
+    den = float(np.linalg.norm(b))
+    return float(np.linalg.norm(a - b)) / (den if den > 0 else 1.0)
+
+
+def _case(d, d_e, B, L, act="gelu_erf", ragged=True, index=61, ffn_mult=4):
+    heads = d // 16
+    cfg = synth.CONFIGS["C3"].replace(B=B, L=L, d=d, heads=heads, inner_heads=heads, act=act, ffn_mult=ffn_mult,
+                                      ragged=ragged, len_lo=0, len_hi=L, index=index, dtype="bf16")
+    case = synth.make_input_case(cfg, d_e)
+    if ragged:
+        # one full-length user and one without any token: real values where the draw had padding
+        g = np.random.default_rng(index)
+        case["lens"][0] = L
+        case["E"][0] = synth.round_bf16(g.standard_normal(case["E"][0].shape).astype(np.float32))
+        case["tdiff"][0] = synth.round_bf16(g.standard_normal(case["tdiff"][0].shape).astype(np.float32))
+        if B > 2:
+            case["lens"][1] = 0
+            case["E"][1] = np.float32("nan")
+            case["tdiff"][1] = np.float32("nan")
+    rng = np.random.Generator(np.random.Philox(synth.SEED_BASE + 7000 + index))
+    dH = rng.standard_normal(size=(B, L, d), dtype=np.float32) / np.float32(np.sqrt(B * L))
+    if ragged:
+        # padded tokens' upstream gradient must not be read
+        pos = np.arange(L)[None, :, None]
+        dH = np.where(pos < case["lens"][:, None, None], dH, np.float32("nan")).astype(np.float32)
+    return cfg, case, dH
+
+
+def _run_gpu(cfg, case, dH, d_e, ws_fill=None):
+    import paper_2505_04421_amd as lg
+    from gpu_util import guarded_empty
+    model = lg.DeviceModel(cfg, synth.draw_weights(cfg))
+    dev = model.device
+    B, L, d = cfg.B, cfg.L, cfg.d
+    mlp = {k: model.upload(v) for k, v in case["mlp"].items()}
+    wts = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
+    Ed, Td = model.upload(case["E"]), model.upload(case["tdiff"])
+    lens = None if case["lens"] is None else torch.from_numpy(case["lens"].astype(np.int32)).to(dev)
+    n_ws = lg.longer_input_backward_workspace_bytes(model.ccfg, B, L, d_e)
+    nf = lg.longer_input_grad_floats(model.ccfg, L, d_e)
+    assert n_ws > 0 and nf > 0, lg.longer_last_error()
+    ws, g_ws = guarded_empty(dev, (n_ws,), torch.uint8)
+    dE, g_de = guarded_empty(dev, (B, L, d_e), torch.float32)
+    dtd, g_dt = guarded_empty(dev, (B, L, d - d_e), torch.float32)
+    grads, g_gr = guarded_empty(dev, (nf,), torch.float32)
+    if ws_fill is not None:
+        ws.fill_(ws_fill)
+    dH_t = torch.from_numpy(np.ascontiguousarray(dH, dtype=np.float32)).to(dev)
+    lg.longer_input_generation_backward(model.ccfg, wts, Ed, Td, lens, B, L, d_e, dH_t, dE, dtd, grads, ws)
+    torch.cuda.synchronize()
+    for g, what in ((g_ws, "workspace"), (g_de, "dE_out"), (g_dt, "dtdiff_out"), (g_gr, "grads_out")):
+        g.check(what)
+    views = lg.input_grad_views(model.ccfg, L, d_e, grads)
+    return (dE.cpu().numpy().astype(np.float64), dtd.cpu().numpy().astype(np.float64),
+            {k: v.cpu().numpy().astype(np.float64) for k, v in views.items()})
+
+
+def _compare(name, cfg, case, dH, d_e, ws_fill=None):
+    _say("input backward case %s: B=%d L=%d d=%d = %d + %d f=%d act=%s ragged=%s" %
+         (name, cfg.B, cfg.L, cfg.d, d_e, cfg.d - d_e, cfg.ffn_mult * cfg.d, cfg.act, case["lens"] is not None))
+    dE, dtd, g = _run_gpu(cfg, case, dH, d_e, ws_fill)
+    tol = TOL_RELU if cfg.act == "relu" else TOL
+    dH_ref = np.nan_to_num(dH.astype(np.float64), nan=0.0)     # the oracle slices [:n]; the rest is never used
+    dE_ref, dtd_ref, g_ref = org.input_generation_backward(cfg, case["mlp"], case["E"], case["tdiff"], case["lens"], dH_ref)
+    assert np.isfinite(dE).all() and np.isfinite(dtd).all()
+    lens = case["lens"]
+    worst = 0.0
+    for u in range(cfg.B):
+        n = cfg.L if lens is None else int(min(lens[u], cfg.L))
+        assert not dE[u, n:].any() and not dtd[u, n:].any(), "user %d: padded rows must be exact zeros" % u
+        if n == 0:
+            continue
+        e = max(_rel(dE[u], dE_ref[u]), _rel(dtd[u], dtd_ref[u]))
+        worst = max(worst, e)
+        assert e <= tol, ("dE/dtdiff", u, e)
+    _say("  dE, dtdiff: worst per-user rel-L2 %.3e (tol %.0e)" % (worst, tol))
+    for k in ("pos", "w1", "b1", "w2", "b2"):
+        assert np.isfinite(g[k]).all(), k
+        e = _rel(g[k], g_ref[k])
+        _say("  %-4s rel-L2 %.3e" % (k, e))
+        assert e <= tol, (k, e)
+    # rows of the positional embedding no user reaches: exact zeros
+    reach = cfg.L if lens is None else int(min(lens.max(), cfg.L))
+    assert not g["pos"][reach:].any()
+
+
+@pytest.mark.parametrize("d,d_e,B,L,act,ragged", [
+    (128, 96, 5, 333, "gelu_erf", True),      # the headline width as 96 + 32: several tiles and a ragged tail
+    (64, 32, 3, 75, "gelu_erf", True),
+    (64, 32, 4, 200, "relu", True),
+    (256, 224, 2, 130, "gelu_erf", False),
+    (128, 64, 7, 129, "gelu_erf", False),     # one row past a tile
+])
+def test_input_generation_backward(d, d_e, B, L, act, ragged):
+    cfg, case, dH = _case(d, d_e, B, L, act=act, ragged=ragged)
+    _compare("d%d" % d, cfg, case, dH, d_e)
+
+
+def test_input_generation_backward_ignores_stale_workspace():
+    """Workspace full of NaN before the call: no padded row and no stale value reaches a result."""
+    cfg, case, dH = _case(128, 96, 6, 260, index=62)
+    _compare("nan workspace", cfg, case, dH, 96, ws_fill=0xFF)
+
+
+def test_input_generation_backward_short_users_only():
+    """Every user shorter than a tile, one of them empty; the tail of the positional embedding gets zeros."""
+    cfg, case, dH = _case(128, 96, 9, 400, index=63)
+    case["lens"][:] = np.array([17, 0, 5, 33, 1, 64, 2, 90, 31], dtype=np.int32)
+    pos = np.arange(cfg.L)[None, :, None]
+    g = np.random.default_rng(5)
+    E = synth.round_bf16(g.standard_normal(case["E"].shape).astype(np.float32))
+    T = synth.round_bf16(g.standard_normal(case["tdiff"].shape).astype(np.float32))
+    case["E"] = np.where(pos < case["lens"][:, None, None], E, np.float32("nan")).astype(np.float32)
+    case["tdiff"] = np.where(pos < case["lens"][:, None, None], T, np.float32("nan")).astype(np.float32)
+    d3 = g.standard_normal(dH.shape).astype(np.float32) / 50
+    dH = np.where(pos < case["lens"][:, None, None], d3, np.float32("nan")).astype(np.float32)
+    _compare("short users", cfg, case, dH, 96)
+
+
+def test_input_generation_backward_feeds_from_the_model_backward():
+    """Chain: longer_forward_backward's dH_out as the upstream gradient, against the oracle's
+    model_backward -> input_generation_backward on the same inputs."""
+    import paper_2505_04421_amd as lg
+    from oracle import longer_oracle as orc
+    d_e = 96
+    cfg = synth.CONFIGS["C3"].replace(B=4, L=150, ragged=True, len_lo=0, len_hi=150, index=64, dtype="bf16")
+    case_in = synth.make_input_case(cfg, d_e)
+    H_ref = orc.input_generation(cfg, case_in["mlp"], case_in["E"], case_in["tdiff"], case_in["lens"])
+    H = synth.round_bf16(np.nan_to_num(H_ref, nan=0.0).astype(np.float32))
+    case = synth.make_case(cfg)
+    case["H"], case["lens"] = H, case_in["lens"]
+    labels = synth.draw_labels(cfg)
+    _say("chain: model backward -> input generation backward, B=%d L=%d" % (cfg.B, cfg.L))
+    _, _, dH_ref, _, _ = org.model_backward(cfg, case["weights"], H, case["G"], case["lens"], labels, keep="input_only")
+    dE_ref, dtd_ref, g_ref = org.input_generation_backward(cfg, case_in["mlp"], case_in["E"], case_in["tdiff"], case_in["lens"], dH_ref)
+
+    model = lg.DeviceModel(cfg, case["weights"])
+    dev = model.device
+    B, L = cfg.B, cfg.L
+    Hd, Gd = model.upload(H), model.upload(case["G"])
+    lens = torch.from_numpy(case["lens"].astype(np.int32)).to(dev)
+    lab = torch.from_numpy(np.ascontiguousarray(labels, dtype=np.float32)).to(dev)
+    ws = torch.empty(lg.longer_forward_backward_workspace_bytes(model.ccfg, B, L), dtype=torch.uint8, device=dev)
+    loss = torch.empty(4, dtype=torch.float32, device=dev)
+    logits = torch.empty(B, dtype=torch.float32, device=dev)
+    dH = torch.empty(B, L, cfg.d, dtype=torch.float32, device=dev)
+    dG = torch.empty(B, cfg.m, cfg.d, dtype=torch.float32, device=dev)
+    grads = torch.empty(lg.longer_model_grad_floats(model.ccfg), dtype=torch.float32, device=dev)
+    lg.longer_forward_backward(model.ccfg, model.weights, Hd, Gd, lens, B, L, lab, loss, logits, dH, dG, grads, ws)
+    mlp = {k: model.upload(v) for k, v in case_in["mlp"].items()}
+    wts = lg.CInputWeights(**{k: v.data_ptr() for k, v in mlp.items()})
+    Ed, Td = model.upload(case_in["E"]), model.upload(case_in["tdiff"])
+    ws2 = torch.empty(lg.longer_input_backward_workspace_bytes(model.ccfg, B, L, d_e), dtype=torch.uint8, device=dev)
+    dE = torch.empty(B, L, d_e, dtype=torch.float32, device=dev)
+    dtd = torch.empty(B, L, cfg.d - d_e, dtype=torch.float32, device=dev)
+    gin = torch.empty(lg.longer_input_grad_floats(model.ccfg, L, d_e), dtype=torch.float32, device=dev)
+    lg.longer_input_generation_backward(model.ccfg, wts, Ed, Td, lens, B, L, d_e, dH, dE, dtd, gin, ws2)
+    torch.cuda.synchronize()
+    views = lg.input_grad_views(model.ccfg, L, d_e, gin)
+    e = _rel(dE.cpu().numpy().astype(np.float64), dE_ref)
+    _say("  dE rel-L2 %.3e" % e)
+    assert e <= 8e-2
+    for k in ("pos", "w1", "b1", "w2", "b2"):
+        e = _rel(views[k].cpu().numpy().astype(np.float64), g_ref[k])
+        _say("  %-4s rel-L2 %.3e" % (k, e))
+        assert e <= 8e-2, (k, e)
