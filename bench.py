@@ -141,6 +141,8 @@ def run_merge_backward(lg, torch, cfg, case, steps):
             "roofline": {"bound": "hbm", "achieved": work["hbm_bytes"] / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
                          "frac": work["hbm_bytes"] / (ms * 1e-3) / 1e9 / 8000.0,
                          "bytes_per_step": work["hbm_bytes"],
+                         "traffic": 26.57e9 if cfg.name == "C3" else None,
+                         "traffic_source": "profiles/merge_backward_c3_hbm_traffic.md" if cfg.name == "C3" else None,
                          "note": "unfused pass: every activation makes one trip through memory per use (tally in "
                                  "paper_2505_04421_amd/flops.py)"},
             "workspace_bytes": n_ws}
@@ -377,6 +379,9 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the other forward configurations (all_configs)")
     ap.add_argument("--no-probe", action="store_true", help="skip the instruction-rate probes")
     ap.add_argument("--no-backward", action="store_true", help="skip the backward pass of the token merge")
+    ap.add_argument("--merge-backward-only", action="store_true",
+                    help="run nothing but the backward pass of the token merge (2 warm-up calls + --steps timed calls) and "
+                         "print its block: for counter runs under rocprofv3")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP graph replay measurement (profiler runs)")
     ap.add_argument("--probe-all", action="store_true",
                     help="run every mode of the instruction-rate probe (include/longer.h lists them), print "
@@ -414,6 +419,10 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.merge_backward_only:
+        print(json.dumps({"merge_backward": run_merge_backward(lg, torch, cfg, synth.make_case(cfg), args.steps)}))
+        return
 
     if args.probe_all:
         modes = {0: PROBE_MODES[0]}
