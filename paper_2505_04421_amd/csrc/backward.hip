@@ -57,6 +57,8 @@ enum Epilogue {
   EPI_ACT = 2,       // out[m][n] = bf16(v), out2[m][n] = bf16(act(v)), v = acc + bias[n]
   EPI_DACT = 3,      // out[m][n] = bf16(acc * act'(pre[m][n]))
   EPI_F32 = 5,       // outf[m][n] = acc + bias[n]
+  EPI_FFN_MID = 6,   // two products in one launch, v = A B + bias and g = A2 B2 (same shapes):
+                     // out[m][n] = bf16(g * act'(v)), out2[m][n] = bf16(act(v)); v itself is not stored
   EPI_PARTIAL = 4    // parameter gradients: the contraction (over the tokens) is dealt to slices, one workgroup per
                      // tile and slice; outf[slice][m][n] = acc, summed afterwards by bw_reduce_kernel (out2, if
                      // given: [slice][n] column sums of B, the bias gradient's partials)
@@ -91,6 +93,7 @@ struct GemmArgs {
   int epi, act;
   void* out; void* out2; int ldo;
   const __bf16* bias; const float* res; const __bf16* pre;
+  const __bf16* A2; const __bf16* B2; int lda2, ldb2;   // the second product of a two-product launch (EPI_FFN_MID)
 };
 
 // Phi(v) = (1 + erf(v / sqrt 2)) / 2 and exp(-v^2 / 2) from one exponential: for z >= 0,
@@ -118,12 +121,30 @@ __device__ __forceinline__ float act_grad(float v, int act) {
   return c + v * 0.39894228040143268f * e;
 }
 
+// The activation and its derivative at once, for the launch that rounds both to bf16 right away.
+// GELU: Phi(v) - 1/2 as v times an even polynomial of degree 8 (minimax fit on [-3.5, 3.5] that reaches 1/2
+// at the interval's end, clamped to [0, 1] beyond it; absolute error below 1.3e-3, under the bf16
+// rounding step of the values it produces) and the density from one exponential.
+__device__ __forceinline__ void act_both(float v, int act, float* a, float* da) {
+  if (act == LONGER_ACT_RELU) { *a = v > 0.f ? v : 0.f; *da = v > 0.f ? 1.f : 0.f; return; }
+  const float u = v * v;
+  float pl = 9.366767568843253e-06f;
+  pl = fmaf(pl, u, -0.0003847714538096606f);
+  pl = fmaf(pl, u, 0.0064495445928312006f);
+  pl = fmaf(pl, u, -0.05893596715178192f);
+  pl = fmaf(pl, u, 0.3934098519357524f);
+  const float c = __builtin_amdgcn_fmed3f(fmaf(v, pl, 0.5f), 0.f, 1.f);
+  const float e = __expf(-0.5f * u);
+  *a = v * c;
+  *da = fmaf(v * e, 0.39894228040143268f, c);
+}
+
 constexpr int kPitchKC = 40;            // elements per row of a contraction-contiguous LDS tile (32 + 8 pad)
 constexpr int kTileElems = 128 * kPitchKC;   // >= 32 * 128 of the strided form
 constexpr int kStagePitch = 68;         // floats per row of the epilogue's staging area (64 + 4 pad)
 
-template <bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) {
+template <bool A_KC, bool B_KC, bool DUAL = false>
+__global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(16))) __bf16 smem[4 * kTileElems];
   auto sA = [&](int buf) { return smem + buf * kTileElems; };          // two buffers per operand
   auto sB = [&](int buf) { return smem + (2 + buf) * kTileElems; };
@@ -149,13 +170,18 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
   if (!split && !rows_any_valid(g.rows, m0, min(g.M, m0 + 128))) return;   // a tile of padded rows: nobody reads its result
   const int nk = ksteps > kfirst ? (ksteps - kfirst + kstride - 1) / kstride : 0;
 
-  f32x16 acc[2][2];
+  constexpr int NPH = DUAL ? 2 : 1;     // products of the launch
+  f32x16 accs[NPH][2][2];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int ph = 0; ph < NPH; ++ph)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accs[ph][a][b][r] = 0.f;
+  const __bf16* opA = g.A; const __bf16* opB = g.B;
+  int ldA = g.lda, ldB = g.ldb;
 
   // Split GEMM with a bias gradient asked for (out2): the column sums of B over the slice are one more
   // product, ones[32, Kc] B, taken by the waves that hold the first 32 rows of the first M tile;
@@ -186,20 +212,20 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
       if (A_KC) {
         const int row = c >> 2, kc = c & 3;
         const int gr = m0 + row, gk = k0 + 8 * kc;
-        if (gr < g.M && gk < kend) pa[i] = *(const bf16x8*)(g.A + (size_t)gr * g.lda + gk);
+        if (gr < g.M && gk < kend) pa[i] = *(const bf16x8*)(opA + (size_t)gr * ldA + gk);
       } else {
         const int kr = c >> 4, xc = c & 15;
         const int gk = k0 + kr, gx = m0 + 8 * xc;
-        if (gk < kend && gx < g.M && (!split || row_valid(g.rows, gk))) pa[i] = *(const bf16x8*)(g.A + (size_t)gk * g.lda + gx);
+        if (gk < kend && gx < g.M && (!split || row_valid(g.rows, gk))) pa[i] = *(const bf16x8*)(opA + (size_t)gk * ldA + gx);
       }
       if (B_KC) {
         const int row = c >> 2, kc = c & 3;
         const int gr = n0 + row, gk = k0 + 8 * kc;
-        if (gr < g.N && gk < kend) pb[i] = *(const bf16x8*)(g.B + (size_t)gr * g.ldb + gk);
+        if (gr < g.N && gk < kend) pb[i] = *(const bf16x8*)(opB + (size_t)gr * ldB + gk);
       } else {
         const int kr = c >> 4, xc = c & 15;
         const int gk = k0 + kr, gx = n0 + 8 * xc;
-        if (gk < kend && gx < g.N && (!split || row_valid(g.rows, gk))) pb[i] = *(const bf16x8*)(g.B + (size_t)gk * g.ldb + gx);
+        if (gk < kend && gx < g.N && (!split || row_valid(g.rows, gk))) pb[i] = *(const bf16x8*)(opB + (size_t)gk * ldB + gx);
       }
     }
   };
@@ -234,7 +260,12 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
       while (kt < nk && !rows_any_valid(g.rows, (kfirst + kt * kstride) * 32, min(kend, (kfirst + kt * kstride) * 32 + 32))) ++kt;
     return kt;
   };
-  int kt = next_step(0), buf = 0;
+  int buf = 0;
+#pragma unroll
+  for (int ph = 0; ph < NPH; ++ph) {
+  f32x16 (&acc)[2][2] = accs[ph];
+  if (DUAL && ph == 1) { opA = g.A2; opB = g.B2; ldA = g.lda2; ldB = g.ldb2; }
+  int kt = next_step(0);
   if (kt < nk) gload(kt, ra[0], rb[0]);
   while (kt < nk) {
     sstore(buf, ra[0], rb[0]);
@@ -262,6 +293,8 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
     buf ^= 1;
     kt = kn;
   }
+  }
+  f32x16 (&acc)[2][2] = accs[0];
 
   if (!A_KC && !B_KC && bias_sum && hi == 0) {
 #pragma unroll
@@ -274,6 +307,21 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
   static_assert(4 * 32 * kStagePitch * 4 <= 4 * kTileElems * 2, "staging area fits the operand buffers");
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
+    float v2[DUAL ? 4 : 1][8];        // two-product launch: the second product's values of this thread's chunks
+    if constexpr (DUAL) {
+      __syncthreads();
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) stage[tile_row(r, hi) * kStagePitch + 32 * b + l32] = accs[NPH - 1][a][b][r];
+      __syncthreads();
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int id = it * 64 + lane, row = id >> 3, cc = id & 7;
+        *(f32x4*)&v2[it][0] = *(const f32x4*)&stage[row * kStagePitch + 8 * cc];
+        *(f32x4*)&v2[it][4] = *(const f32x4*)&stage[row * kStagePitch + 8 * cc + 4];
+      }
+    }
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < 2; ++b)
@@ -317,6 +365,17 @@ __global__ __launch_bounds__(256, A_KC ? 4 : 3) void bw_gemm_kernel(GemmArgs g) 
 #pragma unroll
         for (int e = 0; e < 8; ++e) ob[e] = (__bf16)(v[e] * act_grad((float)pv[e], g.act));
         *(bf16x8*)((__bf16*)g.out + o) = ob;
+      } else if (DUAL && g.epi == EPI_FFN_MID) {
+        bf16x8 oa;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float av, dv;
+          act_both(v[e], g.act, &av, &dv);
+          oa[e] = (__bf16)av;
+          ob[e] = (__bf16)(v2[DUAL ? it : 0][e] * dv);
+        }
+        *(bf16x8*)((__bf16*)g.out + o) = ob;
+        *(bf16x8*)((__bf16*)g.out2 + o) = oa;
       } else if (g.epi == EPI_F32) {
         *(f32x4*)((float*)g.out + o) = *(const f32x4*)&v[0];
         *(f32x4*)((float*)g.out + o + 4) = *(const f32x4*)&v[4];
@@ -1133,6 +1192,17 @@ __global__ __launch_bounds__(256) void bw_pos_grad_kernel(const float* __restric
   }
 }
 
+// out[c][r] = in[r][c]  (bf16, small parameter matrices; 32 x 32 tiles through LDS)
+__global__ __launch_bounds__(256) void bw_transpose_kernel(const __bf16* __restrict__ in, __bf16* __restrict__ out, int rows, int cols) {
+  __shared__ __bf16 t[32][33];
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32, x = threadIdx.x & 31, y = threadIdx.x >> 5;
+  for (int i = y; i < 32; i += 8)
+    if (r0 + i < rows && c0 + x < cols) t[i][x] = in[(size_t)(r0 + i) * cols + c0 + x];
+  __syncthreads();
+  for (int i = y; i < 32; i += 8)
+    if (c0 + i < cols && r0 + x < rows) out[(size_t)(c0 + i) * rows + r0 + x] = t[x][i];
+}
+
 // ------------------------------------------------------------------------------------ host side
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -1161,7 +1231,8 @@ constexpr size_t kPartialBytes = (size_t)kMaxPartials * 128 * 128 * 4;
 struct Workspace {
   size_t wcat, bcat;                       // per layer: [d][3d] bf16, [3d] bf16
   size_t xin;                              // per layer: fp32 [ntok][d]
-  size_t n1, qkv, o, xmid, n2, h, a;       // one block's recomputed intermediates
+  size_t w1t;                              // per layer: W1 transposed, [f][d] bf16
+  size_t n1, qkv, o, xmid, n2, a;          // one block's recomputed intermediates
   size_t dy, dyb, dh, dn, dxm, dxmb, dob, dqkv, stat;
   size_t part, bpart;                      // partial parameter gradients of one split GEMM (matrix, bias)
   size_t fwd, fwd_bytes, ztmp;             // the fused forward kernel's scratch and output when it recomputes block inputs
@@ -1173,13 +1244,13 @@ static Workspace workspace(int layers, size_t ntok, int d, int f, int heads, siz
   auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
   w.wcat = take((size_t)layers * d * 3 * d * 2);
   w.bcat = take((size_t)layers * up256((size_t)3 * d * 2));
+  w.w1t = take((size_t)layers * d * f * 2);
   w.xin = take((size_t)layers * ntok * d * 4);
   w.n1 = take(ntok * d * 2);
   w.qkv = take(ntok * 3 * d * 2);
   w.o = take(ntok * d * 2);
   w.xmid = take(ntok * d * 4);
   w.n2 = take(ntok * d * 2);
-  w.h = take(ntok * f * 2);
   w.a = take(ntok * f * 2);
   w.dy = take(ntok * d * 4);
   w.dyb = take(ntok * d * 2);
@@ -1260,7 +1331,11 @@ static int gemm(hipStream_t st, bool a_kc, bool b_kc, GemmArgs g, int splits) {
   g.nsplit = splits;
   const int outer = g.epi == EPI_PARTIAL ? splits : ntm, inner = g.epi == EPI_PARTIAL ? ntm * ntn : ntn;
   dim3 grid((unsigned)(((outer + 7) / 8) * 8 * inner));            // see the tile order in the kernel
-  if (a_kc && b_kc) bw_gemm_kernel<true, true><<<grid, 256, 0, st>>>(g);
+  if (g.epi == EPI_FFN_MID) {
+    if (!(a_kc && b_kc) || !aligned16(g.A2) || !aligned16(g.B2) || g.lda2 % 8 || g.ldb2 % 8)
+      return api_error(LONGER_ERR_ARG, "backward GEMM operand misaligned");
+    bw_gemm_kernel<true, true, true><<<grid, 256, 0, st>>>(g);
+  } else if (a_kc && b_kc) bw_gemm_kernel<true, true><<<grid, 256, 0, st>>>(g);
   else if (a_kc && !b_kc) bw_gemm_kernel<true, false><<<grid, 256, 0, st>>>(g);
   else if (!a_kc && !b_kc) bw_gemm_kernel<false, false><<<grid, 256, 0, st>>>(g);
   else return api_error(LONGER_ERR_ARG, "backward GEMM form not built");
@@ -1286,6 +1361,21 @@ static int gemm_rows_t(hipStream_t st, const __bf16* dy, int kc, const __bf16* W
   g.A = dy; g.lda = kc; g.B = W; g.ldb = ldb ? ldb : kc; g.M = (int)ntok; g.N = n; g.Kc = kc;
   g.epi = epi; g.act = act; g.out = out; g.ldo = n; g.pre = pre;
   return gemm(st, true, true, g, 1);
+}
+// The middle of the FFN's backward in one launch: v = x W1 + b1 (recomputed, not stored), g = dy W2^T,
+// a_out = bf16(act(v)), dh_out = bf16(g act'(v)).  x, dy [ntok][d]; w1t = W1 transposed, [f][d]; w2 [f][d].
+static int gemm_ffn_mid(hipStream_t st, const __bf16* x, const __bf16* dy, int d, const __bf16* w1t, const __bf16* w2, int f,
+                        const __bf16* b1, size_t ntok, int act, __bf16* dh_out, __bf16* a_out, RowsValid rows) {
+  GemmArgs g = {};
+  g.rows = rows;
+  g.A = x; g.lda = d; g.B = w1t; g.ldb = d; g.A2 = dy; g.lda2 = d; g.B2 = w2; g.ldb2 = d;
+  g.M = (int)ntok; g.N = f; g.Kc = d;
+  g.epi = EPI_FFN_MID; g.act = act; g.out = dh_out; g.out2 = a_out; g.ldo = f; g.bias = b1;
+  return gemm(st, true, true, g, 1);
+}
+static int transpose(hipStream_t st, const __bf16* in, __bf16* out, int rows, int cols) {
+  bw_transpose_kernel<<<dim3((cols + 31) / 32, (rows + 31) / 32), 256, 0, st>>>(in, out, rows, cols);
+  return launched("transpose");
 }
 // dW [m][n] = x^T dy: x [ntok][.. m columns, pitch lda], dy [ntok][.. n columns, pitch ldb]
 // and db [n] = column sums of dy
@@ -1351,7 +1441,8 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
   auto wcat = [&](int l) { return (__bf16*)(ws + w.wcat) + (size_t)l * d * 3 * d; };
   auto bcat = [&](int l) { return (__bf16*)(ws + w.bcat + (size_t)l * up256((size_t)3 * d * 2)); };
   __bf16* n1 = (__bf16*)(ws + w.n1);   __bf16* qkv = (__bf16*)(ws + w.qkv); __bf16* o = (__bf16*)(ws + w.o);
-  float* xmid = (float*)(ws + w.xmid); __bf16* n2 = (__bf16*)(ws + w.n2);   __bf16* h = (__bf16*)(ws + w.h);
+  float* xmid = (float*)(ws + w.xmid); __bf16* n2 = (__bf16*)(ws + w.n2);
+  auto w1t = [&](int l) { return (__bf16*)(ws + w.w1t) + (size_t)l * d * f; };
   __bf16* a = (__bf16*)(ws + w.a);     float* dy = (float*)(ws + w.dy);     __bf16* dyb = (__bf16*)(ws + w.dyb);
   __bf16* dh = (__bf16*)(ws + w.dh);   __bf16* dn = (__bf16*)(ws + w.dn);   float* dxm = (float*)(ws + w.dxm);
   __bf16* dxmb = (__bf16*)(ws + w.dxmb); __bf16* dob = (__bf16*)(ws + w.dob); __bf16* dqkv = (__bf16*)(ws + w.dqkv);
@@ -1368,13 +1459,13 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     bw_concat_qkv_kernel<<<64, 256, 0, st>>>((const __bf16*)b.wq, (const __bf16*)b.wk, (const __bf16*)b.wv, (const __bf16*)b.bq,
                                              (const __bf16*)b.bk, (const __bf16*)b.bv, wcat(l), bcat(l), d);
     BW_TRY(launched("weight concatenation"));
+    BW_TRY(transpose(st, (const __bf16*)b.w1, w1t(l), d, f));
   }
   bw_load_x0_kernel<<<flat_grid(nt * d / 4), 256, 0, st>>>((const __bf16*)H, xin(0), q, d);
   BW_TRY(launched("input load"));
 
-  // one block forward from its input x: intermediates into the workspace, output (fp32) into y_out
-  // unless that is NULL (the last block's output is not needed)
-  auto forward = [&](int l, float* y_out) -> int {
+  // one block forward from its input x, up to the FFN's input: intermediates into the workspace
+  auto forward = [&](int l) -> int {
     const longer_block& b = inner[l];
     const float* x = xin(l);
     ln_fwd(st, ln_grid, d, x, (const __bf16*)b.ln1_g, (const __bf16*)b.ln1_b, n1, (int)nt, c->ln_eps, rv);
@@ -1385,11 +1476,7 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     BW_TRY(launched("group attention"));
     BW_TRY(gemm_rows(st, o, d, (const __bf16*)b.wo, d, nt, EPI_RES_F32, 0, xmid, nullptr, (const __bf16*)b.bo, x, nullptr, 0, rv));
     ln_fwd(st, ln_grid, d, xmid, (const __bf16*)b.ln2_g, (const __bf16*)b.ln2_b, n2, (int)nt, c->ln_eps, rv);
-    BW_TRY(launched("LayerNorm"));
-    BW_TRY(gemm_rows(st, n2, d, (const __bf16*)b.w1, f, nt, EPI_ACT, c->act, h, a, (const __bf16*)b.b1, nullptr, nullptr, 0, rv));
-    if (y_out)
-      BW_TRY(gemm_rows(st, a, f, (const __bf16*)b.w2, d, nt, EPI_RES_F32, 0, y_out, nullptr, (const __bf16*)b.b2, xmid, nullptr, 0, rv));
-    return 0;
+    return launched("LayerNorm");
   };
 
   // the chain of block inputs (recomputed: nothing is kept from a forward call), by the fused forward
@@ -1410,10 +1497,11 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
   for (int l = s.layers - 1; l >= 0; --l) {
     const longer_block& b = inner[l];
     float* g = grads + (size_t)l * gl.total;
-    BW_TRY(forward(l, nullptr));                 // this block's intermediates, from its input alone
-    // FFN: y = xmid + act(n2 W1 + b1) W2 + b2
+    BW_TRY(forward(l));                          // this block's intermediates, from its input alone
+    // FFN: y = xmid + act(n2 W1 + b1) W2 + b2; the hidden pre-activation is formed inside the launch
+    // that takes its gradient, and only the activated values and the hidden gradient reach memory
+    BW_TRY(gemm_ffn_mid(st, n2, dyb, d, w1t(l), (const __bf16*)b.w2, f, (const __bf16*)b.b1, nt, c->act, dh, a, rv));
     BW_TRY(gemm_wgrad(st, a, f, f, dyb, d, d, nt, part, bpart, g + gl.w2, g + gl.b2, rv));
-    BW_TRY(gemm_rows_t(st, dyb, d, (const __bf16*)b.w2, f, nt, EPI_DACT, c->act, dh, h, 0, rv));
     BW_TRY(gemm_wgrad(st, n2, d, d, dh, f, f, nt, part, bpart, g + gl.w1, g + gl.b1, rv));
     BW_TRY(gemm_rows_t(st, dh, f, (const __bf16*)b.w1, d, nt, EPI_BF16, 0, dn, nullptr, 0, rv));
     BW_TRY(ln_bwd(st, ln_grid, d, dn, xmid, (const __bf16*)b.ln2_g, dy, dxm, dxmb, part, g + gl.ln2_g, (int)nt, c->ln_eps, false, rv));
