@@ -139,15 +139,22 @@ __device__ __forceinline__ void act_both(float v, int act, float* a, float* da) 
   *da = fmaf(v * e, 0.39894228040143268f, c);
 }
 
-constexpr int kPitchKC = 40;            // elements per row of a contraction-contiguous LDS tile (32 + 8 pad)
-constexpr int kTileElems = 128 * kPitchKC;   // >= 32 * 128 of the strided form
 constexpr int kStagePitch = 68;         // floats per row of the epilogue's staging area (64 + 4 pad)
 
-template <bool A_KC, bool B_KC, bool DUAL = false>
+// KS: contraction elements per step.  Every launch uses 32: steps of 64 and 128 (one LDS buffer per operand
+// at 128) were measured for the two-product launch, whose contraction is only the model width, and
+// changed nothing (6.49 - 6.56 ms per merge backward at the headline shape for the three widths).
+template <bool A_KC, bool B_KC, bool DUAL = false, int KS = 32>
 __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel(GemmArgs g) {
-  __shared__ __attribute__((aligned(16))) __bf16 smem[4 * kTileElems];
-  auto sA = [&](int buf) { return smem + buf * kTileElems; };          // two buffers per operand
-  auto sB = [&](int buf) { return smem + (2 + buf) * kTileElems; };
+  static_assert(KS == 32 || (A_KC && B_KC), "wide steps: contraction-contiguous operands only");
+  constexpr int kPitchKC = KS + 8;            // elements per row of a contraction-contiguous LDS tile (8 pad)
+  constexpr int kTileElems = 128 * kPitchKC;  // >= KS * 128 of the strided form
+  constexpr int CPR = KS / 8;                 // 16-byte chunks per tile row (contraction-contiguous form)
+  constexpr int NCH = KS / 16;                // chunks per thread and operand tile
+  constexpr int NBUF = KS >= 128 ? 1 : 2;
+  __shared__ __attribute__((aligned(16))) __bf16 smem[2 * NBUF * kTileElems];
+  auto sA = [&](int buf) { return smem + buf * kTileElems; };          // NBUF buffers per operand
+  auto sB = [&](int buf) { return smem + (NBUF + buf) * kTileElems; };
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int wm = w & 1, wn = w >> 1, hi = lane >> 5, l32 = lane & 31;
   // Tile order.  Workgroups go to the 8 accelerator dies round-robin by index, each die with an L2 of
@@ -165,7 +172,7 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
   // contraction steps of 32: a row GEMM takes them all; slice `outer` of a gradient GEMM takes every
   // nsplit-th step, so that every slice samples the whole batch (long and short users alike)
   const int kstride = split ? g.nsplit : 1, kfirst = split ? outer : 0;
-  const int ksteps = (g.Kc + 31) / 32;
+  const int ksteps = (g.Kc + KS - 1) / KS;
   const int kend = g.Kc;
   if (!split && !rows_any_valid(g.rows, m0, min(g.M, m0 + 128))) return;   // a tile of padded rows: nobody reads its result
   const int nk = ksteps > kfirst ? (ksteps - kfirst + kstride - 1) / kstride : 0;
@@ -199,18 +206,18 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
   // Operand tiles travel global -> registers -> LDS.  One tile = 512 chunks of 16 bytes, two per
   // thread.  (Keeping the loads of four steps in flight was measured: 188 registers, two waves per
   // SIMD instead of four, every GEMM slower.)
-  bf16x8 ra[1][2], rb[1][2];
+  bf16x8 ra[1][NCH], rb[1][NCH];
   auto gload = [&](int kt, bf16x8* pa, bf16x8* pb) {
-    const int k0 = (kfirst + kt * kstride) * 32;
+    const int k0 = (kfirst + kt * kstride) * KS;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NCH; ++i) {
       const int c = tid + 256 * i;
       bf16x8 z;
 #pragma unroll
       for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.f;
       pa[i] = z; pb[i] = z;
       if (A_KC) {
-        const int row = c >> 2, kc = c & 3;
+        const int row = c / CPR, kc = c % CPR;
         const int gr = m0 + row, gk = k0 + 8 * kc;
         if (gr < g.M && gk < kend) pa[i] = *(const bf16x8*)(opA + (size_t)gr * ldA + gk);
       } else {
@@ -219,7 +226,7 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
         if (gk < kend && gx < g.M && (!split || row_valid(g.rows, gk))) pa[i] = *(const bf16x8*)(opA + (size_t)gk * ldA + gx);
       }
       if (B_KC) {
-        const int row = c >> 2, kc = c & 3;
+        const int row = c / CPR, kc = c % CPR;
         const int gr = n0 + row, gk = k0 + 8 * kc;
         if (gr < g.N && gk < kend) pb[i] = *(const bf16x8*)(opB + (size_t)gr * ldB + gk);
       } else {
@@ -231,11 +238,11 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
   };
   auto sstore = [&](int buf, const bf16x8* pa, const bf16x8* pb) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NCH; ++i) {
       const int c = tid + 256 * i;
-      if (A_KC) *(bf16x8*)&sA(buf)[(c >> 2) * kPitchKC + 8 * (c & 3)] = pa[i];
+      if (A_KC) *(bf16x8*)&sA(buf)[(c / CPR) * kPitchKC + 8 * (c % CPR)] = pa[i];
       else      *(bf16x8*)&sA(buf)[(c >> 4) * 128 + 8 * (c & 15)] = pa[i];
-      if (B_KC) *(bf16x8*)&sB(buf)[(c >> 2) * kPitchKC + 8 * (c & 3)] = pb[i];
+      if (B_KC) *(bf16x8*)&sB(buf)[(c / CPR) * kPitchKC + 8 * (c % CPR)] = pb[i];
       else      *(bf16x8*)&sB(buf)[(c >> 4) * 128 + 8 * (c & 15)] = pb[i];
     }
   };
@@ -257,23 +264,28 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
   // padding (the test is the same for the whole workgroup).
   auto next_step = [&](int kt) {
     if (split)
-      while (kt < nk && !rows_any_valid(g.rows, (kfirst + kt * kstride) * 32, min(kend, (kfirst + kt * kstride) * 32 + 32))) ++kt;
+      while (kt < nk && !rows_any_valid(g.rows, (kfirst + kt * kstride) * KS, min(kend, (kfirst + kt * kstride) * KS + KS))) ++kt;
     return kt;
   };
   int buf = 0;
 #pragma unroll
   for (int ph = 0; ph < NPH; ++ph) {
   f32x16 (&acc)[2][2] = accs[ph];
-  if (DUAL && ph == 1) { opA = g.A2; opB = g.B2; ldA = g.lda2; ldB = g.ldb2; }
   int kt = next_step(0);
-  if (kt < nk) gload(kt, ra[0], rb[0]);
+  if (kt < nk && !(DUAL && ph == 1)) gload(kt, ra[0], rb[0]);   // (the second product's first tile is on its way already)
   while (kt < nk) {
+    if (NBUF == 1) __syncthreads();          // the one buffer is still being read by the step before
     sstore(buf, ra[0], rb[0]);
     const int kn = next_step(kt + 1);
-    if (kn < nk) gload(kn, ra[0], rb[0]);
+    if (kn < nk) {
+      gload(kn, ra[0], rb[0]);
+    } else if (DUAL && ph == 0) {            // last step of the first product: request the second product's first tile
+      opA = g.A2; opB = g.B2; ldA = g.lda2; ldB = g.ldb2;
+      gload(0, ra[0], rb[0]);
+    }
     __syncthreads();
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < KS / 16; ++ks) {
       bf16x8 fa[2], fb[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
@@ -290,7 +302,7 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
         for (int b = 0; b < 2; ++b) accb[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fb[b], accb[b], 0, 0, 0);
       }
     }
-    buf ^= 1;
+    buf ^= NBUF - 1;
     kt = kn;
   }
   }
@@ -304,9 +316,34 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
     }
   }
   float* stage = (float*)smem + w * (32 * kStagePitch);
-  static_assert(4 * 32 * kStagePitch * 4 <= 4 * kTileElems * 2, "staging area fits the operand buffers");
+  static_assert(4 * 32 * kStagePitch * 4 <= 2 * NBUF * kTileElems * 2, "staging area fits the operand buffers");
+  // Loads and stores leave one in-order queue: a load that follows a store is not back before the store
+  // has been acknowledged.  What the epilogue reads from memory is therefore requested ahead of its
+  // stores: the bias chunk once (a thread's chunks all lie in the same eight columns), the residual /
+  // pre-activation rows of a 32-row slab before the slab's first store.
+  const int ecc = lane & 7, en = n0 + 64 * wn + 8 * ecc;
+  float biasv[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) biasv[e] = 0.f;
+  if (g.bias && en < g.N) {
+    const bf16x8 bv = *(const bf16x8*)(g.bias + en);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) biasv[e] = (float)bv[e];
+  }
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
+    f32x4 ld[4][2];                   // EPI_RES_F32: the chunk's residual values; EPI_DACT: its pre-activations (first 16 bytes)
+    if (g.epi == EPI_RES_F32 || g.epi == EPI_DACT) {
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int m = m0 + 64 * wm + 32 * a + it * 8 + (lane >> 3);
+        ld[it][0] = f32x4{0.f, 0.f, 0.f, 0.f}; ld[it][1] = ld[it][0];
+        if (m >= g.M || en >= g.N) continue;
+        const size_t o = (size_t)m * g.ldo + en;
+        if (g.epi == EPI_RES_F32) { ld[it][0] = *(const f32x4*)(g.res + o); ld[it][1] = *(const f32x4*)(g.res + o + 4); }
+        else ld[it][0] = *(const f32x4*)(g.pre + o);
+      }
+    }
     float v2[DUAL ? 4 : 1][8];        // two-product launch: the second product's values of this thread's chunks
     if constexpr (DUAL) {
       __syncthreads();
@@ -336,11 +373,8 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
       float v[8];
       *(f32x4*)&v[0] = *(const f32x4*)&stage[row * kStagePitch + 8 * cc];
       *(f32x4*)&v[4] = *(const f32x4*)&stage[row * kStagePitch + 8 * cc + 4];
-      if (g.bias) {
-        const bf16x8 bv = *(const bf16x8*)(g.bias + n);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += (float)bv[e];
-      }
+      for (int e = 0; e < 8; ++e) v[e] += biasv[e];
       const size_t o = (size_t)m * g.ldo + n;
       bf16x8 ob;
       if (g.epi == EPI_BF16) {
@@ -348,7 +382,7 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
         for (int e = 0; e < 8; ++e) ob[e] = (__bf16)v[e];
         *(bf16x8*)((__bf16*)g.out + o) = ob;
       } else if (g.epi == EPI_RES_F32) {
-        const f32x4 r0 = *(const f32x4*)(g.res + o), r1 = *(const f32x4*)(g.res + o + 4);
+        const f32x4 r0 = ld[it][0], r1 = ld[it][1];
         f32x4 o0, o1;
 #pragma unroll
         for (int e = 0; e < 4; ++e) { o0[e] = r0[e] + v[e]; o1[e] = r1[e] + v[4 + e]; }
@@ -361,7 +395,7 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
         *(bf16x8*)((__bf16*)g.out + o) = ob;
         *(bf16x8*)((__bf16*)g.out2 + o) = oa;
       } else if (g.epi == EPI_DACT) {
-        const bf16x8 pv = *(const bf16x8*)(g.pre + o);
+        const bf16x8 pv = __builtin_bit_cast(bf16x8, ld[it][0]);
 #pragma unroll
         for (int e = 0; e < 8; ++e) ob[e] = (__bf16)(v[e] * act_grad((float)pv[e], g.act));
         *(bf16x8*)((__bf16*)g.out + o) = ob;
@@ -575,14 +609,17 @@ __device__ __forceinline__ bool group_of(const RowGeom& q, int r, GroupOf* g) {
   return pos < len;
 }
 
+// A head's DH features as stored (packed bf16): dot products take them two at a time
+// (v_dot2_f32_bf16: fp32 sum of two bf16 products and the accumulator), sums weighted by a
+// scalar widen them one by one.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+template <int DH> struct HeadVec { bf16x8 c[DH / 8]; };
 template <int DH>
-__device__ __forceinline__ void load_head(const __bf16* p, float* v) {
+__device__ __forceinline__ HeadVec<DH> load_head(const __bf16* p) {
+  HeadVec<DH> v;
 #pragma unroll
-  for (int c = 0; c < DH; c += 8) {
-    const bf16x8 t = *(const bf16x8*)(p + c);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[c + e] = (float)t[e];
-  }
+  for (int c = 0; c < DH / 8; ++c) v.c[c] = *(const bf16x8*)(p + 8 * c);
+  return v;
 }
 template <int DH>
 __device__ __forceinline__ void store_head(__bf16* p, const float* v) {
@@ -595,14 +632,29 @@ __device__ __forceinline__ void store_head(__bf16* p, const float* v) {
   }
 }
 template <int DH>
-__device__ __forceinline__ float dot(const float* a, const float* b) {
+__device__ __forceinline__ float dot(const HeadVec<DH>& a, const HeadVec<DH>& b) {
   float s = 0.f;
 #pragma unroll
-  for (int c = 0; c < DH; ++c) s += a[c] * b[c];
+  for (int c = 0; c < DH / 8; ++c) {
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a.c[c], a.c[c], 0, 1), __builtin_shufflevector(b.c[c], b.c[c], 0, 1), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a.c[c], a.c[c], 2, 3), __builtin_shufflevector(b.c[c], b.c[c], 2, 3), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a.c[c], a.c[c], 4, 5), __builtin_shufflevector(b.c[c], b.c[c], 4, 5), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a.c[c], a.c[c], 6, 7), __builtin_shufflevector(b.c[c], b.c[c], 6, 7), s, false);
+  }
   return s;
 }
-
+// acc[:] += w v[:]
 template <int DH>
+__device__ __forceinline__ void axpy(float* acc, float w, const HeadVec<DH>& v) {
+#pragma unroll
+  for (int c = 0; c < DH / 8; ++c)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[8 * c + e] = fmaf(w, (float)v.c[c][e], acc[8 * c + e]);
+}
+
+// KG: the loops over a group's tokens are unrolled KG times (K <= KG) so that the per-token values
+// stay in registers; tokens past the group's valid count are predicated off.
+template <int DH, int KG>
 __global__ __launch_bounds__(256) void bw_attn_fwd_kernel(const __bf16* qkv, __bf16* o, RowGeom q, int d, int heads) {
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (long long)q.ntok * heads) return;
@@ -613,26 +665,28 @@ __global__ __launch_bounds__(256) void bw_attn_fwd_kernel(const __bf16* qkv, __b
   for (int c = 0; c < DH; ++c) acc[c] = 0.f;
   if (group_of(q, r, &g)) {
     const float scale = rsqrtf((float)DH);
-    float qv[DH], kv[DH], s[kMaxGroup];
-    load_head<DH>(qkv + (size_t)r * 3 * d + h * DH, qv);
+    const HeadVec<DH> qv = load_head<DH>(qkv + (size_t)r * 3 * d + h * DH);
+    const __bf16* kbase = qkv + (size_t)g.first * 3 * d + d + h * DH;
+    float s[KG];
     float mx = -3.0e38f;
-    for (int j = 0; j < g.n; ++j) {
-      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + d + h * DH, kv);
-      s[j] = scale * dot<DH>(qv, kv);
-      mx = fmaxf(mx, s[j]);
+#pragma unroll
+    for (int j = 0; j < KG; ++j) {
+      s[j] = -3.0e38f;
+      if (j < g.n) {
+        s[j] = scale * dot<DH>(qv, load_head<DH>(kbase + (size_t)j * 3 * d));
+        mx = fmaxf(mx, s[j]);
+      }
     }
     float l = 0.f;
-    for (int j = 0; j < g.n; ++j) {
-      s[j] = __expf(s[j] - mx);
+#pragma unroll
+    for (int j = 0; j < KG; ++j) {
+      s[j] = j < g.n ? __expf(s[j] - mx) : 0.f;
       l += s[j];
     }
     const float inv = 1.f / l;
-    for (int j = 0; j < g.n; ++j) {
-      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + 2 * d + h * DH, kv);
-      const float p = s[j] * inv;
 #pragma unroll
-      for (int c = 0; c < DH; ++c) acc[c] += p * kv[c];
-    }
+    for (int j = 0; j < KG; ++j)
+      if (j < g.n) axpy<DH>(acc, s[j] * inv, load_head<DH>(kbase + (size_t)j * 3 * d + d));
   }
   store_head<DH>(o + (size_t)r * d + h * DH, acc);
 }
@@ -640,7 +694,7 @@ __global__ __launch_bounds__(256) void bw_attn_fwd_kernel(const __bf16* qkv, __b
 // Query side of the attention backward: for query row i, P_i. is recomputed, dP_ij = do_i . v_j,
 // D_i = sum_j P_ij dP_ij, dS_ij = P_ij (dP_ij - D_i), dq_i = scale sum_j dS_ij k_j.  Writes dq into
 // dqkv[:, 0:d) and the row's softmax statistics (log-sum-exp of the scaled scores, D_i) into stat.
-template <int DH>
+template <int DH, int KG>
 __global__ __launch_bounds__(256) void bw_attn_bwd_q_kernel(const __bf16* qkv, const __bf16* dob, __bf16* dqkv,
                                                             float2* stat, RowGeom q, int d, int heads) {
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -652,35 +706,33 @@ __global__ __launch_bounds__(256) void bw_attn_bwd_q_kernel(const __bf16* qkv, c
   for (int c = 0; c < DH; ++c) acc[c] = 0.f;
   float2 st = make_float2(0.f, 0.f);
   if (group_of(q, r, &g)) {
-    // one pass over the group's keys with a running maximum: with e_j = exp(s_j - max), l = sum e_j,
-    // dp_j = do . v_j:  D = sum e_j dp_j / l  and  dq = scale (sum e_j dp_j k_j - D sum e_j k_j) / l
     const float scale = rsqrtf((float)DH);
-    float qv[DH], dov[DH], kv[DH], vv[DH], Bv[DH];
+    const HeadVec<DH> qv = load_head<DH>(qkv + (size_t)r * 3 * d + h * DH);
+    const HeadVec<DH> dov = load_head<DH>(dob + (size_t)r * d + h * DH);
+    const __bf16* kbase = qkv + (size_t)g.first * 3 * d + d + h * DH;
+    float s[KG], dp[KG];
+    float mx = -3.0e38f;
 #pragma unroll
-    for (int c = 0; c < DH; ++c) Bv[c] = 0.f;
-    load_head<DH>(qkv + (size_t)r * 3 * d + h * DH, qv);
-    load_head<DH>(dob + (size_t)r * d + h * DH, dov);
-    float mx = -3.0e38f, l = 0.f, Dn = 0.f;
-    for (int j = 0; j < g.n; ++j) {
-      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + d + h * DH, kv);
-      load_head<DH>(qkv + (size_t)(g.first + j) * 3 * d + 2 * d + h * DH, vv);
-      const float sc = scale * dot<DH>(qv, kv);
-      const float mn = fmaxf(mx, sc);
-      const float corr = __expf(mx - mn), e = __expf(sc - mn);
-      const float ed = e * dot<DH>(dov, vv);
-      l = l * corr + e;
-      Dn = Dn * corr + ed;
-#pragma unroll
-      for (int c = 0; c < DH; ++c) {
-        acc[c] = acc[c] * corr + ed * kv[c];
-        Bv[c] = Bv[c] * corr + e * kv[c];
+    for (int j = 0; j < KG; ++j) {
+      s[j] = -3.0e38f; dp[j] = 0.f;
+      if (j < g.n) {
+        s[j] = scale * dot<DH>(qv, load_head<DH>(kbase + (size_t)j * 3 * d));
+        dp[j] = dot<DH>(dov, load_head<DH>(kbase + (size_t)j * 3 * d + d));
+        mx = fmaxf(mx, s[j]);
       }
-      mx = mn;
+    }
+    float l = 0.f, Dn = 0.f;
+#pragma unroll
+    for (int j = 0; j < KG; ++j) {
+      s[j] = j < g.n ? __expf(s[j] - mx) : 0.f;
+      l += s[j];
+      Dn = fmaf(s[j], dp[j], Dn);
     }
     const float inv = 1.f / l;
     const float D = Dn * inv;
 #pragma unroll
-    for (int c = 0; c < DH; ++c) acc[c] = scale * inv * (acc[c] - D * Bv[c]);
+    for (int j = 0; j < KG; ++j)
+      if (j < g.n) axpy<DH>(acc, scale * inv * s[j] * (dp[j] - D), load_head<DH>(kbase + (size_t)j * 3 * d));
     st = make_float2(mx + __logf(l), D);
   }
   store_head<DH>(dqkv + (size_t)r * 3 * d + h * DH, acc);
@@ -689,7 +741,7 @@ __global__ __launch_bounds__(256) void bw_attn_bwd_q_kernel(const __bf16* qkv, c
 
 // Key side: for key row j, over the group's valid queries i: P_ij = exp(s_ij - lse_i),
 // dv_j = sum_i P_ij do_i, dk_j = scale sum_i P_ij (do_i . v_j - D_i) q_i.  Writes dqkv[:, d:3d).
-template <int DH>
+template <int DH, int KG>
 __global__ __launch_bounds__(256) void bw_attn_bwd_kv_kernel(const __bf16* qkv, const __bf16* dob, __bf16* dqkv,
                                                              const float2* stat, RowGeom q, int d, int heads) {
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -701,25 +753,44 @@ __global__ __launch_bounds__(256) void bw_attn_bwd_kv_kernel(const __bf16* qkv, 
   for (int c = 0; c < DH; ++c) { dk[c] = 0.f; dv[c] = 0.f; }
   if (group_of(q, r, &g)) {
     const float scale = rsqrtf((float)DH);
-    float kv[DH], vv[DH], qi[DH], doi[DH];
-    load_head<DH>(qkv + (size_t)r * 3 * d + d + h * DH, kv);
-    load_head<DH>(qkv + (size_t)r * 3 * d + 2 * d + h * DH, vv);
-    for (int i = 0; i < g.n; ++i) {
-      const int ri = g.first + i;
-      load_head<DH>(qkv + (size_t)ri * 3 * d + h * DH, qi);
-      load_head<DH>(dob + (size_t)ri * d + h * DH, doi);
-      const float2 st = stat[(size_t)ri * heads + h];
-      const float p = __expf(scale * dot<DH>(qi, kv) - st.x);
-      const float ds = scale * p * (dot<DH>(doi, vv) - st.y);
+    const HeadVec<DH> kv = load_head<DH>(qkv + (size_t)r * 3 * d + d + h * DH);
+    const HeadVec<DH> vv = load_head<DH>(qkv + (size_t)r * 3 * d + 2 * d + h * DH);
 #pragma unroll
-      for (int c = 0; c < DH; ++c) {
-        dv[c] += p * doi[c];
-        dk[c] += ds * qi[c];
+    for (int i = 0; i < KG; ++i) {
+      if (i < g.n) {
+        const int ri = g.first + i;
+        const HeadVec<DH> qi = load_head<DH>(qkv + (size_t)ri * 3 * d + h * DH);
+        const HeadVec<DH> doi = load_head<DH>(dob + (size_t)ri * d + h * DH);
+        const float2 st = stat[(size_t)ri * heads + h];
+        const float p = __expf(scale * dot<DH>(qi, kv) - st.x);
+        const float ds = scale * p * (dot<DH>(doi, vv) - st.y);
+        axpy<DH>(dv, p, doi);
+        axpy<DH>(dk, ds, qi);
       }
     }
   }
   store_head<DH>(dqkv + (size_t)r * 3 * d + d + h * DH, dk);
   store_head<DH>(dqkv + (size_t)r * 3 * d + 2 * d + h * DH, dv);
+}
+
+// launchers by head width and group size
+template <int DH, int KG>
+static void attn_launch(int which, unsigned grid, hipStream_t st, const __bf16* qkv, const __bf16* dob, __bf16* out, float2* stat,
+                        RowGeom q, int d, int heads) {
+  if (which == 0) bw_attn_fwd_kernel<DH, KG><<<grid, 256, 0, st>>>(qkv, out, q, d, heads);
+  else if (which == 1) bw_attn_bwd_q_kernel<DH, KG><<<grid, 256, 0, st>>>(qkv, dob, out, stat, q, d, heads);
+  else bw_attn_bwd_kv_kernel<DH, KG><<<grid, 256, 0, st>>>(qkv, dob, out, stat, q, d, heads);
+}
+// which: 0 forward (out = o), 1 backward, query side, 2 backward, key side (out = dqkv)
+static void group_attn(int which, int dh, int K, unsigned grid, hipStream_t st, const __bf16* qkv, const __bf16* dob, __bf16* out,
+                       float2* stat, RowGeom q, int d, int heads) {
+#define LONGER_BW_ATTN(DH, KG) attn_launch<DH, KG>(which, grid, st, qkv, dob, out, stat, q, d, heads)
+  if (dh == 16) {
+    if (K <= 4) LONGER_BW_ATTN(16, 4); else if (K <= 8) LONGER_BW_ATTN(16, 8); else if (K <= 16) LONGER_BW_ATTN(16, 16); else LONGER_BW_ATTN(16, 32);
+  } else {
+    if (K <= 4) LONGER_BW_ATTN(32, 4); else if (K <= 8) LONGER_BW_ATTN(32, 8); else if (K <= 16) LONGER_BW_ATTN(32, 16); else LONGER_BW_ATTN(32, 32);
+  }
+#undef LONGER_BW_ATTN
 }
 
 // [wq | wk | wv] side by side: cat[i][j d + c] = w_j[i][c]; biases the same way
@@ -933,25 +1004,24 @@ __global__ __launch_bounds__(256) void bw_set_attn_fwd_kernel(SetAttn a, __bf16*
   float mx = -3.0e38f, l = 0.f;
   if (qd >= 0) {
     const float scale = rsqrtf((float)DH);
-    float qv[DH], kv[DH];
-    load_head<DH>(a.q + (size_t)row * a.qpitch + h * DH, qv);
+    const HeadVec<DH> qv = load_head<DH>(a.q + (size_t)row * a.qpitch + h * DH);
     int lo, hi;
     key_range(a, qd, row - u * a.nq, &lo, &hi);
     // every row of the range is loaded, a hidden key weighs nothing: no branch in the loop, so that the
     // loads of several keys are in flight at once
-    float vv[DH];
 #pragma unroll(DH == 16 ? 4 : 2)
     for (int j = lo + sub; j < hi; j += kSplit) {
       const size_t kr = (size_t)u * a.nk + j;
       const bool vis = visible(qd, a.kdesc[kr], a.gmask);
-      load_head<DH>(a.k + kr * a.kvpitch + h * DH, kv);
-      load_head<DH>(a.v + kr * a.kvpitch + h * DH, vv);
+      const HeadVec<DH> kv = load_head<DH>(a.k + kr * a.kvpitch + h * DH);
+      const HeadVec<DH> vv = load_head<DH>(a.v + kr * a.kvpitch + h * DH);
       const float sc = vis ? scale * dot<DH>(qv, kv) : -3.0e38f;
       const float mn = fmaxf(mx, sc);
       const float corr = __expf(mx - mn), p = vis ? __expf(sc - mn) : 0.f;
       l = l * corr + p;
 #pragma unroll
-      for (int c = 0; c < DH; ++c) acc[c] = acc[c] * corr + p * vv[c];
+      for (int c = 0; c < DH; ++c) acc[c] *= corr;
+      axpy<DH>(acc, p, vv);
       mx = mn;
     }
   }
@@ -984,22 +1054,21 @@ __global__ __launch_bounds__(256) void bw_set_attn_bwd_q_kernel(SetAttn a, const
   const float scale = rsqrtf((float)DH);
   const float lse = stat[(size_t)row * a.heads + h].x;
   if (qd >= 0) {
-    float qv[DH], dov[DH], kv[DH], vv[DH];
-    load_head<DH>(a.q + (size_t)row * a.qpitch + h * DH, qv);
-    load_head<DH>(dob + (size_t)row * d + h * DH, dov);
+    const HeadVec<DH> qv = load_head<DH>(a.q + (size_t)row * a.qpitch + h * DH);
+    const HeadVec<DH> dov = load_head<DH>(dob + (size_t)row * d + h * DH);
     int lo, hi;
     key_range(a, qd, row - u * a.nq, &lo, &hi);
     // (branch-free, unrolled loops as in the forward kernel were slower here: more live registers)
     for (int j = lo + sub; j < hi; j += kSplit) {
       const size_t kr = (size_t)u * a.nk + j;
       if (!visible(qd, a.kdesc[kr], a.gmask)) continue;
-      load_head<DH>(a.k + kr * a.kvpitch + h * DH, kv);
-      load_head<DH>(a.v + kr * a.kvpitch + h * DH, vv);
+      const HeadVec<DH> kv = load_head<DH>(a.k + kr * a.kvpitch + h * DH);
+      const HeadVec<DH> vv = load_head<DH>(a.v + kr * a.kvpitch + h * DH);
       const float p = __expf(scale * dot<DH>(qv, kv) - lse);
       const float pd = p * dot<DH>(dov, vv);
       D += pd;
-#pragma unroll
-      for (int c = 0; c < DH; ++c) { A[c] += pd * kv[c]; Bv[c] += p * kv[c]; }
+      axpy<DH>(A, pd, kv);
+      axpy<DH>(Bv, p, kv);
     }
   }
   D = split_sum(D);
@@ -1027,9 +1096,8 @@ __global__ __launch_bounds__(256) void bw_set_attn_bwd_kv_kernel(SetAttn a, cons
   for (int c = 0; c < DH; ++c) { gk[c] = 0.f; gv[c] = 0.f; }
   if (kd >= 0) {
     const float scale = rsqrtf((float)DH);
-    float kv[DH], vv[DH], qi[DH], doi[DH];
-    load_head<DH>(a.k + (size_t)kr * a.kvpitch + h * DH, kv);
-    load_head<DH>(a.v + (size_t)kr * a.kvpitch + h * DH, vv);
+    const HeadVec<DH> kv = load_head<DH>(a.k + (size_t)kr * a.kvpitch + h * DH);
+    const HeadVec<DH> vv = load_head<DH>(a.v + (size_t)kr * a.kvpitch + h * DH);
     // a sequence key of a self layer is seen by the global rows and by the slots from its own on
     const int own = kr - u * a.nk;
     const int skip_lo = a.m, skip_hi = (a.self && kd >= kSeq) ? max(a.m, own) : a.m;
@@ -1037,13 +1105,13 @@ __global__ __launch_bounds__(256) void bw_set_attn_bwd_kv_kernel(SetAttn a, cons
       const int i = i0 < skip_lo ? i0 : i0 + (skip_hi - skip_lo);      // the rows outside [skip_lo, skip_hi)
       const size_t qr = (size_t)u * a.nq + i;
       if (!visible(a.qdesc[qr], kd, a.gmask)) continue;
-      load_head<DH>(a.q + qr * a.qpitch + h * DH, qi);
-      load_head<DH>(dob + qr * d + h * DH, doi);
+      const HeadVec<DH> qi = load_head<DH>(a.q + qr * a.qpitch + h * DH);
+      const HeadVec<DH> doi = load_head<DH>(dob + qr * d + h * DH);
       const float2 st = stat[qr * a.heads + h];
       const float p = __expf(scale * dot<DH>(qi, kv) - st.x);
       const float ds = scale * p * (dot<DH>(doi, vv) - st.y);
-#pragma unroll
-      for (int c = 0; c < DH; ++c) { gv[c] += p * doi[c]; gk[c] += ds * qi[c]; }
+      axpy<DH>(gv, p, doi);
+      axpy<DH>(gk, ds, qi);
     }
   }
 #pragma unroll
@@ -1471,8 +1539,7 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     ln_fwd(st, ln_grid, d, x, (const __bf16*)b.ln1_g, (const __bf16*)b.ln1_b, n1, (int)nt, c->ln_eps, rv);
     BW_TRY(launched("LayerNorm"));
     BW_TRY(gemm_rows(st, n1, d, wcat(l), 3 * d, nt, EPI_BF16, 0, qkv, nullptr, bcat(l), nullptr, nullptr, 0, rv));
-    if (s.dh == 16) bw_attn_fwd_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, o, q, d, s.heads);
-    else bw_attn_fwd_kernel<32><<<ah_grid, 256, 0, st>>>(qkv, o, q, d, s.heads);
+    group_attn(0, s.dh, s.K, ah_grid, st, qkv, nullptr, o, nullptr, q, d, s.heads);
     BW_TRY(launched("group attention"));
     BW_TRY(gemm_rows(st, o, d, (const __bf16*)b.wo, d, nt, EPI_RES_F32, 0, xmid, nullptr, (const __bf16*)b.bo, x, nullptr, 0, rv));
     ln_fwd(st, ln_grid, d, xmid, (const __bf16*)b.ln2_g, (const __bf16*)b.ln2_b, n2, (int)nt, c->ln_eps, rv);
@@ -1508,13 +1575,8 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     // attention: xmid = x + att W_O + b_O
     BW_TRY(gemm_wgrad(st, o, d, d, dxmb, d, d, nt, part, bpart, g + gl.wo, g + gl.bo, rv));
     BW_TRY(gemm_rows_t(st, dxmb, d, (const __bf16*)b.wo, d, nt, EPI_BF16, 0, dob, nullptr, 0, rv));
-    if (s.dh == 16) {
-      bw_attn_bwd_q_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
-      bw_attn_bwd_kv_kernel<16><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
-    } else {
-      bw_attn_bwd_q_kernel<32><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
-      bw_attn_bwd_kv_kernel<32><<<ah_grid, 256, 0, st>>>(qkv, dob, dqkv, stat, q, d, s.heads);
-    }
+    group_attn(1, s.dh, s.K, ah_grid, st, qkv, dob, dqkv, stat, q, d, s.heads);
+    group_attn(2, s.dh, s.K, ah_grid, st, qkv, dob, dqkv, stat, q, d, s.heads);
     BW_TRY(launched("group attention backward"));
     const size_t wofs[3] = {gl.wq, gl.wk, gl.wv}, bofs[3] = {gl.bq, gl.bk, gl.bv};
     for (int j = 0; j < 3; ++j) {

@@ -75,8 +75,9 @@ def merge_backward_work(cfg, lens: Optional[Sequence[int]] = None, B: Optional[i
     valid tokens.  ``recompute_flops``: the forward products that are computed again (the chain of
     block inputs: all blocks but the last; then every block's intermediates, without its second
     FFN product).  ``hbm_bytes``: what the pass's kernels read and write when every tensor makes one
-    trip per use.  Per valid token and block 40 w + 4 f bytes for the recomputed intermediates and
-    90 w + 10 f for the gradients, 6 w for every block input that the fused forward kernel recomputes (it
+    trip per use.  Per valid token and block 38 w bytes for the recomputed intermediates (up to the
+    FFN's input; the hidden pre-activation is formed again inside the launch that takes its gradient and
+    never stored) and 92 w + 10 f for the gradients, 6 w for every block input that the fused forward kernel recomputes (it
     reads the raw tokens and writes fp32 rows), 12 w once for the input copy and the merge gradient.  A
     padded token is never read; it costs the zeros written for it: 16 w per block (two LayerNorm outputs,
     two LayerNorm gradients with their bf16 copies), 4 w per recomputed block input, 10 w once."""
@@ -91,7 +92,7 @@ def merge_backward_work(cfg, lens: Optional[Sequence[int]] = None, B: Optional[i
     valid = sum(lens_)
     per_block = inner // max(n, 1)
     recompute = (n - 1) * per_block + n * (per_block - ffn2 * valid)
-    per_token = (n - 1) * 6 * w + n * (40 * w + 4 * f) + n * (90 * w + 10 * f) + 12 * w
+    per_token = (n - 1) * 6 * w + n * 38 * w + n * (92 * w + 10 * f) + 12 * w
     per_padded = (n - 1) * 4 * w + n * 16 * w + 10 * w
     return {"gradient_flops": 2 * inner, "recompute_flops": recompute,
             "hbm_bytes": per_token * valid + per_padded * (B * L - valid)}

@@ -40,10 +40,10 @@ def test_backward_work_tally_by_hand_at_the_headline_shape():
     assert w["gradient_flops"] == 2 * 2 * block
     # recomputed: block 0 in full (the chain of block inputs), then both blocks without the second FFN product
     assert w["recompute_flops"] == block + 2 * (block - tokens * 2 * 128 * 512)
-    # bytes per token: 6 w for block 1's input, per block 40 w + 4 f recomputed and 90 w + 10 f of gradients, 12 w once
-    assert w["hbm_bytes"] == tokens * (6 * 128 + 2 * (40 * 128 + 4 * 512) + 2 * (90 * 128 + 10 * 512) + 12 * 128)
+    # bytes per token: 6 w for block 1's input, per block 38 w recomputed and 92 w + 10 f of gradients, 12 w once
+    assert w["hbm_bytes"] == tokens * (6 * 128 + 2 * 38 * 128 + 2 * (92 * 128 + 10 * 512) + 12 * 128)
     # a ragged batch: FLOPs and bytes follow the valid tokens; a padded token costs the zeros written for it
     c = synth.CONFIGS["C2"].replace(B=3)                 # width 64, FFN width 256, one block
     r = flops.merge_backward_work(c, [0, 100, 512])
     assert r["gradient_flops"] == 2 * flops.forward_flops(c, [0, 100, 512])["inner"]
-    assert r["hbm_bytes"] == 612 * ((40 * 64 + 4 * 256) + (90 * 64 + 10 * 256) + 12 * 64) + (3 * 512 - 612) * (16 * 64 + 10 * 64)
+    assert r["hbm_bytes"] == 612 * (38 * 64 + (92 * 64 + 10 * 256) + 12 * 64) + (3 * 512 - 612) * (16 * 64 + 10 * 64)
