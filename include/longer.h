@@ -254,7 +254,8 @@ const char* longer_last_error(void);
  * recomputes the chain of InnerTrans block inputs, then, block by block from the last to the
  * first, the block's intermediates) and mixed precision (bf16 matrix-core operands and stored
  * activations, fp32 accumulation, residual stream, LayerNorm / softmax statistics and parameter
- * gradients).  The function differentiated is longer_token_merge with exact-erf GELU (or ReLU).
+ * gradients).  The function differentiated is longer_token_merge with exact-erf GELU (or ReLU); the
+ * pass evaluates GELU and its derivative to 1.3e-3 absolute, below the bf16 step of the values it stores.
  *   H [B, L, w] raw tokens and the InnerTrans blocks `inner` as for longer_token_merge, in bf16
  *     (cfg->dtype must be LONGER_BF16); w = d, or d / K for LONGER_MERGE_CONCAT;
  *   dM [B, T, d] fp32: gradient of the loss (Eq. 2) with respect to the merged tokens; entries of

@@ -1,6 +1,7 @@
 // Backward pass with activation recomputation and mixed precision (Section 3.6.2):
 // longer_token_merge_backward (the token merge of Section 3.4 alone), longer_forward_backward
-// (the whole model: loss of Eq. 1-2 and the gradient of every input and parameter) and their
+// (the whole model: loss of Eq. 1-2 and the gradient of every input and parameter),
+// longer_input_generation_backward (the stage of Section 3.5.1 in front of the merge) and their
 // size queries.
 //
 // Token merge: nothing is kept from a forward call.  The pass reads the raw tokens H, gets every
@@ -20,12 +21,14 @@
 //   * one bf16 MFMA GEMM (bw_gemm_kernel) whose operands may each be stored with the
 //     contraction index contiguous or strided, which covers y = x W (+ epilogues),
 //     dx = dy W^T and dW = x^T dy (the tokens dealt to slices whose partial results a second
-//     kernel sums; the bias gradient, a column sum, rides along as one more product with ones);
+//     kernel sums; the bias gradient, a column sum, rides along as one more product with ones),
+//     and the middle of the merge's FFN backward as two products under one epilogue (the hidden
+//     pre-activation is formed again there and never stored);
 //   * row kernels: LayerNorm forward / backward (+ gain / shift gradients), the merge's
 //     backward, the reduced stack's row build, masks, head and loss, gradient routing;
-//   * attention, forward and backward, one thread per (row, head) in plain fp32 code: inside a
-//     group of K tokens (InnerTrans: K x K scores per head), and over a user's own rows under
-//     the mask of Eq. 8 (reduced stack).
+//   * attention, forward and backward, one thread per (row, head), heads kept as packed bf16
+//     (two-feature dot products, fp32 sums): inside a group of K tokens (InnerTrans: K x K scores
+//     per head), and over a user's own rows under the mask of Eq. 8 (reduced stack).
 // Padded token rows are never read and cost only the zeros written for them.
 #include "../../include/longer.h"
 #include "device.h"
