@@ -97,6 +97,7 @@ struct GemmArgs {
   void* out; void* out2; int ldo;
   const __bf16* bias; const float* res; const __bf16* pre;
   const __bf16* A2; const __bf16* B2; int lda2, ldb2;   // the second product of a two-product launch (EPI_FFN_MID)
+  int pstride, pstride2;      // EPI_PARTIAL: floats from one slice's partial result to the next (matrix, bias)
 };
 
 // Phi(v) = (1 + erf(v / sqrt 2)) / 2 and exp(-v^2 / 2) from one exponential: for z >= 0,
@@ -315,7 +316,7 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       const int n = n0 + 64 * wn + 32 * b + l32;
-      if (n < g.N) ((float*)g.out2)[(size_t)outer * g.N + n] = accb[b][0];     // row 0 of the ones product
+      if (n < g.N) ((float*)g.out2)[(size_t)outer * g.pstride2 + n] = accb[b][0];     // row 0 of the ones product
     }
   }
   float* stage = (float*)smem + w * (32 * kStagePitch);
@@ -417,7 +418,7 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
         *(f32x4*)((float*)g.out + o) = *(const f32x4*)&v[0];
         *(f32x4*)((float*)g.out + o + 4) = *(const f32x4*)&v[4];
       } else {
-        float* po = (float*)g.out + (size_t)outer * g.M * g.N + o;
+        float* po = (float*)g.out + (size_t)outer * g.pstride + o;
         *(f32x4*)po = *(const f32x4*)&v[0];
         *(f32x4*)(po + 4) = *(const f32x4*)&v[4];
       }
@@ -1462,9 +1463,17 @@ static int gemm_wgrad(hipStream_t st, const __bf16* x, int lda, int m, const __b
   if (splits > most) splits = most;
   const int steps = (int)((ntok + 31) / 32);
   if (splits > steps) splits = steps;
-  g.epi = EPI_PARTIAL; g.out = part; g.out2 = bpart; g.ldo = n;
+  g.epi = EPI_PARTIAL; g.out = part; g.ldo = n;
+  // The bias gradient follows its matrix in every gradient buffer, and `bpart` follows `part` in every
+  // workspace: a slice's bias partial then goes right behind its matrix partial, and one reduction
+  // launch sums both.
+  const bool together = db == dW + (size_t)m * n && bpart == part + kPartialBytes / 4;
+  g.pstride = together ? m * n + n : m * n;
+  g.pstride2 = together ? m * n + n : n;
+  g.out2 = together ? part + (size_t)m * n : bpart;
   int rc = gemm(st, false, false, g, splits);
   if (rc) return rc;
+  if (together) return reduce(st, part, splits, m * n + n, dW);
   rc = reduce(st, part, splits, m * n, dW);
   if (rc) return rc;
   return reduce(st, bpart, splits, n, db);
