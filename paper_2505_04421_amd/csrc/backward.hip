@@ -44,6 +44,7 @@ int inner_chain_f32(const longer_config* cfg, const longer_block* inner, int lay
 namespace bw {
 
 constexpr int kMaxGroup = 32;   // K <= 32
+constexpr int kComputeUnits = 256;
 
 // ------------------------------------------------------------------------------------
 // GEMM  C[M, N] = A[M, Kc] B[Kc, N]  (bf16 operands, fp32 accumulation)
@@ -423,6 +424,187 @@ __global__ __launch_bounds__(256, DUAL ? 2 : (A_KC ? 4 : 3)) void bw_gemm_kernel
         *(f32x4*)(po + 4) = *(const f32x4*)&v[4];
       }
     }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Row GEMM with a short contraction (Kc = K <= 128, the model width): y = x W (+ epilogue) or dx = dy W^T,
+// both operands with the contraction index contiguous (the caller hands W transposed where needed).
+// With so short a contraction a tile per workgroup spends its time on the way from L2 to the compute unit:
+// the weights tile weighs as much as the activation tile and is fetched again by every workgroup, and a
+// step's loads are not back before the previous step's few MFMAs are done.  Here a workgroup stays: it
+// loads its 128 columns of W (both matrices of the two-product launch) into LDS once, then walks over
+// row tiles; the next row tile's activations travel to registers while the current one is multiplied
+// and stored.  512 threads: wave w works on rows 32 (w & 3) .. + 31, columns 64 (w >> 2) .. + 63 of
+// the 128 x 128 tile; the epilogue turns a wave's result through LDS for 16-byte stores.
+// Epilogues: EPI_BF16, EPI_RES_F32, EPI_F32, and with DUAL EPI_FFN_MID.
+template <int K, bool DUAL>
+__global__ __launch_bounds__(512, 1) void bw_rowgemm_kernel(GemmArgs g, int P) {
+  constexpr int PITCH = K + 8, TILE = 128 * PITCH, NPH = DUAL ? 2 : 1, CPR = K / 8;
+  constexpr int NCH = (128 * CPR + 511) / 512;              // 16-byte chunks per thread and operand tile
+  constexpr int STAGE_BYTES = 8 * 32 * kStagePitch * 4;
+  constexpr int A_BYTES = NPH * TILE * 2 > STAGE_BYTES ? NPH * TILE * 2 : STAGE_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem_a[A_BYTES];   // activation tile(s); the epilogue's staging area
+  __shared__ __attribute__((aligned(16))) __bf16 sB[NPH * TILE];           // weights, resident
+  __bf16* sA = (__bf16*)smem_a;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int wm = w & 3, wn = w >> 2, hi = lane >> 5, l32 = lane & 31;
+  float* stage = (float*)smem_a + w * (32 * kStagePitch);
+  const int ntn = (g.N + 127) / 128, ntm = (g.M + 127) / 128;
+  // workgroups of one row-tile sequence (they read the same activations) sit on one die
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int p = (slot / ntn) * 8 + xcd, nt_ = slot % ntn;
+  if (p >= P) return;
+  const int n0 = nt_ * 128;
+
+  const __bf16* opA[2] = {g.A, DUAL ? g.A2 : g.A};
+  const __bf16* opB[2] = {g.B, DUAL ? g.B2 : g.B};
+  const int ldA[2] = {g.lda, DUAL ? g.lda2 : g.lda}, ldB[2] = {g.ldb, DUAL ? g.ldb2 : g.ldb};
+
+#pragma unroll
+  for (int ph = 0; ph < NPH; ++ph)
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + 512 * i;
+      if (c >= 128 * CPR) continue;
+      const int row = c / CPR, kc = c % CPR, gr = n0 + row;
+      bf16x8 v;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.f;
+      if (gr < g.N) v = *(const bf16x8*)(opB[ph] + (size_t)gr * ldB[ph] + 8 * kc);
+      *(bf16x8*)&sB[ph * TILE + row * PITCH + 8 * kc] = v;
+    }
+  const int ecc = lane & 7, en = n0 + 64 * wn + 8 * ecc;
+  float biasv[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) biasv[e] = 0.f;
+  if (g.bias && en < g.N) {
+    const bf16x8 bv = *(const bf16x8*)(g.bias + en);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) biasv[e] = (float)bv[e];
+  }
+
+  bf16x8 ra[NPH][NCH];
+  auto gload = [&](int mt) {
+#pragma unroll
+    for (int ph = 0; ph < NPH; ++ph)
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = tid + 512 * i;
+        bf16x8 v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.f;
+        const int row = c / CPR, kc = c % CPR, gr = mt * 128 + row;
+        if (c < 128 * CPR && gr < g.M) v = *(const bf16x8*)(opA[ph] + (size_t)gr * ldA[ph] + 8 * kc);
+        ra[ph][i] = v;
+      }
+  };
+  auto next_tile = [&](int mt) {      // row tiles without a valid row are passed over: nobody reads their result
+    while (mt < ntm && !rows_any_valid(g.rows, mt * 128, min(g.M, mt * 128 + 128))) mt += P;
+    return mt;
+  };
+  auto frag = [&](const __bf16* s_, int x, int ks) -> bf16x8 { return *(const bf16x8*)&s_[x * PITCH + 16 * ks + 8 * hi]; };
+
+  int mt = next_tile(p);
+  if (mt < ntm) gload(mt);
+  while (mt < ntm) {
+    __syncthreads();                  // the staging area of the tile before is read out (and, first time, sB is written)
+#pragma unroll
+    for (int ph = 0; ph < NPH; ++ph)
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = tid + 512 * i;
+        if (c < 128 * CPR) *(bf16x8*)&sA[ph * TILE + (c / CPR) * PITCH + 8 * (c % CPR)] = ra[ph][i];
+      }
+    const int mn = next_tile(mt + P);
+    if (mn < ntm) gload(mn);          // on its way during the products and the epilogue below
+    __syncthreads();
+    f32x16 acc[NPH][2];
+#pragma unroll
+    for (int ph = 0; ph < NPH; ++ph)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[ph][t][r] = 0.f;
+#pragma unroll
+    for (int ph = 0; ph < NPH; ++ph)
+#pragma unroll
+      for (int ks = 0; ks < K / 16; ++ks) {
+        const bf16x8 fa = frag(sA + ph * TILE, 32 * wm + l32, ks);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          acc[ph][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, frag(sB + ph * TILE, 64 * wn + 32 * t + l32, ks), acc[ph][t], 0, 0, 0);
+      }
+    __syncthreads();                  // every wave is done with the activation tile: its place becomes the staging area
+
+    const int m0 = mt * 128 + 32 * wm;
+    f32x4 ld[4][2];                   // EPI_RES_F32: the chunks' residual values, requested ahead of the stores
+    if (g.epi == EPI_RES_F32) {
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int m = m0 + it * 8 + (lane >> 3);
+        ld[it][0] = f32x4{0.f, 0.f, 0.f, 0.f}; ld[it][1] = ld[it][0];
+        if (m >= g.M || en >= g.N) continue;
+        const size_t o = (size_t)m * g.ldo + en;
+        ld[it][0] = *(const f32x4*)(g.res + o); ld[it][1] = *(const f32x4*)(g.res + o + 4);
+      }
+    }
+    float v2[DUAL ? 4 : 1][8];
+    if constexpr (DUAL) {             // (a wave's staging area is its own: LDS keeps a wave's accesses in order)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) stage[tile_row(r, hi) * kStagePitch + 32 * t + l32] = acc[1][t][r];
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int id = it * 64 + lane, row = id >> 3, cc = id & 7;
+        *(f32x4*)&v2[it][0] = *(const f32x4*)&stage[row * kStagePitch + 8 * cc];
+        *(f32x4*)&v2[it][4] = *(const f32x4*)&stage[row * kStagePitch + 8 * cc + 4];
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) stage[tile_row(r, hi) * kStagePitch + 32 * t + l32] = acc[0][t][r];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int id = it * 64 + lane, row = id >> 3, cc = id & 7;
+      const int m = m0 + row, n = n0 + 64 * wn + 8 * cc;
+      float v[8];
+      *(f32x4*)&v[0] = *(const f32x4*)&stage[row * kStagePitch + 8 * cc];
+      *(f32x4*)&v[4] = *(const f32x4*)&stage[row * kStagePitch + 8 * cc + 4];
+      if (m >= g.M || n >= g.N) continue;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += biasv[e];
+      const size_t o = (size_t)m * g.ldo + n;
+      bf16x8 ob;
+      if (DUAL) {
+        bf16x8 oa;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float av, dv;
+          act_both(v[e], g.act, &av, &dv);
+          oa[e] = (__bf16)av;
+          ob[e] = (__bf16)(v2[DUAL ? it : 0][e] * dv);
+        }
+        *(bf16x8*)((__bf16*)g.out + o) = ob;
+        *(bf16x8*)((__bf16*)g.out2 + o) = oa;
+      } else if (g.epi == EPI_BF16) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ob[e] = (__bf16)v[e];
+        *(bf16x8*)((__bf16*)g.out + o) = ob;
+      } else if (g.epi == EPI_RES_F32) {
+        f32x4 o0, o1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { o0[e] = ld[it][0][e] + v[e]; o1[e] = ld[it][1][e] + v[4 + e]; }
+        *(f32x4*)((float*)g.out + o) = o0;
+        *(f32x4*)((float*)g.out + o + 4) = o1;
+      } else {
+        *(f32x4*)((float*)g.out + o) = *(const f32x4*)&v[0];
+        *(f32x4*)((float*)g.out + o + 4) = *(const f32x4*)&v[4];
+      }
+    }
+    mt = mn;
   }
 }
 
@@ -1303,7 +1485,7 @@ constexpr size_t kPartialBytes = (size_t)kMaxPartials * 128 * 128 * 4;
 struct Workspace {
   size_t wcat, bcat;                       // per layer: [d][3d] bf16, [3d] bf16
   size_t xin;                              // per layer: fp32 [ntok][d]
-  size_t w1t;                              // per layer: W1 transposed, [f][d] bf16
+  size_t w1t, wcatt, wot;                  // per layer, transposed: W1 [f][d], [wq | wk | wv] [3d][d], W_O [d][d] (bf16)
   size_t n1, qkv, o, xmid, n2, a;          // one block's recomputed intermediates
   size_t dy, dyb, dh, dn, dxm, dxmb, dob, dqkv, stat;
   size_t part, bpart;                      // partial parameter gradients of one split GEMM (matrix, bias)
@@ -1317,6 +1499,8 @@ static Workspace workspace(int layers, size_t ntok, int d, int f, int heads, siz
   w.wcat = take((size_t)layers * d * 3 * d * 2);
   w.bcat = take((size_t)layers * up256((size_t)3 * d * 2));
   w.w1t = take((size_t)layers * d * f * 2);
+  w.wcatt = take((size_t)layers * d * 3 * d * 2);
+  w.wot = take((size_t)layers * d * d * 2);
   w.xin = take((size_t)layers * ntok * d * 4);
   w.n1 = take(ntok * d * 2);
   w.qkv = take(ntok * 3 * d * 2);
@@ -1403,6 +1587,21 @@ static int gemm(hipStream_t st, bool a_kc, bool b_kc, GemmArgs g, int splits) {
   g.nsplit = splits;
   const int outer = g.epi == EPI_PARTIAL ? splits : ntm, inner = g.epi == EPI_PARTIAL ? ntm * ntn : ntn;
   dim3 grid((unsigned)(((outer + 7) / 8) * 8 * inner));            // see the tile order in the kernel
+  if (a_kc && b_kc && splits == 1 && (g.Kc == 32 || g.Kc == 64 || g.Kc == 128) &&
+      (g.epi == EPI_FFN_MID || g.epi == EPI_BF16 || g.epi == EPI_RES_F32 || g.epi == EPI_F32)) {
+    if (g.epi == EPI_FFN_MID && (!aligned16(g.A2) || !aligned16(g.B2) || g.lda2 % 8 || g.ldb2 % 8))
+      return api_error(LONGER_ERR_ARG, "backward GEMM operand misaligned");
+    // one workgroup per compute unit, each walking over row tiles for its 128 columns
+    int P = (kComputeUnits / ntn) / 8 * 8;
+    if (P < 8) P = 8;
+    if (P > ((ntm + 7) / 8) * 8) P = ((ntm + 7) / 8) * 8;
+    dim3 pg((unsigned)(P * ntn));
+    const bool dual = g.epi == EPI_FFN_MID;
+#define LONGER_ROWGEMM(KK) (dual ? bw_rowgemm_kernel<KK, true><<<pg, 512, 0, st>>>(g, P) : bw_rowgemm_kernel<KK, false><<<pg, 512, 0, st>>>(g, P))
+    if (g.Kc == 128) LONGER_ROWGEMM(128); else if (g.Kc == 64) LONGER_ROWGEMM(64); else LONGER_ROWGEMM(32);
+#undef LONGER_ROWGEMM
+    return launched("backward row GEMM");
+  }
   if (g.epi == EPI_FFN_MID) {
     if (!(a_kc && b_kc) || !aligned16(g.A2) || !aligned16(g.B2) || g.lda2 % 8 || g.ldb2 % 8)
       return api_error(LONGER_ERR_ARG, "backward GEMM operand misaligned");
@@ -1424,6 +1623,15 @@ static int gemm_rows(hipStream_t st, const __bf16* x, int kc, const __bf16* W, i
   g.A = x; g.lda = kc; g.B = W; g.ldb = ldb ? ldb : n; g.M = (int)ntok; g.N = n; g.Kc = kc;
   g.epi = epi; g.act = act; g.out = out; g.out2 = out2; g.ldo = n; g.bias = bias; g.res = res; g.pre = pre;
   return gemm(st, true, false, g, 1);
+}
+// y = x W (+ epilogue) with W handed over transposed, wt [n][kc]: both operands contraction-contiguous
+static int gemm_rows_wt(hipStream_t st, const __bf16* x, int kc, const __bf16* wt, int n, size_t ntok, int epi,
+                        void* out, const __bf16* bias, const float* res, RowsValid rows) {
+  GemmArgs g = {};
+  g.rows = rows;
+  g.A = x; g.lda = kc; g.B = wt; g.ldb = kc; g.M = (int)ntok; g.N = n; g.Kc = kc;
+  g.epi = epi; g.out = out; g.ldo = n; g.bias = bias; g.res = res;
+  return gemm(st, true, true, g, 1);
 }
 // dx = dy W^T: dy [ntok][kc], W [n][.. kc columns, pitch ldb] row-major (the forward's [in = n][out = kc])
 static int gemm_rows_t(hipStream_t st, const __bf16* dy, int kc, const __bf16* W, int n, size_t ntok, int epi, int act,
@@ -1523,6 +1731,8 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
   __bf16* n1 = (__bf16*)(ws + w.n1);   __bf16* qkv = (__bf16*)(ws + w.qkv); __bf16* o = (__bf16*)(ws + w.o);
   float* xmid = (float*)(ws + w.xmid); __bf16* n2 = (__bf16*)(ws + w.n2);
   auto w1t = [&](int l) { return (__bf16*)(ws + w.w1t) + (size_t)l * d * f; };
+  auto wcatt = [&](int l) { return (__bf16*)(ws + w.wcatt) + (size_t)l * d * 3 * d; };
+  auto wot = [&](int l) { return (__bf16*)(ws + w.wot) + (size_t)l * d * d; };
   __bf16* a = (__bf16*)(ws + w.a);     float* dy = (float*)(ws + w.dy);     __bf16* dyb = (__bf16*)(ws + w.dyb);
   __bf16* dh = (__bf16*)(ws + w.dh);   __bf16* dn = (__bf16*)(ws + w.dn);   float* dxm = (float*)(ws + w.dxm);
   __bf16* dxmb = (__bf16*)(ws + w.dxmb); __bf16* dob = (__bf16*)(ws + w.dob); __bf16* dqkv = (__bf16*)(ws + w.dqkv);
@@ -1540,6 +1750,8 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
                                              (const __bf16*)b.bk, (const __bf16*)b.bv, wcat(l), bcat(l), d);
     BW_TRY(launched("weight concatenation"));
     BW_TRY(transpose(st, (const __bf16*)b.w1, w1t(l), d, f));
+    BW_TRY(transpose(st, wcat(l), wcatt(l), d, 3 * d));
+    BW_TRY(transpose(st, (const __bf16*)b.wo, wot(l), d, d));
   }
   bw_load_x0_kernel<<<flat_grid(nt * d / 4), 256, 0, st>>>((const __bf16*)H, xin(0), q, d);
   BW_TRY(launched("input load"));
@@ -1550,10 +1762,10 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     const float* x = xin(l);
     ln_fwd(st, ln_grid, d, x, (const __bf16*)b.ln1_g, (const __bf16*)b.ln1_b, n1, (int)nt, c->ln_eps, rv);
     BW_TRY(launched("LayerNorm"));
-    BW_TRY(gemm_rows(st, n1, d, wcat(l), 3 * d, nt, EPI_BF16, 0, qkv, nullptr, bcat(l), nullptr, nullptr, 0, rv));
+    BW_TRY(gemm_rows_wt(st, n1, d, wcatt(l), 3 * d, nt, EPI_BF16, qkv, bcat(l), nullptr, rv));
     group_attn(0, s.dh, s.K, ah_grid, st, qkv, nullptr, o, nullptr, q, d, s.heads);
     BW_TRY(launched("group attention"));
-    BW_TRY(gemm_rows(st, o, d, (const __bf16*)b.wo, d, nt, EPI_RES_F32, 0, xmid, nullptr, (const __bf16*)b.bo, x, nullptr, 0, rv));
+    BW_TRY(gemm_rows_wt(st, o, d, wot(l), d, nt, EPI_RES_F32, xmid, (const __bf16*)b.bo, x, rv));
     ln_fwd(st, ln_grid, d, xmid, (const __bf16*)b.ln2_g, (const __bf16*)b.ln2_b, n2, (int)nt, c->ln_eps, rv);
     return launched("LayerNorm");
   };
