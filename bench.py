@@ -141,7 +141,7 @@ def run_merge_backward(lg, torch, cfg, case, steps):
             "roofline": {"bound": "hbm", "achieved": work["hbm_bytes"] / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
                          "frac": work["hbm_bytes"] / (ms * 1e-3) / 1e9 / 8000.0,
                          "bytes_per_step": work["hbm_bytes"],
-                         "traffic": 24.78e9 if cfg.name == "C3" else None,
+                         "traffic": 24.63e9 if cfg.name == "C3" else None,
                          "traffic_source": "profiles/merge_backward_c3_hbm_traffic.md" if cfg.name == "C3" else None,
                          "note": "chain of whole-batch kernels: every stored activation makes one trip through memory per use (tally in "
                                  "paper_2505_04421_amd/flops.py)"},
