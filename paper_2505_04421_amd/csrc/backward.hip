@@ -1308,6 +1308,155 @@ __global__ __launch_bounds__(256) void bw_set_attn_bwd_kv_kernel(SetAttn a, cons
   }
 }
 
+// The same three kernels with one workgroup per (user, head): the rows every thread of the loop reads
+// (the user's keys and values; for the key side its queries, output gradients and their statistics)
+// are copied to LDS once, together with their descriptors, and the loops read them from there (all
+// lanes the same address: a broadcast).  One thread per query row (key row), strided by the workgroup.
+// Dynamic LDS: n rows x (2 DH bf16 + extras), see set_attn_lds_bytes.
+template <int DH>
+__device__ __forceinline__ HeadVec<DH> lds_head(const uint4* s, int row) {
+  HeadVec<DH> v;
+#pragma unroll
+  for (int c = 0; c < DH / 8; ++c) v.c[c] = __builtin_bit_cast(bf16x8, s[row * (DH / 8) + c]);
+  return v;
+}
+template <int DH>
+__device__ __forceinline__ void stage_heads(uint4* dst, const __bf16* src, size_t pitch, int n, int h) {
+  constexpr int CP = DH / 8;
+  for (int c = threadIdx.x; c < n * CP; c += blockDim.x)
+    dst[c] = *(const uint4*)(src + (size_t)(c / CP) * pitch + h * DH + 8 * (c % CP));
+}
+
+template <int DH>
+__global__ __launch_bounds__(512) void bw_set_attn_fwd_lds_kernel(SetAttn a, __bf16* __restrict__ o, int d, float2* __restrict__ stat) {
+  extern __shared__ uint4 sm[];
+  uint4* sK = sm; uint4* sV = sm + (size_t)a.nk * (DH / 8);
+  int* sD = (int*)(sV + (size_t)a.nk * (DH / 8));
+  const int u = blockIdx.x / a.heads, h = blockIdx.x - u * a.heads;
+  stage_heads<DH>(sK, a.k + (size_t)u * a.nk * a.kvpitch, a.kvpitch, a.nk, h);
+  stage_heads<DH>(sV, a.v + (size_t)u * a.nk * a.kvpitch, a.kvpitch, a.nk, h);
+  for (int j = threadIdx.x; j < a.nk; j += blockDim.x) sD[j] = a.kdesc[(size_t)u * a.nk + j];
+  __syncthreads();
+  const float scale = rsqrtf((float)DH);
+  for (int i = threadIdx.x; i < a.nq; i += blockDim.x) {
+    const size_t row = (size_t)u * a.nq + i;
+    const int qd = a.qdesc[row];
+    float acc[DH];
+#pragma unroll
+    for (int c = 0; c < DH; ++c) acc[c] = 0.f;
+    float mx = -3.0e38f, l = 0.f;
+    if (qd >= 0) {
+      const HeadVec<DH> qv = load_head<DH>(a.q + row * a.qpitch + h * DH);
+      int lo, hi;
+      key_range(a, qd, i, &lo, &hi);
+#pragma unroll 2
+      for (int j = lo; j < hi; ++j) {
+        const bool vis = visible(qd, sD[j], a.gmask);
+        const float sc = vis ? scale * dot<DH>(qv, lds_head<DH>(sK, j)) : -3.0e38f;
+        const float mn = fmaxf(mx, sc);
+        const float corr = __expf(mx - mn), p = vis ? __expf(sc - mn) : 0.f;
+        l = l * corr + p;
+#pragma unroll
+        for (int c = 0; c < DH; ++c) acc[c] *= corr;
+        axpy<DH>(acc, p, lds_head<DH>(sV, j));
+        mx = mn;
+      }
+    }
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+#pragma unroll
+    for (int c = 0; c < DH; ++c) acc[c] *= inv;
+    store_head<DH>(o + row * d + h * DH, acc);
+    stat[row * a.heads + h] = make_float2(l > 0.f ? mx + __logf(l) : 0.f, 0.f);
+  }
+}
+
+template <int DH>
+__global__ __launch_bounds__(512) void bw_set_attn_bwd_q_lds_kernel(SetAttn a, const __bf16* __restrict__ dob, int d,
+                                                                    __bf16* __restrict__ dq, int dqpitch, float2* __restrict__ stat) {
+  extern __shared__ uint4 sm[];
+  uint4* sK = sm; uint4* sV = sm + (size_t)a.nk * (DH / 8);
+  int* sD = (int*)(sV + (size_t)a.nk * (DH / 8));
+  const int u = blockIdx.x / a.heads, h = blockIdx.x - u * a.heads;
+  stage_heads<DH>(sK, a.k + (size_t)u * a.nk * a.kvpitch, a.kvpitch, a.nk, h);
+  stage_heads<DH>(sV, a.v + (size_t)u * a.nk * a.kvpitch, a.kvpitch, a.nk, h);
+  for (int j = threadIdx.x; j < a.nk; j += blockDim.x) sD[j] = a.kdesc[(size_t)u * a.nk + j];
+  __syncthreads();
+  const float scale = rsqrtf((float)DH);
+  for (int i = threadIdx.x; i < a.nq; i += blockDim.x) {
+    const size_t row = (size_t)u * a.nq + i;
+    const int qd = a.qdesc[row];
+    float A[DH], Bv[DH];
+#pragma unroll
+    for (int c = 0; c < DH; ++c) { A[c] = 0.f; Bv[c] = 0.f; }
+    float D = 0.f;
+    const float lse = stat[row * a.heads + h].x;
+    if (qd >= 0) {
+      const HeadVec<DH> qv = load_head<DH>(a.q + row * a.qpitch + h * DH);
+      const HeadVec<DH> dov = load_head<DH>(dob + row * d + h * DH);
+      int lo, hi;
+      key_range(a, qd, i, &lo, &hi);
+      for (int j = lo; j < hi; ++j) {
+        if (!visible(qd, sD[j], a.gmask)) continue;
+        const HeadVec<DH> kv = lds_head<DH>(sK, j);
+        const float p = __expf(scale * dot<DH>(qv, kv) - lse);
+        const float pd = p * dot<DH>(dov, lds_head<DH>(sV, j));
+        D += pd;
+        axpy<DH>(A, pd, kv);
+        axpy<DH>(Bv, p, kv);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < DH; ++c) A[c] = scale * (A[c] - D * Bv[c]);
+    store_head<DH>(dq + row * dqpitch + h * DH, A);
+    stat[row * a.heads + h].y = D;
+  }
+}
+
+template <int DH>
+__global__ __launch_bounds__(512) void bw_set_attn_bwd_kv_lds_kernel(SetAttn a, const __bf16* __restrict__ dob, int d,
+                                                                     __bf16* __restrict__ dk, __bf16* __restrict__ dv, int dkvpitch,
+                                                                     const float2* __restrict__ stat) {
+  extern __shared__ uint4 sm[];
+  uint4* sQ = sm; uint4* sO = sm + (size_t)a.nq * (DH / 8);
+  float2* sS = (float2*)(sO + (size_t)a.nq * (DH / 8));
+  int* sD = (int*)(sS + a.nq);
+  const int u = blockIdx.x / a.heads, h = blockIdx.x - u * a.heads;
+  stage_heads<DH>(sQ, a.q + (size_t)u * a.nq * a.qpitch, a.qpitch, a.nq, h);
+  stage_heads<DH>(sO, dob + (size_t)u * a.nq * d, d, a.nq, h);
+  for (int i = threadIdx.x; i < a.nq; i += blockDim.x) {
+    sS[i] = stat[((size_t)u * a.nq + i) * a.heads + h];
+    sD[i] = a.qdesc[(size_t)u * a.nq + i];
+  }
+  __syncthreads();
+  const float scale = rsqrtf((float)DH);
+  for (int own = threadIdx.x; own < a.nk; own += blockDim.x) {
+    const size_t kr = (size_t)u * a.nk + own;
+    const int kd = a.kdesc[kr];
+    float gk[DH], gv[DH];
+#pragma unroll
+    for (int c = 0; c < DH; ++c) { gk[c] = 0.f; gv[c] = 0.f; }
+    if (kd >= 0) {
+      const HeadVec<DH> kv = load_head<DH>(a.k + kr * a.kvpitch + h * DH);
+      const HeadVec<DH> vv = load_head<DH>(a.v + kr * a.kvpitch + h * DH);
+      // a sequence key of a self layer is seen by the global rows and by the slots from its own on
+      const int skip_lo = a.m, skip_hi = (a.self && kd >= kSeq) ? max(a.m, own) : a.m;
+      for (int i0 = 0; i0 < a.nq - (skip_hi - skip_lo); ++i0) {
+        const int i = i0 < skip_lo ? i0 : i0 + (skip_hi - skip_lo);      // the rows outside [skip_lo, skip_hi)
+        if (!visible(sD[i], kd, a.gmask)) continue;
+        const HeadVec<DH> qi = lds_head<DH>(sQ, i);
+        const HeadVec<DH> doi = lds_head<DH>(sO, i);
+        const float2 st = sS[i];
+        const float p = __expf(scale * dot<DH>(qi, kv) - st.x);
+        const float ds = scale * p * (dot<DH>(doi, vv) - st.y);
+        axpy<DH>(gv, p, doi);
+        axpy<DH>(gk, ds, qi);
+      }
+    }
+    store_head<DH>(dk + kr * dkvpitch + h * DH, gk);
+    store_head<DH>(dv + kr * dkvpitch + h * DH, gv);
+  }
+}
+
 // Head and loss (Eq. 1-2) for one user per block: logit = <head_w, the m global rows of Y> + head_b,
 // loss += (softplus form of the cross-entropy) / B, dlogit = (sigmoid(logit) - label) / B, and the
 // gradients that follow: dY (global rows dlogit head_w, the other rows zero; fp32 and bf16), head_w, head_b.
@@ -1906,14 +2055,29 @@ static ModelGrads model_grads(const Dims& mi, const StackDims& s, bool learn) {
   return g;
 }
 
+// bytes of LDS the staged kernels need for n rows (two head vectors per row, its descriptor, and on the
+// key side the query's two statistics)
+static size_t set_attn_lds_bytes(int n, int dh, bool key_side) { return (size_t)n * (2 * dh * 2 + 4 + (key_side ? 8 : 0)); }
+constexpr size_t kSetAttnLdsMax = 64 * 1024;     // what a workgroup may take without an opt-in
+
 template <int DH>
 static void set_attn_launch(hipStream_t st, int which, const SetAttn& a, const __bf16* dob, int d, __bf16* o_or_dq, int pitch,
                             __bf16* dk, __bf16* dv, float2* stat) {
   const unsigned gq = (unsigned)(((size_t)a.B * a.nq * a.heads * kSplit + 255) / 256);
   const unsigned gk = (unsigned)(((size_t)a.B * a.nk * a.heads * kSplit + 255) / 256);
-  if (which == 0) bw_set_attn_fwd_kernel<DH><<<gq, 256, 0, st>>>(a, o_or_dq, d, stat);
-  else if (which == 1) bw_set_attn_bwd_q_kernel<DH><<<gq, 256, 0, st>>>(a, dob, d, o_or_dq, pitch, stat);
-  else bw_set_attn_bwd_kv_kernel<DH><<<gk, 256, 0, st>>>(a, dob, d, dk, dv, pitch, stat);
+  const size_t lq = set_attn_lds_bytes(a.nk, DH, false), lk = set_attn_lds_bytes(a.nq, DH, true);
+  auto threads = [](int n) { int t = (n + 63) / 64 * 64; return t > 512 ? 512 : t; };
+  const unsigned wgs = (unsigned)a.B * a.heads;
+  if (which == 0) {
+    if (lq <= kSetAttnLdsMax) bw_set_attn_fwd_lds_kernel<DH><<<wgs, threads(a.nq), lq, st>>>(a, o_or_dq, d, stat);
+    else bw_set_attn_fwd_kernel<DH><<<gq, 256, 0, st>>>(a, o_or_dq, d, stat);
+  } else if (which == 1) {
+    if (lq <= kSetAttnLdsMax) bw_set_attn_bwd_q_lds_kernel<DH><<<wgs, threads(a.nq), lq, st>>>(a, dob, d, o_or_dq, pitch, stat);
+    else bw_set_attn_bwd_q_kernel<DH><<<gq, 256, 0, st>>>(a, dob, d, o_or_dq, pitch, stat);
+  } else {
+    if (lk <= kSetAttnLdsMax) bw_set_attn_bwd_kv_lds_kernel<DH><<<wgs, threads(a.nk), lk, st>>>(a, dob, d, dk, dv, pitch, stat);
+    else bw_set_attn_bwd_kv_kernel<DH><<<gk, 256, 0, st>>>(a, dob, d, dk, dv, pitch, stat);
+  }
 }
 
 static int run_model(const longer_config* c, const longer_weights* wts, const void* H, const void* G, const int32_t* lens,

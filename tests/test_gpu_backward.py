@@ -254,6 +254,14 @@ def _compare_model(name, case):
     assert abs(grads["head_b"][0] - g_ref["head_b"][0]) <= TOLM * (abs(g_ref["head_b"][0]) + 1.0 / cfg.B)
 
 
+def test_model_backward_long_sequence_many_queries():
+    """975 merged tokens and 900 query slots per user: more rows than the attention kernels of the
+    reduced stack stage in LDS per (user, head), so the row-per-thread kernels run instead."""
+    case = _bf16_case("C2", users=2, L=7800, k_recent=900, ragged=True, len_lo=7000, len_hi=7800)
+    case["lens"][0] = 7800
+    _compare_model("C2 width, L = 7800, k = 900", case)
+
+
 def test_model_backward_c2_shape_ragged():
     case = _bf16_case("C2", users=6, L=203, ragged=True, len_lo=0, len_hi=203)
     case["lens"][:3] = [0, 203, 5]
