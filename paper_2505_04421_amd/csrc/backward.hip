@@ -838,6 +838,26 @@ __device__ __forceinline__ void axpy(float* acc, float w, const HeadVec<DH>& v) 
     for (int e = 0; e < 8; ++e) acc[8 * c + e] = fmaf(w, (float)v.c[c][e], acc[8 * c + e]);
 }
 
+// The same with the weight rounded to bf16: acc[2i] and acc[2i + 1] each take one two-feature product
+// against (w, 0) or (0, w), so the packed features need no widening (half the instructions of axpy).
+// For the long loops of the reduced stack's attention, where the weight is a probability or a
+// score gradient that multiplies bf16 values anyway.
+template <int DH>
+__device__ __forceinline__ void axpy_packed(float* acc, float w, const HeadVec<DH>& v) {
+  const __bf16 wb = (__bf16)w;
+  const bf16x2 w0 = {wb, (__bf16)0.f}, w1 = {(__bf16)0.f, wb};
+#pragma unroll
+  for (int c = 0; c < DH / 8; ++c) {
+    const bf16x2 pr[4] = {__builtin_shufflevector(v.c[c], v.c[c], 0, 1), __builtin_shufflevector(v.c[c], v.c[c], 2, 3),
+                          __builtin_shufflevector(v.c[c], v.c[c], 4, 5), __builtin_shufflevector(v.c[c], v.c[c], 6, 7)};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc[8 * c + 2 * e] = __builtin_amdgcn_fdot2_f32_bf16(pr[e], w0, acc[8 * c + 2 * e], false);
+      acc[8 * c + 2 * e + 1] = __builtin_amdgcn_fdot2_f32_bf16(pr[e], w1, acc[8 * c + 2 * e + 1], false);
+    }
+  }
+}
+
 // KG: the loops over a group's tokens are unrolled KG times (K <= KG) so that the per-token values
 // stay in registers; tokens past the group's valid count are predicated off.
 template <int DH, int KG>
@@ -1327,7 +1347,23 @@ __device__ __forceinline__ void stage_heads(uint4* dst, const __bf16* src, size_
     dst[c] = *(const uint4*)(src + (size_t)(c / CP) * pitch + h * DH + 8 * (c % CP));
 }
 
-template <int DH>
+// S adjacent lanes share a row: lane s of them takes every S-th key (query) of the loop, and the partial
+// results meet through cross-lane shuffles.  The loops are chains of dependent LDS reads and arithmetic,
+// and a workgroup has only as many rows as a user has queries (keys): more lanes per row hide the latency.
+template <int S>
+__device__ __forceinline__ float lanes_sum(float v) {
+#pragma unroll
+  for (int o = 1; o < S; o <<= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+template <int S>
+__device__ __forceinline__ float lanes_max(float v) {
+#pragma unroll
+  for (int o = 1; o < S; o <<= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+template <int DH, int S>
 __global__ __launch_bounds__(512) void bw_set_attn_fwd_lds_kernel(SetAttn a, __bf16* __restrict__ o, int d, float2* __restrict__ stat) {
   extern __shared__ uint4 sm[];
   uint4* sK = sm; uint4* sV = sm + (size_t)a.nk * (DH / 8);
@@ -1338,9 +1374,12 @@ __global__ __launch_bounds__(512) void bw_set_attn_fwd_lds_kernel(SetAttn a, __b
   for (int j = threadIdx.x; j < a.nk; j += blockDim.x) sD[j] = a.kdesc[(size_t)u * a.nk + j];
   __syncthreads();
   const float scale = rsqrtf((float)DH);
-  for (int i = threadIdx.x; i < a.nq; i += blockDim.x) {
-    const size_t row = (size_t)u * a.nq + i;
-    const int qd = a.qdesc[row];
+  const int sub = threadIdx.x % S;
+  for (int base = 0; base < a.nq * S; base += blockDim.x) {        // (blockDim.x is a multiple of 64: a row's lanes share a wave)
+    const int i = (base + threadIdx.x) / S;
+    const bool live = i < a.nq;
+    const size_t row = (size_t)u * a.nq + (live ? i : 0);
+    const int qd = live ? a.qdesc[row] : -1;
     float acc[DH];
 #pragma unroll
     for (int c = 0; c < DH; ++c) acc[c] = 0.f;
@@ -1350,7 +1389,7 @@ __global__ __launch_bounds__(512) void bw_set_attn_fwd_lds_kernel(SetAttn a, __b
       int lo, hi;
       key_range(a, qd, i, &lo, &hi);
 #pragma unroll 2
-      for (int j = lo; j < hi; ++j) {
+      for (int j = lo + sub; j < hi; j += S) {
         const bool vis = visible(qd, sD[j], a.gmask);
         const float sc = vis ? scale * dot<DH>(qv, lds_head<DH>(sK, j)) : -3.0e38f;
         const float mn = fmaxf(mx, sc);
@@ -1358,21 +1397,26 @@ __global__ __launch_bounds__(512) void bw_set_attn_fwd_lds_kernel(SetAttn a, __b
         l = l * corr + p;
 #pragma unroll
         for (int c = 0; c < DH; ++c) acc[c] *= corr;
-        axpy<DH>(acc, p, lds_head<DH>(sV, j));
+        axpy_packed<DH>(acc, p, lds_head<DH>(sV, j));
         mx = mn;
       }
     }
+    const float mall = lanes_max<S>(mx);
+    const float corr = __expf(mx - mall);          // a lane without a visible key: l = 0, acc = 0
+    l = lanes_sum<S>(l * corr);
     const float inv = l > 0.f ? 1.f / l : 0.f;
 #pragma unroll
-    for (int c = 0; c < DH; ++c) acc[c] *= inv;
-    store_head<DH>(o + row * d + h * DH, acc);
-    stat[row * a.heads + h] = make_float2(l > 0.f ? mx + __logf(l) : 0.f, 0.f);
+    for (int c = 0; c < DH; ++c) acc[c] = lanes_sum<S>(acc[c] * corr) * inv;
+    if (live && sub == 0) {
+      store_head<DH>(o + row * d + h * DH, acc);
+      stat[row * a.heads + h] = make_float2(l > 0.f ? mall + __logf(l) : 0.f, 0.f);
+    }
   }
 }
 
-template <int DH>
+template <int DH, int S>
 __global__ __launch_bounds__(512) void bw_set_attn_bwd_q_lds_kernel(SetAttn a, const __bf16* __restrict__ dob, int d,
-                                                                    __bf16* __restrict__ dq, int dqpitch, float2* __restrict__ stat) {
+                                                                   __bf16* __restrict__ dq, int dqpitch, float2* __restrict__ stat) {
   extern __shared__ uint4 sm[];
   uint4* sK = sm; uint4* sV = sm + (size_t)a.nk * (DH / 8);
   int* sD = (int*)(sV + (size_t)a.nk * (DH / 8));
@@ -1382,40 +1426,46 @@ __global__ __launch_bounds__(512) void bw_set_attn_bwd_q_lds_kernel(SetAttn a, c
   for (int j = threadIdx.x; j < a.nk; j += blockDim.x) sD[j] = a.kdesc[(size_t)u * a.nk + j];
   __syncthreads();
   const float scale = rsqrtf((float)DH);
-  for (int i = threadIdx.x; i < a.nq; i += blockDim.x) {
-    const size_t row = (size_t)u * a.nq + i;
-    const int qd = a.qdesc[row];
+  const int sub = threadIdx.x % S;
+  for (int base = 0; base < a.nq * S; base += blockDim.x) {
+    const int i = (base + threadIdx.x) / S;
+    const bool live = i < a.nq;
+    const size_t row = (size_t)u * a.nq + (live ? i : 0);
+    const int qd = live ? a.qdesc[row] : -1;
     float A[DH], Bv[DH];
 #pragma unroll
     for (int c = 0; c < DH; ++c) { A[c] = 0.f; Bv[c] = 0.f; }
     float D = 0.f;
-    const float lse = stat[row * a.heads + h].x;
     if (qd >= 0) {
+      const float lse = stat[row * a.heads + h].x;
       const HeadVec<DH> qv = load_head<DH>(a.q + row * a.qpitch + h * DH);
       const HeadVec<DH> dov = load_head<DH>(dob + row * d + h * DH);
       int lo, hi;
       key_range(a, qd, i, &lo, &hi);
-      for (int j = lo; j < hi; ++j) {
+      for (int j = lo + sub; j < hi; j += S) {
         if (!visible(qd, sD[j], a.gmask)) continue;
         const HeadVec<DH> kv = lds_head<DH>(sK, j);
         const float p = __expf(scale * dot<DH>(qv, kv) - lse);
         const float pd = p * dot<DH>(dov, lds_head<DH>(sV, j));
         D += pd;
-        axpy<DH>(A, pd, kv);
-        axpy<DH>(Bv, p, kv);
+        axpy_packed<DH>(A, pd, kv);
+        axpy_packed<DH>(Bv, p, kv);
       }
     }
+    D = lanes_sum<S>(D);
 #pragma unroll
-    for (int c = 0; c < DH; ++c) A[c] = scale * (A[c] - D * Bv[c]);
-    store_head<DH>(dq + row * dqpitch + h * DH, A);
-    stat[row * a.heads + h].y = D;
+    for (int c = 0; c < DH; ++c) A[c] = scale * (lanes_sum<S>(A[c]) - D * lanes_sum<S>(Bv[c]));
+    if (live && sub == 0) {
+      store_head<DH>(dq + row * dqpitch + h * DH, A);
+      stat[row * a.heads + h].y = D;
+    }
   }
 }
 
-template <int DH>
+template <int DH, int S>
 __global__ __launch_bounds__(512) void bw_set_attn_bwd_kv_lds_kernel(SetAttn a, const __bf16* __restrict__ dob, int d,
-                                                                     __bf16* __restrict__ dk, __bf16* __restrict__ dv, int dkvpitch,
-                                                                     const float2* __restrict__ stat) {
+                                                                    __bf16* __restrict__ dk, __bf16* __restrict__ dv, int dkvpitch,
+                                                                    const float2* __restrict__ stat) {
   extern __shared__ uint4 sm[];
   uint4* sQ = sm; uint4* sO = sm + (size_t)a.nq * (DH / 8);
   float2* sS = (float2*)(sO + (size_t)a.nq * (DH / 8));
@@ -1429,9 +1479,12 @@ __global__ __launch_bounds__(512) void bw_set_attn_bwd_kv_lds_kernel(SetAttn a, 
   }
   __syncthreads();
   const float scale = rsqrtf((float)DH);
-  for (int own = threadIdx.x; own < a.nk; own += blockDim.x) {
-    const size_t kr = (size_t)u * a.nk + own;
-    const int kd = a.kdesc[kr];
+  const int sub = threadIdx.x % S;
+  for (int base = 0; base < a.nk * S; base += blockDim.x) {
+    const int own = (base + threadIdx.x) / S;
+    const bool live = own < a.nk;
+    const size_t kr = (size_t)u * a.nk + (live ? own : 0);
+    const int kd = live ? a.kdesc[kr] : -1;
     float gk[DH], gv[DH];
 #pragma unroll
     for (int c = 0; c < DH; ++c) { gk[c] = 0.f; gv[c] = 0.f; }
@@ -1440,7 +1493,7 @@ __global__ __launch_bounds__(512) void bw_set_attn_bwd_kv_lds_kernel(SetAttn a, 
       const HeadVec<DH> vv = load_head<DH>(a.v + kr * a.kvpitch + h * DH);
       // a sequence key of a self layer is seen by the global rows and by the slots from its own on
       const int skip_lo = a.m, skip_hi = (a.self && kd >= kSeq) ? max(a.m, own) : a.m;
-      for (int i0 = 0; i0 < a.nq - (skip_hi - skip_lo); ++i0) {
+      for (int i0 = sub; i0 < a.nq - (skip_hi - skip_lo); i0 += S) {
         const int i = i0 < skip_lo ? i0 : i0 + (skip_hi - skip_lo);      // the rows outside [skip_lo, skip_hi)
         if (!visible(sD[i], kd, a.gmask)) continue;
         const HeadVec<DH> qi = lds_head<DH>(sQ, i);
@@ -1448,12 +1501,16 @@ __global__ __launch_bounds__(512) void bw_set_attn_bwd_kv_lds_kernel(SetAttn a, 
         const float2 st = sS[i];
         const float p = __expf(scale * dot<DH>(qi, kv) - st.x);
         const float ds = scale * p * (dot<DH>(doi, vv) - st.y);
-        axpy<DH>(gv, p, doi);
-        axpy<DH>(gk, ds, qi);
+        axpy_packed<DH>(gv, p, doi);
+        axpy_packed<DH>(gk, ds, qi);
       }
     }
-    store_head<DH>(dk + kr * dkvpitch + h * DH, gk);
-    store_head<DH>(dv + kr * dkvpitch + h * DH, gv);
+#pragma unroll
+    for (int c = 0; c < DH; ++c) { gk[c] = lanes_sum<S>(gk[c]); gv[c] = lanes_sum<S>(gv[c]); }
+    if (live && sub == 0) {
+      store_head<DH>(dk + kr * dkvpitch + h * DH, gk);
+      store_head<DH>(dv + kr * dkvpitch + h * DH, gv);
+    }
   }
 }
 
@@ -2068,16 +2125,16 @@ static void set_attn_launch(hipStream_t st, int which, const SetAttn& a, const _
   const size_t lq = set_attn_lds_bytes(a.nk, DH, false), lk = set_attn_lds_bytes(a.nq, DH, true);
   auto threads = [](int n) { int t = (n + 63) / 64 * 64; return t > 512 ? 512 : t; };
   const unsigned wgs = (unsigned)a.B * a.heads;
-  if (which == 0) {
-    if (lq <= kSetAttnLdsMax) bw_set_attn_fwd_lds_kernel<DH><<<wgs, threads(a.nq), lq, st>>>(a, o_or_dq, d, stat);
-    else bw_set_attn_fwd_kernel<DH><<<gq, 256, 0, st>>>(a, o_or_dq, d, stat);
-  } else if (which == 1) {
-    if (lq <= kSetAttnLdsMax) bw_set_attn_bwd_q_lds_kernel<DH><<<wgs, threads(a.nq), lq, st>>>(a, dob, d, o_or_dq, pitch, stat);
-    else bw_set_attn_bwd_q_kernel<DH><<<gq, 256, 0, st>>>(a, dob, d, o_or_dq, pitch, stat);
-  } else {
-    if (lk <= kSetAttnLdsMax) bw_set_attn_bwd_kv_lds_kernel<DH><<<wgs, threads(a.nk), lk, st>>>(a, dob, d, dk, dv, pitch, stat);
-    else bw_set_attn_bwd_kv_kernel<DH><<<gk, 256, 0, st>>>(a, dob, d, dk, dv, pitch, stat);
-  }
+  // lanes per row: 1 / 2 / 4 / 8 measured at the headline batch (forward, query side, key side, four layers each):
+  // 429 + 511 + 399, 324 + 367 + 336, 276 + 322 + 336, 274 + 324 + 380 us
+  constexpr int kLanes = 4;
+  if ((which == 2 ? lk : lq) <= kSetAttnLdsMax) {
+    if (which == 0) bw_set_attn_fwd_lds_kernel<DH, kLanes><<<wgs, threads(a.nq * kLanes), lq, st>>>(a, o_or_dq, d, stat);
+    else if (which == 1) bw_set_attn_bwd_q_lds_kernel<DH, kLanes><<<wgs, threads(a.nq * kLanes), lq, st>>>(a, dob, d, o_or_dq, pitch, stat);
+    else bw_set_attn_bwd_kv_lds_kernel<DH, kLanes><<<wgs, threads(a.nk * kLanes), lk, st>>>(a, dob, d, dk, dv, pitch, stat);
+  } else if (which == 0) bw_set_attn_fwd_kernel<DH><<<gq, 256, 0, st>>>(a, o_or_dq, d, stat);
+  else if (which == 1) bw_set_attn_bwd_q_kernel<DH><<<gq, 256, 0, st>>>(a, dob, d, o_or_dq, pitch, stat);
+  else bw_set_attn_bwd_kv_kernel<DH><<<gk, 256, 0, st>>>(a, dob, d, dk, dv, pitch, stat);
 }
 
 static int run_model(const longer_config* c, const longer_weights* wts, const void* H, const void* G, const int32_t* lens,
