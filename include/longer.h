@@ -309,7 +309,7 @@ int longer_forward_backward(const longer_config* cfg, const longer_weights* w, c
  * order pos [L, d_e] | w1 [d, f] | b1 [f] | w2 [f, d] | b2 [d] (f = ffn_mult d; overwritten, not
  * accumulated; the positional embedding's row p sums over the users whose sequence reaches p).
  * The hidden layer is recomputed from E and tdiff (bf16 operands, fp32 accumulation, as in the
- * forward call); padded tokens are neither read nor written beyond those zeros.
+ * forward call; GELU and its derivative to 1.3e-3 absolute, as in longer_token_merge_backward); padded tokens are neither read nor written beyond those zeros.
  * cfg: dtype LONGER_BF16, merge LONGER_MERGE_MEAN, d a multiple of 32 (at most 512), f at most
  * 2048, d_e a multiple of 32 below d.  E, tdiff, w: device, bf16, as for longer_input_generation;
  * lens: device int32 [B] or NULL.  ws: device, 256-byte aligned, at least

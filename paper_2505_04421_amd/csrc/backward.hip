@@ -2292,13 +2292,13 @@ static int run_model(const longer_config* c, const longer_weights* wts, const vo
 
 // ------------------------------------------------------------------------------------
 // Input generation backward (longer_input_generation_backward)
-struct InputWs { size_t x, h, a, dyb, dh, dx, part, bpart, total; };
+struct InputWs { size_t w1t, x, a, dyb, dh, dx, part, bpart, total; };
 static InputWs input_ws(size_t ntok, int d, int f) {
   InputWs w;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
+  w.w1t = take((size_t)d * f * 2);
   w.x = take(ntok * d * 2);
-  w.h = take(ntok * f * 2);
   w.a = take(ntok * f * 2);
   w.dyb = take(ntok * d * 2);
   w.dh = take(ntok * f * 2);
@@ -2451,7 +2451,7 @@ int longer_input_generation_backward(const longer_config* cfg, const longer_inpu
   const bw::InputGrads gl = bw::input_grads(L, d, f, d_e);
   hipStream_t st = (hipStream_t)stream;
   char* w8 = (char*)ws;
-  __bf16* x = (__bf16*)(w8 + l.x);   __bf16* h = (__bf16*)(w8 + l.h);   __bf16* a = (__bf16*)(w8 + l.a);
+  __bf16* x = (__bf16*)(w8 + l.x);   __bf16* w1t = (__bf16*)(w8 + l.w1t); __bf16* a = (__bf16*)(w8 + l.a);
   __bf16* dyb = (__bf16*)(w8 + l.dyb); __bf16* dh = (__bf16*)(w8 + l.dh); float* dx = (float*)(w8 + l.dx);
   float* part = (float*)(w8 + l.part); float* bpart = (float*)(w8 + l.bpart);
   const bw::RowGeom q = {lens, L, 1, (int)nt};
@@ -2461,11 +2461,11 @@ int longer_input_generation_backward(const longer_config* cfg, const longer_inpu
   bw::bw_input_rows_kernel<<<eg, 256, 0, st>>>((const __bf16*)E, (const __bf16*)w->pos, (const __bf16*)tdiff, x, q, d, d_e);
   bw::bw_cast_rows_kernel<<<eg, 256, 0, st>>>(dH, dyb, q, d);
   if ((rc = bw::launched("input rows"))) return rc;
-  // forward, recomputed: hidden pre-activation and activation
-  if ((rc = bw::gemm_rows(st, x, d, (const __bf16*)w->w1, f, nt, bw::EPI_ACT, cfg->act, h, a, (const __bf16*)w->b1, nullptr, nullptr, 0, rv))) return rc;
+  // the hidden pre-activation is formed again inside the launch that takes its gradient (as in the merge's FFN)
+  if ((rc = bw::transpose(st, (const __bf16*)w->w1, w1t, d, f))) return rc;
+  if ((rc = bw::gemm_ffn_mid(st, x, dyb, d, w1t, (const __bf16*)w->w2, f, (const __bf16*)w->b1, nt, cfg->act, dh, a, rv))) return rc;
   // H = a w2 + b2
   if ((rc = bw::gemm_wgrad(st, a, f, f, dyb, d, d, nt, part, bpart, grads_out + gl.w2, grads_out + gl.b2, rv))) return rc;
-  if ((rc = bw::gemm_rows_t(st, dyb, d, (const __bf16*)w->w2, f, nt, bw::EPI_DACT, cfg->act, dh, h, 0, rv))) return rc;
   if ((rc = bw::gemm_wgrad(st, x, d, d, dh, f, f, nt, part, bpart, grads_out + gl.w1, grads_out + gl.b1, rv))) return rc;
   if ((rc = bw::gemm_rows_t(st, dh, f, (const __bf16*)w->w1, d, nt, bw::EPI_F32, 0, dx, nullptr, 0, rv))) return rc;
   bw::bw_split_input_grad_kernel<<<eg, 256, 0, st>>>(dx, dE_out, dtdiff_out, q, d, d_e);

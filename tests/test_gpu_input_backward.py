@@ -4,8 +4,8 @@ Section 3.5.1 under mixed precision) against the fp64 oracle
 
 Tolerance.  The GPU pass rounds the MLP's input, hidden pre-activation, activated hidden values, the
 upstream gradient and the hidden gradient to bf16 (2^-9 relative each, about 1.1e-3 rms), five
-independent roundings on the longest path, so the expected relative L2 error is about 2.5e-3; the bar
-is 1e-2 (GELU).  With ReLU the derivative is a step and a hidden unit within the forward's rounding
+independent roundings on the longest path, and evaluates GELU and its derivative to 1.3e-3 absolute, so the
+expected relative L2 error is about 3e-3; the bar is 1e-2 (GELU).  With ReLU the derivative is a step and a hidden unit within the forward's rounding
 error of zero takes the other branch (a difference of that unit's whole contribution): 1e-1 there,
 the bar of the other backward tests with ReLU (observed 5e-2 per user at width 64, 256 hidden units)."""
 import sys
