@@ -1179,11 +1179,12 @@ __device__ __forceinline__ void key_range(const SetAttn& a, int qd, int i, int* 
   }
 }
 
-// The set-attention kernels give a (row, head) pair to kSplit adjacent lanes, each taking every kSplit-th
-// key (query) of the loop, and combine the lanes' partial results with cross-lane shuffles: the loops
-// are short chains of dependent loads, and there are only B (m + k) heads rows to spread over the chip.
-constexpr int kSplit = 1;   // measured at the headline batch: 8 lanes per pair were no faster (the kernels are bound by
-                            // their instruction count), and slower in the two backward kernels
+// Row-per-thread set-attention kernels, reading keys (queries) from global memory: the ones that run when a
+// user's rows do not fit the LDS-staged kernels further down.  They give a (row, head) pair to kSplit adjacent
+// lanes, each taking every kSplit-th key (query) of the loop, and combine the lanes' partial results with
+// cross-lane shuffles.
+constexpr int kSplit = 1;   // measured at the headline batch: with the keys in global memory 8 lanes per pair were no
+                            // faster, and slower in the two backward kernels
 __device__ __forceinline__ float split_sum(float v) {
 #pragma unroll
   for (int o = 1; o < kSplit; o <<= 1) v += __shfl_xor(v, o, 64);
