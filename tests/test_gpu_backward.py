@@ -11,7 +11,7 @@ a step: a hidden unit whose pre-activation lies within the forward pass's own ro
 contribution, not of a rounding; the bar there is 1e-1 (observed: 2e-2 at width 64, up to 7e-2 for a
 parameter vector at width 32, where a block has only 64-128 hidden units).  The bar holds for the cases
 drawn here; it is not a bound: over 60 further seeds of the random configurations below, five ReLU
-configurations whose reduced stack has only 10-90 rows in the whole batch came out at 1.0e-1 to 1.6e-1 for
+configurations whose reduced stack has only 10-132 rows in the whole batch came out at 1.0e-1 to 1.6e-1 for
 one parameter vector (a bias or LayerNorm shift of the main stack), and the same five configurations with
 GELU at 1.2e-2 to 1.5e-2."""
 import sys
