@@ -172,3 +172,50 @@ def test_rate_probe_argument_checks():
     assert lib.longer_probe_rate(0, 10, 4, None, None) == -1
     assert lib.longer_probe_rate(99, 10, 4, ctypes.c_void_p(4096), None) == -1
     assert lib.longer_probe_rate(0, 0, 4, ctypes.c_void_p(4096), None) == -1
+
+
+def test_backward_entry_points_check_their_arguments_before_any_launch():
+    """The three backward calls and their size queries: unsupported configurations, NULL pointers,
+    alignment and workspace size are turned into status codes on the host (no GPU needed)."""
+    lib = lg.load_library()
+    c3 = lg.make_config(synth.CONFIGS["C3"])
+    fake, ws = ctypes.c_void_p(4096), ctypes.c_void_p(1 << 20)
+    # size queries: positive for the headline shape, 0 with a message otherwise
+    assert lg.longer_backward_workspace_bytes(c3, 4, 64) > 0 and lg.longer_block_grad_floats(c3) == 12 * 128 * 128 + 13 * 128
+    assert lg.longer_forward_backward_workspace_bytes(c3, 4, 64) > lg.longer_backward_workspace_bytes(c3, 4, 64)
+    assert lg.longer_input_backward_workspace_bytes(c3, 4, 64, 96) > 0
+    assert lg.longer_input_grad_floats(c3, 64, 96) == 64 * 96 + 2 * 128 * 512 + 512 + 128
+    fp32 = lg.make_config(synth.CONFIGS["C1"])
+    assert lg.longer_backward_workspace_bytes(fp32, 4, 64) == 0 and "LONGER_BF16" in lg.longer_last_error()
+    assert lg.longer_input_backward_workspace_bytes(fp32, 4, 64, 32) == 0 and "LONGER_BF16" in lg.longer_last_error()
+    for d_e in (0, 48, 128):
+        assert lg.longer_input_backward_workspace_bytes(c3, 4, 64, d_e) == 0 and "d_e" in lg.longer_last_error()
+    concat = lg.make_config(synth.CONFIGS["P1"])
+    assert lg.longer_input_backward_workspace_bytes(concat, 4, 64, 96) == 0 and "mean merge" in lg.longer_last_error()
+    # the token merge's backward
+    blk = (lg.binding.CBlock * 2)()
+    rc = lib.longer_token_merge_backward(ctypes.byref(c3), blk, fake, None, 4, 64, fake, fake, fake, ws, 1 << 40, None)
+    assert rc == -1 and "parameter 0 is NULL" in lg.longer_last_error()
+    for b in blk:
+        for name, _ in lg.binding.CBlock._fields_:
+            setattr(b, name, 4096)                                          # never dereferenced
+    rc = lib.longer_token_merge_backward(ctypes.byref(c3), blk, fake, None, 4, 64, fake, fake, fake, None, 0, None)
+    assert rc == -1
+    rc = lib.longer_token_merge_backward(ctypes.byref(c3), blk, fake, None, 4, 64, fake, fake, fake, ws, 16, None)
+    assert rc == -2 and "workspace" in lg.longer_last_error()
+    rc = lib.longer_token_merge_backward(ctypes.byref(c3), blk, None, None, 4, 64, fake, fake, fake, ws, 1 << 40, None)
+    assert rc == -1
+    # the input generation's backward
+    w = lg.CInputWeights(pos=4096, w1=4096, b1=4096, w2=4096, b2=4096)      # never dereferenced
+    args = (fake, fake, None, 4, 64, 96, fake, fake, fake, fake)
+    rc = lib.longer_input_generation_backward(ctypes.byref(c3), ctypes.byref(w), *args, ws, 16, None)
+    assert rc == -2 and "workspace" in lg.longer_last_error()
+    rc = lib.longer_input_generation_backward(ctypes.byref(c3), None, *args, ws, 1 << 40, None)
+    assert rc == -1 and "null" in lg.longer_last_error().lower()
+    rc = lib.longer_input_generation_backward(ctypes.byref(c3), ctypes.byref(w), *args, ctypes.c_void_p((1 << 20) + 16), 1 << 40, None)
+    assert rc == -1 and "aligned" in lg.longer_last_error()
+    odd = (ctypes.c_void_p(4096 + 4),) + args[1:]
+    rc = lib.longer_input_generation_backward(ctypes.byref(c3), ctypes.byref(w), *odd, ws, 1 << 40, None)
+    assert rc == -1 and "aligned" in lg.longer_last_error()
+    rc = lib.longer_input_generation_backward(ctypes.byref(fp32), ctypes.byref(w), *args, ws, 1 << 40, None)
+    assert rc == -1 and "LONGER_BF16" in lg.longer_last_error()
