@@ -979,15 +979,95 @@ __global__ __launch_bounds__(256) void bw_attn_bwd_kv_kernel(const __bf16* qkv, 
   store_head<DH>(dqkv + (size_t)r * 3 * d + 2 * d + h * DH, dv);
 }
 
+// Both sides in one launch, when every group lies inside one workgroup's rows (L a multiple of K, and K a divisor
+// of the 256 / heads rows a workgroup holds): the query side first, its statistics to LDS, then the key side from
+// there.  The second pass finds the group's rows in the cache that the first pass filled, so the pair reads
+// q, k, v and the output gradient from memory once instead of twice.
+template <int DH, int KG>
+__global__ __launch_bounds__(256) void bw_attn_bwd_fused_kernel(const __bf16* qkv, const __bf16* dob, __bf16* dqkv,
+                                                                RowGeom q, int d, int heads) {
+  __shared__ float2 sst[256];
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  const bool inside = idx < (long long)q.ntok * heads;
+  const int r = inside ? (int)(idx / heads) : 0, h = inside ? (int)(idx - (long long)r * heads) : 0;
+  const int r0 = (int)(((long long)blockIdx.x * 256) / heads);
+  GroupOf g;
+  const bool valid = inside && group_of(q, r, &g);
+  const float scale = rsqrtf((float)DH);
+  float2 st = make_float2(0.f, 0.f);
+  {
+    float acc[DH];
+#pragma unroll
+    for (int c = 0; c < DH; ++c) acc[c] = 0.f;
+    if (valid) {
+      const HeadVec<DH> qv = load_head<DH>(qkv + (size_t)r * 3 * d + h * DH);
+      const HeadVec<DH> dov = load_head<DH>(dob + (size_t)r * d + h * DH);
+      const __bf16* kbase = qkv + (size_t)g.first * 3 * d + d + h * DH;
+      float s[KG], dp[KG];
+      float mx = -3.0e38f;
+#pragma unroll
+      for (int j = 0; j < KG; ++j) {
+        s[j] = -3.0e38f; dp[j] = 0.f;
+        if (j < g.n) {
+          s[j] = scale * dot<DH>(qv, load_head<DH>(kbase + (size_t)j * 3 * d));
+          dp[j] = dot<DH>(dov, load_head<DH>(kbase + (size_t)j * 3 * d + d));
+          mx = fmaxf(mx, s[j]);
+        }
+      }
+      float l = 0.f, Dn = 0.f;
+#pragma unroll
+      for (int j = 0; j < KG; ++j) {
+        s[j] = j < g.n ? __expf(s[j] - mx) : 0.f;
+        l += s[j];
+        Dn = fmaf(s[j], dp[j], Dn);
+      }
+      const float inv = 1.f / l;
+      const float D = Dn * inv;
+#pragma unroll
+      for (int j = 0; j < KG; ++j)
+        if (j < g.n) axpy<DH>(acc, scale * inv * s[j] * (dp[j] - D), load_head<DH>(kbase + (size_t)j * 3 * d));
+      st = make_float2(mx + __logf(l), D);
+    }
+    if (inside) store_head<DH>(dqkv + (size_t)r * 3 * d + h * DH, acc);
+  }
+  sst[threadIdx.x] = st;
+  __syncthreads();
+  float dk[DH], dv[DH];
+#pragma unroll
+  for (int c = 0; c < DH; ++c) { dk[c] = 0.f; dv[c] = 0.f; }
+  if (valid) {
+    const HeadVec<DH> kv = load_head<DH>(qkv + (size_t)r * 3 * d + d + h * DH);
+    const HeadVec<DH> vv = load_head<DH>(qkv + (size_t)r * 3 * d + 2 * d + h * DH);
+#pragma unroll
+    for (int i = 0; i < KG; ++i) {
+      if (i < g.n) {
+        const int ri = g.first + i;
+        const HeadVec<DH> qi = load_head<DH>(qkv + (size_t)ri * 3 * d + h * DH);
+        const HeadVec<DH> doi = load_head<DH>(dob + (size_t)ri * d + h * DH);
+        const float2 si = sst[(ri - r0) * heads + h];
+        const float p = __expf(scale * dot<DH>(qi, kv) - si.x);
+        const float ds = scale * p * (dot<DH>(doi, vv) - si.y);
+        axpy<DH>(dv, p, doi);
+        axpy<DH>(dk, ds, qi);
+      }
+    }
+  }
+  if (inside) {
+    store_head<DH>(dqkv + (size_t)r * 3 * d + d + h * DH, dk);
+    store_head<DH>(dqkv + (size_t)r * 3 * d + 2 * d + h * DH, dv);
+  }
+}
+
 // launchers by head width and group size
 template <int DH, int KG>
 static void attn_launch(int which, unsigned grid, hipStream_t st, const __bf16* qkv, const __bf16* dob, __bf16* out, float2* stat,
                         RowGeom q, int d, int heads) {
   if (which == 0) bw_attn_fwd_kernel<DH, KG><<<grid, 256, 0, st>>>(qkv, out, q, d, heads);
+  else if (which == 3) bw_attn_bwd_fused_kernel<DH, KG><<<grid, 256, 0, st>>>(qkv, dob, out, q, d, heads);
   else if (which == 1) bw_attn_bwd_q_kernel<DH, KG><<<grid, 256, 0, st>>>(qkv, dob, out, stat, q, d, heads);
   else bw_attn_bwd_kv_kernel<DH, KG><<<grid, 256, 0, st>>>(qkv, dob, out, stat, q, d, heads);
 }
-// which: 0 forward (out = o), 1 backward, query side, 2 backward, key side (out = dqkv)
+// which: 0 forward (out = o), 1 backward, query side, 2 backward, key side (out = dqkv), 3 both sides in one launch
 static void group_attn(int which, int dh, int K, unsigned grid, hipStream_t st, const __bf16* qkv, const __bf16* dob, __bf16* out,
                        float2* stat, RowGeom q, int d, int heads) {
 #define LONGER_BW_ATTN(DH, KG) attn_launch<DH, KG>(which, grid, st, qkv, dob, out, stat, q, d, heads)
@@ -2006,8 +2086,12 @@ static int run(const longer_config* c, const longer_block* inner, const void* H,
     // attention: xmid = x + att W_O + b_O
     BW_TRY(gemm_wgrad(st, o, d, d, dxmb, d, d, nt, part, bpart, g + gl.wo, g + gl.bo, rv));
     BW_TRY(gemm_rows_t(st, dxmb, d, (const __bf16*)b.wo, d, nt, EPI_BF16, 0, dob, nullptr, 0, rv));
-    group_attn(1, s.dh, s.K, ah_grid, st, qkv, dob, dqkv, stat, q, d, s.heads);
-    group_attn(2, s.dh, s.K, ah_grid, st, qkv, dob, dqkv, stat, q, d, s.heads);
+    if (L % s.K == 0 && 256 % s.heads == 0 && (256 / s.heads) % s.K == 0) {     // every group inside one workgroup's rows
+      group_attn(3, s.dh, s.K, ah_grid, st, qkv, dob, dqkv, stat, q, d, s.heads);
+    } else {
+      group_attn(1, s.dh, s.K, ah_grid, st, qkv, dob, dqkv, stat, q, d, s.heads);
+      group_attn(2, s.dh, s.K, ah_grid, st, qkv, dob, dqkv, stat, q, d, s.heads);
+    }
     BW_TRY(launched("group attention backward"));
     const size_t wofs[3] = {gl.wq, gl.wk, gl.wv}, bofs[3] = {gl.bq, gl.bk, gl.bv};
     for (int j = 0; j < 3; ++j) {
